@@ -1,0 +1,392 @@
+/*
+ * mor_oracle.c -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, obviously-correct CPU implementation of what the MoR
+ * analyse-select-quantize path computes, written from the paper's definitions.
+ * It exists so that the HIP kernels can be checked against something that was
+ * not derived from them.  It shares no code, header, table or constant
+ * generator with the HIP path, and nothing in the product path may call it.
+ * Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg use it.
+ *
+ * What follows the paper, passage by passage:
+ *   - partitioning of X into blocks B (per tensor, 2-D block, sub-channel):
+ *     Section 3, first paragraph;
+ *   - amax = max(abs(b)) and scale = q_amax / amax: Algorithm 1, the two
+ *     assignments at the top of the group loop and of the block loop, used
+ *     here in their plain FP32 form (the "standard per-block FP32 amax
+ *     scaling" of the ablation in Section 4.1.2);
+ *   - E4M3 / E5M2 value sets, saturation and underflow: Section 1 (format
+ *     widths) and Section 2, first paragraph (ranges 2^-9..448, 2^-16..57344,
+ *     clipping large values, flushing small ones to zero);
+ *   - mean relative error over non-zero elements, strict "<" against the
+ *     threshold: Eq. (1)-(2);
+ *   - local errors aggregated into one global error and one tensor-wide
+ *     decision: Section 3.1, the paragraph on Figure 2;
+ *   - total relative error of E4M3 strictly below that of E5M2, else BF16
+ *     (E5M2 is a yardstick only): Eq. (3) and the two-way paragraph of
+ *     Section 3.2;
+ *   - first accepted type wins, last type unconditional: Algorithm 2;
+ *   - BF16 = leave the block in its original precision: Section 3;
+ *   - dequantize and de-scale back to the original range: Section 4, the
+ *     fake-quantization paragraph (Figure 4);
+ *   - 0.5 %-wide histogram bins, last bin open-ended from 5.5 %: Section 4.1.3.
+ *
+ * Readings taken where the paper is silent (each is also listed in the design
+ * notes of the repository):
+ *   R1  amax is the integer maximum of (bits & 0x7FFF) over BF16 bit patterns.
+ *   R2  scale s = fl32(q_amax / amax), a multiplier; amax == 0 -> s = 1;
+ *       quotient overflowing to +inf -> s = FLT_MAX; non-finite amax -> s = 1.
+ *   R3  OCP E4M3 (no infinities, 0x7F/0xFF = NaN, bias 7) and E5M2 (bias 15),
+ *       round to nearest, ties to the even code, magnitudes above the largest
+ *       finite value clip to it, sign always kept, NaN -> 0x7F | sign.
+ *   R4  tensor-wide error = sum of block error sums / sum of block non-zero
+ *       counts (Eq. (2) taken over the whole tensor).
+ *   R5  Q(x) in Eq. (2) is the de-scaled FP8 value without re-rounding to BF16.
+ *   R6  the scaled value is y = fl32(x * s) (one binary32 multiply); the error
+ *       term is |y - q| / |y| evaluated in binary64.  The unscaled-domain form
+ *       |x - q/s| / |x| is also produced so tests can show the two agree.
+ *   R7  a non-zero x whose quantized value is zero contributes exactly 1;
+ *       a block without non-zero elements has metric 0.
+ *   R8  Eq. (3) is strict: a tie selects BF16.
+ *   R9  a block holding Inf or NaN: amax = that pattern, s = 1, codes by R3,
+ *       error sums = +inf, selection = BF16.
+ *   R10 de-scaling multiplies by s_inv = fl32(1 / s), then rounds to BF16 RNE.
+ *
+ * parity unpinned: R8 (tie handling) and R9 (non-finite policy) are fixed by
+ * these readings only; nothing in the paper pins them.
+ */
+#include <float.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------ formats */
+
+static float bits_to_f32(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
+static uint32_t f32_to_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+
+/* BF16 is the upper half of a binary32: widening is exact. */
+static float bf16_to_f32(uint16_t b) { return bits_to_f32((uint32_t)b << 16); }
+
+/* Value of an FP8 code from the format definition.  ebits/mbits = 4/3 (E4M3,
+ * bias 7, no infinities, S.1111.111 = NaN) or 5/2 (E5M2, bias 15, IEEE-like
+ * infinities and NaNs).  Returns NaN / +-inf as doubles where the code says so. */
+static double fp8_value(unsigned code, int ebits, int mbits)
+{
+    int bias = (1 << (ebits - 1)) - 1;
+    unsigned sign = (code >> 7) & 1u;
+    unsigned e = (code >> mbits) & ((1u << ebits) - 1u);
+    unsigned m = code & ((1u << mbits) - 1u);
+    double mag;
+    if (ebits == 4) {
+        if (e == 15u && m == 7u) return NAN;
+    } else {
+        if (e == 31u) return m ? NAN : (sign ? -INFINITY : INFINITY);
+    }
+    if (e == 0u)
+        mag = ldexp((double)m, 1 - bias - mbits);              /* subnormal: m * 2^(1-bias-mbits) */
+    else
+        mag = ldexp(1.0 + ldexp((double)m, -mbits), (int)e - bias);
+    return sign ? -mag : mag;
+}
+
+static unsigned fp8_max_finite_code(int ebits) { return ebits == 4 ? 0x7Eu : 0x7Bu; }
+
+/* Round-to-nearest, ties-to-even-code, clipping encoder, written as a search
+ * over the decoded non-negative finite values (they increase with the code). */
+static uint8_t fp8_encode(float y, int ebits, int mbits)
+{
+    unsigned sign = (f32_to_bits(y) >> 31) << 7;
+    unsigned top = fp8_max_finite_code(ebits);
+    double a;
+    unsigned lo, hi;
+    if (isnan(y)) return (uint8_t)(sign | 0x7Fu);
+    a = fabs((double)y);
+    if (a >= fp8_value(top, ebits, mbits)) return (uint8_t)(sign | top);   /* clip (also Inf) */
+    /* largest code lo with value(lo) <= a; value(0) = 0 <= a always */
+    lo = 0; hi = top;
+    while (hi - lo > 1u) {
+        unsigned mid = (lo + hi) / 2u;
+        if (fp8_value(mid, ebits, mbits) <= a) lo = mid; else hi = mid;
+    }
+    {
+        double dlo = a - fp8_value(lo, ebits, mbits);
+        double dhi = fp8_value(hi, ebits, mbits) - a;
+        unsigned pick;
+        if (dlo < dhi) pick = lo;
+        else if (dhi < dlo) pick = hi;
+        else pick = (lo & 1u) ? hi : lo;                       /* tie: even code */
+        return (uint8_t)(sign | pick);
+    }
+}
+
+uint8_t mor_oracle_e4m3_encode(float y) { return fp8_encode(y, 4, 3); }
+uint8_t mor_oracle_e5m2_encode(float y) { return fp8_encode(y, 5, 2); }
+double  mor_oracle_e4m3_decode(uint8_t c) { return fp8_value(c, 4, 3); }
+double  mor_oracle_e5m2_decode(uint8_t c) { return fp8_value(c, 5, 2); }
+
+/* binary32 -> BF16, round to nearest even; NaN -> quiet NaN with the sign kept. */
+uint16_t mor_oracle_f32_to_bf16(float f)
+{
+    uint32_t u = f32_to_bits(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)(((u >> 16) & 0x8000u) | 0x7FC0u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+/* R2: the FP32 scale of a block from its amax. */
+float mor_oracle_scale(float amax, float q_amax)
+{
+    volatile float s;
+    if (!(amax < INFINITY)) return 1.0f;       /* Inf or NaN */
+    if (amax == 0.0f) return 1.0f;
+    s = q_amax / amax;                          /* one correctly rounded binary32 division */
+    if (isinf(s)) return FLT_MAX;
+    return s;
+}
+
+/* ------------------------------------------------------------ partitioning */
+
+enum { GRAN_TENSOR = 0, GRAN_SUB_1x128 = 1, GRAN_BLOCK_128x128 = 2 };
+enum { CRIT_MEAN_REL_ERR = 0, CRIT_E4M3_VS_E5M2 = 1 };
+enum { SCOPE_PARTITION = 0, SCOPE_TENSOR = 1 };
+
+static int part_shape(int gran, int64_t rows, int64_t cols, int64_t *pr, int64_t *pc)
+{
+    switch (gran) {
+    case GRAN_TENSOR:        *pr = rows; *pc = cols; return 0;
+    case GRAN_SUB_1x128:     *pr = 1;    *pc = 128;  return (cols % 128) ? -1 : 0;
+    case GRAN_BLOCK_128x128: *pr = 128;  *pc = 128;  return (rows % 128 || cols % 128) ? -1 : 0;
+    default: return -1;
+    }
+}
+
+int64_t mor_oracle_num_partitions(int gran, int64_t rows, int64_t cols)
+{
+    int64_t pr, pc;
+    if (rows <= 0 || cols <= 0 || part_shape(gran, rows, cols, &pr, &pc)) return -1;
+    return (rows / pr) * (cols / pc);
+}
+
+/* --------------------------------------------------- one block of the tensor */
+
+typedef struct {
+    float  amax, scale;
+    double err_sum, err5_sum, err_sum_unscaled;
+    uint32_t nnz;
+} block_result;
+
+/* Error sums of one block for one FP8 format; optionally writes the codes. */
+static double block_error(const uint16_t *x, int64_t ld, int64_t pr, int64_t pc, float s,
+                          int ebits, int mbits, int nonfinite,
+                          uint8_t *codes, int64_t ld_codes, double *unscaled_out)
+{
+    double sum = 0.0, sum_u = 0.0;
+    for (int64_t r = 0; r < pr; ++r) {
+        for (int64_t c = 0; c < pc; ++c) {
+            uint16_t b = x[r * ld + c];
+            float xf = bf16_to_f32(b);
+            volatile float y = xf * s;                     /* R6: one binary32 multiply */
+            uint8_t code = fp8_encode(y, ebits, mbits);
+            if (codes) codes[r * ld_codes + c] = code;
+            if ((b & 0x7FFFu) == 0u) continue;             /* Eq. (1): non-zero elements only */
+            if (nonfinite) continue;                        /* R9: sums forced to +inf below */
+            {
+                double qv = fp8_value(code, ebits, mbits);
+                double yd = (double)y;
+                if (qv == 0.0) {                            /* R7: flushed */
+                    sum += 1.0;
+                    sum_u += 1.0;
+                } else {
+                    sum += fabs(yd - qv) / fabs(yd);
+                    sum_u += fabs((double)xf - qv / (double)s) / fabs((double)xf);
+                }
+            }
+        }
+    }
+    if (nonfinite) { sum = INFINITY; sum_u = INFINITY; }
+    if (unscaled_out) *unscaled_out = sum_u;
+    return sum;
+}
+
+static void analyze_block(const uint16_t *x, int64_t ld, int64_t pr, int64_t pc, int crit,
+                          uint8_t *codes, int64_t ld_codes, block_result *out)
+{
+    uint16_t a = 0;
+    uint32_t nnz = 0;
+    int nonfinite;
+    for (int64_t r = 0; r < pr; ++r)
+        for (int64_t c = 0; c < pc; ++c) {
+            uint16_t m = (uint16_t)(x[r * ld + c] & 0x7FFFu);
+            if (m > a) a = m;                               /* R1 */
+            if (m) ++nnz;
+        }
+    nonfinite = a >= 0x7F80u;
+    out->amax = bf16_to_f32(a);
+    out->nnz = nnz;
+    out->scale = mor_oracle_scale(out->amax, 448.0f);
+    out->err_sum = block_error(x, ld, pr, pc, out->scale, 4, 3, nonfinite, codes, ld_codes,
+                               &out->err_sum_unscaled);
+    if (crit == CRIT_E4M3_VS_E5M2) {
+        float s5 = mor_oracle_scale(out->amax, 57344.0f);
+        out->err5_sum = block_error(x, ld, pr, pc, s5, 5, 2, nonfinite, NULL, 0, NULL);
+    } else {
+        out->err5_sum = 0.0;
+    }
+}
+
+/* Algorithm 2 with the type list [E4M3, BF16]: 1 = accept E4M3. */
+static int accept_e4m3(int crit, double err_sum, double err5_sum, uint64_t nnz, float threshold)
+{
+    if (crit == CRIT_E4M3_VS_E5M2) return err_sum < err5_sum;             /* Eq. (3), R8 */
+    {
+        double metric = nnz ? err_sum / (double)nnz : 0.0;                /* Eq. (1)-(2), R7 */
+        return metric < (double)threshold;
+    }
+}
+
+/* -------------------------------------------------------------- entry points */
+
+/*
+ * Full analyse-select-quantize of one operand.
+ *   x            [rows x ld] BF16 bit patterns, row-major, ld >= cols
+ *   fp8          [rows x cols] E4M3 codes, dense (leading dimension cols), all blocks
+ *   bf16         [rows x cols] dense; written only where the block's mask is 1; may be NULL
+ *   scale, amax  [P] float;  err_sum, err5_sum, err_sum_unscaled [P] double (the last two may
+ *   be NULL);  nnz [P] uint32;  mask [P] uint8 (0 = E4M3, 1 = BF16)
+ * Blocks are numbered row-major over the block grid.  Returns 0, or -1 on a bad shape.
+ */
+int mor_oracle_analyze_quantize(const uint16_t *x, int64_t rows, int64_t cols, int64_t ld,
+                                int gran, int scope, int crit, float threshold,
+                                uint8_t *fp8, uint16_t *bf16,
+                                float *scale, float *amax, double *err_sum, uint32_t *nnz,
+                                uint8_t *mask, double *err5_sum, double *err_sum_unscaled)
+{
+    int64_t pr, pc, gr, gc, P;
+    if (rows <= 0 || cols <= 0 || ld < cols || part_shape(gran, rows, cols, &pr, &pc)) return -1;
+    gr = rows / pr; gc = cols / pc; P = gr * gc;
+
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t p = 0; p < P; ++p) {
+        int64_t br = p / gc, bc = p % gc;
+        block_result res;
+        analyze_block(x + br * pr * ld + bc * pc, ld, pr, pc, crit,
+                      fp8 + br * pr * cols + bc * pc, cols, &res);
+        scale[p] = res.scale; amax[p] = res.amax; err_sum[p] = res.err_sum; nnz[p] = res.nnz;
+        if (err5_sum) err5_sum[p] = res.err5_sum;
+        if (err_sum_unscaled) err_sum_unscaled[p] = res.err_sum_unscaled;
+        mask[p] = accept_e4m3(crit, res.err_sum, res.err5_sum, res.nnz, threshold) ? 0 : 1;
+    }
+
+    if (scope == SCOPE_TENSOR) {                            /* R4: one decision for the tensor */
+        double tot = 0.0, tot5 = 0.0;
+        uint64_t n = 0;
+        uint8_t m;
+        for (int64_t p = 0; p < P; ++p) {
+            tot += err_sum[p]; n += nnz[p];
+            if (crit == CRIT_E4M3_VS_E5M2 && err5_sum) tot5 += err5_sum[p];
+        }
+        if (crit == CRIT_E4M3_VS_E5M2 && !err5_sum) return -1;
+        m = accept_e4m3(crit, tot, tot5, n, threshold) ? 0 : 1;
+        for (int64_t p = 0; p < P; ++p) mask[p] = m;
+    }
+
+    if (bf16) {
+#pragma omp parallel for schedule(dynamic, 16)
+        for (int64_t p = 0; p < P; ++p) {
+            if (!mask[p]) continue;
+            int64_t br = p / gc, bc = p % gc;
+            for (int64_t r = 0; r < pr; ++r)
+                memcpy(bf16 + (br * pr + r) * cols + bc * pc,
+                       x + (br * pr + r) * ld + bc * pc, (size_t)pc * 2);
+        }
+    }
+    return 0;
+}
+
+/*
+ * De-quantize: E4M3 blocks -> bf16_rne(fl32(q * s_inv)), s_inv = fl32(1 / s) (R10);
+ * BF16 blocks -> the fallback bits verbatim.  All arrays dense (leading dimension cols).
+ */
+int mor_oracle_dequantize(const uint8_t *fp8, const float *scale, const uint8_t *mask,
+                          const uint16_t *bf16, int64_t rows, int64_t cols, int gran,
+                          uint16_t *y)
+{
+    int64_t pr, pc, gr, gc, P;
+    if (rows <= 0 || cols <= 0 || part_shape(gran, rows, cols, &pr, &pc)) return -1;
+    gr = rows / pr; gc = cols / pc; P = gr * gc;
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t p = 0; p < P; ++p) {
+        int64_t br = p / gc, bc = p % gc;
+        volatile float s_inv = 1.0f / scale[p];
+        for (int64_t r = 0; r < pr; ++r)
+            for (int64_t c = 0; c < pc; ++c) {
+                int64_t i = (br * pr + r) * cols + bc * pc + c;
+                if (mask[p]) {
+                    if (!bf16) continue;
+                    y[i] = bf16[i];
+                } else {
+                    float q = (float)fp8_value(fp8[i], 4, 3);       /* exact in binary32 */
+                    volatile float v = q * s_inv;
+                    y[i] = mor_oracle_f32_to_bf16(v);
+                }
+            }
+    }
+    return 0;
+}
+
+/*
+ * Selection statistics over the per-block outputs (Section 4.1.3): block and element counts
+ * per chosen type, aggregate error, a 12-bin histogram of block metrics in 0.5 % steps with
+ * an open last bin, and the number of blocks whose metric lies within near_tol * threshold
+ * of the threshold.  The block metric is taken in binary32, err_sum / nnz (0 when nnz = 0),
+ * because it decides integer bin indices and both sides must decide in the same precision.
+ */
+typedef struct {
+    uint64_t n_part, n_fp8_part, n_bf16_part, n_elem_fp8, n_elem_bf16, nnz_total, n_near_threshold;
+    double err_sum_total, mean_err;
+    uint32_t hist[12];
+    uint32_t pad_;
+} oracle_stats;
+
+int mor_oracle_select_stats(const float *err_sum, const uint32_t *nnz, const uint8_t *mask,
+                            int64_t rows, int64_t cols, int gran, float threshold, float near_tol,
+                            oracle_stats *out)
+{
+    int64_t pr, pc, P;
+    if (rows <= 0 || cols <= 0 || part_shape(gran, rows, cols, &pr, &pc)) return -1;
+    P = (rows / pr) * (cols / pc);
+    memset(out, 0, sizeof *out);
+    out->n_part = (uint64_t)P;
+    for (int64_t p = 0; p < P; ++p) {
+        volatile float metric = nnz[p] ? err_sum[p] / (float)nnz[p] : 0.0f;
+        int bin = 0;
+        if (mask[p]) { out->n_bf16_part++; out->n_elem_bf16 += (uint64_t)(pr * pc); }
+        else         { out->n_fp8_part++;  out->n_elem_fp8  += (uint64_t)(pr * pc); }
+        out->err_sum_total += (double)err_sum[p];
+        out->nnz_total += nnz[p];
+        if (!(metric < INFINITY)) bin = 11;
+        else
+            for (int k = 1; k <= 11; ++k)
+                if (metric >= (float)(0.005 * k)) bin = k;
+        out->hist[bin]++;
+        if (fabs((double)metric - (double)threshold) <= (double)near_tol * (double)threshold)
+            out->n_near_threshold++;
+    }
+    out->mean_err = out->nnz_total ? out->err_sum_total / (double)out->nnz_total : 0.0;
+    return 0;
+}
+
+int mor_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

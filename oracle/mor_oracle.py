@@ -1,0 +1,195 @@
+"""ctypes front end of the CPU oracle (``mor_oracle.c``) -- TEST INFRASTRUCTURE ONLY.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py``
+may import this module.  It never touches the HIP library and the HIP binding never
+touches it.  Argument marshalling only: all arithmetic is in the C file.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mor_oracle.c")
+_LIB = os.path.join(_HERE, "libmor_oracle.so")
+
+GRAN = {"tensor": 0, "sub1x128": 1, "block128": 2}
+CRIT = {"mean_rel_err": 0, "e4m3_vs_e5m2": 1}
+SCOPE = {"partition": 0, "tensor": 1}
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (strict IEEE: no contraction, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c11", "-O2", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
+               "-Wall", "-Wextra", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class _Stats(C.Structure):
+    _fields_ = [("n_part", C.c_uint64), ("n_fp8_part", C.c_uint64), ("n_bf16_part", C.c_uint64),
+                ("n_elem_fp8", C.c_uint64), ("n_elem_bf16", C.c_uint64), ("nnz_total", C.c_uint64),
+                ("n_near_threshold", C.c_uint64),
+                ("err_sum_total", C.c_double), ("mean_err", C.c_double),
+                ("hist", C.c_uint32 * 12), ("pad_", C.c_uint32)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        L.mor_oracle_e4m3_encode.argtypes = [C.c_float]; L.mor_oracle_e4m3_encode.restype = C.c_uint8
+        L.mor_oracle_e5m2_encode.argtypes = [C.c_float]; L.mor_oracle_e5m2_encode.restype = C.c_uint8
+        L.mor_oracle_e4m3_decode.argtypes = [C.c_uint8]; L.mor_oracle_e4m3_decode.restype = C.c_double
+        L.mor_oracle_e5m2_decode.argtypes = [C.c_uint8]; L.mor_oracle_e5m2_decode.restype = C.c_double
+        L.mor_oracle_f32_to_bf16.argtypes = [C.c_float]; L.mor_oracle_f32_to_bf16.restype = C.c_uint16
+        L.mor_oracle_scale.argtypes = [C.c_float, C.c_float]; L.mor_oracle_scale.restype = C.c_float
+        L.mor_oracle_num_partitions.argtypes = [C.c_int, C.c_int64, C.c_int64]
+        L.mor_oracle_num_partitions.restype = C.c_int64
+        L.mor_oracle_analyze_quantize.argtypes = [
+            C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_float,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+            C.c_void_p, C.c_void_p]
+        L.mor_oracle_analyze_quantize.restype = C.c_int
+        L.mor_oracle_dequantize.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_int64, C.c_int64, C.c_int, C.c_void_p]
+        L.mor_oracle_dequantize.restype = C.c_int
+        L.mor_oracle_select_stats.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+                                              C.c_int, C.c_float, C.c_float, C.POINTER(_Stats)]
+        L.mor_oracle_select_stats.restype = C.c_int
+        L.mor_oracle_threads.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def e4m3_encode(y: float) -> int:
+    return int(lib().mor_oracle_e4m3_encode(float(np.float32(y))))
+
+
+def e5m2_encode(y: float) -> int:
+    return int(lib().mor_oracle_e5m2_encode(float(np.float32(y))))
+
+
+def e4m3_decode(code: int) -> float:
+    return float(lib().mor_oracle_e4m3_decode(int(code)))
+
+
+def e5m2_decode(code: int) -> float:
+    return float(lib().mor_oracle_e5m2_decode(int(code)))
+
+
+def e4m3_encode_array(y: np.ndarray) -> np.ndarray:
+    f = lib().mor_oracle_e4m3_encode
+    y = np.asarray(y, dtype=np.float32)
+    return np.fromiter((f(float(v)) for v in y.reshape(-1)), dtype=np.uint8, count=y.size).reshape(y.shape)
+
+
+def e5m2_encode_array(y: np.ndarray) -> np.ndarray:
+    f = lib().mor_oracle_e5m2_encode
+    y = np.asarray(y, dtype=np.float32)
+    return np.fromiter((f(float(v)) for v in y.reshape(-1)), dtype=np.uint8, count=y.size).reshape(y.shape)
+
+
+def f32_to_bf16(v: float) -> int:
+    return int(lib().mor_oracle_f32_to_bf16(float(np.float32(v))))
+
+
+def scale(amax: float, q_amax: float = 448.0) -> float:
+    return float(lib().mor_oracle_scale(float(np.float32(amax)), float(q_amax)))
+
+
+def num_partitions(gran: str, rows: int, cols: int) -> int:
+    return int(lib().mor_oracle_num_partitions(GRAN[gran], rows, cols))
+
+
+def threads() -> int:
+    return int(lib().mor_oracle_threads())
+
+
+@dataclass
+class Analysis:
+    fp8: np.ndarray            # (rows, cols) uint8, E4M3 codes of every block
+    bf16: np.ndarray           # (rows, cols) uint16, input bits where mask == 1, `fill` elsewhere
+    scale: np.ndarray          # (P,) float32
+    amax: np.ndarray           # (P,) float32
+    err_sum: np.ndarray        # (P,) float64
+    nnz: np.ndarray            # (P,) uint32
+    mask: np.ndarray           # (P,) uint8, 0 = E4M3, 1 = BF16
+    err5_sum: np.ndarray       # (P,) float64 (zeros unless criterion is e4m3_vs_e5m2)
+    err_sum_unscaled: np.ndarray  # (P,) float64, Eq. (2) evaluated in the unscaled domain
+
+    def metric(self) -> np.ndarray:
+        n = self.nnz.astype(np.float64)
+        with np.errstate(invalid="ignore", divide="ignore"):
+            return np.where(n > 0, self.err_sum / np.maximum(n, 1), 0.0)
+
+
+def analyze_quantize(x: np.ndarray, gran: str, scope: str = "partition", crit: str = "mean_rel_err",
+                     threshold: float = 0.045, bf16_fill: int = 0, ld: int | None = None,
+                     cols: int | None = None) -> Analysis:
+    """Run the oracle on BF16 bit patterns ``x`` (2-D uint16).  ``ld``/``cols`` allow a padded
+    leading dimension: ``x`` is then (rows, ld) and only the first ``cols`` columns are used."""
+    x = np.ascontiguousarray(x, dtype=np.uint16)
+    rows = x.shape[0]
+    ld = x.shape[1] if ld is None else ld
+    cols = x.shape[1] if cols is None else cols
+    P = num_partitions(gran, rows, cols)
+    if P < 0:
+        raise ValueError(f"bad shape {rows}x{cols} for granularity {gran}")
+    fp8 = np.zeros((rows, cols), np.uint8)
+    bf16 = np.full((rows, cols), bf16_fill, np.uint16)
+    sc = np.zeros(P, np.float32); am = np.zeros(P, np.float32)
+    es = np.zeros(P, np.float64); e5 = np.zeros(P, np.float64); eu = np.zeros(P, np.float64)
+    nz = np.zeros(P, np.uint32); mk = np.zeros(P, np.uint8)
+    rc = lib().mor_oracle_analyze_quantize(
+        _p(x), rows, cols, ld, GRAN[gran], SCOPE[scope], CRIT[crit], float(np.float32(threshold)),
+        _p(fp8), _p(bf16), _p(sc), _p(am), _p(es), _p(nz), _p(mk), _p(e5), _p(eu))
+    if rc != 0:
+        raise ValueError("mor_oracle_analyze_quantize rejected the arguments")
+    return Analysis(fp8, bf16, sc, am, es, nz, mk, e5, eu)
+
+
+def dequantize(fp8: np.ndarray, scale_: np.ndarray, mask: np.ndarray, bf16: np.ndarray | None,
+               gran: str, fill: int = 0) -> np.ndarray:
+    fp8 = np.ascontiguousarray(fp8, dtype=np.uint8)
+    rows, cols = fp8.shape
+    y = np.full((rows, cols), fill, np.uint16)
+    scale_ = np.ascontiguousarray(scale_, np.float32)
+    mask = np.ascontiguousarray(mask, np.uint8)
+    if bf16 is not None:
+        bf16 = np.ascontiguousarray(bf16, np.uint16)
+    rc = lib().mor_oracle_dequantize(_p(fp8), _p(scale_), _p(mask), _p(bf16), rows, cols, GRAN[gran], _p(y))
+    if rc != 0:
+        raise ValueError("mor_oracle_dequantize rejected the arguments")
+    return y
+
+
+def select_stats(err_sum: np.ndarray, nnz: np.ndarray, mask: np.ndarray, rows: int, cols: int, gran: str,
+                 threshold: float = 0.045, near_tol: float = 1e-5) -> dict:
+    err_sum = np.ascontiguousarray(err_sum, np.float32)
+    nnz = np.ascontiguousarray(nnz, np.uint32)
+    mask = np.ascontiguousarray(mask, np.uint8)
+    st = _Stats()
+    rc = lib().mor_oracle_select_stats(_p(err_sum), _p(nnz), _p(mask), rows, cols, GRAN[gran],
+                                       float(np.float32(threshold)), float(np.float32(near_tol)), C.byref(st))
+    if rc != 0:
+        raise ValueError("mor_oracle_select_stats rejected the arguments")
+    d = {k: getattr(st, k) for k, _ in _Stats._fields_ if k not in ("hist", "pad_")}
+    d["hist"] = [int(v) for v in st.hist]
+    return d
+
+
+if __name__ == "__main__":
+    print(build(force=True))

@@ -1,0 +1,121 @@
+"""Test-only third implementation of the analyse-select-quantize definitions in exact rational
+arithmetic (``fractions``), for tiny inputs.  Independent of both the C oracle and the HIP path:
+it is written directly from the format definitions (Section 1-2 of the paper) and Eq. (1)-(3).
+Only the two binary32 roundings the method fixes (scale = fl32(q_amax/amax), y = fl32(x*s)) use
+numpy float32 as a library primitive."""
+from fractions import Fraction
+import bisect
+import math
+
+import numpy as np
+
+
+def fp8_values(ebits, mbits):
+    """code -> exact value for all non-negative finite codes, from the format definition."""
+    bias = 2 ** (ebits - 1) - 1
+    vals = {}
+    for code in range(128):
+        e = code >> mbits
+        m = code & (2 ** mbits - 1)
+        if ebits == 4 and e == 15 and m == 7:
+            continue                      # E4M3: S.1111.111 is NaN, there are no infinities
+        if ebits == 5 and e == 31:
+            continue                      # E5M2: inf / NaN
+        if e == 0:
+            v = Fraction(m, 2 ** mbits) * Fraction(2) ** (1 - bias)
+        else:
+            v = (1 + Fraction(m, 2 ** mbits)) * Fraction(2) ** (e - bias)
+        vals[code] = v
+    return vals
+
+
+_TABLES = {}
+
+
+def _table(ebits, mbits):
+    key = (ebits, mbits)
+    if key not in _TABLES:
+        vals = fp8_values(ebits, mbits)
+        codes = sorted(vals, key=lambda c: vals[c])
+        _TABLES[key] = (codes, [vals[c] for c in codes])
+    return _TABLES[key]
+
+
+def fp8_encode(y, ebits, mbits):
+    """Nearest representable value, ties to the even code, clip beyond the largest finite value."""
+    y = float(y)
+    sign = 0x80 if math.copysign(1.0, y) < 0 else 0
+    if math.isnan(y):
+        return sign | 0x7F
+    codes, values = _table(ebits, mbits)
+    if math.isinf(y):
+        return sign | codes[-1]
+    a = abs(Fraction(y))
+    if a >= values[-1]:
+        return sign | codes[-1]
+    i = bisect.bisect_right(values, a) - 1          # values[i] <= a < values[i+1]
+    dlo, dhi = a - values[i], values[i + 1] - a
+    if dlo < dhi:
+        pick = codes[i]
+    elif dhi < dlo:
+        pick = codes[i + 1]
+    else:
+        pick = codes[i] if codes[i] % 2 == 0 else codes[i + 1]
+    return sign | pick
+
+
+def fp8_decode(code, ebits, mbits):
+    codes, values = _table(ebits, mbits)
+    v = fp8_values(ebits, mbits)[code & 0x7F]
+    return -v if code & 0x80 else v
+
+
+def bf16_to_f32(b):
+    return np.array([int(b) << 16], dtype=np.uint32).view(np.float32)[0]
+
+
+def scale_of(amax, qmax):
+    amax = np.float32(amax)
+    if not np.isfinite(amax) or amax == 0:
+        return np.float32(1.0)
+    with np.errstate(over="ignore"):
+        s = np.float32(qmax) / amax
+    return np.float32(np.finfo(np.float32).max) if np.isinf(s) else s
+
+
+def analyze_block(bits, crit="mean_rel_err", threshold=0.045):
+    """bits: iterable of BF16 bit patterns of ONE block.  Returns dict with exact-rational sums."""
+    bits = [int(b) for b in bits]
+    a = max(b & 0x7FFF for b in bits)
+    amax = bf16_to_f32(a)
+    out = {"amax": float(amax), "nnz": sum(1 for b in bits if b & 0x7FFF)}
+
+    def run(qmax, ebits, mbits):
+        s = scale_of(amax, qmax)
+        codes, total = [], Fraction(0)
+        for b in bits:
+            with np.errstate(over="ignore", under="ignore", invalid="ignore"):
+                y = np.float32(bf16_to_f32(b) * s)
+            c = fp8_encode(y, ebits, mbits)
+            codes.append(c)
+            if b & 0x7FFF == 0:
+                continue
+            q = fp8_decode(c, ebits, mbits)
+            if q == 0:
+                total += 1
+            else:
+                yy = Fraction(float(y))
+                total += abs(yy - q) / abs(yy)
+        return float(s), codes, total
+
+    s, codes, err = run(448.0, 4, 3)
+    out.update(scale=s, codes=codes, err_sum=err)
+    if crit == "e4m3_vs_e5m2":
+        _, _, err5 = run(57344.0, 5, 2)
+        out["err5_sum"] = err5
+        out["fp8"] = err < err5
+    else:
+        metric = err / out["nnz"] if out["nnz"] else Fraction(0)
+        out["metric"] = metric
+        out["fp8"] = metric < Fraction(float(np.float32(threshold)))
+    return out
