@@ -1,0 +1,172 @@
+/*
+ * mor.h -- C ABI of the MI355X (gfx950) MoR analyse-select-quantize library.
+ *
+ * MoR (Mixture of Representations) takes a BF16 GEMM operand X, a partition B of
+ * X into blocks, an ordered list of representation types and acceptance metrics,
+ * and returns the quantized tensor X_Q plus per-block metadata D (Algorithm 2).
+ * This library implements the recipe with the type list [E4M3, BF16]:
+ * for every block it computes amax and an FP32 scale (Algorithm 1, in its plain
+ * per-block FP32 form), quantizes to FP8 E4M3, evaluates the acceptance metric
+ * (Eq. 1-2 or Eq. 3) on the de-quantized values, and keeps either the FP8
+ * payload or the original BF16 block.
+ *
+ * Conventions shared by all entry points
+ *   - Every data pointer is DEVICE memory owned by the caller.  mor_params and
+ *     mor_outputs themselves are HOST structs, read before the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work on it; they never allocate, free or synchronize.
+ *     Results are valid once the stream has reached the end of the call's work.
+ *   - Tensors are row-major; a leading dimension `ld` counts ELEMENTS between
+ *     the starts of consecutive rows.
+ *   - Blocks are numbered row-major over the block grid: for 1x128 sub-channels
+ *     p = r * (cols/128) + c/128, for 128x128 blocks p = (r/128)*(cols/128) + c/128,
+ *     for per-tensor granularity there is one block, p = 0.  P = number of blocks.
+ *   - mask[p] = 0: block kept as FP8 E4M3;  mask[p] = 1: block kept as BF16.
+ *   - Argument errors are reported synchronously through the return code and
+ *     nothing is launched.  Non-finite data is not an error: a block holding Inf
+ *     or NaN gets scale 1, err_sum = +inf and is kept in BF16.
+ *   - No call is made into any CPU fallback: without a working HIP device the
+ *     entry points return MOR_ERR_HIP.
+ */
+#ifndef MOR_H_
+#define MOR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOR_OK = 0,
+    MOR_ERR_NULL = 1,        /* a required pointer is NULL */
+    MOR_ERR_SHAPE = 2,       /* rows/cols <= 0, ld < cols, or not a multiple of the block shape */
+    MOR_ERR_ALIGN = 3,       /* a pointer is not 16-byte aligned or a leading dimension breaks 16-byte rows */
+    MOR_ERR_UNSUPPORTED = 4, /* enum value or format set this build does not implement */
+    MOR_ERR_WORKSPACE = 5,   /* workspace NULL or smaller than mor_workspace_bytes() */
+    MOR_ERR_HIP = 6          /* a HIP launch or runtime call failed */
+} mor_status;
+
+/* The partition B of the tensor (Section 3, first paragraph). */
+typedef enum {
+    MOR_GRAN_TENSOR = 0,        /* one block: the whole tensor */
+    MOR_GRAN_SUB_1x128 = 1,     /* sub-channel blocks of 1 x 128 along the columns; cols % 128 == 0 */
+    MOR_GRAN_BLOCK_128x128 = 2  /* 2-D blocks of 128 x 128; rows % 128 == 0 and cols % 128 == 0 */
+} mor_granularity;
+
+/* Representation types, most to least aggressive (Section 3); `formats` is a bit-or. */
+enum { MOR_FMT_E4M3 = 1, MOR_FMT_E5M2 = 2, MOR_FMT_BF16 = 4 };
+
+/* Acceptance metric M_1 for E4M3. */
+typedef enum {
+    MOR_CRIT_MEAN_REL_ERR = 0,  /* Eq. (1)-(2): mean relative error over non-zeros < threshold */
+    MOR_CRIT_E4M3_VS_E5M2 = 1   /* Eq. (3), two-way recipe of Section 3.2: total relative error of
+                                   E4M3 strictly below that of E5M2; E5M2 itself is never emitted */
+} mor_criterion;
+
+/* Where the decision is taken. */
+typedef enum {
+    MOR_SCOPE_PARTITION = 0,    /* sub-tensor MoR (Section 3.2): one decision per block */
+    MOR_SCOPE_TENSOR = 1        /* tensor-level MoR (Section 3.1): block error sums are aggregated,
+                                   sum(err_sum)/sum(nnz) (or the two Eq. 3 totals) decides once and
+                                   every mask[p] receives that decision */
+} mor_scope;
+
+/* How the per-block scale is formed. */
+typedef enum {
+    MOR_SCALE_FP32_AMAX = 0     /* s = fl32(448 / amax), "standard per-block FP32 amax scaling"
+                                   (Section 4.1.2).  amax == 0 -> s = 1; an overflowing quotient
+                                   -> s = FLT_MAX; non-finite amax -> s = 1. */
+} mor_scaling;
+
+typedef struct mor_params {
+    int64_t  rows, cols;  /* operand shape, elements */
+    int64_t  ld;          /* leading dimension of x in elements, >= cols, multiple of 8 */
+    int32_t  granularity; /* mor_granularity */
+    int32_t  scope;       /* mor_scope */
+    int32_t  criterion;   /* mor_criterion */
+    int32_t  scaling;     /* mor_scaling */
+    uint32_t formats;     /* must be MOR_FMT_E4M3 | MOR_FMT_BF16 */
+    float    threshold;   /* th_E4M3 of Eq. (2), e.g. 0.045f (Section 4.1.1); ignored for Eq. (3) */
+} mor_params;
+
+typedef struct mor_outputs {
+    uint8_t*  fp8;      /* [rows x ld_fp8] E4M3 codes, written for EVERY block (also BF16 ones) */
+    int64_t   ld_fp8;   /* >= cols, multiple of 8 */
+    uint16_t* bf16;     /* [rows x ld_bf16] BF16 fallback: input bits, written ONLY in blocks with
+                           mask == 1, other regions untouched.  May be NULL (no payload emitted)
+                           and may equal the input pointer (writes are then skipped). */
+    int64_t   ld_bf16;  /* >= cols, multiple of 8 (ignored when bf16 is NULL) */
+    float*    scale;    /* [P] multiplier s: q = E4M3(fl32(x * s)) */
+    float*    amax;     /* [P] max |x| of the block (a BF16 value widened to float) */
+    float*    err_sum;  /* [P] sum over non-zero x of |y - q| / |y|, y = fl32(x * s); a non-zero x
+                           whose q is zero contributes 1 */
+    uint32_t* nnz;      /* [P] number of non-zero elements (+-0 excluded) */
+    uint8_t*  mask;     /* [P] 0 = E4M3, 1 = BF16 */
+    float*    err5_sum; /* [P] the same error sum for E5M2 with s5 = fl32(57344 / amax); required
+                           for MOR_CRIT_E4M3_VS_E5M2, otherwise ignored and may be NULL */
+} mor_outputs;
+
+/* Selection statistics (Section 4.1.3). Lives in DEVICE memory; 8-byte aligned. */
+typedef struct mor_stats {
+    uint64_t n_part;            /* P */
+    uint64_t n_fp8_part;        /* blocks with mask == 0 */
+    uint64_t n_bf16_part;       /* blocks with mask == 1 */
+    uint64_t n_elem_fp8;        /* elements inside FP8 blocks */
+    uint64_t n_elem_bf16;       /* elements inside BF16 blocks */
+    uint64_t nnz_total;         /* sum of nnz */
+    uint64_t n_near_threshold;  /* blocks with |metric - th| <= near_tol * th */
+    double   err_sum_total;     /* sum of err_sum */
+    double   mean_err;          /* err_sum_total / nnz_total (0 when nnz_total == 0) */
+    uint32_t hist[12];          /* block metrics err_sum/nnz (binary32) in bins [0,0.5%), [0.5%,1%),
+                                   ..., [5%,5.5%), [5.5%, inf] */
+    uint32_t reserved;          /* used internally as a completion counter; reads back 0 */
+} mor_stats;
+
+/* Number of blocks for a shape, or -1 if the shape is invalid for the granularity. */
+int64_t mor_num_partitions(int32_t granularity, int64_t rows, int64_t cols);
+
+/* Bytes of device scratch mor_analyze_quantize needs for these parameters (0 on invalid
+ * parameters).  Contents need no initialisation and are meaningless afterwards. */
+size_t mor_workspace_bytes(const mor_params* params);
+
+/*
+ * Algorithm 2 with [E4M3, BF16] over one operand.
+ *   x          device, [rows x ld] BF16 bit patterns, 16-byte aligned, read-only
+ *   out        host struct of device pointers, see mor_outputs
+ *   workspace  device scratch of at least mor_workspace_bytes(params) bytes, 16-byte aligned;
+ *              may be NULL when that size is 0
+ * One fused pass for sub-tensor granularities; per-tensor granularity needs the global amax
+ * first and therefore reads x twice.  Concurrent calls must not share a workspace.
+ */
+mor_status mor_analyze_quantize(const mor_params* params, const uint16_t* x, const mor_outputs* out,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Inverse path (the de-quantize / de-scale half of the fake-quantization workflow, Section 4,
+ * Figure 4): y = bf16_rne(fl32(E4M3value(fp8) * fl32(1 / scale[p]))) in blocks with mask 0,
+ * y = bf16 fallback bits in blocks with mask 1.  `bf16` may be NULL only if no block has
+ * mask 1 is the caller's promise (masked blocks are then left untouched in y).
+ * Uses rows, cols and granularity of params; params->ld is ignored.
+ */
+mor_status mor_dequantize(const mor_params* params, const uint8_t* fp8, int64_t ld_fp8,
+                          const float* scale, const uint8_t* mask,
+                          const uint16_t* bf16, int64_t ld_bf16,
+                          uint16_t* y, int64_t ld_y, void* stream);
+
+/*
+ * Selection statistics of one analysed operand (Section 4.1.3): counts of blocks and elements
+ * per chosen type, aggregate error, 0.5 %-bin histogram of the block metrics, and the number of
+ * blocks within near_tol * threshold of the threshold.  err_sum, nnz, mask are the [P] arrays
+ * mor_analyze_quantize wrote; out_dev is a device mor_stats, fully overwritten.
+ */
+mor_status mor_select_stats(const mor_params* params, const float* err_sum, const uint32_t* nnz,
+                            const uint8_t* mask, float near_tol, mor_stats* out_dev, void* stream);
+
+const char* mor_status_string(mor_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOR_H_ */

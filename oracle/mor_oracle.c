@@ -187,6 +187,9 @@ static double block_error(const uint16_t *x, int64_t ld, int64_t pr, int64_t pc,
                           uint8_t *codes, int64_t ld_codes, double *unscaled_out)
 {
     double sum = 0.0, sum_u = 0.0;
+    /* rows of one large block (per-tensor granularity) are spread over threads; for small
+     * blocks the caller already runs one block per thread and this region stays serial */
+#pragma omp parallel for reduction(+ : sum, sum_u) schedule(static) if (pr >= 256)
     for (int64_t r = 0; r < pr; ++r) {
         for (int64_t c = 0; c < pc; ++c) {
             uint16_t b = x[r * ld + c];
@@ -271,7 +274,7 @@ int mor_oracle_analyze_quantize(const uint16_t *x, int64_t rows, int64_t cols, i
     if (rows <= 0 || cols <= 0 || ld < cols || part_shape(gran, rows, cols, &pr, &pc)) return -1;
     gr = rows / pr; gc = cols / pc; P = gr * gc;
 
-#pragma omp parallel for schedule(dynamic, 16)
+#pragma omp parallel for schedule(dynamic, 16) if (P > 1)
     for (int64_t p = 0; p < P; ++p) {
         int64_t br = p / gc, bc = p % gc;
         block_result res;

@@ -1,0 +1,185 @@
+"""Thin ctypes binding of ``libmor.so`` (the C ABI declared in ``include/mor.h``).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.  PyTorch is used for
+device memory and the current stream, nothing else.  There is no CPU fallback: if the library is
+missing or no GPU is present the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmor.so")
+
+MOR_GRAN_TENSOR, MOR_GRAN_SUB_1x128, MOR_GRAN_BLOCK_128x128 = 0, 1, 2
+MOR_FMT_E4M3, MOR_FMT_E5M2, MOR_FMT_BF16 = 1, 2, 4
+MOR_CRIT_MEAN_REL_ERR, MOR_CRIT_E4M3_VS_E5M2 = 0, 1
+MOR_SCOPE_PARTITION, MOR_SCOPE_TENSOR = 0, 1
+MOR_SCALE_FP32_AMAX = 0
+
+GRAN = {"tensor": MOR_GRAN_TENSOR, "sub1x128": MOR_GRAN_SUB_1x128, "block128": MOR_GRAN_BLOCK_128x128}
+CRIT = {"mean_rel_err": MOR_CRIT_MEAN_REL_ERR, "e4m3_vs_e5m2": MOR_CRIT_E4M3_VS_E5M2}
+SCOPE = {"partition": MOR_SCOPE_PARTITION, "tensor": MOR_SCOPE_TENSOR}
+
+EXPORTS = ("mor_num_partitions", "mor_workspace_bytes", "mor_analyze_quantize", "mor_dequantize",
+           "mor_select_stats", "mor_status_string")
+
+
+class MorParams(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64),
+                ("granularity", C.c_int32), ("scope", C.c_int32), ("criterion", C.c_int32), ("scaling", C.c_int32),
+                ("formats", C.c_uint32), ("threshold", C.c_float)]
+
+
+class MorOutputs(C.Structure):
+    _fields_ = [("fp8", C.c_void_p), ("ld_fp8", C.c_int64), ("bf16", C.c_void_p), ("ld_bf16", C.c_int64),
+                ("scale", C.c_void_p), ("amax", C.c_void_p), ("err_sum", C.c_void_p), ("nnz", C.c_void_p),
+                ("mask", C.c_void_p), ("err5_sum", C.c_void_p)]
+
+
+class MorStats(C.Structure):
+    _fields_ = [("n_part", C.c_uint64), ("n_fp8_part", C.c_uint64), ("n_bf16_part", C.c_uint64),
+                ("n_elem_fp8", C.c_uint64), ("n_elem_bf16", C.c_uint64), ("nnz_total", C.c_uint64),
+                ("n_near_threshold", C.c_uint64), ("err_sum_total", C.c_double), ("mean_err", C.c_double),
+                ("hist", C.c_uint32 * 12), ("reserved", C.c_uint32)]
+
+
+class MorError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        msg = load().mor_status_string(self.status).decode()
+        super().__init__(f"{where}: {msg} (status {self.status})")
+
+
+_lib = None
+
+
+def load():
+    """Load libmor.so (built in-tree by ``paper_2512_22804_amd.build``).  Raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} not built: run `python -m paper_2512_22804_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        L.mor_num_partitions.argtypes = [C.c_int32, C.c_int64, C.c_int64]
+        L.mor_num_partitions.restype = C.c_int64
+        L.mor_workspace_bytes.argtypes = [C.POINTER(MorParams)]
+        L.mor_workspace_bytes.restype = C.c_size_t
+        L.mor_analyze_quantize.argtypes = [C.POINTER(MorParams), C.c_void_p, C.POINTER(MorOutputs), C.c_void_p,
+                                           C.c_size_t, C.c_void_p]
+        L.mor_analyze_quantize.restype = C.c_int
+        L.mor_dequantize.argtypes = [C.POINTER(MorParams), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_int64, C.c_void_p, C.c_int64, C.c_void_p]
+        L.mor_dequantize.restype = C.c_int
+        L.mor_select_stats.argtypes = [C.POINTER(MorParams), C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p,
+                                       C.c_void_p]
+        L.mor_select_stats.restype = C.c_int
+        L.mor_status_string.argtypes = [C.c_int]
+        L.mor_status_string.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def make_params(rows: int, cols: int, gran: str | int, scope: str | int = "partition", crit: str | int = "mean_rel_err",
+                threshold: float = 0.045, ld: int | None = None, formats: int = MOR_FMT_E4M3 | MOR_FMT_BF16,
+                scaling: int = MOR_SCALE_FP32_AMAX) -> MorParams:
+    g = GRAN[gran] if isinstance(gran, str) else gran
+    s = SCOPE[scope] if isinstance(scope, str) else scope
+    c = CRIT[crit] if isinstance(crit, str) else crit
+    return MorParams(rows, cols, cols if ld is None else ld, g, s, c, scaling, formats, threshold)
+
+
+def mor_num_partitions(gran: str | int, rows: int, cols: int) -> int:
+    g = GRAN[gran] if isinstance(gran, str) else gran
+    return int(load().mor_num_partitions(g, rows, cols))
+
+
+def mor_workspace_bytes(params: MorParams) -> int:
+    return int(load().mor_workspace_bytes(C.byref(params)))
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+@dataclass
+class MorResult:
+    """Device buffers written by :func:`mor_analyze_quantize`."""
+    fp8: torch.Tensor        # (rows, ld_fp8) uint8 E4M3 codes
+    bf16: torch.Tensor | None  # (rows, ld_bf16) int16 BF16 bits, written only where mask == 1
+    scale: torch.Tensor      # (P,) float32
+    amax: torch.Tensor       # (P,) float32
+    err_sum: torch.Tensor    # (P,) float32
+    nnz: torch.Tensor        # (P,) int32 (bit pattern of uint32)
+    mask: torch.Tensor       # (P,) uint8
+    err5_sum: torch.Tensor | None
+    workspace: torch.Tensor | None
+    params: MorParams
+
+
+def alloc_outputs(params: MorParams, device, want_bf16: bool = True, bf16_fill: int | None = None) -> MorResult:
+    """Allocate the output buffers of one call (dense leading dimensions)."""
+    rows, cols = params.rows, params.cols
+    P = mor_num_partitions(params.granularity, rows, cols)
+    if P < 0:
+        raise MorError(2, "alloc_outputs")
+    fp8 = torch.empty((rows, cols), dtype=torch.uint8, device=device)
+    bf16 = None
+    if want_bf16:
+        bf16 = (torch.empty((rows, cols), dtype=torch.int16, device=device) if bf16_fill is None else
+                torch.full((rows, cols), bf16_fill if bf16_fill < 0x8000 else bf16_fill - 0x10000, dtype=torch.int16, device=device))
+    f32 = lambda: torch.empty(P, dtype=torch.float32, device=device)
+    err5 = f32() if params.criterion == MOR_CRIT_E4M3_VS_E5M2 else None
+    nbytes = mor_workspace_bytes(params)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device) if nbytes else None
+    return MorResult(fp8, bf16, f32(), f32(), f32(), torch.empty(P, dtype=torch.int32, device=device),
+                     torch.empty(P, dtype=torch.uint8, device=device), err5, ws, params)
+
+
+def mor_analyze_quantize(params: MorParams, x: torch.Tensor, out: MorResult) -> None:
+    """Enqueue the analyse-select-quantize pass of ``x`` (int16/bfloat16 device tensor holding BF16 bits,
+    row stride ``params.ld``) on the current stream, writing into ``out``."""
+    if not x.is_cuda:
+        raise ValueError("x must live in device memory")
+    o = MorOutputs(_ptr(out.fp8), out.fp8.stride(0), _ptr(out.bf16), out.bf16.stride(0) if out.bf16 is not None else 0,
+                   _ptr(out.scale), _ptr(out.amax), _ptr(out.err_sum), _ptr(out.nnz), _ptr(out.mask), _ptr(out.err5_sum))
+    ws = out.workspace
+    rc = load().mor_analyze_quantize(C.byref(params), _ptr(x), C.byref(o), _ptr(ws), ws.numel() if ws is not None else 0,
+                                     _stream())
+    if rc != 0:
+        raise MorError(rc, "mor_analyze_quantize")
+
+
+def mor_dequantize(params: MorParams, fp8: torch.Tensor, scale: torch.Tensor, mask: torch.Tensor,
+                   bf16: torch.Tensor | None, y: torch.Tensor) -> None:
+    rc = load().mor_dequantize(C.byref(params), _ptr(fp8), fp8.stride(0), _ptr(scale), _ptr(mask), _ptr(bf16),
+                               bf16.stride(0) if bf16 is not None else 0, _ptr(y), y.stride(0), _stream())
+    if rc != 0:
+        raise MorError(rc, "mor_dequantize")
+
+
+def mor_select_stats(params: MorParams, err_sum: torch.Tensor, nnz: torch.Tensor, mask: torch.Tensor,
+                     near_tol: float, out_dev: torch.Tensor) -> None:
+    """``out_dev``: device uint8 tensor of ``ctypes.sizeof(MorStats)`` bytes, 8-byte aligned."""
+    if out_dev.numel() * out_dev.element_size() < C.sizeof(MorStats):
+        raise ValueError("out_dev too small")
+    rc = load().mor_select_stats(C.byref(params), _ptr(err_sum), _ptr(nnz), _ptr(mask), near_tol, _ptr(out_dev), _stream())
+    if rc != 0:
+        raise MorError(rc, "mor_select_stats")
+
+
+def read_stats(out_dev: torch.Tensor) -> dict:
+    """Copy a device mor_stats back to the host as a dict (synchronizes)."""
+    raw = bytes(out_dev.cpu().numpy().tobytes()[:C.sizeof(MorStats)])
+    st = MorStats.from_buffer_copy(raw)
+    d = {k: getattr(st, k) for k, _ in MorStats._fields_ if k != "hist"}
+    d["hist"] = [int(v) for v in st.hist]
+    return d

@@ -1,0 +1,210 @@
+// Device-side building blocks of the MoR analyse-select-quantize kernels (gfx950 only).
+//
+// Arithmetic contract (must stay bit-identical for amax, scale, FP8 codes and nnz; the error
+// sums are binary32 and only need ~1e-6 relative accuracy):
+//   amax  = integer max of (bits & 0x7FFF) over the block's BF16 patterns;
+//   s     = fl32(448 / amax), one IEEE division (Algorithm 1: s = q_amax / amax);
+//   y     = fl32(x * s), one IEEE multiply -- this file must be compiled with
+//           -ffp-contract=off so the multiply is never fused into a later subtract;
+//   code  = OCP E4M3 round-to-nearest-even of y, magnitudes above 448 clipped to 448;
+//   term  = |y - q| / |y| for x != 0 (Eq. 1-2), exactly 1 when q == 0.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mor {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+constexpr float kE4M3Max = 448.0f;
+constexpr float kE5M2Max = 57344.0f;
+constexpr float kFltMax = 3.402823466e+38f;
+// Blocks whose amax (as BF16 bits) is below this take the branch-free element path.  Above
+// it (amax >= 2^25, Inf, NaN) x*s can round to an exact zero or be non-finite, which the
+// branch-free path does not model, so such blocks take the careful path.
+constexpr uint32_t kFastAmaxBits = 0x4C00u;
+constexpr uint32_t kInfBits = 0x7F80u;
+
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b)));
+}
+__device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b)));
+}
+
+// Scale of a block from its amax bits (BF16 pattern, sign cleared).
+__device__ __forceinline__ float scale_from_amax_bits(uint32_t abits, float q_amax) {
+    if (abits == 0u || abits >= kInfBits) return 1.0f;
+    float s = q_amax / __uint_as_float(abits << 16);   // correctly rounded IEEE division
+    return __builtin_fminf(s, kFltMax);                // +inf -> FLT_MAX
+}
+
+// ---- per-lane summary of 8 BF16 values held in a u32x4: packed amax and non-zero count
+struct Scan8 {
+    uint32_t amax2;   // two u16 running maxima of (bits & 0x7FFF)
+    uint32_t nz2;     // two u16 running counts of non-zero elements
+};
+__device__ __forceinline__ void scan8(const u32x4& raw, Scan8& sc) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        uint32_t m = raw[j] & 0x7FFF7FFFu;
+        sc.amax2 = pk_max_u16(sc.amax2, m);
+        sc.nz2 += pk_min_u16(m, 0x00010001u);
+    }
+}
+__device__ __forceinline__ uint32_t fold_max16(uint32_t v2) { return max(v2 & 0xFFFFu, v2 >> 16); }
+__device__ __forceinline__ uint32_t fold_add16(uint32_t v2) { return (v2 & 0xFFFFu) + (v2 >> 16); }
+
+// ---- E4M3: branch-free path ------------------------------------------------------------
+// Valid when the block's amax bits are < kFastAmaxBits: then |y| <= 448*(1+2^-23), so the
+// hardware conversion (round-to-nearest-even, no clipping needed) is the method's encoder,
+// and a non-zero x never produces y == 0.  clamp(|d| * rcp|y|) yields 0 for x == 0
+// (0 * inf = NaN clamps to 0) and 1 for flushed values (|y| * rcp|y|, or inf for
+// subnormal y, clamps to 1).
+template <bool E5M2>
+__device__ __forceinline__ int cvt_pk8(float a, float b, int old, bool hi) {
+    if constexpr (E5M2) return hi ? __builtin_amdgcn_cvt_pk_bf8_f32(a, b, old, true) : __builtin_amdgcn_cvt_pk_bf8_f32(a, b, old, false);
+    else return hi ? __builtin_amdgcn_cvt_pk_fp8_f32(a, b, old, true) : __builtin_amdgcn_cvt_pk_fp8_f32(a, b, old, false);
+}
+template <bool E5M2>
+__device__ __forceinline__ f32x2 cvt_pk_f32(int v, bool hi) {
+    if constexpr (E5M2) return hi ? __builtin_amdgcn_cvt_pk_f32_bf8(v, true) : __builtin_amdgcn_cvt_pk_f32_bf8(v, false);
+    else return hi ? __builtin_amdgcn_cvt_pk_f32_fp8(v, true) : __builtin_amdgcn_cvt_pk_f32_fp8(v, false);
+}
+__device__ __forceinline__ float rel_term(float y, float q) {
+    float d = y - q;
+    return __builtin_amdgcn_fmed3f(__builtin_fabsf(d) * __builtin_amdgcn_rcpf(__builtin_fabsf(y)), 0.0f, 1.0f);
+}
+
+// Quantize 8 values with scale s; returns the 8 codes (little-endian element order) and adds
+// the 8 error terms to err0/err1.
+template <bool E5M2>
+__device__ __forceinline__ u32x2 quant8_fast(const u32x4& raw, float s, float& err0, float& err1) {
+    int w0 = 0, w1 = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float y0 = __uint_as_float(raw[j] << 16) * s;
+        float y1 = __uint_as_float(raw[j] & 0xFFFF0000u) * s;
+        f32x2 q;
+        if (j == 0) { w0 = cvt_pk8<E5M2>(y0, y1, w0, false); q = cvt_pk_f32<E5M2>(w0, false); }
+        if (j == 1) { w0 = cvt_pk8<E5M2>(y0, y1, w0, true);  q = cvt_pk_f32<E5M2>(w0, true); }
+        if (j == 2) { w1 = cvt_pk8<E5M2>(y0, y1, w1, false); q = cvt_pk_f32<E5M2>(w1, false); }
+        if (j == 3) { w1 = cvt_pk8<E5M2>(y0, y1, w1, true);  q = cvt_pk_f32<E5M2>(w1, true); }
+        err0 += rel_term(y0, q.x);
+        err1 += rel_term(y1, q.y);
+    }
+    u32x2 r; r.x = (uint32_t)w0; r.y = (uint32_t)w1;
+    return r;
+}
+
+// ---- E4M3 / E5M2: careful path (any input) ------------------------------------------------
+template <bool E5M2>
+__device__ __forceinline__ uint32_t encode_careful(float y) {
+    constexpr float top = E5M2 ? kE5M2Max : kE4M3Max;
+    uint32_t sign = (__float_as_uint(y) >> 24) & 0x80u;
+    if (y != y) return sign | 0x7Fu;
+    float c = __builtin_fminf(__builtin_fmaxf(y, -top), top);      // clip; keeps -0
+    return (uint32_t)cvt_pk8<E5M2>(c, c, 0, false) & 0xFFu;
+}
+template <bool E5M2>
+__device__ __forceinline__ float term_careful(uint32_t xbits16, float y, uint32_t code) {
+    if ((xbits16 & 0x7FFFu) == 0u) return 0.0f;
+    float q = cvt_pk_f32<E5M2>((int)code, false).x;
+    if (q == 0.0f) return 1.0f;
+    return __builtin_fabsf(y - q) / __builtin_fabsf(y);
+}
+template <bool E5M2>
+__device__ __forceinline__ u32x2 quant8_careful(const u32x4& raw, float s, float& err0, float& err1) {
+    u32x2 r; r.x = 0u; r.y = 0u;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        uint32_t b0 = raw[j] & 0xFFFFu, b1 = raw[j] >> 16;
+        float y0 = __uint_as_float(b0 << 16) * s;
+        float y1 = __uint_as_float(b1 << 16) * s;
+        uint32_t c0 = encode_careful<E5M2>(y0), c1 = encode_careful<E5M2>(y1);
+        err0 += term_careful<E5M2>(b0, y0, c0);
+        err1 += term_careful<E5M2>(b1, y1, c1);
+        uint32_t two = c0 | (c1 << 8);
+        if (j < 2) r.x |= two << (16 * j); else r.y |= two << (16 * (j - 2));
+    }
+    return r;
+}
+
+// Quantize 8 values choosing the path from the block's amax bits (uniform per block).
+template <bool E5M2>
+__device__ __forceinline__ u32x2 quant8(const u32x4& raw, uint32_t abits, float s, float& err0, float& err1) {
+    if (abits < kFastAmaxBits) return quant8_fast<E5M2>(raw, s, err0, err1);
+    return quant8_careful<E5M2>(raw, s, err0, err1);
+}
+
+// ---- cross-lane reductions over the 16 lanes of a DPP row -----------------------------------
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each 8 lanes
+constexpr int kDppMirror = 0x140;     // lane i <-> 15-i inside each 16 lanes
+
+__device__ __forceinline__ uint32_t row_allmax_u32(uint32_t v) {
+    v = max(v, dpp_u32<kDppXor1>(v));
+    v = max(v, dpp_u32<kDppXor2>(v));
+    v = max(v, dpp_u32<kDppHalfMirror>(v));
+    v = max(v, dpp_u32<kDppMirror>(v));
+    return v;
+}
+__device__ __forceinline__ uint32_t row_allsum_u32(uint32_t v) {
+    v += dpp_u32<kDppXor1>(v);
+    v += dpp_u32<kDppXor2>(v);
+    v += dpp_u32<kDppHalfMirror>(v);
+    v += dpp_u32<kDppMirror>(v);
+    return v;
+}
+__device__ __forceinline__ float row_allsum_f32(float v) {
+    v += dpp_f32<kDppXor1>(v);
+    v += dpp_f32<kDppXor2>(v);
+    v += dpp_f32<kDppHalfMirror>(v);
+    v += dpp_f32<kDppMirror>(v);
+    return v;
+}
+// All 64 lanes: row results are uniform per row, so reading lanes 0,16,32,48 finishes the job.
+__device__ __forceinline__ uint32_t wave_allmax_u32(uint32_t v) {
+    v = row_allmax_u32(v);
+    uint32_t a = __builtin_amdgcn_readlane((int)v, 0), b = __builtin_amdgcn_readlane((int)v, 16);
+    uint32_t c = __builtin_amdgcn_readlane((int)v, 32), d = __builtin_amdgcn_readlane((int)v, 48);
+    return max(max(a, b), max(c, d));
+}
+__device__ __forceinline__ uint32_t wave_allsum_u32(uint32_t v) {
+    v = row_allsum_u32(v);
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 0) + (uint32_t)__builtin_amdgcn_readlane((int)v, 16) +
+           (uint32_t)__builtin_amdgcn_readlane((int)v, 32) + (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+}
+__device__ __forceinline__ float wave_allsum_f32(float v) {
+    v = row_allsum_f32(v);
+    float a = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    float b = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    float c = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return (a + b) + (c + d);
+}
+
+// ---- Algorithm 2 with [E4M3, BF16]: 0 = keep E4M3, 1 = keep BF16 ------------------------------
+__device__ __forceinline__ uint32_t decide_eq2(float err_sum, uint32_t nnz, float th) {
+    float metric = nnz ? err_sum / (float)nnz : 0.0f;
+    return (metric < th) ? 0u : 1u;               // false for NaN / inf
+}
+__device__ __forceinline__ uint32_t decide_eq3(float err4, float err5) { return (err4 < err5) ? 0u : 1u; }
+
+__device__ __forceinline__ u32x4 load16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
+__device__ __forceinline__ void store16(void* p, const u32x4& v) { *reinterpret_cast<u32x4*>(p) = v; }
+__device__ __forceinline__ void store8(void* p, const u32x2& v) { *reinterpret_cast<u32x2*>(p) = v; }
+
+}  // namespace mor

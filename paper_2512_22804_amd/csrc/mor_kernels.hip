@@ -1,0 +1,650 @@
+// HIP kernels of the MoR analyse-select-quantize path for gfx950 (MI355X), and their launchers.
+//
+// One fused HBM pass per operand for sub-tensor granularities: 128-bit BF16 loads, integer amax,
+// one IEEE division per block, hardware OCP-E4M3 conversion, relative-error reduction, decision
+// (Algorithm 2 with [E4M3, BF16]) and emission, all from registers.  Per-tensor granularity needs
+// the global amax before anything can be scaled and therefore reads the operand twice.
+// The path is HBM-bound: there is no contraction in it, so no MFMA.
+#include "mor_device.h"
+#include "mor_launch.h"
+
+namespace mor {
+
+enum { kCritEq2 = 0, kCritEq3 = 1 };
+
+// ======================================================================================
+// 1 x 128 sub-channel blocks (Section 3: sub-channel partition; DeepSeek-style activations)
+// A 16-lane DPP row owns one block at a time (16 lanes x 8 elements); a wave works on 4 blocks
+// per load instruction and keeps 4 loads in flight, so every reduction stays inside a row.
+// ======================================================================================
+template <int CRIT, bool DEFER>
+__device__ __forceinline__ void sub_block_body(const u32x4& raw, int l, int64_t p, const KOut& o, int64_t off_fp8,
+                                               int64_t off_bf16, float th) {
+    Scan8 sc{0u, 0u};
+    scan8(raw, sc);
+    const uint32_t abits = row_allmax_u32(fold_max16(sc.amax2));
+    const float s = scale_from_amax_bits(abits, kE4M3Max);
+    float e0 = 0.0f, e1 = 0.0f;
+    const u32x2 codes = quant8<false>(raw, abits, s, e0, e1);
+    store8(o.fp8 + off_fp8 + l * 8, codes);
+    float err = row_allsum_f32(e0 + e1);
+    const uint32_t nnz = row_allsum_u32(fold_add16(sc.nz2));
+    if (abits >= kInfBits) err = __builtin_inff();
+    float err5 = 0.0f;
+    if constexpr (CRIT == kCritEq3) {
+        const float s5 = scale_from_amax_bits(abits, kE5M2Max);
+        float f0 = 0.0f, f1 = 0.0f;
+        (void)quant8<true>(raw, abits, s5, f0, f1);
+        err5 = row_allsum_f32(f0 + f1);
+        if (abits >= kInfBits) err5 = __builtin_inff();
+    }
+    uint32_t mask = 0u;
+    if constexpr (!DEFER) mask = (CRIT == kCritEq3) ? decide_eq3(err, err5) : decide_eq2(err, nnz, th);
+    if (l == 0) {
+        o.scale[p] = s;
+        o.amax[p] = __uint_as_float(abits << 16);
+        o.err_sum[p] = err;
+        o.nnz[p] = nnz;
+        if constexpr (CRIT == kCritEq3) o.err5_sum[p] = err5;
+        if constexpr (!DEFER) o.mask[p] = (uint8_t)mask;
+    }
+    if constexpr (!DEFER) {
+        if (mask && o.bf16) store16(o.bf16 + off_bf16 + l * 8, raw);
+    }
+}
+
+// Dense operands (every leading dimension == cols): blocks are consecutive 256-byte runs.
+template <int CRIT, bool DEFER>
+__global__ __launch_bounds__(256) void k_sub1x128_flat(const uint16_t* __restrict__ x, KOut o, int64_t n_part, float th) {
+    const int lane = threadIdx.x & 63, g = lane >> 4, l = lane & 15;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t pbase = wave * 16 + g * 4;
+    u32x4 raw[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int64_t p = pbase + k;
+        if (p < n_part) raw[k] = load16(x + p * 128 + l * 8);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int64_t p = pbase + k;
+        if (p < n_part) sub_block_body<CRIT, DEFER>(raw[k], l, p, o, p * 128, p * 128, th);
+    }
+}
+
+// Strided operands: grid.x = 128-column block, grid.y strides over groups of 16 rows.
+template <int CRIT, bool DEFER>
+__global__ __launch_bounds__(256) void k_sub1x128_strided(const uint16_t* __restrict__ x, KShape sh, KOut o, float th) {
+    const int lane = threadIdx.x & 63, g = lane >> 4, l = lane & 15;
+    const int64_t cb = blockIdx.x, cpr = sh.cols / 128;
+    for (int64_t r = (int64_t)blockIdx.y * 16 + (threadIdx.x >> 6) * 4 + g; r < sh.rows; r += (int64_t)gridDim.y * 16) {
+        const u32x4 raw = load16(x + r * sh.ld + cb * 128 + l * 8);
+        sub_block_body<CRIT, DEFER>(raw, l, r * cpr + cb, o, r * o.ld_fp8 + cb * 128, r * o.ld_bf16 + cb * 128, th);
+    }
+}
+
+// ======================================================================================
+// 128 x 128 blocks (Section 4.1.1 "Per-Block"): one 256-thread workgroup per block, the whole
+// 32 KB tile lives in registers (8 x 16 B per lane); LDS only carries 4 per-wave partials.
+// ======================================================================================
+template <int CRIT, bool DEFER>
+__global__ __launch_bounds__(256) void k_block128(const uint16_t* __restrict__ x, KShape sh, KOut o, float th) {
+    __shared__ uint32_t sh_amax[4];
+    __shared__ float sh_err[4];
+    __shared__ float sh_err5[4];
+    __shared__ uint32_t sh_nnz[4];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, l = lane & 15;
+    const int64_t tc = blockIdx.x, tr = blockIdx.y;
+    const int64_t col = tc * 128 + l * 8;
+    const int64_t row0 = tr * 128 + w * 4 + (lane >> 4);
+    u32x4 raw[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) raw[i] = load16(x + (row0 + i * 16) * sh.ld + col);
+    Scan8 sc{0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) scan8(raw[i], sc);
+    const uint32_t wa = wave_allmax_u32(fold_max16(sc.amax2));
+    if (lane == 0) sh_amax[w] = wa;
+    __syncthreads();
+    const uint32_t abits = max(max(sh_amax[0], sh_amax[1]), max(sh_amax[2], sh_amax[3]));
+    const float s = scale_from_amax_bits(abits, kE4M3Max);
+    float e0 = 0.0f, e1 = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const u32x2 codes = quant8<false>(raw[i], abits, s, e0, e1);
+        store8(o.fp8 + (row0 + i * 16) * o.ld_fp8 + col, codes);
+    }
+    const float werr = wave_allsum_f32(e0 + e1);
+    const uint32_t wnnz = wave_allsum_u32(fold_add16(sc.nz2));
+    float werr5 = 0.0f;
+    if constexpr (CRIT == kCritEq3) {
+        const float s5 = scale_from_amax_bits(abits, kE5M2Max);
+        float f0 = 0.0f, f1 = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) (void)quant8<true>(raw[i], abits, s5, f0, f1);
+        werr5 = wave_allsum_f32(f0 + f1);
+    }
+    if (lane == 0) { sh_err[w] = werr; sh_nnz[w] = wnnz; sh_err5[w] = werr5; }
+    __syncthreads();
+    float err = (sh_err[0] + sh_err[1]) + (sh_err[2] + sh_err[3]);
+    float err5 = (sh_err5[0] + sh_err5[1]) + (sh_err5[2] + sh_err5[3]);
+    const uint32_t nnz = (sh_nnz[0] + sh_nnz[1]) + (sh_nnz[2] + sh_nnz[3]);
+    if (abits >= kInfBits) { err = __builtin_inff(); err5 = __builtin_inff(); }
+    uint32_t mask = 0u;
+    if constexpr (!DEFER) mask = (CRIT == kCritEq3) ? decide_eq3(err, err5) : decide_eq2(err, nnz, th);
+    if (threadIdx.x == 0) {
+        const int64_t p = tr * gridDim.x + tc;
+        o.scale[p] = s;
+        o.amax[p] = __uint_as_float(abits << 16);
+        o.err_sum[p] = err;
+        o.nnz[p] = nnz;
+        if constexpr (CRIT == kCritEq3) o.err5_sum[p] = err5;
+        if constexpr (!DEFER) o.mask[p] = (uint8_t)mask;
+    }
+    if constexpr (!DEFER) {
+        if (mask && o.bf16) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) store16(o.bf16 + (row0 + i * 16) * o.ld_bf16 + col, raw[i]);
+        }
+    }
+}
+
+// ======================================================================================
+// Per-tensor granularity (Section 4.1.1 "Per-Tensor"): pass A = global amax, pass B = quantize
+// with the global scale + per-workgroup error partials, finalize = decision, then a conditional
+// copy of the BF16 fallback.  Everything is stream-ordered; the host never waits.
+// ======================================================================================
+constexpr int kTensorChunksPerThread = 8;                       // 16-byte chunks per thread in pass B
+constexpr int kTensorChunksPerBlock = 256 * kTensorChunksPerThread;
+constexpr int kMaxAmaxBlocks = 1024;
+
+__device__ __forceinline__ uint32_t block_allmax_u32(uint32_t v, uint32_t* sh4) {
+    const uint32_t wv = wave_allmax_u32(v);
+    if ((threadIdx.x & 63) == 0) sh4[threadIdx.x >> 6] = wv;
+    __syncthreads();
+    const uint32_t r = max(max(sh4[0], sh4[1]), max(sh4[2], sh4[3]));
+    __syncthreads();
+    return r;
+}
+
+// Pass A, dense: grid-stride over 16-byte chunks.
+__global__ __launch_bounds__(256) void k_tensor_amax_flat(const uint16_t* __restrict__ x, int64_t n_chunks,
+                                                          uint32_t* __restrict__ part) {
+    __shared__ uint32_t sh4[4];
+    uint32_t a2 = 0u;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < n_chunks; c += stride) {
+        const u32x4 v = load16(x + c * 8);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a2 = pk_max_u16(a2, v[j] & 0x7FFF7FFFu);
+    }
+    const uint32_t a = block_allmax_u32(fold_max16(a2), sh4);
+    if (threadIdx.x == 0) part[blockIdx.x] = a;
+}
+// Pass A, strided: one workgroup strides over rows; lanes stride over the row's chunks.
+__global__ __launch_bounds__(256) void k_tensor_amax_strided(const uint16_t* __restrict__ x, KShape sh,
+                                                             uint32_t* __restrict__ part) {
+    __shared__ uint32_t sh4[4];
+    uint32_t a2 = 0u;
+    const int64_t cpr = sh.cols / 8;
+    for (int64_t r = blockIdx.x; r < sh.rows; r += gridDim.x)
+        for (int64_t c = threadIdx.x; c < cpr; c += 256) {
+            const u32x4 v = load16(x + r * sh.ld + c * 8);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a2 = pk_max_u16(a2, v[j] & 0x7FFF7FFFu);
+        }
+    const uint32_t a = block_allmax_u32(fold_max16(a2), sh4);
+    if (threadIdx.x == 0) part[blockIdx.x] = a;
+}
+
+__device__ __forceinline__ uint32_t global_amax_bits(const uint32_t* __restrict__ part, int n_part_amax, uint32_t* sh4) {
+    uint32_t a = 0u;
+    for (int i = threadIdx.x; i < n_part_amax; i += 256) a = max(a, part[i]);
+    return block_allmax_u32(a, sh4);
+}
+
+struct TensorPartials {
+    float* err;
+    float* err5;
+    uint32_t* nnz;
+};
+
+template <int CRIT>
+__device__ __forceinline__ void tensor_block_finish(float e, float e5, uint32_t nz2, const TensorPartials& tp, int64_t slot,
+                                                    float* shf, uint32_t* shu) {
+    const float werr = wave_allsum_f32(e);
+    const uint32_t wnnz = wave_allsum_u32(fold_add16(nz2));
+    float werr5 = 0.0f;
+    if constexpr (CRIT == kCritEq3) werr5 = wave_allsum_f32(e5);
+    const int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { shf[w] = werr; shf[4 + w] = werr5; shu[w] = wnnz; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        tp.err[slot] = (shf[0] + shf[1]) + (shf[2] + shf[3]);
+        tp.nnz[slot] = (shu[0] + shu[1]) + (shu[2] + shu[3]);
+        if constexpr (CRIT == kCritEq3) tp.err5[slot] = (shf[4] + shf[5]) + (shf[6] + shf[7]);
+    }
+}
+
+// Pass B, dense: a workgroup owns 2048 consecutive chunks (32 KB of input).
+template <int CRIT>
+__global__ __launch_bounds__(256) void k_tensor_quant_flat(const uint16_t* __restrict__ x, int64_t n_chunks, KOut o,
+                                                           const uint32_t* __restrict__ amax_part, int n_amax_part,
+                                                           TensorPartials tp) {
+    __shared__ uint32_t sh4[4];
+    __shared__ float shf[8];
+    __shared__ uint32_t shu[4];
+    const int64_t c0 = (int64_t)blockIdx.x * kTensorChunksPerBlock + threadIdx.x;
+    u32x4 raw[kTensorChunksPerThread];
+#pragma unroll
+    for (int u = 0; u < kTensorChunksPerThread; ++u) {
+        const int64_t c = c0 + u * 256;
+        if (c < n_chunks) raw[u] = load16(x + c * 8);
+        else { raw[u].x = 0u; raw[u].y = 0u; raw[u].z = 0u; raw[u].w = 0u; }
+    }
+    const uint32_t abits = global_amax_bits(amax_part, n_amax_part, sh4);
+    const float s = scale_from_amax_bits(abits, kE4M3Max);
+    const float s5 = (CRIT == kCritEq3) ? scale_from_amax_bits(abits, kE5M2Max) : 0.0f;
+    Scan8 sc{0u, 0u};
+    float e0 = 0.0f, e1 = 0.0f, f0 = 0.0f, f1 = 0.0f;
+#pragma unroll
+    for (int u = 0; u < kTensorChunksPerThread; ++u) {
+        const int64_t c = c0 + u * 256;
+        scan8(raw[u], sc);
+        const u32x2 codes = quant8<false>(raw[u], abits, s, e0, e1);
+        if (c < n_chunks) store8(o.fp8 + c * 8, codes);
+        if constexpr (CRIT == kCritEq3) (void)quant8<true>(raw[u], abits, s5, f0, f1);
+    }
+    tensor_block_finish<CRIT>(e0 + e1, f0 + f1, sc.nz2, tp, blockIdx.x, shf, shu);
+}
+// Pass B, strided: a workgroup owns a 16-row x 128-column tile, one chunk per thread.
+template <int CRIT>
+__global__ __launch_bounds__(256) void k_tensor_quant_strided(const uint16_t* __restrict__ x, KShape sh, KOut o,
+                                                              const uint32_t* __restrict__ amax_part, int n_amax_part,
+                                                              TensorPartials tp) {
+    __shared__ uint32_t sh4[4];
+    __shared__ float shf[8];
+    __shared__ uint32_t shu[4];
+    const int64_t r = (int64_t)blockIdx.y * 16 + (threadIdx.x >> 4);
+    const int64_t c = (int64_t)blockIdx.x * 128 + (threadIdx.x & 15) * 8;
+    const bool live = r < sh.rows && c < sh.cols;
+    u32x4 raw; raw.x = 0u; raw.y = 0u; raw.z = 0u; raw.w = 0u;
+    if (live) raw = load16(x + r * sh.ld + c);
+    const uint32_t abits = global_amax_bits(amax_part, n_amax_part, sh4);
+    const float s = scale_from_amax_bits(abits, kE4M3Max);
+    Scan8 sc{0u, 0u};
+    float e0 = 0.0f, e1 = 0.0f, f0 = 0.0f, f1 = 0.0f;
+    scan8(raw, sc);
+    const u32x2 codes = quant8<false>(raw, abits, s, e0, e1);
+    if (live) store8(o.fp8 + r * o.ld_fp8 + c, codes);
+    if constexpr (CRIT == kCritEq3) (void)quant8<true>(raw, abits, scale_from_amax_bits(abits, kE5M2Max), f0, f1);
+    tensor_block_finish<CRIT>(e0 + e1, f0 + f1, sc.nz2, tp, (int64_t)blockIdx.y * gridDim.x + blockIdx.x, shf, shu);
+}
+
+template <typename T>
+__device__ __forceinline__ T block_sum_256(T v, T* sh) {
+    sh[threadIdx.x] = v;
+    __syncthreads();
+#pragma unroll
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) sh[threadIdx.x] += sh[threadIdx.x + s];
+        __syncthreads();
+    }
+    const T r = sh[0];
+    __syncthreads();
+    return r;
+}
+
+// Finalize: sum the partials in binary64, take the decision, write the block outputs (P = 1).
+template <int CRIT>
+__global__ __launch_bounds__(256) void k_tensor_finalize(TensorPartials tp, int64_t n_quant_part, const uint32_t* __restrict__ amax_part,
+                                                         int n_amax_part, KOut o, float th, uint32_t* __restrict__ decision) {
+    __shared__ uint32_t sh4[4];
+    __shared__ double shd[256];
+    __shared__ unsigned long long shl[256];
+    const uint32_t abits = global_amax_bits(amax_part, n_amax_part, sh4);
+    double e = 0.0, e5 = 0.0;
+    unsigned long long n = 0;
+    for (int64_t i = threadIdx.x; i < n_quant_part; i += 256) {
+        e += (double)tp.err[i];
+        n += tp.nnz[i];
+        if constexpr (CRIT == kCritEq3) e5 += (double)tp.err5[i];
+    }
+    e = block_sum_256<double>(e, shd);
+    n = block_sum_256<unsigned long long>(n, shl);
+    if constexpr (CRIT == kCritEq3) e5 = block_sum_256<double>(e5, shd);
+    if (threadIdx.x == 0) {
+        if (abits >= kInfBits) { e = (double)__builtin_inff(); e5 = e; }
+        uint32_t mask;
+        if constexpr (CRIT == kCritEq3) mask = (e < e5) ? 0u : 1u;
+        else mask = ((n ? e / (double)n : 0.0) < (double)th) ? 0u : 1u;
+        o.scale[0] = scale_from_amax_bits(abits, kE4M3Max);
+        o.amax[0] = __uint_as_float(abits << 16);
+        o.err_sum[0] = (float)e;
+        o.nnz[0] = n > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)n;
+        if constexpr (CRIT == kCritEq3) o.err5_sum[0] = (float)e5;
+        o.mask[0] = (uint8_t)mask;
+        decision[0] = mask;
+    }
+}
+
+// Conditional BF16 fallback copy: does nothing unless decision[0] == 1.
+__global__ __launch_bounds__(256) void k_fallback_copy_flat(const uint16_t* __restrict__ x, uint16_t* __restrict__ dst,
+                                                            int64_t n_chunks, const uint32_t* __restrict__ decision) {
+    if (decision[0] == 0u) return;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < n_chunks; c += stride) store16(dst + c * 8, load16(x + c * 8));
+}
+__global__ __launch_bounds__(256) void k_fallback_copy_strided(const uint16_t* __restrict__ x, KShape sh, uint16_t* __restrict__ dst,
+                                                               int64_t ld_dst, const uint32_t* __restrict__ decision) {
+    if (decision[0] == 0u) return;
+    const int64_t cpr = sh.cols / 8;
+    for (int64_t r = blockIdx.x; r < sh.rows; r += gridDim.x)
+        for (int64_t c = threadIdx.x; c < cpr; c += 256) store16(dst + r * ld_dst + c * 8, load16(x + r * sh.ld + c * 8));
+}
+
+// ======================================================================================
+// Tensor-level decision over sub-tensor scaling (Section 3.1): the deferred block kernels wrote
+// err_sum / nnz per block; aggregate sum(err_sum) / sum(nnz), decide once, broadcast the mask.
+// ======================================================================================
+struct ScopePartials {
+    double* err;
+    double* err5;
+    unsigned long long* nnz;
+};
+template <int CRIT>
+__global__ __launch_bounds__(256) void k_scope_reduce(KOut o, int64_t n_part, ScopePartials sp) {
+    __shared__ double shd[256];
+    __shared__ unsigned long long shl[256];
+    double e = 0.0, e5 = 0.0;
+    unsigned long long n = 0;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x; p < n_part; p += stride) {
+        e += (double)o.err_sum[p];
+        n += o.nnz[p];
+        if constexpr (CRIT == kCritEq3) e5 += (double)o.err5_sum[p];
+    }
+    e = block_sum_256<double>(e, shd);
+    n = block_sum_256<unsigned long long>(n, shl);
+    if constexpr (CRIT == kCritEq3) e5 = block_sum_256<double>(e5, shd);
+    if (threadIdx.x == 0) { sp.err[blockIdx.x] = e; sp.nnz[blockIdx.x] = n; if constexpr (CRIT == kCritEq3) sp.err5[blockIdx.x] = e5; }
+}
+template <int CRIT>
+__global__ __launch_bounds__(256) void k_scope_decide(ScopePartials sp, int n_blocks, float th, uint32_t* __restrict__ decision) {
+    __shared__ double shd[256];
+    __shared__ unsigned long long shl[256];
+    double e = 0.0, e5 = 0.0;
+    unsigned long long n = 0;
+    for (int i = threadIdx.x; i < n_blocks; i += 256) {
+        e += sp.err[i];
+        n += sp.nnz[i];
+        if constexpr (CRIT == kCritEq3) e5 += sp.err5[i];
+    }
+    e = block_sum_256<double>(e, shd);
+    n = block_sum_256<unsigned long long>(n, shl);
+    if constexpr (CRIT == kCritEq3) e5 = block_sum_256<double>(e5, shd);
+    if (threadIdx.x == 0) {
+        uint32_t mask;
+        if constexpr (CRIT == kCritEq3) mask = (e < e5) ? 0u : 1u;
+        else mask = ((n ? e / (double)n : 0.0) < (double)th) ? 0u : 1u;
+        decision[0] = mask;
+    }
+}
+__global__ __launch_bounds__(256) void k_scope_fill_mask(uint8_t* __restrict__ mask, int64_t n_part, const uint32_t* __restrict__ decision) {
+    const uint8_t m = (uint8_t)decision[0];
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x; p < n_part; p += stride) mask[p] = m;
+}
+
+// ======================================================================================
+// De-quantize / de-scale (Section 4, Figure 4): grid.x = 128-column block, grid.y strides over
+// groups of 16 rows, one 8-element chunk per thread.
+// ======================================================================================
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+    const uint32_t u = __float_as_uint(f);
+    if (f != f) return ((u >> 16) & 0x8000u) | 0x7FC0u;
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+template <int GRAN>
+__global__ __launch_bounds__(256) void k_dequant(int64_t rows, int64_t cols, const uint8_t* __restrict__ fp8, int64_t ld_fp8,
+                                                 const float* __restrict__ scale, const uint8_t* __restrict__ mask,
+                                                 const uint16_t* __restrict__ bf16, int64_t ld_bf16, uint16_t* __restrict__ y,
+                                                 int64_t ld_y) {
+    const int64_t cb = blockIdx.x, cpr = (cols + 127) / 128;
+    const int64_t c = cb * 128 + (threadIdx.x & 15) * 8;
+    if (c >= cols) return;
+    for (int64_t r = (int64_t)blockIdx.y * 16 + (threadIdx.x >> 4); r < rows; r += (int64_t)gridDim.y * 16) {
+        int64_t p = 0;
+        if (GRAN == 1) p = r * cpr + cb;
+        if (GRAN == 2) p = (r >> 7) * cpr + cb;
+        if (mask[p]) {
+            if (bf16) store16(y + r * ld_y + c, load16(bf16 + r * ld_bf16 + c));
+            continue;
+        }
+        const float s_inv = 1.0f / scale[p];                        // correctly rounded IEEE division
+        const u32x2 q = *reinterpret_cast<const u32x2*>(fp8 + r * ld_fp8 + c);
+        u32x4 out;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int word = (int)(j < 2 ? q.x : q.y);
+            const f32x2 v = (j & 1) ? cvt_pk_f32<false>(word, true) : cvt_pk_f32<false>(word, false);
+            out[j] = f32_to_bf16_rne(v.x * s_inv) | (f32_to_bf16_rne(v.y * s_inv) << 16);
+        }
+        store16(y + r * ld_y + c, out);
+    }
+}
+
+// ======================================================================================
+// Selection statistics (Section 4.1.3)
+// ======================================================================================
+struct StatsDev {   // must match mor_stats in include/mor.h
+    unsigned long long n_part, n_fp8_part, n_bf16_part, n_elem_fp8, n_elem_bf16, nnz_total, n_near_threshold;
+    double err_sum_total, mean_err;
+    uint32_t hist[12];
+    uint32_t reserved;
+};
+__global__ void k_stats_zero(StatsDev* st) {
+    if (threadIdx.x < sizeof(StatsDev) / 4) reinterpret_cast<uint32_t*>(st)[threadIdx.x] = 0u;
+}
+__global__ __launch_bounds__(256) void k_stats(int64_t n_part, unsigned long long elems_per_part, const float* __restrict__ err_sum,
+                                               const uint32_t* __restrict__ nnz, const uint8_t* __restrict__ mask, float th,
+                                               float near_tol, StatsDev* __restrict__ st) {
+    __shared__ uint32_t sh_hist[12];
+    __shared__ double shd[256];
+    __shared__ unsigned long long shl[256];
+    __shared__ bool last;
+    if (threadIdx.x < 12) sh_hist[threadIdx.x] = 0u;
+    __syncthreads();
+    double e = 0.0;
+    unsigned long long n = 0, n_bf16 = 0, n_near = 0;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x; p < n_part; p += stride) {
+        const float es = err_sum[p];
+        const uint32_t nz = nnz[p];
+        const float metric = nz ? es / (float)nz : 0.0f;           // binary32, IEEE division
+        int bin = 0;
+        if (!(metric < __builtin_inff())) bin = 11;
+        else {
+#pragma unroll
+            for (int k = 1; k <= 11; ++k)
+                if (metric >= (float)(0.005 * k)) bin = k;
+        }
+        atomicAdd(&sh_hist[bin], 1u);
+        e += (double)es;
+        n += nz;
+        n_bf16 += mask[p] ? 1u : 0u;
+        if (fabs((double)metric - (double)th) <= (double)near_tol * (double)th) n_near += 1u;
+    }
+    e = block_sum_256<double>(e, shd);
+    n = block_sum_256<unsigned long long>(n, shl);
+    n_bf16 = block_sum_256<unsigned long long>(n_bf16, shl);
+    n_near = block_sum_256<unsigned long long>(n_near, shl);
+    if (threadIdx.x < 12 && sh_hist[threadIdx.x]) atomicAdd(&st->hist[threadIdx.x], sh_hist[threadIdx.x]);
+    if (threadIdx.x == 0) {
+        atomicAdd(&st->err_sum_total, e);
+        atomicAdd(&st->nnz_total, n);
+        atomicAdd(&st->n_bf16_part, n_bf16);
+        atomicAdd(&st->n_near_threshold, n_near);
+    }
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) last = (atomicAdd(&st->reserved, 1u) == gridDim.x - 1);
+    __syncthreads();
+    if (last && threadIdx.x == 0) {
+        __threadfence();
+        const unsigned long long nb = atomicAdd(&st->n_bf16_part, 0ull);
+        const unsigned long long nn = atomicAdd(&st->nnz_total, 0ull);
+        const double et = atomicAdd(&st->err_sum_total, 0.0);
+        st->n_part = (unsigned long long)n_part;
+        st->n_fp8_part = (unsigned long long)n_part - nb;
+        st->n_elem_bf16 = nb * elems_per_part;
+        st->n_elem_fp8 = ((unsigned long long)n_part - nb) * elems_per_part;
+        st->mean_err = nn ? et / (double)nn : 0.0;
+        st->reserved = 0u;
+    }
+}
+
+// ======================================================================================
+// Launchers
+// ======================================================================================
+static inline size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
+
+static int64_t tensor_quant_blocks(int64_t rows, int64_t cols) {
+    const int64_t flat = (rows * cols / 8 + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
+    const int64_t strided = ((cols + 127) / 128) * ((rows + 15) / 16);
+    return flat > strided ? flat : strided;
+}
+
+TensorPlan plan_tensor(int64_t rows, int64_t cols) {
+    TensorPlan pl;
+    pl.amax_blocks = kMaxAmaxBlocks;
+    pl.quant_blocks = tensor_quant_blocks(rows, cols);
+    size_t off = 0;
+    pl.off_amax_part = off; off = align16(off + sizeof(uint32_t) * (size_t)pl.amax_blocks);
+    pl.off_err_part = off;  off = align16(off + sizeof(float) * (size_t)pl.quant_blocks);
+    pl.off_err5_part = off; off = align16(off + sizeof(float) * (size_t)pl.quant_blocks);
+    pl.off_nnz_part = off;  off = align16(off + sizeof(uint32_t) * (size_t)pl.quant_blocks);
+    pl.off_decision = off;  off = align16(off + 16);
+    pl.bytes = off;
+    return pl;
+}
+
+constexpr int kScopeBlocks = 256;
+size_t scope_workspace_bytes(int64_t) { return align16(3 * sizeof(double) * kScopeBlocks + 16); }
+
+static bool is_flat(const KShape& sh, const KOut& o) {
+    return sh.ld == sh.cols && o.ld_fp8 == sh.cols && (o.bf16 == nullptr || o.ld_bf16 == sh.cols);
+}
+static int clamp_grid_y(int64_t v) { return (int)(v < 1 ? 1 : (v > 65535 ? 65535 : v)); }
+
+#define MOR_DISPATCH_CRIT_DEFER(KERNEL, ...)                                                     \
+    do {                                                                                         \
+        if (crit == kCritEq3) { if (defer) KERNEL<kCritEq3, true> __VA_ARGS__; else KERNEL<kCritEq3, false> __VA_ARGS__; } \
+        else                  { if (defer) KERNEL<kCritEq2, true> __VA_ARGS__; else KERNEL<kCritEq2, false> __VA_ARGS__; } \
+    } while (0)
+
+hipError_t launch_sub1x128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st) {
+    const int64_t n_part = sh.rows * (sh.cols / 128);
+    if (is_flat(sh, o)) {
+        const int64_t blocks = (n_part + 63) / 64;
+        if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+        MOR_DISPATCH_CRIT_DEFER(k_sub1x128_flat, <<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, o, n_part, th));
+    } else {
+        const dim3 grid((unsigned)(sh.cols / 128), (unsigned)clamp_grid_y((sh.rows + 15) / 16));
+        MOR_DISPATCH_CRIT_DEFER(k_sub1x128_strided, <<<grid, dim3(256), 0, st>>>(x, sh, o, th));
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_block128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st) {
+    const int64_t tr = sh.rows / 128, tc = sh.cols / 128;
+    if (tr > 65535) return hipErrorInvalidValue;   // rows beyond 8.3 M are not supported by this launch shape
+    const dim3 grid((unsigned)tc, (unsigned)tr);
+    MOR_DISPATCH_CRIT_DEFER(k_block128, <<<grid, dim3(256), 0, st>>>(x, sh, o, th));
+    return hipGetLastError();
+}
+
+hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int crit, float th, void* ws, hipStream_t st) {
+    const TensorPlan pl = plan_tensor(sh.rows, sh.cols);
+    char* w = static_cast<char*>(ws);
+    uint32_t* amax_part = reinterpret_cast<uint32_t*>(w + pl.off_amax_part);
+    TensorPartials tp{reinterpret_cast<float*>(w + pl.off_err_part), reinterpret_cast<float*>(w + pl.off_err5_part),
+                      reinterpret_cast<uint32_t*>(w + pl.off_nnz_part)};
+    uint32_t* decision = reinterpret_cast<uint32_t*>(w + pl.off_decision);
+    const int64_t n_chunks = sh.rows * sh.cols / 8;
+    const bool flat = is_flat(sh, o);
+    int n_amax;
+    int64_t n_quant;
+    if (flat) {
+        int64_t want = (n_chunks + 256 * 8 - 1) / (256 * 8);
+        n_amax = (int)(want < 1 ? 1 : (want > kMaxAmaxBlocks ? kMaxAmaxBlocks : want));
+        k_tensor_amax_flat<<<dim3(n_amax), dim3(256), 0, st>>>(x, n_chunks, amax_part);
+        n_quant = (n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
+        if (n_quant > 0x7FFFFFFF) return hipErrorInvalidValue;
+        if (crit == kCritEq3) k_tensor_quant_flat<kCritEq3><<<dim3((unsigned)n_quant), dim3(256), 0, st>>>(x, n_chunks, o, amax_part, n_amax, tp);
+        else k_tensor_quant_flat<kCritEq2><<<dim3((unsigned)n_quant), dim3(256), 0, st>>>(x, n_chunks, o, amax_part, n_amax, tp);
+    } else {
+        n_amax = (int)(sh.rows < kMaxAmaxBlocks ? sh.rows : kMaxAmaxBlocks);
+        k_tensor_amax_strided<<<dim3(n_amax), dim3(256), 0, st>>>(x, sh, amax_part);
+        const int64_t gx = (sh.cols + 127) / 128, gy = (sh.rows + 15) / 16;
+        if (gy > 65535) return hipErrorInvalidValue;
+        n_quant = gx * gy;
+        const dim3 grid((unsigned)gx, (unsigned)gy);
+        if (crit == kCritEq3) k_tensor_quant_strided<kCritEq3><<<grid, dim3(256), 0, st>>>(x, sh, o, amax_part, n_amax, tp);
+        else k_tensor_quant_strided<kCritEq2><<<grid, dim3(256), 0, st>>>(x, sh, o, amax_part, n_amax, tp);
+    }
+    if (crit == kCritEq3) k_tensor_finalize<kCritEq3><<<dim3(1), dim3(256), 0, st>>>(tp, n_quant, amax_part, n_amax, o, th, decision);
+    else k_tensor_finalize<kCritEq2><<<dim3(1), dim3(256), 0, st>>>(tp, n_quant, amax_part, n_amax, o, th, decision);
+    if (o.bf16) {
+        if (flat) k_fallback_copy_flat<<<dim3(2048), dim3(256), 0, st>>>(x, o.bf16, n_chunks, decision);
+        else k_fallback_copy_strided<<<dim3((unsigned)(sh.rows < 4096 ? sh.rows : 4096)), dim3(256), 0, st>>>(x, sh, o.bf16, o.ld_bf16, decision);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_scope_finalize(const uint16_t* x, const KShape& sh, const KOut& o, int64_t n_part, int crit, float th,
+                                 void* ws, hipStream_t st) {
+    char* w = static_cast<char*>(ws);
+    ScopePartials sp{reinterpret_cast<double*>(w), reinterpret_cast<double*>(w) + kScopeBlocks,
+                     reinterpret_cast<unsigned long long*>(w) + 2 * kScopeBlocks};
+    uint32_t* decision = reinterpret_cast<uint32_t*>(w + 3 * sizeof(double) * kScopeBlocks);
+    int64_t want = (n_part + 1023) / 1024;
+    const int nb = (int)(want < 1 ? 1 : (want > kScopeBlocks ? kScopeBlocks : want));
+    if (crit == kCritEq3) {
+        k_scope_reduce<kCritEq3><<<dim3(nb), dim3(256), 0, st>>>(o, n_part, sp);
+        k_scope_decide<kCritEq3><<<dim3(1), dim3(256), 0, st>>>(sp, nb, th, decision);
+    } else {
+        k_scope_reduce<kCritEq2><<<dim3(nb), dim3(256), 0, st>>>(o, n_part, sp);
+        k_scope_decide<kCritEq2><<<dim3(1), dim3(256), 0, st>>>(sp, nb, th, decision);
+    }
+    k_scope_fill_mask<<<dim3(nb), dim3(256), 0, st>>>(o.mask, n_part, decision);
+    if (o.bf16) {
+        const bool flat = sh.ld == sh.cols && o.ld_bf16 == sh.cols;
+        if (flat) k_fallback_copy_flat<<<dim3(2048), dim3(256), 0, st>>>(x, o.bf16, sh.rows * sh.cols / 8, decision);
+        else k_fallback_copy_strided<<<dim3((unsigned)(sh.rows < 4096 ? sh.rows : 4096)), dim3(256), 0, st>>>(x, sh, o.bf16, o.ld_bf16, decision);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_dequantize(int gran, int64_t rows, int64_t cols, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
+                             const uint8_t* mask, const uint16_t* bf16, int64_t ld_bf16, uint16_t* y, int64_t ld_y,
+                             hipStream_t st) {
+    const dim3 grid((unsigned)((cols + 127) / 128), (unsigned)clamp_grid_y((rows + 15) / 16));
+    if (gran == 0) k_dequant<0><<<grid, dim3(256), 0, st>>>(rows, cols, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y);
+    else if (gran == 1) k_dequant<1><<<grid, dim3(256), 0, st>>>(rows, cols, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y);
+    else k_dequant<2><<<grid, dim3(256), 0, st>>>(rows, cols, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y);
+    return hipGetLastError();
+}
+
+hipError_t launch_select_stats(int64_t n_part, int64_t elems_per_part, const float* err_sum, const uint32_t* nnz,
+                               const uint8_t* mask, float th, float near_tol, void* out_dev, hipStream_t st) {
+    static_assert(sizeof(StatsDev) == 128, "mor_stats layout");
+    StatsDev* sd = static_cast<StatsDev*>(out_dev);
+    k_stats_zero<<<dim3(1), dim3(64), 0, st>>>(sd);
+    int64_t want = (n_part + 2047) / 2048;
+    const int nb = (int)(want < 1 ? 1 : (want > 256 ? 256 : want));
+    k_stats<<<dim3(nb), dim3(256), 0, st>>>(n_part, (unsigned long long)elems_per_part, err_sum, nnz, mask, th, near_tol, sd);
+    return hipGetLastError();
+}
+
+}  // namespace mor

@@ -1,0 +1,51 @@
+// Host-side launch interface between the C ABI (mor_api.hip) and the kernels (mor_kernels.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace mor {
+
+// Device pointers of one call, passed to kernels by value.
+struct KOut {
+    uint8_t*  fp8;      int64_t ld_fp8;
+    uint16_t* bf16;     int64_t ld_bf16;     // bf16 == nullptr: no fallback payload is written
+    float*    scale;
+    float*    amax;
+    float*    err_sum;
+    uint32_t* nnz;
+    uint8_t*  mask;
+    float*    err5_sum;
+};
+
+struct KShape {
+    int64_t rows, cols, ld;
+};
+
+// Workspace layout for the passes that need one (all offsets 16-byte aligned).
+struct TensorPlan {
+    int     amax_blocks;     // grid of the amax pass
+    int64_t quant_blocks;    // grid of the quantize pass
+    size_t  off_amax_part;   // uint32[amax_blocks]
+    size_t  off_err_part;    // float[quant_blocks]
+    size_t  off_err5_part;   // float[quant_blocks]
+    size_t  off_nnz_part;    // uint32[quant_blocks]
+    size_t  off_decision;    // uint32[4]: decision for the conditional fallback copy
+    size_t  bytes;
+};
+TensorPlan plan_tensor(int64_t rows, int64_t cols);
+size_t scope_workspace_bytes(int64_t n_part);
+
+hipError_t launch_sub1x128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st);
+hipError_t launch_block128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st);
+hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int crit, float th, void* ws, hipStream_t st);
+// Tensor-scope decision over per-block sums already written by a deferred sub-tensor pass.
+hipError_t launch_scope_finalize(const uint16_t* x, const KShape& sh, const KOut& o, int64_t n_part, int crit, float th,
+                                 void* ws, hipStream_t st);
+hipError_t launch_dequantize(int gran, int64_t rows, int64_t cols, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
+                             const uint8_t* mask, const uint16_t* bf16, int64_t ld_bf16, uint16_t* y, int64_t ld_y,
+                             hipStream_t st);
+hipError_t launch_select_stats(int64_t n_part, int64_t elems_per_part, const float* err_sum, const uint32_t* nnz,
+                               const uint8_t* mask, float th, float near_tol, void* out_dev, hipStream_t st);
+
+}  // namespace mor
