@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoR analyse-select-quantize hot path on one MI355X.
+
+A "step" is one pass of the whole path over the operand sweep of one Llama-style layer
+(hidden 4096, ffn 14336, 8192 tokens): for each of the 12 operands one ``mor_analyze_quantize``
+call (activation 1x128, weights 128x128, gradients per-tensor; Eq. 2, th = 4.5 %) followed by one
+``mor_select_stats`` call, all on one stream, inputs already resident in HBM.
+
+Prints ONE JSON line on stdout: whole-job throughput in GB/s of BF16 input, the roofline record
+of the dominant kernel (timed live with HIP events recorded by the library around each kernel),
+and the CPU oracle timed on a bounded sample of the same workload.  Everything else goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+META_BYTES = 17                # scale + amax + err_sum + nnz + mask per block
+THRESHOLD = 0.045
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(kernel: str, n_elem: int, n_part: int, fallback_frac: float) -> float:
+    """Bytes the method must move for one launch of `kernel` over an operand of n_elem elements."""
+    if kernel in ("sub1x128", "block128"):
+        return 2.0 * n_elem + n_elem + 2.0 * fallback_frac * n_elem + META_BYTES * n_part
+    if kernel == "tensor_amax":
+        return 2.0 * n_elem
+    if kernel == "tensor_quant":
+        return 2.0 * n_elem + n_elem
+    if kernel == "fallback_copy":
+        return 4.0 * n_elem * fallback_frac
+    return 0.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--row-div", type=int, default=1, help="divide every operand's rows (debug only; 1 = full workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-div", type=int, default=4, help="oracle is timed on the first rows/N rows of every operand")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus must be 1.")
+        return 2
+
+    import torch
+    from paper_2512_22804_amd import binding as B
+    from paper_2512_22804_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the HIP path has no CPU fallback.")
+        return 3
+    B.load()
+    dev = torch.device("cuda:0")
+
+    t0 = time.time()
+    sweep = W.cfg5(row_div=args.row_div)
+    log(f"[bench] generated {len(sweep)} operands in {time.time() - t0:.1f}s")
+
+    ops = []
+    for name, xb, gran in sweep:
+        rows, cols = xb.shape
+        params = B.make_params(rows, cols, gran, "partition", "mean_rel_err", THRESHOLD)
+        x = torch.from_numpy(xb.view(np.int16)).to(dev)
+        out = B.alloc_outputs(params, dev, want_bf16=True)
+        stats = torch.zeros(128, dtype=torch.uint8, device=dev)
+        ops.append({"name": name, "gran": gran, "params": params, "x": x, "out": out, "stats": stats, "n": rows * cols,
+                    "P": B.mor_num_partitions(gran, rows, cols), "host": xb})
+    n_total = sum(o["n"] for o in ops)
+    torch.cuda.synchronize()
+
+    def step(profiles=None):
+        for i, o in enumerate(ops):
+            if profiles is None:
+                B.mor_analyze_quantize(o["params"], o["x"], o["out"])
+            else:
+                B.mor_analyze_quantize_profiled(o["params"], o["x"], o["out"], profiles[i])
+            B.mor_select_stats(o["params"], o["out"].err_sum, o["out"].nnz, o["out"].mask, 1e-5, o["stats"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed / args.steps * 1e3
+    value = 2.0 * n_total / (elapsed / args.steps) / 1e9
+    log(f"[bench] {args.steps} steps, {ms_per_step:.3f} ms/step, {value:.1f} GB/s of BF16 input")
+
+    # selection result (after the timed region)
+    stats = [B.read_stats(o["stats"]) for o in ops]
+    fp8_elems = sum(s["n_elem_fp8"] for s in stats)
+    fp8_parts = sum(s["n_fp8_part"] for s in stats)
+    tot_parts = sum(s["n_part"] for s in stats)
+    fp8_tensors = sum(1 for s in stats if s["n_bf16_part"] == 0)
+    near = sum(s["n_near_threshold"] for s in stats)
+    for o, s in zip(ops, stats):
+        o["fallback_frac"] = s["n_elem_bf16"] / float(s["n_elem_fp8"] + s["n_elem_bf16"])
+        log(f"[bench]   {o['name']:8s} {o['gran']:9s} {o['params'].rows}x{o['params'].cols} mean_err={s['mean_err']:.5f} "
+            f"bf16_blocks={s['n_bf16_part']}/{s['n_part']}")
+
+    # per-kernel timing: the same steps again with the library recording HIP events around each kernel
+    ev = B.HipEvents()
+    profiles = [ev.new_profile(8) for _ in ops]
+    per_kernel = {}
+    for it in range(args.steps):
+        step(profiles)
+        torch.cuda.synchronize()
+        for o, pr in zip(ops, profiles):
+            for k in range(pr.count):
+                kname = B.KERNEL_NAMES[pr.kernel[k]]
+                ms = ev.elapsed_ms(pr.start[k], pr.stop[k])
+                rec = per_kernel.setdefault(kname, {"ms": 0.0, "launches": 0, "bytes": 0.0})
+                rec["ms"] += ms
+                rec["launches"] += 1
+                rec["bytes"] += algorithmic_bytes(kname, o["n"], o["P"], o["fallback_frac"])
+    ev.destroy()
+    for k, r in sorted(per_kernel.items(), key=lambda kv: -kv[1]["ms"]):
+        gbs = r["bytes"] / (r["ms"] * 1e-3) / 1e9 if r["ms"] > 0 else 0.0
+        log(f"[bench]   kernel {k:16s} launches={r['launches']:4d} avg={r['ms'] / r['launches'] * 1e3:9.1f} us "
+            f"alg_bytes/launch={r['bytes'] / r['launches'] / 1e6:9.2f} MB  -> {gbs:7.1f} GB/s")
+    dom_name, dom = max(per_kernel.items(), key=lambda kv: kv[1]["ms"])
+    achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath) and args.row_div == 1:
+        try:
+            traffic = json.load(open(tpath)).get(dom_name, {}).get("bytes_per_launch")
+        except Exception:
+            traffic = None
+    roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "avg_launch_us": round(dom["ms"] / dom["launches"] * 1e3, 2),
+                "algorithmic_bytes_per_launch": round(dom["bytes"] / dom["launches"], 1),
+                "per_kernel": {k: {"avg_us": round(r["ms"] / r["launches"] * 1e3, 2),
+                                   "gbs": round(r["bytes"] / (r["ms"] * 1e-3) / 1e9, 1) if r["ms"] > 0 else 0.0,
+                                   "share_of_gpu_time": round(r["ms"] / sum(x["ms"] for x in per_kernel.values()), 4)}
+                               for k, r in per_kernel.items()}}
+
+    # whole-step algorithmic bytes -> achieved HBM GB/s of the step
+    step_bytes = 0.0
+    for o in ops:
+        if o["gran"] == "tensor":
+            step_bytes += sum(algorithmic_bytes(k, o["n"], 1, o["fallback_frac"]) for k in ("tensor_amax", "tensor_quant", "fallback_copy"))
+        else:
+            step_bytes += algorithmic_bytes(o["gran"], o["n"], o["P"], o["fallback_frac"])
+    step_gbs = step_bytes / (elapsed / args.steps) / 1e9
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import mor_oracle as O      # the oracle is test infrastructure: timed here as a reported baseline only
+        O.build()
+        div = max(1, args.cpu_sample_div)
+        n_cpu = 0
+        t_cpu = 0.0
+        for o in ops:
+            rows = max(128, (o["host"].shape[0] // div) // 128 * 128)
+            xs = np.ascontiguousarray(o["host"][:rows])
+            tt = time.perf_counter()
+            O.analyze_quantize(xs, o["gran"], "partition", "mean_rel_err", THRESHOLD)
+            t_cpu += time.perf_counter() - tt
+            n_cpu += xs.size
+        cpu_baseline = {"value": round(2.0 * n_cpu / t_cpu / 1e9, 4), "unit": "GB/s", "cores": O.threads(), "kind": "oracle",
+                        "sample": f"first 1/{div} of the rows of each of the 12 operands ({n_cpu} elements, {t_cpu:.1f} s)"}
+        log(f"[bench] cpu oracle: {cpu_baseline}")
+
+    result = {
+        "metric": "GB/s of BF16 input analysed+quantized (fraction of HBM peak); FP8-selected %",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "cfg5: operand sweep of one Llama-style 8B layer (X 8192x4096 1x128; W_qkv 6144x4096, W_o 4096x4096, "
+                               "W_gate/W_up 14336x4096, W_down 4096x14336 128x128; six same-shape gradients per-tensor); "
+                               "Eq.2 th=4.5%; analyze_quantize + select_stats per operand, one stream",
+                   "elements_per_step": n_total, "row_div": args.row_div, "criterion": "mean_rel_err", "threshold": THRESHOLD},
+        "hbm_algorithmic_gbs": round(step_gbs, 1), "hbm_frac_of_peak": round(step_gbs / HBM_PEAK_GBS, 4),
+        "fp8_selected_pct": {"by_elements": round(100.0 * fp8_elems / n_total, 3), "by_blocks": round(100.0 * fp8_parts / tot_parts, 3),
+                             "by_tensors": round(100.0 * fp8_tensors / len(ops), 3), "near_threshold_blocks": near},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -144,10 +144,33 @@ mor_status mor_analyze_quantize(const mor_params* params, const uint16_t* x, con
                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Measurement aid: the same call, with the caller's HIP events recorded on `stream` right before
+ * and after each kernel it launches, so a benchmark can time individual kernels inside its own
+ * timed loop.  `profile` is a HOST struct: the caller fills `capacity` (<= 8) and that many
+ * created hipEvent_t handles in start[] / stop[]; on return `count` kernels were bracketed and
+ * kernel[i] names the i-th one (mor_kernel_id).  Kernels beyond `capacity` run un-bracketed.
+ */
+typedef enum {
+    MOR_KERNEL_SUB_1x128 = 1, MOR_KERNEL_BLOCK_128x128 = 2, MOR_KERNEL_TENSOR_AMAX = 3,
+    MOR_KERNEL_TENSOR_QUANT = 4, MOR_KERNEL_TENSOR_FINALIZE = 5, MOR_KERNEL_FALLBACK_COPY = 6,
+    MOR_KERNEL_SCOPE_REDUCE = 7, MOR_KERNEL_SCOPE_DECIDE = 8, MOR_KERNEL_SCOPE_FILL_MASK = 9
+} mor_kernel_id;
+typedef struct mor_profile {
+    int32_t capacity;
+    int32_t count;
+    void*   start[8];   /* hipEvent_t */
+    void*   stop[8];    /* hipEvent_t */
+    int32_t kernel[8];  /* mor_kernel_id */
+} mor_profile;
+mor_status mor_analyze_quantize_profiled(const mor_params* params, const uint16_t* x, const mor_outputs* out,
+                                         void* workspace, size_t workspace_bytes, void* stream,
+                                         mor_profile* profile);
+
+/*
  * Inverse path (the de-quantize / de-scale half of the fake-quantization workflow, Section 4,
  * Figure 4): y = bf16_rne(fl32(E4M3value(fp8) * fl32(1 / scale[p]))) in blocks with mask 0,
- * y = bf16 fallback bits in blocks with mask 1.  `bf16` may be NULL only if no block has
- * mask 1 is the caller's promise (masked blocks are then left untouched in y).
+ * y = bf16 fallback bits in blocks with mask 1.  `bf16` may be NULL; blocks with mask 1 are then
+ * left untouched in y.
  * Uses rows, cols and granularity of params; params->ld is ignored.
  */
 mor_status mor_dequantize(const mor_params* params, const uint8_t* fp8, int64_t ld_fp8,

@@ -25,8 +25,11 @@ GRAN = {"tensor": MOR_GRAN_TENSOR, "sub1x128": MOR_GRAN_SUB_1x128, "block128": M
 CRIT = {"mean_rel_err": MOR_CRIT_MEAN_REL_ERR, "e4m3_vs_e5m2": MOR_CRIT_E4M3_VS_E5M2}
 SCOPE = {"partition": MOR_SCOPE_PARTITION, "tensor": MOR_SCOPE_TENSOR}
 
-EXPORTS = ("mor_num_partitions", "mor_workspace_bytes", "mor_analyze_quantize", "mor_dequantize",
-           "mor_select_stats", "mor_status_string")
+EXPORTS = ("mor_num_partitions", "mor_workspace_bytes", "mor_analyze_quantize", "mor_analyze_quantize_profiled",
+           "mor_dequantize", "mor_select_stats", "mor_status_string")
+
+KERNEL_NAMES = {1: "sub1x128", 2: "block128", 3: "tensor_amax", 4: "tensor_quant", 5: "tensor_finalize",
+                6: "fallback_copy", 7: "scope_reduce", 8: "scope_decide", 9: "scope_fill_mask"}
 
 
 class MorParams(C.Structure):
@@ -46,6 +49,11 @@ class MorStats(C.Structure):
                 ("n_elem_fp8", C.c_uint64), ("n_elem_bf16", C.c_uint64), ("nnz_total", C.c_uint64),
                 ("n_near_threshold", C.c_uint64), ("err_sum_total", C.c_double), ("mean_err", C.c_double),
                 ("hist", C.c_uint32 * 12), ("reserved", C.c_uint32)]
+
+
+class MorProfile(C.Structure):
+    _fields_ = [("capacity", C.c_int32), ("count", C.c_int32), ("start", C.c_void_p * 8), ("stop", C.c_void_p * 8),
+                ("kernel", C.c_int32 * 8)]
 
 
 class MorError(RuntimeError):
@@ -72,6 +80,9 @@ def load():
         L.mor_analyze_quantize.argtypes = [C.POINTER(MorParams), C.c_void_p, C.POINTER(MorOutputs), C.c_void_p,
                                            C.c_size_t, C.c_void_p]
         L.mor_analyze_quantize.restype = C.c_int
+        L.mor_analyze_quantize_profiled.argtypes = [C.POINTER(MorParams), C.c_void_p, C.POINTER(MorOutputs), C.c_void_p,
+                                                    C.c_size_t, C.c_void_p, C.POINTER(MorProfile)]
+        L.mor_analyze_quantize_profiled.restype = C.c_int
         L.mor_dequantize.argtypes = [C.POINTER(MorParams), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_int64, C.c_void_p, C.c_int64, C.c_void_p]
         L.mor_dequantize.restype = C.c_int
@@ -144,18 +155,83 @@ def alloc_outputs(params: MorParams, device, want_bf16: bool = True, bf16_fill: 
                      torch.empty(P, dtype=torch.uint8, device=device), err5, ws, params)
 
 
+def _outputs_struct(out: MorResult) -> MorOutputs:
+    return MorOutputs(_ptr(out.fp8), out.fp8.stride(0), _ptr(out.bf16), out.bf16.stride(0) if out.bf16 is not None else 0,
+                      _ptr(out.scale), _ptr(out.amax), _ptr(out.err_sum), _ptr(out.nnz), _ptr(out.mask), _ptr(out.err5_sum))
+
+
 def mor_analyze_quantize(params: MorParams, x: torch.Tensor, out: MorResult) -> None:
     """Enqueue the analyse-select-quantize pass of ``x`` (int16/bfloat16 device tensor holding BF16 bits,
     row stride ``params.ld``) on the current stream, writing into ``out``."""
     if not x.is_cuda:
         raise ValueError("x must live in device memory")
-    o = MorOutputs(_ptr(out.fp8), out.fp8.stride(0), _ptr(out.bf16), out.bf16.stride(0) if out.bf16 is not None else 0,
-                   _ptr(out.scale), _ptr(out.amax), _ptr(out.err_sum), _ptr(out.nnz), _ptr(out.mask), _ptr(out.err5_sum))
+    o = _outputs_struct(out)
     ws = out.workspace
     rc = load().mor_analyze_quantize(C.byref(params), _ptr(x), C.byref(o), _ptr(ws), ws.numel() if ws is not None else 0,
                                      _stream())
     if rc != 0:
         raise MorError(rc, "mor_analyze_quantize")
+
+
+def mor_analyze_quantize_profiled(params: MorParams, x: torch.Tensor, out: MorResult, profile: MorProfile) -> None:
+    """Same call with the caller's HIP events recorded around each kernel (see :class:`HipEvents`)."""
+    if not x.is_cuda:
+        raise ValueError("x must live in device memory")
+    o = _outputs_struct(out)
+    ws = out.workspace
+    rc = load().mor_analyze_quantize_profiled(C.byref(params), _ptr(x), C.byref(o), _ptr(ws),
+                                              ws.numel() if ws is not None else 0, _stream(), C.byref(profile))
+    if rc != 0:
+        raise MorError(rc, "mor_analyze_quantize_profiled")
+
+
+class HipEvents:
+    """Raw hipEvent_t handles (timing enabled) created through the HIP runtime that PyTorch already loaded; they can
+    be recorded by the library on the stream its kernels run on."""
+
+    def __init__(self):
+        self.rt = C.CDLL("libamdhip64.so")
+        self.rt.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.rt.hipEventDestroy.argtypes = [C.c_void_p]
+        self.rt.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.rt.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.rt.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        self.events = []
+
+    def create(self) -> C.c_void_p:
+        ev = C.c_void_p()
+        rc = self.rt.hipEventCreate(C.byref(ev))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate failed ({rc})")
+        self.events.append(ev)
+        return ev
+
+    def record(self, ev, stream=None) -> None:
+        rc = self.rt.hipEventRecord(ev, _stream() if stream is None else stream)
+        if rc != 0:
+            raise RuntimeError(f"hipEventRecord failed ({rc})")
+
+    def new_profile(self, capacity: int = 8) -> MorProfile:
+        pr = MorProfile()
+        pr.capacity = capacity
+        for i in range(capacity):
+            pr.start[i] = self.create().value
+            pr.stop[i] = self.create().value
+        return pr
+
+    def elapsed_ms(self, a, b) -> float:
+        ms = C.c_float()
+        self.rt.hipEventSynchronize(C.c_void_p(b) if isinstance(b, int) else b)
+        rc = self.rt.hipEventElapsedTime(C.byref(ms), C.c_void_p(a) if isinstance(a, int) else a,
+                                         C.c_void_p(b) if isinstance(b, int) else b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed ({rc})")
+        return float(ms.value)
+
+    def destroy(self) -> None:
+        for ev in self.events:
+            self.rt.hipEventDestroy(ev)
+        self.events = []
 
 
 def mor_dequantize(params: MorParams, fp8: torch.Tensor, scale: torch.Tensor, mask: torch.Tensor,

@@ -44,8 +44,8 @@ size_t mor_workspace_bytes(const mor_params* p) {
     return 0;
 }
 
-mor_status mor_analyze_quantize(const mor_params* p, const uint16_t* x, const mor_outputs* out, void* workspace,
-                                size_t workspace_bytes, void* stream) {
+static mor_status analyze_quantize_impl(const mor_params* p, const uint16_t* x, const mor_outputs* out, void* workspace,
+                                        size_t workspace_bytes, void* stream, mor::KProf* prof) {
     if (!p || !x || !out) return MOR_ERR_NULL;
     mor_status st = check_common(p);
     if (st != MOR_OK) return st;
@@ -74,19 +74,34 @@ mor_status mor_analyze_quantize(const mor_params* p, const uint16_t* x, const mo
     hipError_t e;
     switch (p->granularity) {
     case MOR_GRAN_TENSOR:
-        e = mor::launch_tensor(x, sh, ko, p->criterion, p->threshold, workspace, hs);
+        e = mor::launch_tensor(x, sh, ko, p->criterion, p->threshold, workspace, hs, prof);
         break;
     case MOR_GRAN_SUB_1x128:
-        e = mor::launch_sub1x128(x, sh, ko, p->criterion, defer, p->threshold, hs);
+        e = mor::launch_sub1x128(x, sh, ko, p->criterion, defer, p->threshold, hs, prof);
         break;
     default:
-        e = mor::launch_block128(x, sh, ko, p->criterion, defer, p->threshold, hs);
+        e = mor::launch_block128(x, sh, ko, p->criterion, defer, p->threshold, hs, prof);
         break;
     }
     if (e == hipSuccess && defer && p->granularity != MOR_GRAN_TENSOR)
         e = mor::launch_scope_finalize(x, sh, ko, mor_num_partitions(p->granularity, p->rows, p->cols), p->criterion,
-                                       p->threshold, workspace, hs);
+                                       p->threshold, workspace, hs, prof);
     return e == hipSuccess ? MOR_OK : MOR_ERR_HIP;
+}
+
+mor_status mor_analyze_quantize(const mor_params* p, const uint16_t* x, const mor_outputs* out, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+    return analyze_quantize_impl(p, x, out, workspace, workspace_bytes, stream, nullptr);
+}
+
+mor_status mor_analyze_quantize_profiled(const mor_params* p, const uint16_t* x, const mor_outputs* out, void* workspace,
+                                         size_t workspace_bytes, void* stream, mor_profile* profile) {
+    static_assert(sizeof(mor_profile) == sizeof(mor::KProf), "mor_profile layout");
+    if (!profile) return MOR_ERR_NULL;
+    profile->count = 0;
+    for (int i = 0; i < profile->capacity && i < 8; ++i)
+        if (!profile->start[i] || !profile->stop[i]) return MOR_ERR_NULL;
+    return analyze_quantize_impl(p, x, out, workspace, workspace_bytes, stream, reinterpret_cast<mor::KProf*>(profile));
 }
 
 mor_status mor_dequantize(const mor_params* p, const uint8_t* fp8, int64_t ld_fp8, const float* scale, const uint8_t* mask,

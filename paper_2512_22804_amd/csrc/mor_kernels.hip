@@ -509,6 +509,19 @@ __global__ __launch_bounds__(256) void k_stats(int64_t n_part, unsigned long lon
 // ======================================================================================
 static inline size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
 
+// Records the caller's events around one kernel launch when profiling is requested.
+struct ProfScope {
+    KProf* prof; hipStream_t st; int slot;
+    ProfScope(KProf* p, int kernel_id, hipStream_t s) : prof(p), st(s), slot(-1) {
+        if (prof && prof->count < prof->capacity && prof->count < 8) {
+            slot = prof->count++;
+            prof->kernel[slot] = kernel_id;
+            (void)hipEventRecord(prof->start[slot], st);
+        }
+    }
+    ~ProfScope() { if (slot >= 0) (void)hipEventRecord(prof->stop[slot], st); }
+};
+
 static int64_t tensor_quant_blocks(int64_t rows, int64_t cols) {
     const int64_t flat = (rows * cols / 8 + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
     const int64_t strided = ((cols + 127) / 128) * ((rows + 15) / 16);
@@ -543,8 +556,9 @@ static int clamp_grid_y(int64_t v) { return (int)(v < 1 ? 1 : (v > 65535 ? 65535
         else                  { if (defer) KERNEL<kCritEq2, true> __VA_ARGS__; else KERNEL<kCritEq2, false> __VA_ARGS__; } \
     } while (0)
 
-hipError_t launch_sub1x128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st) {
+hipError_t launch_sub1x128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st, KProf* prof) {
     const int64_t n_part = sh.rows * (sh.cols / 128);
+    ProfScope ps(prof, kKernSub1x128, st);
     if (is_flat(sh, o)) {
         const int64_t blocks = (n_part + 63) / 64;
         if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
@@ -556,15 +570,16 @@ hipError_t launch_sub1x128(const uint16_t* x, const KShape& sh, const KOut& o, i
     return hipGetLastError();
 }
 
-hipError_t launch_block128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st) {
+hipError_t launch_block128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st, KProf* prof) {
     const int64_t tr = sh.rows / 128, tc = sh.cols / 128;
     if (tr > 65535) return hipErrorInvalidValue;   // rows beyond 8.3 M are not supported by this launch shape
     const dim3 grid((unsigned)tc, (unsigned)tr);
+    ProfScope ps(prof, kKernBlock128, st);
     MOR_DISPATCH_CRIT_DEFER(k_block128, <<<grid, dim3(256), 0, st>>>(x, sh, o, th));
     return hipGetLastError();
 }
 
-hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int crit, float th, void* ws, hipStream_t st) {
+hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int crit, float th, void* ws, hipStream_t st, KProf* prof) {
     const TensorPlan pl = plan_tensor(sh.rows, sh.cols);
     char* w = static_cast<char*>(ws);
     uint32_t* amax_part = reinterpret_cast<uint32_t*>(w + pl.off_amax_part);
@@ -578,24 +593,30 @@ hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int
     if (flat) {
         int64_t want = (n_chunks + 256 * 8 - 1) / (256 * 8);
         n_amax = (int)(want < 1 ? 1 : (want > kMaxAmaxBlocks ? kMaxAmaxBlocks : want));
-        k_tensor_amax_flat<<<dim3(n_amax), dim3(256), 0, st>>>(x, n_chunks, amax_part);
+        { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_flat<<<dim3(n_amax), dim3(256), 0, st>>>(x, n_chunks, amax_part); }
         n_quant = (n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
         if (n_quant > 0x7FFFFFFF) return hipErrorInvalidValue;
+        ProfScope ps(prof, kKernTensorQuant, st);
         if (crit == kCritEq3) k_tensor_quant_flat<kCritEq3><<<dim3((unsigned)n_quant), dim3(256), 0, st>>>(x, n_chunks, o, amax_part, n_amax, tp);
         else k_tensor_quant_flat<kCritEq2><<<dim3((unsigned)n_quant), dim3(256), 0, st>>>(x, n_chunks, o, amax_part, n_amax, tp);
     } else {
         n_amax = (int)(sh.rows < kMaxAmaxBlocks ? sh.rows : kMaxAmaxBlocks);
-        k_tensor_amax_strided<<<dim3(n_amax), dim3(256), 0, st>>>(x, sh, amax_part);
+        { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_strided<<<dim3(n_amax), dim3(256), 0, st>>>(x, sh, amax_part); }
         const int64_t gx = (sh.cols + 127) / 128, gy = (sh.rows + 15) / 16;
         if (gy > 65535) return hipErrorInvalidValue;
         n_quant = gx * gy;
         const dim3 grid((unsigned)gx, (unsigned)gy);
+        ProfScope ps(prof, kKernTensorQuant, st);
         if (crit == kCritEq3) k_tensor_quant_strided<kCritEq3><<<grid, dim3(256), 0, st>>>(x, sh, o, amax_part, n_amax, tp);
         else k_tensor_quant_strided<kCritEq2><<<grid, dim3(256), 0, st>>>(x, sh, o, amax_part, n_amax, tp);
     }
-    if (crit == kCritEq3) k_tensor_finalize<kCritEq3><<<dim3(1), dim3(256), 0, st>>>(tp, n_quant, amax_part, n_amax, o, th, decision);
-    else k_tensor_finalize<kCritEq2><<<dim3(1), dim3(256), 0, st>>>(tp, n_quant, amax_part, n_amax, o, th, decision);
+    {
+        ProfScope ps(prof, kKernTensorFinalize, st);
+        if (crit == kCritEq3) k_tensor_finalize<kCritEq3><<<dim3(1), dim3(256), 0, st>>>(tp, n_quant, amax_part, n_amax, o, th, decision);
+        else k_tensor_finalize<kCritEq2><<<dim3(1), dim3(256), 0, st>>>(tp, n_quant, amax_part, n_amax, o, th, decision);
+    }
     if (o.bf16) {
+        ProfScope ps(prof, kKernFallbackCopy, st);
         if (flat) k_fallback_copy_flat<<<dim3(2048), dim3(256), 0, st>>>(x, o.bf16, n_chunks, decision);
         else k_fallback_copy_strided<<<dim3((unsigned)(sh.rows < 4096 ? sh.rows : 4096)), dim3(256), 0, st>>>(x, sh, o.bf16, o.ld_bf16, decision);
     }
@@ -603,22 +624,29 @@ hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int
 }
 
 hipError_t launch_scope_finalize(const uint16_t* x, const KShape& sh, const KOut& o, int64_t n_part, int crit, float th,
-                                 void* ws, hipStream_t st) {
+                                 void* ws, hipStream_t st, KProf* prof) {
     char* w = static_cast<char*>(ws);
     ScopePartials sp{reinterpret_cast<double*>(w), reinterpret_cast<double*>(w) + kScopeBlocks,
                      reinterpret_cast<unsigned long long*>(w) + 2 * kScopeBlocks};
     uint32_t* decision = reinterpret_cast<uint32_t*>(w + 3 * sizeof(double) * kScopeBlocks);
     int64_t want = (n_part + 1023) / 1024;
     const int nb = (int)(want < 1 ? 1 : (want > kScopeBlocks ? kScopeBlocks : want));
-    if (crit == kCritEq3) {
-        k_scope_reduce<kCritEq3><<<dim3(nb), dim3(256), 0, st>>>(o, n_part, sp);
-        k_scope_decide<kCritEq3><<<dim3(1), dim3(256), 0, st>>>(sp, nb, th, decision);
-    } else {
-        k_scope_reduce<kCritEq2><<<dim3(nb), dim3(256), 0, st>>>(o, n_part, sp);
-        k_scope_decide<kCritEq2><<<dim3(1), dim3(256), 0, st>>>(sp, nb, th, decision);
+    {
+        ProfScope ps(prof, kKernScopeReduce, st);
+        if (crit == kCritEq3) k_scope_reduce<kCritEq3><<<dim3(nb), dim3(256), 0, st>>>(o, n_part, sp);
+        else k_scope_reduce<kCritEq2><<<dim3(nb), dim3(256), 0, st>>>(o, n_part, sp);
     }
-    k_scope_fill_mask<<<dim3(nb), dim3(256), 0, st>>>(o.mask, n_part, decision);
+    {
+        ProfScope ps(prof, kKernScopeDecide, st);
+        if (crit == kCritEq3) k_scope_decide<kCritEq3><<<dim3(1), dim3(256), 0, st>>>(sp, nb, th, decision);
+        else k_scope_decide<kCritEq2><<<dim3(1), dim3(256), 0, st>>>(sp, nb, th, decision);
+    }
+    {
+        ProfScope ps(prof, kKernScopeFillMask, st);
+        k_scope_fill_mask<<<dim3(nb), dim3(256), 0, st>>>(o.mask, n_part, decision);
+    }
     if (o.bf16) {
+        ProfScope ps(prof, kKernFallbackCopy, st);
         const bool flat = sh.ld == sh.cols && o.ld_bf16 == sh.cols;
         if (flat) k_fallback_copy_flat<<<dim3(2048), dim3(256), 0, st>>>(x, o.bf16, sh.rows * sh.cols / 8, decision);
         else k_fallback_copy_strided<<<dim3((unsigned)(sh.rows < 4096 ? sh.rows : 4096)), dim3(256), 0, st>>>(x, sh, o.bf16, o.ld_bf16, decision);

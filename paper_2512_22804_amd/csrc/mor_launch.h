@@ -36,12 +36,25 @@ struct TensorPlan {
 TensorPlan plan_tensor(int64_t rows, int64_t cols);
 size_t scope_workspace_bytes(int64_t n_part);
 
-hipError_t launch_sub1x128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st);
-hipError_t launch_block128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st);
-hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int crit, float th, void* ws, hipStream_t st);
+// Optional per-kernel timing: when non-null, start[i]/stop[i] are recorded around the i-th kernel.
+struct KProf {
+    int32_t capacity;
+    int32_t count;
+    hipEvent_t start[8];
+    hipEvent_t stop[8];
+    int32_t kernel[8];
+};
+enum KernelId {
+    kKernSub1x128 = 1, kKernBlock128 = 2, kKernTensorAmax = 3, kKernTensorQuant = 4, kKernTensorFinalize = 5,
+    kKernFallbackCopy = 6, kKernScopeReduce = 7, kKernScopeDecide = 8, kKernScopeFillMask = 9
+};
+
+hipError_t launch_sub1x128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st, KProf* prof);
+hipError_t launch_block128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st, KProf* prof);
+hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int crit, float th, void* ws, hipStream_t st, KProf* prof);
 // Tensor-scope decision over per-block sums already written by a deferred sub-tensor pass.
 hipError_t launch_scope_finalize(const uint16_t* x, const KShape& sh, const KOut& o, int64_t n_part, int crit, float th,
-                                 void* ws, hipStream_t st);
+                                 void* ws, hipStream_t st, KProf* prof);
 hipError_t launch_dequantize(int gran, int64_t rows, int64_t cols, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
                              const uint8_t* mask, const uint16_t* bf16, int64_t ld_bf16, uint16_t* y, int64_t ld_y,
                              hipStream_t st);
