@@ -53,7 +53,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--row-div", type=int, default=1, help="divide every operand's rows (debug only; 1 = full workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-div", type=int, default=4, help="oracle is timed on the first rows/N rows of every operand")
+    ap.add_argument("--cpu-sample-div", type=int, default=1, help="oracle is timed on the first rows/N rows of every operand")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus must be 1.")

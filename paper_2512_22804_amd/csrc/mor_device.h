@@ -45,14 +45,21 @@ __device__ __forceinline__ float scale_from_amax_bits(uint32_t abits, float q_am
 // ---- per-lane summary of 8 BF16 values held in a u32x4: packed amax and non-zero count
 struct Scan8 {
     uint32_t amax2;   // two u16 running maxima of (bits & 0x7FFF)
-    uint32_t nz2;     // two u16 running counts of non-zero elements
+    uint32_t zero2;   // two u16 running counts of ZERO elements (+-0)
 };
+// 1 for a zero half-word, 0 otherwise: saturating 1 - m on both halves (v_pk_sub_u16 clamp).
+__device__ __forceinline__ uint32_t pk_is_zero_u16(uint32_t m) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_sub_sat(__builtin_bit_cast(u16x2, 0x00010001u), __builtin_bit_cast(u16x2, m)));
+}
+__device__ __forceinline__ uint32_t pk_add_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, (u16x2)(__builtin_bit_cast(u16x2, a) + __builtin_bit_cast(u16x2, b)));
+}
 __device__ __forceinline__ void scan8(const u32x4& raw, Scan8& sc) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         uint32_t m = raw[j] & 0x7FFF7FFFu;
         sc.amax2 = pk_max_u16(sc.amax2, m);
-        sc.nz2 += pk_min_u16(m, 0x00010001u);
+        sc.zero2 = pk_add_u16(sc.zero2, pk_is_zero_u16(m));
     }
 }
 __device__ __forceinline__ uint32_t fold_max16(uint32_t v2) { return max(v2 & 0xFFFFu, v2 >> 16); }
@@ -116,28 +123,32 @@ __device__ __forceinline__ float term_careful(uint32_t xbits16, float y, uint32_
     if (q == 0.0f) return 1.0f;
     return __builtin_fabsf(y - q) / __builtin_fabsf(y);
 }
+// Careful path over 8 consecutive elements re-read from memory (the data is still in L2): a rolled
+// loop keeps this rarely taken path small.  Writes the 8 codes to `dst` unless it is null.
 template <bool E5M2>
-__device__ __forceinline__ u32x2 quant8_careful(const u32x4& raw, float s, float& err0, float& err1) {
-    u32x2 r; r.x = 0u; r.y = 0u;
-#pragma unroll
+__device__ __forceinline__ float quant8_careful_mem(const uint16_t* __restrict__ src, float s, uint8_t* dst) {
+    const uint32_t* src32 = reinterpret_cast<const uint32_t*>(src);
+    uint32_t* dst32 = reinterpret_cast<uint32_t*>(dst);
+    float err = 0.0f;
+    uint32_t codes = 0u;
+#pragma clang loop unroll(disable)
     for (int j = 0; j < 4; ++j) {
-        uint32_t b0 = raw[j] & 0xFFFFu, b1 = raw[j] >> 16;
-        float y0 = __uint_as_float(b0 << 16) * s;
-        float y1 = __uint_as_float(b1 << 16) * s;
-        uint32_t c0 = encode_careful<E5M2>(y0), c1 = encode_careful<E5M2>(y1);
-        err0 += term_careful<E5M2>(b0, y0, c0);
-        err1 += term_careful<E5M2>(b1, y1, c1);
-        uint32_t two = c0 | (c1 << 8);
-        if (j < 2) r.x |= two << (16 * j); else r.y |= two << (16 * (j - 2));
+        const uint32_t w = src32[j];
+        const uint32_t b0 = w & 0xFFFFu, b1 = w >> 16;
+        const float y0 = __uint_as_float(b0 << 16) * s;
+        const float y1 = __uint_as_float(b1 << 16) * s;
+        const uint32_t c0 = encode_careful<E5M2>(y0), c1 = encode_careful<E5M2>(y1);
+        err += term_careful<E5M2>(b0, y0, c0);
+        err += term_careful<E5M2>(b1, y1, c1);
+        const uint32_t two = c0 | (c1 << 8);
+        if (j & 1) {
+            codes |= two << 16;
+            if (dst) dst32[j >> 1] = codes;
+        } else {
+            codes = two;
+        }
     }
-    return r;
-}
-
-// Quantize 8 values choosing the path from the block's amax bits (uniform per block).
-template <bool E5M2>
-__device__ __forceinline__ u32x2 quant8(const u32x4& raw, uint32_t abits, float s, float& err0, float& err1) {
-    if (abits < kFastAmaxBits) return quant8_fast<E5M2>(raw, s, err0, err1);
-    return quant8_careful<E5M2>(raw, s, err0, err1);
+    return err;
 }
 
 // ---- cross-lane reductions over the 16 lanes of a DPP row -----------------------------------

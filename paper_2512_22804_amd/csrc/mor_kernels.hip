@@ -18,26 +18,32 @@ enum { kCritEq2 = 0, kCritEq3 = 1 };
 // per load instruction and keeps 4 loads in flight, so every reduction stays inside a row.
 // ======================================================================================
 template <int CRIT, bool DEFER>
-__device__ __forceinline__ void sub_block_body(const u32x4& raw, int l, int64_t p, const KOut& o, int64_t off_fp8,
-                                               int64_t off_bf16, float th) {
+__device__ __forceinline__ void sub_block_body(const u32x4& raw, const uint16_t* __restrict__ src, int l, int64_t p,
+                                               const KOut& o, uint8_t* __restrict__ dst_fp8, uint16_t* __restrict__ dst_bf16,
+                                               float th) {
     Scan8 sc{0u, 0u};
     scan8(raw, sc);
     const uint32_t abits = row_allmax_u32(fold_max16(sc.amax2));
     const float s = scale_from_amax_bits(abits, kE4M3Max);
-    float e0 = 0.0f, e1 = 0.0f;
-    const u32x2 codes = quant8<false>(raw, abits, s, e0, e1);
-    store8(o.fp8 + off_fp8 + l * 8, codes);
-    float err = row_allsum_f32(e0 + e1);
-    const uint32_t nnz = row_allsum_u32(fold_add16(sc.nz2));
-    if (abits >= kInfBits) err = __builtin_inff();
-    float err5 = 0.0f;
-    if constexpr (CRIT == kCritEq3) {
-        const float s5 = scale_from_amax_bits(abits, kE5M2Max);
-        float f0 = 0.0f, f1 = 0.0f;
-        (void)quant8<true>(raw, abits, s5, f0, f1);
-        err5 = row_allsum_f32(f0 + f1);
-        if (abits >= kInfBits) err5 = __builtin_inff();
+    float e, e5 = 0.0f;
+    if (abits < kFastAmaxBits) {
+        float e0 = 0.0f, e1 = 0.0f;
+        store8(dst_fp8, quant8_fast<false>(raw, s, e0, e1));
+        e = e0 + e1;
+        if constexpr (CRIT == kCritEq3) {
+            float f0 = 0.0f, f1 = 0.0f;
+            (void)quant8_fast<true>(raw, scale_from_amax_bits(abits, kE5M2Max), f0, f1);
+            e5 = f0 + f1;
+        }
+    } else {
+        e = quant8_careful_mem<false>(src, s, dst_fp8);
+        if constexpr (CRIT == kCritEq3) e5 = quant8_careful_mem<true>(src, scale_from_amax_bits(abits, kE5M2Max), nullptr);
     }
+    float err = row_allsum_f32(e);
+    const uint32_t nnz = 128u - row_allsum_u32(fold_add16(sc.zero2));
+    float err5 = 0.0f;
+    if constexpr (CRIT == kCritEq3) err5 = row_allsum_f32(e5);
+    if (abits >= kInfBits) { err = __builtin_inff(); err5 = __builtin_inff(); }
     uint32_t mask = 0u;
     if constexpr (!DEFER) mask = (CRIT == kCritEq3) ? decide_eq3(err, err5) : decide_eq2(err, nnz, th);
     if (l == 0) {
@@ -49,7 +55,7 @@ __device__ __forceinline__ void sub_block_body(const u32x4& raw, int l, int64_t 
         if constexpr (!DEFER) o.mask[p] = (uint8_t)mask;
     }
     if constexpr (!DEFER) {
-        if (mask && o.bf16) store16(o.bf16 + off_bf16 + l * 8, raw);
+        if (mask && dst_bf16) store16(dst_bf16, raw);
     }
 }
 
@@ -68,7 +74,8 @@ __global__ __launch_bounds__(256) void k_sub1x128_flat(const uint16_t* __restric
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int64_t p = pbase + k;
-        if (p < n_part) sub_block_body<CRIT, DEFER>(raw[k], l, p, o, p * 128, p * 128, th);
+        const int64_t off = p * 128 + l * 8;
+        if (p < n_part) sub_block_body<CRIT, DEFER>(raw[k], x + off, l, p, o, o.fp8 + off, o.bf16 ? o.bf16 + off : nullptr, th);
     }
 }
 
@@ -78,8 +85,10 @@ __global__ __launch_bounds__(256) void k_sub1x128_strided(const uint16_t* __rest
     const int lane = threadIdx.x & 63, g = lane >> 4, l = lane & 15;
     const int64_t cb = blockIdx.x, cpr = sh.cols / 128;
     for (int64_t r = (int64_t)blockIdx.y * 16 + (threadIdx.x >> 6) * 4 + g; r < sh.rows; r += (int64_t)gridDim.y * 16) {
-        const u32x4 raw = load16(x + r * sh.ld + cb * 128 + l * 8);
-        sub_block_body<CRIT, DEFER>(raw, l, r * cpr + cb, o, r * o.ld_fp8 + cb * 128, r * o.ld_bf16 + cb * 128, th);
+        const uint16_t* src = x + r * sh.ld + cb * 128 + l * 8;
+        const u32x4 raw = load16(src);
+        sub_block_body<CRIT, DEFER>(raw, src, l, r * cpr + cb, o, o.fp8 + r * o.ld_fp8 + cb * 128 + l * 8,
+                                    o.bf16 ? o.bf16 + r * o.ld_bf16 + cb * 128 + l * 8 : nullptr, th);
     }
 }
 
@@ -92,14 +101,16 @@ __global__ __launch_bounds__(256) void k_block128(const uint16_t* __restrict__ x
     __shared__ uint32_t sh_amax[4];
     __shared__ float sh_err[4];
     __shared__ float sh_err5[4];
-    __shared__ uint32_t sh_nnz[4];
+    __shared__ uint32_t sh_zero[4];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, l = lane & 15;
     const int64_t tc = blockIdx.x, tr = blockIdx.y;
     const int64_t col = tc * 128 + l * 8;
     const int64_t row0 = tr * 128 + w * 4 + (lane >> 4);
+    const uint16_t* __restrict__ src = x + row0 * sh.ld + col;
+    uint8_t* __restrict__ dst = o.fp8 + row0 * o.ld_fp8 + col;
     u32x4 raw[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) raw[i] = load16(x + (row0 + i * 16) * sh.ld + col);
+    for (int i = 0; i < 8; ++i) raw[i] = load16(src + (int64_t)i * 16 * sh.ld);
     Scan8 sc{0u, 0u};
 #pragma unroll
     for (int i = 0; i < 8; ++i) scan8(raw[i], sc);
@@ -108,27 +119,37 @@ __global__ __launch_bounds__(256) void k_block128(const uint16_t* __restrict__ x
     __syncthreads();
     const uint32_t abits = max(max(sh_amax[0], sh_amax[1]), max(sh_amax[2], sh_amax[3]));
     const float s = scale_from_amax_bits(abits, kE4M3Max);
-    float e0 = 0.0f, e1 = 0.0f;
+    float e, e5 = 0.0f;
+    if (abits < kFastAmaxBits) {
+        float e0 = 0.0f, e1 = 0.0f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const u32x2 codes = quant8<false>(raw[i], abits, s, e0, e1);
-        store8(o.fp8 + (row0 + i * 16) * o.ld_fp8 + col, codes);
+        for (int i = 0; i < 8; ++i) store8(dst + (int64_t)i * 16 * o.ld_fp8, quant8_fast<false>(raw[i], s, e0, e1));
+        e = e0 + e1;
+        if constexpr (CRIT == kCritEq3) {
+            const float s5 = scale_from_amax_bits(abits, kE5M2Max);
+            float f0 = 0.0f, f1 = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) (void)quant8_fast<true>(raw[i], s5, f0, f1);
+            e5 = f0 + f1;
+        }
+    } else {
+        e = 0.0f;
+#pragma clang loop unroll(disable)
+        for (int i = 0; i < 8; ++i) {
+            e += quant8_careful_mem<false>(src + (int64_t)i * 16 * sh.ld, s, dst + (int64_t)i * 16 * o.ld_fp8);
+            if constexpr (CRIT == kCritEq3)
+                e5 += quant8_careful_mem<true>(src + (int64_t)i * 16 * sh.ld, scale_from_amax_bits(abits, kE5M2Max), nullptr);
+        }
     }
-    const float werr = wave_allsum_f32(e0 + e1);
-    const uint32_t wnnz = wave_allsum_u32(fold_add16(sc.nz2));
+    const float werr = wave_allsum_f32(e);
+    const uint32_t wzero = wave_allsum_u32(fold_add16(sc.zero2));
     float werr5 = 0.0f;
-    if constexpr (CRIT == kCritEq3) {
-        const float s5 = scale_from_amax_bits(abits, kE5M2Max);
-        float f0 = 0.0f, f1 = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) (void)quant8<true>(raw[i], abits, s5, f0, f1);
-        werr5 = wave_allsum_f32(f0 + f1);
-    }
-    if (lane == 0) { sh_err[w] = werr; sh_nnz[w] = wnnz; sh_err5[w] = werr5; }
+    if constexpr (CRIT == kCritEq3) werr5 = wave_allsum_f32(e5);
+    if (lane == 0) { sh_err[w] = werr; sh_zero[w] = wzero; sh_err5[w] = werr5; }
     __syncthreads();
     float err = (sh_err[0] + sh_err[1]) + (sh_err[2] + sh_err[3]);
     float err5 = (sh_err5[0] + sh_err5[1]) + (sh_err5[2] + sh_err5[3]);
-    const uint32_t nnz = (sh_nnz[0] + sh_nnz[1]) + (sh_nnz[2] + sh_nnz[3]);
+    const uint32_t nnz = 128u * 128u - ((sh_zero[0] + sh_zero[1]) + (sh_zero[2] + sh_zero[3]));
     if (abits >= kInfBits) { err = __builtin_inff(); err5 = __builtin_inff(); }
     uint32_t mask = 0u;
     if constexpr (!DEFER) mask = (CRIT == kCritEq3) ? decide_eq3(err, err5) : decide_eq2(err, nnz, th);
@@ -143,16 +164,18 @@ __global__ __launch_bounds__(256) void k_block128(const uint16_t* __restrict__ x
     }
     if constexpr (!DEFER) {
         if (mask && o.bf16) {
+            uint16_t* __restrict__ dbf = o.bf16 + row0 * o.ld_bf16 + col;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) store16(o.bf16 + (row0 + i * 16) * o.ld_bf16 + col, raw[i]);
+            for (int i = 0; i < 8; ++i) store16(dbf + (int64_t)i * 16 * o.ld_bf16, raw[i]);
         }
     }
 }
 
 // ======================================================================================
 // Per-tensor granularity (Section 4.1.1 "Per-Tensor"): pass A = global amax, pass B = quantize
-// with the global scale + per-workgroup error partials, finalize = decision, then a conditional
-// copy of the BF16 fallback.  Everything is stream-ordered; the host never waits.
+// with the global scale; the last workgroup of pass B to finish sums the per-workgroup error
+// partials in binary64 and takes the decision; then a conditional copy of the BF16 fallback.
+// Everything is stream-ordered; the host never waits.
 // ======================================================================================
 constexpr int kTensorChunksPerThread = 8;                       // 16-byte chunks per thread in pass B
 constexpr int kTensorChunksPerBlock = 256 * kTensorChunksPerThread;
@@ -166,18 +189,27 @@ __device__ __forceinline__ uint32_t block_allmax_u32(uint32_t v, uint32_t* sh4) 
     __syncthreads();
     return r;
 }
+__device__ __forceinline__ uint32_t amax2_of(const u32x4& v, uint32_t a2) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) a2 = pk_max_u16(a2, v[j] & 0x7FFF7FFFu);
+    return a2;
+}
 
-// Pass A, dense: grid-stride over 16-byte chunks.
+// Pass A, dense: grid-stride over 16-byte chunks, 8 loads in flight per lane.
 __global__ __launch_bounds__(256) void k_tensor_amax_flat(const uint16_t* __restrict__ x, int64_t n_chunks,
                                                           uint32_t* __restrict__ part) {
     __shared__ uint32_t sh4[4];
     uint32_t a2 = 0u;
     const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < n_chunks; c += stride) {
-        const u32x4 v = load16(x + c * 8);
+    int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    for (; c + 7 * stride < n_chunks; c += 8 * stride) {
+        u32x4 v[8];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) a2 = pk_max_u16(a2, v[j] & 0x7FFF7FFFu);
+        for (int u = 0; u < 8; ++u) v[u] = load16(x + (c + u * stride) * 8);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a2 = amax2_of(v[u], a2);
     }
+    for (; c < n_chunks; c += stride) a2 = amax2_of(load16(x + c * 8), a2);
     const uint32_t a = block_allmax_u32(fold_max16(a2), sh4);
     if (threadIdx.x == 0) part[blockIdx.x] = a;
 }
@@ -188,11 +220,7 @@ __global__ __launch_bounds__(256) void k_tensor_amax_strided(const uint16_t* __r
     uint32_t a2 = 0u;
     const int64_t cpr = sh.cols / 8;
     for (int64_t r = blockIdx.x; r < sh.rows; r += gridDim.x)
-        for (int64_t c = threadIdx.x; c < cpr; c += 256) {
-            const u32x4 v = load16(x + r * sh.ld + c * 8);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) a2 = pk_max_u16(a2, v[j] & 0x7FFF7FFFu);
-        }
+        for (int64_t c = threadIdx.x; c < cpr; c += 256) a2 = amax2_of(load16(x + r * sh.ld + c * 8), a2);
     const uint32_t a = block_allmax_u32(fold_max16(a2), sh4);
     if (threadIdx.x == 0) part[blockIdx.x] = a;
 }
@@ -203,83 +231,13 @@ __device__ __forceinline__ uint32_t global_amax_bits(const uint32_t* __restrict_
     return block_allmax_u32(a, sh4);
 }
 
-struct TensorPartials {
+struct TensorPartials {   // one slot per pass-B workgroup (at most kMaxQuantBlocks)
     float* err;
     float* err5;
-    uint32_t* nnz;
+    uint32_t* zero;        // zero elements seen by the workgroup (padding chunks count as zeros)
+    uint32_t* abits;       // [0] = global amax bits, published by workgroup 0 of pass B
 };
-
-template <int CRIT>
-__device__ __forceinline__ void tensor_block_finish(float e, float e5, uint32_t nz2, const TensorPartials& tp, int64_t slot,
-                                                    float* shf, uint32_t* shu) {
-    const float werr = wave_allsum_f32(e);
-    const uint32_t wnnz = wave_allsum_u32(fold_add16(nz2));
-    float werr5 = 0.0f;
-    if constexpr (CRIT == kCritEq3) werr5 = wave_allsum_f32(e5);
-    const int w = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) { shf[w] = werr; shf[4 + w] = werr5; shu[w] = wnnz; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        tp.err[slot] = (shf[0] + shf[1]) + (shf[2] + shf[3]);
-        tp.nnz[slot] = (shu[0] + shu[1]) + (shu[2] + shu[3]);
-        if constexpr (CRIT == kCritEq3) tp.err5[slot] = (shf[4] + shf[5]) + (shf[6] + shf[7]);
-    }
-}
-
-// Pass B, dense: a workgroup owns 2048 consecutive chunks (32 KB of input).
-template <int CRIT>
-__global__ __launch_bounds__(256) void k_tensor_quant_flat(const uint16_t* __restrict__ x, int64_t n_chunks, KOut o,
-                                                           const uint32_t* __restrict__ amax_part, int n_amax_part,
-                                                           TensorPartials tp) {
-    __shared__ uint32_t sh4[4];
-    __shared__ float shf[8];
-    __shared__ uint32_t shu[4];
-    const int64_t c0 = (int64_t)blockIdx.x * kTensorChunksPerBlock + threadIdx.x;
-    u32x4 raw[kTensorChunksPerThread];
-#pragma unroll
-    for (int u = 0; u < kTensorChunksPerThread; ++u) {
-        const int64_t c = c0 + u * 256;
-        if (c < n_chunks) raw[u] = load16(x + c * 8);
-        else { raw[u].x = 0u; raw[u].y = 0u; raw[u].z = 0u; raw[u].w = 0u; }
-    }
-    const uint32_t abits = global_amax_bits(amax_part, n_amax_part, sh4);
-    const float s = scale_from_amax_bits(abits, kE4M3Max);
-    const float s5 = (CRIT == kCritEq3) ? scale_from_amax_bits(abits, kE5M2Max) : 0.0f;
-    Scan8 sc{0u, 0u};
-    float e0 = 0.0f, e1 = 0.0f, f0 = 0.0f, f1 = 0.0f;
-#pragma unroll
-    for (int u = 0; u < kTensorChunksPerThread; ++u) {
-        const int64_t c = c0 + u * 256;
-        scan8(raw[u], sc);
-        const u32x2 codes = quant8<false>(raw[u], abits, s, e0, e1);
-        if (c < n_chunks) store8(o.fp8 + c * 8, codes);
-        if constexpr (CRIT == kCritEq3) (void)quant8<true>(raw[u], abits, s5, f0, f1);
-    }
-    tensor_block_finish<CRIT>(e0 + e1, f0 + f1, sc.nz2, tp, blockIdx.x, shf, shu);
-}
-// Pass B, strided: a workgroup owns a 16-row x 128-column tile, one chunk per thread.
-template <int CRIT>
-__global__ __launch_bounds__(256) void k_tensor_quant_strided(const uint16_t* __restrict__ x, KShape sh, KOut o,
-                                                              const uint32_t* __restrict__ amax_part, int n_amax_part,
-                                                              TensorPartials tp) {
-    __shared__ uint32_t sh4[4];
-    __shared__ float shf[8];
-    __shared__ uint32_t shu[4];
-    const int64_t r = (int64_t)blockIdx.y * 16 + (threadIdx.x >> 4);
-    const int64_t c = (int64_t)blockIdx.x * 128 + (threadIdx.x & 15) * 8;
-    const bool live = r < sh.rows && c < sh.cols;
-    u32x4 raw; raw.x = 0u; raw.y = 0u; raw.z = 0u; raw.w = 0u;
-    if (live) raw = load16(x + r * sh.ld + c);
-    const uint32_t abits = global_amax_bits(amax_part, n_amax_part, sh4);
-    const float s = scale_from_amax_bits(abits, kE4M3Max);
-    Scan8 sc{0u, 0u};
-    float e0 = 0.0f, e1 = 0.0f, f0 = 0.0f, f1 = 0.0f;
-    scan8(raw, sc);
-    const u32x2 codes = quant8<false>(raw, abits, s, e0, e1);
-    if (live) store8(o.fp8 + r * o.ld_fp8 + c, codes);
-    if constexpr (CRIT == kCritEq3) (void)quant8<true>(raw, abits, scale_from_amax_bits(abits, kE5M2Max), f0, f1);
-    tensor_block_finish<CRIT>(e0 + e1, f0 + f1, sc.nz2, tp, (int64_t)blockIdx.y * gridDim.x + blockIdx.x, shf, shu);
-}
+constexpr int kMaxQuantBlocks = 1024;
 
 template <typename T>
 __device__ __forceinline__ T block_sum_256(T v, T* sh) {
@@ -294,46 +252,202 @@ __device__ __forceinline__ T block_sum_256(T v, T* sh) {
     __syncthreads();
     return r;
 }
+// Same result on every thread, two barriers, fixed summation order.
+template <typename T>
+__device__ __forceinline__ T block_sum_shfl(T v, T* sh4) {
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) v += __shfl_xor(v, m, 64);
+    if ((threadIdx.x & 63) == 0) sh4[threadIdx.x >> 6] = v;
+    __syncthreads();
+    const T r = (sh4[0] + sh4[1]) + (sh4[2] + sh4[3]);
+    __syncthreads();
+    return r;
+}
 
-// Finalize: sum the partials in binary64, take the decision, write the block outputs (P = 1).
+struct TensorAcc {
+    float e0, e1, f0, f1;
+    uint32_t zero2;
+};
+__device__ __forceinline__ uint32_t zero2_of(const u32x4& v, uint32_t z2) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) z2 = pk_add_u16(z2, pk_is_zero_u16(v[j] & 0x7FFF7FFFu));
+    return z2;
+}
 template <int CRIT>
-__global__ __launch_bounds__(256) void k_tensor_finalize(TensorPartials tp, int64_t n_quant_part, const uint32_t* __restrict__ amax_part,
-                                                         int n_amax_part, KOut o, float th, uint32_t* __restrict__ decision) {
-    __shared__ uint32_t sh4[4];
-    __shared__ double shd[256];
-    __shared__ unsigned long long shl[256];
-    const uint32_t abits = global_amax_bits(amax_part, n_amax_part, sh4);
-    double e = 0.0, e5 = 0.0;
-    unsigned long long n = 0;
-    for (int64_t i = threadIdx.x; i < n_quant_part; i += 256) {
-        e += (double)tp.err[i];
-        n += tp.nnz[i];
-        if constexpr (CRIT == kCritEq3) e5 += (double)tp.err5[i];
-    }
-    e = block_sum_256<double>(e, shd);
-    n = block_sum_256<unsigned long long>(n, shl);
-    if constexpr (CRIT == kCritEq3) e5 = block_sum_256<double>(e5, shd);
+__device__ __forceinline__ void tensor_publish(const TensorAcc& a, const TensorPartials& tp, int slot) {
+    __shared__ float shf[8];
+    __shared__ uint32_t shu[4];
+    const float werr = wave_allsum_f32(a.e0 + a.e1);
+    const uint32_t wzero = wave_allsum_u32(fold_add16(a.zero2));
+    float werr5 = 0.0f;
+    if constexpr (CRIT == kCritEq3) werr5 = wave_allsum_f32(a.f0 + a.f1);
+    const int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { shf[w] = werr; shf[4 + w] = werr5; shu[w] = wzero; }
+    __syncthreads();
     if (threadIdx.x == 0) {
-        if (abits >= kInfBits) { e = (double)__builtin_inff(); e5 = e; }
-        uint32_t mask;
-        if constexpr (CRIT == kCritEq3) mask = (e < e5) ? 0u : 1u;
-        else mask = ((n ? e / (double)n : 0.0) < (double)th) ? 0u : 1u;
-        o.scale[0] = scale_from_amax_bits(abits, kE4M3Max);
-        o.amax[0] = __uint_as_float(abits << 16);
-        o.err_sum[0] = (float)e;
-        o.nnz[0] = n > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)n;
-        if constexpr (CRIT == kCritEq3) o.err5_sum[0] = (float)e5;
-        o.mask[0] = (uint8_t)mask;
-        decision[0] = mask;
+        tp.err[slot] = (shf[0] + shf[1]) + (shf[2] + shf[3]);
+        tp.zero[slot] = (shu[0] + shu[1]) + (shu[2] + shu[3]);
+        if constexpr (CRIT == kCritEq3) tp.err5[slot] = (shf[4] + shf[5]) + (shf[6] + shf[7]);
     }
 }
 
-// Conditional BF16 fallback copy: does nothing unless decision[0] == 1.
+// Pass B, dense: persistent workgroups stride over tiles of 2048 consecutive chunks (32 KB of input);
+// the next tile's loads are issued before the current tile is processed (two register sets).
+template <int CRIT>
+__global__ __launch_bounds__(256) void k_tensor_quant_flat(const uint16_t* __restrict__ x, int64_t n_chunks, int64_t n_tiles,
+                                                           KOut o, const uint32_t* __restrict__ amax_part, int n_amax_part,
+                                                           TensorPartials tp) {
+    __shared__ uint32_t sh4[4];
+    u32x4 bufA[kTensorChunksPerThread], bufB[kTensorChunksPerThread];
+    auto load_tile = [&](u32x4* raw, int64_t tile) {
+        const int64_t c0 = tile * kTensorChunksPerBlock + threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < kTensorChunksPerThread; ++u) {
+            const int64_t c = c0 + u * 256;
+            if (c < n_chunks) raw[u] = load16(x + c * 8);
+            else { raw[u].x = 0u; raw[u].y = 0u; raw[u].z = 0u; raw[u].w = 0u; }
+        }
+    };
+    int64_t t = blockIdx.x;
+    load_tile(bufA, t);
+    const uint32_t abits = global_amax_bits(amax_part, n_amax_part, sh4);
+    if (blockIdx.x == 0 && threadIdx.x == 0) tp.abits[0] = abits;
+    const float s = scale_from_amax_bits(abits, kE4M3Max);
+    const float s5 = (CRIT == kCritEq3) ? scale_from_amax_bits(abits, kE5M2Max) : 0.0f;
+    TensorAcc acc{0.0f, 0.0f, 0.0f, 0.0f, 0u};
+    auto process = [&](const u32x4* raw, int64_t tile) {
+        const int64_t c0 = tile * kTensorChunksPerBlock + threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < kTensorChunksPerThread; ++u) acc.zero2 = zero2_of(raw[u], acc.zero2);
+        if (abits < kFastAmaxBits) {
+#pragma unroll
+            for (int u = 0; u < kTensorChunksPerThread; ++u) {
+                const int64_t c = c0 + u * 256;
+                const u32x2 codes = quant8_fast<false>(raw[u], s, acc.e0, acc.e1);
+                if (c < n_chunks) store8(o.fp8 + c * 8, codes);
+                if constexpr (CRIT == kCritEq3) (void)quant8_fast<true>(raw[u], s5, acc.f0, acc.f1);
+            }
+        } else {
+#pragma clang loop unroll(disable)
+            for (int u = 0; u < kTensorChunksPerThread; ++u) {
+                const int64_t c = c0 + u * 256;
+                if (c < n_chunks) {
+                    acc.e0 += quant8_careful_mem<false>(x + c * 8, s, o.fp8 + c * 8);
+                    if constexpr (CRIT == kCritEq3) acc.f0 += quant8_careful_mem<true>(x + c * 8, s5, nullptr);
+                }
+            }
+        }
+    };
+    const int64_t G = gridDim.x;
+    for (;;) {
+        const int64_t tb = t + G;
+        if (tb < n_tiles) load_tile(bufB, tb);
+        process(bufA, t);
+        if (tb >= n_tiles) break;
+        t = tb + G;
+        if (t < n_tiles) load_tile(bufA, t);
+        process(bufB, tb);
+        if (t >= n_tiles) break;
+    }
+    tensor_publish<CRIT>(acc, tp, blockIdx.x);
+}
+// Pass B, strided: persistent workgroups stride over 16-row x 128-column tiles, one chunk per thread.
+template <int CRIT>
+__global__ __launch_bounds__(256) void k_tensor_quant_strided(const uint16_t* __restrict__ x, KShape sh, uint32_t tiles_x,
+                                                              uint32_t n_tiles, KOut o, const uint32_t* __restrict__ amax_part,
+                                                              int n_amax_part, TensorPartials tp) {
+    __shared__ uint32_t sh4[4];
+    const uint32_t abits = global_amax_bits(amax_part, n_amax_part, sh4);
+    if (blockIdx.x == 0 && threadIdx.x == 0) tp.abits[0] = abits;
+    const float s = scale_from_amax_bits(abits, kE4M3Max);
+    const float s5 = (CRIT == kCritEq3) ? scale_from_amax_bits(abits, kE5M2Max) : 0.0f;
+    TensorAcc acc{0.0f, 0.0f, 0.0f, 0.0f, 0u};
+    for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint32_t ty = tile / tiles_x, tx = tile - ty * tiles_x;
+        const int64_t r = (int64_t)ty * 16 + (threadIdx.x >> 4);
+        const int64_t c = (int64_t)tx * 128 + (threadIdx.x & 15) * 8;
+        const bool live = r < sh.rows && c < sh.cols;
+        u32x4 raw; raw.x = 0u; raw.y = 0u; raw.z = 0u; raw.w = 0u;
+        if (live) raw = load16(x + r * sh.ld + c);
+        acc.zero2 = zero2_of(raw, acc.zero2);
+        if (abits < kFastAmaxBits) {
+            const u32x2 codes = quant8_fast<false>(raw, s, acc.e0, acc.e1);
+            if (live) store8(o.fp8 + r * o.ld_fp8 + c, codes);
+            if constexpr (CRIT == kCritEq3) (void)quant8_fast<true>(raw, s5, acc.f0, acc.f1);
+        } else if (live) {
+            acc.e0 += quant8_careful_mem<false>(x + r * sh.ld + c, s, o.fp8 + r * o.ld_fp8 + c);
+            if constexpr (CRIT == kCritEq3) acc.f0 += quant8_careful_mem<true>(x + r * sh.ld + c, s5, nullptr);
+        }
+    }
+    tensor_publish<CRIT>(acc, tp, blockIdx.x);
+}
+
+// Pass C: every workgroup re-derives the tensor's decision from the per-workgroup partials
+// (binary64 sums in a fixed order, so all workgroups agree), workgroup 0 writes the block outputs
+// (P = 1), and if the decision is BF16 the grid copies the operand into the fallback buffer.
+template <int CRIT>
+__global__ __launch_bounds__(256) void k_tensor_finish(TensorPartials tp, int n_slots, unsigned long long n_padded, KOut o, float th,
+                                                       const uint16_t* __restrict__ x, KShape sh, int flat) {
+    __shared__ double shd[4];
+    __shared__ unsigned long long shl[4];
+    double se = 0.0, se5 = 0.0;
+    unsigned long long sz = 0;
+    for (int i = threadIdx.x; i < n_slots; i += 256) {
+        se += (double)tp.err[i];
+        sz += tp.zero[i];
+        if constexpr (CRIT == kCritEq3) se5 += (double)tp.err5[i];
+    }
+    se = block_sum_shfl<double>(se, shd);
+    sz = block_sum_shfl<unsigned long long>(sz, shl);
+    if constexpr (CRIT == kCritEq3) se5 = block_sum_shfl<double>(se5, shd);
+    const uint32_t abits = tp.abits[0];
+    const unsigned long long n = n_padded - sz;
+    if (abits >= kInfBits) { se = (double)__builtin_inff(); se5 = se; }
+    uint32_t mask;
+    if constexpr (CRIT == kCritEq3) mask = (se < se5) ? 0u : 1u;
+    else mask = ((n ? se / (double)n : 0.0) < (double)th) ? 0u : 1u;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        o.scale[0] = scale_from_amax_bits(abits, kE4M3Max);
+        o.amax[0] = __uint_as_float(abits << 16);
+        o.err_sum[0] = (float)se;
+        o.nnz[0] = n > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)n;
+        if constexpr (CRIT == kCritEq3) o.err5_sum[0] = (float)se5;
+        o.mask[0] = (uint8_t)mask;
+    }
+    if (mask == 0u || o.bf16 == nullptr) return;
+    if (flat) {
+        const int64_t n_chunks = sh.rows * sh.cols / 8;
+        const int64_t stride = (int64_t)gridDim.x * 256;
+        int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+        for (; c + 3 * stride < n_chunks; c += 4 * stride) {
+            u32x4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = load16(x + (c + u * stride) * 8);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) store16(o.bf16 + (c + u * stride) * 8, v[u]);
+        }
+        for (; c < n_chunks; c += stride) store16(o.bf16 + c * 8, load16(x + c * 8));
+    } else {
+        const int64_t cpr = sh.cols / 8;
+        for (int64_t r = blockIdx.x; r < sh.rows; r += gridDim.x)
+            for (int64_t c = threadIdx.x; c < cpr; c += 256) store16(o.bf16 + r * o.ld_bf16 + c * 8, load16(x + r * sh.ld + c * 8));
+    }
+}
+
+// Conditional BF16 fallback copy for the tensor-scope path: does nothing unless decision[0] == 1.
 __global__ __launch_bounds__(256) void k_fallback_copy_flat(const uint16_t* __restrict__ x, uint16_t* __restrict__ dst,
                                                             int64_t n_chunks, const uint32_t* __restrict__ decision) {
     if (decision[0] == 0u) return;
     const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < n_chunks; c += stride) store16(dst + c * 8, load16(x + c * 8));
+    int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    for (; c + 3 * stride < n_chunks; c += 4 * stride) {
+        u32x4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = load16(x + (c + u * stride) * 8);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) store16(dst + (c + u * stride) * 8, v[u]);
+    }
+    for (; c < n_chunks; c += stride) store16(dst + c * 8, load16(x + c * 8));
 }
 __global__ __launch_bounds__(256) void k_fallback_copy_strided(const uint16_t* __restrict__ x, KShape sh, uint16_t* __restrict__ dst,
                                                                int64_t ld_dst, const uint32_t* __restrict__ decision) {
@@ -443,65 +557,103 @@ struct StatsDev {   // must match mor_stats in include/mor.h
     uint32_t hist[12];
     uint32_t reserved;
 };
+__device__ __forceinline__ int stats_bin(float metric) {
+    if (!(metric < __builtin_inff())) return 11;
+    int bin = 0;
+#pragma unroll
+    for (int k = 1; k <= 11; ++k)
+        if (metric >= (float)(0.005 * k)) bin = k;
+    return bin;
+}
+struct StatsAcc {
+    double e;
+    unsigned long long n;
+    uint32_t n_bf16, n_near;
+};
+__device__ __forceinline__ void stats_accumulate(int64_t p, const float* __restrict__ err_sum, const uint32_t* __restrict__ nnz,
+                                                 const uint8_t* __restrict__ mask, float th, float near_tol, uint32_t* sh_hist,
+                                                 StatsAcc& a) {
+    const float es = err_sum[p];
+    const uint32_t nz = nnz[p];
+    const float metric = nz ? es / (float)nz : 0.0f;           // binary32, IEEE division
+    atomicAdd(&sh_hist[stats_bin(metric)], 1u);
+    a.e += (double)es;
+    a.n += nz;
+    a.n_bf16 += mask[p] ? 1u : 0u;
+    if (fabs((double)metric - (double)th) <= (double)near_tol * (double)th) a.n_near += 1u;
+}
+__device__ __forceinline__ void stats_finish(StatsDev* st, int64_t n_part, unsigned long long elems_per_part, double e,
+                                             unsigned long long n, unsigned long long n_bf16, unsigned long long n_near) {
+    st->n_part = (unsigned long long)n_part;
+    st->n_fp8_part = (unsigned long long)n_part - n_bf16;
+    st->n_bf16_part = n_bf16;
+    st->n_elem_fp8 = ((unsigned long long)n_part - n_bf16) * elems_per_part;
+    st->n_elem_bf16 = n_bf16 * elems_per_part;
+    st->nnz_total = n;
+    st->n_near_threshold = n_near;
+    st->err_sum_total = e;
+    st->mean_err = n ? e / (double)n : 0.0;
+    st->reserved = 0u;
+}
+
+// Up to a few thousand blocks: one workgroup, no atomics on global memory, deterministic sums.
+__global__ __launch_bounds__(256) void k_stats_single(int64_t n_part, unsigned long long elems_per_part,
+                                                      const float* __restrict__ err_sum, const uint32_t* __restrict__ nnz,
+                                                      const uint8_t* __restrict__ mask, float th, float near_tol,
+                                                      StatsDev* __restrict__ st) {
+    __shared__ uint32_t sh_hist[12];
+    __shared__ uint32_t sh_cnt[2];
+    __shared__ double shd[256];
+    __shared__ unsigned long long shl[256];
+    if (threadIdx.x < 12) sh_hist[threadIdx.x] = 0u;
+    if (threadIdx.x < 2) sh_cnt[threadIdx.x] = 0u;
+    __syncthreads();
+    StatsAcc a{0.0, 0ull, 0u, 0u};
+    for (int64_t p = threadIdx.x; p < n_part; p += 256) stats_accumulate(p, err_sum, nnz, mask, th, near_tol, sh_hist, a);
+    if (a.n_bf16) atomicAdd(&sh_cnt[0], a.n_bf16);
+    if (a.n_near) atomicAdd(&sh_cnt[1], a.n_near);
+    const double e = block_sum_256<double>(a.e, shd);
+    const unsigned long long n = block_sum_256<unsigned long long>(a.n, shl);
+    if (threadIdx.x < 12) st->hist[threadIdx.x] = sh_hist[threadIdx.x];
+    if (threadIdx.x == 0) stats_finish(st, n_part, elems_per_part, e, n, sh_cnt[0], sh_cnt[1]);
+}
+
+// Many blocks: the accumulators live in the output struct, cleared by a tiny kernel first and
+// turned into the derived fields by a tiny kernel afterwards (no device-wide fences needed).
 __global__ void k_stats_zero(StatsDev* st) {
     if (threadIdx.x < sizeof(StatsDev) / 4) reinterpret_cast<uint32_t*>(st)[threadIdx.x] = 0u;
 }
-__global__ __launch_bounds__(256) void k_stats(int64_t n_part, unsigned long long elems_per_part, const float* __restrict__ err_sum,
-                                               const uint32_t* __restrict__ nnz, const uint8_t* __restrict__ mask, float th,
-                                               float near_tol, StatsDev* __restrict__ st) {
+__global__ __launch_bounds__(256) void k_stats_multi(int64_t n_part, unsigned long long elems_per_part,
+                                                     const float* __restrict__ err_sum, const uint32_t* __restrict__ nnz,
+                                                     const uint8_t* __restrict__ mask, float th, float near_tol,
+                                                     StatsDev* __restrict__ st) {
     __shared__ uint32_t sh_hist[12];
+    __shared__ uint32_t sh_cnt[2];
     __shared__ double shd[256];
     __shared__ unsigned long long shl[256];
-    __shared__ bool last;
     if (threadIdx.x < 12) sh_hist[threadIdx.x] = 0u;
+    if (threadIdx.x < 2) sh_cnt[threadIdx.x] = 0u;
     __syncthreads();
-    double e = 0.0;
-    unsigned long long n = 0, n_bf16 = 0, n_near = 0;
+    StatsAcc a{0.0, 0ull, 0u, 0u};
     const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x; p < n_part; p += stride) {
-        const float es = err_sum[p];
-        const uint32_t nz = nnz[p];
-        const float metric = nz ? es / (float)nz : 0.0f;           // binary32, IEEE division
-        int bin = 0;
-        if (!(metric < __builtin_inff())) bin = 11;
-        else {
-#pragma unroll
-            for (int k = 1; k <= 11; ++k)
-                if (metric >= (float)(0.005 * k)) bin = k;
-        }
-        atomicAdd(&sh_hist[bin], 1u);
-        e += (double)es;
-        n += nz;
-        n_bf16 += mask[p] ? 1u : 0u;
-        if (fabs((double)metric - (double)th) <= (double)near_tol * (double)th) n_near += 1u;
-    }
-    e = block_sum_256<double>(e, shd);
-    n = block_sum_256<unsigned long long>(n, shl);
-    n_bf16 = block_sum_256<unsigned long long>(n_bf16, shl);
-    n_near = block_sum_256<unsigned long long>(n_near, shl);
+    for (int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x; p < n_part; p += stride)
+        stats_accumulate(p, err_sum, nnz, mask, th, near_tol, sh_hist, a);
+    if (a.n_bf16) atomicAdd(&sh_cnt[0], a.n_bf16);
+    if (a.n_near) atomicAdd(&sh_cnt[1], a.n_near);
+    const double e = block_sum_256<double>(a.e, shd);
+    const unsigned long long n = block_sum_256<unsigned long long>(a.n, shl);
     if (threadIdx.x < 12 && sh_hist[threadIdx.x]) atomicAdd(&st->hist[threadIdx.x], sh_hist[threadIdx.x]);
     if (threadIdx.x == 0) {
         atomicAdd(&st->err_sum_total, e);
         atomicAdd(&st->nnz_total, n);
-        atomicAdd(&st->n_bf16_part, n_bf16);
-        atomicAdd(&st->n_near_threshold, n_near);
+        atomicAdd(&st->n_bf16_part, (unsigned long long)sh_cnt[0]);
+        atomicAdd(&st->n_near_threshold, (unsigned long long)sh_cnt[1]);
     }
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) last = (atomicAdd(&st->reserved, 1u) == gridDim.x - 1);
-    __syncthreads();
-    if (last && threadIdx.x == 0) {
-        __threadfence();
-        const unsigned long long nb = atomicAdd(&st->n_bf16_part, 0ull);
-        const unsigned long long nn = atomicAdd(&st->nnz_total, 0ull);
-        const double et = atomicAdd(&st->err_sum_total, 0.0);
-        st->n_part = (unsigned long long)n_part;
-        st->n_fp8_part = (unsigned long long)n_part - nb;
-        st->n_elem_bf16 = nb * elems_per_part;
-        st->n_elem_fp8 = ((unsigned long long)n_part - nb) * elems_per_part;
-        st->mean_err = nn ? et / (double)nn : 0.0;
-        st->reserved = 0u;
-    }
+}
+// Derived fields once every workgroup of k_stats_multi has finished (next kernel on the stream).
+__global__ void k_stats_finish(int64_t n_part, unsigned long long elems_per_part, StatsDev* __restrict__ st) {
+    if (threadIdx.x == 0)
+        stats_finish(st, n_part, elems_per_part, st->err_sum_total, st->nnz_total, st->n_bf16_part, st->n_near_threshold);
 }
 
 // ======================================================================================
@@ -522,22 +674,16 @@ struct ProfScope {
     ~ProfScope() { if (slot >= 0) (void)hipEventRecord(prof->stop[slot], st); }
 };
 
-static int64_t tensor_quant_blocks(int64_t rows, int64_t cols) {
-    const int64_t flat = (rows * cols / 8 + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
-    const int64_t strided = ((cols + 127) / 128) * ((rows + 15) / 16);
-    return flat > strided ? flat : strided;
-}
-
-TensorPlan plan_tensor(int64_t rows, int64_t cols) {
+TensorPlan plan_tensor(int64_t, int64_t) {
     TensorPlan pl;
     pl.amax_blocks = kMaxAmaxBlocks;
-    pl.quant_blocks = tensor_quant_blocks(rows, cols);
+    pl.quant_blocks = kMaxQuantBlocks;
     size_t off = 0;
     pl.off_amax_part = off; off = align16(off + sizeof(uint32_t) * (size_t)pl.amax_blocks);
     pl.off_err_part = off;  off = align16(off + sizeof(float) * (size_t)pl.quant_blocks);
     pl.off_err5_part = off; off = align16(off + sizeof(float) * (size_t)pl.quant_blocks);
-    pl.off_nnz_part = off;  off = align16(off + sizeof(uint32_t) * (size_t)pl.quant_blocks);
-    pl.off_decision = off;  off = align16(off + 16);
+    pl.off_nnz_part = off;  off = align16(off + sizeof(uint32_t) * (size_t)pl.quant_blocks);   // zero counts
+    pl.off_decision = off;  off = align16(off + 16);                                           // [0] global amax bits
     pl.bytes = off;
     return pl;
 }
@@ -584,41 +730,41 @@ hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int
     char* w = static_cast<char*>(ws);
     uint32_t* amax_part = reinterpret_cast<uint32_t*>(w + pl.off_amax_part);
     TensorPartials tp{reinterpret_cast<float*>(w + pl.off_err_part), reinterpret_cast<float*>(w + pl.off_err5_part),
-                      reinterpret_cast<uint32_t*>(w + pl.off_nnz_part)};
-    uint32_t* decision = reinterpret_cast<uint32_t*>(w + pl.off_decision);
+                      reinterpret_cast<uint32_t*>(w + pl.off_nnz_part), reinterpret_cast<uint32_t*>(w + pl.off_decision)};
     const int64_t n_chunks = sh.rows * sh.cols / 8;
     const bool flat = is_flat(sh, o);
-    int n_amax;
-    int64_t n_quant;
+    int n_amax, n_slots;
+    unsigned long long n_padded;
     if (flat) {
         int64_t want = (n_chunks + 256 * 8 - 1) / (256 * 8);
         n_amax = (int)(want < 1 ? 1 : (want > kMaxAmaxBlocks ? kMaxAmaxBlocks : want));
         { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_flat<<<dim3(n_amax), dim3(256), 0, st>>>(x, n_chunks, amax_part); }
-        n_quant = (n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
-        if (n_quant > 0x7FFFFFFF) return hipErrorInvalidValue;
+        const int64_t n_tiles = (n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
+        n_slots = (int)(n_tiles < kMaxQuantBlocks ? n_tiles : kMaxQuantBlocks);
+        if (n_tiles / n_slots > 2000) return hipErrorInvalidValue;   // 16-bit per-lane zero counters (32 per tile)
+        n_padded = (unsigned long long)n_tiles * kTensorChunksPerBlock * 8;
         ProfScope ps(prof, kKernTensorQuant, st);
-        if (crit == kCritEq3) k_tensor_quant_flat<kCritEq3><<<dim3((unsigned)n_quant), dim3(256), 0, st>>>(x, n_chunks, o, amax_part, n_amax, tp);
-        else k_tensor_quant_flat<kCritEq2><<<dim3((unsigned)n_quant), dim3(256), 0, st>>>(x, n_chunks, o, amax_part, n_amax, tp);
+        if (crit == kCritEq3) k_tensor_quant_flat<kCritEq3><<<dim3(n_slots), dim3(256), 0, st>>>(x, n_chunks, n_tiles, o, amax_part, n_amax, tp);
+        else k_tensor_quant_flat<kCritEq2><<<dim3(n_slots), dim3(256), 0, st>>>(x, n_chunks, n_tiles, o, amax_part, n_amax, tp);
     } else {
         n_amax = (int)(sh.rows < kMaxAmaxBlocks ? sh.rows : kMaxAmaxBlocks);
         { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_strided<<<dim3(n_amax), dim3(256), 0, st>>>(x, sh, amax_part); }
         const int64_t gx = (sh.cols + 127) / 128, gy = (sh.rows + 15) / 16;
-        if (gy > 65535) return hipErrorInvalidValue;
-        n_quant = gx * gy;
-        const dim3 grid((unsigned)gx, (unsigned)gy);
+        if (gx * gy > 0x7FFFFFFF) return hipErrorInvalidValue;
+        // 16-bit zero counters per lane: at most 8 zeros per tile and lane, so 4096 tiles per workgroup are safe
+        int64_t min_blocks = (gx * gy + 4095) / 4096;
+        if (min_blocks > kMaxQuantBlocks) return hipErrorInvalidValue;
+        n_slots = (int)(gx * gy < kMaxQuantBlocks ? gx * gy : kMaxQuantBlocks);
+        n_padded = (unsigned long long)(gx * gy) * 2048ull;
         ProfScope ps(prof, kKernTensorQuant, st);
-        if (crit == kCritEq3) k_tensor_quant_strided<kCritEq3><<<grid, dim3(256), 0, st>>>(x, sh, o, amax_part, n_amax, tp);
-        else k_tensor_quant_strided<kCritEq2><<<grid, dim3(256), 0, st>>>(x, sh, o, amax_part, n_amax, tp);
+        if (crit == kCritEq3) k_tensor_quant_strided<kCritEq3><<<dim3(n_slots), dim3(256), 0, st>>>(x, sh, (uint32_t)gx, (uint32_t)(gx * gy), o, amax_part, n_amax, tp);
+        else k_tensor_quant_strided<kCritEq2><<<dim3(n_slots), dim3(256), 0, st>>>(x, sh, (uint32_t)gx, (uint32_t)(gx * gy), o, amax_part, n_amax, tp);
     }
     {
-        ProfScope ps(prof, kKernTensorFinalize, st);
-        if (crit == kCritEq3) k_tensor_finalize<kCritEq3><<<dim3(1), dim3(256), 0, st>>>(tp, n_quant, amax_part, n_amax, o, th, decision);
-        else k_tensor_finalize<kCritEq2><<<dim3(1), dim3(256), 0, st>>>(tp, n_quant, amax_part, n_amax, o, th, decision);
-    }
-    if (o.bf16) {
         ProfScope ps(prof, kKernFallbackCopy, st);
-        if (flat) k_fallback_copy_flat<<<dim3(2048), dim3(256), 0, st>>>(x, o.bf16, n_chunks, decision);
-        else k_fallback_copy_strided<<<dim3((unsigned)(sh.rows < 4096 ? sh.rows : 4096)), dim3(256), 0, st>>>(x, sh, o.bf16, o.ld_bf16, decision);
+        const int grid = o.bf16 ? 2048 : 1;
+        if (crit == kCritEq3) k_tensor_finish<kCritEq3><<<dim3(grid), dim3(256), 0, st>>>(tp, n_slots, n_padded, o, th, x, sh, flat ? 1 : 0);
+        else k_tensor_finish<kCritEq2><<<dim3(grid), dim3(256), 0, st>>>(tp, n_slots, n_padded, o, th, x, sh, flat ? 1 : 0);
     }
     return hipGetLastError();
 }
@@ -668,10 +814,15 @@ hipError_t launch_select_stats(int64_t n_part, int64_t elems_per_part, const flo
                                const uint8_t* mask, float th, float near_tol, void* out_dev, hipStream_t st) {
     static_assert(sizeof(StatsDev) == 128, "mor_stats layout");
     StatsDev* sd = static_cast<StatsDev*>(out_dev);
-    k_stats_zero<<<dim3(1), dim3(64), 0, st>>>(sd);
-    int64_t want = (n_part + 2047) / 2048;
-    const int nb = (int)(want < 1 ? 1 : (want > 256 ? 256 : want));
-    k_stats<<<dim3(nb), dim3(256), 0, st>>>(n_part, (unsigned long long)elems_per_part, err_sum, nnz, mask, th, near_tol, sd);
+    if (n_part <= 8192) {
+        k_stats_single<<<dim3(1), dim3(256), 0, st>>>(n_part, (unsigned long long)elems_per_part, err_sum, nnz, mask, th, near_tol, sd);
+    } else {
+        k_stats_zero<<<dim3(1), dim3(64), 0, st>>>(sd);
+        int64_t want = (n_part + 1023) / 1024;
+        const int nb = (int)(want > 1024 ? 1024 : want);
+        k_stats_multi<<<dim3(nb), dim3(256), 0, st>>>(n_part, (unsigned long long)elems_per_part, err_sum, nnz, mask, th, near_tol, sd);
+        k_stats_finish<<<dim3(1), dim3(64), 0, st>>>(n_part, (unsigned long long)elems_per_part, sd);
+    }
     return hipGetLastError();
 }
 
