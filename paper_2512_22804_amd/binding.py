@@ -13,7 +13,7 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmor.so")
+LIB_PATH = os.environ.get("MOR_LIB_PATH", os.path.join(_HERE, "libmor.so"))
 
 MOR_GRAN_TENSOR, MOR_GRAN_SUB_1x128, MOR_GRAN_BLOCK_128x128 = 0, 1, 2
 MOR_FMT_E4M3, MOR_FMT_E5M2, MOR_FMT_BF16 = 1, 2, 4

@@ -160,6 +160,11 @@ template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
 }
+// Value of lane `SRC` (0..15) of each 16-lane row, in every lane of that row.
+template <int SRC>
+__device__ __forceinline__ float row_bcast_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x150 + SRC, 0xF, 0xF, true));
+}
 constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
 constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
 constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each 8 lanes
@@ -208,9 +213,11 @@ __device__ __forceinline__ float wave_allsum_f32(float v) {
 }
 
 // ---- Algorithm 2 with [E4M3, BF16]: 0 = keep E4M3, 1 = keep BF16 ------------------------------
+// Eq. (2): err_sum / nnz < th, evaluated division-free as err_sum < th * nnz (the metric of a
+// block without non-zero elements is 0).  False for NaN / inf sums.
 __device__ __forceinline__ uint32_t decide_eq2(float err_sum, uint32_t nnz, float th) {
-    float metric = nnz ? err_sum / (float)nnz : 0.0f;
-    return (metric < th) ? 0u : 1u;               // false for NaN / inf
+    const bool accept = nnz ? (err_sum < th * (float)nnz) : (0.0f < th);
+    return accept ? 0u : 1u;
 }
 __device__ __forceinline__ uint32_t decide_eq3(float err4, float err5) { return (err4 < err5) ? 0u : 1u; }
 

@@ -60,22 +60,177 @@ __device__ __forceinline__ void sub_block_body(const u32x4& raw, const uint16_t*
 }
 
 // Dense operands (every leading dimension == cols): blocks are consecutive 256-byte runs.
-template <int CRIT, bool DEFER>
-__global__ __launch_bounds__(256) void k_sub1x128_flat(const uint16_t* __restrict__ x, KOut o, int64_t n_part, float th) {
-    const int lane = threadIdx.x & 63, g = lane >> 4, l = lane & 15;
-    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int64_t pbase = wave * 16 + g * 4;
-    u32x4 raw[4];
+// A wave owns 64 consecutive blocks.  DPP row g (16 lanes x 8 elements) works through blocks
+// g*16 .. g*16+15, eight at a time with all eight loads in flight; lane j of the row keeps the
+// scalars of block g*16+j, so the per-block work (division, decision, metadata) is done once per
+// 16 blocks by 64 lanes in parallel and the metadata stores are contiguous 256-byte runs.
+// Batched 16-lane butterflies over N independent values: the N chains interleave, which hides the
+// DPP read-after-write wait states.
+template <int CTRL, int N>
+__device__ __forceinline__ void rows_max_step(uint32_t (&v)[N]) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const int64_t p = pbase + k;
-        if (p < n_part) raw[k] = load16(x + p * 128 + l * 8);
+    for (int i = 0; i < N; ++i) v[i] = max(v[i], dpp_u32<CTRL>(v[i]));
+}
+template <int CTRL, int N>
+__device__ __forceinline__ void rows_add_step(float (&v)[N]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] += dpp_f32<CTRL>(v[i]);
+}
+template <int N>
+__device__ __forceinline__ void rows_allmax(uint32_t (&v)[N]) {
+    rows_max_step<kDppXor1, N>(v); rows_max_step<kDppXor2, N>(v); rows_max_step<kDppHalfMirror, N>(v); rows_max_step<kDppMirror, N>(v);
+}
+template <int N>
+__device__ __forceinline__ void rows_allsum(float (&v)[N]) {
+    rows_add_step<kDppXor1, N>(v); rows_add_step<kDppXor2, N>(v); rows_add_step<kDppHalfMirror, N>(v); rows_add_step<kDppMirror, N>(v);
+}
+
+// Rarely taken: some block of this unit has amax >= 2^25 or is non-finite.  Rolled loop, data re-read
+// from memory, every block of the unit goes through the careful element path (valid for any input).
+template <int CRIT>
+__device__ __forceinline__ void sub_unit_careful(const uint16_t* __restrict__ xl, uint8_t* __restrict__ fl, int lane, float my_s,
+                                                 float my_s5, float& my_err, float& my_err5) {
+    const int l = lane & 15;
+#pragma clang loop unroll(disable)
+    for (int k = 0; k < 8; ++k) {
+        const int src_lane = (lane & 48) + k;
+        const float s_k = __shfl(my_s, src_lane, 64);
+        float e = quant8_careful_mem<false>(xl + k * 128, s_k, fl + k * 128);
+        e = row_allsum_f32(e);
+        if ((l & 7) == k) my_err = e;
+        if constexpr (CRIT == kCritEq3) {
+            const float s5_k = __shfl(my_s5, src_lane, 64);
+            float e5 = quant8_careful_mem<true>(xl + k * 128, s5_k, nullptr);
+            e5 = row_allsum_f32(e5);
+            if ((l & 7) == k) my_err5 = e5;
+        }
     }
+}
+
+// One unit = 32 consecutive blocks: DPP row g (16 lanes x 8 elements) owns blocks g*8 .. g*8+7 of the
+// unit, all eight already loaded into raw[].  Lane j (and its mirror j+8) of the row keeps the scalars of
+// block g*8+j, so the per-block work (division, decision, metadata) runs once per 8 blocks.
+template <int CRIT, bool DEFER>
+__device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const uint16_t* __restrict__ x, const KOut& o, int64_t unit,
+                                                 int lane, float th) {
+    const int g = lane >> 4, l = lane & 15, own = l & 7;
+    const int64_t prow = unit * 32 + g * 8;
+    const int64_t off = prow * 128 + l * 8;
+    uint8_t* __restrict__ fl = o.fp8 + off;
+#ifdef MOR_DBG_NOCOMPUTE
+    {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const int64_t p = pbase + k;
-        const int64_t off = p * 128 + l * 8;
-        if (p < n_part) sub_block_body<CRIT, DEFER>(raw[k], x + off, l, p, o, o.fp8 + off, o.bf16 ? o.bf16 + off : nullptr, th);
+        for (int k = 0; k < 8; ++k) { u32x2 c; c.x = raw[k].x ^ raw[k].z; c.y = raw[k].y ^ raw[k].w; store8(fl + k * 128, c); }
+        return;
+    }
+#endif
+    // phase 1: per-block amax (to the owner lane) and zero counts (packed 4 blocks per dword)
+    uint32_t ab[8];
+    uint32_t zp0 = 0u, zp1 = 0u;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        Scan8 sc{0u, 0u};
+        scan8(raw[k], sc);
+        ab[k] = fold_max16(sc.amax2);
+        const uint32_t zc = __builtin_amdgcn_sad_u16(sc.zero2, 0u, 0u);       // low + high half-word counts (<= 8)
+        if (k < 4) zp0 |= zc << (8 * k); else zp1 |= zc << (8 * (k - 4));
+    }
+    rows_allmax<8>(ab);
+    uint32_t amax_unit = 0u, my_abits = 0u;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        amax_unit = max(amax_unit, ab[k]);
+        if (own == k) my_abits = ab[k];
+    }
+    zp0 = row_allsum_u32(zp0);        // byte sums <= 128: no carry between bytes
+    zp1 = row_allsum_u32(zp1);
+    const uint32_t my_zero = (((own & 4) ? zp1 : zp0) >> (8 * (own & 3))) & 0xFFu;
+    const float my_s = scale_from_amax_bits(my_abits, kE4M3Max);
+    float my_s5 = 0.0f;
+    if constexpr (CRIT == kCritEq3) my_s5 = scale_from_amax_bits(my_abits, kE5M2Max);
+    // phase 2: quantize with the owner's scale, reduce the error terms to the owner
+    float my_err = 0.0f, my_err5 = 0.0f;
+    if (__any(amax_unit >= kFastAmaxBits)) {
+        sub_unit_careful<CRIT>(x + off, fl, lane, my_s, my_s5, my_err, my_err5);
+    } else {
+        float e[8], e5[8];
+#define MOR_SUB_ONE(K)                                                                     \
+        {                                                                                  \
+            float e0 = 0.0f, e1 = 0.0f;                                                    \
+            store8(fl + K * 128, quant8_fast<false>(raw[K], row_bcast_f32<K>(my_s), e0, e1)); \
+            e[K] = e0 + e1;                                                                \
+            if constexpr (CRIT == kCritEq3) {                                              \
+                float f0 = 0.0f, f1 = 0.0f;                                                \
+                (void)quant8_fast<true>(raw[K], row_bcast_f32<K>(my_s5), f0, f1);          \
+                e5[K] = f0 + f1;                                                           \
+            }                                                                              \
+            __builtin_amdgcn_sched_barrier(0);                                             \
+        }
+        MOR_SUB_ONE(0) MOR_SUB_ONE(1) MOR_SUB_ONE(2) MOR_SUB_ONE(3) MOR_SUB_ONE(4) MOR_SUB_ONE(5) MOR_SUB_ONE(6) MOR_SUB_ONE(7)
+#undef MOR_SUB_ONE
+        rows_allsum<8>(e);
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (own == k) my_err = e[k];
+        if constexpr (CRIT == kCritEq3) {
+            rows_allsum<8>(e5);
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (own == k) my_err5 = e5[k];
+        }
+    }
+    if (my_abits >= kInfBits) { my_err = __builtin_inff(); my_err5 = my_err; }
+    uint32_t my_mask = 0u;
+    if constexpr (!DEFER) my_mask = (CRIT == kCritEq3) ? decide_eq3(my_err, my_err5) : decide_eq2(my_err, 128u - my_zero, th);
+    if (l < 8) {
+        const int64_t p = prow + l;
+        o.scale[p] = my_s;
+        o.amax[p] = __uint_as_float(my_abits << 16);
+        o.err_sum[p] = my_err;
+        o.nnz[p] = 128u - my_zero;
+        if constexpr (CRIT == kCritEq3) o.err5_sum[p] = my_err5;
+        if constexpr (!DEFER) o.mask[p] = (uint8_t)my_mask;
+    }
+    if constexpr (!DEFER) {
+        if (o.bf16) {
+            const unsigned long long want = __ballot(l < 8 && my_mask != 0u);
+            if (want) {
+                const uint32_t bits = (uint32_t)(want >> (lane & 48)) & 0xFFu;   // my row's eight blocks
+                uint16_t* __restrict__ bl = o.bf16 + off;
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if ((bits >> k) & 1u) store16(bl + k * 128, raw[k]);
+            }
+        }
+    }
+}
+
+// Dense operands (every leading dimension == cols): blocks are consecutive 256-byte runs.
+// Persistent waves stride over units of 32 blocks (8 KB of input) with two register sets: the loads of
+// the next unit are in flight while the current one is processed, so HBM latency overlaps the VALU work.
+template <int CRIT, bool DEFER>
+__global__ __launch_bounds__(256) void k_sub1x128_flat(const uint16_t* __restrict__ x, KOut o, int64_t n_units, float th) {
+    const int lane = threadIdx.x & 63, g = lane >> 4, l = lane & 15;
+    const int64_t W = (int64_t)gridDim.x * 4;
+    int64_t u = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (u >= n_units) return;
+    const uint16_t* __restrict__ xl = x + (g * 8) * 128 + l * 8;
+    u32x4 bufA[8], bufB[8];
+    auto load_unit = [&](u32x4 (&raw)[8], int64_t unit) {
+        const uint16_t* __restrict__ src = xl + unit * (32 * 128);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) raw[k] = load16(src + k * 128);
+    };
+    load_unit(bufA, u);
+    for (;;) {
+        const int64_t ub = u + W;
+        if (ub < n_units) load_unit(bufB, ub);
+        sub_unit_process<CRIT, DEFER>(bufA, x, o, u, lane, th);
+        if (ub >= n_units) break;
+        u = ub + W;
+        if (u < n_units) load_unit(bufA, u);
+        sub_unit_process<CRIT, DEFER>(bufB, x, o, ub, lane, th);
+        if (u >= n_units) break;
     }
 }
 
@@ -179,7 +334,7 @@ __global__ __launch_bounds__(256) void k_block128(const uint16_t* __restrict__ x
 // ======================================================================================
 constexpr int kTensorChunksPerThread = 8;                       // 16-byte chunks per thread in pass B
 constexpr int kTensorChunksPerBlock = 256 * kTensorChunksPerThread;
-constexpr int kMaxAmaxBlocks = 1024;
+constexpr int kMaxAmaxBlocks = 2048;
 
 __device__ __forceinline__ uint32_t block_allmax_u32(uint32_t v, uint32_t* sh4) {
     const uint32_t wv = wave_allmax_u32(v);
@@ -195,21 +350,26 @@ __device__ __forceinline__ uint32_t amax2_of(const u32x4& v, uint32_t a2) {
     return a2;
 }
 
-// Pass A, dense: grid-stride over 16-byte chunks, 8 loads in flight per lane.
+// Pass A, dense.
 __global__ __launch_bounds__(256) void k_tensor_amax_flat(const uint16_t* __restrict__ x, int64_t n_chunks,
                                                           uint32_t* __restrict__ part) {
     __shared__ uint32_t sh4[4];
     uint32_t a2 = 0u;
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    for (; c + 7 * stride < n_chunks; c += 8 * stride) {
-        u32x4 v[8];
+    // a workgroup reads tiles of 2048 consecutive chunks (32 KB): 8 x 16 B per lane in flight, 4 KB apart
+    const int64_t n_tiles = (n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
+    for (int64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const int64_t c0 = t * kTensorChunksPerBlock + threadIdx.x;
+        if (c0 + 7 * 256 < n_chunks) {
+            u32x4 v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = load16(x + (c + u * stride) * 8);
+            for (int u = 0; u < 8; ++u) v[u] = load16(x + (c0 + u * 256) * 8);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) a2 = amax2_of(v[u], a2);
+            for (int u = 0; u < 8; ++u) a2 = amax2_of(v[u], a2);
+        } else {
+            for (int u = 0; u < 8; ++u)
+                if (c0 + u * 256 < n_chunks) a2 = amax2_of(load16(x + (c0 + u * 256) * 8), a2);
+        }
     }
-    for (; c < n_chunks; c += stride) a2 = amax2_of(load16(x + c * 8), a2);
     const uint32_t a = block_allmax_u32(fold_max16(a2), sh4);
     if (threadIdx.x == 0) part[blockIdx.x] = a;
 }
@@ -694,6 +854,7 @@ size_t scope_workspace_bytes(int64_t) { return align16(3 * sizeof(double) * kSco
 static bool is_flat(const KShape& sh, const KOut& o) {
     return sh.ld == sh.cols && o.ld_fp8 == sh.cols && (o.bf16 == nullptr || o.ld_bf16 == sh.cols);
 }
+constexpr int64_t kSubFlatMaxBlocks = 1024;   // persistent: 256 CUs x 4 workgroups of 4 waves
 static int clamp_grid_y(int64_t v) { return (int)(v < 1 ? 1 : (v > 65535 ? 65535 : v)); }
 
 #define MOR_DISPATCH_CRIT_DEFER(KERNEL, ...)                                                     \
@@ -706,9 +867,22 @@ hipError_t launch_sub1x128(const uint16_t* x, const KShape& sh, const KOut& o, i
     const int64_t n_part = sh.rows * (sh.cols / 128);
     ProfScope ps(prof, kKernSub1x128, st);
     if (is_flat(sh, o)) {
-        const int64_t blocks = (n_part + 63) / 64;
-        if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
-        MOR_DISPATCH_CRIT_DEFER(k_sub1x128_flat, <<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, o, n_part, th));
+        // whole units (32 consecutive blocks) go to the flat kernel, the remaining blocks to the strided kernel
+        const int64_t n_units = n_part / 32, n_full = n_units * 32, n_tail = n_part - n_full;
+        int64_t blocks = (n_units + 3) / 4;
+        if (blocks > kSubFlatMaxBlocks) blocks = kSubFlatMaxBlocks;
+        if (blocks > 0) MOR_DISPATCH_CRIT_DEFER(k_sub1x128_flat, <<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, o, n_units, th));
+        if (n_tail > 0) {
+            KShape ts{n_tail, 128, 128};
+            KOut to = o;
+            to.fp8 += n_full * 128; to.ld_fp8 = 128;
+            if (to.bf16) to.bf16 += n_full * 128;
+            to.ld_bf16 = 128;
+            to.scale += n_full; to.amax += n_full; to.err_sum += n_full; to.nnz += n_full; to.mask += n_full;
+            if (to.err5_sum) to.err5_sum += n_full;
+            const dim3 grid(1u, (unsigned)clamp_grid_y((n_tail + 15) / 16));
+            MOR_DISPATCH_CRIT_DEFER(k_sub1x128_strided, <<<grid, dim3(256), 0, st>>>(x + n_full * 128, ts, to, th));
+        }
     } else {
         const dim3 grid((unsigned)(sh.cols / 128), (unsigned)clamp_grid_y((sh.rows + 15) / 16));
         MOR_DISPATCH_CRIT_DEFER(k_sub1x128_strided, <<<grid, dim3(256), 0, st>>>(x, sh, o, th));
