@@ -153,7 +153,8 @@ mor_status mor_analyze_quantize(const mor_params* params, const uint16_t* x, con
 typedef enum {
     MOR_KERNEL_SUB_1x128 = 1, MOR_KERNEL_BLOCK_128x128 = 2, MOR_KERNEL_TENSOR_AMAX = 3,
     MOR_KERNEL_TENSOR_QUANT = 4, MOR_KERNEL_TENSOR_FINALIZE = 5, MOR_KERNEL_FALLBACK_COPY = 6,
-    MOR_KERNEL_SCOPE_REDUCE = 7, MOR_KERNEL_SCOPE_DECIDE = 8, MOR_KERNEL_SCOPE_FILL_MASK = 9
+    MOR_KERNEL_SCOPE_REDUCE = 7, MOR_KERNEL_SCOPE_DECIDE = 8, MOR_KERNEL_SCOPE_FILL_MASK = 9,
+    MOR_KERNEL_STATS_PARTIAL = 10, MOR_KERNEL_STATS_FINAL = 11
 } mor_kernel_id;
 typedef struct mor_profile {
     int32_t capacity;
@@ -165,6 +166,32 @@ typedef struct mor_profile {
 mor_status mor_analyze_quantize_profiled(const mor_params* params, const uint16_t* x, const mor_outputs* out,
                                          void* workspace, size_t workspace_bytes, void* stream,
                                          mor_profile* profile);
+
+/*
+ * Many operands in one call.  MoR is applied to every GEMM operand of the four linear layers of each
+ * transformer block (Section 4): dozens of calls per layer, each worth only tens of microseconds of HBM
+ * time.  The batch entry point groups dense operands of equal granularity and criterion into single
+ * launches (descriptor tables travel in the kernel arguments), so launch overhead is paid per group,
+ * not per operand.  Results are identical to calling mor_analyze_quantize (and mor_select_stats when
+ * `stats` is set) operand by operand, in order, on the same stream.
+ *   items      host array; every pointer inside is device memory as for the single-operand calls;
+ *              `stats` (optional, device mor_stats*) receives the operand's selection statistics
+ *   near_tol   as for mor_select_stats
+ *   workspace  device scratch of mor_batch_workspace_bytes(items, n_items) bytes, 16-byte aligned
+ *   profile    optional measurement aid as in mor_analyze_quantize_profiled (NULL for none)
+ * n_items must be in [1, MOR_BATCH_MAX].  Operands must not overlap each other's outputs.
+ */
+#define MOR_BATCH_MAX 64
+typedef struct mor_batch_item {
+    mor_params      params;
+    const uint16_t* x;
+    mor_outputs     out;
+    mor_stats*      stats;
+} mor_batch_item;
+size_t     mor_batch_workspace_bytes(const mor_batch_item* items, int32_t n_items);
+mor_status mor_analyze_quantize_batch(const mor_batch_item* items, int32_t n_items, float near_tol,
+                                      void* workspace, size_t workspace_bytes, void* stream,
+                                      mor_profile* profile);
 
 /*
  * Inverse path (the de-quantize / de-scale half of the fake-quantization workflow, Section 4,

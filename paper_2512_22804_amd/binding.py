@@ -26,10 +26,13 @@ CRIT = {"mean_rel_err": MOR_CRIT_MEAN_REL_ERR, "e4m3_vs_e5m2": MOR_CRIT_E4M3_VS_
 SCOPE = {"partition": MOR_SCOPE_PARTITION, "tensor": MOR_SCOPE_TENSOR}
 
 EXPORTS = ("mor_num_partitions", "mor_workspace_bytes", "mor_analyze_quantize", "mor_analyze_quantize_profiled",
-           "mor_dequantize", "mor_select_stats", "mor_status_string")
+           "mor_batch_workspace_bytes", "mor_analyze_quantize_batch", "mor_dequantize", "mor_select_stats",
+           "mor_status_string")
+MOR_BATCH_MAX = 64
 
 KERNEL_NAMES = {1: "sub1x128", 2: "block128", 3: "tensor_amax", 4: "tensor_quant", 5: "tensor_finalize",
-                6: "fallback_copy", 7: "scope_reduce", 8: "scope_decide", 9: "scope_fill_mask"}
+                6: "fallback_copy", 7: "scope_reduce", 8: "scope_decide", 9: "scope_fill_mask",
+                10: "stats_partial", 11: "stats_final"}
 
 
 class MorParams(C.Structure):
@@ -54,6 +57,10 @@ class MorStats(C.Structure):
 class MorProfile(C.Structure):
     _fields_ = [("capacity", C.c_int32), ("count", C.c_int32), ("start", C.c_void_p * 8), ("stop", C.c_void_p * 8),
                 ("kernel", C.c_int32 * 8)]
+
+
+class MorBatchItem(C.Structure):
+    _fields_ = [("params", MorParams), ("x", C.c_void_p), ("out", MorOutputs), ("stats", C.c_void_p)]
 
 
 class MorError(RuntimeError):
@@ -83,6 +90,11 @@ def load():
         L.mor_analyze_quantize_profiled.argtypes = [C.POINTER(MorParams), C.c_void_p, C.POINTER(MorOutputs), C.c_void_p,
                                                     C.c_size_t, C.c_void_p, C.POINTER(MorProfile)]
         L.mor_analyze_quantize_profiled.restype = C.c_int
+        L.mor_batch_workspace_bytes.argtypes = [C.POINTER(MorBatchItem), C.c_int32]
+        L.mor_batch_workspace_bytes.restype = C.c_size_t
+        L.mor_analyze_quantize_batch.argtypes = [C.POINTER(MorBatchItem), C.c_int32, C.c_float, C.c_void_p, C.c_size_t,
+                                                 C.c_void_p, C.POINTER(MorProfile)]
+        L.mor_analyze_quantize_batch.restype = C.c_int
         L.mor_dequantize.argtypes = [C.POINTER(MorParams), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_int64, C.c_void_p, C.c_int64, C.c_void_p]
         L.mor_dequantize.restype = C.c_int
@@ -183,6 +195,31 @@ def mor_analyze_quantize_profiled(params: MorParams, x: torch.Tensor, out: MorRe
                                               ws.numel() if ws is not None else 0, _stream(), C.byref(profile))
     if rc != 0:
         raise MorError(rc, "mor_analyze_quantize_profiled")
+
+
+def make_batch(entries) -> "C.Array":
+    """entries: sequence of (params, x, out: MorResult, stats: torch.Tensor | None).  Returns the host item array."""
+    arr = (MorBatchItem * len(entries))()
+    for i, (params, x, out, stats) in enumerate(entries):
+        arr[i].params = params
+        arr[i].x = x.data_ptr()
+        arr[i].out = _outputs_struct(out)
+        arr[i].stats = stats.data_ptr() if stats is not None else None
+    return arr
+
+
+def mor_batch_workspace_bytes(items) -> int:
+    return int(load().mor_batch_workspace_bytes(items, len(items)))
+
+
+def mor_analyze_quantize_batch(items, near_tol: float, workspace: torch.Tensor | None, profile: MorProfile | None = None) -> None:
+    """Enqueue the analyse-select-quantize pass (and, where an item carries a stats buffer, its selection
+    statistics) of every operand in ``items`` (from :func:`make_batch`) on the current stream."""
+    rc = load().mor_analyze_quantize_batch(items, len(items), near_tol, _ptr(workspace),
+                                           workspace.numel() if workspace is not None else 0, _stream(),
+                                           C.byref(profile) if profile is not None else None)
+    if rc != 0:
+        raise MorError(rc, "mor_analyze_quantize_batch")
 
 
 class HipEvents:

@@ -37,15 +37,8 @@ int64_t mor_num_partitions(int32_t granularity, int64_t rows, int64_t cols) {
     }
 }
 
-size_t mor_workspace_bytes(const mor_params* p) {
-    if (check_common(p) != MOR_OK) return 0;
-    if (p->granularity == MOR_GRAN_TENSOR) return mor::plan_tensor(p->rows, p->cols).bytes;
-    if (p->scope == MOR_SCOPE_TENSOR) return mor::scope_workspace_bytes(mor_num_partitions(p->granularity, p->rows, p->cols));
-    return 0;
-}
-
-static mor_status analyze_quantize_impl(const mor_params* p, const uint16_t* x, const mor_outputs* out, void* workspace,
-                                        size_t workspace_bytes, void* stream, mor::KProf* prof) {
+// Validates one operand and converts it to the launcher's descriptor.
+static mor_status make_item(const mor_params* p, const uint16_t* x, const mor_outputs* out, mor_stats* stats, mor::BatchItem* item) {
     if (!p || !x || !out) return MOR_ERR_NULL;
     mor_status st = check_common(p);
     if (st != MOR_OK) return st;
@@ -58,50 +51,88 @@ static mor_status analyze_quantize_impl(const mor_params* p, const uint16_t* x, 
     if (p->ld < p->cols || out->ld_fp8 < p->cols) return MOR_ERR_SHAPE;
     const bool want_bf16 = out->bf16 != nullptr && out->bf16 != x;
     if (want_bf16 && out->ld_bf16 < p->cols) return MOR_ERR_SHAPE;
+    if (p->granularity == MOR_GRAN_BLOCK_128x128 && p->rows / 128 > 65535 && p->scope == MOR_SCOPE_TENSOR) return MOR_ERR_SHAPE;
     if (p->ld % 8 || out->ld_fp8 % 8 || (want_bf16 && out->ld_bf16 % 8)) return MOR_ERR_ALIGN;
     if (!aligned16(x) || (reinterpret_cast<uintptr_t>(out->fp8) & 7u) || (want_bf16 && !aligned16(out->bf16))) return MOR_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(out->scale) | reinterpret_cast<uintptr_t>(out->amax) |
          reinterpret_cast<uintptr_t>(out->err_sum) | reinterpret_cast<uintptr_t>(out->nnz)) & 3u) return MOR_ERR_ALIGN;
-    const size_t need = mor_workspace_bytes(p);
+    if (stats && (reinterpret_cast<uintptr_t>(stats) & 7u)) return MOR_ERR_ALIGN;
+    item->sh = mor::KShape{p->rows, p->cols, p->ld};
+    item->o = mor::KOut{out->fp8, out->ld_fp8, want_bf16 ? out->bf16 : nullptr, want_bf16 ? out->ld_bf16 : p->cols,
+                        out->scale, out->amax, out->err_sum, out->nnz, out->mask, out->err5_sum};
+    item->x = x;
+    item->gran = p->granularity;
+    item->crit = p->criterion;
+    item->scope = p->granularity == MOR_GRAN_TENSOR ? MOR_SCOPE_PARTITION : p->scope;
+    item->th = p->threshold;
+    item->stats = stats;
+    return MOR_OK;
+}
+
+size_t mor_workspace_bytes(const mor_params* p) {
+    if (check_common(p) != MOR_OK) return 0;
+    mor::BatchItem it{};
+    it.sh = mor::KShape{p->rows, p->cols, p->ld};
+    it.gran = p->granularity;
+    it.scope = p->granularity == MOR_GRAN_TENSOR ? MOR_SCOPE_PARTITION : p->scope;
+    it.o.ld_fp8 = p->cols;
+    return mor::batch_workspace_bytes(&it, 1);
+}
+
+static mor_status run_batch(const mor::BatchItem* items, int n, float near_tol, void* workspace, size_t workspace_bytes, void* stream,
+                            mor_profile* profile) {
+    const size_t need = mor::batch_workspace_bytes(items, n);
     if (need && (!workspace || workspace_bytes < need)) return MOR_ERR_WORKSPACE;
     if (need && !aligned16(workspace)) return MOR_ERR_ALIGN;
-
-    mor::KShape sh{p->rows, p->cols, p->ld};
-    mor::KOut ko{out->fp8, out->ld_fp8, want_bf16 ? out->bf16 : nullptr, want_bf16 ? out->ld_bf16 : p->cols,
-                 out->scale, out->amax, out->err_sum, out->nnz, out->mask, out->err5_sum};
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    const bool defer = p->scope == MOR_SCOPE_TENSOR;
-    hipError_t e;
-    switch (p->granularity) {
-    case MOR_GRAN_TENSOR:
-        e = mor::launch_tensor(x, sh, ko, p->criterion, p->threshold, workspace, hs, prof);
-        break;
-    case MOR_GRAN_SUB_1x128:
-        e = mor::launch_sub1x128(x, sh, ko, p->criterion, defer, p->threshold, hs, prof);
-        break;
-    default:
-        e = mor::launch_block128(x, sh, ko, p->criterion, defer, p->threshold, hs, prof);
-        break;
+    static_assert(sizeof(mor_profile) == sizeof(mor::KProf), "mor_profile layout");
+    if (profile) {
+        profile->count = 0;
+        for (int i = 0; i < profile->capacity && i < 8; ++i)
+            if (!profile->start[i] || !profile->stop[i]) return MOR_ERR_NULL;
     }
-    if (e == hipSuccess && defer && p->granularity != MOR_GRAN_TENSOR)
-        e = mor::launch_scope_finalize(x, sh, ko, mor_num_partitions(p->granularity, p->rows, p->cols), p->criterion,
-                                       p->threshold, workspace, hs, prof);
+    hipError_t e = mor::launch_batch(items, n, near_tol, workspace, workspace_bytes, static_cast<hipStream_t>(stream),
+                                     reinterpret_cast<mor::KProf*>(profile));
     return e == hipSuccess ? MOR_OK : MOR_ERR_HIP;
 }
 
 mor_status mor_analyze_quantize(const mor_params* p, const uint16_t* x, const mor_outputs* out, void* workspace,
                                 size_t workspace_bytes, void* stream) {
-    return analyze_quantize_impl(p, x, out, workspace, workspace_bytes, stream, nullptr);
+    mor::BatchItem it{};
+    mor_status st = make_item(p, x, out, nullptr, &it);
+    if (st != MOR_OK) return st;
+    return run_batch(&it, 1, 0.0f, workspace, workspace_bytes, stream, nullptr);
 }
 
 mor_status mor_analyze_quantize_profiled(const mor_params* p, const uint16_t* x, const mor_outputs* out, void* workspace,
                                          size_t workspace_bytes, void* stream, mor_profile* profile) {
-    static_assert(sizeof(mor_profile) == sizeof(mor::KProf), "mor_profile layout");
     if (!profile) return MOR_ERR_NULL;
-    profile->count = 0;
-    for (int i = 0; i < profile->capacity && i < 8; ++i)
-        if (!profile->start[i] || !profile->stop[i]) return MOR_ERR_NULL;
-    return analyze_quantize_impl(p, x, out, workspace, workspace_bytes, stream, reinterpret_cast<mor::KProf*>(profile));
+    mor::BatchItem it{};
+    mor_status st = make_item(p, x, out, nullptr, &it);
+    if (st != MOR_OK) return st;
+    return run_batch(&it, 1, 0.0f, workspace, workspace_bytes, stream, profile);
+}
+
+size_t mor_batch_workspace_bytes(const mor_batch_item* items, int32_t n_items) {
+    if (!items || n_items <= 0) return 0;
+    size_t total = 0;
+    for (int32_t i = 0; i < n_items; ++i) {
+        mor::BatchItem it{};
+        if (make_item(&items[i].params, items[i].x, &items[i].out, items[i].stats, &it) != MOR_OK) return 0;
+        total += mor::batch_workspace_bytes(&it, 1);
+    }
+    return total;
+}
+
+mor_status mor_analyze_quantize_batch(const mor_batch_item* items, int32_t n_items, float near_tol, void* workspace,
+                                      size_t workspace_bytes, void* stream, mor_profile* profile) {
+    if (!items) return MOR_ERR_NULL;
+    if (n_items <= 0 || n_items > MOR_BATCH_MAX) return MOR_ERR_SHAPE;
+    mor::BatchItem its[MOR_BATCH_MAX];
+    for (int32_t i = 0; i < n_items; ++i) {
+        mor_status st = make_item(&items[i].params, items[i].x, &items[i].out, items[i].stats, &its[i]);
+        if (st != MOR_OK) return st;
+    }
+    return run_batch(its, n_items, near_tol, workspace, workspace_bytes, stream, profile);
 }
 
 mor_status mor_dequantize(const mor_params* p, const uint8_t* fp8, int64_t ld_fp8, const float* scale, const uint8_t* mask,

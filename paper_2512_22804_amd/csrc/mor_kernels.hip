@@ -817,6 +817,385 @@ __global__ void k_stats_finish(int64_t n_part, unsigned long long elems_per_part
 }
 
 // ======================================================================================
+// Grouped kernels: one launch processes up to kMaxGroup dense operands of the same granularity and
+// criterion.  A training step quantizes many operands (four linear layers x {activation, weight,
+// gradient} per transformer block, Section 4), each worth only tens of microseconds of HBM time, so
+// per-launch overhead is paid once per group instead of once per operand.  The descriptor tables
+// travel in the kernel-argument segment: no staging copy, nothing allocated.
+// ======================================================================================
+constexpr int kMaxGroup = 16;
+
+struct GroupSub {
+    int n;
+    int64_t unit_end[kMaxGroup];          // running total of 32-block units
+    const uint16_t* x[kMaxGroup];
+    KOut o[kMaxGroup];
+    float th[kMaxGroup];
+};
+__device__ __forceinline__ int group_find(const int64_t* end, int n, int64_t v) {
+    int i = 0;
+    while (i + 1 < n && v >= end[i]) ++i;
+    return __builtin_amdgcn_readfirstlane(i);
+}
+template <int CRIT>
+__global__ __launch_bounds__(256) void k_sub1x128_group(GroupSub g) {
+    const int lane = threadIdx.x & 63, row = lane >> 4, l = lane & 15;
+    const int64_t W = (int64_t)gridDim.x * 4, total = g.unit_end[g.n - 1];
+    int64_t u = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (u >= total) return;
+    const int lane_off = (row * 8) * 128 + l * 8;
+    u32x4 bufA[8], bufB[8];
+    auto load_unit = [&](u32x4 (&raw)[8], int64_t unit, int& op, int64_t& local) {
+        op = group_find(g.unit_end, g.n, unit);
+        local = unit - (op ? g.unit_end[op - 1] : 0);
+        const uint16_t* __restrict__ src = g.x[op] + local * (32 * 128) + lane_off;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) raw[k] = load16(src + k * 128);
+    };
+    int opA, opB;
+    int64_t locA, locB;
+    load_unit(bufA, u, opA, locA);
+    for (;;) {
+        const int64_t ub = u + W;
+        if (ub < total) load_unit(bufB, ub, opB, locB);
+        sub_unit_process<CRIT, false>(bufA, g.x[opA], g.o[opA], locA, lane, g.th[opA]);
+        if (ub >= total) break;
+        u = ub + W;
+        if (u < total) load_unit(bufA, u, opA, locA);
+        sub_unit_process<CRIT, false>(bufB, g.x[opB], g.o[opB], locB, lane, g.th[opB]);
+        if (u >= total) break;
+    }
+}
+
+struct GroupBlock {
+    int n;
+    int64_t tile_end[kMaxGroup];          // running total of 128x128 tiles
+    int32_t tiles_x[kMaxGroup];
+    int64_t ld[kMaxGroup];
+    const uint16_t* x[kMaxGroup];
+    KOut o[kMaxGroup];
+    float th[kMaxGroup];
+};
+template <int CRIT>
+__global__ __launch_bounds__(256) void k_block128_group(GroupBlock g) {
+    __shared__ uint32_t sh_amax[4];
+    __shared__ float sh_err[4];
+    __shared__ float sh_err5[4];
+    __shared__ uint32_t sh_zero[4];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, l = lane & 15;
+    const int op = group_find(g.tile_end, g.n, blockIdx.x);
+    const int64_t p = (int64_t)blockIdx.x - (op ? g.tile_end[op - 1] : 0);
+    const int64_t tr = p / g.tiles_x[op], tc = p - tr * g.tiles_x[op];
+    const KOut& o = g.o[op];
+    const int64_t ld = g.ld[op];
+    const int64_t col = tc * 128 + l * 8;
+    const int64_t row0 = tr * 128 + w * 4 + (lane >> 4);
+    const uint16_t* __restrict__ src = g.x[op] + row0 * ld + col;
+    uint8_t* __restrict__ dst = o.fp8 + row0 * o.ld_fp8 + col;
+    u32x4 raw[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) raw[i] = load16(src + (int64_t)i * 16 * ld);
+    Scan8 sc{0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) scan8(raw[i], sc);
+    const uint32_t wa = wave_allmax_u32(fold_max16(sc.amax2));
+    if (lane == 0) sh_amax[w] = wa;
+    __syncthreads();
+    const uint32_t abits = max(max(sh_amax[0], sh_amax[1]), max(sh_amax[2], sh_amax[3]));
+    const float s = scale_from_amax_bits(abits, kE4M3Max);
+    float e, e5 = 0.0f;
+    if (abits < kFastAmaxBits) {
+        float e0 = 0.0f, e1 = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) store8(dst + (int64_t)i * 16 * o.ld_fp8, quant8_fast<false>(raw[i], s, e0, e1));
+        e = e0 + e1;
+        if constexpr (CRIT == kCritEq3) {
+            const float s5 = scale_from_amax_bits(abits, kE5M2Max);
+            float f0 = 0.0f, f1 = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) (void)quant8_fast<true>(raw[i], s5, f0, f1);
+            e5 = f0 + f1;
+        }
+    } else {
+        e = 0.0f;
+#pragma clang loop unroll(disable)
+        for (int i = 0; i < 8; ++i) {
+            e += quant8_careful_mem<false>(src + (int64_t)i * 16 * ld, s, dst + (int64_t)i * 16 * o.ld_fp8);
+            if constexpr (CRIT == kCritEq3)
+                e5 += quant8_careful_mem<true>(src + (int64_t)i * 16 * ld, scale_from_amax_bits(abits, kE5M2Max), nullptr);
+        }
+    }
+    const float werr = wave_allsum_f32(e);
+    const uint32_t wzero = wave_allsum_u32(fold_add16(sc.zero2));
+    float werr5 = 0.0f;
+    if constexpr (CRIT == kCritEq3) werr5 = wave_allsum_f32(e5);
+    if (lane == 0) { sh_err[w] = werr; sh_zero[w] = wzero; sh_err5[w] = werr5; }
+    __syncthreads();
+    float err = (sh_err[0] + sh_err[1]) + (sh_err[2] + sh_err[3]);
+    float err5 = (sh_err5[0] + sh_err5[1]) + (sh_err5[2] + sh_err5[3]);
+    const uint32_t nnz = 128u * 128u - ((sh_zero[0] + sh_zero[1]) + (sh_zero[2] + sh_zero[3]));
+    if (abits >= kInfBits) { err = __builtin_inff(); err5 = __builtin_inff(); }
+    const uint32_t mask = (CRIT == kCritEq3) ? decide_eq3(err, err5) : decide_eq2(err, nnz, g.th[op]);
+    if (threadIdx.x == 0) {
+        o.scale[p] = s;
+        o.amax[p] = __uint_as_float(abits << 16);
+        o.err_sum[p] = err;
+        o.nnz[p] = nnz;
+        if constexpr (CRIT == kCritEq3) o.err5_sum[p] = err5;
+        o.mask[p] = (uint8_t)mask;
+    }
+    if (mask && o.bf16) {
+        uint16_t* __restrict__ dbf = o.bf16 + row0 * o.ld_bf16 + col;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) store16(dbf + (int64_t)i * 16 * o.ld_bf16, raw[i]);
+    }
+}
+
+// Per-tensor operands of a group share three launches (amax, quantize, finish + fallback copy).
+struct TensorOp {
+    const uint16_t* x;
+    int64_t n_chunks, n_tiles;
+    KOut o;
+    float th;
+    int n_amax, n_slots;                 // workgroups this operand gets in pass A / pass B
+    uint32_t* amax_part;                 // [n_amax]
+    float* err; float* err5; uint32_t* zero;   // [n_slots] each
+    uint32_t* abits;                     // [1]
+    StatsDev* stats;                     // optional
+};
+struct GroupTensor {
+    int n;
+    int32_t amax_end[kMaxGroup], slot_end[kMaxGroup], copy_end[kMaxGroup];   // running workgroup totals per pass
+    float near_tol;
+    TensorOp op[kMaxGroup];
+};
+__device__ __forceinline__ int group_find32(const int32_t* end, int n, int v) {
+    int i = 0;
+    while (i + 1 < n && v >= end[i]) ++i;
+    return __builtin_amdgcn_readfirstlane(i);
+}
+__global__ __launch_bounds__(256) void k_tensor_amax_group(GroupTensor g) {
+    __shared__ uint32_t sh4[4];
+    const int op = group_find32(g.amax_end, g.n, blockIdx.x);
+    const TensorOp& t = g.op[op];
+    const int b = blockIdx.x - (op ? g.amax_end[op - 1] : 0);
+    uint32_t a2 = 0u;
+    for (int64_t tile = b; tile < t.n_tiles; tile += t.n_amax) {
+        const int64_t c0 = tile * kTensorChunksPerBlock + threadIdx.x;
+        if (c0 + 7 * 256 < t.n_chunks) {
+            u32x4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = load16(t.x + (c0 + u * 256) * 8);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a2 = amax2_of(v[u], a2);
+        } else {
+            for (int u = 0; u < 8; ++u)
+                if (c0 + u * 256 < t.n_chunks) a2 = amax2_of(load16(t.x + (c0 + u * 256) * 8), a2);
+        }
+    }
+    const uint32_t a = block_allmax_u32(fold_max16(a2), sh4);
+    if (threadIdx.x == 0) t.amax_part[b] = a;
+}
+template <int CRIT>
+__global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
+    __shared__ uint32_t sh4[4];
+    const int op = group_find32(g.slot_end, g.n, blockIdx.x);
+    const TensorOp& t = g.op[op];
+    const int b = blockIdx.x - (op ? g.slot_end[op - 1] : 0);
+    const uint16_t* __restrict__ x = t.x;
+    uint8_t* __restrict__ fp8 = t.o.fp8;
+    const int64_t n_chunks = t.n_chunks, n_tiles = t.n_tiles, G = t.n_slots;
+    u32x4 bufA[kTensorChunksPerThread], bufB[kTensorChunksPerThread];
+    auto load_tile = [&](u32x4* raw, int64_t tile) {
+        const int64_t c0 = tile * kTensorChunksPerBlock + threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < kTensorChunksPerThread; ++u) {
+            const int64_t c = c0 + u * 256;
+            if (c < n_chunks) raw[u] = load16(x + c * 8);
+            else { raw[u].x = 0u; raw[u].y = 0u; raw[u].z = 0u; raw[u].w = 0u; }
+        }
+    };
+    int64_t tl = b;
+    load_tile(bufA, tl);
+    const uint32_t abits = global_amax_bits(t.amax_part, t.n_amax, sh4);
+    if (b == 0 && threadIdx.x == 0) t.abits[0] = abits;
+    const float s = scale_from_amax_bits(abits, kE4M3Max);
+    const float s5 = (CRIT == kCritEq3) ? scale_from_amax_bits(abits, kE5M2Max) : 0.0f;
+    TensorAcc acc{0.0f, 0.0f, 0.0f, 0.0f, 0u};
+    auto process = [&](const u32x4* raw, int64_t tile) {
+        const int64_t c0 = tile * kTensorChunksPerBlock + threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < kTensorChunksPerThread; ++u) acc.zero2 = zero2_of(raw[u], acc.zero2);
+        if (abits < kFastAmaxBits) {
+#pragma unroll
+            for (int u = 0; u < kTensorChunksPerThread; ++u) {
+                const int64_t c = c0 + u * 256;
+                const u32x2 codes = quant8_fast<false>(raw[u], s, acc.e0, acc.e1);
+                if (c < n_chunks) store8(fp8 + c * 8, codes);
+                if constexpr (CRIT == kCritEq3) (void)quant8_fast<true>(raw[u], s5, acc.f0, acc.f1);
+            }
+        } else {
+#pragma clang loop unroll(disable)
+            for (int u = 0; u < kTensorChunksPerThread; ++u) {
+                const int64_t c = c0 + u * 256;
+                if (c < n_chunks) {
+                    acc.e0 += quant8_careful_mem<false>(x + c * 8, s, fp8 + c * 8);
+                    if constexpr (CRIT == kCritEq3) acc.f0 += quant8_careful_mem<true>(x + c * 8, s5, nullptr);
+                }
+            }
+        }
+    };
+    for (;;) {
+        const int64_t tb = tl + G;
+        if (tb < n_tiles) load_tile(bufB, tb);
+        process(bufA, tl);
+        if (tb >= n_tiles) break;
+        tl = tb + G;
+        if (tl < n_tiles) load_tile(bufA, tl);
+        process(bufB, tb);
+        if (tl >= n_tiles) break;
+    }
+    TensorPartials tp{t.err, t.err5, t.zero, t.abits};
+    tensor_publish<CRIT>(acc, tp, b);
+}
+template <int CRIT>
+__global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g) {
+    __shared__ double shd[4];
+    __shared__ unsigned long long shl[4];
+    const int op = group_find32(g.copy_end, g.n, blockIdx.x);
+    const TensorOp& t = g.op[op];
+    const int b = blockIdx.x - (op ? g.copy_end[op - 1] : 0);
+    const int nb = g.copy_end[op] - (op ? g.copy_end[op - 1] : 0);
+    double se = 0.0, se5 = 0.0;
+    unsigned long long sz = 0;
+    for (int i = threadIdx.x; i < t.n_slots; i += 256) {
+        se += (double)t.err[i];
+        sz += t.zero[i];
+        if constexpr (CRIT == kCritEq3) se5 += (double)t.err5[i];
+    }
+    se = block_sum_shfl<double>(se, shd);
+    sz = block_sum_shfl<unsigned long long>(sz, shl);
+    if constexpr (CRIT == kCritEq3) se5 = block_sum_shfl<double>(se5, shd);
+    const uint32_t abits = t.abits[0];
+    const unsigned long long n_padded = (unsigned long long)t.n_tiles * kTensorChunksPerBlock * 8;
+    const unsigned long long n = n_padded - sz;
+    if (abits >= kInfBits) { se = (double)__builtin_inff(); se5 = se; }
+    uint32_t mask;
+    if constexpr (CRIT == kCritEq3) mask = (se < se5) ? 0u : 1u;
+    else mask = ((n ? se / (double)n : 0.0) < (double)t.th) ? 0u : 1u;
+    if (b == 0 && threadIdx.x == 0) {
+        const KOut& o = t.o;
+        const float err_f = (float)se;
+        const uint32_t nnz32 = n > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)n;
+        o.scale[0] = scale_from_amax_bits(abits, kE4M3Max);
+        o.amax[0] = __uint_as_float(abits << 16);
+        o.err_sum[0] = err_f;
+        o.nnz[0] = nnz32;
+        if constexpr (CRIT == kCritEq3) o.err5_sum[0] = (float)se5;
+        o.mask[0] = (uint8_t)mask;
+        if (t.stats) {     // statistics of a one-block operand, same arithmetic as k_stats_single
+            StatsDev* st = t.stats;
+            const float metric = nnz32 ? err_f / (float)nnz32 : 0.0f;
+#pragma unroll
+            for (int k = 0; k < 12; ++k) st->hist[k] = 0u;
+            st->hist[stats_bin(metric)] = 1u;
+            const bool near = fabs((double)metric - (double)t.th) <= (double)g.near_tol * (double)t.th;
+            stats_finish(st, 1, (unsigned long long)t.n_chunks * 8ull, (double)err_f, nnz32, mask, near ? 1ull : 0ull);
+        }
+    }
+    if (mask == 0u || t.o.bf16 == nullptr) return;
+    const int64_t stride = (int64_t)nb * 256;
+    int64_t c = (int64_t)b * 256 + threadIdx.x;
+    const uint16_t* __restrict__ x = t.x;
+    uint16_t* __restrict__ dst = t.o.bf16;
+    for (; c + 3 * stride < t.n_chunks; c += 4 * stride) {
+        u32x4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = load16(x + (c + u * stride) * 8);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) store16(dst + (c + u * stride) * 8, v[u]);
+    }
+    for (; c < t.n_chunks; c += stride) store16(dst + c * 8, load16(x + c * 8));
+}
+
+// Statistics of sub-tensor operands of a group: pass 1 writes one partial record per workgroup into
+// the workspace, pass 2 (one workgroup per operand) combines them in a fixed order.
+struct StatsRec {      // 128 bytes
+    double e;
+    unsigned long long n, n_bf16, n_near;
+    uint32_t hist[12];
+    uint32_t pad[12];
+};
+struct StatsOp {
+    const float* err_sum; const uint32_t* nnz; const uint8_t* mask;
+    int64_t n_part; unsigned long long elems_per_part;
+    float th;
+    StatsRec* rec;          // [n_wg]
+    StatsDev* out;
+};
+struct GroupStats {
+    int n;
+    int32_t wg_end[kMaxGroup];
+    float near_tol;
+    StatsOp op[kMaxGroup];
+};
+__global__ __launch_bounds__(256) void k_stats_group_partial(GroupStats g) {
+    __shared__ uint32_t sh_hist[12];
+    __shared__ uint32_t sh_cnt[2];
+    __shared__ double shd[4];
+    __shared__ unsigned long long shl[4];
+    const int op = group_find32(g.wg_end, g.n, blockIdx.x);
+    const StatsOp& t = g.op[op];
+    const int b = blockIdx.x - (op ? g.wg_end[op - 1] : 0);
+    const int nb = g.wg_end[op] - (op ? g.wg_end[op - 1] : 0);
+    if (threadIdx.x < 12) sh_hist[threadIdx.x] = 0u;
+    if (threadIdx.x < 2) sh_cnt[threadIdx.x] = 0u;
+    __syncthreads();
+    StatsAcc a{0.0, 0ull, 0u, 0u};
+    uint32_t lh[12];
+#pragma unroll
+    for (int k = 0; k < 12; ++k) lh[k] = 0u;
+    for (int64_t p = (int64_t)b * 256 + threadIdx.x; p < t.n_part; p += (int64_t)nb * 256) {
+        const float es = t.err_sum[p];
+        const uint32_t nz = t.nnz[p];
+        const float metric = nz ? es / (float)nz : 0.0f;
+        const int bin = stats_bin(metric);
+#pragma unroll
+        for (int k = 0; k < 12; ++k) lh[k] += (bin == k) ? 1u : 0u;
+        a.e += (double)es;
+        a.n += nz;
+        a.n_bf16 += t.mask[p] ? 1u : 0u;
+        if (fabs((double)metric - (double)t.th) <= (double)g.near_tol * (double)t.th) a.n_near += 1u;
+    }
+#pragma unroll
+    for (int k = 0; k < 12; ++k)
+        if (lh[k]) atomicAdd(&sh_hist[k], lh[k]);
+    if (a.n_bf16) atomicAdd(&sh_cnt[0], a.n_bf16);
+    if (a.n_near) atomicAdd(&sh_cnt[1], a.n_near);
+    const double e = block_sum_shfl<double>(a.e, shd);
+    const unsigned long long n = block_sum_shfl<unsigned long long>(a.n, shl);
+    StatsRec* r = t.rec + b;
+    if (threadIdx.x < 12) r->hist[threadIdx.x] = sh_hist[threadIdx.x];
+    if (threadIdx.x == 0) { r->e = e; r->n = n; r->n_bf16 = sh_cnt[0]; r->n_near = sh_cnt[1]; }
+}
+__global__ __launch_bounds__(64) void k_stats_group_final(GroupStats g) {
+    const int op = blockIdx.x;
+    const StatsOp& t = g.op[op];
+    const int nb = g.wg_end[op] - (op ? g.wg_end[op - 1] : 0);
+    if (threadIdx.x < 12) {
+        uint32_t h = 0u;
+        for (int i = 0; i < nb; ++i) h += t.rec[i].hist[threadIdx.x];
+        t.out->hist[threadIdx.x] = h;
+    }
+    if (threadIdx.x == 0) {
+        double e = 0.0;
+        unsigned long long n = 0, nbf = 0, nn = 0;
+        for (int i = 0; i < nb; ++i) { e += t.rec[i].e; n += t.rec[i].n; nbf += t.rec[i].n_bf16; nn += t.rec[i].n_near; }
+        stats_finish(t.out, t.n_part, t.elems_per_part, e, n, nbf, nn);
+    }
+}
+
+// ======================================================================================
 // Launchers
 // ======================================================================================
 static inline size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
@@ -971,6 +1350,228 @@ hipError_t launch_scope_finalize(const uint16_t* x, const KShape& sh, const KOut
         if (flat) k_fallback_copy_flat<<<dim3(2048), dim3(256), 0, st>>>(x, o.bf16, sh.rows * sh.cols / 8, decision);
         else k_fallback_copy_strided<<<dim3((unsigned)(sh.rows < 4096 ? sh.rows : 4096)), dim3(256), 0, st>>>(x, sh, o.bf16, o.ld_bf16, decision);
     }
+    return hipGetLastError();
+}
+
+// ---- batches ---------------------------------------------------------------------------------
+namespace {
+enum { kGranTensor = 0, kGranSub = 1, kGranBlock = 2 };
+constexpr int kStatsMaxWg = 64;
+
+bool item_is_flat(const BatchItem& it) { return is_flat(it.sh, it.o); }
+bool item_grouped(const BatchItem& it) {
+    if (it.gran == kGranBlock) return it.scope == 0 && it.sh.cols / 128 <= 0x7FFFFFFF;
+    if (it.gran == kGranSub) return it.scope == 0 && item_is_flat(it);
+    return item_is_flat(it);     // per-tensor: the scope does not matter (one block)
+}
+int64_t item_parts(const BatchItem& it) {
+    if (it.gran == kGranSub) return it.sh.rows * (it.sh.cols / 128);
+    if (it.gran == kGranBlock) return (it.sh.rows / 128) * (it.sh.cols / 128);
+    return 1;
+}
+int64_t item_elems_per_part(const BatchItem& it) {
+    if (it.gran == kGranSub) return 128;
+    if (it.gran == kGranBlock) return 128 * 128;
+    return it.sh.rows * it.sh.cols;
+}
+int stats_wgs(int64_t n_part) {
+    int64_t w = (n_part + 2047) / 2048;
+    return (int)(w < 1 ? 1 : (w > kStatsMaxWg ? kStatsMaxWg : w));
+}
+size_t item_workspace(const BatchItem& it) {
+    size_t b = 0;
+    if (it.gran == kGranTensor) b += plan_tensor(it.sh.rows, it.sh.cols).bytes;
+    else if (it.scope == 1) b += scope_workspace_bytes(item_parts(it));
+    if (it.stats && it.gran != kGranTensor && item_grouped(it)) b += align16(sizeof(StatsRec) * kStatsMaxWg);
+    return b;
+}
+int share(int64_t mine, int64_t total, int budget, int64_t cap) {
+    int64_t v = total > 0 ? (mine * budget + total - 1) / total : 1;
+    if (v > cap) v = cap;
+    if (v > budget) v = budget;
+    return (int)(v < 1 ? 1 : v);
+}
+}  // namespace
+
+size_t batch_workspace_bytes(const BatchItem* items, int n) {
+    size_t b = 0;
+    for (int i = 0; i < n; ++i) b += item_workspace(items[i]);
+    return b;
+}
+
+hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws, size_t ws_bytes, hipStream_t st, KProf* prof) {
+    static_assert(sizeof(GroupSub) <= 3800 && sizeof(GroupBlock) <= 3800 && sizeof(GroupTensor) <= 3800 && sizeof(GroupStats) <= 3800,
+                  "kernel-argument segment is 4 KB");
+    static_assert(sizeof(StatsRec) == 128, "StatsRec layout");
+    char* wsp = static_cast<char*>(ws);
+    size_t ws_off = 0;
+    auto carve = [&](size_t bytes) -> char* { char* p = wsp + ws_off; ws_off += align16(bytes); return p; };
+    (void)ws_bytes;
+    hipError_t err = hipSuccess;
+
+    for (int crit = 0; crit < 2 && err == hipSuccess; ++crit) {
+        // ---- 1x128 sub-channel operands
+        {
+            GroupSub g; g.n = 0;
+            int64_t total = 0;
+            auto flush = [&]() {
+                if (g.n == 0) return;
+                int64_t blocks = (total + 3) / 4;
+                if (blocks > kSubFlatMaxBlocks) blocks = kSubFlatMaxBlocks;
+                ProfScope ps(prof, kKernSub1x128, st);
+                if (crit == kCritEq3) k_sub1x128_group<kCritEq3><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(g);
+                else k_sub1x128_group<kCritEq2><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(g);
+                g.n = 0; total = 0;
+            };
+            for (int i = 0; i < n; ++i) {
+                const BatchItem& it = items[i];
+                if (it.gran != kGranSub || it.crit != crit || !item_grouped(it)) continue;
+                const int64_t n_part = item_parts(it), n_units = n_part / 32, n_full = n_units * 32, n_tail = n_part - n_full;
+                if (n_units > 0) {
+                    total += n_units;
+                    g.unit_end[g.n] = total; g.x[g.n] = it.x; g.o[g.n] = it.o; g.th[g.n] = it.th;
+                    if (++g.n == kMaxGroup) flush();
+                }
+                if (n_tail > 0) {     // fewer than 32 blocks left: the strided kernel takes them
+                    KShape ts{n_tail, 128, 128};
+                    KOut to = it.o;
+                    to.fp8 += n_full * 128; to.ld_fp8 = 128;
+                    if (to.bf16) to.bf16 += n_full * 128;
+                    to.ld_bf16 = 128;
+                    to.scale += n_full; to.amax += n_full; to.err_sum += n_full; to.nnz += n_full; to.mask += n_full;
+                    if (to.err5_sum) to.err5_sum += n_full;
+                    const dim3 grid(1u, (unsigned)clamp_grid_y((n_tail + 15) / 16));
+                    if (crit == kCritEq3) k_sub1x128_strided<kCritEq3, false><<<grid, dim3(256), 0, st>>>(it.x + n_full * 128, ts, to, it.th);
+                    else k_sub1x128_strided<kCritEq2, false><<<grid, dim3(256), 0, st>>>(it.x + n_full * 128, ts, to, it.th);
+                }
+            }
+            flush();
+        }
+        // ---- 128x128 block operands
+        {
+            GroupBlock g; g.n = 0;
+            int64_t total = 0;
+            auto flush = [&]() {
+                if (g.n == 0) return;
+                ProfScope ps(prof, kKernBlock128, st);
+                if (crit == kCritEq3) k_block128_group<kCritEq3><<<dim3((unsigned)total), dim3(256), 0, st>>>(g);
+                else k_block128_group<kCritEq2><<<dim3((unsigned)total), dim3(256), 0, st>>>(g);
+                g.n = 0; total = 0;
+            };
+            for (int i = 0; i < n; ++i) {
+                const BatchItem& it = items[i];
+                if (it.gran != kGranBlock || it.crit != crit || !item_grouped(it)) continue;
+                const int64_t tiles = item_parts(it);
+                if (tiles > 0x7FFFFFFF) return hipErrorInvalidValue;
+                if (total + tiles > 0x7FFFFFFF) flush();
+                total += tiles;
+                g.tile_end[g.n] = total; g.tiles_x[g.n] = (int32_t)(it.sh.cols / 128); g.ld[g.n] = it.sh.ld;
+                g.x[g.n] = it.x; g.o[g.n] = it.o; g.th[g.n] = it.th;
+                if (++g.n == kMaxGroup) flush();
+            }
+            flush();
+        }
+        // ---- per-tensor operands: amax pass, quantize pass, finish (+ fallback copy) pass
+        {
+            int idx[kMaxGroup];
+            int cnt = 0;
+            auto flush = [&]() {
+                if (cnt == 0) return;
+                GroupTensor g; g.n = cnt; g.near_tol = near_tol;
+                int64_t total_tiles = 0;
+                for (int k = 0; k < cnt; ++k) {
+                    const BatchItem& it = items[idx[k]];
+                    const int64_t n_chunks = it.sh.rows * it.sh.cols / 8;
+                    total_tiles += (n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
+                }
+                int a_end = 0, s_end = 0, c_end = 0;
+                for (int k = 0; k < cnt; ++k) {
+                    const BatchItem& it = items[idx[k]];
+                    TensorOp& t = g.op[k];
+                    t.x = it.x; t.o = it.o; t.th = it.th;
+                    t.n_chunks = it.sh.rows * it.sh.cols / 8;
+                    t.n_tiles = (t.n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
+                    t.n_amax = share(t.n_tiles, total_tiles, kMaxAmaxBlocks, t.n_tiles);
+                    t.n_slots = share(t.n_tiles, total_tiles, kMaxQuantBlocks, t.n_tiles);
+                    const TensorPlan pl = plan_tensor(it.sh.rows, it.sh.cols);
+                    char* w = carve(pl.bytes);
+                    t.amax_part = reinterpret_cast<uint32_t*>(w + pl.off_amax_part);
+                    t.err = reinterpret_cast<float*>(w + pl.off_err_part);
+                    t.err5 = reinterpret_cast<float*>(w + pl.off_err5_part);
+                    t.zero = reinterpret_cast<uint32_t*>(w + pl.off_nnz_part);
+                    t.abits = reinterpret_cast<uint32_t*>(w + pl.off_decision);
+                    t.stats = static_cast<StatsDev*>(it.stats);
+                    a_end += t.n_amax; s_end += t.n_slots;
+                    c_end += it.o.bf16 ? share(t.n_tiles, total_tiles, 2048, 2048) : 1;
+                    g.amax_end[k] = a_end; g.slot_end[k] = s_end; g.copy_end[k] = c_end;
+                }
+                { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_group<<<dim3(a_end), dim3(256), 0, st>>>(g); }
+                {
+                    ProfScope ps(prof, kKernTensorQuant, st);
+                    if (crit == kCritEq3) k_tensor_quant_group<kCritEq3><<<dim3(s_end), dim3(256), 0, st>>>(g);
+                    else k_tensor_quant_group<kCritEq2><<<dim3(s_end), dim3(256), 0, st>>>(g);
+                }
+                {
+                    ProfScope ps(prof, kKernFallbackCopy, st);
+                    if (crit == kCritEq3) k_tensor_finish_group<kCritEq3><<<dim3(c_end), dim3(256), 0, st>>>(g);
+                    else k_tensor_finish_group<kCritEq2><<<dim3(c_end), dim3(256), 0, st>>>(g);
+                }
+                cnt = 0;
+            };
+            for (int i = 0; i < n; ++i) {
+                const BatchItem& it = items[i];
+                if (it.gran != kGranTensor || it.crit != crit || !item_grouped(it)) continue;
+                const int64_t n_tiles = (it.sh.rows * it.sh.cols / 8 + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
+                if (n_tiles > 2000ll * kMaxQuantBlocks) return hipErrorInvalidValue;   // 16-bit per-lane zero counters
+                idx[cnt] = i;
+                if (++cnt == kMaxGroup) flush();
+            }
+            flush();
+        }
+    }
+    // ---- operands the grouped kernels do not cover: padded leading dimensions, tensor-level decision over
+    //      sub-tensor scaling.  One operand at a time.
+    for (int i = 0; i < n && err == hipSuccess; ++i) {
+        const BatchItem& it = items[i];
+        if (item_grouped(it)) continue;
+        const bool defer = it.scope == 1;
+        if (it.gran == kGranTensor) {
+            err = launch_tensor(it.x, it.sh, it.o, it.crit, it.th, carve(plan_tensor(it.sh.rows, it.sh.cols).bytes), st, prof);
+        } else {
+            err = it.gran == kGranSub ? launch_sub1x128(it.x, it.sh, it.o, it.crit, defer, it.th, st, prof)
+                                      : launch_block128(it.x, it.sh, it.o, it.crit, defer, it.th, st, prof);
+            if (err == hipSuccess && defer)
+                err = launch_scope_finalize(it.x, it.sh, it.o, item_parts(it), it.crit, it.th, carve(scope_workspace_bytes(item_parts(it))), st, prof);
+        }
+        if (err == hipSuccess && it.stats)
+            err = launch_select_stats(item_parts(it), item_elems_per_part(it), it.o.err_sum, it.o.nnz, it.o.mask, it.th, near_tol, it.stats, st);
+    }
+    // ---- statistics of the grouped sub-tensor operands
+    {
+        GroupStats g; g.n = 0; g.near_tol = near_tol;
+        int wg_total = 0;
+        auto flush = [&]() {
+            if (g.n == 0) return;
+            { ProfScope ps(prof, kKernStatsPartial, st); k_stats_group_partial<<<dim3(wg_total), dim3(256), 0, st>>>(g); }
+            { ProfScope ps(prof, kKernStatsFinal, st); k_stats_group_final<<<dim3(g.n), dim3(64), 0, st>>>(g); }
+            g.n = 0; wg_total = 0;
+        };
+        for (int i = 0; i < n; ++i) {
+            const BatchItem& it = items[i];
+            if (!it.stats || it.gran == kGranTensor || !item_grouped(it)) continue;
+            StatsOp& t = g.op[g.n];
+            t.err_sum = it.o.err_sum; t.nnz = it.o.nnz; t.mask = it.o.mask;
+            t.n_part = item_parts(it); t.elems_per_part = (unsigned long long)item_elems_per_part(it);
+            t.th = it.th;
+            t.rec = reinterpret_cast<StatsRec*>(carve(sizeof(StatsRec) * kStatsMaxWg));
+            t.out = static_cast<StatsDev*>(it.stats);
+            wg_total += stats_wgs(t.n_part);
+            g.wg_end[g.n] = wg_total;
+            if (++g.n == kMaxGroup) flush();
+        }
+        flush();
+    }
+    if (err != hipSuccess) return err;
     return hipGetLastError();
 }
 

@@ -46,8 +46,21 @@ struct KProf {
 };
 enum KernelId {
     kKernSub1x128 = 1, kKernBlock128 = 2, kKernTensorAmax = 3, kKernTensorQuant = 4, kKernTensorFinalize = 5,
-    kKernFallbackCopy = 6, kKernScopeReduce = 7, kKernScopeDecide = 8, kKernScopeFillMask = 9
+    kKernFallbackCopy = 6, kKernScopeReduce = 7, kKernScopeDecide = 8, kKernScopeFillMask = 9,
+    kKernStatsPartial = 10, kKernStatsFinal = 11
 };
+
+// One operand of a batch (validated by the caller).
+struct BatchItem {
+    KShape sh;
+    KOut o;
+    const uint16_t* x;
+    int gran, crit, scope;
+    float th;
+    void* stats;            // device mor_stats* or nullptr
+};
+size_t batch_workspace_bytes(const BatchItem* items, int n);
+hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws, size_t ws_bytes, hipStream_t st, KProf* prof);
 
 hipError_t launch_sub1x128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st, KProf* prof);
 hipError_t launch_block128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st, KProf* prof);

@@ -1,0 +1,104 @@
+"""The batch entry point must give exactly what operand-by-operand calls give (which the parity tests
+check against the oracle), for every mix of granularity, criterion, scope and layout."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_22804_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TH = 0.045
+
+
+def build_cases():
+    g1 = W.gradient(256, 512, 11, tiny_half=True)
+    cases = [
+        ("act-sub", W.activation(200, 1024, 1), "sub1x128", "partition", "mean_rel_err", None),          # 1600 blocks: ragged tail unit
+        ("grad-sub", g1, "sub1x128", "partition", "mean_rel_err", None),
+        ("grad-sub-eq3", g1, "sub1x128", "partition", "e4m3_vs_e5m2", None),
+        ("w-block", W.weight(384, 512, 3), "block128", "partition", "mean_rel_err", None),
+        ("grad-block", W.gradient(256, 768, 4), "block128", "partition", "mean_rel_err", None),
+        ("grad-block-eq3", g1, "block128", "partition", "e4m3_vs_e5m2", None),
+        ("w-tensor", W.weight(300, 520, 5), "tensor", "partition", "mean_rel_err", None),
+        ("grad-tensor", W.gradient(256, 1024, 6), "tensor", "partition", "mean_rel_err", None),
+        ("grad-tensor-eq3", g1, "tensor", "partition", "e4m3_vs_e5m2", None),
+        ("tiny-tensor", W.activation(1, 8, 7), "tensor", "partition", "mean_rel_err", None),
+        ("sub-tensor-scope", g1, "sub1x128", "tensor", "mean_rel_err", None),
+        ("block-tensor-scope", g1, "block128", "tensor", "e4m3_vs_e5m2", None),
+        ("strided-sub", W.gradient(128, 640, 8, tiny_half=True), "sub1x128", "partition", "mean_rel_err", 512),
+        ("strided-block", W.gradient(128, 640, 9, tiny_half=True), "block128", "partition", "mean_rel_err", 512),
+        ("strided-tensor", W.gradient(128, 640, 10), "tensor", "partition", "mean_rel_err", 512),
+        ("patterns-sub", np.random.default_rng(1).permutation(np.arange(65536, dtype=np.uint32).astype(np.uint16)).reshape(512, 128),
+         "sub1x128", "partition", "mean_rel_err", None),
+    ]
+    return cases
+
+
+def test_batch_equals_single_calls(oracle):
+    import parity
+    from paper_2512_22804_amd import binding as B
+    cases = build_cases()
+    dev = torch.device("cuda:0")
+    entries, singles, keep = [], [], []
+    for name, xb, gran, scope, crit, cols in cases:
+        rows, ld = xb.shape
+        cols = ld if cols is None else cols
+        params = B.make_params(rows, cols, gran, scope, crit, TH, ld=ld)
+        x = parity.to_dev(xb)
+        out_b = B.alloc_outputs(params, dev, bf16_fill=parity.FILL)
+        out_s = B.alloc_outputs(params, dev, bf16_fill=parity.FILL)
+        st_b = torch.full((128,), 0xEE, dtype=torch.uint8, device=dev)
+        st_s = torch.full((128,), 0xEE, dtype=torch.uint8, device=dev)
+        entries.append((params, x, out_b, st_b))
+        singles.append((params, x, out_s, st_s))
+        keep.append((name, xb, gran, scope, crit, cols))
+    items = B.make_batch(entries)
+    nbytes = B.mor_batch_workspace_bytes(items)
+    assert nbytes > 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    for _ in range(2):                      # twice: the workspace is reusable without re-initialisation
+        B.mor_analyze_quantize_batch(items, 1e-2, ws)
+    for params, x, out, st in singles:
+        B.mor_analyze_quantize(params, x, out)
+        B.mor_select_stats(params, out.err_sum, out.nnz, out.mask, 1e-2, st)
+    torch.cuda.synchronize()
+    for (name, xb, gran, scope, crit, cols), (_, _, ob, sb), (_, _, os_, ss) in zip(keep, entries, singles):
+        for f in ("fp8", "bf16", "scale", "amax", "nnz", "mask", "err_sum", "err5_sum"):
+            a, b = getattr(ob, f), getattr(os_, f)
+            if a is None:
+                continue
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), (name, f)
+        got, want = B.read_stats(sb), B.read_stats(ss)
+        for k in want:
+            if k in ("err_sum_total", "mean_err"):
+                assert got[k] == pytest.approx(want[k], rel=1e-12) or (np.isinf(got[k]) and np.isinf(want[k])), (name, k)
+            else:
+                assert got[k] == want[k], (name, k, got[k], want[k])
+        # and the statistics agree with the oracle's on the oracle's own per-block outputs
+        a = oracle.analyze_quantize(xb, gran, scope, crit, TH, ld=xb.shape[1], cols=cols)
+        if np.array_equal(a.mask, ob.mask.cpu().numpy()):
+            ref = oracle.select_stats(ob.err_sum.cpu().numpy(), a.nnz, a.mask, xb.shape[0], cols, gran, TH, 1e-2)
+            for k in ("n_part", "n_fp8_part", "n_bf16_part", "n_elem_fp8", "n_elem_bf16", "nnz_total", "hist", "n_near_threshold"):
+                assert got[k] == ref[k], (name, k)
+
+
+def test_batch_argument_errors():
+    import parity
+    from paper_2512_22804_amd import binding as B
+    xb = W.activation(128, 256, 1)
+    x = parity.to_dev(xb)
+    params = B.make_params(128, 256, "tensor")
+    out = B.alloc_outputs(params, x.device)
+    items = B.make_batch([(params, x, out, None)])
+    with pytest.raises(B.MorError) as e:
+        B.mor_analyze_quantize_batch(items, 1e-5, None)
+    assert e.value.status == 5                                   # workspace missing
+    bad = B.make_batch([(B.make_params(128, 200, "sub1x128"), x, out, None)])
+    assert B.mor_batch_workspace_bytes(bad) == 0
+    with pytest.raises(B.MorError) as e:
+        B.mor_analyze_quantize_batch(bad, 1e-5, None)
+    assert e.value.status == 2
+    torch.cuda.synchronize()
