@@ -2,9 +2,10 @@
 """Benchmark of the MoR analyse-select-quantize hot path on one MI355X.
 
 A "step" is one pass of the whole path over the operand sweep of one Llama-style layer
-(hidden 4096, ffn 14336, 8192 tokens): for each of the 12 operands one ``mor_analyze_quantize``
-call (activation 1x128, weights 128x128, gradients per-tensor; Eq. 2, th = 4.5 %) followed by one
-``mor_select_stats`` call, all on one stream, inputs already resident in HBM.
+(hidden 4096, ffn 14336, 8192 tokens): the 12 operands (activation 1x128, weights 128x128, gradients
+per-tensor; Eq. 2, th = 4.5 %) go through ONE ``mor_analyze_quantize_batch`` call that also produces
+each operand's selection statistics, on one stream, inputs already resident in HBM.  With
+``--per-operand`` the same work is issued as 12 ``mor_analyze_quantize`` + 12 ``mor_select_stats`` calls.
 
 Prints ONE JSON line on stdout: whole-job throughput in GB/s of BF16 input, the roofline record
 of the dominant kernel (timed live with HIP events recorded by the library around each kernel),
@@ -43,7 +44,13 @@ def algorithmic_bytes(kernel: str, n_elem: int, n_part: int, fallback_frac: floa
         return 2.0 * n_elem + n_elem
     if kernel == "fallback_copy":
         return 4.0 * n_elem * fallback_frac
+    if kernel in ("stats_partial",):
+        return 9.0 * n_part
     return 0.0
+
+
+KERNEL_GRAN = {"sub1x128": "sub1x128", "block128": "block128", "tensor_amax": "tensor", "tensor_quant": "tensor",
+               "fallback_copy": "tensor"}
 
 
 def main() -> int:
@@ -53,6 +60,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--row-div", type=int, default=1, help="divide every operand's rows (debug only; 1 = full workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-operand", action="store_true", help="one analyze + one stats call per operand instead of one batch call")
     ap.add_argument("--cpu-sample-div", type=int, default=1, help="oracle is timed on the first rows/N rows of every operand")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -83,9 +91,15 @@ def main() -> int:
         ops.append({"name": name, "gran": gran, "params": params, "x": x, "out": out, "stats": stats, "n": rows * cols,
                     "P": B.mor_num_partitions(gran, rows, cols), "host": xb})
     n_total = sum(o["n"] for o in ops)
+    items = B.make_batch([(o["params"], o["x"], o["out"], o["stats"]) for o in ops])
+    ws_bytes = B.mor_batch_workspace_bytes(items)
+    batch_ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
     def step(profiles=None):
+        if not args.per_operand:
+            B.mor_analyze_quantize_batch(items, 1e-5, batch_ws, profiles[0] if profiles is not None else None)
+            return
         for i, o in enumerate(ops):
             if profiles is None:
                 B.mor_analyze_quantize(o["params"], o["x"], o["out"])
@@ -131,7 +145,16 @@ def main() -> int:
                 rec = per_kernel.setdefault(kname, {"ms": 0.0, "launches": 0, "bytes": 0.0})
                 rec["ms"] += ms
                 rec["launches"] += 1
-                rec["bytes"] += algorithmic_bytes(kname, o["n"], o["P"], o["fallback_frac"])
+                if args.per_operand:
+                    rec["bytes"] += algorithmic_bytes(kname, o["n"], o["P"], o["fallback_frac"])
+                else:      # a grouped launch covers every operand of that granularity
+                    for q in ops:
+                        if kname.startswith("stats"):
+                            rec["bytes"] += algorithmic_bytes(kname, q["n"], q["P"], 0.0) if q["gran"] != "tensor" else 0.0
+                        elif KERNEL_GRAN.get(kname) == q["gran"]:
+                            rec["bytes"] += algorithmic_bytes(kname, q["n"], q["P"], q["fallback_frac"])
+            if not args.per_operand:
+                break
     ev.destroy()
     for k, r in sorted(per_kernel.items(), key=lambda kv: -kv[1]["ms"]):
         gbs = r["bytes"] / (r["ms"] * 1e-3) / 1e9 if r["ms"] > 0 else 0.0
@@ -189,7 +212,8 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "cfg5: operand sweep of one Llama-style 8B layer (X 8192x4096 1x128; W_qkv 6144x4096, W_o 4096x4096, "
                                "W_gate/W_up 14336x4096, W_down 4096x14336 128x128; six same-shape gradients per-tensor); "
-                               "Eq.2 th=4.5%; analyze_quantize + select_stats per operand, one stream",
+                               "Eq.2 th=4.5%; " + ("analyze_quantize + select_stats per operand" if args.per_operand else
+                                                 "one analyze_quantize_batch call incl. statistics") + ", one stream",
                    "elements_per_step": n_total, "row_div": args.row_div, "criterion": "mean_rel_err", "threshold": THRESHOLD},
         "hbm_algorithmic_gbs": round(step_gbs, 1), "hbm_frac_of_peak": round(step_gbs / HBM_PEAK_GBS, 4),
         "fp8_selected_pct": {"by_elements": round(100.0 * fp8_elems / n_total, 3), "by_blocks": round(100.0 * fp8_parts / tot_parts, 3),

@@ -1104,18 +1104,23 @@ __global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g) {
         }
     }
     if (mask == 0u || t.o.bf16 == nullptr) return;
-    const int64_t stride = (int64_t)nb * 256;
-    int64_t c = (int64_t)b * 256 + threadIdx.x;
+    // copy in tiles of 1024 consecutive chunks (16 KB): four 16-byte loads in flight per lane
     const uint16_t* __restrict__ x = t.x;
     uint16_t* __restrict__ dst = t.o.bf16;
-    for (; c + 3 * stride < t.n_chunks; c += 4 * stride) {
-        u32x4 v[4];
+    const int64_t n_ctiles = (t.n_chunks + 1023) / 1024;
+    for (int64_t ct = b; ct < n_ctiles; ct += nb) {
+        const int64_t c0 = ct * 1024 + threadIdx.x;
+        if (c0 + 3 * 256 < t.n_chunks) {
+            u32x4 v[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = load16(x + (c + u * stride) * 8);
+            for (int u = 0; u < 4; ++u) v[u] = load16(x + (c0 + u * 256) * 8);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) store16(dst + (c + u * stride) * 8, v[u]);
+            for (int u = 0; u < 4; ++u) store16(dst + (c0 + u * 256) * 8, v[u]);
+        } else {
+            for (int u = 0; u < 4; ++u)
+                if (c0 + u * 256 < t.n_chunks) store16(dst + (c0 + u * 256) * 8, load16(x + (c0 + u * 256) * 8));
+        }
     }
-    for (; c < t.n_chunks; c += stride) store16(dst + c * 8, load16(x + c * 8));
 }
 
 // Statistics of sub-tensor operands of a group: pass 1 writes one partial record per workgroup into
@@ -1178,21 +1183,30 @@ __global__ __launch_bounds__(256) void k_stats_group_partial(GroupStats g) {
     if (threadIdx.x < 12) r->hist[threadIdx.x] = sh_hist[threadIdx.x];
     if (threadIdx.x == 0) { r->e = e; r->n = n; r->n_bf16 = sh_cnt[0]; r->n_near = sh_cnt[1]; }
 }
-__global__ __launch_bounds__(64) void k_stats_group_final(GroupStats g) {
+__global__ __launch_bounds__(256) void k_stats_group_final(GroupStats g) {
+    __shared__ uint32_t sh_hist[12];
+    __shared__ double shd[4];
+    __shared__ unsigned long long shl[4];
     const int op = blockIdx.x;
     const StatsOp& t = g.op[op];
-    const int nb = g.wg_end[op] - (op ? g.wg_end[op - 1] : 0);
-    if (threadIdx.x < 12) {
-        uint32_t h = 0u;
-        for (int i = 0; i < nb; ++i) h += t.rec[i].hist[threadIdx.x];
-        t.out->hist[threadIdx.x] = h;
+    const int nb = g.wg_end[op] - (op ? g.wg_end[op - 1] : 0);       // <= 256: one record per thread
+    if (threadIdx.x < 12) sh_hist[threadIdx.x] = 0u;
+    __syncthreads();
+    double e = 0.0;
+    unsigned long long n = 0, nbf = 0, nn = 0;
+    if ((int)threadIdx.x < nb) {
+        const StatsRec& r = t.rec[threadIdx.x];
+        e = r.e; n = r.n; nbf = r.n_bf16; nn = r.n_near;
+#pragma unroll
+        for (int k = 0; k < 12; ++k)
+            if (r.hist[k]) atomicAdd(&sh_hist[k], r.hist[k]);
     }
-    if (threadIdx.x == 0) {
-        double e = 0.0;
-        unsigned long long n = 0, nbf = 0, nn = 0;
-        for (int i = 0; i < nb; ++i) { e += t.rec[i].e; n += t.rec[i].n; nbf += t.rec[i].n_bf16; nn += t.rec[i].n_near; }
-        stats_finish(t.out, t.n_part, t.elems_per_part, e, n, nbf, nn);
-    }
+    e = block_sum_shfl<double>(e, shd);          // fixed order: deterministic
+    n = block_sum_shfl<unsigned long long>(n, shl);
+    nbf = block_sum_shfl<unsigned long long>(nbf, shl);
+    nn = block_sum_shfl<unsigned long long>(nn, shl);
+    if (threadIdx.x < 12) t.out->hist[threadIdx.x] = sh_hist[threadIdx.x];
+    if (threadIdx.x == 0) stats_finish(t.out, t.n_part, t.elems_per_part, e, n, nbf, nn);
 }
 
 // ======================================================================================
@@ -1356,7 +1370,7 @@ hipError_t launch_scope_finalize(const uint16_t* x, const KShape& sh, const KOut
 // ---- batches ---------------------------------------------------------------------------------
 namespace {
 enum { kGranTensor = 0, kGranSub = 1, kGranBlock = 2 };
-constexpr int kStatsMaxWg = 64;
+constexpr int kStatsMaxWg = 256;
 
 bool item_is_flat(const BatchItem& it) { return is_flat(it.sh, it.o); }
 bool item_grouped(const BatchItem& it) {
@@ -1375,7 +1389,7 @@ int64_t item_elems_per_part(const BatchItem& it) {
     return it.sh.rows * it.sh.cols;
 }
 int stats_wgs(int64_t n_part) {
-    int64_t w = (n_part + 2047) / 2048;
+    int64_t w = (n_part + 1023) / 1024;
     return (int)(w < 1 ? 1 : (w > kStatsMaxWg ? kStatsMaxWg : w));
 }
 size_t item_workspace(const BatchItem& it) {
@@ -1553,7 +1567,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
         auto flush = [&]() {
             if (g.n == 0) return;
             { ProfScope ps(prof, kKernStatsPartial, st); k_stats_group_partial<<<dim3(wg_total), dim3(256), 0, st>>>(g); }
-            { ProfScope ps(prof, kKernStatsFinal, st); k_stats_group_final<<<dim3(g.n), dim3(64), 0, st>>>(g); }
+            { ProfScope ps(prof, kKernStatsFinal, st); k_stats_group_final<<<dim3(g.n), dim3(256), 0, st>>>(g); }
             g.n = 0; wg_total = 0;
         };
         for (int i = 0; i < n; ++i) {
