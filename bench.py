@@ -34,16 +34,18 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(kernel: str, n_elem: int, n_part: int, fallback_frac: float) -> float:
-    """Bytes the method must move for one launch of `kernel` over an operand of n_elem elements."""
+def algorithmic_bytes(kernel: str, n_elem: int, n_part: int, fallback_frac: float, fused: bool = False) -> float:
+    """Bytes the method must move for one launch of `kernel` over an operand of n_elem elements.  `fused`: the
+    per-tensor quantize pass also wrote the BF16 fallback (its decision was proven by the amax pass), so the
+    copy pass moved nothing."""
     if kernel in ("sub1x128", "block128"):
         return 2.0 * n_elem + n_elem + 2.0 * fallback_frac * n_elem + META_BYTES * n_part
     if kernel == "tensor_amax":
         return 2.0 * n_elem
     if kernel == "tensor_quant":
-        return 2.0 * n_elem + n_elem
+        return 2.0 * n_elem + n_elem + (2.0 * n_elem if fused else 0.0)
     if kernel == "fallback_copy":
-        return 4.0 * n_elem * fallback_frac
+        return 0.0 if fused else 4.0 * n_elem * fallback_frac
     if kernel in ("stats_partial",):
         return 9.0 * n_part
     return 0.0
@@ -119,7 +121,11 @@ def main() -> int:
     value = 2.0 * n_total / (elapsed / args.steps) / 1e9
     log(f"[bench] {args.steps} steps, {ms_per_step:.3f} ms/step, {value:.1f} GB/s of BF16 input")
 
-    # selection result (after the timed region)
+    # selection result (after the timed region).  The batch call also reports, per operand, whether the quantize pass
+    # wrote the fallback itself; in --per-operand mode one untimed batch call supplies that flag.
+    if args.per_operand:
+        B.mor_analyze_quantize_batch(items, 1e-5, batch_ws, None)
+        torch.cuda.synchronize()
     stats = [B.read_stats(o["stats"]) for o in ops]
     fp8_elems = sum(s["n_elem_fp8"] for s in stats)
     fp8_parts = sum(s["n_fp8_part"] for s in stats)
@@ -128,6 +134,7 @@ def main() -> int:
     near = sum(s["n_near_threshold"] for s in stats)
     for o, s in zip(ops, stats):
         o["fallback_frac"] = s["n_elem_bf16"] / float(s["n_elem_fp8"] + s["n_elem_bf16"])
+        o["fused_fallback"] = bool(s["flags"] & B.MOR_STATS_FLAG_FUSED_FALLBACK)
         log(f"[bench]   {o['name']:8s} {o['gran']:9s} {o['params'].rows}x{o['params'].cols} mean_err={s['mean_err']:.5f} "
             f"bf16_blocks={s['n_bf16_part']}/{s['n_part']}")
 
@@ -146,13 +153,13 @@ def main() -> int:
                 rec["ms"] += ms
                 rec["launches"] += 1
                 if args.per_operand:
-                    rec["bytes"] += algorithmic_bytes(kname, o["n"], o["P"], o["fallback_frac"])
+                    rec["bytes"] += algorithmic_bytes(kname, o["n"], o["P"], o["fallback_frac"], o["fused_fallback"])
                 else:      # a grouped launch covers every operand of that granularity
                     for q in ops:
                         if kname.startswith("stats"):
                             rec["bytes"] += algorithmic_bytes(kname, q["n"], q["P"], 0.0) if q["gran"] != "tensor" else 0.0
                         elif KERNEL_GRAN.get(kname) == q["gran"]:
-                            rec["bytes"] += algorithmic_bytes(kname, q["n"], q["P"], q["fallback_frac"])
+                            rec["bytes"] += algorithmic_bytes(kname, q["n"], q["P"], q["fallback_frac"], q["fused_fallback"])
             if not args.per_operand:
                 break
     ev.destroy()
@@ -182,7 +189,8 @@ def main() -> int:
     step_bytes = 0.0
     for o in ops:
         if o["gran"] == "tensor":
-            step_bytes += sum(algorithmic_bytes(k, o["n"], 1, o["fallback_frac"]) for k in ("tensor_amax", "tensor_quant", "fallback_copy"))
+            step_bytes += sum(algorithmic_bytes(k, o["n"], 1, o["fallback_frac"], o["fused_fallback"])
+                              for k in ("tensor_amax", "tensor_quant", "fallback_copy"))
         else:
             step_bytes += algorithmic_bytes(o["gran"], o["n"], o["P"], o["fallback_frac"])
     step_gbs = step_bytes / (elapsed / args.steps) / 1e9

@@ -121,8 +121,13 @@ typedef struct mor_stats {
     double   mean_err;          /* err_sum_total / nnz_total (0 when nnz_total == 0) */
     uint32_t hist[12];          /* block metrics err_sum/nnz (binary32) in bins [0,0.5%), [0.5%,1%),
                                    ..., [5%,5.5%), [5.5%, inf] */
-    uint32_t reserved;          /* used internally as a completion counter; reads back 0 */
+    uint32_t flags;             /* MOR_STATS_FLAG_* bits; 0 from mor_select_stats */
 } mor_stats;
+/* Set by mor_analyze_quantize_batch for a per-tensor operand whose BF16 decision was already proven
+ * by the amax pass (enough elements certain to flush to zero), so that the fallback payload was
+ * written by the quantize pass and the separate copy pass was skipped.  Informational only: the
+ * outputs do not depend on it. */
+#define MOR_STATS_FLAG_FUSED_FALLBACK 1u
 
 /* Number of blocks for a shape, or -1 if the shape is invalid for the granularity. */
 int64_t mor_num_partitions(int32_t granularity, int64_t rows, int64_t cols);

@@ -29,6 +29,7 @@ EXPORTS = ("mor_num_partitions", "mor_workspace_bytes", "mor_analyze_quantize", 
            "mor_batch_workspace_bytes", "mor_analyze_quantize_batch", "mor_dequantize", "mor_select_stats",
            "mor_status_string")
 MOR_BATCH_MAX = 64
+MOR_STATS_FLAG_FUSED_FALLBACK = 1
 
 KERNEL_NAMES = {1: "sub1x128", 2: "block128", 3: "tensor_amax", 4: "tensor_quant", 5: "tensor_finalize",
                 6: "fallback_copy", 7: "scope_reduce", 8: "scope_decide", 9: "scope_fill_mask",
@@ -51,7 +52,7 @@ class MorStats(C.Structure):
     _fields_ = [("n_part", C.c_uint64), ("n_fp8_part", C.c_uint64), ("n_bf16_part", C.c_uint64),
                 ("n_elem_fp8", C.c_uint64), ("n_elem_bf16", C.c_uint64), ("nnz_total", C.c_uint64),
                 ("n_near_threshold", C.c_uint64), ("err_sum_total", C.c_double), ("mean_err", C.c_double),
-                ("hist", C.c_uint32 * 12), ("reserved", C.c_uint32)]
+                ("hist", C.c_uint32 * 12), ("flags", C.c_uint32)]
 
 
 class MorProfile(C.Structure):

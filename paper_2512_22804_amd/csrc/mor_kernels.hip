@@ -961,6 +961,8 @@ struct TensorOp {
     uint32_t* amax_part;                 // [n_amax]
     float* err; float* err5; uint32_t* zero;   // [n_slots] each
     uint32_t* abits;                     // [1]
+    uint32_t* flush_part;                // [n_amax] lower bounds on the number of elements certain to flush to zero
+    unsigned long long flush_need;       // that many certain flushes prove the BF16 decision (0 = proof not attempted)
     StatsDev* stats;                     // optional
 };
 struct GroupTensor {
@@ -974,12 +976,21 @@ __device__ __forceinline__ int group_find32(const int32_t* end, int n, int v) {
     while (i + 1 < n && v >= end[i]) ++i;
     return __builtin_amdgcn_readfirstlane(i);
 }
+// Pass A also gathers a PROOF of the BF16 decision where one exists.  Section 4.1.3 observes that a
+// per-tensor scale falls back as soon as ~2.4 % of the values flush to zero; each flushed non-zero
+// element contributes exactly 1 to the error sum of Eq. (1)-(2), so "flushed >= th * N" already implies
+// "mean relative error >= th".  An element certainly flushes when |x| < amax * 2^-20 (then
+// |x * 448/amax| < 2^-11, below half of E4M3's smallest subnormal); with the lane's RUNNING amax in
+// place of the final one the test only becomes stricter, so the count is a lower bound.  When the
+// bound reaches flush_need, pass B writes the BF16 fallback in the same sweep and the separate copy
+// pass (2 more bytes read per element) is skipped.  The outputs are the same either way.
 __global__ __launch_bounds__(256) void k_tensor_amax_group(GroupTensor g) {
     __shared__ uint32_t sh4[4];
     const int op = group_find32(g.amax_end, g.n, blockIdx.x);
     const TensorOp& t = g.op[op];
     const int b = blockIdx.x - (op ? g.amax_end[op - 1] : 0);
-    uint32_t a2 = 0u;
+    const bool prove = t.flush_need != 0ull;
+    uint32_t a2 = 0u, keep2 = 0u, seen = 0u;      // keep2: per half-word count of elements NOT certain to flush
     for (int64_t tile = b; tile < t.n_tiles; tile += t.n_amax) {
         const int64_t c0 = tile * kTensorChunksPerBlock + threadIdx.x;
         if (c0 + 7 * 256 < t.n_chunks) {
@@ -988,6 +999,19 @@ __global__ __launch_bounds__(256) void k_tensor_amax_group(GroupTensor g) {
             for (int u = 0; u < 8; ++u) v[u] = load16(t.x + (c0 + u * 256) * 8);
 #pragma unroll
             for (int u = 0; u < 8; ++u) a2 = amax2_of(v[u], a2);
+            if (prove) {
+                // t = running amax with 20 taken off the exponent (0 if that underflows); 1 <= m < t  <=>  m-1 < t-1
+                const uint32_t t2 = pk_sub_sat_u16(a2, 0x0A000A00u);
+                const uint32_t tm1 = pk_sub_sat_u16(t2, 0x00010001u);
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t mm1 = pk_sub_u16(v[u][j] & 0x7FFF7FFFu, 0x00010001u);     // wraps to 0xFFFF for zeros
+                        keep2 = pk_add_u16(keep2, pk_is_zero_u16(pk_sub_sat_u16(tm1, mm1)));
+                    }
+                seen += 64u;
+            }
         } else {
             for (int u = 0; u < 8; ++u)
                 if (c0 + u * 256 < t.n_chunks) a2 = amax2_of(load16(t.x + (c0 + u * 256) * 8), a2);
@@ -995,6 +1019,21 @@ __global__ __launch_bounds__(256) void k_tensor_amax_group(GroupTensor g) {
     }
     const uint32_t a = block_allmax_u32(fold_max16(a2), sh4);
     if (threadIdx.x == 0) t.amax_part[b] = a;
+    if (prove) {
+        const uint32_t wf = wave_allsum_u32(seen - fold_add16(keep2));
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) sh4[threadIdx.x >> 6] = wf;
+        __syncthreads();
+        if (threadIdx.x == 0) t.flush_part[b] = (sh4[0] + sh4[1]) + (sh4[2] + sh4[3]);
+    }
+}
+// Sum of the certain-flush lower bounds of an operand; same value in every workgroup that calls it.
+__device__ __forceinline__ bool tensor_fallback_proven(const TensorOp& t, unsigned long long* shl) {
+    if (t.flush_need == 0ull) return false;
+    unsigned long long f = 0;
+    for (int i = threadIdx.x; i < t.n_amax; i += 256) f += t.flush_part[i];
+    f = block_sum_shfl<unsigned long long>(f, shl);
+    return f >= t.flush_need;
 }
 template <int CRIT>
 __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
@@ -1017,7 +1056,10 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
     };
     int64_t tl = b;
     load_tile(bufA, tl);
+    __shared__ unsigned long long shl4[4];
     const uint32_t abits = global_amax_bits(t.amax_part, t.n_amax, sh4);
+    const bool proven = tensor_fallback_proven(t, shl4);     // then the BF16 fallback is written in this sweep
+    uint16_t* __restrict__ bf16 = t.o.bf16;
     if (b == 0 && threadIdx.x == 0) t.abits[0] = abits;
     const float s = scale_from_amax_bits(abits, kE4M3Max);
     const float s5 = (CRIT == kCritEq3) ? scale_from_amax_bits(abits, kE5M2Max) : 0.0f;
@@ -1026,6 +1068,13 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
         const int64_t c0 = tile * kTensorChunksPerBlock + threadIdx.x;
 #pragma unroll
         for (int u = 0; u < kTensorChunksPerThread; ++u) acc.zero2 = zero2_of(raw[u], acc.zero2);
+        if (proven) {
+#pragma unroll
+            for (int u = 0; u < kTensorChunksPerThread; ++u) {
+                const int64_t c = c0 + u * 256;
+                if (c < n_chunks) store16(bf16 + c * 8, raw[u]);
+            }
+        }
         if (abits < kFastAmaxBits) {
 #pragma unroll
             for (int u = 0; u < kTensorChunksPerThread; ++u) {
@@ -1083,6 +1132,7 @@ __global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g) {
     uint32_t mask;
     if constexpr (CRIT == kCritEq3) mask = (se < se5) ? 0u : 1u;
     else mask = ((n ? se / (double)n : 0.0) < (double)t.th) ? 0u : 1u;
+    const bool proven = tensor_fallback_proven(t, shl);       // pass B already wrote the fallback
     if (b == 0 && threadIdx.x == 0) {
         const KOut& o = t.o;
         const float err_f = (float)se;
@@ -1101,9 +1151,10 @@ __global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g) {
             st->hist[stats_bin(metric)] = 1u;
             const bool near = fabs((double)metric - (double)t.th) <= (double)g.near_tol * (double)t.th;
             stats_finish(st, 1, (unsigned long long)t.n_chunks * 8ull, (double)err_f, nnz32, mask, near ? 1ull : 0ull);
+            st->reserved = proven ? 1u : 0u;
         }
     }
-    if (mask == 0u || t.o.bf16 == nullptr) return;
+    if (proven || mask == 0u || t.o.bf16 == nullptr) return;
     // copy in tiles of 1024 consecutive chunks (16 KB): four 16-byte loads in flight per lane
     const uint16_t* __restrict__ x = t.x;
     uint16_t* __restrict__ dst = t.o.bf16;
@@ -1237,6 +1288,7 @@ TensorPlan plan_tensor(int64_t, int64_t) {
     pl.off_err5_part = off; off = align16(off + sizeof(float) * (size_t)pl.quant_blocks);
     pl.off_nnz_part = off;  off = align16(off + sizeof(uint32_t) * (size_t)pl.quant_blocks);   // zero counts
     pl.off_decision = off;  off = align16(off + 16);                                           // [0] global amax bits
+    pl.off_flush_part = off; off = align16(off + sizeof(uint32_t) * (size_t)pl.amax_blocks);   // certain-flush lower bounds
     pl.bytes = off;
     return pl;
 }
@@ -1514,6 +1566,10 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                     t.err5 = reinterpret_cast<float*>(w + pl.off_err5_part);
                     t.zero = reinterpret_cast<uint32_t*>(w + pl.off_nnz_part);
                     t.abits = reinterpret_cast<uint32_t*>(w + pl.off_decision);
+                    t.flush_part = reinterpret_cast<uint32_t*>(w + pl.off_flush_part);
+                    t.flush_need = 0ull;
+                    if (crit == kCritEq2 && it.o.bf16 && it.th > 0.0f && it.th < 0.9f)      // 1 % margin over th * N covers the
+                        t.flush_need = (unsigned long long)(1.01 * (double)it.th * (double)(it.sh.rows * it.sh.cols)) + 1ull;   // binary32 sums
                     t.stats = static_cast<StatsDev*>(it.stats);
                     a_end += t.n_amax; s_end += t.n_slots;
                     c_end += it.o.bf16 ? share(t.n_tiles, total_tiles, 2048, 2048) : 1;

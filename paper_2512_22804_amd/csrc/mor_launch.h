@@ -30,7 +30,8 @@ struct TensorPlan {
     size_t  off_err_part;    // float[quant_blocks]
     size_t  off_err5_part;   // float[quant_blocks]
     size_t  off_nnz_part;    // uint32[quant_blocks]
-    size_t  off_decision;    // uint32[4]: decision for the conditional fallback copy
+    size_t  off_decision;    // uint32[4]: [0] global amax bits
+    size_t  off_flush_part;  // uint32[amax_blocks]
     size_t  bytes;
 };
 TensorPlan plan_tensor(int64_t rows, int64_t cols);

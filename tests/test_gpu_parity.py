@@ -255,7 +255,7 @@ def test_select_stats_parity(P, oracle, gran, shape):
     got = B.read_stats(out)
     for k in ("n_part", "n_fp8_part", "n_bf16_part", "n_elem_fp8", "n_elem_bf16", "nnz_total", "n_near_threshold", "hist"):
         assert got[k] == want[k], (k, got[k], want[k])
-    assert got["reserved"] == 0
+    assert got["flags"] == 0
     assert got["err_sum_total"] == pytest.approx(want["err_sum_total"], rel=1e-12)
     assert got["mean_err"] == pytest.approx(want["mean_err"], rel=1e-12)
 
@@ -300,3 +300,24 @@ def test_full_cfg4(P):
     xb = W.cfg4(rows=2048, tiny_half=True)[0][1]
     r = P.compare(xb, "sub1x128", threshold=TH, label="cfg4b")
     assert 0 < r["n_bf16"] < r["P"]
+
+
+@pytest.mark.parametrize("frac", [0.0, 0.02, 0.03, 0.042, 0.0455, 0.047, 0.06, 0.2, 1.0])
+def test_per_tensor_fallback_with_and_without_proof(P, frac):
+    """Per-tensor operands whose flushed fraction sweeps across the threshold: below it the error of the
+    surviving values decides, just above it the decision is BF16 without the flush-count proof, well above
+    it the proof triggers and the fallback is written by the quantize pass.  All must match the oracle."""
+    rng = np.random.default_rng(int(frac * 1e4) + 1)
+    rows, cols = 768, 1024
+    x = np.exp2(rng.uniform(-3.0, 3.0, size=(rows, cols))).astype(np.float32) * (rng.integers(0, 2, size=(rows, cols)) * 2 - 1)
+    x[0, 0] = 8.0                                                  # exact values inside the range: error 0 for them
+    x = np.where(rng.random((rows, cols)) < 0.5, np.round(x * 4) / 4, x).astype(np.float32)
+    tiny = rng.random((rows, cols)) < frac
+    x[tiny] = np.float32(2.0 ** -40) * (1 + rng.random(int(tiny.sum())).astype(np.float32))
+    x[rng.random((rows, cols)) < 0.03] = 0.0
+    xb = W.f32_to_bf16_bits(x)
+    r = P.compare(xb, "tensor", threshold=TH, label=f"flush-{frac}")
+    if 0.06 <= frac < 1.0:                       # at 1.0 every value is tiny, so nothing flushes
+        assert r["n_bf16"] == 1
+    P.compare(xb, "tensor", crit="e4m3_vs_e5m2", label=f"flush-{frac}-eq3")
+    P.compare(xb, "tensor", threshold=0.5, label=f"flush-{frac}-th0.5")
