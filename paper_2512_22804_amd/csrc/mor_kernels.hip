@@ -397,7 +397,16 @@ struct TensorPartials {   // one slot per pass-B workgroup (at most kMaxQuantBlo
     uint32_t* zero;        // zero elements seen by the workgroup (padding chunks count as zeros)
     uint32_t* abits;       // [0] = global amax bits, published by workgroup 0 of pass B
 };
-constexpr int kMaxQuantBlocks = 1024;
+#ifndef MOR_TQ_SLOTS
+#define MOR_TQ_SLOTS 16384
+#endif
+#ifndef MOR_TQ_DOUBLE
+#define MOR_TQ_DOUBLE 0
+#endif
+#ifndef MOR_TQ_SB
+#define MOR_TQ_SB 0
+#endif
+constexpr int kMaxQuantBlocks = MOR_TQ_SLOTS;
 
 template <typename T>
 __device__ __forceinline__ T block_sum_256(T v, T* sh) {
@@ -824,6 +833,9 @@ __global__ void k_stats_finish(int64_t n_part, unsigned long long elems_per_part
 // travel in the kernel-argument segment: no staging copy, nothing allocated.
 // ======================================================================================
 constexpr int kMaxGroup = 16;
+#ifndef MOR_SUB_DOUBLE
+#define MOR_SUB_DOUBLE 0
+#endif
 
 struct GroupSub {
     int n;
@@ -844,7 +856,10 @@ __global__ __launch_bounds__(256) void k_sub1x128_group(GroupSub g) {
     int64_t u = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (u >= total) return;
     const int lane_off = (row * 8) * 128 + l * 8;
-    u32x4 bufA[8], bufB[8];
+    u32x4 bufA[8];
+#if MOR_SUB_DOUBLE
+    u32x4 bufB[8];
+#endif
     auto load_unit = [&](u32x4 (&raw)[8], int64_t unit, int& op, int64_t& local) {
         op = group_find(g.unit_end, g.n, unit);
         local = unit - (op ? g.unit_end[op - 1] : 0);
@@ -852,9 +867,19 @@ __global__ __launch_bounds__(256) void k_sub1x128_group(GroupSub g) {
 #pragma unroll
         for (int k = 0; k < 8; ++k) raw[k] = load16(src + k * 128);
     };
-    int opA, opB;
-    int64_t locA, locB;
+    int opA;
+    int64_t locA;
     load_unit(bufA, u, opA, locA);
+#if !MOR_SUB_DOUBLE
+    for (;;) {
+        sub_unit_process<CRIT, false>(bufA, g.x[opA], g.o[opA], locA, lane, g.th[opA]);
+        u += W;
+        if (u >= total) break;
+        load_unit(bufA, u, opA, locA);
+    }
+#else
+    int opB;
+    int64_t locB;
     for (;;) {
         const int64_t ub = u + W;
         if (ub < total) load_unit(bufB, ub, opB, locB);
@@ -865,6 +890,7 @@ __global__ __launch_bounds__(256) void k_sub1x128_group(GroupSub g) {
         sub_unit_process<CRIT, false>(bufB, g.x[opB], g.o[opB], locB, lane, g.th[opB]);
         if (u >= total) break;
     }
+#endif
 }
 
 struct GroupBlock {
@@ -1044,7 +1070,10 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
     const uint16_t* __restrict__ x = t.x;
     uint8_t* __restrict__ fp8 = t.o.fp8;
     const int64_t n_chunks = t.n_chunks, n_tiles = t.n_tiles, G = t.n_slots;
-    u32x4 bufA[kTensorChunksPerThread], bufB[kTensorChunksPerThread];
+    u32x4 bufA[kTensorChunksPerThread];
+#if MOR_TQ_DOUBLE
+    u32x4 bufB[kTensorChunksPerThread];
+#endif
     auto load_tile = [&](u32x4* raw, int64_t tile) {
         const int64_t c0 = tile * kTensorChunksPerBlock + threadIdx.x;
 #pragma unroll
@@ -1082,6 +1111,9 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
                 const u32x2 codes = quant8_fast<false>(raw[u], s, acc.e0, acc.e1);
                 if (c < n_chunks) store8(fp8 + c * 8, codes);
                 if constexpr (CRIT == kCritEq3) (void)quant8_fast<true>(raw[u], s5, acc.f0, acc.f1);
+#if MOR_TQ_SB
+                __builtin_amdgcn_sched_barrier(0);
+#endif
             }
         } else {
 #pragma clang loop unroll(disable)
@@ -1094,6 +1126,7 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
             }
         }
     };
+#if MOR_TQ_DOUBLE
     for (;;) {
         const int64_t tb = tl + G;
         if (tb < n_tiles) load_tile(bufB, tb);
@@ -1104,6 +1137,14 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
         process(bufB, tb);
         if (tl >= n_tiles) break;
     }
+#else
+    for (;;) {
+        process(bufA, tl);
+        tl += G;
+        if (tl >= n_tiles) break;
+        load_tile(bufA, tl);
+    }
+#endif
     TensorPartials tp{t.err, t.err5, t.zero, t.abits};
     tensor_publish<CRIT>(acc, tp, b);
 }
@@ -1299,7 +1340,10 @@ size_t scope_workspace_bytes(int64_t) { return align16(3 * sizeof(double) * kSco
 static bool is_flat(const KShape& sh, const KOut& o) {
     return sh.ld == sh.cols && o.ld_fp8 == sh.cols && (o.bf16 == nullptr || o.ld_bf16 == sh.cols);
 }
-constexpr int64_t kSubFlatMaxBlocks = 1024;   // persistent: 256 CUs x 4 workgroups of 4 waves
+#ifndef MOR_SUB_BLOCKS
+#define MOR_SUB_BLOCKS 1024
+#endif
+constexpr int64_t kSubFlatMaxBlocks = MOR_SUB_BLOCKS;   // workgroups of 4 waves; each wave strides over 8 KB units
 static int clamp_grid_y(int64_t v) { return (int)(v < 1 ? 1 : (v > 65535 ? 65535 : v)); }
 
 #define MOR_DISPATCH_CRIT_DEFER(KERNEL, ...)                                                     \
