@@ -1236,69 +1236,81 @@ struct GroupStats {
     float near_tol;
     StatsOp op[kMaxGroup];
 };
+// Block-wide sums of 14 small counters (12 histogram bins, BF16 blocks, near-threshold blocks) without
+// same-address atomics: DPP wave sums, one LDS row per wave, then 14 lanes add the four rows.
+__device__ __forceinline__ void block_counts_14(const uint32_t (&v)[14], uint32_t (*sh)[14]) {
+    const int w = threadIdx.x >> 6;
+#pragma unroll
+    for (int k = 0; k < 14; ++k) {
+        const uint32_t s = wave_allsum_u32(v[k]);
+        if ((threadIdx.x & 63) == 0) sh[w][k] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x < 14) sh[0][threadIdx.x] = (sh[0][threadIdx.x] + sh[1][threadIdx.x]) + (sh[2][threadIdx.x] + sh[3][threadIdx.x]);
+    __syncthreads();
+}
 __global__ __launch_bounds__(256) void k_stats_group_partial(GroupStats g) {
-    __shared__ uint32_t sh_hist[12];
-    __shared__ uint32_t sh_cnt[2];
+    __shared__ uint32_t sh_cnt[4][14];
     __shared__ double shd[4];
     __shared__ unsigned long long shl[4];
     const int op = group_find32(g.wg_end, g.n, blockIdx.x);
     const StatsOp& t = g.op[op];
     const int b = blockIdx.x - (op ? g.wg_end[op - 1] : 0);
     const int nb = g.wg_end[op] - (op ? g.wg_end[op - 1] : 0);
-    if (threadIdx.x < 12) sh_hist[threadIdx.x] = 0u;
-    if (threadIdx.x < 2) sh_cnt[threadIdx.x] = 0u;
-    __syncthreads();
-    StatsAcc a{0.0, 0ull, 0u, 0u};
-    uint32_t lh[12];
+    double e = 0.0;
+    unsigned long long n = 0;
+    uint32_t cnt[14];
 #pragma unroll
-    for (int k = 0; k < 12; ++k) lh[k] = 0u;
+    for (int k = 0; k < 14; ++k) cnt[k] = 0u;
     for (int64_t p = (int64_t)b * 256 + threadIdx.x; p < t.n_part; p += (int64_t)nb * 256) {
         const float es = t.err_sum[p];
         const uint32_t nz = t.nnz[p];
         const float metric = nz ? es / (float)nz : 0.0f;
         const int bin = stats_bin(metric);
 #pragma unroll
-        for (int k = 0; k < 12; ++k) lh[k] += (bin == k) ? 1u : 0u;
-        a.e += (double)es;
-        a.n += nz;
-        a.n_bf16 += t.mask[p] ? 1u : 0u;
-        if (fabs((double)metric - (double)t.th) <= (double)g.near_tol * (double)t.th) a.n_near += 1u;
+        for (int k = 0; k < 12; ++k) cnt[k] += (bin == k) ? 1u : 0u;
+        e += (double)es;
+        n += nz;
+        cnt[12] += t.mask[p] ? 1u : 0u;
+        cnt[13] += (fabs((double)metric - (double)t.th) <= (double)g.near_tol * (double)t.th) ? 1u : 0u;
     }
-#pragma unroll
-    for (int k = 0; k < 12; ++k)
-        if (lh[k]) atomicAdd(&sh_hist[k], lh[k]);
-    if (a.n_bf16) atomicAdd(&sh_cnt[0], a.n_bf16);
-    if (a.n_near) atomicAdd(&sh_cnt[1], a.n_near);
-    const double e = block_sum_shfl<double>(a.e, shd);
-    const unsigned long long n = block_sum_shfl<unsigned long long>(a.n, shl);
+    block_counts_14(cnt, sh_cnt);
+    e = block_sum_shfl<double>(e, shd);
+    n = block_sum_shfl<unsigned long long>(n, shl);
+    if (nb == 1) {      // the whole operand in one workgroup: write the result, no second pass needed
+        if (threadIdx.x < 12) t.out->hist[threadIdx.x] = sh_cnt[0][threadIdx.x];
+        if (threadIdx.x == 0) stats_finish(t.out, t.n_part, t.elems_per_part, e, n, sh_cnt[0][12], sh_cnt[0][13]);
+        return;
+    }
     StatsRec* r = t.rec + b;
-    if (threadIdx.x < 12) r->hist[threadIdx.x] = sh_hist[threadIdx.x];
-    if (threadIdx.x == 0) { r->e = e; r->n = n; r->n_bf16 = sh_cnt[0]; r->n_near = sh_cnt[1]; }
+    if (threadIdx.x < 12) r->hist[threadIdx.x] = sh_cnt[0][threadIdx.x];
+    if (threadIdx.x == 0) { r->e = e; r->n = n; r->n_bf16 = sh_cnt[0][12]; r->n_near = sh_cnt[0][13]; }
 }
 __global__ __launch_bounds__(256) void k_stats_group_final(GroupStats g) {
-    __shared__ uint32_t sh_hist[12];
+    __shared__ uint32_t sh_cnt[4][14];
     __shared__ double shd[4];
     __shared__ unsigned long long shl[4];
     const int op = blockIdx.x;
     const StatsOp& t = g.op[op];
     const int nb = g.wg_end[op] - (op ? g.wg_end[op - 1] : 0);       // <= 256: one record per thread
-    if (threadIdx.x < 12) sh_hist[threadIdx.x] = 0u;
-    __syncthreads();
+    if (nb == 1) return;                                             // already final
     double e = 0.0;
-    unsigned long long n = 0, nbf = 0, nn = 0;
+    unsigned long long n = 0;
+    uint32_t cnt[14];
+#pragma unroll
+    for (int k = 0; k < 14; ++k) cnt[k] = 0u;
     if ((int)threadIdx.x < nb) {
         const StatsRec& r = t.rec[threadIdx.x];
-        e = r.e; n = r.n; nbf = r.n_bf16; nn = r.n_near;
+        e = r.e; n = r.n;
+        cnt[12] = (uint32_t)r.n_bf16; cnt[13] = (uint32_t)r.n_near;  // per-workgroup counts fit 32 bits
 #pragma unroll
-        for (int k = 0; k < 12; ++k)
-            if (r.hist[k]) atomicAdd(&sh_hist[k], r.hist[k]);
+        for (int k = 0; k < 12; ++k) cnt[k] = r.hist[k];
     }
+    block_counts_14(cnt, sh_cnt);
     e = block_sum_shfl<double>(e, shd);          // fixed order: deterministic
     n = block_sum_shfl<unsigned long long>(n, shl);
-    nbf = block_sum_shfl<unsigned long long>(nbf, shl);
-    nn = block_sum_shfl<unsigned long long>(nn, shl);
-    if (threadIdx.x < 12) t.out->hist[threadIdx.x] = sh_hist[threadIdx.x];
-    if (threadIdx.x == 0) stats_finish(t.out, t.n_part, t.elems_per_part, e, n, nbf, nn);
+    if (threadIdx.x < 12) t.out->hist[threadIdx.x] = sh_cnt[0][threadIdx.x];
+    if (threadIdx.x == 0) stats_finish(t.out, t.n_part, t.elems_per_part, e, n, sh_cnt[0][12], sh_cnt[0][13]);
 }
 
 // ======================================================================================
@@ -1485,8 +1497,9 @@ int64_t item_elems_per_part(const BatchItem& it) {
     return it.sh.rows * it.sh.cols;
 }
 int stats_wgs(int64_t n_part) {
+    if (n_part <= 4096) return 1;                       // one workgroup writes the result directly
     int64_t w = (n_part + 1023) / 1024;
-    return (int)(w < 1 ? 1 : (w > kStatsMaxWg ? kStatsMaxWg : w));
+    return (int)(w > kStatsMaxWg ? kStatsMaxWg : w);
 }
 size_t item_workspace(const BatchItem& it) {
     size_t b = 0;
@@ -1667,7 +1680,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
         auto flush = [&]() {
             if (g.n == 0) return;
             { ProfScope ps(prof, kKernStatsPartial, st); k_stats_group_partial<<<dim3(wg_total), dim3(256), 0, st>>>(g); }
-            { ProfScope ps(prof, kKernStatsFinal, st); k_stats_group_final<<<dim3(g.n), dim3(256), 0, st>>>(g); }
+            if (wg_total > g.n) { ProfScope ps(prof, kKernStatsFinal, st); k_stats_group_final<<<dim3(g.n), dim3(256), 0, st>>>(g); }
             g.n = 0; wg_total = 0;
         };
         for (int i = 0; i < n; ++i) {
