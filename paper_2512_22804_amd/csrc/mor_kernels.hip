@@ -110,9 +110,9 @@ __device__ __forceinline__ void sub_unit_careful(const uint16_t* __restrict__ xl
 // One unit = 32 consecutive blocks: DPP row g (16 lanes x 8 elements) owns blocks g*8 .. g*8+7 of the
 // unit, all eight already loaded into raw[].  Lane j (and its mirror j+8) of the row keeps the scalars of
 // block g*8+j, so the per-block work (division, decision, metadata) runs once per 8 blocks.
-template <int CRIT, bool DEFER>
+template <int CRIT>
 __device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const uint16_t* __restrict__ x, const KOut& o, int64_t unit,
-                                                 int lane, float th) {
+                                                 int lane, float th, bool defer) {
     const int g = lane >> 4, l = lane & 15, own = l & 7;
     const int64_t prow = unit * 32 + g * 8;
     const int64_t off = prow * 128 + l * 8;
@@ -181,7 +181,7 @@ __device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const ui
     }
     if (my_abits >= kInfBits) { my_err = __builtin_inff(); my_err5 = my_err; }
     uint32_t my_mask = 0u;
-    if constexpr (!DEFER) my_mask = (CRIT == kCritEq3) ? decide_eq3(my_err, my_err5) : decide_eq2(my_err, 128u - my_zero, th);
+    if (!defer) my_mask = (CRIT == kCritEq3) ? decide_eq3(my_err, my_err5) : decide_eq2(my_err, 128u - my_zero, th);
     if (l < 8) {
         const int64_t p = prow + l;
         o.scale[p] = my_s;
@@ -189,48 +189,17 @@ __device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const ui
         o.err_sum[p] = my_err;
         o.nnz[p] = 128u - my_zero;
         if constexpr (CRIT == kCritEq3) o.err5_sum[p] = my_err5;
-        if constexpr (!DEFER) o.mask[p] = (uint8_t)my_mask;
+        if (!defer) o.mask[p] = (uint8_t)my_mask;
     }
-    if constexpr (!DEFER) {
-        if (o.bf16) {
-            const unsigned long long want = __ballot(l < 8 && my_mask != 0u);
-            if (want) {
-                const uint32_t bits = (uint32_t)(want >> (lane & 48)) & 0xFFu;   // my row's eight blocks
-                uint16_t* __restrict__ bl = o.bf16 + off;
+    if (!defer && o.bf16) {
+        const unsigned long long want = __ballot(l < 8 && my_mask != 0u);
+        if (want) {
+            const uint32_t bits = (uint32_t)(want >> (lane & 48)) & 0xFFu;   // my row's eight blocks
+            uint16_t* __restrict__ bl = o.bf16 + off;
 #pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    if ((bits >> k) & 1u) store16(bl + k * 128, raw[k]);
-            }
+            for (int k = 0; k < 8; ++k)
+                if ((bits >> k) & 1u) store16(bl + k * 128, raw[k]);
         }
-    }
-}
-
-// Dense operands (every leading dimension == cols): blocks are consecutive 256-byte runs.
-// Persistent waves stride over units of 32 blocks (8 KB of input) with two register sets: the loads of
-// the next unit are in flight while the current one is processed, so HBM latency overlaps the VALU work.
-template <int CRIT, bool DEFER>
-__global__ __launch_bounds__(256) void k_sub1x128_flat(const uint16_t* __restrict__ x, KOut o, int64_t n_units, float th) {
-    const int lane = threadIdx.x & 63, g = lane >> 4, l = lane & 15;
-    const int64_t W = (int64_t)gridDim.x * 4;
-    int64_t u = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (u >= n_units) return;
-    const uint16_t* __restrict__ xl = x + (g * 8) * 128 + l * 8;
-    u32x4 bufA[8], bufB[8];
-    auto load_unit = [&](u32x4 (&raw)[8], int64_t unit) {
-        const uint16_t* __restrict__ src = xl + unit * (32 * 128);
-#pragma unroll
-        for (int k = 0; k < 8; ++k) raw[k] = load16(src + k * 128);
-    };
-    load_unit(bufA, u);
-    for (;;) {
-        const int64_t ub = u + W;
-        if (ub < n_units) load_unit(bufB, ub);
-        sub_unit_process<CRIT, DEFER>(bufA, x, o, u, lane, th);
-        if (ub >= n_units) break;
-        u = ub + W;
-        if (u < n_units) load_unit(bufA, u);
-        sub_unit_process<CRIT, DEFER>(bufB, x, o, ub, lane, th);
-        if (u >= n_units) break;
     }
 }
 
@@ -244,85 +213,6 @@ __global__ __launch_bounds__(256) void k_sub1x128_strided(const uint16_t* __rest
         const u32x4 raw = load16(src);
         sub_block_body<CRIT, DEFER>(raw, src, l, r * cpr + cb, o, o.fp8 + r * o.ld_fp8 + cb * 128 + l * 8,
                                     o.bf16 ? o.bf16 + r * o.ld_bf16 + cb * 128 + l * 8 : nullptr, th);
-    }
-}
-
-// ======================================================================================
-// 128 x 128 blocks (Section 4.1.1 "Per-Block"): one 256-thread workgroup per block, the whole
-// 32 KB tile lives in registers (8 x 16 B per lane); LDS only carries 4 per-wave partials.
-// ======================================================================================
-template <int CRIT, bool DEFER>
-__global__ __launch_bounds__(256) void k_block128(const uint16_t* __restrict__ x, KShape sh, KOut o, float th) {
-    __shared__ uint32_t sh_amax[4];
-    __shared__ float sh_err[4];
-    __shared__ float sh_err5[4];
-    __shared__ uint32_t sh_zero[4];
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, l = lane & 15;
-    const int64_t tc = blockIdx.x, tr = blockIdx.y;
-    const int64_t col = tc * 128 + l * 8;
-    const int64_t row0 = tr * 128 + w * 4 + (lane >> 4);
-    const uint16_t* __restrict__ src = x + row0 * sh.ld + col;
-    uint8_t* __restrict__ dst = o.fp8 + row0 * o.ld_fp8 + col;
-    u32x4 raw[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) raw[i] = load16(src + (int64_t)i * 16 * sh.ld);
-    Scan8 sc{0u, 0u};
-#pragma unroll
-    for (int i = 0; i < 8; ++i) scan8(raw[i], sc);
-    const uint32_t wa = wave_allmax_u32(fold_max16(sc.amax2));
-    if (lane == 0) sh_amax[w] = wa;
-    __syncthreads();
-    const uint32_t abits = max(max(sh_amax[0], sh_amax[1]), max(sh_amax[2], sh_amax[3]));
-    const float s = scale_from_amax_bits(abits, kE4M3Max);
-    float e, e5 = 0.0f;
-    if (abits < kFastAmaxBits) {
-        float e0 = 0.0f, e1 = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) store8(dst + (int64_t)i * 16 * o.ld_fp8, quant8_fast<false>(raw[i], s, e0, e1));
-        e = e0 + e1;
-        if constexpr (CRIT == kCritEq3) {
-            const float s5 = scale_from_amax_bits(abits, kE5M2Max);
-            float f0 = 0.0f, f1 = 0.0f;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) (void)quant8_fast<true>(raw[i], s5, f0, f1);
-            e5 = f0 + f1;
-        }
-    } else {
-        e = 0.0f;
-#pragma clang loop unroll(disable)
-        for (int i = 0; i < 8; ++i) {
-            e += quant8_careful_mem<false>(src + (int64_t)i * 16 * sh.ld, s, dst + (int64_t)i * 16 * o.ld_fp8);
-            if constexpr (CRIT == kCritEq3)
-                e5 += quant8_careful_mem<true>(src + (int64_t)i * 16 * sh.ld, scale_from_amax_bits(abits, kE5M2Max), nullptr);
-        }
-    }
-    const float werr = wave_allsum_f32(e);
-    const uint32_t wzero = wave_allsum_u32(fold_add16(sc.zero2));
-    float werr5 = 0.0f;
-    if constexpr (CRIT == kCritEq3) werr5 = wave_allsum_f32(e5);
-    if (lane == 0) { sh_err[w] = werr; sh_zero[w] = wzero; sh_err5[w] = werr5; }
-    __syncthreads();
-    float err = (sh_err[0] + sh_err[1]) + (sh_err[2] + sh_err[3]);
-    float err5 = (sh_err5[0] + sh_err5[1]) + (sh_err5[2] + sh_err5[3]);
-    const uint32_t nnz = 128u * 128u - ((sh_zero[0] + sh_zero[1]) + (sh_zero[2] + sh_zero[3]));
-    if (abits >= kInfBits) { err = __builtin_inff(); err5 = __builtin_inff(); }
-    uint32_t mask = 0u;
-    if constexpr (!DEFER) mask = (CRIT == kCritEq3) ? decide_eq3(err, err5) : decide_eq2(err, nnz, th);
-    if (threadIdx.x == 0) {
-        const int64_t p = tr * gridDim.x + tc;
-        o.scale[p] = s;
-        o.amax[p] = __uint_as_float(abits << 16);
-        o.err_sum[p] = err;
-        o.nnz[p] = nnz;
-        if constexpr (CRIT == kCritEq3) o.err5_sum[p] = err5;
-        if constexpr (!DEFER) o.mask[p] = (uint8_t)mask;
-    }
-    if constexpr (!DEFER) {
-        if (mask && o.bf16) {
-            uint16_t* __restrict__ dbf = o.bf16 + row0 * o.ld_bf16 + col;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) store16(dbf + (int64_t)i * 16 * o.ld_bf16, raw[i]);
-        }
     }
 }
 
@@ -350,29 +240,6 @@ __device__ __forceinline__ uint32_t amax2_of(const u32x4& v, uint32_t a2) {
     return a2;
 }
 
-// Pass A, dense.
-__global__ __launch_bounds__(256) void k_tensor_amax_flat(const uint16_t* __restrict__ x, int64_t n_chunks,
-                                                          uint32_t* __restrict__ part) {
-    __shared__ uint32_t sh4[4];
-    uint32_t a2 = 0u;
-    // a workgroup reads tiles of 2048 consecutive chunks (32 KB): 8 x 16 B per lane in flight, 4 KB apart
-    const int64_t n_tiles = (n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
-    for (int64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-        const int64_t c0 = t * kTensorChunksPerBlock + threadIdx.x;
-        if (c0 + 7 * 256 < n_chunks) {
-            u32x4 v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = load16(x + (c0 + u * 256) * 8);
-#pragma unroll
-            for (int u = 0; u < 8; ++u) a2 = amax2_of(v[u], a2);
-        } else {
-            for (int u = 0; u < 8; ++u)
-                if (c0 + u * 256 < n_chunks) a2 = amax2_of(load16(x + (c0 + u * 256) * 8), a2);
-        }
-    }
-    const uint32_t a = block_allmax_u32(fold_max16(a2), sh4);
-    if (threadIdx.x == 0) part[blockIdx.x] = a;
-}
 // Pass A, strided: one workgroup strides over rows; lanes stride over the row's chunks.
 __global__ __launch_bounds__(256) void k_tensor_amax_strided(const uint16_t* __restrict__ x, KShape sh,
                                                              uint32_t* __restrict__ part) {
@@ -460,66 +327,6 @@ __device__ __forceinline__ void tensor_publish(const TensorAcc& a, const TensorP
     }
 }
 
-// Pass B, dense: persistent workgroups stride over tiles of 2048 consecutive chunks (32 KB of input);
-// the next tile's loads are issued before the current tile is processed (two register sets).
-template <int CRIT>
-__global__ __launch_bounds__(256) void k_tensor_quant_flat(const uint16_t* __restrict__ x, int64_t n_chunks, int64_t n_tiles,
-                                                           KOut o, const uint32_t* __restrict__ amax_part, int n_amax_part,
-                                                           TensorPartials tp) {
-    __shared__ uint32_t sh4[4];
-    u32x4 bufA[kTensorChunksPerThread], bufB[kTensorChunksPerThread];
-    auto load_tile = [&](u32x4* raw, int64_t tile) {
-        const int64_t c0 = tile * kTensorChunksPerBlock + threadIdx.x;
-#pragma unroll
-        for (int u = 0; u < kTensorChunksPerThread; ++u) {
-            const int64_t c = c0 + u * 256;
-            if (c < n_chunks) raw[u] = load16(x + c * 8);
-            else { raw[u].x = 0u; raw[u].y = 0u; raw[u].z = 0u; raw[u].w = 0u; }
-        }
-    };
-    int64_t t = blockIdx.x;
-    load_tile(bufA, t);
-    const uint32_t abits = global_amax_bits(amax_part, n_amax_part, sh4);
-    if (blockIdx.x == 0 && threadIdx.x == 0) tp.abits[0] = abits;
-    const float s = scale_from_amax_bits(abits, kE4M3Max);
-    const float s5 = (CRIT == kCritEq3) ? scale_from_amax_bits(abits, kE5M2Max) : 0.0f;
-    TensorAcc acc{0.0f, 0.0f, 0.0f, 0.0f, 0u};
-    auto process = [&](const u32x4* raw, int64_t tile) {
-        const int64_t c0 = tile * kTensorChunksPerBlock + threadIdx.x;
-#pragma unroll
-        for (int u = 0; u < kTensorChunksPerThread; ++u) acc.zero2 = zero2_of(raw[u], acc.zero2);
-        if (abits < kFastAmaxBits) {
-#pragma unroll
-            for (int u = 0; u < kTensorChunksPerThread; ++u) {
-                const int64_t c = c0 + u * 256;
-                const u32x2 codes = quant8_fast<false>(raw[u], s, acc.e0, acc.e1);
-                if (c < n_chunks) store8(o.fp8 + c * 8, codes);
-                if constexpr (CRIT == kCritEq3) (void)quant8_fast<true>(raw[u], s5, acc.f0, acc.f1);
-            }
-        } else {
-#pragma clang loop unroll(disable)
-            for (int u = 0; u < kTensorChunksPerThread; ++u) {
-                const int64_t c = c0 + u * 256;
-                if (c < n_chunks) {
-                    acc.e0 += quant8_careful_mem<false>(x + c * 8, s, o.fp8 + c * 8);
-                    if constexpr (CRIT == kCritEq3) acc.f0 += quant8_careful_mem<true>(x + c * 8, s5, nullptr);
-                }
-            }
-        }
-    };
-    const int64_t G = gridDim.x;
-    for (;;) {
-        const int64_t tb = t + G;
-        if (tb < n_tiles) load_tile(bufB, tb);
-        process(bufA, t);
-        if (tb >= n_tiles) break;
-        t = tb + G;
-        if (t < n_tiles) load_tile(bufA, t);
-        process(bufB, tb);
-        if (t >= n_tiles) break;
-    }
-    tensor_publish<CRIT>(acc, tp, blockIdx.x);
-}
 // Pass B, strided: persistent workgroups stride over 16-row x 128-column tiles, one chunk per thread.
 template <int CRIT>
 __global__ __launch_bounds__(256) void k_tensor_quant_strided(const uint16_t* __restrict__ x, KShape sh, uint32_t tiles_x,
@@ -843,6 +650,7 @@ struct GroupSub {
     const uint16_t* x[kMaxGroup];
     KOut o[kMaxGroup];
     float th[kMaxGroup];
+    uint8_t defer[kMaxGroup];             // 1: tensor-level decision follows, write no mask / fallback here
 };
 __device__ __forceinline__ int group_find(const int64_t* end, int n, int64_t v) {
     int i = 0;
@@ -872,7 +680,7 @@ __global__ __launch_bounds__(256) void k_sub1x128_group(GroupSub g) {
     load_unit(bufA, u, opA, locA);
 #if !MOR_SUB_DOUBLE
     for (;;) {
-        sub_unit_process<CRIT, false>(bufA, g.x[opA], g.o[opA], locA, lane, g.th[opA]);
+        sub_unit_process<CRIT>(bufA, g.x[opA], g.o[opA], locA, lane, g.th[opA], g.defer[opA] != 0);
         u += W;
         if (u >= total) break;
         load_unit(bufA, u, opA, locA);
@@ -883,11 +691,11 @@ __global__ __launch_bounds__(256) void k_sub1x128_group(GroupSub g) {
     for (;;) {
         const int64_t ub = u + W;
         if (ub < total) load_unit(bufB, ub, opB, locB);
-        sub_unit_process<CRIT, false>(bufA, g.x[opA], g.o[opA], locA, lane, g.th[opA]);
+        sub_unit_process<CRIT>(bufA, g.x[opA], g.o[opA], locA, lane, g.th[opA], g.defer[opA] != 0);
         if (ub >= total) break;
         u = ub + W;
         if (u < total) load_unit(bufA, u, opA, locA);
-        sub_unit_process<CRIT, false>(bufB, g.x[opB], g.o[opB], locB, lane, g.th[opB]);
+        sub_unit_process<CRIT>(bufB, g.x[opB], g.o[opB], locB, lane, g.th[opB], g.defer[opB] != 0);
         if (u >= total) break;
     }
 #endif
@@ -901,7 +709,10 @@ struct GroupBlock {
     const uint16_t* x[kMaxGroup];
     KOut o[kMaxGroup];
     float th[kMaxGroup];
+    uint8_t defer[kMaxGroup];
 };
+// One 256-thread workgroup per 128x128 block (Section 4.1.1 "Per-Block"): the whole 32 KB tile lives in
+// registers (8 x 16 B per lane); LDS only carries 4 per-wave partials.
 template <int CRIT>
 __global__ __launch_bounds__(256) void k_block128_group(GroupBlock g) {
     __shared__ uint32_t sh_amax[4];
@@ -961,14 +772,15 @@ __global__ __launch_bounds__(256) void k_block128_group(GroupBlock g) {
     float err5 = (sh_err5[0] + sh_err5[1]) + (sh_err5[2] + sh_err5[3]);
     const uint32_t nnz = 128u * 128u - ((sh_zero[0] + sh_zero[1]) + (sh_zero[2] + sh_zero[3]));
     if (abits >= kInfBits) { err = __builtin_inff(); err5 = __builtin_inff(); }
-    const uint32_t mask = (CRIT == kCritEq3) ? decide_eq3(err, err5) : decide_eq2(err, nnz, g.th[op]);
+    const bool defer = g.defer[op] != 0;
+    const uint32_t mask = defer ? 0u : ((CRIT == kCritEq3) ? decide_eq3(err, err5) : decide_eq2(err, nnz, g.th[op]));
     if (threadIdx.x == 0) {
         o.scale[p] = s;
         o.amax[p] = __uint_as_float(abits << 16);
         o.err_sum[p] = err;
         o.nnz[p] = nnz;
         if constexpr (CRIT == kCritEq3) o.err5_sum[p] = err5;
-        o.mask[p] = (uint8_t)mask;
+        if (!defer) o.mask[p] = (uint8_t)mask;
     }
     if (mask && o.bf16) {
         uint16_t* __restrict__ dbf = o.bf16 + row0 * o.ld_bf16 + col;
@@ -1089,7 +901,7 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
     const uint32_t abits = global_amax_bits(t.amax_part, t.n_amax, sh4);
     const bool proven = tensor_fallback_proven(t, shl4);     // then the BF16 fallback is written in this sweep
     uint16_t* __restrict__ bf16 = t.o.bf16;
-    if (b == 0 && threadIdx.x == 0) t.abits[0] = abits;
+    if (b == 0 && threadIdx.x == 0) { t.abits[0] = abits; t.abits[1] = proven ? 1u : 0u; }
     const float s = scale_from_amax_bits(abits, kE4M3Max);
     const float s5 = (CRIT == kCritEq3) ? scale_from_amax_bits(abits, kE5M2Max) : 0.0f;
     TensorAcc acc{0.0f, 0.0f, 0.0f, 0.0f, 0u};
@@ -1156,6 +968,8 @@ __global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g) {
     const TensorOp& t = g.op[op];
     const int b = blockIdx.x - (op ? g.copy_end[op - 1] : 0);
     const int nb = g.copy_end[op] - (op ? g.copy_end[op - 1] : 0);
+    const bool proven = t.abits[1] != 0u;                     // pass B already wrote the fallback
+    if (proven && b != 0) return;                             // only the operand's first workgroup has work left
     double se = 0.0, se5 = 0.0;
     unsigned long long sz = 0;
     for (int i = threadIdx.x; i < t.n_slots; i += 256) {
@@ -1173,7 +987,6 @@ __global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g) {
     uint32_t mask;
     if constexpr (CRIT == kCritEq3) mask = (se < se5) ? 0u : 1u;
     else mask = ((n ? se / (double)n : 0.0) < (double)t.th) ? 0u : 1u;
-    const bool proven = tensor_fallback_proven(t, shl);       // pass B already wrote the fallback
     if (b == 0 && threadIdx.x == 0) {
         const KOut& o = t.o;
         const float err_f = (float)se;
@@ -1364,39 +1177,11 @@ static int clamp_grid_y(int64_t v) { return (int)(v < 1 ? 1 : (v > 65535 ? 65535
         else                  { if (defer) KERNEL<kCritEq2, true> __VA_ARGS__; else KERNEL<kCritEq2, false> __VA_ARGS__; } \
     } while (0)
 
+// Padded leading dimensions: one operand per launch.
 hipError_t launch_sub1x128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st, KProf* prof) {
-    const int64_t n_part = sh.rows * (sh.cols / 128);
     ProfScope ps(prof, kKernSub1x128, st);
-    if (is_flat(sh, o)) {
-        // whole units (32 consecutive blocks) go to the flat kernel, the remaining blocks to the strided kernel
-        const int64_t n_units = n_part / 32, n_full = n_units * 32, n_tail = n_part - n_full;
-        int64_t blocks = (n_units + 3) / 4;
-        if (blocks > kSubFlatMaxBlocks) blocks = kSubFlatMaxBlocks;
-        if (blocks > 0) MOR_DISPATCH_CRIT_DEFER(k_sub1x128_flat, <<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, o, n_units, th));
-        if (n_tail > 0) {
-            KShape ts{n_tail, 128, 128};
-            KOut to = o;
-            to.fp8 += n_full * 128; to.ld_fp8 = 128;
-            if (to.bf16) to.bf16 += n_full * 128;
-            to.ld_bf16 = 128;
-            to.scale += n_full; to.amax += n_full; to.err_sum += n_full; to.nnz += n_full; to.mask += n_full;
-            if (to.err5_sum) to.err5_sum += n_full;
-            const dim3 grid(1u, (unsigned)clamp_grid_y((n_tail + 15) / 16));
-            MOR_DISPATCH_CRIT_DEFER(k_sub1x128_strided, <<<grid, dim3(256), 0, st>>>(x + n_full * 128, ts, to, th));
-        }
-    } else {
-        const dim3 grid((unsigned)(sh.cols / 128), (unsigned)clamp_grid_y((sh.rows + 15) / 16));
-        MOR_DISPATCH_CRIT_DEFER(k_sub1x128_strided, <<<grid, dim3(256), 0, st>>>(x, sh, o, th));
-    }
-    return hipGetLastError();
-}
-
-hipError_t launch_block128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st, KProf* prof) {
-    const int64_t tr = sh.rows / 128, tc = sh.cols / 128;
-    if (tr > 65535) return hipErrorInvalidValue;   // rows beyond 8.3 M are not supported by this launch shape
-    const dim3 grid((unsigned)tc, (unsigned)tr);
-    ProfScope ps(prof, kKernBlock128, st);
-    MOR_DISPATCH_CRIT_DEFER(k_block128, <<<grid, dim3(256), 0, st>>>(x, sh, o, th));
+    const dim3 grid((unsigned)(sh.cols / 128), (unsigned)clamp_grid_y((sh.rows + 15) / 16));
+    MOR_DISPATCH_CRIT_DEFER(k_sub1x128_strided, <<<grid, dim3(256), 0, st>>>(x, sh, o, th));
     return hipGetLastError();
 }
 
@@ -1406,31 +1191,16 @@ hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int
     uint32_t* amax_part = reinterpret_cast<uint32_t*>(w + pl.off_amax_part);
     TensorPartials tp{reinterpret_cast<float*>(w + pl.off_err_part), reinterpret_cast<float*>(w + pl.off_err5_part),
                       reinterpret_cast<uint32_t*>(w + pl.off_nnz_part), reinterpret_cast<uint32_t*>(w + pl.off_decision)};
-    const int64_t n_chunks = sh.rows * sh.cols / 8;
-    const bool flat = is_flat(sh, o);
-    int n_amax, n_slots;
-    unsigned long long n_padded;
-    if (flat) {
-        int64_t want = (n_chunks + 256 * 8 - 1) / (256 * 8);
-        n_amax = (int)(want < 1 ? 1 : (want > kMaxAmaxBlocks ? kMaxAmaxBlocks : want));
-        { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_flat<<<dim3(n_amax), dim3(256), 0, st>>>(x, n_chunks, amax_part); }
-        const int64_t n_tiles = (n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
-        n_slots = (int)(n_tiles < kMaxQuantBlocks ? n_tiles : kMaxQuantBlocks);
-        if (n_tiles / n_slots > 2000) return hipErrorInvalidValue;   // 16-bit per-lane zero counters (32 per tile)
-        n_padded = (unsigned long long)n_tiles * kTensorChunksPerBlock * 8;
-        ProfScope ps(prof, kKernTensorQuant, st);
-        if (crit == kCritEq3) k_tensor_quant_flat<kCritEq3><<<dim3(n_slots), dim3(256), 0, st>>>(x, n_chunks, n_tiles, o, amax_part, n_amax, tp);
-        else k_tensor_quant_flat<kCritEq2><<<dim3(n_slots), dim3(256), 0, st>>>(x, n_chunks, n_tiles, o, amax_part, n_amax, tp);
-    } else {
-        n_amax = (int)(sh.rows < kMaxAmaxBlocks ? sh.rows : kMaxAmaxBlocks);
-        { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_strided<<<dim3(n_amax), dim3(256), 0, st>>>(x, sh, amax_part); }
-        const int64_t gx = (sh.cols + 127) / 128, gy = (sh.rows + 15) / 16;
-        if (gx * gy > 0x7FFFFFFF) return hipErrorInvalidValue;
-        // 16-bit zero counters per lane: at most 8 zeros per tile and lane, so 4096 tiles per workgroup are safe
-        int64_t min_blocks = (gx * gy + 4095) / 4096;
-        if (min_blocks > kMaxQuantBlocks) return hipErrorInvalidValue;
-        n_slots = (int)(gx * gy < kMaxQuantBlocks ? gx * gy : kMaxQuantBlocks);
-        n_padded = (unsigned long long)(gx * gy) * 2048ull;
+    const int n_amax = (int)(sh.rows < kMaxAmaxBlocks ? sh.rows : kMaxAmaxBlocks);
+    { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_strided<<<dim3(n_amax), dim3(256), 0, st>>>(x, sh, amax_part); }
+    const int64_t gx = (sh.cols + 127) / 128, gy = (sh.rows + 15) / 16;
+    if (gx * gy > 0x7FFFFFFF) return hipErrorInvalidValue;
+    // 16-bit zero counters per lane: at most 8 zeros per tile and lane, so 4096 tiles per workgroup are safe
+    const int64_t min_blocks = (gx * gy + 4095) / 4096;
+    if (min_blocks > kMaxQuantBlocks) return hipErrorInvalidValue;
+    const int n_slots = (int)(gx * gy < kMaxQuantBlocks ? gx * gy : kMaxQuantBlocks);
+    const unsigned long long n_padded = (unsigned long long)(gx * gy) * 2048ull;
+    {
         ProfScope ps(prof, kKernTensorQuant, st);
         if (crit == kCritEq3) k_tensor_quant_strided<kCritEq3><<<dim3(n_slots), dim3(256), 0, st>>>(x, sh, (uint32_t)gx, (uint32_t)(gx * gy), o, amax_part, n_amax, tp);
         else k_tensor_quant_strided<kCritEq2><<<dim3(n_slots), dim3(256), 0, st>>>(x, sh, (uint32_t)gx, (uint32_t)(gx * gy), o, amax_part, n_amax, tp);
@@ -1438,8 +1208,9 @@ hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int
     {
         ProfScope ps(prof, kKernFallbackCopy, st);
         const int grid = o.bf16 ? 2048 : 1;
-        if (crit == kCritEq3) k_tensor_finish<kCritEq3><<<dim3(grid), dim3(256), 0, st>>>(tp, n_slots, n_padded, o, th, x, sh, flat ? 1 : 0);
-        else k_tensor_finish<kCritEq2><<<dim3(grid), dim3(256), 0, st>>>(tp, n_slots, n_padded, o, th, x, sh, flat ? 1 : 0);
+        const int flat = (sh.ld == sh.cols && o.ld_bf16 == sh.cols) ? 1 : 0;
+        if (crit == kCritEq3) k_tensor_finish<kCritEq3><<<dim3(grid), dim3(256), 0, st>>>(tp, n_slots, n_padded, o, th, x, sh, flat);
+        else k_tensor_finish<kCritEq2><<<dim3(grid), dim3(256), 0, st>>>(tp, n_slots, n_padded, o, th, x, sh, flat);
     }
     return hipGetLastError();
 }
@@ -1482,8 +1253,8 @@ constexpr int kStatsMaxWg = 256;
 
 bool item_is_flat(const BatchItem& it) { return is_flat(it.sh, it.o); }
 bool item_grouped(const BatchItem& it) {
-    if (it.gran == kGranBlock) return it.scope == 0 && it.sh.cols / 128 <= 0x7FFFFFFF;
-    if (it.gran == kGranSub) return it.scope == 0 && item_is_flat(it);
+    if (it.gran == kGranBlock) return it.sh.cols / 128 <= 0x7FFFFFFF;
+    if (it.gran == kGranSub) return item_is_flat(it);
     return item_is_flat(it);     // per-tensor: the scope does not matter (one block)
 }
 int64_t item_parts(const BatchItem& it) {
@@ -1552,7 +1323,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 const int64_t n_part = item_parts(it), n_units = n_part / 32, n_full = n_units * 32, n_tail = n_part - n_full;
                 if (n_units > 0) {
                     total += n_units;
-                    g.unit_end[g.n] = total; g.x[g.n] = it.x; g.o[g.n] = it.o; g.th[g.n] = it.th;
+                    g.unit_end[g.n] = total; g.x[g.n] = it.x; g.o[g.n] = it.o; g.th[g.n] = it.th; g.defer[g.n] = it.scope == 1;
                     if (++g.n == kMaxGroup) flush();
                 }
                 if (n_tail > 0) {     // fewer than 32 blocks left: the strided kernel takes them
@@ -1564,8 +1335,8 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                     to.scale += n_full; to.amax += n_full; to.err_sum += n_full; to.nnz += n_full; to.mask += n_full;
                     if (to.err5_sum) to.err5_sum += n_full;
                     const dim3 grid(1u, (unsigned)clamp_grid_y((n_tail + 15) / 16));
-                    if (crit == kCritEq3) k_sub1x128_strided<kCritEq3, false><<<grid, dim3(256), 0, st>>>(it.x + n_full * 128, ts, to, it.th);
-                    else k_sub1x128_strided<kCritEq2, false><<<grid, dim3(256), 0, st>>>(it.x + n_full * 128, ts, to, it.th);
+                    const bool defer = it.scope == 1;
+                    MOR_DISPATCH_CRIT_DEFER(k_sub1x128_strided, <<<grid, dim3(256), 0, st>>>(it.x + n_full * 128, ts, to, it.th));
                 }
             }
             flush();
@@ -1589,7 +1360,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 if (total + tiles > 0x7FFFFFFF) flush();
                 total += tiles;
                 g.tile_end[g.n] = total; g.tiles_x[g.n] = (int32_t)(it.sh.cols / 128); g.ld[g.n] = it.sh.ld;
-                g.x[g.n] = it.x; g.o[g.n] = it.o; g.th[g.n] = it.th;
+                g.x[g.n] = it.x; g.o[g.n] = it.o; g.th[g.n] = it.th; g.defer[g.n] = it.scope == 1;
                 if (++g.n == kMaxGroup) flush();
             }
             flush();
@@ -1656,8 +1427,13 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
             flush();
         }
     }
-    // ---- operands the grouped kernels do not cover: padded leading dimensions, tensor-level decision over
-    //      sub-tensor scaling.  One operand at a time.
+    // ---- tensor-level decision (Section 3.1) over the per-block sums the grouped passes left behind
+    for (int i = 0; i < n && err == hipSuccess; ++i) {
+        const BatchItem& it = items[i];
+        if (!item_grouped(it) || it.gran == kGranTensor || it.scope != 1) continue;
+        err = launch_scope_finalize(it.x, it.sh, it.o, item_parts(it), it.crit, it.th, carve(scope_workspace_bytes(item_parts(it))), st, prof);
+    }
+    // ---- operands the grouped kernels do not cover (padded leading dimensions), one at a time
     for (int i = 0; i < n && err == hipSuccess; ++i) {
         const BatchItem& it = items[i];
         if (item_grouped(it)) continue;
@@ -1665,8 +1441,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
         if (it.gran == kGranTensor) {
             err = launch_tensor(it.x, it.sh, it.o, it.crit, it.th, carve(plan_tensor(it.sh.rows, it.sh.cols).bytes), st, prof);
         } else {
-            err = it.gran == kGranSub ? launch_sub1x128(it.x, it.sh, it.o, it.crit, defer, it.th, st, prof)
-                                      : launch_block128(it.x, it.sh, it.o, it.crit, defer, it.th, st, prof);
+            err = launch_sub1x128(it.x, it.sh, it.o, it.crit, defer, it.th, st, prof);
             if (err == hipSuccess && defer)
                 err = launch_scope_finalize(it.x, it.sh, it.o, item_parts(it), it.crit, it.th, carve(scope_workspace_bytes(item_parts(it))), st, prof);
         }

@@ -64,7 +64,6 @@ size_t batch_workspace_bytes(const BatchItem* items, int n);
 hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws, size_t ws_bytes, hipStream_t st, KProf* prof);
 
 hipError_t launch_sub1x128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st, KProf* prof);
-hipError_t launch_block128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st, KProf* prof);
 hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int crit, float th, void* ws, hipStream_t st, KProf* prof);
 // Tensor-scope decision over per-block sums already written by a deferred sub-tensor pass.
 hipError_t launch_scope_finalize(const uint16_t* x, const KShape& sh, const KOut& o, int64_t n_part, int crit, float th,
