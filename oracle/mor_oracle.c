@@ -29,7 +29,10 @@
  *   - BF16 = leave the block in its original precision: Section 3;
  *   - dequantize and de-scale back to the original range: Section 4, the
  *     fake-quantization paragraph (Figure 4);
- *   - 0.5 %-wide histogram bins, last bin open-ended from 5.5 %: Section 4.1.3.
+ *   - 0.5 %-wide histogram bins, last bin open-ended from 5.5 %: Section 4.1.3;
+ *   - group amax mantissa scaling, exponent lowered by one when m_g > m_b:
+ *     Algorithm 1; global mantissa from the global amax before the blocks are
+ *     quantized: Section 3.1, the paragraph on Figure 2.
  *
  * Readings taken where the paper is silent (each is also listed in the design
  * notes of the repository):
@@ -51,9 +54,21 @@
  *   R9  a block holding Inf or NaN: amax = that pattern, s = 1, codes by R3,
  *       error sums = +inf, selection = BF16.
  *   R10 de-scaling multiplies by s_inv = fl32(1 / s), then rounds to BF16 RNE.
+ *   R16 GAM (Algorithm 1) is run with one group = the whole tensor, the
+ *       configuration of the paper's experiments (Section 2, the paragraph
+ *       after the algorithm's description).  mantissa(s) and exponent(s) are
+ *       those of the binary32 number s = m * 2^e, 1 <= m < 2.  The scale that
+ *       is applied is m_g * 2^e, exact in binary32.  The stored E8M0 code is
+ *       e + 127, the stored group mantissa the 23 fraction bits of m_g.
+ *   R17 "E8M0 per-block scaling" (Section 4.1.2, third ablation) is the power
+ *       of two 2^exponent(s_b), i.e. Algorithm 1 with m_g = 1: the largest
+ *       power of two that cannot saturate.
+ *   R18 s_g and s_b in Algorithm 1 follow R2 (zero / non-finite amax -> 1,
+ *       overflow -> FLT_MAX) before mantissa and exponent are taken.
  *
- * parity unpinned: R8 (tie handling) and R9 (non-finite policy) are fixed by
- * these readings only; nothing in the paper pins them.
+ * parity unpinned: R8 (tie handling), R9 (non-finite policy) and R17 (which
+ * power of two the E8M0 ablation uses) are fixed by these readings only;
+ * nothing in the paper pins them.
  */
 #include <float.h>
 #include <math.h>
@@ -150,6 +165,41 @@ float mor_oracle_scale(float amax, float q_amax)
     return s;
 }
 
+/* --------------------------------------------------- Algorithm 1 (GAM, R16-R18) */
+
+enum { SCALING_FP32_AMAX = 0, SCALING_GAM = 1, SCALING_E8M0 = 2 };
+
+/* s = m * 2^e with 1 <= m < 2, for a positive finite s. */
+static void mantissa_exponent(float s, double *m, int *e)
+{
+    int k;
+    double f = frexp((double)s, &k);     /* s = f * 2^k, 0.5 <= f < 1 */
+    *m = 2.0 * f;
+    *e = k - 1;
+}
+
+/* m_g of Algorithm 1 for a group whose amax is g_amax (1.0 for E8M0-only scaling, R17). */
+double mor_oracle_group_mantissa(float g_amax, float q_amax, int scaling)
+{
+    double m_g;
+    int e_g;
+    if (scaling != SCALING_GAM) return 1.0;
+    mantissa_exponent(mor_oracle_scale(g_amax, q_amax), &m_g, &e_g);
+    return m_g;
+}
+
+/* The block loop of Algorithm 1: exponent of s_b, one lower when m_g > m_b.
+ * Returns the scale that is applied, m_g * 2^e; *e_out receives e. */
+float mor_oracle_gam_block_scale(float b_amax, float q_amax, double m_g, int *e_out)
+{
+    double m_b;
+    int e;
+    mantissa_exponent(mor_oracle_scale(b_amax, q_amax), &m_b, &e);
+    if (!(m_g <= m_b)) e = e - 1;
+    if (e_out) *e_out = e;
+    return (float)ldexp(m_g, e);          /* 24 significant bits, normal range: exact */
+}
+
 /* ------------------------------------------------------------ partitioning */
 
 enum { GRAN_TENSOR = 0, GRAN_SUB_1x128 = 1, GRAN_BLOCK_128x128 = 2 };
@@ -179,6 +229,7 @@ typedef struct {
     float  amax, scale;
     double err_sum, err5_sum, err_sum_unscaled;
     uint32_t nnz;
+    int    e8m0;            /* biased exponent of the E4M3 scale (GAM / E8M0 scaling), else 0 */
 } block_result;
 
 /* Error sums of one block for one FP8 format; optionally writes the codes. */
@@ -218,6 +269,7 @@ static double block_error(const uint16_t *x, int64_t ld, int64_t pr, int64_t pc,
 }
 
 static void analyze_block(const uint16_t *x, int64_t ld, int64_t pr, int64_t pc, int crit,
+                          int scaling, double m_g, double m_g5,
                           uint8_t *codes, int64_t ld_codes, block_result *out)
 {
     uint16_t a = 0;
@@ -232,11 +284,19 @@ static void analyze_block(const uint16_t *x, int64_t ld, int64_t pr, int64_t pc,
     nonfinite = a >= 0x7F80u;
     out->amax = bf16_to_f32(a);
     out->nnz = nnz;
-    out->scale = mor_oracle_scale(out->amax, 448.0f);
+    out->e8m0 = 0;
+    if (scaling == SCALING_FP32_AMAX) {
+        out->scale = mor_oracle_scale(out->amax, 448.0f);
+    } else {
+        int e;
+        out->scale = mor_oracle_gam_block_scale(out->amax, 448.0f, m_g, &e);
+        out->e8m0 = e + 127;
+    }
     out->err_sum = block_error(x, ld, pr, pc, out->scale, 4, 3, nonfinite, codes, ld_codes,
                                &out->err_sum_unscaled);
     if (crit == CRIT_E4M3_VS_E5M2) {
-        float s5 = mor_oracle_scale(out->amax, 57344.0f);
+        float s5 = scaling == SCALING_FP32_AMAX ? mor_oracle_scale(out->amax, 57344.0f)
+                                                : mor_oracle_gam_block_scale(out->amax, 57344.0f, m_g5, NULL);
         out->err5_sum = block_error(x, ld, pr, pc, s5, 5, 2, nonfinite, NULL, 0, NULL);
     } else {
         out->err5_sum = 0.0;
@@ -264,22 +324,46 @@ static int accept_e4m3(int crit, double err_sum, double err5_sum, uint64_t nnz, 
  *   be NULL);  nnz [P] uint32;  mask [P] uint8 (0 = E4M3, 1 = BF16)
  * Blocks are numbered row-major over the block grid.  Returns 0, or -1 on a bad shape.
  */
-int mor_oracle_analyze_quantize(const uint16_t *x, int64_t rows, int64_t cols, int64_t ld,
-                                int gran, int scope, int crit, float threshold,
-                                uint8_t *fp8, uint16_t *bf16,
-                                float *scale, float *amax, double *err_sum, uint32_t *nnz,
-                                uint8_t *mask, double *err5_sum, double *err_sum_unscaled)
+/*
+ * The same with a choice of scaling algorithm: 0 = FP32 amax, 1 = GAM (Algorithm 1, one group),
+ * 2 = E8M0 only.  For 1 and 2, e8m0 [P] receives the block exponents (biased by 127) and
+ * group_mantissa [1] the 23 fraction bits of m_g (0 for E8M0-only); scale [P] is the applied
+ * scale m_g * 2^e.  Both extra outputs may be NULL.
+ */
+int mor_oracle_analyze_quantize_ex(const uint16_t *x, int64_t rows, int64_t cols, int64_t ld,
+                                   int gran, int scope, int crit, int scaling, float threshold,
+                                   uint8_t *fp8, uint16_t *bf16,
+                                   float *scale, float *amax, double *err_sum, uint32_t *nnz,
+                                   uint8_t *mask, double *err5_sum, double *err_sum_unscaled,
+                                   uint8_t *e8m0, uint32_t *group_mantissa)
 {
     int64_t pr, pc, gr, gc, P;
+    double m_g = 1.0, m_g5 = 1.0;
     if (rows <= 0 || cols <= 0 || ld < cols || part_shape(gran, rows, cols, &pr, &pc)) return -1;
+    if (scaling < SCALING_FP32_AMAX || scaling > SCALING_E8M0) return -1;
     gr = rows / pr; gc = cols / pc; P = gr * gc;
+
+    if (scaling == SCALING_GAM) {          /* the group loop of Algorithm 1, one group */
+        uint16_t g = 0;
+        float g_amax;
+        for (int64_t r = 0; r < rows; ++r)
+            for (int64_t c = 0; c < cols; ++c) {
+                uint16_t m = (uint16_t)(x[r * ld + c] & 0x7FFFu);
+                if (m > g) g = m;
+            }
+        g_amax = bf16_to_f32(g);
+        m_g = mor_oracle_group_mantissa(g_amax, 448.0f, scaling);
+        m_g5 = mor_oracle_group_mantissa(g_amax, 57344.0f, scaling);
+    }
+    if (group_mantissa) *group_mantissa = (uint32_t)ldexp(m_g - 1.0, 23);
 
 #pragma omp parallel for schedule(dynamic, 16) if (P > 1)
     for (int64_t p = 0; p < P; ++p) {
         int64_t br = p / gc, bc = p % gc;
         block_result res;
-        analyze_block(x + br * pr * ld + bc * pc, ld, pr, pc, crit,
+        analyze_block(x + br * pr * ld + bc * pc, ld, pr, pc, crit, scaling, m_g, m_g5,
                       fp8 + br * pr * cols + bc * pc, cols, &res);
+        if (e8m0) e8m0[p] = (uint8_t)res.e8m0;
         scale[p] = res.scale; amax[p] = res.amax; err_sum[p] = res.err_sum; nnz[p] = res.nnz;
         if (err5_sum) err5_sum[p] = res.err5_sum;
         if (err_sum_unscaled) err_sum_unscaled[p] = res.err_sum_unscaled;
@@ -310,6 +394,18 @@ int mor_oracle_analyze_quantize(const uint16_t *x, int64_t rows, int64_t cols, i
         }
     }
     return 0;
+}
+
+/* FP32 amax scaling (the hot path's default). */
+int mor_oracle_analyze_quantize(const uint16_t *x, int64_t rows, int64_t cols, int64_t ld,
+                                int gran, int scope, int crit, float threshold,
+                                uint8_t *fp8, uint16_t *bf16,
+                                float *scale, float *amax, double *err_sum, uint32_t *nnz,
+                                uint8_t *mask, double *err5_sum, double *err_sum_unscaled)
+{
+    return mor_oracle_analyze_quantize_ex(x, rows, cols, ld, gran, scope, crit, SCALING_FP32_AMAX,
+                                          threshold, fp8, bf16, scale, amax, err_sum, nnz, mask,
+                                          err5_sum, err_sum_unscaled, NULL, NULL);
 }
 
 /*

@@ -20,6 +20,7 @@ _LIB = os.path.join(_HERE, "libmor_oracle.so")
 GRAN = {"tensor": 0, "sub1x128": 1, "block128": 2}
 CRIT = {"mean_rel_err": 0, "e4m3_vs_e5m2": 1}
 SCOPE = {"partition": 0, "tensor": 1}
+SCALING = {"fp32_amax": 0, "gam": 1, "e8m0": 2}
 
 
 def build(force: bool = False) -> str:
@@ -59,6 +60,15 @@ def lib():
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
             C.c_void_p, C.c_void_p]
         L.mor_oracle_analyze_quantize.restype = C.c_int
+        L.mor_oracle_analyze_quantize_ex.argtypes = [
+            C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.mor_oracle_analyze_quantize_ex.restype = C.c_int
+        L.mor_oracle_group_mantissa.argtypes = [C.c_float, C.c_float, C.c_int]
+        L.mor_oracle_group_mantissa.restype = C.c_double
+        L.mor_oracle_gam_block_scale.argtypes = [C.c_float, C.c_float, C.c_double, C.POINTER(C.c_int)]
+        L.mor_oracle_gam_block_scale.restype = C.c_float
         L.mor_oracle_dequantize.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_int64, C.c_int64, C.c_int, C.c_void_p]
         L.mor_oracle_dequantize.restype = C.c_int
@@ -110,6 +120,18 @@ def scale(amax: float, q_amax: float = 448.0) -> float:
     return float(lib().mor_oracle_scale(float(np.float32(amax)), float(q_amax)))
 
 
+def group_mantissa(g_amax: float, q_amax: float = 448.0, scaling: str = "gam") -> float:
+    """m_g of Algorithm 1 as a number in [1, 2)."""
+    return float(lib().mor_oracle_group_mantissa(float(np.float32(g_amax)), float(q_amax), SCALING[scaling]))
+
+
+def gam_block_scale(b_amax: float, m_g: float, q_amax: float = 448.0) -> tuple[float, int]:
+    """Applied scale m_g * 2^e and the exponent e of one block (Algorithm 1, block loop)."""
+    e = C.c_int(0)
+    s = lib().mor_oracle_gam_block_scale(float(np.float32(b_amax)), float(q_amax), float(m_g), C.byref(e))
+    return float(s), int(e.value)
+
+
 def num_partitions(gran: str, rows: int, cols: int) -> int:
     return int(lib().mor_oracle_num_partitions(GRAN[gran], rows, cols))
 
@@ -129,6 +151,8 @@ class Analysis:
     mask: np.ndarray           # (P,) uint8, 0 = E4M3, 1 = BF16
     err5_sum: np.ndarray       # (P,) float64 (zeros unless criterion is e4m3_vs_e5m2)
     err_sum_unscaled: np.ndarray  # (P,) float64, Eq. (2) evaluated in the unscaled domain
+    e8m0: np.ndarray | None = None          # (P,) uint8 block exponents + 127 (GAM / E8M0 scaling)
+    group_mantissa: int | None = None       # 23 fraction bits of m_g (GAM / E8M0 scaling)
 
     def metric(self) -> np.ndarray:
         n = self.nnz.astype(np.float64)
@@ -138,7 +162,7 @@ class Analysis:
 
 def analyze_quantize(x: np.ndarray, gran: str, scope: str = "partition", crit: str = "mean_rel_err",
                      threshold: float = 0.045, bf16_fill: int = 0, ld: int | None = None,
-                     cols: int | None = None) -> Analysis:
+                     cols: int | None = None, scaling: str = "fp32_amax") -> Analysis:
     """Run the oracle on BF16 bit patterns ``x`` (2-D uint16).  ``ld``/``cols`` allow a padded
     leading dimension: ``x`` is then (rows, ld) and only the first ``cols`` columns are used."""
     x = np.ascontiguousarray(x, dtype=np.uint16)
@@ -153,12 +177,21 @@ def analyze_quantize(x: np.ndarray, gran: str, scope: str = "partition", crit: s
     sc = np.zeros(P, np.float32); am = np.zeros(P, np.float32)
     es = np.zeros(P, np.float64); e5 = np.zeros(P, np.float64); eu = np.zeros(P, np.float64)
     nz = np.zeros(P, np.uint32); mk = np.zeros(P, np.uint8)
-    rc = lib().mor_oracle_analyze_quantize(
-        _p(x), rows, cols, ld, GRAN[gran], SCOPE[scope], CRIT[crit], float(np.float32(threshold)),
-        _p(fp8), _p(bf16), _p(sc), _p(am), _p(es), _p(nz), _p(mk), _p(e5), _p(eu))
+    if scaling == "fp32_amax":
+        rc = lib().mor_oracle_analyze_quantize(
+            _p(x), rows, cols, ld, GRAN[gran], SCOPE[scope], CRIT[crit], float(np.float32(threshold)),
+            _p(fp8), _p(bf16), _p(sc), _p(am), _p(es), _p(nz), _p(mk), _p(e5), _p(eu))
+        if rc != 0:
+            raise ValueError("mor_oracle_analyze_quantize rejected the arguments")
+        return Analysis(fp8, bf16, sc, am, es, nz, mk, e5, eu)
+    ex = np.zeros(P, np.uint8)
+    gm = np.zeros(1, np.uint32)
+    rc = lib().mor_oracle_analyze_quantize_ex(
+        _p(x), rows, cols, ld, GRAN[gran], SCOPE[scope], CRIT[crit], SCALING[scaling], float(np.float32(threshold)),
+        _p(fp8), _p(bf16), _p(sc), _p(am), _p(es), _p(nz), _p(mk), _p(e5), _p(eu), _p(ex), _p(gm))
     if rc != 0:
-        raise ValueError("mor_oracle_analyze_quantize rejected the arguments")
-    return Analysis(fp8, bf16, sc, am, es, nz, mk, e5, eu)
+        raise ValueError("mor_oracle_analyze_quantize_ex rejected the arguments")
+    return Analysis(fp8, bf16, sc, am, es, nz, mk, e5, eu, ex, int(gm[0]))
 
 
 def dequantize(fp8: np.ndarray, scale_: np.ndarray, mask: np.ndarray, bf16: np.ndarray | None,

@@ -83,15 +83,40 @@ def scale_of(amax, qmax):
     return np.float32(np.finfo(np.float32).max) if np.isinf(s) else s
 
 
-def analyze_block(bits, crit="mean_rel_err", threshold=0.045):
-    """bits: iterable of BF16 bit patterns of ONE block.  Returns dict with exact-rational sums."""
+def _mant_exp(v):
+    """v = m * 2^e with 1 <= m < 2, exactly, for a positive Fraction v."""
+    e = 0
+    while v >= 2 ** (e + 1):
+        e += 1
+    while v < Fraction(2) ** e:
+        e -= 1
+    return v / Fraction(2) ** e, e
+
+
+def gam_scale(b_amax, g_amax, qmax, e8m0_only=False):
+    """Algorithm 1 with one group, in exact rationals: (applied scale, exponent e, m_g)."""
+    m_g = Fraction(1) if e8m0_only else _mant_exp(Fraction(float(scale_of(g_amax, qmax))))[0]
+    m_b, e = _mant_exp(Fraction(float(scale_of(b_amax, qmax))))
+    if m_g > m_b:
+        e -= 1
+    return m_g * Fraction(2) ** e, e, m_g
+
+
+def analyze_block(bits, crit="mean_rel_err", threshold=0.045, scaling="fp32_amax", g_amax=None):
+    """bits: iterable of BF16 bit patterns of ONE block.  Returns dict with exact-rational sums.
+    scaling 'gam' / 'e8m0' take the block's scale from Algorithm 1 (g_amax = amax of the tensor)."""
     bits = [int(b) for b in bits]
     a = max(b & 0x7FFF for b in bits)
     amax = bf16_to_f32(a)
     out = {"amax": float(amax), "nnz": sum(1 for b in bits if b & 0x7FFF)}
 
     def run(qmax, ebits, mbits):
-        s = scale_of(amax, qmax)
+        if scaling == "fp32_amax":
+            s = scale_of(amax, qmax)
+        else:
+            sf = gam_scale(amax, amax if g_amax is None else g_amax, qmax, scaling == "e8m0")[0]
+            s = np.float32(float(sf))
+            assert Fraction(float(s)) == sf          # the applied scale is a binary32 number
         codes, total = [], Fraction(0)
         for b in bits:
             with np.errstate(over="ignore", under="ignore", invalid="ignore"):
