@@ -5,8 +5,8 @@
  * X into blocks, an ordered list of representation types and acceptance metrics,
  * and returns the quantized tensor X_Q plus per-block metadata D (Algorithm 2).
  * This library implements the recipe with the type list [E4M3, BF16]:
- * for every block it computes amax and an FP32 scale (Algorithm 1, in its plain
- * per-block FP32 form), quantizes to FP8 E4M3, evaluates the acceptance metric
+ * for every block it computes amax and a scale (Algorithm 1: plain per-block
+ * FP32 form, GAM, or E8M0 only), quantizes to FP8 E4M3, evaluates the acceptance metric
  * (Eq. 1-2 or Eq. 3) on the de-quantized values, and keeps either the FP8
  * payload or the original BF16 block.
  *
@@ -75,9 +75,18 @@ typedef enum {
 
 /* How the per-block scale is formed. */
 typedef enum {
-    MOR_SCALE_FP32_AMAX = 0     /* s = fl32(448 / amax), "standard per-block FP32 amax scaling"
+    MOR_SCALE_FP32_AMAX = 0,    /* s = fl32(448 / amax), "standard per-block FP32 amax scaling"
                                    (Section 4.1.2).  amax == 0 -> s = 1; an overflowing quotient
                                    -> s = FLT_MAX; non-finite amax -> s = 1. */
+    MOR_SCALE_GAM = 1,          /* Group Amax Mantissa scaling (Algorithm 1) with one group = the whole
+                                   operand: s_g = fl32(448 / amax of the operand), m_g = its mantissa;
+                                   per block s_b as above, e = exponent(s_b), lowered by one when
+                                   m_g > mantissa(s_b); applied scale s = m_g * 2^e (s_b/2 < s <= s_b).
+                                   Stored form: one 23-bit mantissa + one E8M0 byte per block.  The
+                                   operand is read once more for its amax (Section 3.1, Figure 2).
+                                   For Eq. (3) the E5M2 side uses its own m_g from 57344 / amax. */
+    MOR_SCALE_E8M0 = 2          /* E8M0-only per-block scaling (ablation of Section 4.1.2): the power of
+                                   two 2^exponent(s_b), i.e. the above with m_g = 1; no extra read. */
 } mor_scaling;
 
 typedef struct mor_params {
@@ -106,6 +115,11 @@ typedef struct mor_outputs {
     uint8_t*  mask;     /* [P] 0 = E4M3, 1 = BF16 */
     float*    err5_sum; /* [P] the same error sum for E5M2 with s5 = fl32(57344 / amax); required
                            for MOR_CRIT_E4M3_VS_E5M2, otherwise ignored and may be NULL */
+    uint8_t*  scale_e8m0;     /* [P] MOR_SCALE_GAM / MOR_SCALE_E8M0: biased exponent (bias 127) of scale[p];
+                                 optional (NULL = not written); untouched for MOR_SCALE_FP32_AMAX */
+    uint32_t* group_mantissa; /* [1] MOR_SCALE_GAM / MOR_SCALE_E8M0: the 23 fraction bits of m_g (0 for
+                                 E8M0-only), so that scale[p] == bits((scale_e8m0[p] << 23) | group_mantissa);
+                                 optional; untouched for MOR_SCALE_FP32_AMAX */
 } mor_outputs;
 
 /* Selection statistics (Section 4.1.3). Lives in DEVICE memory; 8-byte aligned. */
@@ -209,6 +223,17 @@ mor_status mor_dequantize(const mor_params* params, const uint8_t* fp8, int64_t 
                           const float* scale, const uint8_t* mask,
                           const uint16_t* bf16, int64_t ld_bf16,
                           uint16_t* y, int64_t ld_y, void* stream);
+
+/*
+ * The same from the stored form of GAM / E8M0 scaling (Algorithm 1 and the paragraph before it: the
+ * per-block scale is rebuilt on the fly from the shared 23-bit group mantissa and the block's 8-bit
+ * exponent): scale[p] = bits((scale_e8m0[p] << 23) | group_mantissa[0]).  scale_e8m0 [P] and
+ * group_mantissa [1] are device arrays as written by mor_analyze_quantize.
+ */
+mor_status mor_dequantize_e8m0(const mor_params* params, const uint8_t* fp8, int64_t ld_fp8,
+                               const uint8_t* scale_e8m0, const uint32_t* group_mantissa, const uint8_t* mask,
+                               const uint16_t* bf16, int64_t ld_bf16,
+                               uint16_t* y, int64_t ld_y, void* stream);
 
 /*
  * Selection statistics of one analysed operand (Section 4.1.3): counts of blocks and elements

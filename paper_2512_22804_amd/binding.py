@@ -19,14 +19,15 @@ MOR_GRAN_TENSOR, MOR_GRAN_SUB_1x128, MOR_GRAN_BLOCK_128x128 = 0, 1, 2
 MOR_FMT_E4M3, MOR_FMT_E5M2, MOR_FMT_BF16 = 1, 2, 4
 MOR_CRIT_MEAN_REL_ERR, MOR_CRIT_E4M3_VS_E5M2 = 0, 1
 MOR_SCOPE_PARTITION, MOR_SCOPE_TENSOR = 0, 1
-MOR_SCALE_FP32_AMAX = 0
+MOR_SCALE_FP32_AMAX, MOR_SCALE_GAM, MOR_SCALE_E8M0 = 0, 1, 2
 
 GRAN = {"tensor": MOR_GRAN_TENSOR, "sub1x128": MOR_GRAN_SUB_1x128, "block128": MOR_GRAN_BLOCK_128x128}
 CRIT = {"mean_rel_err": MOR_CRIT_MEAN_REL_ERR, "e4m3_vs_e5m2": MOR_CRIT_E4M3_VS_E5M2}
 SCOPE = {"partition": MOR_SCOPE_PARTITION, "tensor": MOR_SCOPE_TENSOR}
+SCALING = {"fp32_amax": MOR_SCALE_FP32_AMAX, "gam": MOR_SCALE_GAM, "e8m0": MOR_SCALE_E8M0}
 
 EXPORTS = ("mor_num_partitions", "mor_workspace_bytes", "mor_analyze_quantize", "mor_analyze_quantize_profiled",
-           "mor_batch_workspace_bytes", "mor_analyze_quantize_batch", "mor_dequantize", "mor_select_stats",
+           "mor_batch_workspace_bytes", "mor_analyze_quantize_batch", "mor_dequantize", "mor_dequantize_e8m0", "mor_select_stats",
            "mor_status_string")
 MOR_BATCH_MAX = 64
 MOR_STATS_FLAG_FUSED_FALLBACK = 1
@@ -45,7 +46,7 @@ class MorParams(C.Structure):
 class MorOutputs(C.Structure):
     _fields_ = [("fp8", C.c_void_p), ("ld_fp8", C.c_int64), ("bf16", C.c_void_p), ("ld_bf16", C.c_int64),
                 ("scale", C.c_void_p), ("amax", C.c_void_p), ("err_sum", C.c_void_p), ("nnz", C.c_void_p),
-                ("mask", C.c_void_p), ("err5_sum", C.c_void_p)]
+                ("mask", C.c_void_p), ("err5_sum", C.c_void_p), ("scale_e8m0", C.c_void_p), ("group_mantissa", C.c_void_p)]
 
 
 class MorStats(C.Structure):
@@ -99,6 +100,9 @@ def load():
         L.mor_dequantize.argtypes = [C.POINTER(MorParams), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_int64, C.c_void_p, C.c_int64, C.c_void_p]
         L.mor_dequantize.restype = C.c_int
+        L.mor_dequantize_e8m0.argtypes = [C.POINTER(MorParams), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p]
+        L.mor_dequantize_e8m0.restype = C.c_int
         L.mor_select_stats.argtypes = [C.POINTER(MorParams), C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p,
                                        C.c_void_p]
         L.mor_select_stats.restype = C.c_int
@@ -110,11 +114,12 @@ def load():
 
 def make_params(rows: int, cols: int, gran: str | int, scope: str | int = "partition", crit: str | int = "mean_rel_err",
                 threshold: float = 0.045, ld: int | None = None, formats: int = MOR_FMT_E4M3 | MOR_FMT_BF16,
-                scaling: int = MOR_SCALE_FP32_AMAX) -> MorParams:
+                scaling: str | int = MOR_SCALE_FP32_AMAX) -> MorParams:
     g = GRAN[gran] if isinstance(gran, str) else gran
     s = SCOPE[scope] if isinstance(scope, str) else scope
     c = CRIT[crit] if isinstance(crit, str) else crit
-    return MorParams(rows, cols, cols if ld is None else ld, g, s, c, scaling, formats, threshold)
+    sc = SCALING[scaling] if isinstance(scaling, str) else scaling
+    return MorParams(rows, cols, cols if ld is None else ld, g, s, c, sc, formats, threshold)
 
 
 def mor_num_partitions(gran: str | int, rows: int, cols: int) -> int:
@@ -147,6 +152,8 @@ class MorResult:
     err5_sum: torch.Tensor | None
     workspace: torch.Tensor | None
     params: MorParams
+    scale_e8m0: torch.Tensor | None = None      # (P,) uint8, GAM / E8M0 scaling only
+    group_mantissa: torch.Tensor | None = None  # (1,) int32, GAM / E8M0 scaling only
 
 
 def alloc_outputs(params: MorParams, device, want_bf16: bool = True, bf16_fill: int | None = None) -> MorResult:
@@ -164,13 +171,18 @@ def alloc_outputs(params: MorParams, device, want_bf16: bool = True, bf16_fill: 
     err5 = f32() if params.criterion == MOR_CRIT_E4M3_VS_E5M2 else None
     nbytes = mor_workspace_bytes(params)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=device) if nbytes else None
+    e8m0 = gmant = None
+    if params.scaling != MOR_SCALE_FP32_AMAX:
+        e8m0 = torch.full((P,), 0xEE, dtype=torch.uint8, device=device)
+        gmant = torch.full((1,), -1, dtype=torch.int32, device=device)
     return MorResult(fp8, bf16, f32(), f32(), f32(), torch.empty(P, dtype=torch.int32, device=device),
-                     torch.empty(P, dtype=torch.uint8, device=device), err5, ws, params)
+                     torch.empty(P, dtype=torch.uint8, device=device), err5, ws, params, e8m0, gmant)
 
 
 def _outputs_struct(out: MorResult) -> MorOutputs:
     return MorOutputs(_ptr(out.fp8), out.fp8.stride(0), _ptr(out.bf16), out.bf16.stride(0) if out.bf16 is not None else 0,
-                      _ptr(out.scale), _ptr(out.amax), _ptr(out.err_sum), _ptr(out.nnz), _ptr(out.mask), _ptr(out.err5_sum))
+                      _ptr(out.scale), _ptr(out.amax), _ptr(out.err_sum), _ptr(out.nnz), _ptr(out.mask), _ptr(out.err5_sum),
+                      _ptr(out.scale_e8m0), _ptr(out.group_mantissa))
 
 
 def mor_analyze_quantize(params: MorParams, x: torch.Tensor, out: MorResult) -> None:
@@ -278,6 +290,16 @@ def mor_dequantize(params: MorParams, fp8: torch.Tensor, scale: torch.Tensor, ma
                                bf16.stride(0) if bf16 is not None else 0, _ptr(y), y.stride(0), _stream())
     if rc != 0:
         raise MorError(rc, "mor_dequantize")
+
+
+def mor_dequantize_e8m0(params: MorParams, fp8: torch.Tensor, scale_e8m0: torch.Tensor, group_mantissa: torch.Tensor,
+                        mask: torch.Tensor, bf16: torch.Tensor | None, y: torch.Tensor) -> None:
+    """De-quantize from the stored form of GAM / E8M0 scaling (one byte per block + one shared mantissa)."""
+    rc = load().mor_dequantize_e8m0(C.byref(params), _ptr(fp8), fp8.stride(0), _ptr(scale_e8m0), _ptr(group_mantissa),
+                                    _ptr(mask), _ptr(bf16), bf16.stride(0) if bf16 is not None else 0, _ptr(y),
+                                    y.stride(0), _stream())
+    if rc != 0:
+        raise MorError(rc, "mor_dequantize_e8m0")
 
 
 def mor_select_stats(params: MorParams, err_sum: torch.Tensor, nnz: torch.Tensor, mask: torch.Tensor,

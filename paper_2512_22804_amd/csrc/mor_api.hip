@@ -44,7 +44,7 @@ static mor_status make_item(const mor_params* p, const uint16_t* x, const mor_ou
     if (st != MOR_OK) return st;
     if (p->scope != MOR_SCOPE_PARTITION && p->scope != MOR_SCOPE_TENSOR) return MOR_ERR_UNSUPPORTED;
     if (p->criterion != MOR_CRIT_MEAN_REL_ERR && p->criterion != MOR_CRIT_E4M3_VS_E5M2) return MOR_ERR_UNSUPPORTED;
-    if (p->scaling != MOR_SCALE_FP32_AMAX) return MOR_ERR_UNSUPPORTED;
+    if (p->scaling < MOR_SCALE_FP32_AMAX || p->scaling > MOR_SCALE_E8M0) return MOR_ERR_UNSUPPORTED;
     if (p->formats != (MOR_FMT_E4M3 | MOR_FMT_BF16)) return MOR_ERR_UNSUPPORTED;
     if (!out->fp8 || !out->scale || !out->amax || !out->err_sum || !out->nnz || !out->mask) return MOR_ERR_NULL;
     if (p->criterion == MOR_CRIT_E4M3_VS_E5M2 && !out->err5_sum) return MOR_ERR_NULL;
@@ -57,12 +57,15 @@ static mor_status make_item(const mor_params* p, const uint16_t* x, const mor_ou
     if ((reinterpret_cast<uintptr_t>(out->scale) | reinterpret_cast<uintptr_t>(out->amax) |
          reinterpret_cast<uintptr_t>(out->err_sum) | reinterpret_cast<uintptr_t>(out->nnz)) & 3u) return MOR_ERR_ALIGN;
     if (stats && (reinterpret_cast<uintptr_t>(stats) & 7u)) return MOR_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(out->group_mantissa) & 3u) return MOR_ERR_ALIGN;
     item->sh = mor::KShape{p->rows, p->cols, p->ld};
     item->o = mor::KOut{out->fp8, out->ld_fp8, want_bf16 ? out->bf16 : nullptr, want_bf16 ? out->ld_bf16 : p->cols,
-                        out->scale, out->amax, out->err_sum, out->nnz, out->mask, out->err5_sum};
+                        out->scale, out->amax, out->err_sum, out->nnz, out->mask, out->err5_sum,
+                        out->scale_e8m0, out->group_mantissa};
     item->x = x;
     item->gran = p->granularity;
     item->crit = p->criterion;
+    item->scaling = p->scaling;
     item->scope = p->granularity == MOR_GRAN_TENSOR ? MOR_SCOPE_PARTITION : p->scope;
     item->th = p->threshold;
     item->stats = stats;
@@ -76,6 +79,7 @@ size_t mor_workspace_bytes(const mor_params* p) {
     it.gran = p->granularity;
     it.scope = p->granularity == MOR_GRAN_TENSOR ? MOR_SCOPE_PARTITION : p->scope;
     it.o.ld_fp8 = p->cols;
+    it.scaling = p->scaling;
     return mor::batch_workspace_bytes(&it, 1);
 }
 
@@ -127,6 +131,7 @@ mor_status mor_analyze_quantize_batch(const mor_batch_item* items, int32_t n_ite
                                       size_t workspace_bytes, void* stream, mor_profile* profile) {
     if (!items) return MOR_ERR_NULL;
     if (n_items <= 0 || n_items > MOR_BATCH_MAX) return MOR_ERR_SHAPE;
+    static_assert(MOR_BATCH_MAX == mor::kBatchMax, "batch limit");
     mor::BatchItem its[MOR_BATCH_MAX];
     for (int32_t i = 0; i < n_items; ++i) {
         mor_status st = make_item(&items[i].params, items[i].x, &items[i].out, items[i].stats, &its[i]);
@@ -135,18 +140,33 @@ mor_status mor_analyze_quantize_batch(const mor_batch_item* items, int32_t n_ite
     return run_batch(its, n_items, near_tol, workspace, workspace_bytes, stream, profile);
 }
 
-mor_status mor_dequantize(const mor_params* p, const uint8_t* fp8, int64_t ld_fp8, const float* scale, const uint8_t* mask,
-                          const uint16_t* bf16, int64_t ld_bf16, uint16_t* y, int64_t ld_y, void* stream) {
-    if (!p || !fp8 || !scale || !mask || !y) return MOR_ERR_NULL;
+static mor_status dequantize_any(const mor_params* p, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
+                                 const uint8_t* e8m0, const uint32_t* gmant, const uint8_t* mask, const uint16_t* bf16,
+                                 int64_t ld_bf16, uint16_t* y, int64_t ld_y, void* stream) {
+    if (!p || !fp8 || !mask || !y) return MOR_ERR_NULL;
+    if (!scale && !(e8m0 && gmant)) return MOR_ERR_NULL;
     mor_status st = check_common(p);
     if (st != MOR_OK) return st;
     if (ld_fp8 < p->cols || ld_y < p->cols || (bf16 && ld_bf16 < p->cols)) return MOR_ERR_SHAPE;
     if (ld_fp8 % 8 || ld_y % 8 || (bf16 && ld_bf16 % 8)) return MOR_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(fp8) & 7u) || !aligned16(y) || (bf16 && !aligned16(bf16))) return MOR_ERR_ALIGN;
-    if (reinterpret_cast<uintptr_t>(scale) & 3u) return MOR_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(scale) | reinterpret_cast<uintptr_t>(gmant)) & 3u) return MOR_ERR_ALIGN;
     hipError_t e = mor::launch_dequantize(p->granularity, p->rows, p->cols, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y,
-                                          static_cast<hipStream_t>(stream));
+                                          e8m0, gmant, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? MOR_OK : MOR_ERR_HIP;
+}
+
+mor_status mor_dequantize(const mor_params* p, const uint8_t* fp8, int64_t ld_fp8, const float* scale, const uint8_t* mask,
+                          const uint16_t* bf16, int64_t ld_bf16, uint16_t* y, int64_t ld_y, void* stream) {
+    if (!scale) return MOR_ERR_NULL;
+    return dequantize_any(p, fp8, ld_fp8, scale, nullptr, nullptr, mask, bf16, ld_bf16, y, ld_y, stream);
+}
+
+mor_status mor_dequantize_e8m0(const mor_params* p, const uint8_t* fp8, int64_t ld_fp8, const uint8_t* scale_e8m0,
+                               const uint32_t* group_mantissa, const uint8_t* mask, const uint16_t* bf16, int64_t ld_bf16,
+                               uint16_t* y, int64_t ld_y, void* stream) {
+    if (!scale_e8m0 || !group_mantissa) return MOR_ERR_NULL;
+    return dequantize_any(p, fp8, ld_fp8, nullptr, scale_e8m0, group_mantissa, mask, bf16, ld_bf16, y, ld_y, stream);
 }
 
 mor_status mor_select_stats(const mor_params* p, const float* err_sum, const uint32_t* nnz, const uint8_t* mask, float near_tol,

@@ -42,6 +42,26 @@ __device__ __forceinline__ float scale_from_amax_bits(uint32_t abits, float q_am
     return __builtin_fminf(s, kFltMax);                // +inf -> FLT_MAX
 }
 
+// Scaling algorithms.  kScaleFp32: the scale above.  kScaleGam (Algorithm 1 with one group per tensor):
+// the block keeps the exponent of its ideal scale s_b, lowered by one when the group's mantissa m_g
+// exceeds the block's own m_b, and takes m_g as its mantissa, so the applied scale m_g * 2^e never
+// exceeds s_b and is more than s_b / 2.  kScaleE8M0: the same with m_g = 1, a pure power of two.
+// `mg` holds the 23 fraction bits of m_g.
+enum { kScaleFp32 = 0, kScaleGam = 1, kScaleE8M0 = 2 };
+__device__ __forceinline__ uint32_t group_mantissa_bits(uint32_t group_abits, float q_amax, uint32_t mode) {
+    return mode == kScaleGam ? (__float_as_uint(scale_from_amax_bits(group_abits, q_amax)) & 0x7FFFFFu) : 0u;
+}
+__device__ __forceinline__ float block_scale(uint32_t abits, float q_amax, uint32_t mode, uint32_t mg) {
+    const float s_b = scale_from_amax_bits(abits, q_amax);
+    if (mode == kScaleFp32) return s_b;
+    const uint32_t b = __float_as_uint(s_b);                 // positive, normal: s_b >= 448 / BF16max > 2^-120
+    const uint32_t e = (b >> 23) - ((mg > (b & 0x7FFFFFu)) ? 1u : 0u);
+    return __uint_as_float((e << 23) | mg);
+}
+// With a scale of up to one binade below s_b, the smallest BF16 subnormal times the scale can round to a
+// binary32 zero one binade of amax earlier, so the branch-free path ends at 2^24 instead of 2^25.
+__device__ __forceinline__ uint32_t fast_amax_limit(uint32_t mode) { return mode == kScaleFp32 ? kFastAmaxBits : kFastAmaxBits - 0x80u; }
+
 // ---- per-lane summary of 8 BF16 values held in a u32x4: packed amax and non-zero count
 struct Scan8 {
     uint32_t amax2;   // two u16 running maxima of (bits & 0x7FFF)

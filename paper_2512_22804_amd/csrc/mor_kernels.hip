@@ -20,24 +20,24 @@ enum { kCritEq2 = 0, kCritEq3 = 1 };
 template <int CRIT, bool DEFER>
 __device__ __forceinline__ void sub_block_body(const u32x4& raw, const uint16_t* __restrict__ src, int l, int64_t p,
                                                const KOut& o, uint8_t* __restrict__ dst_fp8, uint16_t* __restrict__ dst_bf16,
-                                               float th) {
+                                               float th, uint32_t mode, uint32_t mg, uint32_t mg5) {
     Scan8 sc{0u, 0u};
     scan8(raw, sc);
     const uint32_t abits = row_allmax_u32(fold_max16(sc.amax2));
-    const float s = scale_from_amax_bits(abits, kE4M3Max);
+    const float s = block_scale(abits, kE4M3Max, mode, mg);
     float e, e5 = 0.0f;
-    if (abits < kFastAmaxBits) {
+    if (abits < fast_amax_limit(mode)) {
         float e0 = 0.0f, e1 = 0.0f;
         store8(dst_fp8, quant8_fast<false>(raw, s, e0, e1));
         e = e0 + e1;
         if constexpr (CRIT == kCritEq3) {
             float f0 = 0.0f, f1 = 0.0f;
-            (void)quant8_fast<true>(raw, scale_from_amax_bits(abits, kE5M2Max), f0, f1);
+            (void)quant8_fast<true>(raw, block_scale(abits, kE5M2Max, mode, mg5), f0, f1);
             e5 = f0 + f1;
         }
     } else {
         e = quant8_careful_mem<false>(src, s, dst_fp8);
-        if constexpr (CRIT == kCritEq3) e5 = quant8_careful_mem<true>(src, scale_from_amax_bits(abits, kE5M2Max), nullptr);
+        if constexpr (CRIT == kCritEq3) e5 = quant8_careful_mem<true>(src, block_scale(abits, kE5M2Max, mode, mg5), nullptr);
     }
     float err = row_allsum_f32(e);
     const uint32_t nnz = 128u - row_allsum_u32(fold_add16(sc.zero2));
@@ -53,6 +53,7 @@ __device__ __forceinline__ void sub_block_body(const u32x4& raw, const uint16_t*
         o.nnz[p] = nnz;
         if constexpr (CRIT == kCritEq3) o.err5_sum[p] = err5;
         if constexpr (!DEFER) o.mask[p] = (uint8_t)mask;
+        if (mode != kScaleFp32 && o.e8m0) o.e8m0[p] = (uint8_t)(__float_as_uint(s) >> 23);
     }
     if constexpr (!DEFER) {
         if (mask && dst_bf16) store16(dst_bf16, raw);
@@ -112,7 +113,7 @@ __device__ __forceinline__ void sub_unit_careful(const uint16_t* __restrict__ xl
 // block g*8+j, so the per-block work (division, decision, metadata) runs once per 8 blocks.
 template <int CRIT>
 __device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const uint16_t* __restrict__ x, const KOut& o, int64_t unit,
-                                                 int lane, float th, bool defer) {
+                                                 int lane, float th, bool defer, uint32_t mode, uint32_t mg, uint32_t mg5) {
     const int g = lane >> 4, l = lane & 15, own = l & 7;
     const int64_t prow = unit * 32 + g * 8;
     const int64_t off = prow * 128 + l * 8;
@@ -145,12 +146,12 @@ __device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const ui
     zp0 = row_allsum_u32(zp0);        // byte sums <= 128: no carry between bytes
     zp1 = row_allsum_u32(zp1);
     const uint32_t my_zero = (((own & 4) ? zp1 : zp0) >> (8 * (own & 3))) & 0xFFu;
-    const float my_s = scale_from_amax_bits(my_abits, kE4M3Max);
+    const float my_s = block_scale(my_abits, kE4M3Max, mode, mg);
     float my_s5 = 0.0f;
-    if constexpr (CRIT == kCritEq3) my_s5 = scale_from_amax_bits(my_abits, kE5M2Max);
+    if constexpr (CRIT == kCritEq3) my_s5 = block_scale(my_abits, kE5M2Max, mode, mg5);
     // phase 2: quantize with the owner's scale, reduce the error terms to the owner
     float my_err = 0.0f, my_err5 = 0.0f;
-    if (__any(amax_unit >= kFastAmaxBits)) {
+    if (__any(amax_unit >= fast_amax_limit(mode))) {
         sub_unit_careful<CRIT>(x + off, fl, lane, my_s, my_s5, my_err, my_err5);
     } else {
         float e[8], e5[8];
@@ -190,6 +191,7 @@ __device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const ui
         o.nnz[p] = 128u - my_zero;
         if constexpr (CRIT == kCritEq3) o.err5_sum[p] = my_err5;
         if (!defer) o.mask[p] = (uint8_t)my_mask;
+        if (mode != kScaleFp32 && o.e8m0) o.e8m0[p] = (uint8_t)(__float_as_uint(my_s) >> 23);
     }
     if (!defer && o.bf16) {
         const unsigned long long want = __ballot(l < 8 && my_mask != 0u);
@@ -205,14 +207,16 @@ __device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const ui
 
 // Strided operands: grid.x = 128-column block, grid.y strides over groups of 16 rows.
 template <int CRIT, bool DEFER>
-__global__ __launch_bounds__(256) void k_sub1x128_strided(const uint16_t* __restrict__ x, KShape sh, KOut o, float th) {
+__global__ __launch_bounds__(256) void k_sub1x128_strided(const uint16_t* __restrict__ x, KShape sh, KOut o, float th,
+                                                          uint32_t mode, const uint32_t* __restrict__ gam) {
     const int lane = threadIdx.x & 63, g = lane >> 4, l = lane & 15;
+    const uint32_t mg = mode ? gam[0] : 0u, mg5 = mode ? gam[1] : 0u;
     const int64_t cb = blockIdx.x, cpr = sh.cols / 128;
     for (int64_t r = (int64_t)blockIdx.y * 16 + (threadIdx.x >> 6) * 4 + g; r < sh.rows; r += (int64_t)gridDim.y * 16) {
         const uint16_t* src = x + r * sh.ld + cb * 128 + l * 8;
         const u32x4 raw = load16(src);
         sub_block_body<CRIT, DEFER>(raw, src, l, r * cpr + cb, o, o.fp8 + r * o.ld_fp8 + cb * 128 + l * 8,
-                                    o.bf16 ? o.bf16 + r * o.ld_bf16 + cb * 128 + l * 8 : nullptr, th);
+                                    o.bf16 ? o.bf16 + r * o.ld_bf16 + cb * 128 + l * 8 : nullptr, th, mode, mg, mg5);
     }
 }
 
@@ -331,12 +335,13 @@ __device__ __forceinline__ void tensor_publish(const TensorAcc& a, const TensorP
 template <int CRIT>
 __global__ __launch_bounds__(256) void k_tensor_quant_strided(const uint16_t* __restrict__ x, KShape sh, uint32_t tiles_x,
                                                               uint32_t n_tiles, KOut o, const uint32_t* __restrict__ amax_part,
-                                                              int n_amax_part, TensorPartials tp) {
+                                                              int n_amax_part, TensorPartials tp, uint32_t mode) {
     __shared__ uint32_t sh4[4];
     const uint32_t abits = global_amax_bits(amax_part, n_amax_part, sh4);
     if (blockIdx.x == 0 && threadIdx.x == 0) tp.abits[0] = abits;
-    const float s = scale_from_amax_bits(abits, kE4M3Max);
-    const float s5 = (CRIT == kCritEq3) ? scale_from_amax_bits(abits, kE5M2Max) : 0.0f;
+    // one block = the group: under GAM the block's own mantissa is the group mantissa, the scale is s_b
+    const float s = block_scale(abits, kE4M3Max, mode, group_mantissa_bits(abits, kE4M3Max, mode));
+    const float s5 = (CRIT == kCritEq3) ? block_scale(abits, kE5M2Max, mode, group_mantissa_bits(abits, kE5M2Max, mode)) : 0.0f;
     TensorAcc acc{0.0f, 0.0f, 0.0f, 0.0f, 0u};
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const uint32_t ty = tile / tiles_x, tx = tile - ty * tiles_x;
@@ -346,7 +351,7 @@ __global__ __launch_bounds__(256) void k_tensor_quant_strided(const uint16_t* __
         u32x4 raw; raw.x = 0u; raw.y = 0u; raw.z = 0u; raw.w = 0u;
         if (live) raw = load16(x + r * sh.ld + c);
         acc.zero2 = zero2_of(raw, acc.zero2);
-        if (abits < kFastAmaxBits) {
+        if (abits < fast_amax_limit(mode)) {
             const u32x2 codes = quant8_fast<false>(raw, s, acc.e0, acc.e1);
             if (live) store8(o.fp8 + r * o.ld_fp8 + c, codes);
             if constexpr (CRIT == kCritEq3) (void)quant8_fast<true>(raw, s5, acc.f0, acc.f1);
@@ -363,7 +368,7 @@ __global__ __launch_bounds__(256) void k_tensor_quant_strided(const uint16_t* __
 // (P = 1), and if the decision is BF16 the grid copies the operand into the fallback buffer.
 template <int CRIT>
 __global__ __launch_bounds__(256) void k_tensor_finish(TensorPartials tp, int n_slots, unsigned long long n_padded, KOut o, float th,
-                                                       const uint16_t* __restrict__ x, KShape sh, int flat) {
+                                                       const uint16_t* __restrict__ x, KShape sh, int flat, uint32_t mode) {
     __shared__ double shd[4];
     __shared__ unsigned long long shl[4];
     double se = 0.0, se5 = 0.0;
@@ -383,7 +388,11 @@ __global__ __launch_bounds__(256) void k_tensor_finish(TensorPartials tp, int n_
     if constexpr (CRIT == kCritEq3) mask = (se < se5) ? 0u : 1u;
     else mask = ((n ? se / (double)n : 0.0) < (double)th) ? 0u : 1u;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        o.scale[0] = scale_from_amax_bits(abits, kE4M3Max);
+        const uint32_t mg = group_mantissa_bits(abits, kE4M3Max, mode);
+        const float s = block_scale(abits, kE4M3Max, mode, mg);
+        o.scale[0] = s;
+        if (mode != kScaleFp32 && o.e8m0) o.e8m0[0] = (uint8_t)(__float_as_uint(s) >> 23);
+        if (mode != kScaleFp32 && o.gmant) o.gmant[0] = mg;
         o.amax[0] = __uint_as_float(abits << 16);
         o.err_sum[0] = (float)se;
         o.nnz[0] = n > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)n;
@@ -499,7 +508,7 @@ template <int GRAN>
 __global__ __launch_bounds__(256) void k_dequant(int64_t rows, int64_t cols, const uint8_t* __restrict__ fp8, int64_t ld_fp8,
                                                  const float* __restrict__ scale, const uint8_t* __restrict__ mask,
                                                  const uint16_t* __restrict__ bf16, int64_t ld_bf16, uint16_t* __restrict__ y,
-                                                 int64_t ld_y) {
+                                                 int64_t ld_y, const uint8_t* __restrict__ e8m0, const uint32_t* __restrict__ gmant) {
     const int64_t cb = blockIdx.x, cpr = (cols + 127) / 128;
     const int64_t c = cb * 128 + (threadIdx.x & 15) * 8;
     if (c >= cols) return;
@@ -511,7 +520,9 @@ __global__ __launch_bounds__(256) void k_dequant(int64_t rows, int64_t cols, con
             if (bf16) store16(y + r * ld_y + c, load16(bf16 + r * ld_bf16 + c));
             continue;
         }
-        const float s_inv = 1.0f / scale[p];                        // correctly rounded IEEE division
+        // stored GAM form (Algorithm 1): the scale is rebuilt from the shared mantissa and the block's E8M0 byte
+        const float s = e8m0 ? __uint_as_float(((uint32_t)e8m0[p] << 23) | gmant[0]) : scale[p];
+        const float s_inv = 1.0f / s;                               // correctly rounded IEEE division
         const u32x2 q = *reinterpret_cast<const u32x2*>(fp8 + r * ld_fp8 + c);
         u32x4 out;
 #pragma unroll
@@ -651,6 +662,8 @@ struct GroupSub {
     KOut o[kMaxGroup];
     float th[kMaxGroup];
     uint8_t defer[kMaxGroup];             // 1: tensor-level decision follows, write no mask / fallback here
+    uint8_t mode[kMaxGroup];              // scaling algorithm
+    const uint32_t* gam[kMaxGroup];       // mode != 0: {mantissa for E4M3, mantissa for E5M2} of the operand's group
 };
 __device__ __forceinline__ int group_find(const int64_t* end, int n, int64_t v) {
     int i = 0;
@@ -675,12 +688,18 @@ __global__ __launch_bounds__(256) void k_sub1x128_group(GroupSub g) {
 #pragma unroll
         for (int k = 0; k < 8; ++k) raw[k] = load16(src + k * 128);
     };
+    auto process = [&](const u32x4 (&raw)[8], int op, int64_t local) {
+        const uint32_t mode = g.mode[op];
+        uint32_t mg = 0u, mg5 = 0u;
+        if (mode) { mg = g.gam[op][0]; if constexpr (CRIT == kCritEq3) mg5 = g.gam[op][1]; }
+        sub_unit_process<CRIT>(raw, g.x[op], g.o[op], local, lane, g.th[op], g.defer[op] != 0, mode, mg, mg5);
+    };
     int opA;
     int64_t locA;
     load_unit(bufA, u, opA, locA);
 #if !MOR_SUB_DOUBLE
     for (;;) {
-        sub_unit_process<CRIT>(bufA, g.x[opA], g.o[opA], locA, lane, g.th[opA], g.defer[opA] != 0);
+        process(bufA, opA, locA);
         u += W;
         if (u >= total) break;
         load_unit(bufA, u, opA, locA);
@@ -691,11 +710,11 @@ __global__ __launch_bounds__(256) void k_sub1x128_group(GroupSub g) {
     for (;;) {
         const int64_t ub = u + W;
         if (ub < total) load_unit(bufB, ub, opB, locB);
-        sub_unit_process<CRIT>(bufA, g.x[opA], g.o[opA], locA, lane, g.th[opA], g.defer[opA] != 0);
+        process(bufA, opA, locA);
         if (ub >= total) break;
         u = ub + W;
         if (u < total) load_unit(bufA, u, opA, locA);
-        sub_unit_process<CRIT>(bufB, g.x[opB], g.o[opB], locB, lane, g.th[opB], g.defer[opB] != 0);
+        process(bufB, opB, locB);
         if (u >= total) break;
     }
 #endif
@@ -710,6 +729,8 @@ struct GroupBlock {
     KOut o[kMaxGroup];
     float th[kMaxGroup];
     uint8_t defer[kMaxGroup];
+    uint8_t mode[kMaxGroup];
+    const uint32_t* gam[kMaxGroup];
 };
 // One 256-thread workgroup per 128x128 block (Section 4.1.1 "Per-Block"): the whole 32 KB tile lives in
 // registers (8 x 16 B per lane); LDS only carries 4 per-wave partials.
@@ -739,15 +760,18 @@ __global__ __launch_bounds__(256) void k_block128_group(GroupBlock g) {
     if (lane == 0) sh_amax[w] = wa;
     __syncthreads();
     const uint32_t abits = max(max(sh_amax[0], sh_amax[1]), max(sh_amax[2], sh_amax[3]));
-    const float s = scale_from_amax_bits(abits, kE4M3Max);
+    const uint32_t mode = g.mode[op];
+    uint32_t mg = 0u, mg5 = 0u;
+    if (mode) { mg = g.gam[op][0]; mg5 = g.gam[op][1]; }
+    const float s = block_scale(abits, kE4M3Max, mode, mg);
     float e, e5 = 0.0f;
-    if (abits < kFastAmaxBits) {
+    if (abits < fast_amax_limit(mode)) {
         float e0 = 0.0f, e1 = 0.0f;
 #pragma unroll
         for (int i = 0; i < 8; ++i) store8(dst + (int64_t)i * 16 * o.ld_fp8, quant8_fast<false>(raw[i], s, e0, e1));
         e = e0 + e1;
         if constexpr (CRIT == kCritEq3) {
-            const float s5 = scale_from_amax_bits(abits, kE5M2Max);
+            const float s5 = block_scale(abits, kE5M2Max, mode, mg5);
             float f0 = 0.0f, f1 = 0.0f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) (void)quant8_fast<true>(raw[i], s5, f0, f1);
@@ -759,7 +783,7 @@ __global__ __launch_bounds__(256) void k_block128_group(GroupBlock g) {
         for (int i = 0; i < 8; ++i) {
             e += quant8_careful_mem<false>(src + (int64_t)i * 16 * ld, s, dst + (int64_t)i * 16 * o.ld_fp8);
             if constexpr (CRIT == kCritEq3)
-                e5 += quant8_careful_mem<true>(src + (int64_t)i * 16 * ld, scale_from_amax_bits(abits, kE5M2Max), nullptr);
+                e5 += quant8_careful_mem<true>(src + (int64_t)i * 16 * ld, block_scale(abits, kE5M2Max, mode, mg5), nullptr);
         }
     }
     const float werr = wave_allsum_f32(e);
@@ -781,6 +805,7 @@ __global__ __launch_bounds__(256) void k_block128_group(GroupBlock g) {
         o.nnz[p] = nnz;
         if constexpr (CRIT == kCritEq3) o.err5_sum[p] = err5;
         if (!defer) o.mask[p] = (uint8_t)mask;
+        if (mode != kScaleFp32 && o.e8m0) o.e8m0[p] = (uint8_t)(__float_as_uint(s) >> 23);
     }
     if (mask && o.bf16) {
         uint16_t* __restrict__ dbf = o.bf16 + row0 * o.ld_bf16 + col;
@@ -795,6 +820,7 @@ struct TensorOp {
     int64_t n_chunks, n_tiles;
     KOut o;
     float th;
+    uint32_t mode;                       // scaling algorithm
     int n_amax, n_slots;                 // workgroups this operand gets in pass A / pass B
     uint32_t* amax_part;                 // [n_amax]
     float* err; float* err5; uint32_t* zero;   // [n_slots] each
@@ -902,8 +928,11 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
     const bool proven = tensor_fallback_proven(t, shl4);     // then the BF16 fallback is written in this sweep
     uint16_t* __restrict__ bf16 = t.o.bf16;
     if (b == 0 && threadIdx.x == 0) { t.abits[0] = abits; t.abits[1] = proven ? 1u : 0u; }
-    const float s = scale_from_amax_bits(abits, kE4M3Max);
-    const float s5 = (CRIT == kCritEq3) ? scale_from_amax_bits(abits, kE5M2Max) : 0.0f;
+    // one block = the group: under GAM the block's own mantissa is the group mantissa and the scale is s_b
+    const uint32_t mode = t.mode;
+    const float s = block_scale(abits, kE4M3Max, mode, group_mantissa_bits(abits, kE4M3Max, mode));
+    const float s5 = (CRIT == kCritEq3) ? block_scale(abits, kE5M2Max, mode, group_mantissa_bits(abits, kE5M2Max, mode)) : 0.0f;
+    const bool fast = abits < fast_amax_limit(mode);
     TensorAcc acc{0.0f, 0.0f, 0.0f, 0.0f, 0u};
     auto process = [&](const u32x4* raw, int64_t tile) {
         const int64_t c0 = tile * kTensorChunksPerBlock + threadIdx.x;
@@ -916,7 +945,7 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
                 if (c < n_chunks) store16(bf16 + c * 8, raw[u]);
             }
         }
-        if (abits < kFastAmaxBits) {
+        if (fast) {
 #pragma unroll
             for (int u = 0; u < kTensorChunksPerThread; ++u) {
                 const int64_t c = c0 + u * 256;
@@ -991,7 +1020,11 @@ __global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g) {
         const KOut& o = t.o;
         const float err_f = (float)se;
         const uint32_t nnz32 = n > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)n;
-        o.scale[0] = scale_from_amax_bits(abits, kE4M3Max);
+        const uint32_t mg = group_mantissa_bits(abits, kE4M3Max, t.mode);
+        const float s = block_scale(abits, kE4M3Max, t.mode, mg);
+        o.scale[0] = s;
+        if (t.mode != kScaleFp32 && o.e8m0) o.e8m0[0] = (uint8_t)(__float_as_uint(s) >> 23);
+        if (t.mode != kScaleFp32 && o.gmant) o.gmant[0] = mg;
         o.amax[0] = __uint_as_float(abits << 16);
         o.err_sum[0] = err_f;
         o.nnz[0] = nnz32;
@@ -1025,6 +1058,31 @@ __global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g) {
             for (int u = 0; u < 4; ++u)
                 if (c0 + u * 256 < t.n_chunks) store16(dst + (c0 + u * 256) * 8, load16(x + (c0 + u * 256) * 8));
         }
+    }
+}
+
+// Group loop of Algorithm 1 for sub-tensor operands: the operand's amax (partials of pass A) gives the
+// group mantissas for E4M3 and E5M2, which the block kernels read; also written to the caller's output.
+// E8M0-only operands have no amax pass (n_amax = 0) and a zero mantissa.
+struct GamOp {
+    const uint32_t* amax_part; int n_amax;
+    uint32_t mode;
+    uint32_t* gam;         // [2] workspace words read by the block kernels
+    uint32_t* gmant;       // caller's group-mantissa output, may be nullptr
+};
+struct GroupGam {
+    int n;
+    GamOp op[kMaxGroup];
+};
+__global__ __launch_bounds__(256) void k_gam_prepare(GroupGam g) {
+    __shared__ uint32_t sh4[4];
+    const GamOp& t = g.op[blockIdx.x];
+    const uint32_t gbits = global_amax_bits(t.amax_part, t.n_amax, sh4);
+    if (threadIdx.x == 0) {
+        const uint32_t mg = group_mantissa_bits(gbits, kE4M3Max, t.mode);
+        t.gam[0] = mg;
+        t.gam[1] = group_mantissa_bits(gbits, kE5M2Max, t.mode);
+        if (t.gmant) t.gmant[0] = mg;
     }
 }
 
@@ -1178,14 +1236,16 @@ static int clamp_grid_y(int64_t v) { return (int)(v < 1 ? 1 : (v > 65535 ? 65535
     } while (0)
 
 // Padded leading dimensions: one operand per launch.
-hipError_t launch_sub1x128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st, KProf* prof) {
+static hipError_t launch_sub1x128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, uint32_t mode,
+                                  const uint32_t* gam, hipStream_t st, KProf* prof) {
     ProfScope ps(prof, kKernSub1x128, st);
     const dim3 grid((unsigned)(sh.cols / 128), (unsigned)clamp_grid_y((sh.rows + 15) / 16));
-    MOR_DISPATCH_CRIT_DEFER(k_sub1x128_strided, <<<grid, dim3(256), 0, st>>>(x, sh, o, th));
+    MOR_DISPATCH_CRIT_DEFER(k_sub1x128_strided, <<<grid, dim3(256), 0, st>>>(x, sh, o, th, mode, gam));
     return hipGetLastError();
 }
 
-hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int crit, float th, void* ws, hipStream_t st, KProf* prof) {
+static hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int crit, float th, uint32_t mode, void* ws,
+                                hipStream_t st, KProf* prof) {
     const TensorPlan pl = plan_tensor(sh.rows, sh.cols);
     char* w = static_cast<char*>(ws);
     uint32_t* amax_part = reinterpret_cast<uint32_t*>(w + pl.off_amax_part);
@@ -1202,20 +1262,20 @@ hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int
     const unsigned long long n_padded = (unsigned long long)(gx * gy) * 2048ull;
     {
         ProfScope ps(prof, kKernTensorQuant, st);
-        if (crit == kCritEq3) k_tensor_quant_strided<kCritEq3><<<dim3(n_slots), dim3(256), 0, st>>>(x, sh, (uint32_t)gx, (uint32_t)(gx * gy), o, amax_part, n_amax, tp);
-        else k_tensor_quant_strided<kCritEq2><<<dim3(n_slots), dim3(256), 0, st>>>(x, sh, (uint32_t)gx, (uint32_t)(gx * gy), o, amax_part, n_amax, tp);
+        if (crit == kCritEq3) k_tensor_quant_strided<kCritEq3><<<dim3(n_slots), dim3(256), 0, st>>>(x, sh, (uint32_t)gx, (uint32_t)(gx * gy), o, amax_part, n_amax, tp, mode);
+        else k_tensor_quant_strided<kCritEq2><<<dim3(n_slots), dim3(256), 0, st>>>(x, sh, (uint32_t)gx, (uint32_t)(gx * gy), o, amax_part, n_amax, tp, mode);
     }
     {
         ProfScope ps(prof, kKernFallbackCopy, st);
         const int grid = o.bf16 ? 2048 : 1;
         const int flat = (sh.ld == sh.cols && o.ld_bf16 == sh.cols) ? 1 : 0;
-        if (crit == kCritEq3) k_tensor_finish<kCritEq3><<<dim3(grid), dim3(256), 0, st>>>(tp, n_slots, n_padded, o, th, x, sh, flat);
-        else k_tensor_finish<kCritEq2><<<dim3(grid), dim3(256), 0, st>>>(tp, n_slots, n_padded, o, th, x, sh, flat);
+        if (crit == kCritEq3) k_tensor_finish<kCritEq3><<<dim3(grid), dim3(256), 0, st>>>(tp, n_slots, n_padded, o, th, x, sh, flat, mode);
+        else k_tensor_finish<kCritEq2><<<dim3(grid), dim3(256), 0, st>>>(tp, n_slots, n_padded, o, th, x, sh, flat, mode);
     }
     return hipGetLastError();
 }
 
-hipError_t launch_scope_finalize(const uint16_t* x, const KShape& sh, const KOut& o, int64_t n_part, int crit, float th,
+static hipError_t launch_scope_finalize(const uint16_t* x, const KShape& sh, const KOut& o, int64_t n_part, int crit, float th,
                                  void* ws, hipStream_t st, KProf* prof) {
     char* w = static_cast<char*>(ws);
     ScopePartials sp{reinterpret_cast<double*>(w), reinterpret_cast<double*>(w) + kScopeBlocks,
@@ -1277,6 +1337,10 @@ size_t item_workspace(const BatchItem& it) {
     if (it.gran == kGranTensor) b += plan_tensor(it.sh.rows, it.sh.cols).bytes;
     else if (it.scope == 1) b += scope_workspace_bytes(item_parts(it));
     if (it.stats && it.gran != kGranTensor && item_grouped(it)) b += align16(sizeof(StatsRec) * kStatsMaxWg);
+    if (it.gran != kGranTensor && it.scaling != kScaleFp32) {
+        b += 16;                                                                   // group mantissa words
+        if (it.scaling == kScaleGam) b += align16(sizeof(uint32_t) * kMaxAmaxBlocks);   // amax partials of the pre-pass
+    }
     return b;
 }
 int share(int64_t mine, int64_t total, int budget, int64_t cap) {
@@ -1303,6 +1367,59 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
     (void)ws_bytes;
     hipError_t err = hipSuccess;
 
+    // ---- Algorithm 1, group loop: operands with sub-tensor blocks and GAM / E8M0 scaling get their group
+    //      mantissas first (GAM: one more read of the operand for its amax)
+    const uint32_t* gam_of[kBatchMax] = {};
+    {
+        int idx[kBatchMax];
+        int cnt = 0;
+        for (int i = 0; i < n; ++i)
+            if (items[i].gran != kGranTensor && items[i].scaling != kScaleFp32) idx[cnt++] = i;
+        for (int base = 0; base < cnt; base += kMaxGroup) {
+            const int m = cnt - base < kMaxGroup ? cnt - base : kMaxGroup;
+            GroupGam gg; gg.n = m;
+            GroupTensor ga; ga.n = 0; ga.near_tol = near_tol;
+            int slot_of[kMaxGroup];
+            int64_t total_tiles = 0;
+            for (int k = 0; k < m; ++k) {
+                const BatchItem& it = items[idx[base + k]];
+                uint32_t* gam = reinterpret_cast<uint32_t*>(carve(16));
+                gam_of[idx[base + k]] = gam;
+                GamOp& q = gg.op[k];
+                q.amax_part = nullptr; q.n_amax = 0; q.mode = (uint32_t)it.scaling; q.gam = gam; q.gmant = it.o.gmant;
+                slot_of[k] = -1;
+                if (it.scaling != kScaleGam) continue;
+                uint32_t* part = reinterpret_cast<uint32_t*>(carve(sizeof(uint32_t) * kMaxAmaxBlocks));
+                q.amax_part = part;
+                if (it.sh.ld == it.sh.cols) {
+                    TensorOp& t = ga.op[ga.n];
+                    t = TensorOp{};
+                    t.x = it.x;
+                    t.n_chunks = it.sh.rows * it.sh.cols / 8;
+                    t.n_tiles = (t.n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
+                    t.amax_part = part;
+                    total_tiles += t.n_tiles;
+                    slot_of[k] = ga.n++;
+                } else {
+                    q.n_amax = (int)(it.sh.rows < kMaxAmaxBlocks ? it.sh.rows : kMaxAmaxBlocks);
+                    ProfScope ps(prof, kKernTensorAmax, st);
+                    k_tensor_amax_strided<<<dim3(q.n_amax), dim3(256), 0, st>>>(it.x, it.sh, part);
+                }
+            }
+            int a_end = 0;
+            for (int j = 0; j < ga.n; ++j) {
+                TensorOp& t = ga.op[j];
+                t.n_amax = share(t.n_tiles, total_tiles, kMaxAmaxBlocks, t.n_tiles);
+                a_end += t.n_amax;
+                ga.amax_end[j] = a_end;
+            }
+            for (int k = 0; k < m; ++k)
+                if (slot_of[k] >= 0) gg.op[k].n_amax = ga.op[slot_of[k]].n_amax;
+            if (ga.n) { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_group<<<dim3(a_end), dim3(256), 0, st>>>(ga); }
+            k_gam_prepare<<<dim3(m), dim3(256), 0, st>>>(gg);
+        }
+    }
+
     for (int crit = 0; crit < 2 && err == hipSuccess; ++crit) {
         // ---- 1x128 sub-channel operands
         {
@@ -1324,6 +1441,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 if (n_units > 0) {
                     total += n_units;
                     g.unit_end[g.n] = total; g.x[g.n] = it.x; g.o[g.n] = it.o; g.th[g.n] = it.th; g.defer[g.n] = it.scope == 1;
+                    g.mode[g.n] = (uint8_t)it.scaling; g.gam[g.n] = gam_of[i];
                     if (++g.n == kMaxGroup) flush();
                 }
                 if (n_tail > 0) {     // fewer than 32 blocks left: the strided kernel takes them
@@ -1336,7 +1454,8 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                     if (to.err5_sum) to.err5_sum += n_full;
                     const dim3 grid(1u, (unsigned)clamp_grid_y((n_tail + 15) / 16));
                     const bool defer = it.scope == 1;
-                    MOR_DISPATCH_CRIT_DEFER(k_sub1x128_strided, <<<grid, dim3(256), 0, st>>>(it.x + n_full * 128, ts, to, it.th));
+                    if (to.e8m0) to.e8m0 += n_full;
+                    MOR_DISPATCH_CRIT_DEFER(k_sub1x128_strided, <<<grid, dim3(256), 0, st>>>(it.x + n_full * 128, ts, to, it.th, (uint32_t)it.scaling, gam_of[i]));
                 }
             }
             flush();
@@ -1361,6 +1480,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 total += tiles;
                 g.tile_end[g.n] = total; g.tiles_x[g.n] = (int32_t)(it.sh.cols / 128); g.ld[g.n] = it.sh.ld;
                 g.x[g.n] = it.x; g.o[g.n] = it.o; g.th[g.n] = it.th; g.defer[g.n] = it.scope == 1;
+                g.mode[g.n] = (uint8_t)it.scaling; g.gam[g.n] = gam_of[i];
                 if (++g.n == kMaxGroup) flush();
             }
             flush();
@@ -1382,7 +1502,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 for (int k = 0; k < cnt; ++k) {
                     const BatchItem& it = items[idx[k]];
                     TensorOp& t = g.op[k];
-                    t.x = it.x; t.o = it.o; t.th = it.th;
+                    t.x = it.x; t.o = it.o; t.th = it.th; t.mode = (uint32_t)it.scaling;
                     t.n_chunks = it.sh.rows * it.sh.cols / 8;
                     t.n_tiles = (t.n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
                     t.n_amax = share(t.n_tiles, total_tiles, kMaxAmaxBlocks, t.n_tiles);
@@ -1439,9 +1559,9 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
         if (item_grouped(it)) continue;
         const bool defer = it.scope == 1;
         if (it.gran == kGranTensor) {
-            err = launch_tensor(it.x, it.sh, it.o, it.crit, it.th, carve(plan_tensor(it.sh.rows, it.sh.cols).bytes), st, prof);
+            err = launch_tensor(it.x, it.sh, it.o, it.crit, it.th, (uint32_t)it.scaling, carve(plan_tensor(it.sh.rows, it.sh.cols).bytes), st, prof);
         } else {
-            err = launch_sub1x128(it.x, it.sh, it.o, it.crit, defer, it.th, st, prof);
+            err = launch_sub1x128(it.x, it.sh, it.o, it.crit, defer, it.th, (uint32_t)it.scaling, gam_of[i], st, prof);
             if (err == hipSuccess && defer)
                 err = launch_scope_finalize(it.x, it.sh, it.o, item_parts(it), it.crit, it.th, carve(scope_workspace_bytes(item_parts(it))), st, prof);
         }
@@ -1479,11 +1599,11 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
 
 hipError_t launch_dequantize(int gran, int64_t rows, int64_t cols, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
                              const uint8_t* mask, const uint16_t* bf16, int64_t ld_bf16, uint16_t* y, int64_t ld_y,
-                             hipStream_t st) {
+                             const uint8_t* e8m0, const uint32_t* gmant, hipStream_t st) {
     const dim3 grid((unsigned)((cols + 127) / 128), (unsigned)clamp_grid_y((rows + 15) / 16));
-    if (gran == 0) k_dequant<0><<<grid, dim3(256), 0, st>>>(rows, cols, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y);
-    else if (gran == 1) k_dequant<1><<<grid, dim3(256), 0, st>>>(rows, cols, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y);
-    else k_dequant<2><<<grid, dim3(256), 0, st>>>(rows, cols, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y);
+    if (gran == 0) k_dequant<0><<<grid, dim3(256), 0, st>>>(rows, cols, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y, e8m0, gmant);
+    else if (gran == 1) k_dequant<1><<<grid, dim3(256), 0, st>>>(rows, cols, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y, e8m0, gmant);
+    else k_dequant<2><<<grid, dim3(256), 0, st>>>(rows, cols, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y, e8m0, gmant);
     return hipGetLastError();
 }
 

@@ -16,6 +16,8 @@ struct KOut {
     uint32_t* nnz;
     uint8_t*  mask;
     float*    err5_sum;
+    uint8_t*  e8m0;     // [P] biased exponents of the applied scales (GAM / E8M0 scaling), may be nullptr
+    uint32_t* gmant;    // [1] fraction bits of the group mantissa, may be nullptr
 };
 
 struct KShape {
@@ -51,26 +53,24 @@ enum KernelId {
     kKernStatsPartial = 10, kKernStatsFinal = 11
 };
 
+constexpr int kBatchMax = 64;     // operands per batch call
+
 // One operand of a batch (validated by the caller).
 struct BatchItem {
     KShape sh;
     KOut o;
     const uint16_t* x;
     int gran, crit, scope;
+    int scaling;            // 0 FP32 amax, 1 GAM, 2 E8M0 only
     float th;
     void* stats;            // device mor_stats* or nullptr
 };
 size_t batch_workspace_bytes(const BatchItem* items, int n);
 hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws, size_t ws_bytes, hipStream_t st, KProf* prof);
 
-hipError_t launch_sub1x128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, hipStream_t st, KProf* prof);
-hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int crit, float th, void* ws, hipStream_t st, KProf* prof);
-// Tensor-scope decision over per-block sums already written by a deferred sub-tensor pass.
-hipError_t launch_scope_finalize(const uint16_t* x, const KShape& sh, const KOut& o, int64_t n_part, int crit, float th,
-                                 void* ws, hipStream_t st, KProf* prof);
 hipError_t launch_dequantize(int gran, int64_t rows, int64_t cols, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
                              const uint8_t* mask, const uint16_t* bf16, int64_t ld_bf16, uint16_t* y, int64_t ld_y,
-                             hipStream_t st);
+                             const uint8_t* e8m0, const uint32_t* gmant, hipStream_t st);
 hipError_t launch_select_stats(int64_t n_part, int64_t elems_per_part, const float* err_sum, const uint32_t* nnz,
                                const uint8_t* mask, float th, float near_tol, void* out_dev, hipStream_t st);
 

@@ -30,11 +30,11 @@ def u16(t: torch.Tensor) -> np.ndarray:
 
 
 def run_gpu(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "mean_rel_err", threshold: float = 0.045,
-            cols: int | None = None, want_bf16: bool = True):
+            cols: int | None = None, want_bf16: bool = True, scaling: str = "fp32_amax"):
     """xb: (rows, ld) uint16.  Returns (params, MorResult) with outputs still on the device."""
     rows, ld = xb.shape
     cols = ld if cols is None else cols
-    params = B.make_params(rows, cols, gran, scope, crit, threshold, ld=ld)
+    params = B.make_params(rows, cols, gran, scope, crit, threshold, ld=ld, scaling=scaling)
     x = to_dev(xb)
     out = B.alloc_outputs(params, x.device, want_bf16=want_bf16, bf16_fill=FILL)
     B.mor_analyze_quantize(params, x, out)
@@ -43,13 +43,17 @@ def run_gpu(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "me
 
 
 def compare(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "mean_rel_err", threshold: float = 0.045,
-            cols: int | None = None, label: str = "") -> dict:
+            cols: int | None = None, label: str = "", scaling: str = "fp32_amax") -> dict:
     rows, ld = xb.shape
     cols = ld if cols is None else cols
-    print(f"[parity] {label} shape={rows}x{cols} ld={ld} gran={gran} scope={scope} crit={crit} th={threshold}", flush=True)
-    params, g = run_gpu(xb, gran, scope, crit, threshold, cols)
-    a = O.analyze_quantize(xb, gran, scope, crit, threshold, bf16_fill=FILL, ld=ld, cols=cols)
+    print(f"[parity] {label} shape={rows}x{cols} ld={ld} gran={gran} scope={scope} crit={crit} th={threshold} "
+          f"scaling={scaling}", flush=True)
+    params, g = run_gpu(xb, gran, scope, crit, threshold, cols, scaling=scaling)
+    a = O.analyze_quantize(xb, gran, scope, crit, threshold, bf16_fill=FILL, ld=ld, cols=cols, scaling=scaling)
     P = a.mask.size
+    if scaling != "fp32_amax":      # stored form of the scales: one E8M0 byte per block, one 23-bit mantissa
+        assert np.array_equal(g.scale_e8m0.cpu().numpy(), a.e8m0), "E8M0 exponents differ"
+        assert int(g.group_mantissa.cpu().numpy().view(np.uint32)[0]) == a.group_mantissa, "group mantissa differs"
 
     g_amax = g.amax.cpu().numpy(); g_scale = g.scale.cpu().numpy()
     assert np.array_equal(g_amax.view(np.uint32), a.amax.view(np.uint32)), "amax differs"

@@ -34,7 +34,7 @@ def test_exports_every_declared_symbol(B):
 def test_struct_layouts(B):
     assert C.sizeof(B.MorStats) == 128
     assert C.sizeof(B.MorParams) == 48
-    assert C.sizeof(B.MorOutputs) == 80
+    assert C.sizeof(B.MorOutputs) == 96
 
 
 def test_num_partitions(B):

@@ -211,7 +211,7 @@ def test_argument_errors(P):
     assert status(B.make_params(128, 256, "sub1x128", ld=260)) == 3    # ld % 8
     assert status(B.make_params(128, 256, 7)) == 4
     assert status(B.make_params(128, 256, "sub1x128", formats=B.MOR_FMT_E4M3 | B.MOR_FMT_E5M2 | B.MOR_FMT_BF16)) == 4
-    assert status(B.make_params(128, 256, "sub1x128", scaling=1)) == 4
+    assert status(B.make_params(128, 256, "sub1x128", scaling=3)) == 4
     assert status(B.make_params(128, 256, "sub1x128", crit=5)) == 4
     assert status(B.make_params(128, 256, "sub1x128"), xx=x.view(-1)[1:]) == 3   # misaligned input
 
