@@ -165,7 +165,7 @@ mor_status mor_analyze_quantize(const mor_params* params, const uint16_t* x, con
 /*
  * Measurement aid: the same call, with the caller's HIP events recorded on `stream` right before
  * and after each kernel it launches, so a benchmark can time individual kernels inside its own
- * timed loop.  `profile` is a HOST struct: the caller fills `capacity` (<= 8) and that many
+ * timed loop.  `profile` is a HOST struct: the caller fills `capacity` (<= MOR_PROFILE_MAX) and that many
  * created hipEvent_t handles in start[] / stop[]; on return `count` kernels were bracketed and
  * kernel[i] names the i-th one (mor_kernel_id).  Kernels beyond `capacity` run un-bracketed.
  */
@@ -173,14 +173,17 @@ typedef enum {
     MOR_KERNEL_SUB_1x128 = 1, MOR_KERNEL_BLOCK_128x128 = 2, MOR_KERNEL_TENSOR_AMAX = 3,
     MOR_KERNEL_TENSOR_QUANT = 4, MOR_KERNEL_TENSOR_FINALIZE = 5, MOR_KERNEL_FALLBACK_COPY = 6,
     MOR_KERNEL_SCOPE_REDUCE = 7, MOR_KERNEL_SCOPE_DECIDE = 8, MOR_KERNEL_SCOPE_FILL_MASK = 9,
-    MOR_KERNEL_STATS_PARTIAL = 10, MOR_KERNEL_STATS_FINAL = 11
+    MOR_KERNEL_STATS_PARTIAL = 10, MOR_KERNEL_STATS_FINAL = 11,
+    MOR_KERNEL_GROUP_AMAX = 12,      /* amax of the whole operand for GAM scaling of sub-tensor blocks */
+    MOR_KERNEL_GROUP_MANTISSA = 13
 } mor_kernel_id;
+#define MOR_PROFILE_MAX 16
 typedef struct mor_profile {
     int32_t capacity;
     int32_t count;
-    void*   start[8];   /* hipEvent_t */
-    void*   stop[8];    /* hipEvent_t */
-    int32_t kernel[8];  /* mor_kernel_id */
+    void*   start[MOR_PROFILE_MAX];   /* hipEvent_t */
+    void*   stop[MOR_PROFILE_MAX];    /* hipEvent_t */
+    int32_t kernel[MOR_PROFILE_MAX];  /* mor_kernel_id */
 } mor_profile;
 mor_status mor_analyze_quantize_profiled(const mor_params* params, const uint16_t* x, const mor_outputs* out,
                                          void* workspace, size_t workspace_bytes, void* stream,

@@ -30,11 +30,12 @@ EXPORTS = ("mor_num_partitions", "mor_workspace_bytes", "mor_analyze_quantize", 
            "mor_batch_workspace_bytes", "mor_analyze_quantize_batch", "mor_dequantize", "mor_dequantize_e8m0", "mor_select_stats",
            "mor_status_string")
 MOR_BATCH_MAX = 64
+MOR_PROFILE_MAX = 16
 MOR_STATS_FLAG_FUSED_FALLBACK = 1
 
 KERNEL_NAMES = {1: "sub1x128", 2: "block128", 3: "tensor_amax", 4: "tensor_quant", 5: "tensor_finalize",
                 6: "fallback_copy", 7: "scope_reduce", 8: "scope_decide", 9: "scope_fill_mask",
-                10: "stats_partial", 11: "stats_final"}
+                10: "stats_partial", 11: "stats_final", 12: "group_amax", 13: "group_mantissa"}
 
 
 class MorParams(C.Structure):
@@ -57,8 +58,8 @@ class MorStats(C.Structure):
 
 
 class MorProfile(C.Structure):
-    _fields_ = [("capacity", C.c_int32), ("count", C.c_int32), ("start", C.c_void_p * 8), ("stop", C.c_void_p * 8),
-                ("kernel", C.c_int32 * 8)]
+    _fields_ = [("capacity", C.c_int32), ("count", C.c_int32), ("start", C.c_void_p * MOR_PROFILE_MAX),
+                ("stop", C.c_void_p * MOR_PROFILE_MAX), ("kernel", C.c_int32 * MOR_PROFILE_MAX)]
 
 
 class MorBatchItem(C.Structure):

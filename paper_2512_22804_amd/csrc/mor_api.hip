@@ -91,7 +91,7 @@ static mor_status run_batch(const mor::BatchItem* items, int n, float near_tol, 
     static_assert(sizeof(mor_profile) == sizeof(mor::KProf), "mor_profile layout");
     if (profile) {
         profile->count = 0;
-        for (int i = 0; i < profile->capacity && i < 8; ++i)
+        for (int i = 0; i < profile->capacity && i < mor::kProfMax; ++i)
             if (!profile->start[i] || !profile->stop[i]) return MOR_ERR_NULL;
     }
     hipError_t e = mor::launch_batch(items, n, near_tol, workspace, workspace_bytes, static_cast<hipStream_t>(stream),

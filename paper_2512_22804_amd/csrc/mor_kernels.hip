@@ -1193,7 +1193,7 @@ static inline size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
 struct ProfScope {
     KProf* prof; hipStream_t st; int slot;
     ProfScope(KProf* p, int kernel_id, hipStream_t s) : prof(p), st(s), slot(-1) {
-        if (prof && prof->count < prof->capacity && prof->count < 8) {
+        if (prof && prof->count < prof->capacity && prof->count < kProfMax) {
             slot = prof->count++;
             prof->kernel[slot] = kernel_id;
             (void)hipEventRecord(prof->start[slot], st);
@@ -1402,7 +1402,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                     slot_of[k] = ga.n++;
                 } else {
                     q.n_amax = (int)(it.sh.rows < kMaxAmaxBlocks ? it.sh.rows : kMaxAmaxBlocks);
-                    ProfScope ps(prof, kKernTensorAmax, st);
+                    ProfScope ps(prof, kKernGroupAmax, st);
                     k_tensor_amax_strided<<<dim3(q.n_amax), dim3(256), 0, st>>>(it.x, it.sh, part);
                 }
             }
@@ -1415,8 +1415,8 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
             }
             for (int k = 0; k < m; ++k)
                 if (slot_of[k] >= 0) gg.op[k].n_amax = ga.op[slot_of[k]].n_amax;
-            if (ga.n) { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_group<<<dim3(a_end), dim3(256), 0, st>>>(ga); }
-            k_gam_prepare<<<dim3(m), dim3(256), 0, st>>>(gg);
+            if (ga.n) { ProfScope ps(prof, kKernGroupAmax, st); k_tensor_amax_group<<<dim3(a_end), dim3(256), 0, st>>>(ga); }
+            { ProfScope ps(prof, kKernGroupMantissa, st); k_gam_prepare<<<dim3(m), dim3(256), 0, st>>>(gg); }
         }
     }
 

@@ -39,18 +39,19 @@ struct TensorPlan {
 TensorPlan plan_tensor(int64_t rows, int64_t cols);
 size_t scope_workspace_bytes(int64_t n_part);
 
+constexpr int kProfMax = 16;
 // Optional per-kernel timing: when non-null, start[i]/stop[i] are recorded around the i-th kernel.
 struct KProf {
     int32_t capacity;
     int32_t count;
-    hipEvent_t start[8];
-    hipEvent_t stop[8];
-    int32_t kernel[8];
+    hipEvent_t start[kProfMax];
+    hipEvent_t stop[kProfMax];
+    int32_t kernel[kProfMax];
 };
 enum KernelId {
     kKernSub1x128 = 1, kKernBlock128 = 2, kKernTensorAmax = 3, kKernTensorQuant = 4, kKernTensorFinalize = 5,
     kKernFallbackCopy = 6, kKernScopeReduce = 7, kKernScopeDecide = 8, kKernScopeFillMask = 9,
-    kKernStatsPartial = 10, kKernStatsFinal = 11
+    kKernStatsPartial = 10, kKernStatsFinal = 11, kKernGroupAmax = 12, kKernGroupMantissa = 13
 };
 
 constexpr int kBatchMax = 64;     // operands per batch call
