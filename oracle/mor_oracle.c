@@ -65,10 +65,28 @@
  *       power of two that cannot saturate.
  *   R18 s_g and s_b in Algorithm 1 follow R2 (zero / non-finite amax -> 1,
  *       overflow -> FLT_MAX) before mantissa and exponent are taken.
+ *   R19 three-way selection [E4M3, E5M2, BF16] (Section 3.2, first recipe): M_1 is
+ *       the chosen criterion (the paper uses Eq. (3)); M_2 is Eq. (4),
+ *       max|b| / min|b| < 57344 / 2^-14, with the minimum taken over the NON-ZERO
+ *       elements (every metric of the paper excludes zeros; a zero would make the
+ *       ratio infinite for any block that holds one).  A block without non-zero
+ *       elements passes M_2 (there is no range to cover).  The ratio test is
+ *       evaluated exactly as amax < 57344 * 2^14 * amin.  An E5M2 block is
+ *       quantized with the E5M2 scale (q_amax = 57344); its scale / E8M0 outputs
+ *       are those of that scale.  A block holding Inf or NaN fails M_2 (R9).
+ *   R20 further partitions: per-channel rows (1 x cols) and columns (rows x 1)
+ *       (Section 3, first paragraph; Section 4.1.1), column sub-channels 128 x 1
+ *       (the "sub-columns" of Section 3 / the transposed operands of Section 4),
+ *       64 x 64 blocks (Section 4.1.2, first ablation).  Ragged edges, on which
+ *       the paper is silent: the grid is ceil(rows/pr) x ceil(cols/pc) and the
+ *       last block of a row / column of the grid is simply smaller.
+ *   R21 fake quantization (Section 4, Figure 4) is de-quantize(quantize(x)):
+ *       BF16 in, BF16 out; blocks kept in BF16 pass through unchanged.
  *
- * parity unpinned: R8 (tie handling), R9 (non-finite policy) and R17 (which
- * power of two the E8M0 ablation uses) are fixed by these readings only;
- * nothing in the paper pins them.
+ * parity unpinned: R8 (tie handling), R9 (non-finite policy), R17 (which
+ * power of two the E8M0 ablation uses), R19 (zeros in the minimum of Eq. (4))
+ * and R20 (ragged edges) are fixed by these readings only; nothing in the paper
+ * pins them.
  */
 #include <float.h>
 #include <math.h>
@@ -202,34 +220,49 @@ float mor_oracle_gam_block_scale(float b_amax, float q_amax, double m_g, int *e_
 
 /* ------------------------------------------------------------ partitioning */
 
-enum { GRAN_TENSOR = 0, GRAN_SUB_1x128 = 1, GRAN_BLOCK_128x128 = 2 };
+enum { GRAN_TENSOR = 0, GRAN_SUB_1x128 = 1, GRAN_BLOCK_128x128 = 2, GRAN_CHANNEL_ROW = 3,
+       GRAN_CHANNEL_COL = 4, GRAN_SUB_128x1 = 5, GRAN_BLOCK_64x64 = 6 };
+enum { FMT_E4M3 = 1, FMT_E5M2 = 2, FMT_BF16 = 4 };
 enum { CRIT_MEAN_REL_ERR = 0, CRIT_E4M3_VS_E5M2 = 1 };
 enum { SCOPE_PARTITION = 0, SCOPE_TENSOR = 1 };
 
-static int part_shape(int gran, int64_t rows, int64_t cols, int64_t *pr, int64_t *pc)
+/* Nominal block shape pr x pc of a partition (Section 3, first paragraph; R20).  With
+ * ragged == 0 the tensor must be a whole number of blocks, otherwise edge blocks are smaller. */
+static int part_shape_ex(int gran, int64_t rows, int64_t cols, int ragged, int64_t *pr, int64_t *pc)
 {
     switch (gran) {
-    case GRAN_TENSOR:        *pr = rows; *pc = cols; return 0;
-    case GRAN_SUB_1x128:     *pr = 1;    *pc = 128;  return (cols % 128) ? -1 : 0;
-    case GRAN_BLOCK_128x128: *pr = 128;  *pc = 128;  return (rows % 128 || cols % 128) ? -1 : 0;
+    case GRAN_TENSOR:        *pr = rows; *pc = cols; break;
+    case GRAN_SUB_1x128:     *pr = 1;    *pc = 128;  break;
+    case GRAN_BLOCK_128x128: *pr = 128;  *pc = 128;  break;
+    case GRAN_CHANNEL_ROW:   *pr = 1;    *pc = cols; break;
+    case GRAN_CHANNEL_COL:   *pr = rows; *pc = 1;    break;
+    case GRAN_SUB_128x1:     *pr = 128;  *pc = 1;    break;
+    case GRAN_BLOCK_64x64:   *pr = 64;   *pc = 64;   break;
     default: return -1;
     }
+    if (!ragged && (rows % *pr || cols % *pc)) return -1;
+    return 0;
 }
 
-int64_t mor_oracle_num_partitions(int gran, int64_t rows, int64_t cols)
+int64_t mor_oracle_num_partitions_ex(int gran, int64_t rows, int64_t cols, int ragged)
 {
     int64_t pr, pc;
-    if (rows <= 0 || cols <= 0 || part_shape(gran, rows, cols, &pr, &pc)) return -1;
-    return (rows / pr) * (cols / pc);
+    if (rows <= 0 || cols <= 0 || part_shape_ex(gran, rows, cols, ragged, &pr, &pc)) return -1;
+    return ((rows + pr - 1) / pr) * ((cols + pc - 1) / pc);
+}
+int64_t mor_oracle_num_partitions(int gran, int64_t rows, int64_t cols)
+{
+    return mor_oracle_num_partitions_ex(gran, rows, cols, 0);
 }
 
 /* --------------------------------------------------- one block of the tensor */
 
 typedef struct {
-    float  amax, scale;
+    float  amax, amin, scale, scale5;
     double err_sum, err5_sum, err_sum_unscaled;
     uint32_t nnz;
-    int    e8m0;            /* biased exponent of the E4M3 scale (GAM / E8M0 scaling), else 0 */
+    int    e8m0, e8m0_5;    /* biased exponents of the E4M3 / E5M2 scales (GAM / E8M0 scaling), else 0 */
+    int    nonfinite;
 } block_result;
 
 /* Error sums of one block for one FP8 format; optionally writes the codes. */
@@ -240,7 +273,7 @@ static double block_error(const uint16_t *x, int64_t ld, int64_t pr, int64_t pc,
     double sum = 0.0, sum_u = 0.0;
     /* rows of one large block (per-tensor granularity) are spread over threads; for small
      * blocks the caller already runs one block per thread and this region stays serial */
-#pragma omp parallel for reduction(+ : sum, sum_u) schedule(static) if (pr >= 256)
+#pragma omp parallel for reduction(+ : sum, sum_u) schedule(static) if (pr * pc >= 65536)
     for (int64_t r = 0; r < pr; ++r) {
         for (int64_t c = 0; c < pc; ++c) {
             uint16_t b = x[r * ld + c];
@@ -268,42 +301,41 @@ static double block_error(const uint16_t *x, int64_t ld, int64_t pr, int64_t pc,
     return sum;
 }
 
-static void analyze_block(const uint16_t *x, int64_t ld, int64_t pr, int64_t pc, int crit,
+/* amax, smallest non-zero magnitude, non-zero count, the scales of Algorithm 1 for both FP8
+ * formats, the E4M3 codes and error sum, and (want5) the E5M2 error sum of one block. */
+static void analyze_block(const uint16_t *x, int64_t ld, int64_t pr, int64_t pc, int want5,
                           int scaling, double m_g, double m_g5,
                           uint8_t *codes, int64_t ld_codes, block_result *out)
 {
-    uint16_t a = 0;
+    uint16_t a = 0, lo = 0;
     uint32_t nnz = 0;
-    int nonfinite;
     for (int64_t r = 0; r < pr; ++r)
         for (int64_t c = 0; c < pc; ++c) {
             uint16_t m = (uint16_t)(x[r * ld + c] & 0x7FFFu);
             if (m > a) a = m;                               /* R1 */
-            if (m) ++nnz;
+            if (m) { ++nnz; if (lo == 0 || m < lo) lo = m; }
         }
-    nonfinite = a >= 0x7F80u;
+    out->nonfinite = a >= 0x7F80u;
     out->amax = bf16_to_f32(a);
+    out->amin = bf16_to_f32(lo);
     out->nnz = nnz;
-    out->e8m0 = 0;
+    out->e8m0 = 0; out->e8m0_5 = 0;
     if (scaling == SCALING_FP32_AMAX) {
         out->scale = mor_oracle_scale(out->amax, 448.0f);
+        out->scale5 = mor_oracle_scale(out->amax, 57344.0f);
     } else {
         int e;
         out->scale = mor_oracle_gam_block_scale(out->amax, 448.0f, m_g, &e);
         out->e8m0 = e + 127;
+        out->scale5 = mor_oracle_gam_block_scale(out->amax, 57344.0f, m_g5, &e);
+        out->e8m0_5 = e + 127;
     }
-    out->err_sum = block_error(x, ld, pr, pc, out->scale, 4, 3, nonfinite, codes, ld_codes,
+    out->err_sum = block_error(x, ld, pr, pc, out->scale, 4, 3, out->nonfinite, codes, ld_codes,
                                &out->err_sum_unscaled);
-    if (crit == CRIT_E4M3_VS_E5M2) {
-        float s5 = scaling == SCALING_FP32_AMAX ? mor_oracle_scale(out->amax, 57344.0f)
-                                                : mor_oracle_gam_block_scale(out->amax, 57344.0f, m_g5, NULL);
-        out->err5_sum = block_error(x, ld, pr, pc, s5, 5, 2, nonfinite, NULL, 0, NULL);
-    } else {
-        out->err5_sum = 0.0;
-    }
+    out->err5_sum = want5 ? block_error(x, ld, pr, pc, out->scale5, 5, 2, out->nonfinite, NULL, 0, NULL) : 0.0;
 }
 
-/* Algorithm 2 with the type list [E4M3, BF16]: 1 = accept E4M3. */
+/* M_1 of Algorithm 2 for E4M3: 1 = accept. */
 static int accept_e4m3(int crit, double err_sum, double err5_sum, uint64_t nnz, float threshold)
 {
     if (crit == CRIT_E4M3_VS_E5M2) return err_sum < err5_sum;             /* Eq. (3), R8 */
@@ -313,37 +345,64 @@ static int accept_e4m3(int crit, double err_sum, double err5_sum, uint64_t nnz, 
     }
 }
 
+/* M_2 of the three-way recipe, Eq. (4), R19: the block's dynamic range fits E5M2's normal range. */
+static int accept_e5m2(float amax, float amin, uint32_t nnz, int nonfinite)
+{
+    if (nonfinite) return 0;
+    if (nnz == 0) return 1;
+    return (double)amax < 57344.0 * 16384.0 * (double)amin;   /* exact: both are BF16 values */
+}
+
 /* -------------------------------------------------------------- entry points */
 
+typedef struct {
+    int64_t  rows, cols, ld;
+    int32_t  gran, scope, crit, scaling;
+    uint32_t formats;       /* FMT_E4M3 | FMT_BF16, or FMT_E4M3 | FMT_E5M2 | FMT_BF16 (three-way) */
+    int32_t  ragged;        /* 1: edge blocks may be smaller than the nominal block (R20) */
+    float    threshold;
+} oracle_params;
+
+typedef struct {
+    uint8_t  *fp8;          /* [rows x cols] dense: E4M3 codes; E5M2 codes in blocks with mask == 2 */
+    uint16_t *bf16;         /* [rows x cols] dense; written only where mask == 1; may be NULL */
+    float    *scale;        /* [P] scale of the payload in fp8 (E5M2 scale where mask == 2) */
+    float    *amax;         /* [P] */
+    double   *err_sum;      /* [P] */
+    uint32_t *nnz;          /* [P] */
+    uint8_t  *mask;         /* [P] 0 = E4M3, 1 = BF16, 2 = E5M2 */
+    double   *err5_sum;     /* [P] or NULL */
+    double   *err_sum_unscaled; /* [P] or NULL */
+    uint8_t  *e8m0;         /* [P] or NULL (GAM / E8M0 scaling) */
+    uint32_t *group_mantissa;   /* [2] or NULL: fraction bits of m_g for E4M3 and for E5M2 */
+    float    *amin;         /* [P] or NULL: smallest non-zero magnitude (0 when there is none) */
+    uint16_t *fake;         /* [rows x cols] or NULL: fake-quantized tensor (R21) */
+} oracle_out;
+
 /*
- * Full analyse-select-quantize of one operand.
- *   x            [rows x ld] BF16 bit patterns, row-major, ld >= cols
- *   fp8          [rows x cols] E4M3 codes, dense (leading dimension cols), all blocks
- *   bf16         [rows x cols] dense; written only where the block's mask is 1; may be NULL
- *   scale, amax  [P] float;  err_sum, err5_sum, err_sum_unscaled [P] double (the last two may
- *   be NULL);  nnz [P] uint32;  mask [P] uint8 (0 = E4M3, 1 = BF16)
- * Blocks are numbered row-major over the block grid.  Returns 0, or -1 on a bad shape.
+ * Full analyse-select-quantize of one operand (Algorithm 2; scales by Algorithm 1).
+ * Blocks are numbered row-major over the block grid.  Returns 0, or -1 on bad arguments.
  */
-/*
- * The same with a choice of scaling algorithm: 0 = FP32 amax, 1 = GAM (Algorithm 1, one group),
- * 2 = E8M0 only.  For 1 and 2, e8m0 [P] receives the block exponents (biased by 127) and
- * group_mantissa [1] the 23 fraction bits of m_g (0 for E8M0-only); scale [P] is the applied
- * scale m_g * 2^e.  Both extra outputs may be NULL.
- */
-int mor_oracle_analyze_quantize_ex(const uint16_t *x, int64_t rows, int64_t cols, int64_t ld,
-                                   int gran, int scope, int crit, int scaling, float threshold,
-                                   uint8_t *fp8, uint16_t *bf16,
-                                   float *scale, float *amax, double *err_sum, uint32_t *nnz,
-                                   uint8_t *mask, double *err5_sum, double *err_sum_unscaled,
-                                   uint8_t *e8m0, uint32_t *group_mantissa)
+int mor_oracle_run(const oracle_params *pp, const uint16_t *x, const oracle_out *o)
 {
+    const int64_t rows = pp->rows, cols = pp->cols, ld = pp->ld;
+    const int three = pp->formats == (FMT_E4M3 | FMT_E5M2 | FMT_BF16);
+    const int want5 = pp->crit == CRIT_E4M3_VS_E5M2;
     int64_t pr, pc, gr, gc, P;
     double m_g = 1.0, m_g5 = 1.0;
-    if (rows <= 0 || cols <= 0 || ld < cols || part_shape(gran, rows, cols, &pr, &pc)) return -1;
-    if (scaling < SCALING_FP32_AMAX || scaling > SCALING_E8M0) return -1;
-    gr = rows / pr; gc = cols / pc; P = gr * gc;
+    float *scale5;
+    uint8_t *e8m0_5;
+    if (rows <= 0 || cols <= 0 || ld < cols || part_shape_ex(pp->gran, rows, cols, pp->ragged, &pr, &pc)) return -1;
+    if (pp->scaling < SCALING_FP32_AMAX || pp->scaling > SCALING_E8M0) return -1;
+    if (!three && pp->formats != (FMT_E4M3 | FMT_BF16)) return -1;
+    if (three && pp->scope != SCOPE_PARTITION) return -1;     /* the paper's three-way recipe is per block */
+    if (want5 && !o->err5_sum) return -1;
+    gr = (rows + pr - 1) / pr; gc = (cols + pc - 1) / pc; P = gr * gc;
+    scale5 = (float *)malloc(sizeof(float) * (size_t)P);
+    e8m0_5 = (uint8_t *)malloc((size_t)P);
+    if (!scale5 || !e8m0_5) { free(scale5); free(e8m0_5); return -1; }
 
-    if (scaling == SCALING_GAM) {          /* the group loop of Algorithm 1, one group */
+    if (pp->scaling == SCALING_GAM) {          /* the group loop of Algorithm 1, one group */
         uint16_t g = 0;
         float g_amax;
         for (int64_t r = 0; r < rows; ++r)
@@ -352,48 +411,93 @@ int mor_oracle_analyze_quantize_ex(const uint16_t *x, int64_t rows, int64_t cols
                 if (m > g) g = m;
             }
         g_amax = bf16_to_f32(g);
-        m_g = mor_oracle_group_mantissa(g_amax, 448.0f, scaling);
-        m_g5 = mor_oracle_group_mantissa(g_amax, 57344.0f, scaling);
+        m_g = mor_oracle_group_mantissa(g_amax, 448.0f, pp->scaling);
+        m_g5 = mor_oracle_group_mantissa(g_amax, 57344.0f, pp->scaling);
     }
-    if (group_mantissa) *group_mantissa = (uint32_t)ldexp(m_g - 1.0, 23);
+    if (o->group_mantissa) {
+        o->group_mantissa[0] = (uint32_t)ldexp(m_g - 1.0, 23);
+        o->group_mantissa[1] = (uint32_t)ldexp(m_g5 - 1.0, 23);
+    }
 
 #pragma omp parallel for schedule(dynamic, 16) if (P > 1)
     for (int64_t p = 0; p < P; ++p) {
         int64_t br = p / gc, bc = p % gc;
+        int64_t r0 = br * pr, c0 = bc * pc;
+        int64_t h = rows - r0 < pr ? rows - r0 : pr, w = cols - c0 < pc ? cols - c0 : pc;
         block_result res;
-        analyze_block(x + br * pr * ld + bc * pc, ld, pr, pc, crit, scaling, m_g, m_g5,
-                      fp8 + br * pr * cols + bc * pc, cols, &res);
-        if (e8m0) e8m0[p] = (uint8_t)res.e8m0;
-        scale[p] = res.scale; amax[p] = res.amax; err_sum[p] = res.err_sum; nnz[p] = res.nnz;
-        if (err5_sum) err5_sum[p] = res.err5_sum;
-        if (err_sum_unscaled) err_sum_unscaled[p] = res.err_sum_unscaled;
-        mask[p] = accept_e4m3(crit, res.err_sum, res.err5_sum, res.nnz, threshold) ? 0 : 1;
+        analyze_block(x + r0 * ld + c0, ld, h, w, want5, pp->scaling, m_g, m_g5,
+                      o->fp8 + r0 * cols + c0, cols, &res);
+        if (o->e8m0) o->e8m0[p] = (uint8_t)res.e8m0;
+        e8m0_5[p] = (uint8_t)res.e8m0_5; scale5[p] = res.scale5;
+        o->scale[p] = res.scale; o->amax[p] = res.amax; o->err_sum[p] = res.err_sum; o->nnz[p] = res.nnz;
+        if (o->amin) o->amin[p] = res.amin;
+        if (o->err5_sum) o->err5_sum[p] = res.err5_sum;
+        if (o->err_sum_unscaled) o->err_sum_unscaled[p] = res.err_sum_unscaled;
+        /* Algorithm 2: the first accepted type wins, the last type is unconditional */
+        if (accept_e4m3(pp->crit, res.err_sum, res.err5_sum, res.nnz, pp->threshold)) o->mask[p] = 0;
+        else if (three && accept_e5m2(res.amax, res.amin, res.nnz, res.nonfinite)) o->mask[p] = 2;
+        else o->mask[p] = 1;
     }
 
-    if (scope == SCOPE_TENSOR) {                            /* R4: one decision for the tensor */
+    if (pp->scope == SCOPE_TENSOR) {                        /* R4: one decision for the tensor */
         double tot = 0.0, tot5 = 0.0;
         uint64_t n = 0;
         uint8_t m;
         for (int64_t p = 0; p < P; ++p) {
-            tot += err_sum[p]; n += nnz[p];
-            if (crit == CRIT_E4M3_VS_E5M2 && err5_sum) tot5 += err5_sum[p];
+            tot += o->err_sum[p]; n += o->nnz[p];
+            if (want5) tot5 += o->err5_sum[p];
         }
-        if (crit == CRIT_E4M3_VS_E5M2 && !err5_sum) return -1;
-        m = accept_e4m3(crit, tot, tot5, n, threshold) ? 0 : 1;
-        for (int64_t p = 0; p < P; ++p) mask[p] = m;
+        m = accept_e4m3(pp->crit, tot, tot5, n, pp->threshold) ? 0 : 1;
+        for (int64_t p = 0; p < P; ++p) o->mask[p] = m;
     }
 
-    if (bf16) {
-#pragma omp parallel for schedule(dynamic, 16)
-        for (int64_t p = 0; p < P; ++p) {
-            if (!mask[p]) continue;
-            int64_t br = p / gc, bc = p % gc;
-            for (int64_t r = 0; r < pr; ++r)
-                memcpy(bf16 + (br * pr + r) * cols + bc * pc,
-                       x + (br * pr + r) * ld + bc * pc, (size_t)pc * 2);
+    /* emit: E5M2 payload and scale where E5M2 was chosen, original bits where BF16 was chosen */
+#pragma omp parallel for schedule(dynamic, 16) if (P > 1)
+    for (int64_t p = 0; p < P; ++p) {
+        int64_t br = p / gc, bc = p % gc;
+        int64_t r0 = br * pr, c0 = bc * pc;
+        int64_t h = rows - r0 < pr ? rows - r0 : pr, w = cols - c0 < pc ? cols - c0 : pc;
+        if (o->mask[p] == 2) {
+            (void)block_error(x + r0 * ld + c0, ld, h, w, scale5[p], 5, 2, 0, o->fp8 + r0 * cols + c0, cols, NULL);
+            o->scale[p] = scale5[p];
+            if (o->e8m0) o->e8m0[p] = e8m0_5[p];
+        }
+        if (o->mask[p] == 1 && o->bf16)
+            for (int64_t r = 0; r < h; ++r)
+                memcpy(o->bf16 + (r0 + r) * cols + c0, x + (r0 + r) * ld + c0, (size_t)w * 2);
+        if (o->fake) {                                      /* R21, R10 */
+            volatile float s_inv = 1.0f / o->scale[p];
+            for (int64_t r = 0; r < h; ++r)
+                for (int64_t c = 0; c < w; ++c) {
+                    int64_t i = (r0 + r) * cols + c0 + c;
+                    if (o->mask[p] == 1) { o->fake[i] = x[(r0 + r) * ld + c0 + c]; continue; }
+                    {
+                        float q = (float)(o->mask[p] == 2 ? fp8_value(o->fp8[i], 5, 2) : fp8_value(o->fp8[i], 4, 3));
+                        volatile float v = q * s_inv;
+                        o->fake[i] = mor_oracle_f32_to_bf16(v);
+                    }
+                }
         }
     }
+    free(scale5); free(e8m0_5);
     return 0;
+}
+
+/* Two-way recipe with a choice of scaling algorithm: 0 = FP32 amax, 1 = GAM (Algorithm 1, one
+ * group), 2 = E8M0 only.  group_mantissa [1] receives the 23 fraction bits of m_g. */
+int mor_oracle_analyze_quantize_ex(const uint16_t *x, int64_t rows, int64_t cols, int64_t ld,
+                                   int gran, int scope, int crit, int scaling, float threshold,
+                                   uint8_t *fp8, uint16_t *bf16,
+                                   float *scale, float *amax, double *err_sum, uint32_t *nnz,
+                                   uint8_t *mask, double *err5_sum, double *err_sum_unscaled,
+                                   uint8_t *e8m0, uint32_t *group_mantissa)
+{
+    oracle_params pp = { rows, cols, ld, gran, scope, crit, scaling, FMT_E4M3 | FMT_BF16, 0, threshold };
+    uint32_t gm[2] = { 0u, 0u };
+    oracle_out o = { fp8, bf16, scale, amax, err_sum, nnz, mask, err5_sum, err_sum_unscaled, e8m0, gm, NULL, NULL };
+    int rc = mor_oracle_run(&pp, x, &o);
+    if (group_mantissa) *group_mantissa = gm[0];
+    return rc;
 }
 
 /* FP32 amax scaling (the hot path's default). */
@@ -409,34 +513,43 @@ int mor_oracle_analyze_quantize(const uint16_t *x, int64_t rows, int64_t cols, i
 }
 
 /*
- * De-quantize: E4M3 blocks -> bf16_rne(fl32(q * s_inv)), s_inv = fl32(1 / s) (R10);
- * BF16 blocks -> the fallback bits verbatim.  All arrays dense (leading dimension cols).
+ * De-quantize: E4M3 blocks -> bf16_rne(fl32(q * s_inv)), s_inv = fl32(1 / s) (R10); E5M2 blocks
+ * (mask 2) the same with the E5M2 value of the code; BF16 blocks -> the fallback bits verbatim.
+ * All arrays dense (leading dimension cols).
  */
-int mor_oracle_dequantize(const uint8_t *fp8, const float *scale, const uint8_t *mask,
-                          const uint16_t *bf16, int64_t rows, int64_t cols, int gran,
-                          uint16_t *y)
+int mor_oracle_dequantize_ex(const uint8_t *fp8, const float *scale, const uint8_t *mask,
+                             const uint16_t *bf16, int64_t rows, int64_t cols, int gran, int ragged,
+                             uint16_t *y)
 {
     int64_t pr, pc, gr, gc, P;
-    if (rows <= 0 || cols <= 0 || part_shape(gran, rows, cols, &pr, &pc)) return -1;
-    gr = rows / pr; gc = cols / pc; P = gr * gc;
+    if (rows <= 0 || cols <= 0 || part_shape_ex(gran, rows, cols, ragged, &pr, &pc)) return -1;
+    gr = (rows + pr - 1) / pr; gc = (cols + pc - 1) / pc; P = gr * gc;
 #pragma omp parallel for schedule(dynamic, 16)
     for (int64_t p = 0; p < P; ++p) {
         int64_t br = p / gc, bc = p % gc;
+        int64_t r0 = br * pr, c0 = bc * pc;
+        int64_t h = rows - r0 < pr ? rows - r0 : pr, w = cols - c0 < pc ? cols - c0 : pc;
         volatile float s_inv = 1.0f / scale[p];
-        for (int64_t r = 0; r < pr; ++r)
-            for (int64_t c = 0; c < pc; ++c) {
-                int64_t i = (br * pr + r) * cols + bc * pc + c;
-                if (mask[p]) {
+        for (int64_t r = 0; r < h; ++r)
+            for (int64_t c = 0; c < w; ++c) {
+                int64_t i = (r0 + r) * cols + c0 + c;
+                if (mask[p] == 1) {
                     if (!bf16) continue;
                     y[i] = bf16[i];
                 } else {
-                    float q = (float)fp8_value(fp8[i], 4, 3);       /* exact in binary32 */
+                    float q = (float)(mask[p] == 2 ? fp8_value(fp8[i], 5, 2) : fp8_value(fp8[i], 4, 3));  /* exact */
                     volatile float v = q * s_inv;
                     y[i] = mor_oracle_f32_to_bf16(v);
                 }
             }
     }
     return 0;
+}
+int mor_oracle_dequantize(const uint8_t *fp8, const float *scale, const uint8_t *mask,
+                          const uint16_t *bf16, int64_t rows, int64_t cols, int gran,
+                          uint16_t *y)
+{
+    return mor_oracle_dequantize_ex(fp8, scale, mask, bf16, rows, cols, gran, 0, y);
 }
 
 /*
@@ -451,22 +564,27 @@ typedef struct {
     double err_sum_total, mean_err;
     uint32_t hist[12];
     uint32_t pad_;
+    uint64_t n_e5m2_part, n_elem_e5m2;
 } oracle_stats;
 
-int mor_oracle_select_stats(const float *err_sum, const uint32_t *nnz, const uint8_t *mask,
-                            int64_t rows, int64_t cols, int gran, float threshold, float near_tol,
-                            oracle_stats *out)
+int mor_oracle_select_stats_ex(const float *err_sum, const uint32_t *nnz, const uint8_t *mask,
+                               int64_t rows, int64_t cols, int gran, int ragged, float threshold, float near_tol,
+                               oracle_stats *out)
 {
-    int64_t pr, pc, P;
-    if (rows <= 0 || cols <= 0 || part_shape(gran, rows, cols, &pr, &pc)) return -1;
-    P = (rows / pr) * (cols / pc);
+    int64_t pr, pc, gc, P;
+    if (rows <= 0 || cols <= 0 || part_shape_ex(gran, rows, cols, ragged, &pr, &pc)) return -1;
+    gc = (cols + pc - 1) / pc;
+    P = ((rows + pr - 1) / pr) * gc;
     memset(out, 0, sizeof *out);
     out->n_part = (uint64_t)P;
     for (int64_t p = 0; p < P; ++p) {
+        int64_t r0 = (p / gc) * pr, c0 = (p % gc) * pc;
+        int64_t h = rows - r0 < pr ? rows - r0 : pr, w = cols - c0 < pc ? cols - c0 : pc;
         volatile float metric = nnz[p] ? err_sum[p] / (float)nnz[p] : 0.0f;
         int bin = 0;
-        if (mask[p]) { out->n_bf16_part++; out->n_elem_bf16 += (uint64_t)(pr * pc); }
-        else         { out->n_fp8_part++;  out->n_elem_fp8  += (uint64_t)(pr * pc); }
+        if (mask[p] == 1)      { out->n_bf16_part++; out->n_elem_bf16 += (uint64_t)(h * w); }
+        else if (mask[p] == 2) { out->n_e5m2_part++; out->n_elem_e5m2 += (uint64_t)(h * w); }
+        else                   { out->n_fp8_part++;  out->n_elem_fp8  += (uint64_t)(h * w); }
         out->err_sum_total += (double)err_sum[p];
         out->nnz_total += nnz[p];
         if (!(metric < INFINITY)) bin = 11;
@@ -479,6 +597,29 @@ int mor_oracle_select_stats(const float *err_sum, const uint32_t *nnz, const uin
     }
     out->mean_err = out->nnz_total ? out->err_sum_total / (double)out->nnz_total : 0.0;
     return 0;
+}
+int mor_oracle_select_stats(const float *err_sum, const uint32_t *nnz, const uint8_t *mask,
+                            int64_t rows, int64_t cols, int gran, float threshold, float near_tol,
+                            oracle_stats *out)
+{
+    return mor_oracle_select_stats_ex(err_sum, nnz, mask, rows, cols, gran, 0, threshold, near_tol, out);
+}
+
+/*
+ * Running histogram of one tensor's metric over mini-batches (Section 4.1.3, the paragraphs on
+ * Figure "annotation"): every mini-batch adds ONE count, in the bin of the tensor's relative
+ * error of that step; the histogram is cleared every `reset_interval` steps (6000 in the paper)
+ * before the step's count is added.  `step` counts from 0.  The metric is taken in binary32.
+ */
+void mor_oracle_histogram_update(uint32_t *hist12, float tensor_metric, int64_t step, int64_t reset_interval)
+{
+    int bin = 0;
+    if (reset_interval > 0 && step % reset_interval == 0) memset(hist12, 0, 12 * sizeof(uint32_t));
+    if (!(tensor_metric < INFINITY)) bin = 11;
+    else
+        for (int k = 1; k <= 11; ++k)
+            if (tensor_metric >= (float)(0.005 * k)) bin = k;
+    hist12[bin]++;
 }
 
 int mor_oracle_threads(void)

@@ -102,9 +102,11 @@ def gam_scale(b_amax, g_amax, qmax, e8m0_only=False):
     return m_g * Fraction(2) ** e, e, m_g
 
 
-def analyze_block(bits, crit="mean_rel_err", threshold=0.045, scaling="fp32_amax", g_amax=None):
+def analyze_block(bits, crit="mean_rel_err", threshold=0.045, scaling="fp32_amax", g_amax=None, three_way=False):
     """bits: iterable of BF16 bit patterns of ONE block.  Returns dict with exact-rational sums.
-    scaling 'gam' / 'e8m0' take the block's scale from Algorithm 1 (g_amax = amax of the tensor)."""
+    scaling 'gam' / 'e8m0' take the block's scale from Algorithm 1 (g_amax = amax of the tensor).
+    three_way: type list [E4M3, E5M2, BF16] of Section 3.2; out['choice'] is 'e4m3', 'e5m2' or 'bf16'
+    and out['codes'] / out['scale'] describe the chosen payload (E4M3's when BF16 is chosen)."""
     bits = [int(b) for b in bits]
     a = max(b & 0x7FFF for b in bits)
     amax = bf16_to_f32(a)
@@ -143,4 +145,13 @@ def analyze_block(bits, crit="mean_rel_err", threshold=0.045, scaling="fp32_amax
         metric = err / out["nnz"] if out["nnz"] else Fraction(0)
         out["metric"] = metric
         out["fp8"] = metric < Fraction(float(np.float32(threshold)))
+    out["choice"] = "e4m3" if out["fp8"] else "bf16"
+    if three_way and not out["fp8"]:
+        # Eq. (4): max|b| / min|b| < 57344 / 2^-14 over the non-zero elements, in exact rationals
+        mags = [Fraction(float(bf16_to_f32(b & 0x7FFF))) for b in bits if b & 0x7FFF and (b & 0x7FFF) < 0x7F80]
+        finite = all((b & 0x7FFF) < 0x7F80 for b in bits)
+        fits = finite and (not mags or max(mags) / min(mags) < Fraction(57344) / Fraction(1, 2 ** 14))
+        if fits:
+            s5, codes5, _ = run(57344.0, 5, 2)
+            out.update(choice="e5m2", scale=s5, codes=codes5)
     return out
