@@ -177,10 +177,10 @@ def test_fake_quantize_of_grid_values_is_the_identity(oracle):
 def test_fake_quantize_three_way_decodes_e5m2_blocks(oracle):
     x = np.zeros((2, 128), dtype=np.float32)
     x[0, 0] = 1.0; x[0, 1:] = 2.0 ** -20          # E5M2 block, exactly representable there
-    x[1, :] = 1.0
+    x[1, :] = 1.0                                 # both formats exact: Eq. (3) ties, Eq. (4) holds -> E5M2 as well
     xb = W.f32_to_bf16_bits(x)
     a = oracle.analyze_quantize(xb, "sub1x128", crit="e4m3_vs_e5m2", formats="e4m3|e5m2|bf16", want_fake=True)
-    assert a.mask.tolist() == [2, 1] and np.array_equal(a.fake, xb)
+    assert a.mask.tolist() == [2, 2] and np.array_equal(a.fake, xb)
 
 
 # ---------------------------------------------------------------- running histogram (Section 4.1.3)
