@@ -92,7 +92,7 @@ def main() -> int:
         params = B.make_params(rows, cols, gran, "partition", "mean_rel_err", THRESHOLD)
         x = torch.from_numpy(xb.view(np.int16)).to(dev)
         out = B.alloc_outputs(params, dev, want_bf16=True)
-        stats = torch.zeros(128, dtype=torch.uint8, device=dev)
+        stats = torch.zeros(B.STATS_BYTES, dtype=torch.uint8, device=dev)
         ops.append({"name": name, "gran": gran, "params": params, "x": x, "out": out, "stats": stats, "n": rows * cols,
                     "P": B.mor_num_partitions(gran, rows, cols), "host": xb})
     n_total = sum(o["n"] for o in ops)

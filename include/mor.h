@@ -4,11 +4,12 @@
  * MoR (Mixture of Representations) takes a BF16 GEMM operand X, a partition B of
  * X into blocks, an ordered list of representation types and acceptance metrics,
  * and returns the quantized tensor X_Q plus per-block metadata D (Algorithm 2).
- * This library implements the recipe with the type list [E4M3, BF16]:
- * for every block it computes amax and a scale (Algorithm 1: plain per-block
- * FP32 form, GAM, or E8M0 only), quantizes to FP8 E4M3, evaluates the acceptance metric
- * (Eq. 1-2 or Eq. 3) on the de-quantized values, and keeps either the FP8
- * payload or the original BF16 block.
+ * This library implements the recipes with the type lists [E4M3, BF16] and
+ * [E4M3, E5M2, BF16]: for every block it computes amax and a scale (Algorithm 1:
+ * plain per-block FP32 form, GAM, or E8M0 only), quantizes to FP8 E4M3, evaluates
+ * the acceptance metric (Eq. 1-2 or Eq. 3) on the de-quantized values, and keeps
+ * the E4M3 payload, (three-way recipe, Eq. 4) an E5M2 payload, or the original
+ * BF16 block.
  *
  * Conventions shared by all entry points
  *   - Every data pointer is DEVICE memory owned by the caller.  mor_params and
@@ -18,10 +19,12 @@
  *     Results are valid once the stream has reached the end of the call's work.
  *   - Tensors are row-major; a leading dimension `ld` counts ELEMENTS between
  *     the starts of consecutive rows.
- *   - Blocks are numbered row-major over the block grid: for 1x128 sub-channels
- *     p = r * (cols/128) + c/128, for 128x128 blocks p = (r/128)*(cols/128) + c/128,
- *     for per-tensor granularity there is one block, p = 0.  P = number of blocks.
- *   - mask[p] = 0: block kept as FP8 E4M3;  mask[p] = 1: block kept as BF16.
+ *   - Blocks are numbered row-major over the block grid: for blocks of pr x pc elements
+ *     p = (r/pr) * ceil(cols/pc) + c/pc (1x128 sub-channels: p = r * (cols/128) + c/128;
+ *     128x128 blocks: p = (r/128)*(cols/128) + c/128; per-tensor: one block, p = 0).
+ *     P = number of blocks.
+ *   - mask[p] = 0: block kept as FP8 E4M3;  mask[p] = 1: block kept as BF16;
+ *     mask[p] = 2 (three-way recipe only): block kept as FP8 E5M2.
  *   - Argument errors are reported synchronously through the return code and
  *     nothing is launched.  Non-finite data is not an error: a block holding Inf
  *     or NaN gets scale 1, err_sum = +inf and is kept in BF16.
@@ -51,12 +54,31 @@ typedef enum {
 /* The partition B of the tensor (Section 3, first paragraph). */
 typedef enum {
     MOR_GRAN_TENSOR = 0,        /* one block: the whole tensor */
-    MOR_GRAN_SUB_1x128 = 1,     /* sub-channel blocks of 1 x 128 along the columns; cols % 128 == 0 */
-    MOR_GRAN_BLOCK_128x128 = 2  /* 2-D blocks of 128 x 128; rows % 128 == 0 and cols % 128 == 0 */
+    MOR_GRAN_SUB_1x128 = 1,     /* sub-channel blocks of 1 x 128 along the columns (sub-rows) */
+    MOR_GRAN_BLOCK_128x128 = 2, /* 2-D blocks of 128 x 128 */
+    MOR_GRAN_CHANNEL_ROW = 3,   /* per-channel: every row is one block (first GEMM operand, Section 4.1.1);
+                                   cols <= 16384 */
+    MOR_GRAN_CHANNEL_COL = 4,   /* per-channel: every column is one block (second GEMM operand) */
+    MOR_GRAN_SUB_128x1 = 5,     /* sub-channel blocks of 128 x 1 along the rows (sub-columns: the transposed
+                                   operands of the backward GEMMs, Section 4) */
+    MOR_GRAN_BLOCK_64x64 = 6    /* 2-D blocks of 64 x 64 (block-size ablation of Section 4.1.2) */
 } mor_granularity;
+/* Unless MOR_FLAG_RAGGED is set, rows and cols must be whole numbers of blocks.  cols % 8 == 0 always
+ * (16-byte rows). */
 
-/* Representation types, most to least aggressive (Section 3); `formats` is a bit-or. */
+/* Representation types, most to least aggressive (Section 3); `formats` is a bit-or:
+ * MOR_FMT_E4M3 | MOR_FMT_BF16 (two types) or MOR_FMT_E4M3 | MOR_FMT_E5M2 | MOR_FMT_BF16 (the three-way
+ * recipe of Section 3.2: a block that fails M_1 is kept in E5M2 when its dynamic range fits E5M2's
+ * normal range, Eq. (4): max|b| / min|b| < 57344 / 2^-14, the minimum taken over the non-zero elements,
+ * a block without non-zero elements passing; otherwise BF16).  Three types need MOR_SCOPE_PARTITION and a
+ * granularity other than MOR_GRAN_TENSOR, MOR_GRAN_CHANNEL_COL and MOR_GRAN_SUB_128x1. */
 enum { MOR_FMT_E4M3 = 1, MOR_FMT_E5M2 = 2, MOR_FMT_BF16 = 4 };
+
+/* mor_params.flags */
+enum {
+    MOR_FLAG_RAGGED = 1         /* rows / cols need not be multiples of the block shape (the paper is silent on
+                                   edges): the grid is ceil(rows/pr) x ceil(cols/pc) and edge blocks are smaller */
+};
 
 /* Acceptance metric M_1 for E4M3. */
 typedef enum {
@@ -96,18 +118,22 @@ typedef struct mor_params {
     int32_t  scope;       /* mor_scope */
     int32_t  criterion;   /* mor_criterion */
     int32_t  scaling;     /* mor_scaling */
-    uint32_t formats;     /* must be MOR_FMT_E4M3 | MOR_FMT_BF16 */
+    uint32_t formats;     /* MOR_FMT_E4M3 | MOR_FMT_BF16, or MOR_FMT_E4M3 | MOR_FMT_E5M2 | MOR_FMT_BF16 */
     float    threshold;   /* th_E4M3 of Eq. (2), e.g. 0.045f (Section 4.1.1); ignored for Eq. (3) */
+    uint32_t flags;       /* MOR_FLAG_* bits */
+    uint32_t reserved;    /* must be 0 */
 } mor_params;
 
 typedef struct mor_outputs {
-    uint8_t*  fp8;      /* [rows x ld_fp8] E4M3 codes, written for EVERY block (also BF16 ones) */
+    uint8_t*  fp8;      /* [rows x ld_fp8] E4M3 codes, written for EVERY block (also BF16 ones); E5M2 codes in
+                           blocks with mask == 2 */
     int64_t   ld_fp8;   /* >= cols, multiple of 8 */
     uint16_t* bf16;     /* [rows x ld_bf16] BF16 fallback: input bits, written ONLY in blocks with
                            mask == 1, other regions untouched.  May be NULL (no payload emitted)
                            and may equal the input pointer (writes are then skipped). */
     int64_t   ld_bf16;  /* >= cols, multiple of 8 (ignored when bf16 is NULL) */
-    float*    scale;    /* [P] multiplier s: q = E4M3(fl32(x * s)) */
+    float*    scale;    /* [P] multiplier s of the payload in fp8: q = E4M3(fl32(x * s)); in blocks with
+                           mask == 2 the E5M2 scale (from 57344 / amax): q = E5M2(fl32(x * s)) */
     float*    amax;     /* [P] max |x| of the block (a BF16 value widened to float) */
     float*    err_sum;  /* [P] sum over non-zero x of |y - q| / |y|, y = fl32(x * s); a non-zero x
                            whose q is zero contributes 1 */
@@ -117,15 +143,18 @@ typedef struct mor_outputs {
                            for MOR_CRIT_E4M3_VS_E5M2, otherwise ignored and may be NULL */
     uint8_t*  scale_e8m0;     /* [P] MOR_SCALE_GAM / MOR_SCALE_E8M0: biased exponent (bias 127) of scale[p];
                                  optional (NULL = not written); untouched for MOR_SCALE_FP32_AMAX */
-    uint32_t* group_mantissa; /* [1] MOR_SCALE_GAM / MOR_SCALE_E8M0: the 23 fraction bits of m_g (0 for
-                                 E8M0-only), so that scale[p] == bits((scale_e8m0[p] << 23) | group_mantissa);
+    uint32_t* group_mantissa; /* [2] MOR_SCALE_GAM / MOR_SCALE_E8M0: [0] the 23 fraction bits of m_g (0 for
+                                 E8M0-only), so that scale[p] == bits((scale_e8m0[p] << 23) | group_mantissa[0]);
+                                 [1] the same for the E5M2 scales (used by blocks with mask == 2);
                                  optional; untouched for MOR_SCALE_FP32_AMAX */
+    float*    amin;     /* [P] three-way recipe: smallest non-zero |x| of blocks that failed M_1 (0 when the block
+                           has no non-zero element, and for blocks kept in E4M3); optional */
 } mor_outputs;
 
 /* Selection statistics (Section 4.1.3). Lives in DEVICE memory; 8-byte aligned. */
 typedef struct mor_stats {
     uint64_t n_part;            /* P */
-    uint64_t n_fp8_part;        /* blocks with mask == 0 */
+    uint64_t n_fp8_part;        /* blocks with mask == 0 (E4M3) */
     uint64_t n_bf16_part;       /* blocks with mask == 1 */
     uint64_t n_elem_fp8;        /* elements inside FP8 blocks */
     uint64_t n_elem_bf16;       /* elements inside BF16 blocks */
@@ -136,6 +165,9 @@ typedef struct mor_stats {
     uint32_t hist[12];          /* block metrics err_sum/nnz (binary32) in bins [0,0.5%), [0.5%,1%),
                                    ..., [5%,5.5%), [5.5%, inf] */
     uint32_t flags;             /* MOR_STATS_FLAG_* bits; 0 from mor_select_stats */
+    uint32_t reserved;
+    uint64_t n_e5m2_part;       /* blocks with mask == 2 (three-way recipe) */
+    uint64_t n_elem_e5m2;       /* elements inside E5M2 blocks */
 } mor_stats;
 /* Set by mor_analyze_quantize_batch for a per-tensor operand whose BF16 decision was already proven
  * by the amax pass (enough elements certain to flush to zero), so that the fallback payload was
@@ -143,8 +175,10 @@ typedef struct mor_stats {
  * outputs do not depend on it. */
 #define MOR_STATS_FLAG_FUSED_FALLBACK 1u
 
-/* Number of blocks for a shape, or -1 if the shape is invalid for the granularity. */
+/* Number of blocks for a shape made of whole blocks, or -1 if the shape is invalid for the granularity. */
 int64_t mor_num_partitions(int32_t granularity, int64_t rows, int64_t cols);
+/* The same for a parameter set (honours MOR_FLAG_RAGGED). */
+int64_t mor_params_num_partitions(const mor_params* params);
 
 /* Bytes of device scratch mor_analyze_quantize needs for these parameters (0 on invalid
  * parameters).  Contents need no initialisation and are meaningless afterwards. */
@@ -175,7 +209,11 @@ typedef enum {
     MOR_KERNEL_SCOPE_REDUCE = 7, MOR_KERNEL_SCOPE_DECIDE = 8, MOR_KERNEL_SCOPE_FILL_MASK = 9,
     MOR_KERNEL_STATS_PARTIAL = 10, MOR_KERNEL_STATS_FINAL = 11,
     MOR_KERNEL_GROUP_AMAX = 12,      /* amax of the whole operand for GAM scaling of sub-tensor blocks */
-    MOR_KERNEL_GROUP_MANTISSA = 13
+    MOR_KERNEL_GROUP_MANTISSA = 13,
+    MOR_KERNEL_TEAM_BLOCK = 14,      /* 64x64 blocks, per-channel rows, and 128x128 blocks with ragged edges,
+                                        three types or fake quantization */
+    MOR_KERNEL_COLUMN_TILE = 15,     /* 128x1 sub-columns; per-channel columns: amax and quantize passes */
+    MOR_KERNEL_COLUMN_COMBINE = 16   /* per-channel columns: scales from the amax partials, final decision */
 } mor_kernel_id;
 #define MOR_PROFILE_MAX 16
 typedef struct mor_profile {
@@ -218,9 +256,10 @@ mor_status mor_analyze_quantize_batch(const mor_batch_item* items, int32_t n_ite
 /*
  * Inverse path (the de-quantize / de-scale half of the fake-quantization workflow, Section 4,
  * Figure 4): y = bf16_rne(fl32(E4M3value(fp8) * fl32(1 / scale[p]))) in blocks with mask 0,
+ * the same with the E5M2 value of the code in blocks with mask 2,
  * y = bf16 fallback bits in blocks with mask 1.  `bf16` may be NULL; blocks with mask 1 are then
  * left untouched in y.
- * Uses rows, cols and granularity of params; params->ld is ignored.
+ * Uses rows, cols, granularity and flags of params; params->ld is ignored.
  */
 mor_status mor_dequantize(const mor_params* params, const uint8_t* fp8, int64_t ld_fp8,
                           const float* scale, const uint8_t* mask,
@@ -230,13 +269,29 @@ mor_status mor_dequantize(const mor_params* params, const uint8_t* fp8, int64_t 
 /*
  * The same from the stored form of GAM / E8M0 scaling (Algorithm 1 and the paragraph before it: the
  * per-block scale is rebuilt on the fly from the shared 23-bit group mantissa and the block's 8-bit
- * exponent): scale[p] = bits((scale_e8m0[p] << 23) | group_mantissa[0]).  scale_e8m0 [P] and
- * group_mantissa [1] are device arrays as written by mor_analyze_quantize.
+ * exponent): scale[p] = bits((scale_e8m0[p] << 23) | group_mantissa[0]), with group_mantissa[1] in
+ * blocks with mask 2.  scale_e8m0 [P] and group_mantissa [2] are device arrays as written by
+ * mor_analyze_quantize.
  */
 mor_status mor_dequantize_e8m0(const mor_params* params, const uint8_t* fp8, int64_t ld_fp8,
                                const uint8_t* scale_e8m0, const uint32_t* group_mantissa, const uint8_t* mask,
                                const uint16_t* bf16, int64_t ld_bf16,
                                uint16_t* y, int64_t ld_y, void* stream);
+
+/*
+ * Fake quantization (Section 4, Figure 4), the form in which the paper's training runs applied MoR:
+ * y = de-quantize(quantize(x)) in one call, BF16 in and BF16 out.  Blocks kept in E4M3 (or E5M2) carry
+ * the information loss of that format, y = bf16_rne(fl32(value(code) * fl32(1 / scale[p]))); blocks kept
+ * in BF16 are copied unchanged.  The FP8 payload itself is not materialised: meta->fp8 and meta->bf16
+ * are ignored (may be NULL); the [P] arrays of `meta` are written as by mor_analyze_quantize.
+ *   y          device, [rows x ld_y] BF16 bit patterns, 16-byte aligned, ld_y >= cols, ld_y % 8 == 0;
+ *              must not overlap x
+ *   workspace  device scratch of at least mor_workspace_bytes(params) bytes
+ * Equivalent to mor_analyze_quantize followed by mor_dequantize, with 2 bytes read and 2 written per
+ * element (per-tensor granularity: 4 read) instead of 2 + 1 (+ 2) written and 1 (+ 2) + 2 read again.
+ */
+mor_status mor_fake_quantize(const mor_params* params, const uint16_t* x, uint16_t* y, int64_t ld_y,
+                             const mor_outputs* meta, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Selection statistics of one analysed operand (Section 4.1.3): counts of blocks and elements
@@ -246,6 +301,20 @@ mor_status mor_dequantize_e8m0(const mor_params* params, const uint8_t* fp8, int
  */
 mor_status mor_select_stats(const mor_params* params, const float* err_sum, const uint32_t* nnz,
                             const uint8_t* mask, float near_tol, mor_stats* out_dev, void* stream);
+
+/*
+ * Running histogram of one tensor's relative error over training steps (Section 4.1.3, the paragraphs
+ * on the heat maps): every mini-batch adds ONE count to the 0.5 %-wide bin (last bin open from 5.5 %)
+ * that holds the tensor's error of that step, and the histogram is cleared every reset_interval steps
+ * (6000 in the paper) before the step's count is added.
+ *   hist12_dev      device uint32[12], updated in place (not atomically: one call at a time per histogram)
+ *   stats_dev       device mor_stats of this step's call for the tensor; the tensor's error is
+ *                   (float)stats_dev->mean_err = sum(err_sum) / sum(nnz)
+ *   step            step counter from 0; step % reset_interval == 0 clears first
+ *   reset_interval  > 0, or 0 to never clear
+ */
+mor_status mor_histogram_update(uint32_t* hist12_dev, const mor_stats* stats_dev, int64_t step,
+                                int64_t reset_interval, void* stream);
 
 const char* mor_status_string(mor_status status);
 

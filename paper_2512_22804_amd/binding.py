@@ -16,45 +16,56 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("MOR_LIB_PATH", os.path.join(_HERE, "libmor.so"))
 
 MOR_GRAN_TENSOR, MOR_GRAN_SUB_1x128, MOR_GRAN_BLOCK_128x128 = 0, 1, 2
+MOR_GRAN_CHANNEL_ROW, MOR_GRAN_CHANNEL_COL, MOR_GRAN_SUB_128x1, MOR_GRAN_BLOCK_64x64 = 3, 4, 5, 6
 MOR_FMT_E4M3, MOR_FMT_E5M2, MOR_FMT_BF16 = 1, 2, 4
+MOR_FLAG_RAGGED = 1
 MOR_CRIT_MEAN_REL_ERR, MOR_CRIT_E4M3_VS_E5M2 = 0, 1
 MOR_SCOPE_PARTITION, MOR_SCOPE_TENSOR = 0, 1
 MOR_SCALE_FP32_AMAX, MOR_SCALE_GAM, MOR_SCALE_E8M0 = 0, 1, 2
 
-GRAN = {"tensor": MOR_GRAN_TENSOR, "sub1x128": MOR_GRAN_SUB_1x128, "block128": MOR_GRAN_BLOCK_128x128}
+GRAN = {"tensor": MOR_GRAN_TENSOR, "sub1x128": MOR_GRAN_SUB_1x128, "block128": MOR_GRAN_BLOCK_128x128,
+        "channel_row": MOR_GRAN_CHANNEL_ROW, "channel_col": MOR_GRAN_CHANNEL_COL, "sub128x1": MOR_GRAN_SUB_128x1,
+        "block64": MOR_GRAN_BLOCK_64x64}
+FORMATS = {"e4m3|bf16": MOR_FMT_E4M3 | MOR_FMT_BF16, "e4m3|e5m2|bf16": MOR_FMT_E4M3 | MOR_FMT_E5M2 | MOR_FMT_BF16}
 CRIT = {"mean_rel_err": MOR_CRIT_MEAN_REL_ERR, "e4m3_vs_e5m2": MOR_CRIT_E4M3_VS_E5M2}
 SCOPE = {"partition": MOR_SCOPE_PARTITION, "tensor": MOR_SCOPE_TENSOR}
 SCALING = {"fp32_amax": MOR_SCALE_FP32_AMAX, "gam": MOR_SCALE_GAM, "e8m0": MOR_SCALE_E8M0}
 
-EXPORTS = ("mor_num_partitions", "mor_workspace_bytes", "mor_analyze_quantize", "mor_analyze_quantize_profiled",
-           "mor_batch_workspace_bytes", "mor_analyze_quantize_batch", "mor_dequantize", "mor_dequantize_e8m0", "mor_select_stats",
-           "mor_status_string")
+EXPORTS = ("mor_num_partitions", "mor_params_num_partitions", "mor_workspace_bytes", "mor_analyze_quantize",
+           "mor_analyze_quantize_profiled", "mor_batch_workspace_bytes", "mor_analyze_quantize_batch", "mor_fake_quantize",
+           "mor_dequantize", "mor_dequantize_e8m0", "mor_select_stats", "mor_histogram_update", "mor_status_string")
 MOR_BATCH_MAX = 64
 MOR_PROFILE_MAX = 16
 MOR_STATS_FLAG_FUSED_FALLBACK = 1
 
 KERNEL_NAMES = {1: "sub1x128", 2: "block128", 3: "tensor_amax", 4: "tensor_quant", 5: "tensor_finalize",
                 6: "fallback_copy", 7: "scope_reduce", 8: "scope_decide", 9: "scope_fill_mask",
-                10: "stats_partial", 11: "stats_final", 12: "group_amax", 13: "group_mantissa"}
+                10: "stats_partial", 11: "stats_final", 12: "group_amax", 13: "group_mantissa", 14: "team_block",
+                15: "column_tile", 16: "column_combine"}
 
 
 class MorParams(C.Structure):
     _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64),
                 ("granularity", C.c_int32), ("scope", C.c_int32), ("criterion", C.c_int32), ("scaling", C.c_int32),
-                ("formats", C.c_uint32), ("threshold", C.c_float)]
+                ("formats", C.c_uint32), ("threshold", C.c_float), ("flags", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class MorOutputs(C.Structure):
     _fields_ = [("fp8", C.c_void_p), ("ld_fp8", C.c_int64), ("bf16", C.c_void_p), ("ld_bf16", C.c_int64),
                 ("scale", C.c_void_p), ("amax", C.c_void_p), ("err_sum", C.c_void_p), ("nnz", C.c_void_p),
-                ("mask", C.c_void_p), ("err5_sum", C.c_void_p), ("scale_e8m0", C.c_void_p), ("group_mantissa", C.c_void_p)]
+                ("mask", C.c_void_p), ("err5_sum", C.c_void_p), ("scale_e8m0", C.c_void_p), ("group_mantissa", C.c_void_p),
+                ("amin", C.c_void_p)]
 
 
 class MorStats(C.Structure):
     _fields_ = [("n_part", C.c_uint64), ("n_fp8_part", C.c_uint64), ("n_bf16_part", C.c_uint64),
                 ("n_elem_fp8", C.c_uint64), ("n_elem_bf16", C.c_uint64), ("nnz_total", C.c_uint64),
                 ("n_near_threshold", C.c_uint64), ("err_sum_total", C.c_double), ("mean_err", C.c_double),
-                ("hist", C.c_uint32 * 12), ("flags", C.c_uint32)]
+                ("hist", C.c_uint32 * 12), ("flags", C.c_uint32), ("reserved", C.c_uint32),
+                ("n_e5m2_part", C.c_uint64), ("n_elem_e5m2", C.c_uint64)]
+
+
+STATS_BYTES = C.sizeof(MorStats)     # 144
 
 
 class MorProfile(C.Structure):
@@ -85,6 +96,13 @@ def load():
         L = C.CDLL(LIB_PATH)
         L.mor_num_partitions.argtypes = [C.c_int32, C.c_int64, C.c_int64]
         L.mor_num_partitions.restype = C.c_int64
+        L.mor_params_num_partitions.argtypes = [C.POINTER(MorParams)]
+        L.mor_params_num_partitions.restype = C.c_int64
+        L.mor_fake_quantize.argtypes = [C.POINTER(MorParams), C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(MorOutputs), C.c_void_p,
+                                        C.c_size_t, C.c_void_p]
+        L.mor_fake_quantize.restype = C.c_int
+        L.mor_histogram_update.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p]
+        L.mor_histogram_update.restype = C.c_int
         L.mor_workspace_bytes.argtypes = [C.POINTER(MorParams)]
         L.mor_workspace_bytes.restype = C.c_size_t
         L.mor_analyze_quantize.argtypes = [C.POINTER(MorParams), C.c_void_p, C.POINTER(MorOutputs), C.c_void_p,
@@ -114,18 +132,23 @@ def load():
 
 
 def make_params(rows: int, cols: int, gran: str | int, scope: str | int = "partition", crit: str | int = "mean_rel_err",
-                threshold: float = 0.045, ld: int | None = None, formats: int = MOR_FMT_E4M3 | MOR_FMT_BF16,
-                scaling: str | int = MOR_SCALE_FP32_AMAX) -> MorParams:
+                threshold: float = 0.045, ld: int | None = None, formats: int | str = MOR_FMT_E4M3 | MOR_FMT_BF16,
+                scaling: str | int = MOR_SCALE_FP32_AMAX, ragged: bool = False) -> MorParams:
     g = GRAN[gran] if isinstance(gran, str) else gran
     s = SCOPE[scope] if isinstance(scope, str) else scope
     c = CRIT[crit] if isinstance(crit, str) else crit
     sc = SCALING[scaling] if isinstance(scaling, str) else scaling
-    return MorParams(rows, cols, cols if ld is None else ld, g, s, c, sc, formats, threshold)
+    f = FORMATS[formats] if isinstance(formats, str) else formats
+    return MorParams(rows, cols, cols if ld is None else ld, g, s, c, sc, f, threshold, MOR_FLAG_RAGGED if ragged else 0, 0)
 
 
 def mor_num_partitions(gran: str | int, rows: int, cols: int) -> int:
     g = GRAN[gran] if isinstance(gran, str) else gran
     return int(load().mor_num_partitions(g, rows, cols))
+
+
+def mor_params_num_partitions(params: MorParams) -> int:
+    return int(load().mor_params_num_partitions(C.byref(params)))
 
 
 def mor_workspace_bytes(params: MorParams) -> int:
@@ -154,16 +177,18 @@ class MorResult:
     workspace: torch.Tensor | None
     params: MorParams
     scale_e8m0: torch.Tensor | None = None      # (P,) uint8, GAM / E8M0 scaling only
-    group_mantissa: torch.Tensor | None = None  # (1,) int32, GAM / E8M0 scaling only
+    group_mantissa: torch.Tensor | None = None  # (2,) int32, GAM / E8M0 scaling only: E4M3's, E5M2's
+    amin: torch.Tensor | None = None            # (P,) float32, three-way recipe only
 
 
-def alloc_outputs(params: MorParams, device, want_bf16: bool = True, bf16_fill: int | None = None) -> MorResult:
+def alloc_outputs(params: MorParams, device, want_bf16: bool = True, bf16_fill: int | None = None,
+                  want_fp8: bool = True) -> MorResult:
     """Allocate the output buffers of one call (dense leading dimensions)."""
     rows, cols = params.rows, params.cols
-    P = mor_num_partitions(params.granularity, rows, cols)
+    P = mor_params_num_partitions(params)
     if P < 0:
         raise MorError(2, "alloc_outputs")
-    fp8 = torch.empty((rows, cols), dtype=torch.uint8, device=device)
+    fp8 = torch.empty((rows, cols), dtype=torch.uint8, device=device) if want_fp8 else None
     bf16 = None
     if want_bf16:
         bf16 = (torch.empty((rows, cols), dtype=torch.int16, device=device) if bf16_fill is None else
@@ -175,15 +200,17 @@ def alloc_outputs(params: MorParams, device, want_bf16: bool = True, bf16_fill: 
     e8m0 = gmant = None
     if params.scaling != MOR_SCALE_FP32_AMAX:
         e8m0 = torch.full((P,), 0xEE, dtype=torch.uint8, device=device)
-        gmant = torch.full((1,), -1, dtype=torch.int32, device=device)
+        gmant = torch.full((2,), -1, dtype=torch.int32, device=device)
+    amin = torch.full((P,), -1.0, dtype=torch.float32, device=device) if params.formats & MOR_FMT_E5M2 else None
     return MorResult(fp8, bf16, f32(), f32(), f32(), torch.empty(P, dtype=torch.int32, device=device),
-                     torch.empty(P, dtype=torch.uint8, device=device), err5, ws, params, e8m0, gmant)
+                     torch.empty(P, dtype=torch.uint8, device=device), err5, ws, params, e8m0, gmant, amin)
 
 
 def _outputs_struct(out: MorResult) -> MorOutputs:
-    return MorOutputs(_ptr(out.fp8), out.fp8.stride(0), _ptr(out.bf16), out.bf16.stride(0) if out.bf16 is not None else 0,
+    return MorOutputs(_ptr(out.fp8), out.fp8.stride(0) if out.fp8 is not None else 0, _ptr(out.bf16),
+                      out.bf16.stride(0) if out.bf16 is not None else 0,
                       _ptr(out.scale), _ptr(out.amax), _ptr(out.err_sum), _ptr(out.nnz), _ptr(out.mask), _ptr(out.err5_sum),
-                      _ptr(out.scale_e8m0), _ptr(out.group_mantissa))
+                      _ptr(out.scale_e8m0), _ptr(out.group_mantissa), _ptr(out.amin))
 
 
 def mor_analyze_quantize(params: MorParams, x: torch.Tensor, out: MorResult) -> None:
@@ -209,6 +236,26 @@ def mor_analyze_quantize_profiled(params: MorParams, x: torch.Tensor, out: MorRe
                                               ws.numel() if ws is not None else 0, _stream(), C.byref(profile))
     if rc != 0:
         raise MorError(rc, "mor_analyze_quantize_profiled")
+
+
+def mor_fake_quantize(params: MorParams, x: torch.Tensor, y: torch.Tensor, meta: MorResult) -> None:
+    """Enqueue the fake-quantization pass: ``y`` (same shape as ``x``, BF16 bits) = de-quantize(quantize(x));
+    the [P] arrays of ``meta`` are written as by :func:`mor_analyze_quantize` (its fp8 / bf16 buffers are not used)."""
+    if not x.is_cuda or not y.is_cuda:
+        raise ValueError("x and y must live in device memory")
+    o = _outputs_struct(meta)
+    ws = meta.workspace
+    rc = load().mor_fake_quantize(C.byref(params), _ptr(x), _ptr(y), y.stride(0), C.byref(o), _ptr(ws),
+                                  ws.numel() if ws is not None else 0, _stream())
+    if rc != 0:
+        raise MorError(rc, "mor_fake_quantize")
+
+
+def mor_histogram_update(hist12: torch.Tensor, stats_dev: torch.Tensor, step: int, reset_interval: int) -> None:
+    """``hist12``: device int32/uint32[12]; ``stats_dev``: device mor_stats of this step's call for the tensor."""
+    rc = load().mor_histogram_update(_ptr(hist12), _ptr(stats_dev), step, reset_interval, _stream())
+    if rc != 0:
+        raise MorError(rc, "mor_histogram_update")
 
 
 def make_batch(entries) -> "C.Array":

@@ -7,20 +7,20 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-mor_status check_common(const mor_params* p) {
-    if (!p) return MOR_ERR_NULL;
-    if (p->granularity < MOR_GRAN_TENSOR || p->granularity > MOR_GRAN_BLOCK_128x128) return MOR_ERR_UNSUPPORTED;
-    if (p->rows <= 0 || p->cols <= 0) return MOR_ERR_SHAPE;
-    if (mor_num_partitions(p->granularity, p->rows, p->cols) < 0) return MOR_ERR_SHAPE;
+// Shape rules shared by every entry point.
+mor_status check_shape(int32_t gran, int64_t rows, int64_t cols, bool ragged) {
+    if (gran < MOR_GRAN_TENSOR || gran > MOR_GRAN_BLOCK_64x64) return MOR_ERR_UNSUPPORTED;
+    if (rows <= 0 || cols <= 0) return MOR_ERR_SHAPE;
+    if (cols % 8) return MOR_ERR_SHAPE;                            // 16-byte rows
+    const mor::StatsGeom g = mor::make_geom(gran, rows, cols);
+    if (!ragged && !g.uniform) return MOR_ERR_SHAPE;
+    if (gran == MOR_GRAN_CHANNEL_ROW && cols > 16384) return MOR_ERR_SHAPE;
     return MOR_OK;
 }
-
-int64_t elems_per_part(const mor_params* p) {
-    switch (p->granularity) {
-    case MOR_GRAN_SUB_1x128: return 128;
-    case MOR_GRAN_BLOCK_128x128: return 128 * 128;
-    default: return p->rows * p->cols;
-    }
+mor_status check_common(const mor_params* p) {
+    if (!p) return MOR_ERR_NULL;
+    if ((p->flags & ~(uint32_t)MOR_FLAG_RAGGED) || p->reserved) return MOR_ERR_UNSUPPORTED;
+    return check_shape(p->granularity, p->rows, p->cols, (p->flags & MOR_FLAG_RAGGED) != 0);
 }
 
 }  // namespace
@@ -28,45 +28,67 @@ int64_t elems_per_part(const mor_params* p) {
 extern "C" {
 
 int64_t mor_num_partitions(int32_t granularity, int64_t rows, int64_t cols) {
-    if (rows <= 0 || cols <= 0) return -1;
-    switch (granularity) {
-    case MOR_GRAN_TENSOR: return (cols % 8) ? -1 : 1;            // 16-byte rows
-    case MOR_GRAN_SUB_1x128: return (cols % 128) ? -1 : rows * (cols / 128);
-    case MOR_GRAN_BLOCK_128x128: return (rows % 128 || cols % 128) ? -1 : (rows / 128) * (cols / 128);
-    default: return -1;
-    }
+    if (check_shape(granularity, rows, cols, false) != MOR_OK) return -1;
+    return mor::geom_parts(mor::make_geom(granularity, rows, cols));
+}
+int64_t mor_params_num_partitions(const mor_params* p) {
+    if (check_common(p) != MOR_OK) return -1;
+    return mor::geom_parts(mor::make_geom(p->granularity, p->rows, p->cols));
 }
 
-// Validates one operand and converts it to the launcher's descriptor.
-static mor_status make_item(const mor_params* p, const uint16_t* x, const mor_outputs* out, mor_stats* stats, mor::BatchItem* item) {
+// Validates one operand and converts it to the launcher's descriptor.  `fake_y` non-null: fake quantization
+// into fake_y (the FP8 payload and the fallback buffer of `out` are then ignored).
+static mor_status make_item(const mor_params* p, const uint16_t* x, const mor_outputs* out, mor_stats* stats, uint16_t* fake_y,
+                            int64_t ld_fake, mor::BatchItem* item) {
     if (!p || !x || !out) return MOR_ERR_NULL;
     mor_status st = check_common(p);
     if (st != MOR_OK) return st;
     if (p->scope != MOR_SCOPE_PARTITION && p->scope != MOR_SCOPE_TENSOR) return MOR_ERR_UNSUPPORTED;
     if (p->criterion != MOR_CRIT_MEAN_REL_ERR && p->criterion != MOR_CRIT_E4M3_VS_E5M2) return MOR_ERR_UNSUPPORTED;
     if (p->scaling < MOR_SCALE_FP32_AMAX || p->scaling > MOR_SCALE_E8M0) return MOR_ERR_UNSUPPORTED;
-    if (p->formats != (MOR_FMT_E4M3 | MOR_FMT_BF16)) return MOR_ERR_UNSUPPORTED;
-    if (!out->fp8 || !out->scale || !out->amax || !out->err_sum || !out->nnz || !out->mask) return MOR_ERR_NULL;
+    const bool three = p->formats == (MOR_FMT_E4M3 | MOR_FMT_E5M2 | MOR_FMT_BF16);
+    if (!three && p->formats != (MOR_FMT_E4M3 | MOR_FMT_BF16)) return MOR_ERR_UNSUPPORTED;
+    if (three && (p->scope != MOR_SCOPE_PARTITION || p->granularity == MOR_GRAN_TENSOR || p->granularity == MOR_GRAN_CHANNEL_COL ||
+                  p->granularity == MOR_GRAN_SUB_128x1)) return MOR_ERR_UNSUPPORTED;
+    if ((!fake_y && !out->fp8) || !out->scale || !out->amax || !out->err_sum || !out->nnz || !out->mask) return MOR_ERR_NULL;
     if (p->criterion == MOR_CRIT_E4M3_VS_E5M2 && !out->err5_sum) return MOR_ERR_NULL;
-    if (p->ld < p->cols || out->ld_fp8 < p->cols) return MOR_ERR_SHAPE;
-    const bool want_bf16 = out->bf16 != nullptr && out->bf16 != x;
-    if (want_bf16 && out->ld_bf16 < p->cols) return MOR_ERR_SHAPE;
-    if (p->granularity == MOR_GRAN_BLOCK_128x128 && p->rows / 128 > 65535 && p->scope == MOR_SCOPE_TENSOR) return MOR_ERR_SHAPE;
-    if (p->ld % 8 || out->ld_fp8 % 8 || (want_bf16 && out->ld_bf16 % 8)) return MOR_ERR_ALIGN;
-    if (!aligned16(x) || (reinterpret_cast<uintptr_t>(out->fp8) & 7u) || (want_bf16 && !aligned16(out->bf16))) return MOR_ERR_ALIGN;
+    if (p->ld < p->cols) return MOR_ERR_SHAPE;
+    if (p->ld % 8) return MOR_ERR_ALIGN;
+    if (!aligned16(x)) return MOR_ERR_ALIGN;
+    bool want_bf16;
+    if (fake_y) {
+        if (ld_fake < p->cols) return MOR_ERR_SHAPE;
+        if (ld_fake % 8 || !aligned16(fake_y)) return MOR_ERR_ALIGN;
+        if (fake_y == x) return MOR_ERR_UNSUPPORTED;
+        want_bf16 = true;
+    } else {
+        if (out->ld_fp8 < p->cols) return MOR_ERR_SHAPE;
+        want_bf16 = out->bf16 != nullptr && out->bf16 != x;
+        if (want_bf16 && out->ld_bf16 < p->cols) return MOR_ERR_SHAPE;
+        if (out->ld_fp8 % 8 || (want_bf16 && out->ld_bf16 % 8)) return MOR_ERR_ALIGN;
+        if ((reinterpret_cast<uintptr_t>(out->fp8) & 7u) || (want_bf16 && !aligned16(out->bf16))) return MOR_ERR_ALIGN;
+    }
+    if (p->granularity != MOR_GRAN_TENSOR && p->rows / 128 > 65535 && p->scope == MOR_SCOPE_TENSOR) return MOR_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(out->scale) | reinterpret_cast<uintptr_t>(out->amax) |
-         reinterpret_cast<uintptr_t>(out->err_sum) | reinterpret_cast<uintptr_t>(out->nnz)) & 3u) return MOR_ERR_ALIGN;
+         reinterpret_cast<uintptr_t>(out->err_sum) | reinterpret_cast<uintptr_t>(out->nnz) |
+         reinterpret_cast<uintptr_t>(out->amin)) & 3u) return MOR_ERR_ALIGN;
     if (stats && (reinterpret_cast<uintptr_t>(stats) & 7u)) return MOR_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(out->group_mantissa) & 3u) return MOR_ERR_ALIGN;
     item->sh = mor::KShape{p->rows, p->cols, p->ld};
-    item->o = mor::KOut{out->fp8, out->ld_fp8, want_bf16 ? out->bf16 : nullptr, want_bf16 ? out->ld_bf16 : p->cols,
-                        out->scale, out->amax, out->err_sum, out->nnz, out->mask, out->err5_sum,
-                        out->scale_e8m0, out->group_mantissa};
+    if (fake_y)
+        item->o = mor::KOut{nullptr, p->cols, fake_y, ld_fake, out->scale, out->amax, out->err_sum, out->nnz, out->mask,
+                            out->err5_sum, out->scale_e8m0, out->group_mantissa, out->amin, fake_y, ld_fake};
+    else
+        item->o = mor::KOut{out->fp8, out->ld_fp8, want_bf16 ? out->bf16 : nullptr, want_bf16 ? out->ld_bf16 : p->cols,
+                            out->scale, out->amax, out->err_sum, out->nnz, out->mask, out->err5_sum,
+                            out->scale_e8m0, out->group_mantissa, out->amin, nullptr, 0};
     item->x = x;
     item->gran = p->granularity;
     item->crit = p->criterion;
     item->scaling = p->scaling;
     item->scope = p->granularity == MOR_GRAN_TENSOR ? MOR_SCOPE_PARTITION : p->scope;
+    item->three = three ? 1 : 0;
+    item->ragged = (p->flags & MOR_FLAG_RAGGED) ? 1 : 0;
     item->th = p->threshold;
     item->stats = stats;
     return MOR_OK;
@@ -80,6 +102,7 @@ size_t mor_workspace_bytes(const mor_params* p) {
     it.scope = p->granularity == MOR_GRAN_TENSOR ? MOR_SCOPE_PARTITION : p->scope;
     it.o.ld_fp8 = p->cols;
     it.scaling = p->scaling;
+    it.ragged = (p->flags & MOR_FLAG_RAGGED) ? 1 : 0;
     return mor::batch_workspace_bytes(&it, 1);
 }
 
@@ -102,7 +125,7 @@ static mor_status run_batch(const mor::BatchItem* items, int n, float near_tol, 
 mor_status mor_analyze_quantize(const mor_params* p, const uint16_t* x, const mor_outputs* out, void* workspace,
                                 size_t workspace_bytes, void* stream) {
     mor::BatchItem it{};
-    mor_status st = make_item(p, x, out, nullptr, &it);
+    mor_status st = make_item(p, x, out, nullptr, nullptr, 0, &it);
     if (st != MOR_OK) return st;
     return run_batch(&it, 1, 0.0f, workspace, workspace_bytes, stream, nullptr);
 }
@@ -111,7 +134,7 @@ mor_status mor_analyze_quantize_profiled(const mor_params* p, const uint16_t* x,
                                          size_t workspace_bytes, void* stream, mor_profile* profile) {
     if (!profile) return MOR_ERR_NULL;
     mor::BatchItem it{};
-    mor_status st = make_item(p, x, out, nullptr, &it);
+    mor_status st = make_item(p, x, out, nullptr, nullptr, 0, &it);
     if (st != MOR_OK) return st;
     return run_batch(&it, 1, 0.0f, workspace, workspace_bytes, stream, profile);
 }
@@ -121,7 +144,7 @@ size_t mor_batch_workspace_bytes(const mor_batch_item* items, int32_t n_items) {
     size_t total = 0;
     for (int32_t i = 0; i < n_items; ++i) {
         mor::BatchItem it{};
-        if (make_item(&items[i].params, items[i].x, &items[i].out, items[i].stats, &it) != MOR_OK) return 0;
+        if (make_item(&items[i].params, items[i].x, &items[i].out, items[i].stats, nullptr, 0, &it) != MOR_OK) return 0;
         total += mor::batch_workspace_bytes(&it, 1);
     }
     return total;
@@ -134,10 +157,19 @@ mor_status mor_analyze_quantize_batch(const mor_batch_item* items, int32_t n_ite
     static_assert(MOR_BATCH_MAX == mor::kBatchMax, "batch limit");
     mor::BatchItem its[MOR_BATCH_MAX];
     for (int32_t i = 0; i < n_items; ++i) {
-        mor_status st = make_item(&items[i].params, items[i].x, &items[i].out, items[i].stats, &its[i]);
+        mor_status st = make_item(&items[i].params, items[i].x, &items[i].out, items[i].stats, nullptr, 0, &its[i]);
         if (st != MOR_OK) return st;
     }
     return run_batch(its, n_items, near_tol, workspace, workspace_bytes, stream, profile);
+}
+
+mor_status mor_fake_quantize(const mor_params* p, const uint16_t* x, uint16_t* y, int64_t ld_y, const mor_outputs* meta,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+    if (!y) return MOR_ERR_NULL;
+    mor::BatchItem it{};
+    mor_status st = make_item(p, x, meta, nullptr, y, ld_y, &it);
+    if (st != MOR_OK) return st;
+    return run_batch(&it, 1, 0.0f, workspace, workspace_bytes, stream, nullptr);
 }
 
 static mor_status dequantize_any(const mor_params* p, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
@@ -151,8 +183,8 @@ static mor_status dequantize_any(const mor_params* p, const uint8_t* fp8, int64_
     if (ld_fp8 % 8 || ld_y % 8 || (bf16 && ld_bf16 % 8)) return MOR_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(fp8) & 7u) || !aligned16(y) || (bf16 && !aligned16(bf16))) return MOR_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(scale) | reinterpret_cast<uintptr_t>(gmant)) & 3u) return MOR_ERR_ALIGN;
-    hipError_t e = mor::launch_dequantize(p->granularity, p->rows, p->cols, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y,
-                                          e8m0, gmant, static_cast<hipStream_t>(stream));
+    hipError_t e = mor::launch_dequantize(mor::make_geom(p->granularity, p->rows, p->cols), fp8, ld_fp8, scale, mask, bf16, ld_bf16,
+                                          y, ld_y, e8m0, gmant, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? MOR_OK : MOR_ERR_HIP;
 }
 
@@ -176,9 +208,18 @@ mor_status mor_select_stats(const mor_params* p, const float* err_sum, const uin
     if (st != MOR_OK) return st;
     if ((reinterpret_cast<uintptr_t>(err_sum) | reinterpret_cast<uintptr_t>(nnz)) & 3u) return MOR_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(out_dev) & 7u) return MOR_ERR_ALIGN;
-    static_assert(sizeof(mor_stats) == 128, "mor_stats layout");
-    hipError_t e = mor::launch_select_stats(mor_num_partitions(p->granularity, p->rows, p->cols), elems_per_part(p), err_sum, nnz,
+    static_assert(sizeof(mor_stats) == 144, "mor_stats layout");
+    hipError_t e = mor::launch_select_stats(mor::make_geom(p->granularity, p->rows, p->cols), err_sum, nnz,
                                             mask, p->threshold, near_tol, out_dev, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MOR_OK : MOR_ERR_HIP;
+}
+
+mor_status mor_histogram_update(uint32_t* hist12_dev, const mor_stats* stats_dev, int64_t step, int64_t reset_interval, void* stream) {
+    if (!hist12_dev || !stats_dev) return MOR_ERR_NULL;
+    if (step < 0 || reset_interval < 0) return MOR_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(hist12_dev) & 3u) || (reinterpret_cast<uintptr_t>(stats_dev) & 7u)) return MOR_ERR_ALIGN;
+    const int clear = (reset_interval > 0 && step % reset_interval == 0) ? 1 : 0;
+    hipError_t e = mor::launch_histogram_update(hist12_dev, stats_dev, clear, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? MOR_OK : MOR_ERR_HIP;
 }
 

@@ -133,6 +133,61 @@ __device__ __forceinline__ u32x2 quant8_fast(const u32x4& raw, float s, float& e
     return r;
 }
 
+// binary32 -> BF16, round to nearest even; NaN -> quiet NaN with the sign kept.
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+    const uint32_t u = __float_as_uint(f);
+    if (f != f) return ((u >> 16) & 0x8000u) | 0x7FC0u;
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Finite values only (the branch-free paths never see NaN).
+__device__ __forceinline__ uint32_t f32_to_bf16_rne_finite(float f) {
+    const uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// The same as quant8_fast, optionally (FAKE) also producing the eight de-quantized values
+// bf16_rne(fl32(q * s_inv)) of the fake-quantization workflow (Section 4, Figure 4).
+template <bool E5M2, bool FAKE>
+__device__ __forceinline__ u32x2 quant8_fast_deq(const u32x4& raw, float s, float s_inv, float& err0, float& err1, u32x4& deq) {
+    int w0 = 0, w1 = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float y0 = __uint_as_float(raw[j] << 16) * s;
+        float y1 = __uint_as_float(raw[j] & 0xFFFF0000u) * s;
+        f32x2 q;
+        if (j == 0) { w0 = cvt_pk8<E5M2>(y0, y1, w0, false); q = cvt_pk_f32<E5M2>(w0, false); }
+        if (j == 1) { w0 = cvt_pk8<E5M2>(y0, y1, w0, true);  q = cvt_pk_f32<E5M2>(w0, true); }
+        if (j == 2) { w1 = cvt_pk8<E5M2>(y0, y1, w1, false); q = cvt_pk_f32<E5M2>(w1, false); }
+        if (j == 3) { w1 = cvt_pk8<E5M2>(y0, y1, w1, true);  q = cvt_pk_f32<E5M2>(w1, true); }
+        err0 += rel_term(y0, q.x);
+        err1 += rel_term(y1, q.y);
+        if constexpr (FAKE) deq[j] = f32_to_bf16_rne_finite(q.x * s_inv) | (f32_to_bf16_rne_finite(q.y * s_inv) << 16);
+    }
+    u32x2 r; r.x = (uint32_t)w0; r.y = (uint32_t)w1;
+    return r;
+}
+// Eight values of eight different blocks (one column each): scales s[k], error terms added to err[k].
+template <bool E5M2, bool FAKE>
+__device__ __forceinline__ u32x2 quant8_cols(const u32x4& raw, const float (&s)[8], const float (&s_inv)[8], float (&err)[8], u32x4& deq) {
+    int w0 = 0, w1 = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float y0 = __uint_as_float(raw[j] << 16) * s[2 * j];
+        float y1 = __uint_as_float(raw[j] & 0xFFFF0000u) * s[2 * j + 1];
+        f32x2 q;
+        if (j == 0) { w0 = cvt_pk8<E5M2>(y0, y1, w0, false); q = cvt_pk_f32<E5M2>(w0, false); }
+        if (j == 1) { w0 = cvt_pk8<E5M2>(y0, y1, w0, true);  q = cvt_pk_f32<E5M2>(w0, true); }
+        if (j == 2) { w1 = cvt_pk8<E5M2>(y0, y1, w1, false); q = cvt_pk_f32<E5M2>(w1, false); }
+        if (j == 3) { w1 = cvt_pk8<E5M2>(y0, y1, w1, true);  q = cvt_pk_f32<E5M2>(w1, true); }
+        err[2 * j] += rel_term(y0, q.x);
+        err[2 * j + 1] += rel_term(y1, q.y);
+        if constexpr (FAKE) deq[j] = f32_to_bf16_rne_finite(q.x * s_inv[2 * j]) | (f32_to_bf16_rne_finite(q.y * s_inv[2 * j + 1]) << 16);
+    }
+    u32x2 r; r.x = (uint32_t)w0; r.y = (uint32_t)w1;
+    return r;
+}
+
 // ---- E4M3 / E5M2: careful path (any input) ------------------------------------------------
 template <bool E5M2>
 __device__ __forceinline__ uint32_t encode_careful(float y) {
@@ -151,10 +206,13 @@ __device__ __forceinline__ float term_careful(uint32_t xbits16, float y, uint32_
 }
 // Careful path over 8 consecutive elements re-read from memory (the data is still in L2): a rolled
 // loop keeps this rarely taken path small.  Writes the 8 codes to `dst` unless it is null.
+// With `fake` set, the eight de-quantized BF16 values go there instead of the codes to `dst`.
 template <bool E5M2>
-__device__ __forceinline__ float quant8_careful_mem(const uint16_t* __restrict__ src, float s, uint8_t* dst) {
+__device__ __forceinline__ float quant8_careful_mem(const uint16_t* __restrict__ src, float s, uint8_t* dst,
+                                                    uint16_t* fake = nullptr, float s_inv = 0.0f) {
     const uint32_t* src32 = reinterpret_cast<const uint32_t*>(src);
     uint32_t* dst32 = reinterpret_cast<uint32_t*>(dst);
+    uint32_t* fake32 = reinterpret_cast<uint32_t*>(fake);
     float err = 0.0f;
     uint32_t codes = 0u;
 #pragma clang loop unroll(disable)
@@ -167,7 +225,10 @@ __device__ __forceinline__ float quant8_careful_mem(const uint16_t* __restrict__
         err += term_careful<E5M2>(b0, y0, c0);
         err += term_careful<E5M2>(b1, y1, c1);
         const uint32_t two = c0 | (c1 << 8);
-        if (j & 1) {
+        if (fake) {
+            const f32x2 q = cvt_pk_f32<E5M2>((int)two, false);
+            fake32[j] = f32_to_bf16_rne(q.x * s_inv) | (f32_to_bf16_rne(q.y * s_inv) << 16);
+        } else if (j & 1) {
             codes |= two << 16;
             if (dst) dst32[j >> 1] = codes;
         } else {
@@ -175,6 +236,14 @@ __device__ __forceinline__ float quant8_careful_mem(const uint16_t* __restrict__
         }
     }
     return err;
+}
+// One element of a block of its own (column blocks), careful path: returns the code, adds the term.
+template <bool E5M2>
+__device__ __forceinline__ uint32_t quant1_careful(uint32_t xbits16, float s, float& err) {
+    const float y = __uint_as_float(xbits16 << 16) * s;
+    const uint32_t c = encode_careful<E5M2>(y);
+    err += term_careful<E5M2>(xbits16, y, c);
+    return c;
 }
 
 // ---- cross-lane reductions over the 16 lanes of a DPP row -----------------------------------
@@ -195,6 +264,24 @@ constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
 constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
 constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each 8 lanes
 constexpr int kDppMirror = 0x140;     // lane i <-> 15-i inside each 16 lanes
+
+// Smallest non-zero magnitude pattern of 8 BF16 values, as (pattern - 1) per half-word so that zeros
+// (wrapping to 0xFFFF) never win the minimum.
+__device__ __forceinline__ uint32_t min_nonzero_m1(const u32x4& raw, uint32_t mn2) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) mn2 = pk_min_u16(mn2, pk_sub_u16(raw[j] & 0x7FFF7FFFu, 0x00010001u));
+    return mn2;
+}
+__device__ __forceinline__ uint32_t fold_min16(uint32_t v2) { return min(v2 & 0xFFFFu, v2 >> 16); }
+// Eq. (4) of the three-way recipe: max|b| / min|b| < 57344 / 2^-14 over the non-zero elements, evaluated
+// exactly as amax < 57344 * 2^14 * amin (a BF16 value times 1.75 * 2^29 is exact in binary32; an
+// overflowing product is +inf, and the test then holds as it should).  Blocks without non-zero elements
+// pass; blocks holding Inf or NaN fail.
+__device__ __forceinline__ bool range_fits_e5m2(uint32_t amax_bits, uint32_t amin_bits, uint32_t nnz) {
+    if (amax_bits >= kInfBits) return false;
+    if (nnz == 0u) return true;
+    return __uint_as_float(amax_bits << 16) < 939524096.0f * __uint_as_float(amin_bits << 16);
+}
 
 __device__ __forceinline__ uint32_t row_allmax_u32(uint32_t v) {
     v = max(v, dpp_u32<kDppXor1>(v));
@@ -236,6 +323,18 @@ __device__ __forceinline__ float wave_allsum_f32(float v) {
     float c = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
     float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
     return (a + b) + (c + d);
+}
+
+// Index of the operand a work unit belongs to, from the running totals of a grouped launch (uniform per wave).
+__device__ __forceinline__ int group_find(const int64_t* end, int n, int64_t v) {
+    int i = 0;
+    while (i + 1 < n && v >= end[i]) ++i;
+    return __builtin_amdgcn_readfirstlane(i);
+}
+__device__ __forceinline__ int group_find32(const int32_t* end, int n, int v) {
+    int i = 0;
+    while (i + 1 < n && v >= end[i]) ++i;
+    return __builtin_amdgcn_readfirstlane(i);
 }
 
 // ---- Algorithm 2 with [E4M3, BF16]: 0 = keep E4M3, 1 = keep BF16 ------------------------------

@@ -5,6 +5,8 @@
 // (Algorithm 2 with [E4M3, BF16]) and emission, all from registers.  Per-tensor granularity needs
 // the global amax before anything can be scaled and therefore reads the operand twice.
 // The path is HBM-bound: there is no contraction in it, so no MFMA.
+#include <type_traits>
+
 #include "mor_device.h"
 #include "mor_launch.h"
 
@@ -17,35 +19,55 @@ enum { kCritEq2 = 0, kCritEq3 = 1 };
 // A 16-lane DPP row owns one block at a time (16 lanes x 8 elements); a wave works on 4 blocks
 // per load instruction and keeps 4 loads in flight, so every reduction stays inside a row.
 // ======================================================================================
-template <int CRIT, bool DEFER>
-__device__ __forceinline__ void sub_block_body(const u32x4& raw, const uint16_t* __restrict__ src, int l, int64_t p,
+// One block per 16-lane row, 8 elements per lane.  `valid` is false for lanes beyond the last column of a
+// ragged tensor (they hold zeros and store nothing).  FAKE: the de-quantized values go to dst_fake instead
+// of the codes to dst_fp8.  `three`: the block may end in E5M2 (Section 3.2, three-way recipe).
+template <int CRIT, bool DEFER, bool FAKE>
+__device__ __forceinline__ void sub_block_body(const u32x4& raw, const uint16_t* __restrict__ src, bool valid, int l, int64_t p,
                                                const KOut& o, uint8_t* __restrict__ dst_fp8, uint16_t* __restrict__ dst_bf16,
-                                               float th, uint32_t mode, uint32_t mg, uint32_t mg5) {
+                                               uint16_t* __restrict__ dst_fake, float th, uint32_t mode, uint32_t mg, uint32_t mg5,
+                                               bool three) {
     Scan8 sc{0u, 0u};
     scan8(raw, sc);
     const uint32_t abits = row_allmax_u32(fold_max16(sc.amax2));
-    const float s = block_scale(abits, kE4M3Max, mode, mg);
-    float e, e5 = 0.0f;
-    if (abits < fast_amax_limit(mode)) {
+    float s = block_scale(abits, kE4M3Max, mode, mg);
+    const float s5 = block_scale(abits, kE5M2Max, mode, mg5);
+    const bool fast = abits < fast_amax_limit(mode);
+    auto quantize = [&](auto fmt, float sc_, bool emit) -> float {
+        constexpr bool E5 = decltype(fmt)::value;
+        const float s_inv = FAKE ? 1.0f / sc_ : 0.0f;
         float e0 = 0.0f, e1 = 0.0f;
-        store8(dst_fp8, quant8_fast<false>(raw, s, e0, e1));
-        e = e0 + e1;
-        if constexpr (CRIT == kCritEq3) {
-            float f0 = 0.0f, f1 = 0.0f;
-            (void)quant8_fast<true>(raw, block_scale(abits, kE5M2Max, mode, mg5), f0, f1);
-            e5 = f0 + f1;
+        if (fast) {
+            u32x4 deq;
+            const u32x2 codes = quant8_fast_deq<E5, FAKE>(raw, sc_, s_inv, e0, e1, deq);
+            if (emit && valid) {
+                if constexpr (FAKE) store16(dst_fake, deq);
+                else store8(dst_fp8, codes);
+            }
+        } else if (valid) {
+            e0 = quant8_careful_mem<E5>(src, sc_, emit && !FAKE ? dst_fp8 : nullptr, emit && FAKE ? dst_fake : nullptr, s_inv);
         }
-    } else {
-        e = quant8_careful_mem<false>(src, s, dst_fp8);
-        if constexpr (CRIT == kCritEq3) e5 = quant8_careful_mem<true>(src, block_scale(abits, kE5M2Max, mode, mg5), nullptr);
-    }
-    float err = row_allsum_f32(e);
-    const uint32_t nnz = 128u - row_allsum_u32(fold_add16(sc.zero2));
+        return e0 + e1;
+    };
+    float err = row_allsum_f32(quantize(std::false_type{}, s, true));
     float err5 = 0.0f;
-    if constexpr (CRIT == kCritEq3) err5 = row_allsum_f32(e5);
+    if constexpr (CRIT == kCritEq3) err5 = row_allsum_f32(quantize(std::true_type{}, s5, false));
+    const uint32_t nnz = 128u - row_allsum_u32(fold_add16(sc.zero2));
     if (abits >= kInfBits) { err = __builtin_inff(); err5 = __builtin_inff(); }
     uint32_t mask = 0u;
     if constexpr (!DEFER) mask = (CRIT == kCritEq3) ? decide_eq3(err, err5) : decide_eq2(err, nnz, th);
+    uint32_t amin_bits = 0u;
+    if (three) {                                              // uniform over the launch
+        const uint32_t mn = ~row_allmax_u32(~fold_min16(min_nonzero_m1(raw, 0xFFFFFFFFu))) & 0xFFFFu;
+        if (mask == 1u) {
+            amin_bits = nnz ? mn + 1u : 0u;
+            if (range_fits_e5m2(abits, amin_bits, nnz)) {
+                mask = 2u;
+                s = s5;
+                (void)quantize(std::true_type{}, s5, true);   // the E5M2 payload replaces the E4M3 one
+            }
+        }
+    }
     if (l == 0) {
         o.scale[p] = s;
         o.amax[p] = __uint_as_float(abits << 16);
@@ -54,9 +76,10 @@ __device__ __forceinline__ void sub_block_body(const u32x4& raw, const uint16_t*
         if constexpr (CRIT == kCritEq3) o.err5_sum[p] = err5;
         if constexpr (!DEFER) o.mask[p] = (uint8_t)mask;
         if (mode != kScaleFp32 && o.e8m0) o.e8m0[p] = (uint8_t)(__float_as_uint(s) >> 23);
+        if (three && o.amin) o.amin[p] = __uint_as_float(amin_bits << 16);
     }
     if constexpr (!DEFER) {
-        if (mask && dst_bf16) store16(dst_bf16, raw);
+        if (mask == 1u && dst_bf16 && valid) store16(dst_bf16, raw);
     }
 }
 
@@ -205,18 +228,23 @@ __device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const ui
     }
 }
 
-// Strided operands: grid.x = 128-column block, grid.y strides over groups of 16 rows.
-template <int CRIT, bool DEFER>
+// General 1 x 128 kernel (padded leading dimensions, ragged last column block, three types, fake
+// quantization): grid.x = 128-column block, grid.y strides over groups of 16 rows.
+template <int CRIT, bool DEFER, bool FAKE>
 __global__ __launch_bounds__(256) void k_sub1x128_strided(const uint16_t* __restrict__ x, KShape sh, KOut o, float th,
-                                                          uint32_t mode, const uint32_t* __restrict__ gam) {
+                                                          uint32_t mode, const uint32_t* __restrict__ gam, uint32_t three) {
     const int lane = threadIdx.x & 63, g = lane >> 4, l = lane & 15;
     const uint32_t mg = mode ? gam[0] : 0u, mg5 = mode ? gam[1] : 0u;
-    const int64_t cb = blockIdx.x, cpr = sh.cols / 128;
+    const int64_t cb = blockIdx.x, cpr = (sh.cols + 127) / 128;
+    const int64_t c = cb * 128 + l * 8;
+    const bool valid = c < sh.cols;
     for (int64_t r = (int64_t)blockIdx.y * 16 + (threadIdx.x >> 6) * 4 + g; r < sh.rows; r += (int64_t)gridDim.y * 16) {
-        const uint16_t* src = x + r * sh.ld + cb * 128 + l * 8;
-        const u32x4 raw = load16(src);
-        sub_block_body<CRIT, DEFER>(raw, src, l, r * cpr + cb, o, o.fp8 + r * o.ld_fp8 + cb * 128 + l * 8,
-                                    o.bf16 ? o.bf16 + r * o.ld_bf16 + cb * 128 + l * 8 : nullptr, th, mode, mg, mg5);
+        const uint16_t* src = x + r * sh.ld + c;
+        u32x4 raw; raw.x = 0u; raw.y = 0u; raw.z = 0u; raw.w = 0u;
+        if (valid) raw = load16(src);
+        sub_block_body<CRIT, DEFER, FAKE>(raw, src, valid, l, r * cpr + cb, o, FAKE ? nullptr : o.fp8 + r * o.ld_fp8 + c,
+                                          o.bf16 ? o.bf16 + r * o.ld_bf16 + c : nullptr, FAKE ? o.fake + r * o.ld_fake + c : nullptr,
+                                          th, mode, mg, mg5, three != 0u);
     }
 }
 
@@ -332,7 +360,7 @@ __device__ __forceinline__ void tensor_publish(const TensorAcc& a, const TensorP
 }
 
 // Pass B, strided: persistent workgroups stride over 16-row x 128-column tiles, one chunk per thread.
-template <int CRIT>
+template <int CRIT, bool FAKE>
 __global__ __launch_bounds__(256) void k_tensor_quant_strided(const uint16_t* __restrict__ x, KShape sh, uint32_t tiles_x,
                                                               uint32_t n_tiles, KOut o, const uint32_t* __restrict__ amax_part,
                                                               int n_amax_part, TensorPartials tp, uint32_t mode) {
@@ -342,6 +370,7 @@ __global__ __launch_bounds__(256) void k_tensor_quant_strided(const uint16_t* __
     // one block = the group: under GAM the block's own mantissa is the group mantissa, the scale is s_b
     const float s = block_scale(abits, kE4M3Max, mode, group_mantissa_bits(abits, kE4M3Max, mode));
     const float s5 = (CRIT == kCritEq3) ? block_scale(abits, kE5M2Max, mode, group_mantissa_bits(abits, kE5M2Max, mode)) : 0.0f;
+    const float s_inv = FAKE ? 1.0f / s : 0.0f;
     TensorAcc acc{0.0f, 0.0f, 0.0f, 0.0f, 0u};
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const uint32_t ty = tile / tiles_x, tx = tile - ty * tiles_x;
@@ -352,11 +381,16 @@ __global__ __launch_bounds__(256) void k_tensor_quant_strided(const uint16_t* __
         if (live) raw = load16(x + r * sh.ld + c);
         acc.zero2 = zero2_of(raw, acc.zero2);
         if (abits < fast_amax_limit(mode)) {
-            const u32x2 codes = quant8_fast<false>(raw, s, acc.e0, acc.e1);
-            if (live) store8(o.fp8 + r * o.ld_fp8 + c, codes);
+            u32x4 deq;
+            const u32x2 codes = quant8_fast_deq<false, FAKE>(raw, s, s_inv, acc.e0, acc.e1, deq);
+            if (live) {
+                if constexpr (FAKE) store16(o.fake + r * o.ld_fake + c, deq);
+                else store8(o.fp8 + r * o.ld_fp8 + c, codes);
+            }
             if constexpr (CRIT == kCritEq3) (void)quant8_fast<true>(raw, s5, acc.f0, acc.f1);
         } else if (live) {
-            acc.e0 += quant8_careful_mem<false>(x + r * sh.ld + c, s, o.fp8 + r * o.ld_fp8 + c);
+            acc.e0 += quant8_careful_mem<false>(x + r * sh.ld + c, s, FAKE ? nullptr : o.fp8 + r * o.ld_fp8 + c,
+                                                FAKE ? o.fake + r * o.ld_fake + c : nullptr, s_inv);
             if constexpr (CRIT == kCritEq3) acc.f0 += quant8_careful_mem<true>(x + r * sh.ld + c, s5, nullptr);
         }
     }
@@ -392,7 +426,7 @@ __global__ __launch_bounds__(256) void k_tensor_finish(TensorPartials tp, int n_
         const float s = block_scale(abits, kE4M3Max, mode, mg);
         o.scale[0] = s;
         if (mode != kScaleFp32 && o.e8m0) o.e8m0[0] = (uint8_t)(__float_as_uint(s) >> 23);
-        if (mode != kScaleFp32 && o.gmant) o.gmant[0] = mg;
+        if (mode != kScaleFp32 && o.gmant) { o.gmant[0] = mg; o.gmant[1] = group_mantissa_bits(abits, kE5M2Max, mode); }
         o.amax[0] = __uint_as_float(abits << 16);
         o.err_sum[0] = (float)se;
         o.nnz[0] = n > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)n;
@@ -496,42 +530,81 @@ __global__ __launch_bounds__(256) void k_scope_fill_mask(uint8_t* __restrict__ m
 }
 
 // ======================================================================================
-// De-quantize / de-scale (Section 4, Figure 4): grid.x = 128-column block, grid.y strides over
-// groups of 16 rows, one 8-element chunk per thread.
+// De-quantize / de-scale (Section 4, Figure 4).  Blocks whose width is a multiple of 8 (or the whole
+// row): grid.x = 128-column strip, grid.y strides over groups of 16 rows, one 8-element chunk per
+// thread and row.  Blocks one column wide: one workgroup per 128 x 128 tile, so that a thread's 8
+// column scales are inverted once per tile.
 // ======================================================================================
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-    const uint32_t u = __float_as_uint(f);
-    if (f != f) return ((u >> 16) & 0x8000u) | 0x7FC0u;
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+__device__ __forceinline__ float dequant_scale(const float* __restrict__ scale, const uint8_t* __restrict__ e8m0,
+                                               const uint32_t* __restrict__ gmant, int64_t p, uint32_t mk) {
+    // stored GAM form (Algorithm 1): the scale is rebuilt from the shared mantissa and the block's E8M0 byte
+    return e8m0 ? __uint_as_float(((uint32_t)e8m0[p] << 23) | gmant[mk == 2u ? 1 : 0]) : scale[p];
 }
-template <int GRAN>
-__global__ __launch_bounds__(256) void k_dequant(int64_t rows, int64_t cols, const uint8_t* __restrict__ fp8, int64_t ld_fp8,
+template <bool E5M2>
+__device__ __forceinline__ u32x4 dequant8(const u32x2& q, float s_inv) {
+    u32x4 out;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int word = (int)(j < 2 ? q.x : q.y);
+        const f32x2 v = (j & 1) ? cvt_pk_f32<E5M2>(word, true) : cvt_pk_f32<E5M2>(word, false);
+        out[j] = f32_to_bf16_rne(v.x * s_inv) | (f32_to_bf16_rne(v.y * s_inv) << 16);
+    }
+    return out;
+}
+__global__ __launch_bounds__(256) void k_dequant(StatsGeom g, int pr_log2, int pc_log2, const uint8_t* __restrict__ fp8, int64_t ld_fp8,
                                                  const float* __restrict__ scale, const uint8_t* __restrict__ mask,
                                                  const uint16_t* __restrict__ bf16, int64_t ld_bf16, uint16_t* __restrict__ y,
                                                  int64_t ld_y, const uint8_t* __restrict__ e8m0, const uint32_t* __restrict__ gmant) {
-    const int64_t cb = blockIdx.x, cpr = (cols + 127) / 128;
-    const int64_t c = cb * 128 + (threadIdx.x & 15) * 8;
-    if (c >= cols) return;
-    for (int64_t r = (int64_t)blockIdx.y * 16 + (threadIdx.x >> 4); r < rows; r += (int64_t)gridDim.y * 16) {
-        int64_t p = 0;
-        if (GRAN == 1) p = r * cpr + cb;
-        if (GRAN == 2) p = (r >> 7) * cpr + cb;
-        if (mask[p]) {
+    const int64_t c = (int64_t)blockIdx.x * 128 + (threadIdx.x & 15) * 8;
+    if (c >= g.cols) return;
+    for (int64_t r = (int64_t)blockIdx.y * 16 + (threadIdx.x >> 4); r < g.rows; r += (int64_t)gridDim.y * 16) {
+        const int64_t p = (r >> pr_log2) * g.gc + (c >> pc_log2);
+        const uint32_t mk = mask[p];
+        if (mk == 1u) {
             if (bf16) store16(y + r * ld_y + c, load16(bf16 + r * ld_bf16 + c));
             continue;
         }
-        // stored GAM form (Algorithm 1): the scale is rebuilt from the shared mantissa and the block's E8M0 byte
-        const float s = e8m0 ? __uint_as_float(((uint32_t)e8m0[p] << 23) | gmant[0]) : scale[p];
-        const float s_inv = 1.0f / s;                               // correctly rounded IEEE division
+        const float s_inv = 1.0f / dequant_scale(scale, e8m0, gmant, p, mk);     // correctly rounded IEEE division
         const u32x2 q = *reinterpret_cast<const u32x2*>(fp8 + r * ld_fp8 + c);
-        u32x4 out;
+        store16(y + r * ld_y + c, mk == 2u ? dequant8<true>(q, s_inv) : dequant8<false>(q, s_inv));
+    }
+}
+__global__ __launch_bounds__(256) void k_dequant_columns(StatsGeom g, int pr_log2, const uint8_t* __restrict__ fp8, int64_t ld_fp8,
+                                                         const float* __restrict__ scale, const uint8_t* __restrict__ mask,
+                                                         const uint16_t* __restrict__ bf16, int64_t ld_bf16, uint16_t* __restrict__ y,
+                                                         int64_t ld_y, const uint8_t* __restrict__ e8m0, const uint32_t* __restrict__ gmant) {
+    const int64_t c = (int64_t)blockIdx.x * 128 + (threadIdx.x & 15) * 8;
+    if (c >= g.cols) return;
+    for (int64_t tr = blockIdx.y; tr * 128 < g.rows; tr += gridDim.y) {
+        const int64_t p0 = ((tr * 128) >> pr_log2) * g.gc + c;
+        float s_inv[8];
+        uint32_t mk[8];
+        bool any_bf16 = false;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int word = (int)(j < 2 ? q.x : q.y);
-            const f32x2 v = (j & 1) ? cvt_pk_f32<false>(word, true) : cvt_pk_f32<false>(word, false);
-            out[j] = f32_to_bf16_rne(v.x * s_inv) | (f32_to_bf16_rne(v.y * s_inv) << 16);
+        for (int j = 0; j < 8; ++j) {
+            mk[j] = mask[p0 + j];
+            any_bf16 |= mk[j] == 1u;
+            s_inv[j] = 1.0f / dequant_scale(scale, e8m0, gmant, p0 + j, mk[j]);
         }
-        store16(y + r * ld_y + c, out);
+#pragma unroll 1
+        for (int i = 0; i < 8; ++i) {
+            const int64_t r = tr * 128 + (threadIdx.x >> 4) + i * 16;
+            if (r >= g.rows) break;
+            const u32x2 q = *reinterpret_cast<const u32x2*>(fp8 + r * ld_fp8 + c);
+            u32x4 keep; keep.x = 0u; keep.y = 0u; keep.z = 0u; keep.w = 0u;
+            if (any_bf16) keep = bf16 ? load16(bf16 + r * ld_bf16 + c) : load16(y + r * ld_y + c);
+            u32x4 out;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int word = (int)(j < 2 ? q.x : q.y);
+                const f32x2 v4 = (j & 1) ? cvt_pk_f32<false>(word, true) : cvt_pk_f32<false>(word, false);
+                const f32x2 v5 = (j & 1) ? cvt_pk_f32<true>(word, true) : cvt_pk_f32<true>(word, false);
+                const uint32_t lo = mk[2 * j] == 1u ? (keep[j] & 0xFFFFu) : f32_to_bf16_rne((mk[2 * j] == 2u ? v5.x : v4.x) * s_inv[2 * j]);
+                const uint32_t hi = mk[2 * j + 1] == 1u ? (keep[j] >> 16) : f32_to_bf16_rne((mk[2 * j + 1] == 2u ? v5.y : v4.y) * s_inv[2 * j + 1]);
+                out[j] = lo | (hi << 16);
+            }
+            store16(y + r * ld_y + c, out);
+        }
     }
 }
 
@@ -542,7 +615,9 @@ struct StatsDev {   // must match mor_stats in include/mor.h
     unsigned long long n_part, n_fp8_part, n_bf16_part, n_elem_fp8, n_elem_bf16, nnz_total, n_near_threshold;
     double err_sum_total, mean_err;
     uint32_t hist[12];
-    uint32_t reserved;
+    uint32_t reserved;      // flags
+    uint32_t reserved2;
+    unsigned long long n_e5m2_part, n_elem_e5m2;
 };
 __device__ __forceinline__ int stats_bin(float metric) {
     if (!(metric < __builtin_inff())) return 11;
@@ -552,57 +627,102 @@ __device__ __forceinline__ int stats_bin(float metric) {
         if (metric >= (float)(0.005 * k)) bin = k;
     return bin;
 }
+// Number of elements of block p: blocks at the right / bottom edge of a ragged tensor are smaller.
+__device__ __forceinline__ unsigned long long block_elems(const StatsGeom& g, int64_t p) {
+    if (g.uniform) return (unsigned long long)(g.pr * g.pc);
+    const int64_t br = p / g.gc, bc = p - br * g.gc;
+    const int64_t h = g.rows - br * g.pr < g.pr ? g.rows - br * g.pr : g.pr;
+    const int64_t w = g.cols - bc * g.pc < g.pc ? g.cols - bc * g.pc : g.pc;
+    return (unsigned long long)(h * w);
+}
+constexpr int kStatCnt = 15;     // 12 histogram bins, BF16 blocks, near-threshold blocks, E5M2 blocks
 struct StatsAcc {
     double e;
-    unsigned long long n;
-    uint32_t n_bf16, n_near;
+    unsigned long long n, eb, e5;        // non-zeros; elements in BF16 blocks; elements in E5M2 blocks
+    uint32_t cnt[kStatCnt];
 };
+__device__ __forceinline__ void stats_acc_clear(StatsAcc& a) {
+    a.e = 0.0; a.n = 0ull; a.eb = 0ull; a.e5 = 0ull;
+#pragma unroll
+    for (int k = 0; k < kStatCnt; ++k) a.cnt[k] = 0u;
+}
 __device__ __forceinline__ void stats_accumulate(int64_t p, const float* __restrict__ err_sum, const uint32_t* __restrict__ nnz,
-                                                 const uint8_t* __restrict__ mask, float th, float near_tol, uint32_t* sh_hist,
+                                                 const uint8_t* __restrict__ mask, float th, float near_tol, const StatsGeom& geom,
                                                  StatsAcc& a) {
     const float es = err_sum[p];
     const uint32_t nz = nnz[p];
+    const uint32_t mk = mask[p];
     const float metric = nz ? es / (float)nz : 0.0f;           // binary32, IEEE division
-    atomicAdd(&sh_hist[stats_bin(metric)], 1u);
+    const int bin = stats_bin(metric);
+#pragma unroll
+    for (int k = 0; k < 12; ++k) a.cnt[k] += (bin == k) ? 1u : 0u;
     a.e += (double)es;
     a.n += nz;
-    a.n_bf16 += mask[p] ? 1u : 0u;
-    if (fabs((double)metric - (double)th) <= (double)near_tol * (double)th) a.n_near += 1u;
+    a.cnt[12] += mk == 1u ? 1u : 0u;
+    a.cnt[13] += (fabs((double)metric - (double)th) <= (double)near_tol * (double)th) ? 1u : 0u;
+    a.cnt[14] += mk == 2u ? 1u : 0u;
+    if (mk) {
+        const unsigned long long ne = block_elems(geom, p);
+        if (mk == 1u) a.eb += ne; else a.e5 += ne;
+    }
 }
-__device__ __forceinline__ void stats_finish(StatsDev* st, int64_t n_part, unsigned long long elems_per_part, double e,
-                                             unsigned long long n, unsigned long long n_bf16, unsigned long long n_near) {
+__device__ __forceinline__ void stats_finish(StatsDev* st, int64_t n_part, unsigned long long total_elems, double e,
+                                             unsigned long long n, unsigned long long n_bf16, unsigned long long n_near,
+                                             unsigned long long n_e5, unsigned long long eb, unsigned long long ee5, uint32_t flags) {
     st->n_part = (unsigned long long)n_part;
-    st->n_fp8_part = (unsigned long long)n_part - n_bf16;
+    st->n_fp8_part = (unsigned long long)n_part - n_bf16 - n_e5;
     st->n_bf16_part = n_bf16;
-    st->n_elem_fp8 = ((unsigned long long)n_part - n_bf16) * elems_per_part;
-    st->n_elem_bf16 = n_bf16 * elems_per_part;
+    st->n_e5m2_part = n_e5;
+    st->n_elem_fp8 = total_elems - eb - ee5;
+    st->n_elem_bf16 = eb;
+    st->n_elem_e5m2 = ee5;
     st->nnz_total = n;
     st->n_near_threshold = n_near;
     st->err_sum_total = e;
     st->mean_err = n ? e / (double)n : 0.0;
-    st->reserved = 0u;
+    st->reserved = flags;
+    st->reserved2 = 0u;
+}
+// Block-wide sums of the small counters without same-address atomics: DPP wave sums, one LDS row per
+// wave, then kStatCnt lanes add the four rows.  Result in sh[0][*].
+__device__ __forceinline__ void block_counts(const uint32_t (&v)[kStatCnt], uint32_t (*sh)[kStatCnt]) {
+    const int w = threadIdx.x >> 6;
+#pragma unroll
+    for (int k = 0; k < kStatCnt; ++k) {
+        const uint32_t s = wave_allsum_u32(v[k]);
+        if ((threadIdx.x & 63) == 0) sh[w][k] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x < kStatCnt) sh[0][threadIdx.x] = (sh[0][threadIdx.x] + sh[1][threadIdx.x]) + (sh[2][threadIdx.x] + sh[3][threadIdx.x]);
+    __syncthreads();
+}
+struct StatsShared {
+    uint32_t cnt[4][kStatCnt];
+    double d[4];
+    unsigned long long l[4];
+};
+// Reduces an accumulator over the workgroup: counters end in sh.cnt[0][*], the sums are returned in `a` on every thread.
+__device__ __forceinline__ void stats_block_reduce(StatsAcc& a, StatsShared& sh) {
+    block_counts(a.cnt, sh.cnt);
+    a.e = block_sum_shfl<double>(a.e, sh.d);            // fixed order: deterministic
+    a.n = block_sum_shfl<unsigned long long>(a.n, sh.l);
+    a.eb = block_sum_shfl<unsigned long long>(a.eb, sh.l);
+    a.e5 = block_sum_shfl<unsigned long long>(a.e5, sh.l);
 }
 
 // Up to a few thousand blocks: one workgroup, no atomics on global memory, deterministic sums.
-__global__ __launch_bounds__(256) void k_stats_single(int64_t n_part, unsigned long long elems_per_part,
+__global__ __launch_bounds__(256) void k_stats_single(int64_t n_part, StatsGeom geom,
                                                       const float* __restrict__ err_sum, const uint32_t* __restrict__ nnz,
                                                       const uint8_t* __restrict__ mask, float th, float near_tol,
                                                       StatsDev* __restrict__ st) {
-    __shared__ uint32_t sh_hist[12];
-    __shared__ uint32_t sh_cnt[2];
-    __shared__ double shd[256];
-    __shared__ unsigned long long shl[256];
-    if (threadIdx.x < 12) sh_hist[threadIdx.x] = 0u;
-    if (threadIdx.x < 2) sh_cnt[threadIdx.x] = 0u;
-    __syncthreads();
-    StatsAcc a{0.0, 0ull, 0u, 0u};
-    for (int64_t p = threadIdx.x; p < n_part; p += 256) stats_accumulate(p, err_sum, nnz, mask, th, near_tol, sh_hist, a);
-    if (a.n_bf16) atomicAdd(&sh_cnt[0], a.n_bf16);
-    if (a.n_near) atomicAdd(&sh_cnt[1], a.n_near);
-    const double e = block_sum_256<double>(a.e, shd);
-    const unsigned long long n = block_sum_256<unsigned long long>(a.n, shl);
-    if (threadIdx.x < 12) st->hist[threadIdx.x] = sh_hist[threadIdx.x];
-    if (threadIdx.x == 0) stats_finish(st, n_part, elems_per_part, e, n, sh_cnt[0], sh_cnt[1]);
+    __shared__ StatsShared sh;
+    StatsAcc a;
+    stats_acc_clear(a);
+    for (int64_t p = threadIdx.x; p < n_part; p += 256) stats_accumulate(p, err_sum, nnz, mask, th, near_tol, geom, a);
+    stats_block_reduce(a, sh);
+    if (threadIdx.x < 12) st->hist[threadIdx.x] = sh.cnt[0][threadIdx.x];
+    if (threadIdx.x == 0)
+        stats_finish(st, n_part, (unsigned long long)(geom.rows * geom.cols), a.e, a.n, sh.cnt[0][12], sh.cnt[0][13], sh.cnt[0][14], a.eb, a.e5, 0u);
 }
 
 // Many blocks: the accumulators live in the output struct, cleared by a tiny kernel first and
@@ -610,37 +730,43 @@ __global__ __launch_bounds__(256) void k_stats_single(int64_t n_part, unsigned l
 __global__ void k_stats_zero(StatsDev* st) {
     if (threadIdx.x < sizeof(StatsDev) / 4) reinterpret_cast<uint32_t*>(st)[threadIdx.x] = 0u;
 }
-__global__ __launch_bounds__(256) void k_stats_multi(int64_t n_part, unsigned long long elems_per_part,
+__global__ __launch_bounds__(256) void k_stats_multi(int64_t n_part, StatsGeom geom,
                                                      const float* __restrict__ err_sum, const uint32_t* __restrict__ nnz,
                                                      const uint8_t* __restrict__ mask, float th, float near_tol,
                                                      StatsDev* __restrict__ st) {
-    __shared__ uint32_t sh_hist[12];
-    __shared__ uint32_t sh_cnt[2];
-    __shared__ double shd[256];
-    __shared__ unsigned long long shl[256];
-    if (threadIdx.x < 12) sh_hist[threadIdx.x] = 0u;
-    if (threadIdx.x < 2) sh_cnt[threadIdx.x] = 0u;
-    __syncthreads();
-    StatsAcc a{0.0, 0ull, 0u, 0u};
+    __shared__ StatsShared sh;
+    StatsAcc a;
+    stats_acc_clear(a);
     const int64_t stride = (int64_t)gridDim.x * 256;
     for (int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x; p < n_part; p += stride)
-        stats_accumulate(p, err_sum, nnz, mask, th, near_tol, sh_hist, a);
-    if (a.n_bf16) atomicAdd(&sh_cnt[0], a.n_bf16);
-    if (a.n_near) atomicAdd(&sh_cnt[1], a.n_near);
-    const double e = block_sum_256<double>(a.e, shd);
-    const unsigned long long n = block_sum_256<unsigned long long>(a.n, shl);
-    if (threadIdx.x < 12 && sh_hist[threadIdx.x]) atomicAdd(&st->hist[threadIdx.x], sh_hist[threadIdx.x]);
+        stats_accumulate(p, err_sum, nnz, mask, th, near_tol, geom, a);
+    stats_block_reduce(a, sh);
+    if (threadIdx.x < 12 && sh.cnt[0][threadIdx.x]) atomicAdd(&st->hist[threadIdx.x], sh.cnt[0][threadIdx.x]);
     if (threadIdx.x == 0) {
-        atomicAdd(&st->err_sum_total, e);
-        atomicAdd(&st->nnz_total, n);
-        atomicAdd(&st->n_bf16_part, (unsigned long long)sh_cnt[0]);
-        atomicAdd(&st->n_near_threshold, (unsigned long long)sh_cnt[1]);
+        atomicAdd(&st->err_sum_total, a.e);
+        atomicAdd(&st->nnz_total, a.n);
+        atomicAdd(&st->n_bf16_part, (unsigned long long)sh.cnt[0][12]);
+        atomicAdd(&st->n_near_threshold, (unsigned long long)sh.cnt[0][13]);
+        atomicAdd(&st->n_e5m2_part, (unsigned long long)sh.cnt[0][14]);
+        atomicAdd(&st->n_elem_bf16, a.eb);
+        atomicAdd(&st->n_elem_e5m2, a.e5);
     }
 }
 // Derived fields once every workgroup of k_stats_multi has finished (next kernel on the stream).
-__global__ void k_stats_finish(int64_t n_part, unsigned long long elems_per_part, StatsDev* __restrict__ st) {
+__global__ void k_stats_finish(int64_t n_part, unsigned long long total_elems, StatsDev* __restrict__ st) {
     if (threadIdx.x == 0)
-        stats_finish(st, n_part, elems_per_part, st->err_sum_total, st->nnz_total, st->n_bf16_part, st->n_near_threshold);
+        stats_finish(st, n_part, total_elems, st->err_sum_total, st->nnz_total, st->n_bf16_part, st->n_near_threshold,
+                     st->n_e5m2_part, st->n_elem_bf16, st->n_elem_e5m2, 0u);
+}
+
+// Running histogram of a tensor's error over training steps (Section 4.1.3): one count per step in the
+// bin of (float)mean_err, cleared first on every reset step.
+__global__ void k_histogram_update(uint32_t* __restrict__ hist, const StatsDev* __restrict__ st, int clear) {
+    const int bin = stats_bin((float)st->mean_err);
+    if (threadIdx.x < 12) {
+        const uint32_t old = clear ? 0u : hist[threadIdx.x];
+        hist[threadIdx.x] = old + ((int)threadIdx.x == bin ? 1u : 0u);
+    }
 }
 
 // ======================================================================================
@@ -650,26 +776,22 @@ __global__ void k_stats_finish(int64_t n_part, unsigned long long elems_per_part
 // per-launch overhead is paid once per group instead of once per operand.  The descriptor tables
 // travel in the kernel-argument segment: no staging copy, nothing allocated.
 // ======================================================================================
-constexpr int kMaxGroup = 16;
+constexpr int kMaxGroup = 12;          // per-tensor operands / GAM pre-pass per launch
+constexpr int kMaxGroupSub = 16;       // 1x128 and 128x128 operands per launch
 #ifndef MOR_SUB_DOUBLE
 #define MOR_SUB_DOUBLE 0
 #endif
 
 struct GroupSub {
     int n;
-    int64_t unit_end[kMaxGroup];          // running total of 32-block units
-    const uint16_t* x[kMaxGroup];
-    KOut o[kMaxGroup];
-    float th[kMaxGroup];
-    uint8_t defer[kMaxGroup];             // 1: tensor-level decision follows, write no mask / fallback here
-    uint8_t mode[kMaxGroup];              // scaling algorithm
-    const uint32_t* gam[kMaxGroup];       // mode != 0: {mantissa for E4M3, mantissa for E5M2} of the operand's group
+    int64_t unit_end[kMaxGroupSub];       // running total of 32-block units
+    const uint16_t* x[kMaxGroupSub];
+    KOut o[kMaxGroupSub];
+    float th[kMaxGroupSub];
+    uint8_t defer[kMaxGroupSub];          // 1: tensor-level decision follows, write no mask / fallback here
+    uint8_t mode[kMaxGroupSub];           // scaling algorithm
+    const uint32_t* gam[kMaxGroupSub];    // mode != 0: {mantissa for E4M3, mantissa for E5M2} of the operand's group
 };
-__device__ __forceinline__ int group_find(const int64_t* end, int n, int64_t v) {
-    int i = 0;
-    while (i + 1 < n && v >= end[i]) ++i;
-    return __builtin_amdgcn_readfirstlane(i);
-}
 template <int CRIT>
 __global__ __launch_bounds__(256) void k_sub1x128_group(GroupSub g) {
     const int lane = threadIdx.x & 63, row = lane >> 4, l = lane & 15;
@@ -722,15 +844,15 @@ __global__ __launch_bounds__(256) void k_sub1x128_group(GroupSub g) {
 
 struct GroupBlock {
     int n;
-    int64_t tile_end[kMaxGroup];          // running total of 128x128 tiles
-    int32_t tiles_x[kMaxGroup];
-    int64_t ld[kMaxGroup];
-    const uint16_t* x[kMaxGroup];
-    KOut o[kMaxGroup];
-    float th[kMaxGroup];
-    uint8_t defer[kMaxGroup];
-    uint8_t mode[kMaxGroup];
-    const uint32_t* gam[kMaxGroup];
+    int64_t tile_end[kMaxGroupSub];       // running total of 128x128 tiles
+    int32_t tiles_x[kMaxGroupSub];
+    int64_t ld[kMaxGroupSub];
+    const uint16_t* x[kMaxGroupSub];
+    KOut o[kMaxGroupSub];
+    float th[kMaxGroupSub];
+    uint8_t defer[kMaxGroupSub];
+    uint8_t mode[kMaxGroupSub];
+    const uint32_t* gam[kMaxGroupSub];
 };
 // One 256-thread workgroup per 128x128 block (Section 4.1.1 "Per-Block"): the whole 32 KB tile lives in
 // registers (8 x 16 B per lane); LDS only carries 4 per-wave partials.
@@ -835,11 +957,6 @@ struct GroupTensor {
     float near_tol;
     TensorOp op[kMaxGroup];
 };
-__device__ __forceinline__ int group_find32(const int32_t* end, int n, int v) {
-    int i = 0;
-    while (i + 1 < n && v >= end[i]) ++i;
-    return __builtin_amdgcn_readfirstlane(i);
-}
 // Pass A also gathers a PROOF of the BF16 decision where one exists.  Section 4.1.3 observes that a
 // per-tensor scale falls back as soon as ~2.4 % of the values flush to zero; each flushed non-zero
 // element contributes exactly 1 to the error sum of Eq. (1)-(2), so "flushed >= th * N" already implies
@@ -899,7 +1016,7 @@ __device__ __forceinline__ bool tensor_fallback_proven(const TensorOp& t, unsign
     f = block_sum_shfl<unsigned long long>(f, shl);
     return f >= t.flush_need;
 }
-template <int CRIT>
+template <int CRIT, bool FAKE>
 __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
     __shared__ uint32_t sh4[4];
     const int op = group_find32(g.slot_end, g.n, blockIdx.x);
@@ -933,6 +1050,8 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
     const float s = block_scale(abits, kE4M3Max, mode, group_mantissa_bits(abits, kE4M3Max, mode));
     const float s5 = (CRIT == kCritEq3) ? block_scale(abits, kE5M2Max, mode, group_mantissa_bits(abits, kE5M2Max, mode)) : 0.0f;
     const bool fast = abits < fast_amax_limit(mode);
+    const float s_inv = FAKE ? 1.0f / s : 0.0f;
+    uint16_t* __restrict__ fakep = t.o.fake;     // fake quantization: == bf16, so a proven fallback is already in place
     TensorAcc acc{0.0f, 0.0f, 0.0f, 0.0f, 0u};
     auto process = [&](const u32x4* raw, int64_t tile) {
         const int64_t c0 = tile * kTensorChunksPerBlock + threadIdx.x;
@@ -949,8 +1068,12 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
 #pragma unroll
             for (int u = 0; u < kTensorChunksPerThread; ++u) {
                 const int64_t c = c0 + u * 256;
-                const u32x2 codes = quant8_fast<false>(raw[u], s, acc.e0, acc.e1);
-                if (c < n_chunks) store8(fp8 + c * 8, codes);
+                u32x4 deq;
+                const u32x2 codes = quant8_fast_deq<false, FAKE>(raw[u], s, s_inv, acc.e0, acc.e1, deq);
+                if (c < n_chunks) {
+                    if constexpr (FAKE) { if (!proven) store16(fakep + c * 8, deq); }
+                    else store8(fp8 + c * 8, codes);
+                }
                 if constexpr (CRIT == kCritEq3) (void)quant8_fast<true>(raw[u], s5, acc.f0, acc.f1);
 #if MOR_TQ_SB
                 __builtin_amdgcn_sched_barrier(0);
@@ -961,7 +1084,8 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
             for (int u = 0; u < kTensorChunksPerThread; ++u) {
                 const int64_t c = c0 + u * 256;
                 if (c < n_chunks) {
-                    acc.e0 += quant8_careful_mem<false>(x + c * 8, s, fp8 + c * 8);
+                    acc.e0 += quant8_careful_mem<false>(x + c * 8, s, FAKE ? nullptr : fp8 + c * 8,
+                                                        (FAKE && !proven) ? fakep + c * 8 : nullptr, s_inv);
                     if constexpr (CRIT == kCritEq3) acc.f0 += quant8_careful_mem<true>(x + c * 8, s5, nullptr);
                 }
             }
@@ -1024,7 +1148,7 @@ __global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g) {
         const float s = block_scale(abits, kE4M3Max, t.mode, mg);
         o.scale[0] = s;
         if (t.mode != kScaleFp32 && o.e8m0) o.e8m0[0] = (uint8_t)(__float_as_uint(s) >> 23);
-        if (t.mode != kScaleFp32 && o.gmant) o.gmant[0] = mg;
+        if (t.mode != kScaleFp32 && o.gmant) { o.gmant[0] = mg; o.gmant[1] = group_mantissa_bits(abits, kE5M2Max, t.mode); }
         o.amax[0] = __uint_as_float(abits << 16);
         o.err_sum[0] = err_f;
         o.nnz[0] = nnz32;
@@ -1037,8 +1161,8 @@ __global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g) {
             for (int k = 0; k < 12; ++k) st->hist[k] = 0u;
             st->hist[stats_bin(metric)] = 1u;
             const bool near = fabs((double)metric - (double)t.th) <= (double)g.near_tol * (double)t.th;
-            stats_finish(st, 1, (unsigned long long)t.n_chunks * 8ull, (double)err_f, nnz32, mask, near ? 1ull : 0ull);
-            st->reserved = proven ? 1u : 0u;
+            const unsigned long long total = (unsigned long long)t.n_chunks * 8ull;
+            stats_finish(st, 1, total, (double)err_f, nnz32, mask, near ? 1ull : 0ull, 0ull, mask ? total : 0ull, 0ull, proven ? 1u : 0u);
         }
     }
     if (proven || mask == 0u || t.o.bf16 == nullptr) return;
@@ -1081,8 +1205,9 @@ __global__ __launch_bounds__(256) void k_gam_prepare(GroupGam g) {
     if (threadIdx.x == 0) {
         const uint32_t mg = group_mantissa_bits(gbits, kE4M3Max, t.mode);
         t.gam[0] = mg;
-        t.gam[1] = group_mantissa_bits(gbits, kE5M2Max, t.mode);
-        if (t.gmant) t.gmant[0] = mg;
+        const uint32_t mg5 = group_mantissa_bits(gbits, kE5M2Max, t.mode);
+        t.gam[1] = mg5;
+        if (t.gmant) { t.gmant[0] = mg; t.gmant[1] = mg5; }
     }
 }
 
@@ -1090,98 +1215,66 @@ __global__ __launch_bounds__(256) void k_gam_prepare(GroupGam g) {
 // the workspace, pass 2 (one workgroup per operand) combines them in a fixed order.
 struct StatsRec {      // 128 bytes
     double e;
-    unsigned long long n, n_bf16, n_near;
-    uint32_t hist[12];
-    uint32_t pad[12];
+    unsigned long long n, eb, e5;
+    uint32_t cnt[kStatCnt];
+    uint32_t pad[9];
 };
 struct StatsOp {
     const float* err_sum; const uint32_t* nnz; const uint8_t* mask;
-    int64_t n_part; unsigned long long elems_per_part;
+    int64_t n_part;
+    StatsGeom geom;
     float th;
     StatsRec* rec;          // [n_wg]
     StatsDev* out;
 };
+constexpr int kMaxGroupStats = 12;
 struct GroupStats {
     int n;
-    int32_t wg_end[kMaxGroup];
+    int32_t wg_end[kMaxGroupStats];
     float near_tol;
-    StatsOp op[kMaxGroup];
+    StatsOp op[kMaxGroupStats];
 };
-// Block-wide sums of 14 small counters (12 histogram bins, BF16 blocks, near-threshold blocks) without
-// same-address atomics: DPP wave sums, one LDS row per wave, then 14 lanes add the four rows.
-__device__ __forceinline__ void block_counts_14(const uint32_t (&v)[14], uint32_t (*sh)[14]) {
-    const int w = threadIdx.x >> 6;
-#pragma unroll
-    for (int k = 0; k < 14; ++k) {
-        const uint32_t s = wave_allsum_u32(v[k]);
-        if ((threadIdx.x & 63) == 0) sh[w][k] = s;
-    }
-    __syncthreads();
-    if (threadIdx.x < 14) sh[0][threadIdx.x] = (sh[0][threadIdx.x] + sh[1][threadIdx.x]) + (sh[2][threadIdx.x] + sh[3][threadIdx.x]);
-    __syncthreads();
-}
 __global__ __launch_bounds__(256) void k_stats_group_partial(GroupStats g) {
-    __shared__ uint32_t sh_cnt[4][14];
-    __shared__ double shd[4];
-    __shared__ unsigned long long shl[4];
+    __shared__ StatsShared sh;
     const int op = group_find32(g.wg_end, g.n, blockIdx.x);
     const StatsOp& t = g.op[op];
     const int b = blockIdx.x - (op ? g.wg_end[op - 1] : 0);
     const int nb = g.wg_end[op] - (op ? g.wg_end[op - 1] : 0);
-    double e = 0.0;
-    unsigned long long n = 0;
-    uint32_t cnt[14];
-#pragma unroll
-    for (int k = 0; k < 14; ++k) cnt[k] = 0u;
-    for (int64_t p = (int64_t)b * 256 + threadIdx.x; p < t.n_part; p += (int64_t)nb * 256) {
-        const float es = t.err_sum[p];
-        const uint32_t nz = t.nnz[p];
-        const float metric = nz ? es / (float)nz : 0.0f;
-        const int bin = stats_bin(metric);
-#pragma unroll
-        for (int k = 0; k < 12; ++k) cnt[k] += (bin == k) ? 1u : 0u;
-        e += (double)es;
-        n += nz;
-        cnt[12] += t.mask[p] ? 1u : 0u;
-        cnt[13] += (fabs((double)metric - (double)t.th) <= (double)g.near_tol * (double)t.th) ? 1u : 0u;
-    }
-    block_counts_14(cnt, sh_cnt);
-    e = block_sum_shfl<double>(e, shd);
-    n = block_sum_shfl<unsigned long long>(n, shl);
+    StatsAcc a;
+    stats_acc_clear(a);
+    for (int64_t p = (int64_t)b * 256 + threadIdx.x; p < t.n_part; p += (int64_t)nb * 256)
+        stats_accumulate(p, t.err_sum, t.nnz, t.mask, t.th, g.near_tol, t.geom, a);
+    stats_block_reduce(a, sh);
     if (nb == 1) {      // the whole operand in one workgroup: write the result, no second pass needed
-        if (threadIdx.x < 12) t.out->hist[threadIdx.x] = sh_cnt[0][threadIdx.x];
-        if (threadIdx.x == 0) stats_finish(t.out, t.n_part, t.elems_per_part, e, n, sh_cnt[0][12], sh_cnt[0][13]);
+        if (threadIdx.x < 12) t.out->hist[threadIdx.x] = sh.cnt[0][threadIdx.x];
+        if (threadIdx.x == 0)
+            stats_finish(t.out, t.n_part, (unsigned long long)(t.geom.rows * t.geom.cols), a.e, a.n, sh.cnt[0][12], sh.cnt[0][13],
+                         sh.cnt[0][14], a.eb, a.e5, 0u);
         return;
     }
     StatsRec* r = t.rec + b;
-    if (threadIdx.x < 12) r->hist[threadIdx.x] = sh_cnt[0][threadIdx.x];
-    if (threadIdx.x == 0) { r->e = e; r->n = n; r->n_bf16 = sh_cnt[0][12]; r->n_near = sh_cnt[0][13]; }
+    if (threadIdx.x < kStatCnt) r->cnt[threadIdx.x] = sh.cnt[0][threadIdx.x];
+    if (threadIdx.x == 0) { r->e = a.e; r->n = a.n; r->eb = a.eb; r->e5 = a.e5; }
 }
 __global__ __launch_bounds__(256) void k_stats_group_final(GroupStats g) {
-    __shared__ uint32_t sh_cnt[4][14];
-    __shared__ double shd[4];
-    __shared__ unsigned long long shl[4];
+    __shared__ StatsShared sh;
     const int op = blockIdx.x;
     const StatsOp& t = g.op[op];
     const int nb = g.wg_end[op] - (op ? g.wg_end[op - 1] : 0);       // <= 256: one record per thread
     if (nb == 1) return;                                             // already final
-    double e = 0.0;
-    unsigned long long n = 0;
-    uint32_t cnt[14];
-#pragma unroll
-    for (int k = 0; k < 14; ++k) cnt[k] = 0u;
+    StatsAcc a;
+    stats_acc_clear(a);
     if ((int)threadIdx.x < nb) {
         const StatsRec& r = t.rec[threadIdx.x];
-        e = r.e; n = r.n;
-        cnt[12] = (uint32_t)r.n_bf16; cnt[13] = (uint32_t)r.n_near;  // per-workgroup counts fit 32 bits
+        a.e = r.e; a.n = r.n; a.eb = r.eb; a.e5 = r.e5;
 #pragma unroll
-        for (int k = 0; k < 12; ++k) cnt[k] = r.hist[k];
+        for (int k = 0; k < kStatCnt; ++k) a.cnt[k] = r.cnt[k];      // per-workgroup counts fit 32 bits
     }
-    block_counts_14(cnt, sh_cnt);
-    e = block_sum_shfl<double>(e, shd);          // fixed order: deterministic
-    n = block_sum_shfl<unsigned long long>(n, shl);
-    if (threadIdx.x < 12) t.out->hist[threadIdx.x] = sh_cnt[0][threadIdx.x];
-    if (threadIdx.x == 0) stats_finish(t.out, t.n_part, t.elems_per_part, e, n, sh_cnt[0][12], sh_cnt[0][13]);
+    stats_block_reduce(a, sh);
+    if (threadIdx.x < 12) t.out->hist[threadIdx.x] = sh.cnt[0][threadIdx.x];
+    if (threadIdx.x == 0)
+        stats_finish(t.out, t.n_part, (unsigned long long)(t.geom.rows * t.geom.cols), a.e, a.n, sh.cnt[0][12], sh.cnt[0][13],
+                     sh.cnt[0][14], a.eb, a.e5, 0u);
 }
 
 // ======================================================================================
@@ -1229,18 +1322,25 @@ static bool is_flat(const KShape& sh, const KOut& o) {
 constexpr int64_t kSubFlatMaxBlocks = MOR_SUB_BLOCKS;   // workgroups of 4 waves; each wave strides over 8 KB units
 static int clamp_grid_y(int64_t v) { return (int)(v < 1 ? 1 : (v > 65535 ? 65535 : v)); }
 
-#define MOR_DISPATCH_CRIT_DEFER(KERNEL, ...)                                                     \
-    do {                                                                                         \
-        if (crit == kCritEq3) { if (defer) KERNEL<kCritEq3, true> __VA_ARGS__; else KERNEL<kCritEq3, false> __VA_ARGS__; } \
-        else                  { if (defer) KERNEL<kCritEq2, true> __VA_ARGS__; else KERNEL<kCritEq2, false> __VA_ARGS__; } \
-    } while (0)
-
-// Padded leading dimensions: one operand per launch.
+// The general 1 x 128 kernel: one operand per launch.
+template <int CRIT>
+static void launch_sub1x128_crit(const dim3& grid, const uint16_t* x, const KShape& sh, const KOut& o, bool defer, float th,
+                                 uint32_t mode, const uint32_t* gam, uint32_t three, hipStream_t st) {
+    const bool fake = o.fake != nullptr;
+    if (defer) {
+        if (fake) k_sub1x128_strided<CRIT, true, true><<<grid, dim3(256), 0, st>>>(x, sh, o, th, mode, gam, three);
+        else k_sub1x128_strided<CRIT, true, false><<<grid, dim3(256), 0, st>>>(x, sh, o, th, mode, gam, three);
+    } else {
+        if (fake) k_sub1x128_strided<CRIT, false, true><<<grid, dim3(256), 0, st>>>(x, sh, o, th, mode, gam, three);
+        else k_sub1x128_strided<CRIT, false, false><<<grid, dim3(256), 0, st>>>(x, sh, o, th, mode, gam, three);
+    }
+}
 static hipError_t launch_sub1x128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, uint32_t mode,
-                                  const uint32_t* gam, hipStream_t st, KProf* prof) {
+                                  const uint32_t* gam, uint32_t three, hipStream_t st, KProf* prof) {
     ProfScope ps(prof, kKernSub1x128, st);
-    const dim3 grid((unsigned)(sh.cols / 128), (unsigned)clamp_grid_y((sh.rows + 15) / 16));
-    MOR_DISPATCH_CRIT_DEFER(k_sub1x128_strided, <<<grid, dim3(256), 0, st>>>(x, sh, o, th, mode, gam));
+    const dim3 grid((unsigned)((sh.cols + 127) / 128), (unsigned)clamp_grid_y((sh.rows + 15) / 16));
+    if (crit == kCritEq3) launch_sub1x128_crit<kCritEq3>(grid, x, sh, o, defer, th, mode, gam, three, st);
+    else launch_sub1x128_crit<kCritEq2>(grid, x, sh, o, defer, th, mode, gam, three, st);
     return hipGetLastError();
 }
 
@@ -1262,8 +1362,14 @@ static hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut&
     const unsigned long long n_padded = (unsigned long long)(gx * gy) * 2048ull;
     {
         ProfScope ps(prof, kKernTensorQuant, st);
-        if (crit == kCritEq3) k_tensor_quant_strided<kCritEq3><<<dim3(n_slots), dim3(256), 0, st>>>(x, sh, (uint32_t)gx, (uint32_t)(gx * gy), o, amax_part, n_amax, tp, mode);
-        else k_tensor_quant_strided<kCritEq2><<<dim3(n_slots), dim3(256), 0, st>>>(x, sh, (uint32_t)gx, (uint32_t)(gx * gy), o, amax_part, n_amax, tp, mode);
+        const uint32_t tx = (uint32_t)gx, nt = (uint32_t)(gx * gy);
+        if (o.fake) {
+            if (crit == kCritEq3) k_tensor_quant_strided<kCritEq3, true><<<dim3(n_slots), dim3(256), 0, st>>>(x, sh, tx, nt, o, amax_part, n_amax, tp, mode);
+            else k_tensor_quant_strided<kCritEq2, true><<<dim3(n_slots), dim3(256), 0, st>>>(x, sh, tx, nt, o, amax_part, n_amax, tp, mode);
+        } else {
+            if (crit == kCritEq3) k_tensor_quant_strided<kCritEq3, false><<<dim3(n_slots), dim3(256), 0, st>>>(x, sh, tx, nt, o, amax_part, n_amax, tp, mode);
+            else k_tensor_quant_strided<kCritEq2, false><<<dim3(n_slots), dim3(256), 0, st>>>(x, sh, tx, nt, o, amax_part, n_amax, tp, mode);
+        }
     }
     {
         ProfScope ps(prof, kKernFallbackCopy, st);
@@ -1308,25 +1414,32 @@ static hipError_t launch_scope_finalize(const uint16_t* x, const KShape& sh, con
 
 // ---- batches ---------------------------------------------------------------------------------
 namespace {
-enum { kGranTensor = 0, kGranSub = 1, kGranBlock = 2 };
 constexpr int kStatsMaxWg = 256;
 
+// Which kernels take an operand.
+enum Route {
+    kRouteTensorGroup,      // per-tensor, dense: grouped three-pass kernels
+    kRouteTensorStrided,    // per-tensor, padded leading dimensions
+    kRouteSubFlat,          // 1 x 128, dense, whole blocks, two types, FP8 payload: the persistent grouped kernel
+    kRouteSubGeneral,       // 1 x 128, everything else
+    kRouteBlockHot,         // 128 x 128, whole blocks, two types, FP8 payload
+    kRouteTeam,             // 64 x 64, per-channel rows, and 128 x 128 with ragged edges / three types / fake quantization
+    kRouteSubCol,           // 128 x 1
+    kRouteChannelCol        // per-channel columns
+};
 bool item_is_flat(const BatchItem& it) { return is_flat(it.sh, it.o); }
-bool item_grouped(const BatchItem& it) {
-    if (it.gran == kGranBlock) return it.sh.cols / 128 <= 0x7FFFFFFF;
-    if (it.gran == kGranSub) return item_is_flat(it);
-    return item_is_flat(it);     // per-tensor: the scope does not matter (one block)
+Route route_of(const BatchItem& it) {
+    const bool plain = !it.three && it.o.fake == nullptr;
+    switch (it.gran) {
+    case kGranTensor: return item_is_flat(it) ? kRouteTensorGroup : kRouteTensorStrided;
+    case kGranSub: return (plain && item_is_flat(it) && it.sh.cols % 128 == 0) ? kRouteSubFlat : kRouteSubGeneral;
+    case kGranBlock: return (plain && it.sh.rows % 128 == 0 && it.sh.cols % 128 == 0) ? kRouteBlockHot : kRouteTeam;
+    case kGranBlock64: case kGranRow: return kRouteTeam;
+    case kGranSubCol: return kRouteSubCol;
+    default: return kRouteChannelCol;
+    }
 }
-int64_t item_parts(const BatchItem& it) {
-    if (it.gran == kGranSub) return it.sh.rows * (it.sh.cols / 128);
-    if (it.gran == kGranBlock) return (it.sh.rows / 128) * (it.sh.cols / 128);
-    return 1;
-}
-int64_t item_elems_per_part(const BatchItem& it) {
-    if (it.gran == kGranSub) return 128;
-    if (it.gran == kGranBlock) return 128 * 128;
-    return it.sh.rows * it.sh.cols;
-}
+int64_t item_parts(const BatchItem& it) { return geom_parts(make_geom(it.gran, it.sh.rows, it.sh.cols)); }
 int stats_wgs(int64_t n_part) {
     if (n_part <= 4096) return 1;                       // one workgroup writes the result directly
     int64_t w = (n_part + 1023) / 1024;
@@ -1336,7 +1449,8 @@ size_t item_workspace(const BatchItem& it) {
     size_t b = 0;
     if (it.gran == kGranTensor) b += plan_tensor(it.sh.rows, it.sh.cols).bytes;
     else if (it.scope == 1) b += scope_workspace_bytes(item_parts(it));
-    if (it.stats && it.gran != kGranTensor && item_grouped(it)) b += align16(sizeof(StatsRec) * kStatsMaxWg);
+    if (it.gran == kGranCol) b += column_workspace_bytes(it.sh.rows, it.sh.cols);
+    if (it.stats && it.gran != kGranTensor) b += align16(sizeof(StatsRec) * kStatsMaxWg);
     if (it.gran != kGranTensor && it.scaling != kScaleFp32) {
         b += 16;                                                                   // group mantissa words
         if (it.scaling == kScaleGam) b += align16(sizeof(uint32_t) * kMaxAmaxBlocks);   // amax partials of the pre-pass
@@ -1349,6 +1463,7 @@ int share(int64_t mine, int64_t total, int budget, int64_t cap) {
     if (v > budget) v = budget;
     return (int)(v < 1 ? 1 : v);
 }
+constexpr int kMaxGroupTensor = 12;
 }  // namespace
 
 size_t batch_workspace_bytes(const BatchItem* items, int n) {
@@ -1358,14 +1473,16 @@ size_t batch_workspace_bytes(const BatchItem* items, int n) {
 }
 
 hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws, size_t ws_bytes, hipStream_t st, KProf* prof) {
-    static_assert(sizeof(GroupSub) <= 3800 && sizeof(GroupBlock) <= 3800 && sizeof(GroupTensor) <= 3800 && sizeof(GroupStats) <= 3800,
-                  "kernel-argument segment is 4 KB");
+    static_assert(sizeof(GroupSub) <= 3800 && sizeof(GroupBlock) <= 3800 && sizeof(GroupTensor) <= 3800 && sizeof(GroupStats) <= 3800 &&
+                  sizeof(GroupGam) <= 3800, "kernel-argument segment is 4 KB");
     static_assert(sizeof(StatsRec) == 128, "StatsRec layout");
     char* wsp = static_cast<char*>(ws);
     size_t ws_off = 0;
     auto carve = [&](size_t bytes) -> char* { char* p = wsp + ws_off; ws_off += align16(bytes); return p; };
     (void)ws_bytes;
     hipError_t err = hipSuccess;
+    Route route[kBatchMax];
+    for (int i = 0; i < n; ++i) route[i] = route_of(items[i]);
 
     // ---- Algorithm 1, group loop: operands with sub-tensor blocks and GAM / E8M0 scaling get their group
     //      mantissas first (GAM: one more read of the operand for its amax)
@@ -1375,11 +1492,11 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
         int cnt = 0;
         for (int i = 0; i < n; ++i)
             if (items[i].gran != kGranTensor && items[i].scaling != kScaleFp32) idx[cnt++] = i;
-        for (int base = 0; base < cnt; base += kMaxGroup) {
-            const int m = cnt - base < kMaxGroup ? cnt - base : kMaxGroup;
+        for (int base = 0; base < cnt; base += kMaxGroupTensor) {
+            const int m = cnt - base < kMaxGroupTensor ? cnt - base : kMaxGroupTensor;
             GroupGam gg; gg.n = m;
             GroupTensor ga; ga.n = 0; ga.near_tol = near_tol;
-            int slot_of[kMaxGroup];
+            int slot_of[kMaxGroupTensor];
             int64_t total_tiles = 0;
             for (int k = 0; k < m; ++k) {
                 const BatchItem& it = items[idx[base + k]];
@@ -1421,7 +1538,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
     }
 
     for (int crit = 0; crit < 2 && err == hipSuccess; ++crit) {
-        // ---- 1x128 sub-channel operands
+        // ---- 1x128 sub-channel operands, persistent grouped kernel
         {
             GroupSub g; g.n = 0;
             int64_t total = 0;
@@ -1436,15 +1553,15 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
             };
             for (int i = 0; i < n; ++i) {
                 const BatchItem& it = items[i];
-                if (it.gran != kGranSub || it.crit != crit || !item_grouped(it)) continue;
+                if (route[i] != kRouteSubFlat || it.crit != crit) continue;
                 const int64_t n_part = item_parts(it), n_units = n_part / 32, n_full = n_units * 32, n_tail = n_part - n_full;
                 if (n_units > 0) {
                     total += n_units;
                     g.unit_end[g.n] = total; g.x[g.n] = it.x; g.o[g.n] = it.o; g.th[g.n] = it.th; g.defer[g.n] = it.scope == 1;
                     g.mode[g.n] = (uint8_t)it.scaling; g.gam[g.n] = gam_of[i];
-                    if (++g.n == kMaxGroup) flush();
+                    if (++g.n == kMaxGroupSub) flush();
                 }
-                if (n_tail > 0) {     // fewer than 32 blocks left: the strided kernel takes them
+                if (n_tail > 0) {     // fewer than 32 blocks left: the general kernel takes them
                     KShape ts{n_tail, 128, 128};
                     KOut to = it.o;
                     to.fp8 += n_full * 128; to.ld_fp8 = 128;
@@ -1452,15 +1569,19 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                     to.ld_bf16 = 128;
                     to.scale += n_full; to.amax += n_full; to.err_sum += n_full; to.nnz += n_full; to.mask += n_full;
                     if (to.err5_sum) to.err5_sum += n_full;
-                    const dim3 grid(1u, (unsigned)clamp_grid_y((n_tail + 15) / 16));
-                    const bool defer = it.scope == 1;
                     if (to.e8m0) to.e8m0 += n_full;
-                    MOR_DISPATCH_CRIT_DEFER(k_sub1x128_strided, <<<grid, dim3(256), 0, st>>>(it.x + n_full * 128, ts, to, it.th, (uint32_t)it.scaling, gam_of[i]));
+                    err = launch_sub1x128(it.x + n_full * 128, ts, to, crit, it.scope == 1, it.th, (uint32_t)it.scaling, gam_of[i], 0u, st, nullptr);
                 }
             }
             flush();
         }
-        // ---- 128x128 block operands
+        // ---- 1x128 sub-channel operands, general kernel
+        for (int i = 0; i < n && err == hipSuccess; ++i) {
+            const BatchItem& it = items[i];
+            if (route[i] != kRouteSubGeneral || it.crit != crit) continue;
+            err = launch_sub1x128(it.x, it.sh, it.o, crit, it.scope == 1, it.th, (uint32_t)it.scaling, gam_of[i], (uint32_t)it.three, st, prof);
+        }
+        // ---- 128x128 block operands, whole blocks
         {
             GroupBlock g; g.n = 0;
             int64_t total = 0;
@@ -1473,7 +1594,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
             };
             for (int i = 0; i < n; ++i) {
                 const BatchItem& it = items[i];
-                if (it.gran != kGranBlock || it.crit != crit || !item_grouped(it)) continue;
+                if (route[i] != kRouteBlockHot || it.crit != crit) continue;
                 const int64_t tiles = item_parts(it);
                 if (tiles > 0x7FFFFFFF) return hipErrorInvalidValue;
                 if (total + tiles > 0x7FFFFFFF) flush();
@@ -1481,13 +1602,36 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 g.tile_end[g.n] = total; g.tiles_x[g.n] = (int32_t)(it.sh.cols / 128); g.ld[g.n] = it.sh.ld;
                 g.x[g.n] = it.x; g.o[g.n] = it.o; g.th[g.n] = it.th; g.defer[g.n] = it.scope == 1;
                 g.mode[g.n] = (uint8_t)it.scaling; g.gam[g.n] = gam_of[i];
-                if (++g.n == kMaxGroup) flush();
+                if (++g.n == kMaxGroupSub) flush();
             }
             flush();
         }
-        // ---- per-tensor operands: amax pass, quantize pass, finish (+ fallback copy) pass
-        {
-            int idx[kMaxGroup];
+        // ---- team kernels: 64x64 blocks, per-channel rows, 128x128 blocks with edges / three types / fake quantization
+        for (int kind = 0; kind < 4 && err == hipSuccess; ++kind) {
+            int idx[kBatchMax];
+            int cnt = 0;
+            for (int i = 0; i < n; ++i)
+                if (route[i] == kRouteTeam && items[i].crit == crit && team_kind_of(items[i]) == kind) idx[cnt++] = i;
+            if (cnt) err = launch_team_items(items, idx, cnt, kind, crit, gam_of, st, prof);
+        }
+        // ---- 128x1 sub-columns
+        if (err == hipSuccess) {
+            int idx[kBatchMax];
+            int cnt = 0;
+            for (int i = 0; i < n; ++i)
+                if (route[i] == kRouteSubCol && items[i].crit == crit) idx[cnt++] = i;
+            if (cnt) err = launch_subcol_items(items, idx, cnt, crit, gam_of, st, prof);
+        }
+        // ---- per-channel columns
+        for (int i = 0; i < n && err == hipSuccess; ++i) {
+            const BatchItem& it = items[i];
+            if (route[i] != kRouteChannelCol || it.crit != crit) continue;
+            err = launch_channel_col(it, gam_of[i], carve(column_workspace_bytes(it.sh.rows, it.sh.cols)), st, prof);
+        }
+        // ---- per-tensor operands: amax pass, quantize pass, finish (+ fallback copy) pass; FP8 payload and fake
+        //      quantization are different kernels
+        for (int fake = 0; fake < 2 && err == hipSuccess; ++fake) {
+            int idx[kMaxGroupTensor];
             int cnt = 0;
             auto flush = [&]() {
                 if (cnt == 0) return;
@@ -1526,8 +1670,13 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_group<<<dim3(a_end), dim3(256), 0, st>>>(g); }
                 {
                     ProfScope ps(prof, kKernTensorQuant, st);
-                    if (crit == kCritEq3) k_tensor_quant_group<kCritEq3><<<dim3(s_end), dim3(256), 0, st>>>(g);
-                    else k_tensor_quant_group<kCritEq2><<<dim3(s_end), dim3(256), 0, st>>>(g);
+                    if (fake) {
+                        if (crit == kCritEq3) k_tensor_quant_group<kCritEq3, true><<<dim3(s_end), dim3(256), 0, st>>>(g);
+                        else k_tensor_quant_group<kCritEq2, true><<<dim3(s_end), dim3(256), 0, st>>>(g);
+                    } else {
+                        if (crit == kCritEq3) k_tensor_quant_group<kCritEq3, false><<<dim3(s_end), dim3(256), 0, st>>>(g);
+                        else k_tensor_quant_group<kCritEq2, false><<<dim3(s_end), dim3(256), 0, st>>>(g);
+                    }
                 }
                 {
                     ProfScope ps(prof, kKernFallbackCopy, st);
@@ -1538,37 +1687,30 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
             };
             for (int i = 0; i < n; ++i) {
                 const BatchItem& it = items[i];
-                if (it.gran != kGranTensor || it.crit != crit || !item_grouped(it)) continue;
+                if (route[i] != kRouteTensorGroup || it.crit != crit || (it.o.fake != nullptr) != (fake != 0)) continue;
                 const int64_t n_tiles = (it.sh.rows * it.sh.cols / 8 + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
                 if (n_tiles > 2000ll * kMaxQuantBlocks) return hipErrorInvalidValue;   // 16-bit per-lane zero counters
                 idx[cnt] = i;
-                if (++cnt == kMaxGroup) flush();
+                if (++cnt == kMaxGroupTensor) flush();
             }
             flush();
         }
+        // ---- per-tensor operands with padded leading dimensions, one at a time
+        for (int i = 0; i < n && err == hipSuccess; ++i) {
+            const BatchItem& it = items[i];
+            if (route[i] != kRouteTensorStrided || it.crit != crit) continue;
+            err = launch_tensor(it.x, it.sh, it.o, it.crit, it.th, (uint32_t)it.scaling, carve(plan_tensor(it.sh.rows, it.sh.cols).bytes), st, prof);
+            if (err == hipSuccess && it.stats)
+                err = launch_select_stats(make_geom(it.gran, it.sh.rows, it.sh.cols), it.o.err_sum, it.o.nnz, it.o.mask, it.th, near_tol, it.stats, st);
+        }
     }
-    // ---- tensor-level decision (Section 3.1) over the per-block sums the grouped passes left behind
+    // ---- tensor-level decision (Section 3.1) over the per-block sums the block kernels left behind
     for (int i = 0; i < n && err == hipSuccess; ++i) {
         const BatchItem& it = items[i];
-        if (!item_grouped(it) || it.gran == kGranTensor || it.scope != 1) continue;
+        if (it.gran == kGranTensor || it.scope != 1) continue;
         err = launch_scope_finalize(it.x, it.sh, it.o, item_parts(it), it.crit, it.th, carve(scope_workspace_bytes(item_parts(it))), st, prof);
     }
-    // ---- operands the grouped kernels do not cover (padded leading dimensions), one at a time
-    for (int i = 0; i < n && err == hipSuccess; ++i) {
-        const BatchItem& it = items[i];
-        if (item_grouped(it)) continue;
-        const bool defer = it.scope == 1;
-        if (it.gran == kGranTensor) {
-            err = launch_tensor(it.x, it.sh, it.o, it.crit, it.th, (uint32_t)it.scaling, carve(plan_tensor(it.sh.rows, it.sh.cols).bytes), st, prof);
-        } else {
-            err = launch_sub1x128(it.x, it.sh, it.o, it.crit, defer, it.th, (uint32_t)it.scaling, gam_of[i], st, prof);
-            if (err == hipSuccess && defer)
-                err = launch_scope_finalize(it.x, it.sh, it.o, item_parts(it), it.crit, it.th, carve(scope_workspace_bytes(item_parts(it))), st, prof);
-        }
-        if (err == hipSuccess && it.stats)
-            err = launch_select_stats(item_parts(it), item_elems_per_part(it), it.o.err_sum, it.o.nnz, it.o.mask, it.th, near_tol, it.stats, st);
-    }
-    // ---- statistics of the grouped sub-tensor operands
+    // ---- statistics of the operands with sub-tensor blocks
     {
         GroupStats g; g.n = 0; g.near_tol = near_tol;
         int wg_total = 0;
@@ -1580,16 +1722,17 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
         };
         for (int i = 0; i < n; ++i) {
             const BatchItem& it = items[i];
-            if (!it.stats || it.gran == kGranTensor || !item_grouped(it)) continue;
+            if (!it.stats || it.gran == kGranTensor) continue;
             StatsOp& t = g.op[g.n];
             t.err_sum = it.o.err_sum; t.nnz = it.o.nnz; t.mask = it.o.mask;
-            t.n_part = item_parts(it); t.elems_per_part = (unsigned long long)item_elems_per_part(it);
+            t.geom = make_geom(it.gran, it.sh.rows, it.sh.cols);
+            t.n_part = geom_parts(t.geom);
             t.th = it.th;
             t.rec = reinterpret_cast<StatsRec*>(carve(sizeof(StatsRec) * kStatsMaxWg));
             t.out = static_cast<StatsDev*>(it.stats);
             wg_total += stats_wgs(t.n_part);
             g.wg_end[g.n] = wg_total;
-            if (++g.n == kMaxGroup) flush();
+            if (++g.n == kMaxGroupStats) flush();
         }
         flush();
     }
@@ -1597,29 +1740,45 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
     return hipGetLastError();
 }
 
-hipError_t launch_dequantize(int gran, int64_t rows, int64_t cols, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
+static int log2_or_whole(int64_t block, int64_t dim) {
+    if (block >= dim) return 62;                 // one block spans the dimension: index >> 62 == 0
+    int l = 0;
+    while ((1ll << l) < block) ++l;
+    return l;
+}
+hipError_t launch_dequantize(const StatsGeom& geom, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
                              const uint8_t* mask, const uint16_t* bf16, int64_t ld_bf16, uint16_t* y, int64_t ld_y,
                              const uint8_t* e8m0, const uint32_t* gmant, hipStream_t st) {
-    const dim3 grid((unsigned)((cols + 127) / 128), (unsigned)clamp_grid_y((rows + 15) / 16));
-    if (gran == 0) k_dequant<0><<<grid, dim3(256), 0, st>>>(rows, cols, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y, e8m0, gmant);
-    else if (gran == 1) k_dequant<1><<<grid, dim3(256), 0, st>>>(rows, cols, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y, e8m0, gmant);
-    else k_dequant<2><<<grid, dim3(256), 0, st>>>(rows, cols, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y, e8m0, gmant);
+    const int prl = log2_or_whole(geom.pr, geom.rows), pcl = log2_or_whole(geom.pc, geom.cols);
+    if (geom.pc == 1 && geom.cols > 1) {
+        const dim3 grid((unsigned)((geom.cols + 127) / 128), (unsigned)clamp_grid_y((geom.rows + 127) / 128));
+        k_dequant_columns<<<grid, dim3(256), 0, st>>>(geom, prl, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y, e8m0, gmant);
+    } else {
+        const dim3 grid((unsigned)((geom.cols + 127) / 128), (unsigned)clamp_grid_y((geom.rows + 15) / 16));
+        k_dequant<<<grid, dim3(256), 0, st>>>(geom, prl, pcl, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y, e8m0, gmant);
+    }
     return hipGetLastError();
 }
 
-hipError_t launch_select_stats(int64_t n_part, int64_t elems_per_part, const float* err_sum, const uint32_t* nnz,
+hipError_t launch_select_stats(const StatsGeom& geom, const float* err_sum, const uint32_t* nnz,
                                const uint8_t* mask, float th, float near_tol, void* out_dev, hipStream_t st) {
-    static_assert(sizeof(StatsDev) == 128, "mor_stats layout");
+    static_assert(sizeof(StatsDev) == 144, "mor_stats layout");
     StatsDev* sd = static_cast<StatsDev*>(out_dev);
+    const int64_t n_part = geom_parts(geom);
     if (n_part <= 8192) {
-        k_stats_single<<<dim3(1), dim3(256), 0, st>>>(n_part, (unsigned long long)elems_per_part, err_sum, nnz, mask, th, near_tol, sd);
+        k_stats_single<<<dim3(1), dim3(256), 0, st>>>(n_part, geom, err_sum, nnz, mask, th, near_tol, sd);
     } else {
         k_stats_zero<<<dim3(1), dim3(64), 0, st>>>(sd);
         int64_t want = (n_part + 1023) / 1024;
         const int nb = (int)(want > 1024 ? 1024 : want);
-        k_stats_multi<<<dim3(nb), dim3(256), 0, st>>>(n_part, (unsigned long long)elems_per_part, err_sum, nnz, mask, th, near_tol, sd);
-        k_stats_finish<<<dim3(1), dim3(64), 0, st>>>(n_part, (unsigned long long)elems_per_part, sd);
+        k_stats_multi<<<dim3(nb), dim3(256), 0, st>>>(n_part, geom, err_sum, nnz, mask, th, near_tol, sd);
+        k_stats_finish<<<dim3(1), dim3(64), 0, st>>>(n_part, (unsigned long long)(geom.rows * geom.cols), sd);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_histogram_update(uint32_t* hist, const void* stats_dev, int clear, hipStream_t st) {
+    k_histogram_update<<<dim3(1), dim3(64), 0, st>>>(hist, static_cast<const StatsDev*>(stats_dev), clear);
     return hipGetLastError();
 }
 

@@ -17,12 +17,38 @@ struct KOut {
     uint8_t*  mask;
     float*    err5_sum;
     uint8_t*  e8m0;     // [P] biased exponents of the applied scales (GAM / E8M0 scaling), may be nullptr
-    uint32_t* gmant;    // [1] fraction bits of the group mantissa, may be nullptr
+    uint32_t* gmant;    // [2] fraction bits of the group mantissas (E4M3, E5M2), may be nullptr
+    float*    amin;     // [P] smallest non-zero magnitude of blocks that failed M_1 (three-way recipe), may be nullptr
+    uint16_t* fake;     // fake quantization: de-quantized BF16 output instead of the FP8 payload (then bf16 == fake
+    int64_t   ld_fake;  //   so that BF16 blocks pass through); nullptr otherwise
 };
 
 struct KShape {
     int64_t rows, cols, ld;
 };
+
+// Block grid of an operand: nominal block pr x pc, grid gr x gc (edge blocks smaller when ragged).
+struct StatsGeom {
+    int64_t rows, cols, pr, pc, gc;
+    int32_t uniform;        // 1: every block has pr * pc elements
+};
+enum { kGranTensor = 0, kGranSub = 1, kGranBlock = 2, kGranRow = 3, kGranCol = 4, kGranSubCol = 5, kGranBlock64 = 6 };
+inline StatsGeom make_geom(int gran, int64_t rows, int64_t cols) {
+    StatsGeom g{rows, cols, rows, cols, 1, 1};
+    switch (gran) {
+    case kGranSub:     g.pr = 1;   g.pc = 128; break;
+    case kGranBlock:   g.pr = 128; g.pc = 128; break;
+    case kGranRow:     g.pr = 1;   g.pc = cols; break;
+    case kGranCol:     g.pr = rows; g.pc = 1;  break;
+    case kGranSubCol:  g.pr = 128; g.pc = 1;   break;
+    case kGranBlock64: g.pr = 64;  g.pc = 64;  break;
+    default: break;
+    }
+    g.gc = (cols + g.pc - 1) / g.pc;
+    g.uniform = (rows % g.pr == 0 && cols % g.pc == 0) ? 1 : 0;
+    return g;
+}
+inline int64_t geom_parts(const StatsGeom& g) { return ((g.rows + g.pr - 1) / g.pr) * g.gc; }
 
 // Workspace layout for the passes that need one (all offsets 16-byte aligned).
 struct TensorPlan {
@@ -51,7 +77,8 @@ struct KProf {
 enum KernelId {
     kKernSub1x128 = 1, kKernBlock128 = 2, kKernTensorAmax = 3, kKernTensorQuant = 4, kKernTensorFinalize = 5,
     kKernFallbackCopy = 6, kKernScopeReduce = 7, kKernScopeDecide = 8, kKernScopeFillMask = 9,
-    kKernStatsPartial = 10, kKernStatsFinal = 11, kKernGroupAmax = 12, kKernGroupMantissa = 13
+    kKernStatsPartial = 10, kKernStatsFinal = 11, kKernGroupAmax = 12, kKernGroupMantissa = 13,
+    kKernTeamBlock = 14, kKernColumnTile = 15, kKernColumnCombine = 16
 };
 
 constexpr int kBatchMax = 64;     // operands per batch call
@@ -63,16 +90,28 @@ struct BatchItem {
     const uint16_t* x;
     int gran, crit, scope;
     int scaling;            // 0 FP32 amax, 1 GAM, 2 E8M0 only
+    int three;              // 1: type list [E4M3, E5M2, BF16]
+    int ragged;             // 1: edge blocks may be smaller
     float th;
     void* stats;            // device mor_stats* or nullptr
 };
 size_t batch_workspace_bytes(const BatchItem* items, int n);
 hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws, size_t ws_bytes, hipStream_t st, KProf* prof);
 
-hipError_t launch_dequantize(int gran, int64_t rows, int64_t cols, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
+// mor_partitions.hip: team kernels (64x64, per-channel rows, general 128x128) and column kernels
+int team_kind_of(const BatchItem& it);
+hipError_t launch_team_items(const BatchItem* items, const int* idx, int cnt, int kind, int crit, const uint32_t* const* gam_of,
+                             hipStream_t st, KProf* prof);
+hipError_t launch_subcol_items(const BatchItem* items, const int* idx, int cnt, int crit, const uint32_t* const* gam_of,
+                               hipStream_t st, KProf* prof);
+size_t column_workspace_bytes(int64_t rows, int64_t cols);
+hipError_t launch_channel_col(const BatchItem& it, const uint32_t* gam, void* ws, hipStream_t st, KProf* prof);
+
+hipError_t launch_dequantize(const StatsGeom& geom, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
                              const uint8_t* mask, const uint16_t* bf16, int64_t ld_bf16, uint16_t* y, int64_t ld_y,
                              const uint8_t* e8m0, const uint32_t* gmant, hipStream_t st);
-hipError_t launch_select_stats(int64_t n_part, int64_t elems_per_part, const float* err_sum, const uint32_t* nnz,
+hipError_t launch_select_stats(const StatsGeom& geom, const float* err_sum, const uint32_t* nnz,
                                const uint8_t* mask, float th, float near_tol, void* out_dev, hipStream_t st);
+hipError_t launch_histogram_update(uint32_t* hist, const void* stats_dev, int clear, hipStream_t st);
 
 }  // namespace mor

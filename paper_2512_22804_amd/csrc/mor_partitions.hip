@@ -1,0 +1,749 @@
+// Kernels for the further partitions of the MoR analyse-select-quantize path on gfx950 (MI355X):
+// 64 x 64 blocks, per-channel rows and columns, 128 x 1 sub-columns, ragged edges, the three-way
+// recipe [E4M3, E5M2, BF16] (Section 3.2) and the fake-quantization output (Section 4, Figure 4).
+//
+// "Team" kernels: a team of threads (a wave or a whole workgroup) owns one block and keeps it in
+// registers (8 x 16 bytes per lane), so one HBM pass computes amax, scale, codes, error sums and the
+// decision.  "Column" kernels: a workgroup owns a 128 x 128 tile whose 128 columns belong to 128
+// different blocks; a lane keeps the scalars of its 8 columns.
+#include <type_traits>
+
+#include "mor_device.h"
+#include "mor_launch.h"
+
+namespace mor {
+
+enum { kCritEq2 = 0, kCritEq3 = 1 };
+constexpr int kChunks = 8;     // 16-byte chunks per lane
+
+// ======================================================================================
+// Team kernels
+// ======================================================================================
+enum {
+    kTeamWg128 = 0,     // 128 x 128 block, one workgroup
+    kTeamWave64 = 1,    // 64 x 64 block, one wave; a workgroup takes the four blocks of a 128 x 128 tile
+    kTeamWaveRow = 2,   // one row of at most 4096 elements, one wave; four rows per workgroup
+    kTeamWgRow = 3      // one row of at most 16384 elements, one workgroup
+};
+constexpr int kMaxTeamGroup = 12;
+struct TeamOp {
+    const uint16_t* x;
+    KOut o;
+    int64_t ld, rows, cols;
+    int64_t units_x;        // 128-column tiles per row of tiles (block kinds)
+    float th;
+    uint8_t defer, mode, three, pad;
+    const uint32_t* gam;
+};
+struct GroupTeam {
+    int n;
+    int64_t unit_end[kMaxTeamGroup];
+    TeamOp op[kMaxTeamGroup];
+};
+struct TeamShared {
+    uint32_t u[4];
+    float f[8];
+};
+
+template <int TEAM> __device__ __forceinline__ constexpr bool team_is_wg() { return TEAM == kTeamWg128 || TEAM == kTeamWgRow; }
+
+// All-reduce over the team.  Workgroup teams combine the four wave results through LDS (every thread
+// of the workgroup must call); wave teams stay inside the wave.
+template <int TEAM>
+__device__ __forceinline__ uint32_t team_allmax(uint32_t v, TeamShared& sh) {
+    v = wave_allmax_u32(v);
+    if constexpr (team_is_wg<TEAM>()) {
+        if ((threadIdx.x & 63) == 0) sh.u[threadIdx.x >> 6] = v;
+        __syncthreads();
+        v = max(max(sh.u[0], sh.u[1]), max(sh.u[2], sh.u[3]));
+        __syncthreads();
+    }
+    return v;
+}
+template <int TEAM>
+__device__ __forceinline__ void team_allsum3(float& a, float& b, uint32_t& z, TeamShared& sh) {
+    a = wave_allsum_f32(a);
+    b = wave_allsum_f32(b);
+    z = wave_allsum_u32(z);
+    if constexpr (team_is_wg<TEAM>()) {
+        const int w = threadIdx.x >> 6;
+        if ((threadIdx.x & 63) == 0) { sh.f[w] = a; sh.f[4 + w] = b; sh.u[w] = z; }
+        __syncthreads();
+        a = (sh.f[0] + sh.f[1]) + (sh.f[2] + sh.f[3]);
+        b = (sh.f[4] + sh.f[5]) + (sh.f[6] + sh.f[7]);
+        z = (sh.u[0] + sh.u[1]) + (sh.u[2] + sh.u[3]);
+        __syncthreads();
+    }
+}
+
+template <int TEAM, int CRIT, bool FAKE>
+__device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamShared& sh) {
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const KOut& o = t.o;
+    // ---- geometry: block index p, origin (r0, c0), valid extent h x wd, this lane's chunk positions
+    int64_t p, r0, c0;
+    int h, wd, trow, tcol, rstep, cstep;
+    bool active = true, leader;
+    if constexpr (TEAM == kTeamWg128) {
+        const int64_t tr = unit / t.units_x, tc = unit - tr * t.units_x;
+        p = unit; r0 = tr * 128; c0 = tc * 128;
+        trow = tid >> 4; tcol = (tid & 15) * 8; rstep = 16; cstep = 0;
+        h = (int)(t.rows - r0 < 128 ? t.rows - r0 : 128); wd = (int)(t.cols - c0 < 128 ? t.cols - c0 : 128);
+        leader = tid == 0;
+    } else if constexpr (TEAM == kTeamWave64) {
+        const int64_t tr = unit / t.units_x, tc = unit - tr * t.units_x;
+        const int64_t gc = (t.cols + 63) / 64, gr = (t.rows + 63) / 64;
+        const int64_t br = 2 * tr + (w >> 1), bc = 2 * tc + (w & 1);
+        active = br < gr && bc < gc;
+        p = br * gc + bc; r0 = br * 64; c0 = bc * 64;
+        trow = lane >> 3; tcol = (lane & 7) * 8; rstep = 8; cstep = 0;
+        h = (int)(t.rows - r0 < 64 ? t.rows - r0 : 64); wd = (int)(t.cols - c0 < 64 ? t.cols - c0 : 64);
+        leader = lane == 0;
+    } else if constexpr (TEAM == kTeamWaveRow) {
+        p = unit * 4 + w; r0 = p; c0 = 0;
+        active = p < t.rows;
+        trow = 0; tcol = lane * 8; rstep = 0; cstep = 64 * 8;
+        h = 1; wd = (int)t.cols;
+        leader = lane == 0;
+    } else {
+        p = unit; r0 = p; c0 = 0;
+        trow = 0; tcol = tid * 8; rstep = 0; cstep = 256 * 8;
+        h = 1; wd = (int)t.cols;
+        leader = tid == 0;
+    }
+    if (!active) return;                                   // wave teams only: no barrier is skipped
+    const uint16_t* __restrict__ src = t.x + (r0 + trow) * t.ld + c0 + tcol;
+    const int64_t src_step = (int64_t)rstep * t.ld + cstep;
+    auto is_valid = [&](int i) -> bool { return (trow + i * rstep < h) && (tcol + i * cstep < wd); };
+    u32x4 raw[kChunks];
+#pragma unroll
+    for (int i = 0; i < kChunks; ++i) {
+        if (is_valid(i)) raw[i] = load16(src + i * src_step);
+        else { raw[i].x = 0u; raw[i].y = 0u; raw[i].z = 0u; raw[i].w = 0u; }
+    }
+    // ---- amax and zero count (chunks outside the tensor count as zeros and change nothing)
+    Scan8 sc{0u, 0u};
+#pragma unroll
+    for (int i = 0; i < kChunks; ++i) scan8(raw[i], sc);
+    const uint32_t abits = team_allmax<TEAM>(fold_max16(sc.amax2), sh);
+    const uint32_t mode = t.mode;
+    uint32_t mg = 0u, mg5 = 0u;
+    if (mode) { mg = t.gam[0]; mg5 = t.gam[1]; }
+    float s = block_scale(abits, kE4M3Max, mode, mg);
+    const float s5 = block_scale(abits, kE5M2Max, mode, mg5);
+    // ---- destinations
+    uint8_t* __restrict__ dst8 = FAKE ? nullptr : o.fp8 + (r0 + trow) * o.ld_fp8 + c0 + tcol;
+    const int64_t dst8_step = (int64_t)rstep * o.ld_fp8 + cstep;
+    uint16_t* __restrict__ dstf = FAKE ? o.fake + (r0 + trow) * o.ld_fake + c0 + tcol : nullptr;
+    const int64_t dstf_step = (int64_t)rstep * o.ld_fake + cstep;
+    const bool fast = abits < fast_amax_limit(mode);
+    // quantizes the block with scale `sc_` for format E5M2 ? E5M2 : E4M3; returns this lane's error sum
+    auto quantize = [&](auto fmt, float sc_, bool emit) -> float {
+        constexpr bool E5 = decltype(fmt)::value;
+        const float s_inv = FAKE ? 1.0f / sc_ : 0.0f;        // correctly rounded IEEE division
+        float e0 = 0.0f, e1 = 0.0f;
+        if (fast) {
+#pragma unroll
+            for (int i = 0; i < kChunks; ++i) {
+                u32x4 deq;
+                const u32x2 codes = quant8_fast_deq<E5, FAKE>(raw[i], sc_, s_inv, e0, e1, deq);
+                if (emit && is_valid(i)) {
+                    if constexpr (FAKE) store16(dstf + i * dstf_step, deq);
+                    else store8(dst8 + i * dst8_step, codes);
+                }
+            }
+        } else {
+#pragma clang loop unroll(disable)
+            for (int i = 0; i < kChunks; ++i)
+                if (is_valid(i))
+                    e0 += quant8_careful_mem<E5>(src + i * src_step, sc_, emit && !FAKE ? dst8 + i * dst8_step : nullptr,
+                                                 emit && FAKE ? dstf + i * dstf_step : nullptr, s_inv);
+        }
+        return e0 + e1;
+    };
+    float err = quantize(std::false_type{}, s, true);
+    float err5 = 0.0f;
+    if constexpr (CRIT == kCritEq3) err5 = quantize(std::true_type{}, s5, false);
+    uint32_t zeros = fold_add16(sc.zero2);
+    team_allsum3<TEAM>(err, err5, zeros, sh);
+    constexpr uint32_t kTeamElems = (team_is_wg<TEAM>() ? 256u : 64u) * kChunks * 8u;
+    const uint32_t nnz = kTeamElems - zeros;
+    if (abits >= kInfBits) { err = __builtin_inff(); err5 = __builtin_inff(); }
+    const bool defer = t.defer != 0;
+    uint32_t mask = defer ? 0u : ((CRIT == kCritEq3) ? decide_eq3(err, err5) : decide_eq2(err, nnz, t.th));
+    // ---- three-way recipe: a block that failed M_1 is kept in E5M2 if its dynamic range fits (Eq. 4)
+    uint32_t amin_bits = 0u;
+    if (t.three && mask == 1u) {                           // uniform over the team
+        uint32_t mn2 = 0xFFFFFFFFu;
+#pragma unroll
+        for (int i = 0; i < kChunks; ++i) mn2 = min_nonzero_m1(raw[i], mn2);
+        const uint32_t mn = ~team_allmax<TEAM>(~fold_min16(mn2), sh) & 0xFFFFu;
+        amin_bits = nnz ? mn + 1u : 0u;
+        if (range_fits_e5m2(abits, amin_bits, nnz)) {
+            mask = 2u;
+            s = s5;
+            (void)quantize(std::true_type{}, s5, true);    // the E5M2 payload replaces the E4M3 one
+        }
+    }
+    if (leader) {
+        o.scale[p] = s;
+        o.amax[p] = __uint_as_float(abits << 16);
+        o.err_sum[p] = err;
+        o.nnz[p] = nnz;
+        if constexpr (CRIT == kCritEq3) o.err5_sum[p] = err5;
+        if (!defer) o.mask[p] = (uint8_t)mask;
+        if (mode != kScaleFp32 && o.e8m0) o.e8m0[p] = (uint8_t)(__float_as_uint(s) >> 23);
+        if (t.three && o.amin) o.amin[p] = __uint_as_float(amin_bits << 16);
+    }
+    if (mask == 1u && o.bf16) {                            // BF16: the block stays as it is
+        uint16_t* __restrict__ dbf = o.bf16 + (r0 + trow) * o.ld_bf16 + c0 + tcol;
+        const int64_t dbf_step = (int64_t)rstep * o.ld_bf16 + cstep;
+#pragma unroll
+        for (int i = 0; i < kChunks; ++i)
+            if (is_valid(i)) store16(dbf + i * dbf_step, raw[i]);
+    }
+}
+
+template <int TEAM, int CRIT>
+__global__ __launch_bounds__(256) void k_team_group(GroupTeam g) {
+    __shared__ TeamShared sh;
+    const int op = group_find(g.unit_end, g.n, blockIdx.x);
+    const TeamOp& t = g.op[op];
+    const int64_t unit = (int64_t)blockIdx.x - (op ? g.unit_end[op - 1] : 0);
+    if (t.o.fake) team_block<TEAM, CRIT, true>(t, unit, sh);
+    else team_block<TEAM, CRIT, false>(t, unit, sh);
+}
+
+// ======================================================================================
+// Column kernels: 128 x 1 sub-columns (Section 3: "sub-columns"; the transposed operands of the
+// backward GEMMs, Section 4) and per-channel columns (Section 4.1.1 "Per-Channel", second operand).
+// A workgroup sweeps a strip of 128-row x 128-column tiles; a lane holds 8 rows x 8 columns of a tile
+// and keeps per-column scalars.  Per-channel columns span all strips, so they take three passes:
+//   kColAmax      column amax of the strip                     -> workspace partials
+//   (combine)     column amax, scales                          -> outputs + workspace scales
+//   kColExternal  quantize with those scales, strip error sums -> workspace partials
+//   (combine)     column error sums, decision, fallback columns
+// 128 x 1 sub-columns are complete inside a tile (kColLocal): one pass.
+// ======================================================================================
+enum { kColLocal = 0, kColAmax = 1, kColExternal = 2 };
+struct ColOp {
+    const uint16_t* x;
+    KOut o;
+    int64_t ld, rows, cols;
+    int64_t tiles_x;            // 128-column strips
+    int32_t tiles_per_strip;    // 128-row tiles a workgroup sweeps (1 for kColLocal)
+    float th;
+    uint8_t defer, mode, pad0, pad1;
+    const uint32_t* gam;
+    // per-channel columns: workspace, [n_strips x cols_padded] each, cols_padded = tiles_x * 128
+    uint16_t* part_amax;
+    float* part_err; float* part_err5; uint16_t* part_zero;
+    const float* col_scale; const float* col_scale5;     // [cols_padded]
+};
+struct GroupCol {
+    int n;
+    int64_t unit_end[kMaxTeamGroup];
+    ColOp op[kMaxTeamGroup];
+};
+struct ColShared {
+    uint32_t amax[4][16][4];     // packed per-column maxima: wave, lane column group, 4 words (8 columns)
+    float scale[128], scale5[128];
+    float err[4][128], err5[4][128];
+    uint32_t zero[4][16][4];     // packed per-column zero counts
+    uint16_t abits[128];         // column amax patterns of the tile
+    uint8_t mask[128];
+};
+
+// Combines a lane's 8 per-column values with the lanes that hold the same columns in the other row groups
+// of the wave (lane ^ 16, lane ^ 32).
+__device__ __forceinline__ uint32_t colgroup_max2(uint32_t v) {
+    v = pk_max_u16(v, (uint32_t)__shfl_xor((int)v, 16, 64));
+    return pk_max_u16(v, (uint32_t)__shfl_xor((int)v, 32, 64));
+}
+__device__ __forceinline__ uint32_t colgroup_add2(uint32_t v) {
+    v = pk_add_u16(v, (uint32_t)__shfl_xor((int)v, 16, 64));
+    return pk_add_u16(v, (uint32_t)__shfl_xor((int)v, 32, 64));
+}
+__device__ __forceinline__ float colgroup_addf(float v) {
+    v += __shfl_xor(v, 16, 64);
+    return v + __shfl_xor(v, 32, 64);
+}
+
+template <int CRIT, int MODE, bool FAKE>
+__device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShared& sh) {
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, cg = tid & 15;
+    const KOut& o = t.o;
+    const int64_t strip = unit / t.tiles_x, tc = unit - strip * t.tiles_x;
+    const int64_t c0 = tc * 128, col = c0 + cg * 8;
+    const bool col_ok = col < t.cols;
+    const int64_t cols_padded = t.tiles_x * 128;
+    const uint32_t mode = t.mode;
+    uint32_t mg = 0u, mg5 = 0u;
+    if (mode) { mg = t.gam[0]; mg5 = t.gam[1]; }
+    // strip-level accumulators (per-channel columns); for kColLocal a strip is one tile
+    uint32_t amax2[4] = {0u, 0u, 0u, 0u}, zero2[4] = {0u, 0u, 0u, 0u};
+    float err[8], err5[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { err[k] = 0.0f; err5[k] = 0.0f; }
+    float s[8], s5[8], s_inv[8];
+    uint32_t col_abits[8];
+    bool strip_fast = true;
+    if constexpr (MODE == kColExternal) {
+        bool f = true;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            s[k] = t.col_scale[c0 + cg * 8 + k];
+            s5[k] = CRIT == kCritEq3 ? t.col_scale5[c0 + cg * 8 + k] : 0.0f;
+            s_inv[k] = FAKE ? 1.0f / s[k] : 0.0f;
+            col_abits[k] = col_ok ? __float_as_uint(o.amax[col + k]) >> 16 : 0u;
+            f = f && col_abits[k] < fast_amax_limit(mode);
+        }
+        strip_fast = __syncthreads_and(f ? 1 : 0) != 0;
+    }
+    for (int tt = 0; tt < t.tiles_per_strip; ++tt) {
+        const int64_t r0 = (strip * t.tiles_per_strip + tt) * 128;
+        if (r0 >= t.rows) break;                                       // uniform over the workgroup
+        const int64_t row = r0 + (tid >> 4);
+        const uint16_t* __restrict__ src = t.x + row * t.ld + col;
+        auto is_valid = [&](int i) -> bool { return col_ok && row + i * 16 < t.rows; };
+        u32x4 raw[kChunks];
+#pragma unroll
+        for (int i = 0; i < kChunks; ++i) {
+            if (is_valid(i)) raw[i] = load16(src + (int64_t)i * 16 * t.ld);
+            else { raw[i].x = 0u; raw[i].y = 0u; raw[i].z = 0u; raw[i].w = 0u; }
+        }
+        if constexpr (MODE != kColExternal) {
+#pragma unroll
+            for (int i = 0; i < kChunks; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) amax2[j] = pk_max_u16(amax2[j], raw[i][j] & 0x7FFF7FFFu);
+        }
+        if constexpr (MODE == kColAmax) continue;
+        if constexpr (MODE == kColLocal) {
+            // column amax of the tile: row groups of the wave, then the four waves through LDS
+#pragma unroll
+            for (int j = 0; j < 4; ++j) amax2[j] = colgroup_max2(amax2[j]);
+            if (lane < 16) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sh.amax[w][cg][j] = amax2[j];
+            }
+            __syncthreads();
+            if (tid < 128) {                                           // thread tid owns column tid of the tile
+                const int g16 = tid >> 3, k = tid & 7;
+                uint32_t a = 0u;
+#pragma unroll
+                for (int ww = 0; ww < 4; ++ww) a = max(a, (sh.amax[ww][g16][k >> 1] >> ((k & 1) * 16)) & 0xFFFFu);
+                sh.scale[tid] = block_scale(a, kE4M3Max, mode, mg);
+                sh.scale5[tid] = block_scale(a, kE5M2Max, mode, mg5);
+                sh.abits[tid] = (uint16_t)a;
+            }
+            __syncthreads();
+            bool f = true;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                s[k] = sh.scale[cg * 8 + k];
+                s5[k] = sh.scale5[cg * 8 + k];
+                s_inv[k] = FAKE ? 1.0f / s[k] : 0.0f;
+                col_abits[k] = sh.abits[cg * 8 + k];
+                f = f && col_abits[k] < fast_amax_limit(mode);
+            }
+            strip_fast = __syncthreads_and(f ? 1 : 0) != 0;
+        }
+        // ---- quantize the tile with the per-column scales
+        uint8_t* __restrict__ dst8 = FAKE ? nullptr : o.fp8 + row * o.ld_fp8 + col;
+        uint16_t* __restrict__ dstf = FAKE ? o.fake + row * o.ld_fake + col : nullptr;
+#pragma unroll
+        for (int i = 0; i < kChunks; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) zero2[j] = pk_add_u16(zero2[j], pk_is_zero_u16(raw[i][j] & 0x7FFF7FFFu));
+        if (strip_fast) {
+#pragma unroll
+            for (int i = 0; i < kChunks; ++i) {
+                u32x4 deq;
+                const u32x2 codes = quant8_cols<false, FAKE>(raw[i], s, s_inv, err, deq);
+                if (is_valid(i)) {
+                    if constexpr (FAKE) store16(dstf + (int64_t)i * 16 * o.ld_fake, deq);
+                    else store8(dst8 + (int64_t)i * 16 * o.ld_fp8, codes);
+                }
+                if constexpr (CRIT == kCritEq3) { u32x4 d5; (void)quant8_cols<true, false>(raw[i], s5, s_inv, err5, d5); }
+            }
+        } else {
+            // some column of the strip has amax >= 2^24..2^25 or is non-finite: element-wise careful path
+#pragma clang loop unroll(disable)
+            for (int i = 0; i < kChunks; ++i) {
+                if (!is_valid(i)) continue;
+                const uint32_t* src32 = reinterpret_cast<const uint32_t*>(src + (int64_t)i * 16 * t.ld);
+                uint32_t cw[2] = {0u, 0u};
+                uint32_t dq[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t wv = src32[j];
+                    const uint32_t c_lo = quant1_careful<false>(wv & 0xFFFFu, s[2 * j], err[2 * j]);
+                    const uint32_t c_hi = quant1_careful<false>(wv >> 16, s[2 * j + 1], err[2 * j + 1]);
+                    cw[j >> 1] |= (c_lo | (c_hi << 8)) << ((j & 1) * 16);
+                    if constexpr (FAKE) {
+                        const f32x2 q = cvt_pk_f32<false>((int)(c_lo | (c_hi << 8)), false);
+                        dq[j] = f32_to_bf16_rne(q.x * s_inv[2 * j]) | (f32_to_bf16_rne(q.y * s_inv[2 * j + 1]) << 16);
+                    }
+                    if constexpr (CRIT == kCritEq3) {
+                        (void)quant1_careful<true>(wv & 0xFFFFu, s5[2 * j], err5[2 * j]);
+                        (void)quant1_careful<true>(wv >> 16, s5[2 * j + 1], err5[2 * j + 1]);
+                    }
+                }
+                if constexpr (FAKE) { u32x4 d; d.x = dq[0]; d.y = dq[1]; d.z = dq[2]; d.w = dq[3]; store16(dstf + (int64_t)i * 16 * o.ld_fake, d); }
+                else { u32x2 c; c.x = cw[0]; c.y = cw[1]; store8(dst8 + (int64_t)i * 16 * o.ld_fp8, c); }
+            }
+        }
+        if constexpr (MODE == kColLocal) {
+            // ---- per-column error sums / zero counts of the tile, decision, metadata, fallback columns
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                err[k] = colgroup_addf(err[k]);
+                if constexpr (CRIT == kCritEq3) err5[k] = colgroup_addf(err5[k]);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) zero2[j] = colgroup_add2(zero2[j]);
+            if (lane < 16) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) { sh.err[w][cg * 8 + k] = err[k]; if constexpr (CRIT == kCritEq3) sh.err5[w][cg * 8 + k] = err5[k]; }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sh.zero[w][cg][j] = zero2[j];
+            }
+            __syncthreads();
+            if (tid < 128) {
+                const int g16 = tid >> 3, k = tid & 7;
+                const uint32_t a = sh.abits[tid];
+                float e = (sh.err[0][tid] + sh.err[1][tid]) + (sh.err[2][tid] + sh.err[3][tid]);
+                float e5 = 0.0f;
+                if constexpr (CRIT == kCritEq3) e5 = (sh.err5[0][tid] + sh.err5[1][tid]) + (sh.err5[2][tid] + sh.err5[3][tid]);
+                uint32_t z = 0u;
+#pragma unroll
+                for (int ww = 0; ww < 4; ++ww) z += (sh.zero[ww][g16][k >> 1] >> ((k & 1) * 16)) & 0xFFFFu;
+                const uint32_t nnz = 128u - z;
+                if (a >= kInfBits) { e = __builtin_inff(); e5 = e; }
+                const bool defer = t.defer != 0;
+                const uint32_t mk = defer ? 0u : ((CRIT == kCritEq3) ? decide_eq3(e, e5) : decide_eq2(e, nnz, t.th));
+                sh.mask[tid] = (uint8_t)mk;
+                if (c0 + tid < t.cols) {
+                    const int64_t p = (r0 >> 7) * t.cols + c0 + tid;
+                    o.scale[p] = sh.scale[tid];
+                    o.amax[p] = __uint_as_float(a << 16);
+                    o.err_sum[p] = e;
+                    o.nnz[p] = nnz;
+                    if constexpr (CRIT == kCritEq3) o.err5_sum[p] = e5;
+                    if (!defer) o.mask[p] = (uint8_t)mk;
+                    if (mode != kScaleFp32 && o.e8m0) o.e8m0[p] = (uint8_t)(__float_as_uint(sh.scale[tid]) >> 23);
+                }
+            }
+            __syncthreads();
+            if (o.bf16) {
+                const uint64_t mk8 = *reinterpret_cast<const uint64_t*>(&sh.mask[cg * 8]);
+                if (mk8) {                                             // some of this lane's columns stay in BF16
+#pragma clang loop unroll(disable)
+                    for (int i = 0; i < kChunks; ++i) {
+                        if (!is_valid(i)) continue;
+                        const uint16_t* sp = src + (int64_t)i * 16 * t.ld;
+                        uint16_t* dp = o.bf16 + (row + i * 16) * o.ld_bf16 + col;
+                        for (int k = 0; k < 8; ++k)
+                            if ((mk8 >> (8 * k)) & 0xFFu) dp[k] = sp[k];
+                    }
+                }
+            }
+            __syncthreads();
+            // reset the per-tile accumulators (a strip of kColLocal is a single tile anyway)
+#pragma unroll
+            for (int k = 0; k < 8; ++k) { err[k] = 0.0f; err5[k] = 0.0f; }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { amax2[j] = 0u; zero2[j] = 0u; }
+        }
+    }
+    // ---- per-channel columns: publish the strip's partials
+    if constexpr (MODE == kColAmax) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) amax2[j] = colgroup_max2(amax2[j]);
+        if (lane < 16) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) sh.amax[w][cg][j] = amax2[j];
+        }
+        __syncthreads();
+        if (tid < 128) {
+            const int g16 = tid >> 3, k = tid & 7;
+            uint32_t a = 0u;
+#pragma unroll
+            for (int ww = 0; ww < 4; ++ww) a = max(a, (sh.amax[ww][g16][k >> 1] >> ((k & 1) * 16)) & 0xFFFFu);
+            t.part_amax[strip * cols_padded + c0 + tid] = (uint16_t)a;
+        }
+    }
+    if constexpr (MODE == kColExternal) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            err[k] = colgroup_addf(err[k]);
+            if constexpr (CRIT == kCritEq3) err5[k] = colgroup_addf(err5[k]);
+        }
+        // per-lane zero counts: at most 8 per tile and column, 16 tiles per strip -> fit 16 bits after the wave sum (<= 512)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) zero2[j] = colgroup_add2(zero2[j]);
+        if (lane < 16) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) { sh.err[w][cg * 8 + k] = err[k]; if constexpr (CRIT == kCritEq3) sh.err5[w][cg * 8 + k] = err5[k]; }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) sh.zero[w][cg][j] = zero2[j];
+        }
+        __syncthreads();
+        if (tid < 128) {
+            const int g16 = tid >> 3, k = tid & 7;
+            uint32_t z = 0u;
+#pragma unroll
+            for (int ww = 0; ww < 4; ++ww) z += (sh.zero[ww][g16][k >> 1] >> ((k & 1) * 16)) & 0xFFFFu;
+            const int64_t idx = strip * cols_padded + c0 + tid;
+            t.part_err[idx] = (sh.err[0][tid] + sh.err[1][tid]) + (sh.err[2][tid] + sh.err[3][tid]);
+            if constexpr (CRIT == kCritEq3) t.part_err5[idx] = (sh.err5[0][tid] + sh.err5[1][tid]) + (sh.err5[2][tid] + sh.err5[3][tid]);
+            t.part_zero[idx] = (uint16_t)z;
+        }
+    }
+}
+
+template <int CRIT, int MODE>
+__global__ __launch_bounds__(256) void k_col_group(GroupCol g) {
+    __shared__ ColShared sh;
+    const int op = group_find(g.unit_end, g.n, blockIdx.x);
+    const ColOp& t = g.op[op];
+    const int64_t unit = (int64_t)blockIdx.x - (op ? g.unit_end[op - 1] : 0);
+    if (MODE != kColAmax && t.o.fake) col_strip<CRIT, MODE, true>(t, unit, sh);
+    else col_strip<CRIT, MODE, false>(t, unit, sh);
+}
+
+// Per-channel columns, first combine: column amax over the strips -> amax, scale (Algorithm 1), E8M0 byte.
+__global__ __launch_bounds__(256) void k_col_scales(ColOp t, int n_strips, float* __restrict__ col_scale, float* __restrict__ col_scale5) {
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t cols_padded = t.tiles_x * 128;
+    if (c >= cols_padded) return;
+    uint32_t a = 0u;
+    for (int sidx = 0; sidx < n_strips; ++sidx) a = max(a, (uint32_t)t.part_amax[sidx * cols_padded + c]);
+    uint32_t mg = 0u, mg5 = 0u;
+    if (t.mode) { mg = t.gam[0]; mg5 = t.gam[1]; }
+    const float s = block_scale(a, kE4M3Max, t.mode, mg);
+    col_scale[c] = s;
+    col_scale5[c] = block_scale(a, kE5M2Max, t.mode, mg5);
+    if (c < t.cols) {
+        t.o.amax[c] = __uint_as_float(a << 16);
+        t.o.scale[c] = s;
+        if (t.mode != kScaleFp32 && t.o.e8m0) t.o.e8m0[c] = (uint8_t)(__float_as_uint(s) >> 23);
+    }
+}
+// Second combine: column error sums over the strips (binary64, fixed order), non-zero counts, decision.
+template <int CRIT>
+__global__ __launch_bounds__(256) void k_col_finish(ColOp t, int n_strips) {
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t cols_padded = t.tiles_x * 128;
+    if (c >= t.cols) return;
+    double e = 0.0, e5 = 0.0;
+    unsigned long long z = 0;
+    for (int sidx = 0; sidx < n_strips; ++sidx) {
+        e += (double)t.part_err[sidx * cols_padded + c];
+        z += t.part_zero[sidx * cols_padded + c];
+        if constexpr (CRIT == kCritEq3) e5 += (double)t.part_err5[sidx * cols_padded + c];
+    }
+    // rows beyond the tensor were loaded as zeros: padded rows = strips * tiles_per_strip * 128
+    const unsigned long long padded = (unsigned long long)((t.rows + 127) / 128) * 128ull;
+    const unsigned long long n = padded - z;
+    const uint32_t abits = __float_as_uint(t.o.amax[c]) >> 16;
+    if (abits >= kInfBits) { e = (double)__builtin_inff(); e5 = e; }
+    t.o.err_sum[c] = (float)e;
+    t.o.nnz[c] = n > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)n;
+    if constexpr (CRIT == kCritEq3) t.o.err5_sum[c] = (float)e5;
+    if (!t.defer) {
+        uint32_t mk;
+        if constexpr (CRIT == kCritEq3) mk = (e < e5) ? 0u : 1u;
+        else mk = ((n ? e / (double)n : 0.0) < (double)t.th) ? 0u : 1u;
+        t.o.mask[c] = (uint8_t)mk;
+    }
+}
+// Columns kept in BF16 are copied (2-byte elements; a rare path).
+__global__ __launch_bounds__(256) void k_col_fallback(ColOp t) {
+    const int64_t c = (int64_t)blockIdx.x * 64 + (threadIdx.x & 63);
+    if (c >= t.cols || t.o.mask[c] != 1u) return;
+    for (int64_t r = (int64_t)blockIdx.y * 4 + (threadIdx.x >> 6); r < t.rows; r += (int64_t)gridDim.y * 4)
+        t.o.bf16[r * t.o.ld_bf16 + c] = t.x[r * t.ld + c];
+}
+
+// ======================================================================================
+// Launchers
+// ======================================================================================
+namespace {
+struct ProfScope2 {
+    KProf* prof; hipStream_t st; int slot;
+    ProfScope2(KProf* p, int kernel_id, hipStream_t s) : prof(p), st(s), slot(-1) {
+        if (prof && prof->count < prof->capacity && prof->count < kProfMax) {
+            slot = prof->count++;
+            prof->kernel[slot] = kernel_id;
+            (void)hipEventRecord(prof->start[slot], st);
+        }
+    }
+    ~ProfScope2() { if (slot >= 0) (void)hipEventRecord(prof->stop[slot], st); }
+};
+size_t align16p(size_t v) { return (v + 15) & ~(size_t)15; }
+
+template <int TEAM>
+void launch_team_kind(const GroupTeam& g, int64_t total, int crit, hipStream_t st) {
+    if (crit == kCritEq3) k_team_group<TEAM, kCritEq3><<<dim3((unsigned)total), dim3(256), 0, st>>>(g);
+    else k_team_group<TEAM, kCritEq2><<<dim3((unsigned)total), dim3(256), 0, st>>>(g);
+}
+}  // namespace
+
+int team_kind_of(const BatchItem& it) {
+    switch (it.gran) {
+    case kGranBlock: return kTeamWg128;
+    case kGranBlock64: return kTeamWave64;
+    case kGranRow: return it.sh.cols <= 4096 ? kTeamWaveRow : kTeamWgRow;
+    default: return -1;
+    }
+}
+
+// All operands of `items` (indices idx[0..cnt)) that share one team kind and criterion, in groups.
+hipError_t launch_team_items(const BatchItem* items, const int* idx, int cnt, int kind, int crit, const uint32_t* const* gam_of,
+                             hipStream_t st, KProf* prof) {
+    static_assert(sizeof(GroupTeam) <= 3800 && sizeof(GroupCol) <= 3800, "kernel-argument segment is 4 KB");
+    GroupTeam g; g.n = 0;
+    int64_t total = 0;
+    auto flush = [&]() {
+        if (g.n == 0) return;
+        ProfScope2 ps(prof, kKernTeamBlock, st);
+        switch (kind) {
+        case kTeamWg128: launch_team_kind<kTeamWg128>(g, total, crit, st); break;
+        case kTeamWave64: launch_team_kind<kTeamWave64>(g, total, crit, st); break;
+        case kTeamWaveRow: launch_team_kind<kTeamWaveRow>(g, total, crit, st); break;
+        default: launch_team_kind<kTeamWgRow>(g, total, crit, st); break;
+        }
+        g.n = 0; total = 0;
+    };
+    for (int k = 0; k < cnt; ++k) {
+        const BatchItem& it = items[idx[k]];
+        int64_t units;
+        TeamOp& t = g.op[g.n];
+        t.units_x = (it.sh.cols + 127) / 128;
+        if (kind == kTeamWg128 || kind == kTeamWave64) units = ((it.sh.rows + 127) / 128) * t.units_x;
+        else if (kind == kTeamWaveRow) units = (it.sh.rows + 3) / 4;
+        else units = it.sh.rows;
+        if (units > 0x7FFFFFFF) return hipErrorInvalidValue;
+        if (total + units > 0x7FFFFFFF) { flush(); }
+        TeamOp& u = g.op[g.n];
+        u.x = it.x; u.o = it.o; u.ld = it.sh.ld; u.rows = it.sh.rows; u.cols = it.sh.cols;
+        u.units_x = (it.sh.cols + 127) / 128;
+        u.th = it.th; u.defer = it.scope == 1; u.mode = (uint8_t)it.scaling; u.three = (uint8_t)it.three; u.pad = 0;
+        u.gam = gam_of[idx[k]];
+        total += units;
+        g.unit_end[g.n] = total;
+        if (++g.n == kMaxTeamGroup) flush();
+    }
+    flush();
+    return hipGetLastError();
+}
+
+// ---- column kinds
+namespace {
+struct ColPlan {
+    int32_t tiles_per_strip;
+    int n_strips;
+    int64_t cols_padded;
+    size_t off_amax, off_err, off_err5, off_zero, off_scale, off_scale5, bytes;
+};
+ColPlan plan_columns(int64_t rows, int64_t cols) {
+    ColPlan pl;
+    const int64_t tiles_x = (cols + 127) / 128, tiles_y = (rows + 127) / 128;
+    int64_t per = (tiles_x * tiles_y + 4095) / 4096;      // keep at least ~4096 workgroups when the operand is large
+    if (per < 1) per = 1;
+    if (per > 16) per = 16;                               // 16-bit zero counters: 16 tiles x 128 rows
+    pl.tiles_per_strip = (int32_t)per;
+    pl.n_strips = (int)((tiles_y + per - 1) / per);
+    pl.cols_padded = tiles_x * 128;
+    const size_t n = (size_t)pl.n_strips * (size_t)pl.cols_padded;
+    size_t off = 0;
+    pl.off_amax = off; off = align16p(off + 2 * n);
+    pl.off_err = off; off = align16p(off + 4 * n);
+    pl.off_err5 = off; off = align16p(off + 4 * n);
+    pl.off_zero = off; off = align16p(off + 2 * n);
+    pl.off_scale = off; off = align16p(off + 4 * (size_t)pl.cols_padded);
+    pl.off_scale5 = off; off = align16p(off + 4 * (size_t)pl.cols_padded);
+    pl.bytes = off;
+    return pl;
+}
+void fill_col_op(ColOp& t, const BatchItem& it, const uint32_t* gam) {
+    t = ColOp{};
+    t.x = it.x; t.o = it.o; t.ld = it.sh.ld; t.rows = it.sh.rows; t.cols = it.sh.cols;
+    t.tiles_x = (it.sh.cols + 127) / 128;
+    t.tiles_per_strip = 1;
+    t.th = it.th; t.defer = it.scope == 1; t.mode = (uint8_t)it.scaling;
+    t.gam = gam;
+}
+template <int MODE>
+void launch_col_kind(const GroupCol& g, int64_t total, int crit, hipStream_t st) {
+    if (crit == kCritEq3) k_col_group<kCritEq3, MODE><<<dim3((unsigned)total), dim3(256), 0, st>>>(g);
+    else k_col_group<kCritEq2, MODE><<<dim3((unsigned)total), dim3(256), 0, st>>>(g);
+}
+}  // namespace
+
+size_t column_workspace_bytes(int64_t rows, int64_t cols) { return plan_columns(rows, cols).bytes; }
+
+// 128 x 1 sub-columns: grouped, one pass.
+hipError_t launch_subcol_items(const BatchItem* items, const int* idx, int cnt, int crit, const uint32_t* const* gam_of,
+                               hipStream_t st, KProf* prof) {
+    GroupCol g; g.n = 0;
+    int64_t total = 0;
+    auto flush = [&]() {
+        if (g.n == 0) return;
+        ProfScope2 ps(prof, kKernColumnTile, st);
+        launch_col_kind<kColLocal>(g, total, crit, st);
+        g.n = 0; total = 0;
+    };
+    for (int k = 0; k < cnt; ++k) {
+        const BatchItem& it = items[idx[k]];
+        const int64_t units = ((it.sh.rows + 127) / 128) * ((it.sh.cols + 127) / 128);
+        if (units > 0x7FFFFFFF) return hipErrorInvalidValue;
+        if (total + units > 0x7FFFFFFF) flush();
+        fill_col_op(g.op[g.n], it, gam_of[idx[k]]);
+        total += units;
+        g.unit_end[g.n] = total;
+        if (++g.n == kMaxTeamGroup) flush();
+    }
+    flush();
+    return hipGetLastError();
+}
+
+// Per-channel columns: one operand, five launches (amax, scales, quantize, finish, fallback columns).
+hipError_t launch_channel_col(const BatchItem& it, const uint32_t* gam, void* ws, hipStream_t st, KProf* prof) {
+    const ColPlan pl = plan_columns(it.sh.rows, it.sh.cols);
+    char* w = static_cast<char*>(ws);
+    GroupCol g; g.n = 1;
+    ColOp& t = g.op[0];
+    fill_col_op(t, it, gam);
+    t.tiles_per_strip = pl.tiles_per_strip;
+    t.part_amax = reinterpret_cast<uint16_t*>(w + pl.off_amax);
+    t.part_err = reinterpret_cast<float*>(w + pl.off_err);
+    t.part_err5 = reinterpret_cast<float*>(w + pl.off_err5);
+    t.part_zero = reinterpret_cast<uint16_t*>(w + pl.off_zero);
+    float* col_scale = reinterpret_cast<float*>(w + pl.off_scale);
+    float* col_scale5 = reinterpret_cast<float*>(w + pl.off_scale5);
+    t.col_scale = col_scale; t.col_scale5 = col_scale5;
+    const int64_t total = (int64_t)pl.n_strips * t.tiles_x;
+    if (total > 0x7FFFFFFF) return hipErrorInvalidValue;
+    g.unit_end[0] = total;
+    { ProfScope2 ps(prof, kKernColumnTile, st); launch_col_kind<kColAmax>(g, total, kCritEq2, st); }
+    const unsigned cb = (unsigned)((pl.cols_padded + 255) / 256);
+    { ProfScope2 ps(prof, kKernColumnCombine, st); k_col_scales<<<dim3(cb), dim3(256), 0, st>>>(t, pl.n_strips, col_scale, col_scale5); }
+    { ProfScope2 ps(prof, kKernColumnTile, st); launch_col_kind<kColExternal>(g, total, it.crit, st); }
+    {
+        ProfScope2 ps(prof, kKernColumnCombine, st);
+        if (it.crit == kCritEq3) k_col_finish<kCritEq3><<<dim3(cb), dim3(256), 0, st>>>(t, pl.n_strips);
+        else k_col_finish<kCritEq2><<<dim3(cb), dim3(256), 0, st>>>(t, pl.n_strips);
+    }
+    if (it.o.bf16 && it.scope != 1) {
+        ProfScope2 ps(prof, kKernFallbackCopy, st);
+        int64_t gy = (it.sh.rows + 3) / 4;
+        if (gy > 256) gy = 256;
+        k_col_fallback<<<dim3((unsigned)((it.sh.cols + 63) / 64), (unsigned)gy), dim3(256), 0, st>>>(t);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace mor

@@ -29,12 +29,21 @@ def u16(t: torch.Tensor) -> np.ndarray:
     return t.cpu().numpy().view(np.uint16)
 
 
+def block_map(gran: str, rows: int, cols: int) -> np.ndarray:
+    """(rows, cols) array of block numbers, row-major over the block grid (edge blocks smaller)."""
+    pr, pc = {"tensor": (rows, cols), "sub1x128": (1, 128), "block128": (128, 128), "channel_row": (1, cols),
+              "channel_col": (rows, 1), "sub128x1": (128, 1), "block64": (64, 64)}[gran]
+    gc = -(-cols // pc)
+    return (np.arange(rows)[:, None] // pr) * gc + (np.arange(cols)[None, :] // pc)
+
+
 def run_gpu(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "mean_rel_err", threshold: float = 0.045,
-            cols: int | None = None, want_bf16: bool = True, scaling: str = "fp32_amax"):
+            cols: int | None = None, want_bf16: bool = True, scaling: str = "fp32_amax", formats: str = "e4m3|bf16",
+            ragged: bool = False):
     """xb: (rows, ld) uint16.  Returns (params, MorResult) with outputs still on the device."""
     rows, ld = xb.shape
     cols = ld if cols is None else cols
-    params = B.make_params(rows, cols, gran, scope, crit, threshold, ld=ld, scaling=scaling)
+    params = B.make_params(rows, cols, gran, scope, crit, threshold, ld=ld, scaling=scaling, formats=formats, ragged=ragged)
     x = to_dev(xb)
     out = B.alloc_outputs(params, x.device, want_bf16=want_bf16, bf16_fill=FILL)
     B.mor_analyze_quantize(params, x, out)
@@ -43,34 +52,45 @@ def run_gpu(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "me
 
 
 def compare(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "mean_rel_err", threshold: float = 0.045,
-            cols: int | None = None, label: str = "", scaling: str = "fp32_amax") -> dict:
+            cols: int | None = None, label: str = "", scaling: str = "fp32_amax", formats: str = "e4m3|bf16",
+            ragged: bool = False) -> dict:
     rows, ld = xb.shape
     cols = ld if cols is None else cols
     print(f"[parity] {label} shape={rows}x{cols} ld={ld} gran={gran} scope={scope} crit={crit} th={threshold} "
-          f"scaling={scaling}", flush=True)
-    params, g = run_gpu(xb, gran, scope, crit, threshold, cols, scaling=scaling)
-    a = O.analyze_quantize(xb, gran, scope, crit, threshold, bf16_fill=FILL, ld=ld, cols=cols, scaling=scaling)
+          f"scaling={scaling} formats={formats} ragged={ragged}", flush=True)
+    params, g = run_gpu(xb, gran, scope, crit, threshold, cols, scaling=scaling, formats=formats, ragged=ragged)
+    a = O.analyze_quantize(xb, gran, scope, crit, threshold, bf16_fill=FILL, ld=ld, cols=cols, scaling=scaling,
+                           formats=formats, ragged=ragged)
     P = a.mask.size
-    if scaling != "fp32_amax":      # stored form of the scales: one E8M0 byte per block, one 23-bit mantissa
-        assert np.array_equal(g.scale_e8m0.cpu().numpy(), a.e8m0), "E8M0 exponents differ"
-        assert int(g.group_mantissa.cpu().numpy().view(np.uint32)[0]) == a.group_mantissa, "group mantissa differs"
-
+    three = formats != "e4m3|bf16"
+    bmap = block_map(gran, rows, cols)
+    g_mask = g.mask.cpu().numpy()
+    agree = g_mask == a.mask                # with three types, payload and scale follow the choice
     g_amax = g.amax.cpu().numpy(); g_scale = g.scale.cpu().numpy()
     assert np.array_equal(g_amax.view(np.uint32), a.amax.view(np.uint32)), "amax differs"
-    assert np.array_equal(g_scale.view(np.uint32), a.scale.view(np.uint32)), "scale differs"
+    assert np.array_equal(g_scale.view(np.uint32)[agree], a.scale.view(np.uint32)[agree]), "scale differs"
+    if scaling != "fp32_amax":      # stored form of the scales: one E8M0 byte per block, shared 23-bit mantissas
+        assert np.array_equal(g.scale_e8m0.cpu().numpy()[agree], a.e8m0[agree]), "E8M0 exponents differ"
+        gm = g.group_mantissa.cpu().numpy().view(np.uint32)
+        assert int(gm[0]) == a.group_mantissa and int(gm[1]) == a.group_mantissa5, "group mantissa differs"
     g_fp8 = g.fp8.cpu().numpy()
-    if not np.array_equal(g_fp8, a.fp8):
-        bad = np.argwhere(g_fp8 != a.fp8)
+    same = agree[bmap]
+    if not np.array_equal(g_fp8[same], a.fp8[same]):
+        bad = np.argwhere((g_fp8 != a.fp8) & same)
         r, c = bad[0]
         raise AssertionError(f"fp8 differs at {len(bad)} elements, first ({r},{c}): gpu {g_fp8[r, c]:#x} oracle "
                              f"{a.fp8[r, c]:#x} x={xb[r, c]:#06x}")
     g_nnz = g.nnz.cpu().numpy().view(np.uint32)
     assert np.array_equal(g_nnz, a.nnz), "nnz differs"
+    if three:                                 # smallest non-zero magnitude of the blocks that failed M_1
+        failed = (a.mask != 0) & (g_mask != 0)
+        assert np.array_equal(g.amin.cpu().numpy().view(np.uint32)[failed], a.amin.view(np.uint32)[failed]), "amin differs"
 
     def check_err(ge, oe, what):
         ge = ge.astype(np.float64)
         both_inf = np.isinf(ge) & np.isinf(oe)
-        diff = np.abs(ge - oe)
+        with np.errstate(invalid="ignore"):
+            diff = np.abs(ge - oe)
         diff[both_inf] = 0.0
         ok = diff <= REL_TOL * np.abs(oe)
         metric = np.where(a.nnz > 0, oe / np.maximum(a.nnz, 1), 0.0)
@@ -87,31 +107,71 @@ def compare(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "me
         f5, r5 = check_err(g.err5_sum.cpu().numpy(), a.err5_sum, "err5_sum")
         n_floor += f5; max_rel = max(max_rel, r5)
 
-    g_mask = g.mask.cpu().numpy()
-    # blocks (or the tensor) where the decision may legitimately differ
+    # blocks (or the tensor) where the M_1 decision may legitimately differ
     if scope == "tensor":
         es, e5, n = a.err_sum.sum(), a.err5_sum.sum(), a.nnz.sum()
         es, e5, n = np.full(P, es), np.full(P, e5), np.full(P, n)
     else:
         es, e5, n = a.err_sum, a.err5_sum, a.nnz
     if crit == "e4m3_vs_e5m2":
-        near = np.abs(es - e5) <= REL_TOL * np.maximum(es, e5)
+        with np.errstate(invalid="ignore"):
+            near = np.abs(es - e5) <= REL_TOL * np.maximum(es, e5)
     else:
         with np.errstate(invalid="ignore"):
             metric = np.where(n > 0, es / np.maximum(n, 1), 0.0)
         near = np.abs(metric - np.float32(threshold)) <= REL_TOL * np.float32(threshold)
-    mism = g_mask != a.mask
+    mism = ~agree
     assert not (mism & ~near).any(), f"mask differs in {(mism & ~near).sum()} blocks away from the threshold"
-    assert set(np.unique(g_mask)) <= {0, 1}
+    assert not (mism & (g_mask != 0) & (a.mask != 0)).any(), "E5M2 / BF16 choice (Eq. 4) differs"
+    assert set(np.unique(g_mask)) <= ({0, 1, 2} if three else {0, 1})
 
     # BF16 payload: input bits exactly where the GPU's own mask says BF16, untouched elsewhere
     g_bf16 = u16(g.bf16)
-    pr, pc = {"tensor": (rows, cols), "sub1x128": (1, 128), "block128": (128, 128)}[gran]
-    m2 = np.repeat(np.repeat(g_mask.reshape(rows // pr, cols // pc), pr, axis=0), pc, axis=1).astype(bool)
+    m2 = g_mask[bmap] == 1
     xin = xb[:, :cols]
     assert np.array_equal(g_bf16[m2], xin[m2]), "BF16 fallback payload differs from the input"
     assert np.all(g_bf16[~m2] == FILL), "BF16 buffer written outside fallback blocks"
     if not mism.any():
         assert np.array_equal(g_bf16, a.bf16)
-    return {"P": P, "n_bf16": int(g_mask.sum()), "n_near": int(near.sum()), "n_mask_mismatch_near": int(mism.sum()),
-            "n_floor": n_floor, "max_rel_err": max_rel, "gpu": g, "oracle": a, "params": params}
+    return {"P": P, "n_bf16": int((g_mask == 1).sum()), "n_e5m2": int((g_mask == 2).sum()), "n_near": int(near.sum()),
+            "n_mask_mismatch_near": int(mism.sum()), "n_floor": n_floor, "max_rel_err": max_rel, "gpu": g, "oracle": a,
+            "params": params}
+
+
+def compare_fake(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "mean_rel_err", threshold: float = 0.045,
+                 cols: int | None = None, label: str = "", scaling: str = "fp32_amax", formats: str = "e4m3|bf16",
+                 ragged: bool = False) -> dict:
+    """mor_fake_quantize against the oracle's fake-quantized tensor, and against the library's own
+    analyze + de-quantize pair (which must give the same bits)."""
+    rows, ld = xb.shape
+    cols = ld if cols is None else cols
+    print(f"[parity-fake] {label} shape={rows}x{cols} ld={ld} gran={gran} scope={scope} crit={crit} th={threshold} "
+          f"scaling={scaling} formats={formats} ragged={ragged}", flush=True)
+    params = B.make_params(rows, cols, gran, scope, crit, threshold, ld=ld, scaling=scaling, formats=formats, ragged=ragged)
+    x = to_dev(xb)
+    meta = B.alloc_outputs(params, x.device, want_bf16=False, want_fp8=False)
+    y = torch.full((rows, cols), FILL if FILL < 0x8000 else FILL - 0x10000, dtype=torch.int16, device=x.device)
+    B.mor_fake_quantize(params, x, y, meta)
+    torch.cuda.synchronize()
+    a = O.analyze_quantize(xb, gran, scope, crit, threshold, ld=ld, cols=cols, scaling=scaling, formats=formats,
+                           ragged=ragged, want_fake=True)
+    g_mask = meta.mask.cpu().numpy()
+    assert np.array_equal(meta.amax.cpu().numpy().view(np.uint32), a.amax.view(np.uint32)), "amax differs"
+    assert np.array_equal(meta.nnz.cpu().numpy().view(np.uint32), a.nnz), "nnz differs"
+    agree = g_mask == a.mask
+    same = agree[block_map(gran, rows, cols)]
+    gy = u16(y)
+    if not np.array_equal(gy[same], a.fake[same]):
+        bad = np.argwhere((gy != a.fake) & same)
+        r, c = bad[0]
+        raise AssertionError(f"fake-quantized tensor differs at {len(bad)} elements, first ({r},{c}): gpu {gy[r, c]:#06x} "
+                             f"oracle {a.fake[r, c]:#06x} x={xb[r, c]:#06x}")
+    # the analyse + de-quantize pair of the library gives the same tensor
+    _, g = run_gpu(xb, gran, scope, crit, threshold, cols, scaling=scaling, formats=formats, ragged=ragged)
+    y2 = torch.full_like(y, 0x1111)
+    B.mor_dequantize(params, g.fp8, g.scale, g.mask, g.bf16, y2)
+    torch.cuda.synchronize()
+    assert torch.equal(g.mask, meta.mask) and torch.equal(y2, y), "fake quantization differs from analyse + de-quantize"
+    assert torch.equal(g.err_sum, meta.err_sum) and torch.equal(g.scale, meta.scale)
+    return {"n_mismatch": int((~agree).sum()), "n_bf16": int((g_mask == 1).sum()), "n_e5m2": int((g_mask == 2).sum()), "y": y,
+            "meta": meta, "oracle": a}

@@ -32,9 +32,10 @@ def test_exports_every_declared_symbol(B):
 
 
 def test_struct_layouts(B):
-    assert C.sizeof(B.MorStats) == 128
-    assert C.sizeof(B.MorParams) == 48
-    assert C.sizeof(B.MorOutputs) == 96
+    assert C.sizeof(B.MorStats) == 144 == B.STATS_BYTES
+    assert C.sizeof(B.MorParams) == 56
+    assert C.sizeof(B.MorOutputs) == 104
+    assert C.sizeof(B.MorProfile) == 8 + 16 * 8 * 2 + 16 * 4
 
 
 def test_num_partitions(B):
@@ -48,6 +49,16 @@ def test_num_partitions(B):
     assert B.mor_num_partitions("tensor", 3, 12) == -1
     assert B.mor_num_partitions("tensor", 0, 128) == -1
     assert B.mor_num_partitions(9, 128, 128) == -1
+    assert B.mor_num_partitions("channel_row", 8192, 4096) == 8192
+    assert B.mor_num_partitions("channel_row", 8, 16392) == -1               # rows longer than 16384 elements
+    assert B.mor_num_partitions("channel_col", 8192, 4096) == 4096
+    assert B.mor_num_partitions("sub128x1", 8192, 4096) == 64 * 4096
+    assert B.mor_num_partitions("sub128x1", 100, 4096) == -1
+    assert B.mor_num_partitions("block64", 8192, 14336) == 128 * 224
+    assert B.mor_params_num_partitions(B.make_params(130, 200, "block64", ragged=True)) == 3 * 4
+    assert B.mor_params_num_partitions(B.make_params(130, 200, "block64")) == -1
+    assert B.mor_params_num_partitions(B.make_params(130, 204, "block64", ragged=True)) == -1   # 16-byte rows
+    assert B.mor_params_num_partitions(B.make_params(3, 136, "sub1x128", ragged=True)) == 6
 
 
 def test_workspace_bytes(B):
@@ -57,6 +68,10 @@ def test_workspace_bytes(B):
     t = B.mor_workspace_bytes(B.make_params(8192, 14336, "tensor"))
     assert 0 < t < (1 << 22) and t % 16 == 0
     assert B.mor_workspace_bytes(B.make_params(8192, 100, "sub1x128")) == 0      # invalid -> 0
+    assert B.mor_workspace_bytes(B.make_params(8192, 4096, "channel_row")) == 0
+    assert B.mor_workspace_bytes(B.make_params(8192, 4096, "block64")) == 0
+    c = B.mor_workspace_bytes(B.make_params(8192, 4096, "channel_col"))
+    assert 0 < c < (1 << 23) and c % 16 == 0
 
 
 def test_status_strings(B):

@@ -50,8 +50,8 @@ def test_batch_equals_single_calls(oracle):
         x = parity.to_dev(xb)
         out_b = B.alloc_outputs(params, dev, bf16_fill=parity.FILL)
         out_s = B.alloc_outputs(params, dev, bf16_fill=parity.FILL)
-        st_b = torch.full((128,), 0xEE, dtype=torch.uint8, device=dev)
-        st_s = torch.full((128,), 0xEE, dtype=torch.uint8, device=dev)
+        st_b = torch.full((B.STATS_BYTES,), 0xEE, dtype=torch.uint8, device=dev)
+        st_s = torch.full((B.STATS_BYTES,), 0xEE, dtype=torch.uint8, device=dev)
         entries.append((params, x, out_b, st_b))
         singles.append((params, x, out_s, st_s))
         keep.append((name, xb, gran, scope, crit, cols))

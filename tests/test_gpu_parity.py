@@ -210,7 +210,11 @@ def test_argument_errors(P):
     assert status(B.make_params(128, 256, "sub1x128", ld=128)) == 2    # ld < cols
     assert status(B.make_params(128, 256, "sub1x128", ld=260)) == 3    # ld % 8
     assert status(B.make_params(128, 256, 7)) == 4
-    assert status(B.make_params(128, 256, "sub1x128", formats=B.MOR_FMT_E4M3 | B.MOR_FMT_E5M2 | B.MOR_FMT_BF16)) == 4
+    assert status(B.make_params(128, 256, "sub1x128", formats=B.MOR_FMT_E4M3 | B.MOR_FMT_E5M2)) == 4     # no BF16 at the end
+    assert status(B.make_params(128, 256, "sub1x128", formats=B.MOR_FMT_E4M3)) == 4
+    bad_flags = B.make_params(128, 256, "sub1x128"); bad_flags.flags = 2
+    assert status(bad_flags) == 4
+    assert status(B.make_params(128, 260, "sub1x128", ld=264, ragged=True)) == 2                       # cols % 8
     assert status(B.make_params(128, 256, "sub1x128", scaling=3)) == 4
     assert status(B.make_params(128, 256, "sub1x128", crit=5)) == 4
     assert status(B.make_params(128, 256, "sub1x128"), xx=x.view(-1)[1:]) == 3   # misaligned input
@@ -248,7 +252,7 @@ def test_select_stats_parity(P, oracle, gran, shape):
     err32 = a.err_sum.astype(np.float32)
     want = oracle.select_stats(err32, a.nnz, a.mask, shape[0], shape[1], gran, threshold=TH, near_tol=1e-2)
     params = B.make_params(shape[0], shape[1], gran, threshold=TH)
-    out = torch.full((128,), 0xFF, dtype=torch.uint8, device="cuda")
+    out = torch.full((B.STATS_BYTES,), 0xFF, dtype=torch.uint8, device="cuda")
     for _ in range(2):                                        # second call must fully overwrite the first
         B.mor_select_stats(params, torch.from_numpy(err32).cuda(), torch.from_numpy(a.nnz.view(np.int32)).cuda(),
                            torch.from_numpy(a.mask).cuda(), 1e-2, out)
@@ -265,7 +269,7 @@ def test_select_stats_handworked(P):
     err = np.array([0.0, 0.63, 0.64, 5.75, 5.76, 7.04, 7.05, 100.0, 0.0, np.inf], dtype=np.float32)
     nnz = np.array([128, 128, 128, 128, 128, 128, 128, 128, 0, 128], dtype=np.int32)
     mask = np.array([0, 0, 0, 0, 1, 1, 1, 1, 0, 1], dtype=np.uint8)
-    out = torch.zeros(128, dtype=torch.uint8, device="cuda")
+    out = torch.zeros(B.STATS_BYTES, dtype=torch.uint8, device="cuda")
     B.mor_select_stats(B.make_params(10, 128, "sub1x128", threshold=TH), torch.from_numpy(err).cuda(),
                        torch.from_numpy(nnz).cuda(), torch.from_numpy(mask).cuda(), 1e-3, out)
     got = B.read_stats(out)

@@ -1,0 +1,288 @@
+"""GPU parity tests of the further rows: three-way selection with an E5M2 payload, per-channel rows and
+columns, 128 x 1 sub-columns, 64 x 64 blocks, ragged edges, fake quantization and the running
+histogram.  The HIP library is called through its C ABI and compared with the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_22804_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TH = 0.045
+THREE = "e4m3|e5m2|bf16"
+NEW_GRANS = ["channel_row", "channel_col", "sub128x1", "block64"]
+ALL_GRANS = ["tensor", "sub1x128", "block128"] + NEW_GRANS
+
+
+@pytest.fixture(scope="module")
+def P():
+    import parity
+    from paper_2512_22804_amd import binding as B
+    B.load()
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return parity
+
+
+def wide_operand(seed, rows, cols):
+    """Blocks of 128 columns of three kinds: well-behaved, wide (E4M3 flushes, E5M2 holds), very wide."""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((rows, cols)).astype(np.float32) * np.exp2(rng.integers(-4, 4, size=(rows, 1))).astype(np.float32)
+    kind = rng.integers(0, 3, size=(rows, -(-cols // 128)))
+    k = np.repeat(kind, 128, axis=1)[:, :cols]
+    tail = (np.arange(cols) % 128) >= 16
+    x[(k == 1) & tail] *= np.float32(2.0 ** -22)
+    very = (k == 2) & tail
+    x[very] *= np.exp2(rng.integers(-40, -20, size=int(very.sum()))).astype(np.float32)
+    x[rng.random((rows, cols)) < 0.05] = 0.0
+    return W.f32_to_bf16_bits(x)
+
+
+def all_patterns():
+    return np.arange(65536, dtype=np.uint32).astype(np.uint16)
+
+
+# ------------------------------------------------------------------ new partitions
+
+@pytest.mark.parametrize("gran", NEW_GRANS)
+@pytest.mark.parametrize("scope", ["partition", "tensor"])
+@pytest.mark.parametrize("crit", ["mean_rel_err", "e4m3_vs_e5m2"])
+def test_new_partitions_reduced_workloads(P, gran, scope, crit):
+    cases = {"act": W.activation(384, 1024, W.seed_for(2)), "weight": W.weight(384, 512, W.seed_for(3)),
+             "grad": W.gradient(256, 1792, W.seed_for(4)), "grad_half": W.gradient(384, 768, W.seed_for(4, 1), tiny_half=True),
+             "wide": wide_operand(7, 256, 640)}
+    for name, xb in cases.items():
+        P.compare(xb, gran, scope, crit, TH, label=name)
+
+
+@pytest.mark.parametrize("gran", NEW_GRANS)
+@pytest.mark.parametrize("order", ["natural", "shuffled", "small_shuffled"])
+def test_new_partitions_all_bf16_patterns(P, gran, order):
+    x = all_patterns()
+    rng = np.random.default_rng(3)
+    if order == "shuffled":
+        x = rng.permutation(x)
+    elif order == "small_shuffled":
+        x = rng.permutation(np.where((x & 0x7FFF) >= 0x4B80, (x & 0x807F) | 0x3F00, x))   # amax < 2^25
+    xb = x.reshape(256, 256)
+    if gran in ("channel_col", "sub128x1") and order == "natural":
+        xb = np.ascontiguousarray(xb.T)                      # narrow ranges along the columns
+    for crit in ("mean_rel_err", "e4m3_vs_e5m2"):
+        P.compare(xb, gran, crit=crit, threshold=TH, label=f"patterns-{order}")
+
+
+@pytest.mark.parametrize("gran", NEW_GRANS)
+@pytest.mark.parametrize("scaling", ["gam", "e8m0"])
+def test_new_partitions_gam_scaling(P, gran, scaling):
+    xb = wide_operand(11, 256, 512)
+    P.compare(xb, gran, threshold=TH, scaling=scaling, label="gam")
+    P.compare(xb, gran, scope="tensor", crit="e4m3_vs_e5m2", scaling=scaling, label="gam-eq3-tensor")
+
+
+@pytest.mark.parametrize("gran", NEW_GRANS)
+def test_new_partitions_padded_leading_dimension(P, gran):
+    xb = W.gradient(256, 640, 99, tiny_half=True)
+    r = P.compare(xb, gran, threshold=TH, cols=512, label="strided")
+    dense = P.compare(np.ascontiguousarray(xb[:, :512]), gran, threshold=TH, label="dense-of-strided")
+    assert torch.equal(r["gpu"].fp8, dense["gpu"].fp8) and torch.equal(r["gpu"].mask, dense["gpu"].mask)
+
+
+@pytest.mark.parametrize("cols", [8, 128, 1000, 4096, 4104, 14336, 16384])
+def test_channel_row_widths(P, cols):
+    """Rows handled by one wave (up to 4096 elements) and by one workgroup (up to 16384)."""
+    xb = W.activation(37, cols, cols)
+    P.compare(xb, "channel_row", threshold=TH, label="row-width")
+    P.compare(xb, "channel_row", crit="e4m3_vs_e5m2", formats=THREE, label="row-width-three")
+
+
+def test_channel_col_many_strips(P):
+    """Enough rows that a workgroup sweeps several 128-row tiles per strip and several strips exist."""
+    rows, cols = 8192 + 40, 8192                               # 65 x 64 tiles: two tiles per strip, 33 strips
+    xb = W.activation(rows, cols, 5)
+    rng = np.random.default_rng(5)
+    x = W.bf16_bits_to_f32(xb)
+    bad_cols = rng.choice(cols, size=300, replace=False)
+    hit = rng.random((rows, 300)) < 0.06
+    sub = x[:, bad_cols]
+    sub[hit] *= np.float32(2.0 ** -24)                         # 6 % of these columns flush to zero -> BF16
+    x[:, bad_cols] = sub
+    xb = W.f32_to_bf16_bits(x)
+    r = P.compare(xb, "channel_col", threshold=TH, label="col-strips", ragged=True)
+    assert 250 <= r["n_bf16"] < 400
+    P.compare(xb, "channel_col", scope="tensor", crit="e4m3_vs_e5m2", label="col-strips-tensor")
+
+
+# ------------------------------------------------------------------ ragged edges
+
+@pytest.mark.parametrize("gran", ["sub1x128", "block128", "block64", "sub128x1", "channel_col", "channel_row", "tensor"])
+@pytest.mark.parametrize("rows,cols", [(130, 200), (64, 136), (257, 128), (5, 8), (300, 1032)])
+def test_ragged_edges(P, gran, rows, cols):
+    xb = wide_operand(rows * 7 + cols, rows, cols)
+    for crit in ("mean_rel_err", "e4m3_vs_e5m2"):
+        P.compare(xb, gran, crit=crit, threshold=TH, ragged=True, label="ragged")
+    P.compare(xb, gran, scope="tensor", threshold=TH, ragged=True, label="ragged-tensor-scope")
+    P.compare_fake(xb, gran, threshold=TH, ragged=True, label="ragged-fake")
+
+
+def test_ragged_needs_the_flag(P):
+    from paper_2512_22804_amd import binding as B
+    xb = W.activation(130, 200, 1)
+    with pytest.raises(B.MorError) as e:
+        P.run_gpu(xb, "block64")
+    assert e.value.status == 2
+
+
+# ------------------------------------------------------------------ three-way selection
+
+@pytest.mark.parametrize("gran", ["sub1x128", "block128", "block64", "channel_row"])
+@pytest.mark.parametrize("crit", ["e4m3_vs_e5m2", "mean_rel_err"])
+@pytest.mark.parametrize("scaling", ["fp32_amax", "gam", "e8m0"])
+def test_three_way(P, gran, crit, scaling):
+    xb = wide_operand(21, 256, 512)
+    xb[3, :128] = 0                                        # an empty block of 1 x 128
+    xb[5, 7] = 0x7F80                                      # a non-finite value
+    r = P.compare(xb, gran, crit=crit, threshold=TH, formats=THREE, scaling=scaling, label="three-way")
+    if gran == "sub1x128":
+        assert r["n_e5m2"] > 10 and r["n_bf16"] > 10
+    # de-quantizing from what was emitted reproduces the oracle's de-quantization (E5M2 blocks decode as E5M2)
+    from paper_2512_22804_amd import binding as B
+    from oracle import mor_oracle as O
+    g, a = r["gpu"], r["oracle"]
+    if np.array_equal(g.mask.cpu().numpy(), a.mask):
+        y = torch.empty_like(g.bf16)
+        B.mor_dequantize(r["params"], g.fp8, g.scale, g.mask, g.bf16, y)
+        torch.cuda.synchronize()
+        assert np.array_equal(P.u16(y), O.dequantize(a.fp8, a.scale, a.mask, a.bf16, gran))
+        if scaling != "fp32_amax":
+            y2 = torch.empty_like(g.bf16)
+            B.mor_dequantize_e8m0(r["params"], g.fp8, g.scale_e8m0, g.group_mantissa, g.mask, g.bf16, y2)
+            torch.cuda.synchronize()
+            assert torch.equal(y, y2)
+
+
+def test_three_way_handworked(P):
+    def blk(vals):
+        v = np.zeros(128, dtype=np.float32); v[:len(vals)] = vals
+        return W.f32_to_bf16_bits(v)
+    rows = [blk([1.0] + [2.0 ** -20] * 127),                       # E4M3 flushes, E5M2 exact -> E5M2
+            blk([1.0] + [2.0 ** -30] * 127),                       # range 2^30 does not fit -> BF16
+            blk([1.75] + [2.0 ** -29] * 100),                      # ratio exactly 57344 * 2^14 -> BF16
+            blk([1.75] + [2.0 ** -29 * (1 + 2.0 ** -7)] * 100),    # one BF16 step inside -> E5M2
+            blk([]),                                               # no non-zero element -> Eq. 3 ties, Eq. 4 passes -> E5M2
+            blk([1.0] * 128),                                      # both exact: tie -> E5M2
+            blk([448.0, 144.0, -36.0, 18.0])]                      # 1.125 * 2^k needs the third mantissa bit -> E4M3
+    xb = np.stack(rows * 19)[:128]
+    r = P.compare(xb, "sub1x128", crit="e4m3_vs_e5m2", formats=THREE, label="three-handworked")
+    g = r["gpu"]
+    assert g.mask[:7].tolist() == [2, 1, 1, 2, 2, 2, 0]
+    assert g.scale[0].item() == 57344.0 and g.fp8[0, 0].item() == 0x7B and g.fp8[0, 1].item() == 0x2B
+    P.compare(xb, "block128", crit="e4m3_vs_e5m2", formats=THREE, label="three-handworked-block")
+
+
+def test_three_way_all_patterns(P):
+    x = np.random.default_rng(5).permutation(all_patterns())
+    x = np.where((x & 0x7FFF) >= 0x7F80, x & 0x80FF, x)            # finite, full dynamic range
+    for gran in ("sub1x128", "block64"):
+        for crit in ("e4m3_vs_e5m2", "mean_rel_err"):
+            P.compare(x.reshape(256, 256), gran, crit=crit, formats=THREE, label="three-patterns")
+    sorted_x = np.sort(all_patterns() & 0x7FFF).astype(np.uint16)  # narrow blocks, incl. Inf/NaN blocks at the end
+    P.compare(sorted_x.reshape(512, 128), "sub1x128", crit="e4m3_vs_e5m2", formats=THREE, label="three-sorted")
+
+
+def test_three_way_unsupported_combinations(P):
+    from paper_2512_22804_amd import binding as B
+    xb = W.activation(128, 256, 1)
+    for gran, scope in (("tensor", "partition"), ("channel_col", "partition"), ("sub128x1", "partition"), ("sub1x128", "tensor")):
+        with pytest.raises(B.MorError) as e:
+            P.run_gpu(xb, gran, scope=scope, crit="e4m3_vs_e5m2", formats=THREE)
+        assert e.value.status == 4
+
+
+# ------------------------------------------------------------------ fake quantization
+
+@pytest.mark.parametrize("gran", ALL_GRANS)
+@pytest.mark.parametrize("scope", ["partition", "tensor"])
+def test_fake_quantize(P, gran, scope):
+    for name, xb in (("grad_half", W.gradient(384, 768, W.seed_for(4, 1), tiny_half=True)), ("act", W.activation(256, 1024, 2)),
+                     ("wide", wide_operand(3, 256, 640))):
+        r = P.compare_fake(xb, gran, scope=scope, threshold=TH, label=name)
+        assert r["n_mismatch"] == 0
+    P.compare_fake(wide_operand(4, 256, 512), gran, scope=scope, crit="e4m3_vs_e5m2", scaling="gam", label="fake-gam-eq3")
+
+
+@pytest.mark.parametrize("gran", ["sub1x128", "block128", "block64", "channel_row"])
+def test_fake_quantize_three_way(P, gran):
+    r = P.compare_fake(wide_operand(9, 256, 512), gran, crit="e4m3_vs_e5m2", formats=THREE, label="fake-three")
+    if gran == "sub1x128":
+        assert r["n_e5m2"] > 10
+
+
+@pytest.mark.parametrize("gran", ALL_GRANS)
+def test_fake_quantize_all_patterns_and_strides(P, gran):
+    x = np.random.default_rng(1).permutation(all_patterns())
+    P.compare_fake(x.reshape(256, 256), gran, label="fake-patterns")
+    small = np.where((x & 0x7FFF) >= 0x4B80, (x & 0x807F) | 0x3F00, x)
+    P.compare_fake(small.reshape(256, 256), gran, label="fake-small-patterns")
+    xb = W.gradient(256, 640, 99, tiny_half=True)
+    P.compare_fake(xb, gran, cols=512, label="fake-strided")
+
+
+def test_fake_quantize_per_tensor_fallback_proven_and_not(P):
+    """Per-tensor operands on both sides of the flush-count proof: the output must be the input when BF16 wins."""
+    for frac in (0.0, 0.03, 0.047, 0.2):
+        rng = np.random.default_rng(int(frac * 1e4) + 3)
+        x = np.exp2(rng.uniform(-3.0, 3.0, size=(512, 1024))).astype(np.float32)
+        tiny = rng.random(x.shape) < frac
+        x[tiny] = np.float32(2.0 ** -40)
+        xb = W.f32_to_bf16_bits(x)
+        r = P.compare_fake(xb, "tensor", threshold=TH, label=f"fake-flush-{frac}")
+        if frac >= 0.047:
+            assert r["n_bf16"] == 1 and np.array_equal(P.u16(r["y"]), xb)
+
+
+# ------------------------------------------------------------------ statistics and histogram
+
+def test_stats_with_e5m2_and_ragged(P, oracle):
+    from paper_2512_22804_amd import binding as B
+    xb = wide_operand(31, 300, 1032)
+    for gran, formats, crit in (("sub1x128", THREE, "e4m3_vs_e5m2"), ("block64", THREE, "e4m3_vs_e5m2"), ("sub128x1", "e4m3|bf16", "mean_rel_err")):
+        a = oracle.analyze_quantize(xb, gran, crit=crit, threshold=TH, formats=formats, ragged=True)
+        err32 = a.err_sum.astype(np.float32)
+        want = oracle.select_stats(err32, a.nnz, a.mask, 300, 1032, gran, threshold=TH, near_tol=1e-2, ragged=True)
+        params = B.make_params(300, 1032, gran, crit=crit, threshold=TH, formats=formats, ragged=True)
+        out = torch.full((B.STATS_BYTES,), 0xFF, dtype=torch.uint8, device="cuda")
+        B.mor_select_stats(params, torch.from_numpy(err32).cuda(), torch.from_numpy(a.nnz.view(np.int32)).cuda(),
+                           torch.from_numpy(a.mask).cuda(), 1e-2, out)
+        got = B.read_stats(out)
+        for k in ("n_part", "n_fp8_part", "n_bf16_part", "n_e5m2_part", "n_elem_fp8", "n_elem_bf16", "n_elem_e5m2", "nnz_total",
+                  "n_near_threshold", "hist"):
+            assert got[k] == want[k], (gran, k, got[k], want[k])
+        # the batch call produces the same record
+        x = P.to_dev(xb)
+        res = B.alloc_outputs(params, x.device)
+        st = torch.zeros(B.STATS_BYTES, dtype=torch.uint8, device="cuda")
+        items = B.make_batch([(params, x, res, st)])
+        ws = torch.empty(max(16, B.mor_batch_workspace_bytes(items)), dtype=torch.uint8, device="cuda")
+        B.mor_analyze_quantize_batch(items, 1e-2, ws)
+        torch.cuda.synchronize()
+        got2 = B.read_stats(st)
+        if np.array_equal(res.mask.cpu().numpy(), a.mask):
+            for k in ("n_part", "n_fp8_part", "n_bf16_part", "n_e5m2_part", "n_elem_fp8", "n_elem_bf16", "n_elem_e5m2", "nnz_total"):
+                assert got2[k] == want[k], (gran, k, got2[k], want[k])
+
+
+def test_histogram_update(P, oracle):
+    import ctypes as C
+    from paper_2512_22804_amd import binding as B
+    metrics = [0.0, 0.0049, 0.005, 0.0225, 0.0449, 0.045, 0.0549, 0.055, 0.3, float("inf"), 0.012, 0.012, 0.012, 0.0301]
+    hist = torch.full((12,), 99, dtype=torch.int32, device="cuda")
+    want = np.full(12, 99, dtype=np.uint32)
+    for step, m in enumerate(metrics):
+        st = B.MorStats()
+        st.mean_err = m
+        dev = torch.frombuffer(bytearray(bytes(st)), dtype=torch.uint8).cuda()
+        B.mor_histogram_update(hist, dev, step, 6)
+        oracle.histogram_update(want, np.float32(m), step, 6)
+        torch.cuda.synchronize()
+        assert np.array_equal(hist.cpu().numpy().view(np.uint32), want), (step, m)
+    assert want.sum() == len(metrics) - 12                     # cleared at steps 0, 6 and 12
