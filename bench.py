@@ -38,7 +38,7 @@ def algorithmic_bytes(kernel: str, n_elem: int, n_part: int, fallback_frac: floa
     """Bytes the method must move for one launch of `kernel` over an operand of n_elem elements.  `fused`: the
     per-tensor quantize pass also wrote the BF16 fallback (its decision was proven by the amax pass), so the
     copy pass moved nothing."""
-    if kernel in ("sub1x128", "block128"):
+    if kernel in ("sub1x128", "team_block"):
         return 2.0 * n_elem + n_elem + 2.0 * fallback_frac * n_elem + META_BYTES * n_part
     if kernel == "tensor_amax":
         return 2.0 * n_elem
@@ -51,7 +51,113 @@ def algorithmic_bytes(kernel: str, n_elem: int, n_part: int, fallback_frac: floa
     return 0.0
 
 
-KERNEL_GRAN = {"sub1x128": "sub1x128", "block128": "block128", "tensor_amax": "tensor", "tensor_quant": "tensor",
+def run_variants(ops, B, torch, dev, steps, log):
+    """Times the further rows of the path on the same twelve operands: the paper's own tensor-level recipe
+    (GAM scaling, one decision per tensor) at three partitions, E8M0 scales, the three-way recipe, 64 x 64 blocks,
+    128 x 1 sub-columns, per-channel columns, fake quantization and de-quantization.  Each entry: ms per pass over
+    all twelve operands, GB/s of BF16 input, algorithmic HBM GB/s and its fraction of the 8 TB/s peak."""
+    n_total = sum(o["n"] for o in ops)
+    results = []
+
+    def timed(fn, iters):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        t0 = torch.cuda.Event(enable_timing=True); t1 = torch.cuda.Event(enable_timing=True)
+        t0.record()
+        for _ in range(iters):
+            fn()
+        t1.record()
+        torch.cuda.synchronize()
+        return t0.elapsed_time(t1) / iters
+
+    def analyze_variant(name, gran_of, scope="partition", crit="mean_rel_err", scaling="fp32_amax", formats="e4m3|bf16"):
+        entries, outs = [], []
+        for o in ops:
+            gran = gran_of(o)
+            params = B.make_params(o["params"].rows, o["params"].cols, gran, scope, crit, THRESHOLD, scaling=scaling, formats=formats)
+            out = B.alloc_outputs(params, dev, want_bf16=True)
+            out.workspace = None
+            entries.append((params, o["x"], out, None))
+            outs.append((o, gran, params, out))
+        items = B.make_batch(entries)
+        ws = torch.empty(max(16, B.mor_batch_workspace_bytes(items)), dtype=torch.uint8, device=dev)
+        ms = timed(lambda: B.mor_analyze_quantize_batch(items, 1e-5, ws), steps)
+        nbytes = 0.0
+        n_fp8 = 0
+        for o, gran, params, out in outs:
+            mask = out.mask
+            P = mask.numel()
+            f = float((mask == 1).sum().item()) / P          # blocks are equal-sized here
+            n_fp8 += int(round((1.0 - f) * o["n"]))
+            n = o["n"]
+            if gran == "tensor":
+                b = 5.0 * n + 2.0 * n * f                       # amax pass + quantize pass (+ fallback written once)
+            else:
+                b = 3.0 * n + META_BYTES * P
+                if scope == "tensor":
+                    b += 4.0 * n * f                            # separate copy pass after the tensor-wide decision
+                else:
+                    b += 2.0 * n * f
+                if gran == "channel_col":
+                    b += 2.0 * n                                # column amax pass
+                if scaling == "gam":
+                    b += 2.0 * n                                # group amax pre-pass (Algorithm 1, group loop)
+            nbytes += b
+        del outs, entries, items, ws
+        rec = {"name": name, "ms": round(ms, 4), "input_gbs": round(2.0 * n_total / ms / 1e6, 1),
+               "hbm_algorithmic_gbs": round(nbytes / ms / 1e6, 1), "hbm_frac_of_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4),
+               "fp8_pct_by_elements": round(100.0 * n_fp8 / n_total, 2)}
+        log(f"[bench]   variant {name:34s} {ms:8.3f} ms  {rec['input_gbs']:8.1f} GB/s in  {rec['hbm_algorithmic_gbs']:8.1f} GB/s HBM "
+            f"({100 * rec['hbm_frac_of_peak']:.1f} %)  FP8 {rec['fp8_pct_by_elements']:.1f} %")
+        results.append(rec)
+        torch.cuda.empty_cache()
+
+    own = lambda o: o["gran"]
+    const = lambda g: (lambda o: g)
+    analyze_variant("gam_tensor_level_block128", const("block128"), scope="tensor", scaling="gam")
+    analyze_variant("gam_tensor_level_channel_row", const("channel_row"), scope="tensor", scaling="gam")
+    analyze_variant("gam_tensor_level_per_tensor", const("tensor"), scaling="gam")
+    analyze_variant("e8m0_block128", const("block128"), scaling="e8m0")
+    analyze_variant("two_way_eq3_block128", const("block128"), crit="e4m3_vs_e5m2")
+    analyze_variant("three_way_eq3_block128", const("block128"), crit="e4m3_vs_e5m2", formats="e4m3|e5m2|bf16")
+    analyze_variant("block64", const("block64"))
+    analyze_variant("channel_row", const("channel_row"))
+    analyze_variant("sub128x1", const("sub128x1"))
+    analyze_variant("channel_col", const("channel_col"))
+
+    # fake quantization at the sweep's own granularities, and de-quantization of the sweep's outputs
+    metas, ys = [], []
+    for o in ops:
+        meta = B.alloc_outputs(o["params"], dev, want_bf16=False, want_fp8=False)
+        metas.append(meta)
+        ys.append(torch.empty_like(o["x"]))
+
+    fake_items = B.make_batch([(o["params"], o["x"], meta, None, y) for o, meta, y in zip(ops, metas, ys)])
+    fake_ws = torch.empty(max(16, B.mor_batch_workspace_bytes(fake_items)), dtype=torch.uint8, device=dev)
+    ms = timed(lambda: B.mor_analyze_quantize_batch(fake_items, 1e-5, fake_ws), steps)
+    nbytes = sum((6.0 if o["gran"] == "tensor" else 4.0) * o["n"] + (0 if o["gran"] == "tensor" else META_BYTES * o["P"]) for o in ops)
+    rec = {"name": "fake_quantize_cfg5", "ms": round(ms, 4), "input_gbs": round(2.0 * n_total / ms / 1e6, 1),
+           "hbm_algorithmic_gbs": round(nbytes / ms / 1e6, 1), "hbm_frac_of_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    log(f"[bench]   variant {rec['name']:34s} {ms:8.3f} ms  {rec['input_gbs']:8.1f} GB/s in  {rec['hbm_algorithmic_gbs']:8.1f} GB/s HBM "
+        f"({100 * rec['hbm_frac_of_peak']:.1f} %)")
+    results.append(rec)
+
+    def dequant_all():
+        for o, y in zip(ops, ys):
+            r = o["out"]
+            B.mor_dequantize(o["params"], r.fp8, r.scale, r.mask, r.bf16, y)
+    ms = timed(dequant_all, steps)
+    nbytes = sum((3.0 + 1.0 * o["fallback_frac"]) * o["n"] for o in ops)      # FP8 blocks: 1 + 2; BF16 blocks: 2 + 2
+    rec = {"name": "dequantize_cfg5", "ms": round(ms, 4), "input_gbs": round(2.0 * n_total / ms / 1e6, 1),
+           "hbm_algorithmic_gbs": round(nbytes / ms / 1e6, 1), "hbm_frac_of_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    log(f"[bench]   variant {rec['name']:34s} {ms:8.3f} ms  {rec['input_gbs']:8.1f} GB/s out {rec['hbm_algorithmic_gbs']:8.1f} GB/s HBM "
+        f"({100 * rec['hbm_frac_of_peak']:.1f} %)")
+    results.append(rec)
+    return results
+
+
+KERNEL_GRAN = {"sub1x128": "sub1x128", "team_block": "block128", "tensor_amax": "tensor", "tensor_quant": "tensor",
                "fallback_copy": "tensor"}
 
 
@@ -65,6 +171,7 @@ def main() -> int:
     ap.add_argument("--per-operand", action="store_true", help="one analyze + one stats call per operand instead of one batch call")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device-to-device copies (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--no-variants", action="store_true", help="skip the timing of the further rows (GAM, three-way, partitions, fake quantization)")
     ap.add_argument("--cpu-passes", type=int, default=0, help="oracle passes over the sample (0: repeat until 10 s of oracle time)")
     ap.add_argument("--cpu-sample-div", type=int, default=1, help="oracle is timed on the first rows/N rows of every operand")
     args = ap.parse_args()
@@ -203,8 +310,12 @@ def main() -> int:
             step_bytes += sum(algorithmic_bytes(k, o["n"], 1, o["fallback_frac"], o["fused_fallback"])
                               for k in ("tensor_amax", "tensor_quant", "fallback_copy"))
         else:
-            step_bytes += algorithmic_bytes(o["gran"], o["n"], o["P"], o["fallback_frac"])
+            step_bytes += algorithmic_bytes("team_block" if o["gran"] == "block128" else o["gran"], o["n"], o["P"], o["fallback_frac"])
     step_gbs = step_bytes / (elapsed / args.steps) / 1e9
+
+    variants = None
+    if not args.no_variants and not args.per_operand:
+        variants = run_variants(ops, B, torch, dev, min(args.steps, 10), log)
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -243,6 +354,7 @@ def main() -> int:
                              "by_tensors": round(100.0 * fp8_tensors / len(ops), 3), "near_threshold_blocks": near},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
+        "further_rows": variants,
     }
     print(json.dumps(result), flush=True)
     return 0

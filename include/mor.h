@@ -210,8 +210,7 @@ typedef enum {
     MOR_KERNEL_STATS_PARTIAL = 10, MOR_KERNEL_STATS_FINAL = 11,
     MOR_KERNEL_GROUP_AMAX = 12,      /* amax of the whole operand for GAM scaling of sub-tensor blocks */
     MOR_KERNEL_GROUP_MANTISSA = 13,
-    MOR_KERNEL_TEAM_BLOCK = 14,      /* 64x64 blocks, per-channel rows, and 128x128 blocks with ragged edges,
-                                        three types or fake quantization */
+    MOR_KERNEL_TEAM_BLOCK = 14,      /* 128x128 blocks, 64x64 blocks, per-channel rows (id 2 is no longer used) */
     MOR_KERNEL_COLUMN_TILE = 15,     /* 128x1 sub-columns; per-channel columns: amax and quantize passes */
     MOR_KERNEL_COLUMN_COMBINE = 16   /* per-channel columns: scales from the amax partials, final decision */
 } mor_kernel_id;
@@ -239,6 +238,8 @@ mor_status mor_analyze_quantize_profiled(const mor_params* params, const uint16_
  *   near_tol   as for mor_select_stats
  *   workspace  device scratch of mor_batch_workspace_bytes(items, n_items) bytes, 16-byte aligned
  *   profile    optional measurement aid as in mor_analyze_quantize_profiled (NULL for none)
+ * An item with fake_y set is fake-quantized into fake_y (leading dimension ld_fake_y) as by
+ * mor_fake_quantize; its out.fp8 and out.bf16 are then ignored.
  * n_items must be in [1, MOR_BATCH_MAX].  Operands must not overlap each other's outputs.
  */
 #define MOR_BATCH_MAX 64
@@ -247,6 +248,8 @@ typedef struct mor_batch_item {
     const uint16_t* x;
     mor_outputs     out;
     mor_stats*      stats;
+    uint16_t*       fake_y;      /* NULL: FP8 payload + BF16 fallback; else the fake-quantized tensor */
+    int64_t         ld_fake_y;
 } mor_batch_item;
 size_t     mor_batch_workspace_bytes(const mor_batch_item* items, int32_t n_items);
 mor_status mor_analyze_quantize_batch(const mor_batch_item* items, int32_t n_items, float near_tol,

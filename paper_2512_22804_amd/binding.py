@@ -74,7 +74,8 @@ class MorProfile(C.Structure):
 
 
 class MorBatchItem(C.Structure):
-    _fields_ = [("params", MorParams), ("x", C.c_void_p), ("out", MorOutputs), ("stats", C.c_void_p)]
+    _fields_ = [("params", MorParams), ("x", C.c_void_p), ("out", MorOutputs), ("stats", C.c_void_p),
+                ("fake_y", C.c_void_p), ("ld_fake_y", C.c_int64)]
 
 
 class MorError(RuntimeError):
@@ -259,13 +260,18 @@ def mor_histogram_update(hist12: torch.Tensor, stats_dev: torch.Tensor, step: in
 
 
 def make_batch(entries) -> "C.Array":
-    """entries: sequence of (params, x, out: MorResult, stats: torch.Tensor | None).  Returns the host item array."""
+    """entries: sequence of (params, x, out: MorResult, stats: torch.Tensor | None[, fake_y: torch.Tensor | None]).
+    Returns the host item array."""
     arr = (MorBatchItem * len(entries))()
-    for i, (params, x, out, stats) in enumerate(entries):
+    for i, entry in enumerate(entries):
+        params, x, out, stats = entry[:4]
+        fake_y = entry[4] if len(entry) > 4 else None
         arr[i].params = params
         arr[i].x = x.data_ptr()
         arr[i].out = _outputs_struct(out)
         arr[i].stats = stats.data_ptr() if stats is not None else None
+        arr[i].fake_y = fake_y.data_ptr() if fake_y is not None else None
+        arr[i].ld_fake_y = fake_y.stride(0) if fake_y is not None else 0
     return arr
 
 

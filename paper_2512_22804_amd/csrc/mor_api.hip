@@ -144,7 +144,7 @@ size_t mor_batch_workspace_bytes(const mor_batch_item* items, int32_t n_items) {
     size_t total = 0;
     for (int32_t i = 0; i < n_items; ++i) {
         mor::BatchItem it{};
-        if (make_item(&items[i].params, items[i].x, &items[i].out, items[i].stats, nullptr, 0, &it) != MOR_OK) return 0;
+        if (make_item(&items[i].params, items[i].x, &items[i].out, items[i].stats, items[i].fake_y, items[i].ld_fake_y, &it) != MOR_OK) return 0;
         total += mor::batch_workspace_bytes(&it, 1);
     }
     return total;
@@ -157,7 +157,7 @@ mor_status mor_analyze_quantize_batch(const mor_batch_item* items, int32_t n_ite
     static_assert(MOR_BATCH_MAX == mor::kBatchMax, "batch limit");
     mor::BatchItem its[MOR_BATCH_MAX];
     for (int32_t i = 0; i < n_items; ++i) {
-        mor_status st = make_item(&items[i].params, items[i].x, &items[i].out, items[i].stats, nullptr, 0, &its[i]);
+        mor_status st = make_item(&items[i].params, items[i].x, &items[i].out, items[i].stats, items[i].fake_y, items[i].ld_fake_y, &its[i]);
         if (st != MOR_OK) return st;
     }
     return run_batch(its, n_items, near_tol, workspace, workspace_bytes, stream, profile);

@@ -346,6 +346,24 @@ __device__ __forceinline__ uint32_t decide_eq2(float err_sum, uint32_t nnz, floa
 }
 __device__ __forceinline__ uint32_t decide_eq3(float err4, float err5) { return (err4 < err5) ? 0u : 1u; }
 
+// Bounds-checked streaming accesses through a buffer resource: a lane whose offset is kBufOutside loads
+// zeros and stores nothing, so ragged edges need no per-lane branches.  Offsets are bytes from `base`
+// (32 bits; callers keep them below 2^31).
+typedef __amdgpu_buffer_rsrc_t BufRsrc;
+constexpr uint32_t kBufOutside = 0x80000000u;
+__device__ __forceinline__ BufRsrc make_buf(const void* base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7FFFFFFF, 0x00020000);
+}
+__device__ __forceinline__ u32x4 buf_load16(BufRsrc r, uint32_t voff, uint32_t soff) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 2);          // aux 2: non-temporal
+}
+__device__ __forceinline__ void buf_store16(BufRsrc r, uint32_t voff, uint32_t soff, const u32x4& v) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, soff, 2);
+}
+__device__ __forceinline__ void buf_store8(BufRsrc r, uint32_t voff, uint32_t soff, const u32x2& v) {
+    __builtin_amdgcn_raw_buffer_store_b64(v, r, voff, soff, 2);
+}
+
 // Streaming accesses: every operand byte is touched once per pass, so loads and stores carry the
 // non-temporal hint (measured +5-8 % on a plain copy of the same size on MI355X).
 #ifndef MOR_NT

@@ -842,100 +842,6 @@ __global__ __launch_bounds__(256) void k_sub1x128_group(GroupSub g) {
 #endif
 }
 
-struct GroupBlock {
-    int n;
-    int64_t tile_end[kMaxGroupSub];       // running total of 128x128 tiles
-    int32_t tiles_x[kMaxGroupSub];
-    int64_t ld[kMaxGroupSub];
-    const uint16_t* x[kMaxGroupSub];
-    KOut o[kMaxGroupSub];
-    float th[kMaxGroupSub];
-    uint8_t defer[kMaxGroupSub];
-    uint8_t mode[kMaxGroupSub];
-    const uint32_t* gam[kMaxGroupSub];
-};
-// One 256-thread workgroup per 128x128 block (Section 4.1.1 "Per-Block"): the whole 32 KB tile lives in
-// registers (8 x 16 B per lane); LDS only carries 4 per-wave partials.
-template <int CRIT>
-__global__ __launch_bounds__(256) void k_block128_group(GroupBlock g) {
-    __shared__ uint32_t sh_amax[4];
-    __shared__ float sh_err[4];
-    __shared__ float sh_err5[4];
-    __shared__ uint32_t sh_zero[4];
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, l = lane & 15;
-    const int op = group_find(g.tile_end, g.n, blockIdx.x);
-    const int64_t p = (int64_t)blockIdx.x - (op ? g.tile_end[op - 1] : 0);
-    const int64_t tr = p / g.tiles_x[op], tc = p - tr * g.tiles_x[op];
-    const KOut& o = g.o[op];
-    const int64_t ld = g.ld[op];
-    const int64_t col = tc * 128 + l * 8;
-    const int64_t row0 = tr * 128 + w * 4 + (lane >> 4);
-    const uint16_t* __restrict__ src = g.x[op] + row0 * ld + col;
-    uint8_t* __restrict__ dst = o.fp8 + row0 * o.ld_fp8 + col;
-    u32x4 raw[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) raw[i] = load16(src + (int64_t)i * 16 * ld);
-    Scan8 sc{0u, 0u};
-#pragma unroll
-    for (int i = 0; i < 8; ++i) scan8(raw[i], sc);
-    const uint32_t wa = wave_allmax_u32(fold_max16(sc.amax2));
-    if (lane == 0) sh_amax[w] = wa;
-    __syncthreads();
-    const uint32_t abits = max(max(sh_amax[0], sh_amax[1]), max(sh_amax[2], sh_amax[3]));
-    const uint32_t mode = g.mode[op];
-    uint32_t mg = 0u, mg5 = 0u;
-    if (mode) { mg = g.gam[op][0]; mg5 = g.gam[op][1]; }
-    const float s = block_scale(abits, kE4M3Max, mode, mg);
-    float e, e5 = 0.0f;
-    if (abits < fast_amax_limit(mode)) {
-        float e0 = 0.0f, e1 = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) store8(dst + (int64_t)i * 16 * o.ld_fp8, quant8_fast<false>(raw[i], s, e0, e1));
-        e = e0 + e1;
-        if constexpr (CRIT == kCritEq3) {
-            const float s5 = block_scale(abits, kE5M2Max, mode, mg5);
-            float f0 = 0.0f, f1 = 0.0f;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) (void)quant8_fast<true>(raw[i], s5, f0, f1);
-            e5 = f0 + f1;
-        }
-    } else {
-        e = 0.0f;
-#pragma clang loop unroll(disable)
-        for (int i = 0; i < 8; ++i) {
-            e += quant8_careful_mem<false>(src + (int64_t)i * 16 * ld, s, dst + (int64_t)i * 16 * o.ld_fp8);
-            if constexpr (CRIT == kCritEq3)
-                e5 += quant8_careful_mem<true>(src + (int64_t)i * 16 * ld, block_scale(abits, kE5M2Max, mode, mg5), nullptr);
-        }
-    }
-    const float werr = wave_allsum_f32(e);
-    const uint32_t wzero = wave_allsum_u32(fold_add16(sc.zero2));
-    float werr5 = 0.0f;
-    if constexpr (CRIT == kCritEq3) werr5 = wave_allsum_f32(e5);
-    if (lane == 0) { sh_err[w] = werr; sh_zero[w] = wzero; sh_err5[w] = werr5; }
-    __syncthreads();
-    float err = (sh_err[0] + sh_err[1]) + (sh_err[2] + sh_err[3]);
-    float err5 = (sh_err5[0] + sh_err5[1]) + (sh_err5[2] + sh_err5[3]);
-    const uint32_t nnz = 128u * 128u - ((sh_zero[0] + sh_zero[1]) + (sh_zero[2] + sh_zero[3]));
-    if (abits >= kInfBits) { err = __builtin_inff(); err5 = __builtin_inff(); }
-    const bool defer = g.defer[op] != 0;
-    const uint32_t mask = defer ? 0u : ((CRIT == kCritEq3) ? decide_eq3(err, err5) : decide_eq2(err, nnz, g.th[op]));
-    if (threadIdx.x == 0) {
-        o.scale[p] = s;
-        o.amax[p] = __uint_as_float(abits << 16);
-        o.err_sum[p] = err;
-        o.nnz[p] = nnz;
-        if constexpr (CRIT == kCritEq3) o.err5_sum[p] = err5;
-        if (!defer) o.mask[p] = (uint8_t)mask;
-        if (mode != kScaleFp32 && o.e8m0) o.e8m0[p] = (uint8_t)(__float_as_uint(s) >> 23);
-    }
-    if (mask && o.bf16) {
-        uint16_t* __restrict__ dbf = o.bf16 + row0 * o.ld_bf16 + col;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) store16(dbf + (int64_t)i * 16 * o.ld_bf16, raw[i]);
-    }
-}
-
 // Per-tensor operands of a group share three launches (amax, quantize, finish + fallback copy).
 struct TensorOp {
     const uint16_t* x;
@@ -1422,8 +1328,7 @@ enum Route {
     kRouteTensorStrided,    // per-tensor, padded leading dimensions
     kRouteSubFlat,          // 1 x 128, dense, whole blocks, two types, FP8 payload: the persistent grouped kernel
     kRouteSubGeneral,       // 1 x 128, everything else
-    kRouteBlockHot,         // 128 x 128, whole blocks, two types, FP8 payload
-    kRouteTeam,             // 64 x 64, per-channel rows, and 128 x 128 with ragged edges / three types / fake quantization
+    kRouteTeam,             // 128 x 128, 64 x 64, per-channel rows: a team of lanes keeps the block in registers
     kRouteSubCol,           // 128 x 1
     kRouteChannelCol        // per-channel columns
 };
@@ -1433,8 +1338,7 @@ Route route_of(const BatchItem& it) {
     switch (it.gran) {
     case kGranTensor: return item_is_flat(it) ? kRouteTensorGroup : kRouteTensorStrided;
     case kGranSub: return (plain && item_is_flat(it) && it.sh.cols % 128 == 0) ? kRouteSubFlat : kRouteSubGeneral;
-    case kGranBlock: return (plain && it.sh.rows % 128 == 0 && it.sh.cols % 128 == 0) ? kRouteBlockHot : kRouteTeam;
-    case kGranBlock64: case kGranRow: return kRouteTeam;
+    case kGranBlock: case kGranBlock64: case kGranRow: return kRouteTeam;
     case kGranSubCol: return kRouteSubCol;
     default: return kRouteChannelCol;
     }
@@ -1473,7 +1377,7 @@ size_t batch_workspace_bytes(const BatchItem* items, int n) {
 }
 
 hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws, size_t ws_bytes, hipStream_t st, KProf* prof) {
-    static_assert(sizeof(GroupSub) <= 3800 && sizeof(GroupBlock) <= 3800 && sizeof(GroupTensor) <= 3800 && sizeof(GroupStats) <= 3800 &&
+    static_assert(sizeof(GroupSub) <= 3800 && sizeof(GroupTensor) <= 3800 && sizeof(GroupStats) <= 3800 &&
                   sizeof(GroupGam) <= 3800, "kernel-argument segment is 4 KB");
     static_assert(sizeof(StatsRec) == 128, "StatsRec layout");
     char* wsp = static_cast<char*>(ws);
@@ -1581,32 +1485,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
             if (route[i] != kRouteSubGeneral || it.crit != crit) continue;
             err = launch_sub1x128(it.x, it.sh, it.o, crit, it.scope == 1, it.th, (uint32_t)it.scaling, gam_of[i], (uint32_t)it.three, st, prof);
         }
-        // ---- 128x128 block operands, whole blocks
-        {
-            GroupBlock g; g.n = 0;
-            int64_t total = 0;
-            auto flush = [&]() {
-                if (g.n == 0) return;
-                ProfScope ps(prof, kKernBlock128, st);
-                if (crit == kCritEq3) k_block128_group<kCritEq3><<<dim3((unsigned)total), dim3(256), 0, st>>>(g);
-                else k_block128_group<kCritEq2><<<dim3((unsigned)total), dim3(256), 0, st>>>(g);
-                g.n = 0; total = 0;
-            };
-            for (int i = 0; i < n; ++i) {
-                const BatchItem& it = items[i];
-                if (route[i] != kRouteBlockHot || it.crit != crit) continue;
-                const int64_t tiles = item_parts(it);
-                if (tiles > 0x7FFFFFFF) return hipErrorInvalidValue;
-                if (total + tiles > 0x7FFFFFFF) flush();
-                total += tiles;
-                g.tile_end[g.n] = total; g.tiles_x[g.n] = (int32_t)(it.sh.cols / 128); g.ld[g.n] = it.sh.ld;
-                g.x[g.n] = it.x; g.o[g.n] = it.o; g.th[g.n] = it.th; g.defer[g.n] = it.scope == 1;
-                g.mode[g.n] = (uint8_t)it.scaling; g.gam[g.n] = gam_of[i];
-                if (++g.n == kMaxGroupSub) flush();
-            }
-            flush();
-        }
-        // ---- team kernels: 64x64 blocks, per-channel rows, 128x128 blocks with edges / three types / fake quantization
+        // ---- team kernels: 128x128 and 64x64 blocks, per-channel rows
         for (int kind = 0; kind < 4 && err == hipSuccess; ++kind) {
             int idx[kBatchMax];
             int cnt = 0;
@@ -1623,10 +1502,16 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
             if (cnt) err = launch_subcol_items(items, idx, cnt, crit, gam_of, st, prof);
         }
         // ---- per-channel columns
-        for (int i = 0; i < n && err == hipSuccess; ++i) {
-            const BatchItem& it = items[i];
-            if (route[i] != kRouteChannelCol || it.crit != crit) continue;
-            err = launch_channel_col(it, gam_of[i], carve(column_workspace_bytes(it.sh.rows, it.sh.cols)), st, prof);
+        if (err == hipSuccess) {
+            int idx[kBatchMax];
+            char* ws_of[kBatchMax];
+            int cnt = 0;
+            for (int i = 0; i < n; ++i)
+                if (route[i] == kRouteChannelCol && items[i].crit == crit) {
+                    ws_of[cnt] = carve(column_workspace_bytes(items[i].sh.rows, items[i].sh.cols));
+                    idx[cnt++] = i;
+                }
+            if (cnt) err = launch_channel_col_items(items, idx, cnt, crit, gam_of, ws_of, st, prof);
         }
         // ---- per-tensor operands: amax pass, quantize pass, finish (+ fallback copy) pass; FP8 payload and fake
         //      quantization are different kernels

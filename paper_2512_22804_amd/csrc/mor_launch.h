@@ -105,7 +105,8 @@ hipError_t launch_team_items(const BatchItem* items, const int* idx, int cnt, in
 hipError_t launch_subcol_items(const BatchItem* items, const int* idx, int cnt, int crit, const uint32_t* const* gam_of,
                                hipStream_t st, KProf* prof);
 size_t column_workspace_bytes(int64_t rows, int64_t cols);
-hipError_t launch_channel_col(const BatchItem& it, const uint32_t* gam, void* ws, hipStream_t st, KProf* prof);
+hipError_t launch_channel_col_items(const BatchItem* items, const int* idx, int cnt, int crit, const uint32_t* const* gam_of,
+                                    char* const* ws_of, hipStream_t st, KProf* prof);
 
 hipError_t launch_dequantize(const StatsGeom& geom, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
                              const uint8_t* mask, const uint16_t* bf16, int64_t ld_bf16, uint16_t* y, int64_t ld_y,

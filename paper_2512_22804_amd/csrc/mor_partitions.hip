@@ -76,9 +76,11 @@ __device__ __forceinline__ void team_allsum3(float& a, float& b, uint32_t& z, Te
     }
 }
 
-template <int TEAM, int CRIT, bool FAKE>
+// EDGE = false: the operand has no partial blocks (block teams), or its rows are a whole number of the
+// team's sweeps (row teams), so chunk validity is uniform over the team and costs no per-lane predicates.
+template <int TEAM, int CRIT, bool FAKE, bool EDGE>
 __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamShared& sh) {
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const KOut& o = t.o;
     // ---- geometry: block index p, origin (r0, c0), valid extent h x wd, this lane's chunk positions
     int64_t p, r0, c0;
@@ -114,12 +116,20 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
     if (!active) return;                                   // wave teams only: no barrier is skipped
     const uint16_t* __restrict__ src = t.x + (r0 + trow) * t.ld + c0 + tcol;
     const int64_t src_step = (int64_t)rstep * t.ld + cstep;
-    auto is_valid = [&](int i) -> bool { return (trow + i * rstep < h) && (tcol + i * cstep < wd); };
+    // Whole-block operands of the block teams use plain pointers; everything else (ragged edges, rows) goes through
+    // bounds-checked buffer accesses relative to the block origin, where a lane outside the block costs no branch.
+    constexpr bool BUF = EDGE || TEAM == kTeamWaveRow || TEAM == kTeamWgRow;
+    auto is_valid = [&](int i) -> bool {
+        if constexpr (BUF) return (trow + i * rstep < h) && (tcol + i * cstep < wd);
+        else return true;
+    };
+    const BufRsrc rx = make_buf(t.x + r0 * t.ld + c0);
+    const uint32_t xoff = (uint32_t)((trow * t.ld + tcol) * 2), xstep = (uint32_t)(src_step * 2);
     u32x4 raw[kChunks];
 #pragma unroll
     for (int i = 0; i < kChunks; ++i) {
-        if (is_valid(i)) raw[i] = load16(src + i * src_step);
-        else { raw[i].x = 0u; raw[i].y = 0u; raw[i].z = 0u; raw[i].w = 0u; }
+        if constexpr (BUF) raw[i] = buf_load16(rx, is_valid(i) ? xoff : kBufOutside, i * xstep);
+        else raw[i] = load16(src + i * src_step);
     }
     // ---- amax and zero count (chunks outside the tensor count as zeros and change nothing)
     Scan8 sc{0u, 0u};
@@ -136,6 +146,10 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
     const int64_t dst8_step = (int64_t)rstep * o.ld_fp8 + cstep;
     uint16_t* __restrict__ dstf = FAKE ? o.fake + (r0 + trow) * o.ld_fake + c0 + tcol : nullptr;
     const int64_t dstf_step = (int64_t)rstep * o.ld_fake + cstep;
+    const BufRsrc r8 = make_buf(FAKE ? nullptr : o.fp8 + r0 * o.ld_fp8 + c0);
+    const uint32_t off8 = (uint32_t)(trow * o.ld_fp8 + tcol), step8 = (uint32_t)dst8_step;
+    const BufRsrc rf = make_buf(FAKE ? o.fake + r0 * o.ld_fake + c0 : nullptr);
+    const uint32_t offf = (uint32_t)((trow * o.ld_fake + tcol) * 2), stepf = (uint32_t)(dstf_step * 2);
     const bool fast = abits < fast_amax_limit(mode);
     // quantizes the block with scale `sc_` for format E5M2 ? E5M2 : E4M3; returns this lane's error sum
     auto quantize = [&](auto fmt, float sc_, bool emit) -> float {
@@ -147,15 +161,20 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
             for (int i = 0; i < kChunks; ++i) {
                 u32x4 deq;
                 const u32x2 codes = quant8_fast_deq<E5, FAKE>(raw[i], sc_, s_inv, e0, e1, deq);
-                if (emit && is_valid(i)) {
+                if constexpr (BUF) {
+                    const bool put = emit && is_valid(i);
+                    if constexpr (FAKE) buf_store16(rf, put ? offf : kBufOutside, i * stepf, deq);
+                    else buf_store8(r8, put ? off8 : kBufOutside, i * step8, codes);
+                } else if (emit) {
                     if constexpr (FAKE) store16(dstf + i * dstf_step, deq);
                     else store8(dst8 + i * dst8_step, codes);
                 }
+                __builtin_amdgcn_sched_barrier(0);            // one chunk at a time keeps the register count down
             }
         } else {
 #pragma clang loop unroll(disable)
             for (int i = 0; i < kChunks; ++i)
-                if (is_valid(i))
+                if ((trow + i * rstep < h) && (tcol + i * cstep < wd))
                     e0 += quant8_careful_mem<E5>(src + i * src_step, sc_, emit && !FAKE ? dst8 + i * dst8_step : nullptr,
                                                  emit && FAKE ? dstf + i * dstf_step : nullptr, s_inv);
         }
@@ -198,20 +217,23 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
     if (mask == 1u && o.bf16) {                            // BF16: the block stays as it is
         uint16_t* __restrict__ dbf = o.bf16 + (r0 + trow) * o.ld_bf16 + c0 + tcol;
         const int64_t dbf_step = (int64_t)rstep * o.ld_bf16 + cstep;
+        const BufRsrc rb = make_buf(o.bf16 + r0 * o.ld_bf16 + c0);
+        const uint32_t offb = (uint32_t)((trow * o.ld_bf16 + tcol) * 2), stepb = (uint32_t)(dbf_step * 2);
 #pragma unroll
-        for (int i = 0; i < kChunks; ++i)
-            if (is_valid(i)) store16(dbf + i * dbf_step, raw[i]);
+        for (int i = 0; i < kChunks; ++i) {
+            if constexpr (BUF) buf_store16(rb, is_valid(i) ? offb : kBufOutside, i * stepb, raw[i]);
+            else store16(dbf + i * dbf_step, raw[i]);
+        }
     }
 }
 
-template <int TEAM, int CRIT>
+template <int TEAM, int CRIT, bool FAKE, bool EDGE>
 __global__ __launch_bounds__(256) void k_team_group(GroupTeam g) {
     __shared__ TeamShared sh;
     const int op = group_find(g.unit_end, g.n, blockIdx.x);
     const TeamOp& t = g.op[op];
     const int64_t unit = (int64_t)blockIdx.x - (op ? g.unit_end[op - 1] : 0);
-    if (t.o.fake) team_block<TEAM, CRIT, true>(t, unit, sh);
-    else team_block<TEAM, CRIT, false>(t, unit, sh);
+    team_block<TEAM, CRIT, FAKE, EDGE>(t, unit, sh);
 }
 
 // ======================================================================================
@@ -238,11 +260,14 @@ struct ColOp {
     // per-channel columns: workspace, [n_strips x cols_padded] each, cols_padded = tiles_x * 128
     uint16_t* part_amax;
     float* part_err; float* part_err5; uint16_t* part_zero;
-    const float* col_scale; const float* col_scale5;     // [cols_padded]
+    float* col_scale; float* col_scale5;                 // [cols_padded]
+    int32_t n_strips;
 };
 struct GroupCol {
     int n;
     int64_t unit_end[kMaxTeamGroup];
+    int32_t comb_end[kMaxTeamGroup];      // running workgroup totals of the combine kernels (256 columns each)
+    int32_t copy_end[kMaxTeamGroup];      // running workgroup totals of the fallback-column copy
     ColOp op[kMaxTeamGroup];
 };
 struct ColShared {
@@ -269,7 +294,7 @@ __device__ __forceinline__ float colgroup_addf(float v) {
     return v + __shfl_xor(v, 32, 64);
 }
 
-template <int CRIT, int MODE, bool FAKE>
+template <int CRIT, int MODE, bool FAKE, bool EDGE>
 __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShared& sh) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, cg = tid & 15;
     const KOut& o = t.o;
@@ -286,7 +311,6 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
 #pragma unroll
     for (int k = 0; k < 8; ++k) { err[k] = 0.0f; err5[k] = 0.0f; }
     float s[8], s5[8], s_inv[8];
-    uint32_t col_abits[8];
     bool strip_fast = true;
     if constexpr (MODE == kColExternal) {
         bool f = true;
@@ -295,8 +319,8 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
             s[k] = t.col_scale[c0 + cg * 8 + k];
             s5[k] = CRIT == kCritEq3 ? t.col_scale5[c0 + cg * 8 + k] : 0.0f;
             s_inv[k] = FAKE ? 1.0f / s[k] : 0.0f;
-            col_abits[k] = col_ok ? __float_as_uint(o.amax[col + k]) >> 16 : 0u;
-            f = f && col_abits[k] < fast_amax_limit(mode);
+            const uint32_t col_abits = col_ok ? __float_as_uint(o.amax[col + k]) >> 16 : 0u;
+            f = f && col_abits < fast_amax_limit(mode);
         }
         strip_fast = __syncthreads_and(f ? 1 : 0) != 0;
     }
@@ -305,12 +329,19 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
         if (r0 >= t.rows) break;                                       // uniform over the workgroup
         const int64_t row = r0 + (tid >> 4);
         const uint16_t* __restrict__ src = t.x + row * t.ld + col;
-        auto is_valid = [&](int i) -> bool { return col_ok && row + i * 16 < t.rows; };
+        auto is_valid = [&](int i) -> bool {
+            if constexpr (EDGE) return col_ok && row + i * 16 < t.rows;
+            else return true;                                          // rows and cols are multiples of 128
+        };
+        // ragged operands: bounds-checked buffer accesses relative to the tile origin (a lane outside loads zeros
+        // and stores nothing, without a branch)
+        const BufRsrc rx = make_buf(t.x + r0 * t.ld + c0);
+        const uint32_t xoff = (uint32_t)(((tid >> 4) * t.ld + cg * 8) * 2), xstep = (uint32_t)(16 * t.ld * 2);
         u32x4 raw[kChunks];
 #pragma unroll
         for (int i = 0; i < kChunks; ++i) {
-            if (is_valid(i)) raw[i] = load16(src + (int64_t)i * 16 * t.ld);
-            else { raw[i].x = 0u; raw[i].y = 0u; raw[i].z = 0u; raw[i].w = 0u; }
+            if constexpr (EDGE) raw[i] = buf_load16(rx, is_valid(i) ? xoff : kBufOutside, i * xstep);
+            else raw[i] = load16(src + (int64_t)i * 16 * t.ld);
         }
         if constexpr (MODE != kColExternal) {
 #pragma unroll
@@ -344,14 +375,17 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
                 s[k] = sh.scale[cg * 8 + k];
                 s5[k] = sh.scale5[cg * 8 + k];
                 s_inv[k] = FAKE ? 1.0f / s[k] : 0.0f;
-                col_abits[k] = sh.abits[cg * 8 + k];
-                f = f && col_abits[k] < fast_amax_limit(mode);
+                f = f && (uint32_t)sh.abits[cg * 8 + k] < fast_amax_limit(mode);
             }
             strip_fast = __syncthreads_and(f ? 1 : 0) != 0;
         }
         // ---- quantize the tile with the per-column scales
         uint8_t* __restrict__ dst8 = FAKE ? nullptr : o.fp8 + row * o.ld_fp8 + col;
         uint16_t* __restrict__ dstf = FAKE ? o.fake + row * o.ld_fake + col : nullptr;
+        const BufRsrc r8 = make_buf(FAKE ? nullptr : o.fp8 + r0 * o.ld_fp8 + c0);
+        const uint32_t off8 = (uint32_t)((tid >> 4) * o.ld_fp8 + cg * 8), step8 = (uint32_t)(16 * o.ld_fp8);
+        const BufRsrc rf = make_buf(FAKE ? o.fake + r0 * o.ld_fake + c0 : nullptr);
+        const uint32_t offf = (uint32_t)(((tid >> 4) * o.ld_fake + cg * 8) * 2), stepf = (uint32_t)(16 * o.ld_fake * 2);
 #pragma unroll
         for (int i = 0; i < kChunks; ++i)
 #pragma unroll
@@ -361,11 +395,15 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
             for (int i = 0; i < kChunks; ++i) {
                 u32x4 deq;
                 const u32x2 codes = quant8_cols<false, FAKE>(raw[i], s, s_inv, err, deq);
-                if (is_valid(i)) {
+                if constexpr (EDGE) {
+                    if constexpr (FAKE) buf_store16(rf, is_valid(i) ? offf : kBufOutside, i * stepf, deq);
+                    else buf_store8(r8, is_valid(i) ? off8 : kBufOutside, i * step8, codes);
+                } else {
                     if constexpr (FAKE) store16(dstf + (int64_t)i * 16 * o.ld_fake, deq);
                     else store8(dst8 + (int64_t)i * 16 * o.ld_fp8, codes);
                 }
                 if constexpr (CRIT == kCritEq3) { u32x4 d5; (void)quant8_cols<true, false>(raw[i], s5, s_inv, err5, d5); }
+                __builtin_amdgcn_sched_barrier(0);            // one chunk at a time keeps the register count down
             }
         } else {
             // some column of the strip has amax >= 2^24..2^25 or is non-finite: element-wise careful path
@@ -438,12 +476,21 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
             __syncthreads();
             if (o.bf16) {
                 const uint64_t mk8 = *reinterpret_cast<const uint64_t*>(&sh.mask[cg * 8]);
-                if (mk8) {                                             // some of this lane's columns stay in BF16
+                uint16_t* __restrict__ dbf = o.bf16 + row * o.ld_bf16 + col;
+                if (mk8 == 0x0101010101010101ull) {                    // all eight columns of this lane stay in BF16
+                    const BufRsrc rb = make_buf(o.bf16 + r0 * o.ld_bf16 + c0);
+                    const uint32_t offb = (uint32_t)(((tid >> 4) * o.ld_bf16 + cg * 8) * 2), stepb = (uint32_t)(16 * o.ld_bf16 * 2);
+#pragma unroll
+                    for (int i = 0; i < kChunks; ++i) {
+                        if constexpr (EDGE) buf_store16(rb, is_valid(i) ? offb : kBufOutside, i * stepb, raw[i]);
+                        else store16(dbf + (int64_t)i * 16 * o.ld_bf16, raw[i]);
+                    }
+                } else if (mk8) {                                      // some of them: element by element
 #pragma clang loop unroll(disable)
                     for (int i = 0; i < kChunks; ++i) {
                         if (!is_valid(i)) continue;
                         const uint16_t* sp = src + (int64_t)i * 16 * t.ld;
-                        uint16_t* dp = o.bf16 + (row + i * 16) * o.ld_bf16 + col;
+                        uint16_t* dp = dbf + (int64_t)i * 16 * o.ld_bf16;
                         for (int k = 0; k < 8; ++k)
                             if ((mk8 >> (8 * k)) & 0xFFu) dp[k] = sp[k];
                     }
@@ -503,28 +550,30 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
     }
 }
 
-template <int CRIT, int MODE>
+template <int CRIT, int MODE, bool FAKE, bool EDGE>
 __global__ __launch_bounds__(256) void k_col_group(GroupCol g) {
     __shared__ ColShared sh;
     const int op = group_find(g.unit_end, g.n, blockIdx.x);
     const ColOp& t = g.op[op];
     const int64_t unit = (int64_t)blockIdx.x - (op ? g.unit_end[op - 1] : 0);
-    if (MODE != kColAmax && t.o.fake) col_strip<CRIT, MODE, true>(t, unit, sh);
-    else col_strip<CRIT, MODE, false>(t, unit, sh);
+    col_strip<CRIT, MODE, FAKE, EDGE>(t, unit, sh);
 }
 
 // Per-channel columns, first combine: column amax over the strips -> amax, scale (Algorithm 1), E8M0 byte.
-__global__ __launch_bounds__(256) void k_col_scales(ColOp t, int n_strips, float* __restrict__ col_scale, float* __restrict__ col_scale5) {
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+__global__ __launch_bounds__(256) void k_col_scales(GroupCol g) {
+    const int op = group_find32(g.comb_end, g.n, blockIdx.x);
+    const ColOp& t = g.op[op];
+    const int64_t c = (int64_t)(blockIdx.x - (op ? g.comb_end[op - 1] : 0)) * 256 + threadIdx.x;
     const int64_t cols_padded = t.tiles_x * 128;
     if (c >= cols_padded) return;
     uint32_t a = 0u;
-    for (int sidx = 0; sidx < n_strips; ++sidx) a = max(a, (uint32_t)t.part_amax[sidx * cols_padded + c]);
+#pragma unroll 8
+    for (int sidx = 0; sidx < t.n_strips; ++sidx) a = max(a, (uint32_t)t.part_amax[sidx * cols_padded + c]);
     uint32_t mg = 0u, mg5 = 0u;
     if (t.mode) { mg = t.gam[0]; mg5 = t.gam[1]; }
     const float s = block_scale(a, kE4M3Max, t.mode, mg);
-    col_scale[c] = s;
-    col_scale5[c] = block_scale(a, kE5M2Max, t.mode, mg5);
+    t.col_scale[c] = s;
+    t.col_scale5[c] = block_scale(a, kE5M2Max, t.mode, mg5);
     if (c < t.cols) {
         t.o.amax[c] = __uint_as_float(a << 16);
         t.o.scale[c] = s;
@@ -533,18 +582,21 @@ __global__ __launch_bounds__(256) void k_col_scales(ColOp t, int n_strips, float
 }
 // Second combine: column error sums over the strips (binary64, fixed order), non-zero counts, decision.
 template <int CRIT>
-__global__ __launch_bounds__(256) void k_col_finish(ColOp t, int n_strips) {
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+__global__ __launch_bounds__(256) void k_col_finish(GroupCol g) {
+    const int op = group_find32(g.comb_end, g.n, blockIdx.x);
+    const ColOp& t = g.op[op];
+    const int64_t c = (int64_t)(blockIdx.x - (op ? g.comb_end[op - 1] : 0)) * 256 + threadIdx.x;
     const int64_t cols_padded = t.tiles_x * 128;
     if (c >= t.cols) return;
     double e = 0.0, e5 = 0.0;
     unsigned long long z = 0;
-    for (int sidx = 0; sidx < n_strips; ++sidx) {
+#pragma unroll 8
+    for (int sidx = 0; sidx < t.n_strips; ++sidx) {
         e += (double)t.part_err[sidx * cols_padded + c];
         z += t.part_zero[sidx * cols_padded + c];
         if constexpr (CRIT == kCritEq3) e5 += (double)t.part_err5[sidx * cols_padded + c];
     }
-    // rows beyond the tensor were loaded as zeros: padded rows = strips * tiles_per_strip * 128
+    // rows beyond the tensor were loaded as zeros, up to the end of the last 128-row tile
     const unsigned long long padded = (unsigned long long)((t.rows + 127) / 128) * 128ull;
     const unsigned long long n = padded - z;
     const uint32_t abits = __float_as_uint(t.o.amax[c]) >> 16;
@@ -559,12 +611,29 @@ __global__ __launch_bounds__(256) void k_col_finish(ColOp t, int n_strips) {
         t.o.mask[c] = (uint8_t)mk;
     }
 }
-// Columns kept in BF16 are copied (2-byte elements; a rare path).
-__global__ __launch_bounds__(256) void k_col_fallback(ColOp t) {
-    const int64_t c = (int64_t)blockIdx.x * 64 + (threadIdx.x & 63);
-    if (c >= t.cols || t.o.mask[c] != 1u) return;
-    for (int64_t r = (int64_t)blockIdx.y * 4 + (threadIdx.x >> 6); r < t.rows; r += (int64_t)gridDim.y * 4)
-        t.o.bf16[r * t.o.ld_bf16 + c] = t.x[r * t.ld + c];
+// Columns kept in BF16 are copied: 16 bytes at a time where all eight columns of a chunk are kept, else by element.
+// A workgroup takes one 128-column strip and strides over the rows with the other workgroups of that strip.
+constexpr int kColCopyRowGroups = 32;
+__global__ __launch_bounds__(256) void k_col_fallback(GroupCol g) {
+    const int op = group_find32(g.copy_end, g.n, blockIdx.x);
+    const ColOp& t = g.op[op];
+    if (t.defer || t.o.bf16 == nullptr) return;
+    const int b = blockIdx.x - (op ? g.copy_end[op - 1] : 0);
+    const int64_t strip = b / kColCopyRowGroups, rg = b - strip * kColCopyRowGroups;
+    const int64_t c = strip * 128 + (threadIdx.x & 15) * 8;
+    if (c >= t.cols) return;
+    uint32_t keep = 0u;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) keep |= (t.o.mask[c + k] == 1u ? 1u : 0u) << k;
+    if (!keep) return;
+    for (int64_t r = rg * 16 + (threadIdx.x >> 4); r < t.rows; r += kColCopyRowGroups * 16) {
+        const uint16_t* sp = t.x + r * t.ld + c;
+        uint16_t* dp = t.o.bf16 + r * t.o.ld_bf16 + c;
+        if (keep == 0xFFu) store16(dp, load16(sp));
+        else
+            for (int k = 0; k < 8; ++k)
+                if ((keep >> k) & 1u) dp[k] = sp[k];
+    }
 }
 
 // ======================================================================================
@@ -584,10 +653,25 @@ struct ProfScope2 {
 };
 size_t align16p(size_t v) { return (v + 15) & ~(size_t)15; }
 
+template <int TEAM, bool FAKE, bool EDGE>
+void launch_team_crit(const GroupTeam& g, int64_t total, int crit, hipStream_t st) {
+    const dim3 grid((unsigned)total), block(256);
+    if (crit == kCritEq3) k_team_group<TEAM, kCritEq3, FAKE, EDGE><<<grid, block, 0, st>>>(g);
+    else k_team_group<TEAM, kCritEq2, FAKE, EDGE><<<grid, block, 0, st>>>(g);
+}
 template <int TEAM>
-void launch_team_kind(const GroupTeam& g, int64_t total, int crit, hipStream_t st) {
-    if (crit == kCritEq3) k_team_group<TEAM, kCritEq3><<<dim3((unsigned)total), dim3(256), 0, st>>>(g);
-    else k_team_group<TEAM, kCritEq2><<<dim3((unsigned)total), dim3(256), 0, st>>>(g);
+void launch_team_kind(const GroupTeam& g, int64_t total, int crit, bool fake, bool edge, hipStream_t st) {
+    if (fake) { if (edge) launch_team_crit<TEAM, true, true>(g, total, crit, st); else launch_team_crit<TEAM, true, false>(g, total, crit, st); }
+    else      { if (edge) launch_team_crit<TEAM, false, true>(g, total, crit, st); else launch_team_crit<TEAM, false, false>(g, total, crit, st); }
+}
+// Does the operand need per-lane validity predicates in the team kernel of this kind?
+bool team_needs_edge(const BatchItem& it, int kind) {
+    switch (kind) {
+    case kTeamWg128: return it.sh.rows % 128 != 0 || it.sh.cols % 128 != 0;
+    case kTeamWave64: return it.sh.rows % 64 != 0 || it.sh.cols % 64 != 0;
+    case kTeamWaveRow: return it.sh.cols % 512 != 0;
+    default: return it.sh.cols % 2048 != 0;
+    }
 }
 }  // namespace
 
@@ -604,21 +688,24 @@ int team_kind_of(const BatchItem& it) {
 hipError_t launch_team_items(const BatchItem* items, const int* idx, int cnt, int kind, int crit, const uint32_t* const* gam_of,
                              hipStream_t st, KProf* prof) {
     static_assert(sizeof(GroupTeam) <= 3800 && sizeof(GroupCol) <= 3800, "kernel-argument segment is 4 KB");
+    for (int variant = 0; variant < 4; ++variant) {
+    const bool fake = (variant & 1) != 0, edge = (variant & 2) != 0;
     GroupTeam g; g.n = 0;
     int64_t total = 0;
     auto flush = [&]() {
         if (g.n == 0) return;
         ProfScope2 ps(prof, kKernTeamBlock, st);
         switch (kind) {
-        case kTeamWg128: launch_team_kind<kTeamWg128>(g, total, crit, st); break;
-        case kTeamWave64: launch_team_kind<kTeamWave64>(g, total, crit, st); break;
-        case kTeamWaveRow: launch_team_kind<kTeamWaveRow>(g, total, crit, st); break;
-        default: launch_team_kind<kTeamWgRow>(g, total, crit, st); break;
+        case kTeamWg128: launch_team_kind<kTeamWg128>(g, total, crit, fake, edge, st); break;
+        case kTeamWave64: launch_team_kind<kTeamWave64>(g, total, crit, fake, edge, st); break;
+        case kTeamWaveRow: launch_team_kind<kTeamWaveRow>(g, total, crit, fake, edge, st); break;
+        default: launch_team_kind<kTeamWgRow>(g, total, crit, fake, edge, st); break;
         }
         g.n = 0; total = 0;
     };
     for (int k = 0; k < cnt; ++k) {
         const BatchItem& it = items[idx[k]];
+        if ((it.o.fake != nullptr) != fake || team_needs_edge(it, kind) != edge) continue;
         int64_t units;
         TeamOp& t = g.op[g.n];
         t.units_x = (it.sh.cols + 127) / 128;
@@ -637,6 +724,7 @@ hipError_t launch_team_items(const BatchItem* items, const int* idx, int cnt, in
         if (++g.n == kMaxTeamGroup) flush();
     }
     flush();
+    }
     return hipGetLastError();
 }
 
@@ -676,11 +764,18 @@ void fill_col_op(ColOp& t, const BatchItem& it, const uint32_t* gam) {
     t.th = it.th; t.defer = it.scope == 1; t.mode = (uint8_t)it.scaling;
     t.gam = gam;
 }
-template <int MODE>
-void launch_col_kind(const GroupCol& g, int64_t total, int crit, hipStream_t st) {
-    if (crit == kCritEq3) k_col_group<kCritEq3, MODE><<<dim3((unsigned)total), dim3(256), 0, st>>>(g);
-    else k_col_group<kCritEq2, MODE><<<dim3((unsigned)total), dim3(256), 0, st>>>(g);
+template <int MODE, bool FAKE, bool EDGE>
+void launch_col_crit(const GroupCol& g, int64_t total, int crit, hipStream_t st) {
+    const dim3 grid((unsigned)total), block(256);
+    if (crit == kCritEq3) k_col_group<kCritEq3, MODE, FAKE, EDGE><<<grid, block, 0, st>>>(g);
+    else k_col_group<kCritEq2, MODE, FAKE, EDGE><<<grid, block, 0, st>>>(g);
 }
+template <int MODE>
+void launch_col_kind(const GroupCol& g, int64_t total, int crit, bool fake, bool edge, hipStream_t st) {
+    if (fake) { if (edge) launch_col_crit<MODE, true, true>(g, total, crit, st); else launch_col_crit<MODE, true, false>(g, total, crit, st); }
+    else      { if (edge) launch_col_crit<MODE, false, true>(g, total, crit, st); else launch_col_crit<MODE, false, false>(g, total, crit, st); }
+}
+bool col_needs_edge(const BatchItem& it) { return it.sh.rows % 128 != 0 || it.sh.cols % 128 != 0; }
 }  // namespace
 
 size_t column_workspace_bytes(int64_t rows, int64_t cols) { return plan_columns(rows, cols).bytes; }
@@ -688,16 +783,19 @@ size_t column_workspace_bytes(int64_t rows, int64_t cols) { return plan_columns(
 // 128 x 1 sub-columns: grouped, one pass.
 hipError_t launch_subcol_items(const BatchItem* items, const int* idx, int cnt, int crit, const uint32_t* const* gam_of,
                                hipStream_t st, KProf* prof) {
+    for (int variant = 0; variant < 4; ++variant) {
+    const bool fake = (variant & 1) != 0, edge = (variant & 2) != 0;
     GroupCol g; g.n = 0;
     int64_t total = 0;
     auto flush = [&]() {
         if (g.n == 0) return;
         ProfScope2 ps(prof, kKernColumnTile, st);
-        launch_col_kind<kColLocal>(g, total, crit, st);
+        launch_col_kind<kColLocal>(g, total, crit, fake, edge, st);
         g.n = 0; total = 0;
     };
     for (int k = 0; k < cnt; ++k) {
         const BatchItem& it = items[idx[k]];
+        if ((it.o.fake != nullptr) != fake || col_needs_edge(it) != edge) continue;
         const int64_t units = ((it.sh.rows + 127) / 128) * ((it.sh.cols + 127) / 128);
         if (units > 0x7FFFFFFF) return hipErrorInvalidValue;
         if (total + units > 0x7FFFFFFF) flush();
@@ -707,41 +805,58 @@ hipError_t launch_subcol_items(const BatchItem* items, const int* idx, int cnt, 
         if (++g.n == kMaxTeamGroup) flush();
     }
     flush();
+    }
     return hipGetLastError();
 }
 
-// Per-channel columns: one operand, five launches (amax, scales, quantize, finish, fallback columns).
-hipError_t launch_channel_col(const BatchItem& it, const uint32_t* gam, void* ws, hipStream_t st, KProf* prof) {
-    const ColPlan pl = plan_columns(it.sh.rows, it.sh.cols);
-    char* w = static_cast<char*>(ws);
-    GroupCol g; g.n = 1;
-    ColOp& t = g.op[0];
-    fill_col_op(t, it, gam);
-    t.tiles_per_strip = pl.tiles_per_strip;
-    t.part_amax = reinterpret_cast<uint16_t*>(w + pl.off_amax);
-    t.part_err = reinterpret_cast<float*>(w + pl.off_err);
-    t.part_err5 = reinterpret_cast<float*>(w + pl.off_err5);
-    t.part_zero = reinterpret_cast<uint16_t*>(w + pl.off_zero);
-    float* col_scale = reinterpret_cast<float*>(w + pl.off_scale);
-    float* col_scale5 = reinterpret_cast<float*>(w + pl.off_scale5);
-    t.col_scale = col_scale; t.col_scale5 = col_scale5;
-    const int64_t total = (int64_t)pl.n_strips * t.tiles_x;
-    if (total > 0x7FFFFFFF) return hipErrorInvalidValue;
-    g.unit_end[0] = total;
-    { ProfScope2 ps(prof, kKernColumnTile, st); launch_col_kind<kColAmax>(g, total, kCritEq2, st); }
-    const unsigned cb = (unsigned)((pl.cols_padded + 255) / 256);
-    { ProfScope2 ps(prof, kKernColumnCombine, st); k_col_scales<<<dim3(cb), dim3(256), 0, st>>>(t, pl.n_strips, col_scale, col_scale5); }
-    { ProfScope2 ps(prof, kKernColumnTile, st); launch_col_kind<kColExternal>(g, total, it.crit, st); }
-    {
-        ProfScope2 ps(prof, kKernColumnCombine, st);
-        if (it.crit == kCritEq3) k_col_finish<kCritEq3><<<dim3(cb), dim3(256), 0, st>>>(t, pl.n_strips);
-        else k_col_finish<kCritEq2><<<dim3(cb), dim3(256), 0, st>>>(t, pl.n_strips);
-    }
-    if (it.o.bf16 && it.scope != 1) {
-        ProfScope2 ps(prof, kKernFallbackCopy, st);
-        int64_t gy = (it.sh.rows + 3) / 4;
-        if (gy > 256) gy = 256;
-        k_col_fallback<<<dim3((unsigned)((it.sh.cols + 63) / 64), (unsigned)gy), dim3(256), 0, st>>>(t);
+// Per-channel columns: all operands of one criterion share five launches per kernel variant (amax, scales, quantize,
+// finish, fallback columns).  ws_of[k] is the workspace of operand idx[k] (column_workspace_bytes).
+hipError_t launch_channel_col_items(const BatchItem* items, const int* idx, int cnt, int crit, const uint32_t* const* gam_of,
+                                    char* const* ws_of, hipStream_t st, KProf* prof) {
+    for (int variant = 0; variant < 4; ++variant) {
+        const bool fake = (variant & 1) != 0, edge = (variant & 2) != 0;
+        GroupCol g; g.n = 0;
+        int64_t total = 0;
+        int comb = 0, copy = 0;
+        auto flush = [&]() {
+            if (g.n == 0) return;
+            { ProfScope2 ps(prof, kKernColumnTile, st); launch_col_kind<kColAmax>(g, total, kCritEq2, false, edge, st); }
+            { ProfScope2 ps(prof, kKernColumnCombine, st); k_col_scales<<<dim3((unsigned)comb), dim3(256), 0, st>>>(g); }
+            { ProfScope2 ps(prof, kKernColumnTile, st); launch_col_kind<kColExternal>(g, total, crit, fake, edge, st); }
+            {
+                ProfScope2 ps(prof, kKernColumnCombine, st);
+                if (crit == kCritEq3) k_col_finish<kCritEq3><<<dim3((unsigned)comb), dim3(256), 0, st>>>(g);
+                else k_col_finish<kCritEq2><<<dim3((unsigned)comb), dim3(256), 0, st>>>(g);
+            }
+            { ProfScope2 ps(prof, kKernFallbackCopy, st); k_col_fallback<<<dim3((unsigned)copy), dim3(256), 0, st>>>(g); }
+            g.n = 0; total = 0; comb = 0; copy = 0;
+        };
+        for (int k = 0; k < cnt; ++k) {
+            const BatchItem& it = items[idx[k]];
+            if ((it.o.fake != nullptr) != fake || col_needs_edge(it) != edge) continue;
+            const ColPlan pl = plan_columns(it.sh.rows, it.sh.cols);
+            const int64_t tiles_x = (it.sh.cols + 127) / 128;
+            const int64_t units = (int64_t)pl.n_strips * tiles_x;
+            if (units > 0x3FFFFFFF || tiles_x * kColCopyRowGroups > 0x3FFFFFFF) return hipErrorInvalidValue;
+            if (total + units > 0x7FFFFFFF || (int64_t)copy + tiles_x * kColCopyRowGroups > 0x7FFFFFFF) flush();
+            ColOp& t = g.op[g.n];
+            fill_col_op(t, it, gam_of[idx[k]]);
+            char* w = ws_of[k];
+            t.tiles_per_strip = pl.tiles_per_strip;
+            t.n_strips = pl.n_strips;
+            t.part_amax = reinterpret_cast<uint16_t*>(w + pl.off_amax);
+            t.part_err = reinterpret_cast<float*>(w + pl.off_err);
+            t.part_err5 = reinterpret_cast<float*>(w + pl.off_err5);
+            t.part_zero = reinterpret_cast<uint16_t*>(w + pl.off_zero);
+            t.col_scale = reinterpret_cast<float*>(w + pl.off_scale);
+            t.col_scale5 = reinterpret_cast<float*>(w + pl.off_scale5);
+            total += units;
+            comb += (int)((pl.cols_padded + 255) / 256);
+            copy += (int)(tiles_x * kColCopyRowGroups);
+            g.unit_end[g.n] = total; g.comb_end[g.n] = comb; g.copy_end[g.n] = copy;
+            if (++g.n == kMaxTeamGroup) flush();
+        }
+        flush();
     }
     return hipGetLastError();
 }
