@@ -453,80 +453,100 @@ __global__ __launch_bounds__(256) void k_tensor_finish(TensorPartials tp, int n_
     }
 }
 
-// Conditional BF16 fallback copy for the tensor-scope path: does nothing unless decision[0] == 1.
-__global__ __launch_bounds__(256) void k_fallback_copy_flat(const uint16_t* __restrict__ x, uint16_t* __restrict__ dst,
-                                                            int64_t n_chunks, const uint32_t* __restrict__ decision) {
-    if (decision[0] == 0u) return;
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    for (; c + 3 * stride < n_chunks; c += 4 * stride) {
-        u32x4 v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = load16(x + (c + u * stride) * 8);
-#pragma unroll
-        for (int u = 0; u < 4; ++u) store16(dst + (c + u * stride) * 8, v[u]);
-    }
-    for (; c < n_chunks; c += stride) store16(dst + c * 8, load16(x + c * 8));
-}
-__global__ __launch_bounds__(256) void k_fallback_copy_strided(const uint16_t* __restrict__ x, KShape sh, uint16_t* __restrict__ dst,
-                                                               int64_t ld_dst, const uint32_t* __restrict__ decision) {
-    if (decision[0] == 0u) return;
-    const int64_t cpr = sh.cols / 8;
-    for (int64_t r = blockIdx.x; r < sh.rows; r += gridDim.x)
-        for (int64_t c = threadIdx.x; c < cpr; c += 256) store16(dst + r * ld_dst + c * 8, load16(x + r * sh.ld + c * 8));
-}
-
 // ======================================================================================
 // Tensor-level decision over sub-tensor scaling (Section 3.1): the deferred block kernels wrote
 // err_sum / nnz per block; aggregate sum(err_sum) / sum(nnz), decide once, broadcast the mask.
 // ======================================================================================
-struct ScopePartials {
-    double* err;
-    double* err5;
-    unsigned long long* nnz;
+// Grouped: every operand with a tensor-level decision shares three launches -- partial sums per workgroup, decision
+// (re-derived by every workgroup of the operand from the partials in a fixed order, so all agree) with the mask
+// broadcast, and the conditional copy of the BF16 fallback.
+constexpr int kScopeBlocks = 256;       // partial records per operand
+constexpr int kMaxGroupScope = 16;
+struct ScopeOp {
+    const float* err_sum; const float* err5_sum; const uint32_t* nnz; uint8_t* mask;
+    int64_t n_part;
+    double* part_err; double* part_err5; unsigned long long* part_nnz;     // [kScopeBlocks] each
+    uint32_t* decision;                                                    // [1]
+    float th;
+    int32_t crit;
+    int32_t n_red;                                                         // workgroups of the reduce pass (<= kScopeBlocks)
+    // fallback copy
+    const uint16_t* x; uint16_t* bf16;
+    int64_t rows, cols, ld, ld_bf16;
 };
-template <int CRIT>
-__global__ __launch_bounds__(256) void k_scope_reduce(KOut o, int64_t n_part, ScopePartials sp) {
-    __shared__ double shd[256];
-    __shared__ unsigned long long shl[256];
+struct GroupScope {
+    int n;
+    int32_t red_end[kMaxGroupScope], copy_end[kMaxGroupScope];
+    ScopeOp op[kMaxGroupScope];
+};
+__global__ __launch_bounds__(256) void k_scope_reduce_group(GroupScope g) {
+    __shared__ double shd[4];
+    __shared__ unsigned long long shl[4];
+    const int op = group_find32(g.red_end, g.n, blockIdx.x);
+    const ScopeOp& t = g.op[op];
+    const int b = blockIdx.x - (op ? g.red_end[op - 1] : 0);
     double e = 0.0, e5 = 0.0;
     unsigned long long n = 0;
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x; p < n_part; p += stride) {
-        e += (double)o.err_sum[p];
-        n += o.nnz[p];
-        if constexpr (CRIT == kCritEq3) e5 += (double)o.err5_sum[p];
+    const int64_t stride = (int64_t)t.n_red * 256;
+    for (int64_t p = (int64_t)b * 256 + threadIdx.x; p < t.n_part; p += stride) {
+        e += (double)t.err_sum[p];
+        n += t.nnz[p];
+        if (t.crit == kCritEq3) e5 += (double)t.err5_sum[p];
     }
-    e = block_sum_256<double>(e, shd);
-    n = block_sum_256<unsigned long long>(n, shl);
-    if constexpr (CRIT == kCritEq3) e5 = block_sum_256<double>(e5, shd);
-    if (threadIdx.x == 0) { sp.err[blockIdx.x] = e; sp.nnz[blockIdx.x] = n; if constexpr (CRIT == kCritEq3) sp.err5[blockIdx.x] = e5; }
+    e = block_sum_shfl<double>(e, shd);
+    n = block_sum_shfl<unsigned long long>(n, shl);
+    e5 = block_sum_shfl<double>(e5, shd);
+    if (threadIdx.x == 0) { t.part_err[b] = e; t.part_nnz[b] = n; t.part_err5[b] = e5; }
 }
-template <int CRIT>
-__global__ __launch_bounds__(256) void k_scope_decide(ScopePartials sp, int n_blocks, float th, uint32_t* __restrict__ decision) {
-    __shared__ double shd[256];
-    __shared__ unsigned long long shl[256];
+// Same decision in every workgroup that calls it (fixed summation order over the operand's partial records).
+__device__ __forceinline__ uint32_t scope_decision(const ScopeOp& t, double* shd, unsigned long long* shl) {
     double e = 0.0, e5 = 0.0;
     unsigned long long n = 0;
-    for (int i = threadIdx.x; i < n_blocks; i += 256) {
-        e += sp.err[i];
-        n += sp.nnz[i];
-        if constexpr (CRIT == kCritEq3) e5 += sp.err5[i];
-    }
-    e = block_sum_256<double>(e, shd);
-    n = block_sum_256<unsigned long long>(n, shl);
-    if constexpr (CRIT == kCritEq3) e5 = block_sum_256<double>(e5, shd);
-    if (threadIdx.x == 0) {
-        uint32_t mask;
-        if constexpr (CRIT == kCritEq3) mask = (e < e5) ? 0u : 1u;
-        else mask = ((n ? e / (double)n : 0.0) < (double)th) ? 0u : 1u;
-        decision[0] = mask;
-    }
+    if ((int)threadIdx.x < t.n_red) { e = t.part_err[threadIdx.x]; n = t.part_nnz[threadIdx.x]; e5 = t.part_err5[threadIdx.x]; }
+    e = block_sum_shfl<double>(e, shd);
+    n = block_sum_shfl<unsigned long long>(n, shl);
+    e5 = block_sum_shfl<double>(e5, shd);
+    if (t.crit == kCritEq3) return (e < e5) ? 0u : 1u;
+    return ((n ? e / (double)n : 0.0) < (double)t.th) ? 0u : 1u;
 }
-__global__ __launch_bounds__(256) void k_scope_fill_mask(uint8_t* __restrict__ mask, int64_t n_part, const uint32_t* __restrict__ decision) {
-    const uint8_t m = (uint8_t)decision[0];
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x; p < n_part; p += stride) mask[p] = m;
+__global__ __launch_bounds__(256) void k_scope_decide_group(GroupScope g) {
+    __shared__ double shd[4];
+    __shared__ unsigned long long shl[4];
+    const int op = group_find32(g.red_end, g.n, blockIdx.x);
+    const ScopeOp& t = g.op[op];
+    const int b = blockIdx.x - (op ? g.red_end[op - 1] : 0);
+    const uint32_t m = scope_decision(t, shd, shl);
+    if (b == 0 && threadIdx.x == 0) t.decision[0] = m;
+    const int64_t stride = (int64_t)t.n_red * 256;
+    for (int64_t p = (int64_t)b * 256 + threadIdx.x; p < t.n_part; p += stride) t.mask[p] = (uint8_t)m;
+}
+__global__ __launch_bounds__(256) void k_scope_copy_group(GroupScope g) {
+    const int op = group_find32(g.copy_end, g.n, blockIdx.x);
+    const ScopeOp& t = g.op[op];
+    if (t.bf16 == nullptr || t.decision[0] == 0u) return;
+    const int b = blockIdx.x - (op ? g.copy_end[op - 1] : 0);
+    const int nb = g.copy_end[op] - (op ? g.copy_end[op - 1] : 0);
+    if (t.ld == t.cols && t.ld_bf16 == t.cols) {
+        // tiles of 1024 consecutive chunks (16 KB): four 16-byte loads in flight per lane
+        const int64_t n_chunks = t.rows * t.cols / 8, n_tiles = (n_chunks + 1023) / 1024;
+        for (int64_t ct = b; ct < n_tiles; ct += nb) {
+            const int64_t c0 = ct * 1024 + threadIdx.x;
+            if (c0 + 3 * 256 < n_chunks) {
+                u32x4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) v[u] = load16(t.x + (c0 + u * 256) * 8);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) store16(t.bf16 + (c0 + u * 256) * 8, v[u]);
+            } else {
+                for (int u = 0; u < 4; ++u)
+                    if (c0 + u * 256 < n_chunks) store16(t.bf16 + (c0 + u * 256) * 8, load16(t.x + (c0 + u * 256) * 8));
+            }
+        }
+    } else {
+        const int64_t cpr = t.cols / 8;
+        for (int64_t r = b; r < t.rows; r += nb)
+            for (int64_t c = threadIdx.x; c < cpr; c += 256) store16(t.bf16 + r * t.ld_bf16 + c * 8, load16(t.x + r * t.ld + c * 8));
+    }
 }
 
 // ======================================================================================
@@ -1216,7 +1236,6 @@ TensorPlan plan_tensor(int64_t, int64_t) {
     return pl;
 }
 
-constexpr int kScopeBlocks = 256;
 size_t scope_workspace_bytes(int64_t) { return align16(3 * sizeof(double) * kScopeBlocks + 16); }
 
 static bool is_flat(const KShape& sh, const KOut& o) {
@@ -1287,37 +1306,6 @@ static hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut&
     return hipGetLastError();
 }
 
-static hipError_t launch_scope_finalize(const uint16_t* x, const KShape& sh, const KOut& o, int64_t n_part, int crit, float th,
-                                 void* ws, hipStream_t st, KProf* prof) {
-    char* w = static_cast<char*>(ws);
-    ScopePartials sp{reinterpret_cast<double*>(w), reinterpret_cast<double*>(w) + kScopeBlocks,
-                     reinterpret_cast<unsigned long long*>(w) + 2 * kScopeBlocks};
-    uint32_t* decision = reinterpret_cast<uint32_t*>(w + 3 * sizeof(double) * kScopeBlocks);
-    int64_t want = (n_part + 1023) / 1024;
-    const int nb = (int)(want < 1 ? 1 : (want > kScopeBlocks ? kScopeBlocks : want));
-    {
-        ProfScope ps(prof, kKernScopeReduce, st);
-        if (crit == kCritEq3) k_scope_reduce<kCritEq3><<<dim3(nb), dim3(256), 0, st>>>(o, n_part, sp);
-        else k_scope_reduce<kCritEq2><<<dim3(nb), dim3(256), 0, st>>>(o, n_part, sp);
-    }
-    {
-        ProfScope ps(prof, kKernScopeDecide, st);
-        if (crit == kCritEq3) k_scope_decide<kCritEq3><<<dim3(1), dim3(256), 0, st>>>(sp, nb, th, decision);
-        else k_scope_decide<kCritEq2><<<dim3(1), dim3(256), 0, st>>>(sp, nb, th, decision);
-    }
-    {
-        ProfScope ps(prof, kKernScopeFillMask, st);
-        k_scope_fill_mask<<<dim3(nb), dim3(256), 0, st>>>(o.mask, n_part, decision);
-    }
-    if (o.bf16) {
-        ProfScope ps(prof, kKernFallbackCopy, st);
-        const bool flat = sh.ld == sh.cols && o.ld_bf16 == sh.cols;
-        if (flat) k_fallback_copy_flat<<<dim3(2048), dim3(256), 0, st>>>(x, o.bf16, sh.rows * sh.cols / 8, decision);
-        else k_fallback_copy_strided<<<dim3((unsigned)(sh.rows < 4096 ? sh.rows : 4096)), dim3(256), 0, st>>>(x, sh, o.bf16, o.ld_bf16, decision);
-    }
-    return hipGetLastError();
-}
-
 // ---- batches ---------------------------------------------------------------------------------
 namespace {
 constexpr int kStatsMaxWg = 256;
@@ -1378,7 +1366,7 @@ size_t batch_workspace_bytes(const BatchItem* items, int n) {
 
 hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws, size_t ws_bytes, hipStream_t st, KProf* prof) {
     static_assert(sizeof(GroupSub) <= 3800 && sizeof(GroupTensor) <= 3800 && sizeof(GroupStats) <= 3800 &&
-                  sizeof(GroupGam) <= 3800, "kernel-argument segment is 4 KB");
+                  sizeof(GroupGam) <= 3800 && sizeof(GroupScope) <= 3800, "kernel-argument segment is 4 KB");
     static_assert(sizeof(StatsRec) == 128, "StatsRec layout");
     char* wsp = static_cast<char*>(ws);
     size_t ws_off = 0;
@@ -1590,10 +1578,40 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
         }
     }
     // ---- tensor-level decision (Section 3.1) over the per-block sums the block kernels left behind
-    for (int i = 0; i < n && err == hipSuccess; ++i) {
-        const BatchItem& it = items[i];
-        if (it.gran == kGranTensor || it.scope != 1) continue;
-        err = launch_scope_finalize(it.x, it.sh, it.o, item_parts(it), it.crit, it.th, carve(scope_workspace_bytes(item_parts(it))), st, prof);
+    {
+        GroupScope g; g.n = 0;
+        int red = 0, copy = 0;
+        auto flush = [&]() {
+            if (g.n == 0) return;
+            { ProfScope ps(prof, kKernScopeReduce, st); k_scope_reduce_group<<<dim3(red), dim3(256), 0, st>>>(g); }
+            { ProfScope ps(prof, kKernScopeDecide, st); k_scope_decide_group<<<dim3(red), dim3(256), 0, st>>>(g); }
+            { ProfScope ps(prof, kKernFallbackCopy, st); k_scope_copy_group<<<dim3(copy), dim3(256), 0, st>>>(g); }
+            g.n = 0; red = 0; copy = 0;
+        };
+        int64_t total_elems = 0;
+        for (int i = 0; i < n; ++i)
+            if (items[i].gran != kGranTensor && items[i].scope == 1) total_elems += items[i].sh.rows * items[i].sh.cols;
+        for (int i = 0; i < n; ++i) {
+            const BatchItem& it = items[i];
+            if (it.gran == kGranTensor || it.scope != 1) continue;
+            ScopeOp& t = g.op[g.n];
+            char* w = carve(scope_workspace_bytes(0));
+            t.err_sum = it.o.err_sum; t.err5_sum = it.o.err5_sum; t.nnz = it.o.nnz; t.mask = it.o.mask;
+            t.n_part = item_parts(it);
+            t.part_err = reinterpret_cast<double*>(w); t.part_err5 = t.part_err + kScopeBlocks;
+            t.part_nnz = reinterpret_cast<unsigned long long*>(w) + 2 * kScopeBlocks;
+            t.decision = reinterpret_cast<uint32_t*>(w + 3 * sizeof(double) * kScopeBlocks);
+            t.th = it.th; t.crit = it.crit;
+            int64_t want = (t.n_part + 1023) / 1024;
+            t.n_red = (int)(want < 1 ? 1 : (want > kScopeBlocks ? kScopeBlocks : want));
+            t.x = it.x; t.bf16 = it.o.bf16;
+            t.rows = it.sh.rows; t.cols = it.sh.cols; t.ld = it.sh.ld; t.ld_bf16 = it.o.ld_bf16;
+            red += t.n_red;
+            copy += it.o.bf16 ? share(it.sh.rows * it.sh.cols, total_elems, 4096, 4096) : 1;
+            g.red_end[g.n] = red; g.copy_end[g.n] = copy;
+            if (++g.n == kMaxGroupScope) flush();
+        }
+        flush();
     }
     // ---- statistics of the operands with sub-tensor blocks
     {

@@ -322,7 +322,7 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
             const uint32_t col_abits = col_ok ? __float_as_uint(o.amax[col + k]) >> 16 : 0u;
             f = f && col_abits < fast_amax_limit(mode);
         }
-        strip_fast = __syncthreads_and(f ? 1 : 0) != 0;
+        strip_fast = f;      // per lane: the careful path has no cross-lane step, so no barrier is needed before the loads
     }
     for (int tt = 0; tt < t.tiles_per_strip; ++tt) {
         const int64_t r0 = (strip * t.tiles_per_strip + tt) * 128;
@@ -739,7 +739,7 @@ struct ColPlan {
 ColPlan plan_columns(int64_t rows, int64_t cols) {
     ColPlan pl;
     const int64_t tiles_x = (cols + 127) / 128, tiles_y = (rows + 127) / 128;
-    int64_t per = (tiles_x * tiles_y + 4095) / 4096;      // keep at least ~4096 workgroups when the operand is large
+    int64_t per = (tiles_x * tiles_y + 1023) / 1024;      // ~1024 workgroups per large operand: the per-workgroup set-up is amortised over several tiles
     if (per < 1) per = 1;
     if (per > 16) per = 16;                               // 16-bit zero counters: 16 tiles x 128 rows
     pl.tiles_per_strip = (int32_t)per;
