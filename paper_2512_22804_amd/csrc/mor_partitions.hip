@@ -163,7 +163,7 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
                 const u32x2 codes = quant8_fast_deq<E5, FAKE>(raw[i], sc_, s_inv, e0, e1, deq);
                 if constexpr (BUF) {
                     const bool put = emit && is_valid(i);
-                    if constexpr (FAKE) buf_store16(rf, put ? offf : kBufOutside, i * stepf, deq);
+                    if constexpr (FAKE) buf_store16(rf, put ? offf + i * stepf : kBufOutside, deq);
                     else buf_store8(r8, put ? off8 : kBufOutside, i * step8, codes);
                 } else if (emit) {
                     if constexpr (FAKE) store16(dstf + i * dstf_step, deq);
@@ -221,7 +221,7 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
         const uint32_t offb = (uint32_t)((trow * o.ld_bf16 + tcol) * 2), stepb = (uint32_t)(dbf_step * 2);
 #pragma unroll
         for (int i = 0; i < kChunks; ++i) {
-            if constexpr (BUF) buf_store16(rb, is_valid(i) ? offb : kBufOutside, i * stepb, raw[i]);
+            if constexpr (BUF) buf_store16(rb, is_valid(i) ? offb + i * stepb : kBufOutside, raw[i]);
             else store16(dbf + i * dbf_step, raw[i]);
         }
     }
@@ -396,7 +396,7 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
                 u32x4 deq;
                 const u32x2 codes = quant8_cols<false, FAKE>(raw[i], s, s_inv, err, deq);
                 if constexpr (EDGE) {
-                    if constexpr (FAKE) buf_store16(rf, is_valid(i) ? offf : kBufOutside, i * stepf, deq);
+                    if constexpr (FAKE) buf_store16(rf, is_valid(i) ? offf + i * stepf : kBufOutside, deq);
                     else buf_store8(r8, is_valid(i) ? off8 : kBufOutside, i * step8, codes);
                 } else {
                     if constexpr (FAKE) store16(dstf + (int64_t)i * 16 * o.ld_fake, deq);
@@ -482,7 +482,7 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
                     const uint32_t offb = (uint32_t)(((tid >> 4) * o.ld_bf16 + cg * 8) * 2), stepb = (uint32_t)(16 * o.ld_bf16 * 2);
 #pragma unroll
                     for (int i = 0; i < kChunks; ++i) {
-                        if constexpr (EDGE) buf_store16(rb, is_valid(i) ? offb : kBufOutside, i * stepb, raw[i]);
+                        if constexpr (EDGE) buf_store16(rb, is_valid(i) ? offb + i * stepb : kBufOutside, raw[i]);
                         else store16(dbf + (int64_t)i * 16 * o.ld_bf16, raw[i]);
                     }
                 } else if (mk8) {                                      // some of them: element by element

@@ -112,6 +112,23 @@ def test_channel_col_many_strips(P):
     P.compare(xb, "channel_col", scope="tensor", crit="e4m3_vs_e5m2", label="col-strips-tensor")
 
 
+@pytest.mark.parametrize("gran", NEW_GRANS)
+def test_new_partitions_full_benchmark_sizes(P, gran):
+    """The weight (14336 x 4096) and gradient (8192 x 14336) operands of the benchmark configurations at full size."""
+    (_, w, _), _ = W.cfg3()
+    r = P.compare(w, gran, threshold=TH, label="cfg3-full")
+    print("cfg3:", gran, {k: v for k, v in r.items() if k not in ("gpu", "oracle", "params")})
+    (_, g, _), _ = W.cfg4()
+    r = P.compare(g, gran, threshold=TH, label="cfg4-full")
+    print("cfg4:", gran, {k: v for k, v in r.items() if k not in ("gpu", "oracle", "params")})
+    if gran in ("block64", "channel_row"):
+        P.compare(g, gran, crit="e4m3_vs_e5m2", formats=THREE, label="cfg4-full-three-way")
+    # fake quantization at full size (at this size a 16-byte store whose data registers were reused too early showed up
+    # as rare corrupted dwords; small operands never showed it)
+    P.compare_fake(w, gran, scope="tensor", scaling="gam", threshold=TH, label="cfg3-full-fake-gam-tensor-level")
+    P.compare_fake(g, gran, threshold=TH, label="cfg4-full-fake")
+
+
 # ------------------------------------------------------------------ ragged edges
 
 @pytest.mark.parametrize("gran", ["sub1x128", "block128", "block64", "sub128x1", "channel_col", "channel_row", "tensor"])
@@ -225,6 +242,14 @@ def test_fake_quantize_all_patterns_and_strides(P, gran):
     P.compare_fake(small.reshape(256, 256), gran, label="fake-small-patterns")
     xb = W.gradient(256, 640, 99, tiny_half=True)
     P.compare_fake(xb, gran, cols=512, label="fake-strided")
+
+
+@pytest.mark.parametrize("gran", ["tensor", "sub1x128", "block128"])
+def test_fake_quantize_full_benchmark_sizes(P, gran):
+    (_, w, _), _ = W.cfg3()
+    P.compare_fake(w, gran, threshold=TH, label="cfg3-full-fake")
+    (_, g, _), _ = W.cfg4()
+    P.compare_fake(g, gran, threshold=TH, label="cfg4-full-fake")
 
 
 def test_fake_quantize_per_tensor_fallback_proven_and_not(P):
