@@ -57,7 +57,7 @@ typedef enum {
     MOR_GRAN_SUB_1x128 = 1,     /* sub-channel blocks of 1 x 128 along the columns (sub-rows) */
     MOR_GRAN_BLOCK_128x128 = 2, /* 2-D blocks of 128 x 128 */
     MOR_GRAN_CHANNEL_ROW = 3,   /* per-channel: every row is one block (first GEMM operand, Section 4.1.1);
-                                   cols <= 16384 */
+                                   cols <= 65536 */
     MOR_GRAN_CHANNEL_COL = 4,   /* per-channel: every column is one block (second GEMM operand) */
     MOR_GRAN_SUB_128x1 = 5,     /* sub-channel blocks of 128 x 1 along the rows (sub-columns: the transposed
                                    operands of the backward GEMMs, Section 4) */

@@ -14,7 +14,7 @@ mor_status check_shape(int32_t gran, int64_t rows, int64_t cols, bool ragged) {
     if (cols % 8) return MOR_ERR_SHAPE;                            // 16-byte rows
     const mor::StatsGeom g = mor::make_geom(gran, rows, cols);
     if (!ragged && !g.uniform) return MOR_ERR_SHAPE;
-    if (gran == MOR_GRAN_CHANNEL_ROW && cols > 16384) return MOR_ERR_SHAPE;
+    if (gran == MOR_GRAN_CHANNEL_ROW && cols > 65536) return MOR_ERR_SHAPE;   // a row is held in the registers of one workgroup
     return MOR_OK;
 }
 mor_status check_common(const mor_params* p) {

@@ -23,7 +23,8 @@ enum {
     kTeamWg128 = 0,     // 128 x 128 block, one workgroup
     kTeamWave64 = 1,    // 64 x 64 block, one wave; a workgroup takes the four blocks of a 128 x 128 tile
     kTeamWaveRow = 2,   // one row of at most 4096 elements, one wave; four rows per workgroup
-    kTeamWgRow = 3      // one row of at most 16384 elements, one workgroup
+    kTeamWgRow = 3,     // one row of at most 16384 elements, one workgroup of 256
+    kTeamBigRow = 4     // one row of at most 65536 elements, one workgroup of 1024
 };
 constexpr int kMaxTeamGroup = 12;
 struct TeamOp {
@@ -41,11 +42,13 @@ struct GroupTeam {
     TeamOp op[kMaxTeamGroup];
 };
 struct TeamShared {
-    uint32_t u[4];
-    float f[8];
+    uint32_t u[16];
+    float f[32];
 };
 
-template <int TEAM> __device__ __forceinline__ constexpr bool team_is_wg() { return TEAM == kTeamWg128 || TEAM == kTeamWgRow; }
+template <int TEAM> __device__ __forceinline__ constexpr bool team_is_wg() { return TEAM == kTeamWg128 || TEAM == kTeamWgRow || TEAM == kTeamBigRow; }
+template <int TEAM> __device__ __forceinline__ constexpr int team_threads() { return TEAM == kTeamBigRow ? 1024 : 256; }
+template <int TEAM> __device__ __forceinline__ constexpr int team_waves() { return team_threads<TEAM>() / 64; }
 
 // All-reduce over the team.  Workgroup teams combine the four wave results through LDS (every thread
 // of the workgroup must call); wave teams stay inside the wave.
@@ -55,7 +58,9 @@ __device__ __forceinline__ uint32_t team_allmax(uint32_t v, TeamShared& sh) {
     if constexpr (team_is_wg<TEAM>()) {
         if ((threadIdx.x & 63) == 0) sh.u[threadIdx.x >> 6] = v;
         __syncthreads();
-        v = max(max(sh.u[0], sh.u[1]), max(sh.u[2], sh.u[3]));
+        v = sh.u[0];
+#pragma unroll
+        for (int k = 1; k < team_waves<TEAM>(); ++k) v = max(v, sh.u[k]);
         __syncthreads();
     }
     return v;
@@ -66,12 +71,17 @@ __device__ __forceinline__ void team_allsum3(float& a, float& b, uint32_t& z, Te
     b = wave_allsum_f32(b);
     z = wave_allsum_u32(z);
     if constexpr (team_is_wg<TEAM>()) {
+        constexpr int NW = team_waves<TEAM>();
         const int w = threadIdx.x >> 6;
-        if ((threadIdx.x & 63) == 0) { sh.f[w] = a; sh.f[4 + w] = b; sh.u[w] = z; }
+        if ((threadIdx.x & 63) == 0) { sh.f[w] = a; sh.f[NW + w] = b; sh.u[w] = z; }
         __syncthreads();
-        a = (sh.f[0] + sh.f[1]) + (sh.f[2] + sh.f[3]);
-        b = (sh.f[4] + sh.f[5]) + (sh.f[6] + sh.f[7]);
-        z = (sh.u[0] + sh.u[1]) + (sh.u[2] + sh.u[3]);
+        a = 0.0f; b = 0.0f; z = 0u;
+#pragma unroll
+        for (int k = 0; k < NW; k += 4) {       // fixed order: deterministic
+            a += (sh.f[k] + sh.f[k + 1]) + (sh.f[k + 2] + sh.f[k + 3]);
+            b += (sh.f[NW + k] + sh.f[NW + k + 1]) + (sh.f[NW + k + 2] + sh.f[NW + k + 3]);
+            z += (sh.u[k] + sh.u[k + 1]) + (sh.u[k + 2] + sh.u[k + 3]);
+        }
         __syncthreads();
     }
 }
@@ -109,7 +119,7 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
         leader = lane == 0;
     } else {
         p = unit; r0 = p; c0 = 0;
-        trow = 0; tcol = tid * 8; rstep = 0; cstep = 256 * 8;
+        trow = 0; tcol = tid * 8; rstep = 0; cstep = team_threads<TEAM>() * 8;
         h = 1; wd = (int)t.cols;
         leader = tid == 0;
     }
@@ -118,7 +128,7 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
     const int64_t src_step = (int64_t)rstep * t.ld + cstep;
     // Whole-block operands of the block teams use plain pointers; everything else (ragged edges, rows) goes through
     // bounds-checked buffer accesses relative to the block origin, where a lane outside the block costs no branch.
-    constexpr bool BUF = EDGE || TEAM == kTeamWaveRow || TEAM == kTeamWgRow;
+    constexpr bool BUF = EDGE || TEAM == kTeamWaveRow || TEAM == kTeamWgRow || TEAM == kTeamBigRow;
     auto is_valid = [&](int i) -> bool {
         if constexpr (BUF) return (trow + i * rstep < h) && (tcol + i * cstep < wd);
         else return true;
@@ -185,7 +195,7 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
     if constexpr (CRIT == kCritEq3) err5 = quantize(std::true_type{}, s5, false);
     uint32_t zeros = fold_add16(sc.zero2);
     team_allsum3<TEAM>(err, err5, zeros, sh);
-    constexpr uint32_t kTeamElems = (team_is_wg<TEAM>() ? 256u : 64u) * kChunks * 8u;
+    constexpr uint32_t kTeamElems = (team_is_wg<TEAM>() ? (uint32_t)team_threads<TEAM>() : 64u) * kChunks * 8u;
     const uint32_t nnz = kTeamElems - zeros;
     if (abits >= kInfBits) { err = __builtin_inff(); err5 = __builtin_inff(); }
     const bool defer = t.defer != 0;
@@ -228,7 +238,7 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
 }
 
 template <int TEAM, int CRIT, bool FAKE, bool EDGE>
-__global__ __launch_bounds__(256) void k_team_group(GroupTeam g) {
+__global__ __launch_bounds__(TEAM == kTeamBigRow ? 1024 : 256) void k_team_group(GroupTeam g) {
     __shared__ TeamShared sh;
     const int op = group_find(g.unit_end, g.n, blockIdx.x);
     const TeamOp& t = g.op[op];
@@ -655,7 +665,7 @@ size_t align16p(size_t v) { return (v + 15) & ~(size_t)15; }
 
 template <int TEAM, bool FAKE, bool EDGE>
 void launch_team_crit(const GroupTeam& g, int64_t total, int crit, hipStream_t st) {
-    const dim3 grid((unsigned)total), block(256);
+    const dim3 grid((unsigned)total), block(TEAM == kTeamBigRow ? 1024 : 256);
     if (crit == kCritEq3) k_team_group<TEAM, kCritEq3, FAKE, EDGE><<<grid, block, 0, st>>>(g);
     else k_team_group<TEAM, kCritEq2, FAKE, EDGE><<<grid, block, 0, st>>>(g);
 }
@@ -669,8 +679,7 @@ bool team_needs_edge(const BatchItem& it, int kind) {
     switch (kind) {
     case kTeamWg128: return it.sh.rows % 128 != 0 || it.sh.cols % 128 != 0;
     case kTeamWave64: return it.sh.rows % 64 != 0 || it.sh.cols % 64 != 0;
-    case kTeamWaveRow: return it.sh.cols % 512 != 0;
-    default: return it.sh.cols % 2048 != 0;
+    default: return false;      // row teams always use the bounds-checked accesses
     }
 }
 }  // namespace
@@ -679,7 +688,7 @@ int team_kind_of(const BatchItem& it) {
     switch (it.gran) {
     case kGranBlock: return kTeamWg128;
     case kGranBlock64: return kTeamWave64;
-    case kGranRow: return it.sh.cols <= 4096 ? kTeamWaveRow : kTeamWgRow;
+    case kGranRow: return it.sh.cols <= 4096 ? kTeamWaveRow : (it.sh.cols <= 16384 ? kTeamWgRow : kTeamBigRow);
     default: return -1;
     }
 }
@@ -699,7 +708,8 @@ hipError_t launch_team_items(const BatchItem* items, const int* idx, int cnt, in
         case kTeamWg128: launch_team_kind<kTeamWg128>(g, total, crit, fake, edge, st); break;
         case kTeamWave64: launch_team_kind<kTeamWave64>(g, total, crit, fake, edge, st); break;
         case kTeamWaveRow: launch_team_kind<kTeamWaveRow>(g, total, crit, fake, edge, st); break;
-        default: launch_team_kind<kTeamWgRow>(g, total, crit, fake, edge, st); break;
+        case kTeamWgRow: launch_team_kind<kTeamWgRow>(g, total, crit, fake, edge, st); break;
+        default: launch_team_kind<kTeamBigRow>(g, total, crit, fake, edge, st); break;
         }
         g.n = 0; total = 0;
     };

@@ -50,7 +50,8 @@ def test_num_partitions(B):
     assert B.mor_num_partitions("tensor", 0, 128) == -1
     assert B.mor_num_partitions(9, 128, 128) == -1
     assert B.mor_num_partitions("channel_row", 8192, 4096) == 8192
-    assert B.mor_num_partitions("channel_row", 8, 16392) == -1               # rows longer than 16384 elements
+    assert B.mor_num_partitions("channel_row", 8, 65536) == 8
+    assert B.mor_num_partitions("channel_row", 8, 65544) == -1               # rows longer than 65536 elements
     assert B.mor_num_partitions("channel_col", 8192, 4096) == 4096
     assert B.mor_num_partitions("sub128x1", 8192, 4096) == 64 * 4096
     assert B.mor_num_partitions("sub128x1", 100, 4096) == -1

@@ -87,12 +87,13 @@ def test_new_partitions_padded_leading_dimension(P, gran):
     assert torch.equal(r["gpu"].fp8, dense["gpu"].fp8) and torch.equal(r["gpu"].mask, dense["gpu"].mask)
 
 
-@pytest.mark.parametrize("cols", [8, 128, 1000, 4096, 4104, 14336, 16384])
+@pytest.mark.parametrize("cols", [8, 128, 1000, 4096, 4104, 14336, 16384, 16392, 28672, 65536])
 def test_channel_row_widths(P, cols):
-    """Rows handled by one wave (up to 4096 elements) and by one workgroup (up to 16384)."""
+    """Rows handled by one wave (up to 4096 elements), by a workgroup of 256 (up to 16384) and of 1024 (up to 65536)."""
     xb = W.activation(37, cols, cols)
     P.compare(xb, "channel_row", threshold=TH, label="row-width")
     P.compare(xb, "channel_row", crit="e4m3_vs_e5m2", formats=THREE, label="row-width-three")
+    P.compare_fake(xb, "channel_row", scope="tensor", scaling="gam", label="row-width-fake")
 
 
 def test_channel_col_many_strips(P):
