@@ -80,3 +80,55 @@ def test_status_strings(B):
     seen = {lib.mor_status_string(i).decode() for i in range(7)}
     assert len(seen) == 7 and lib.mor_status_string(0).decode() == "ok"
     assert "unknown" in lib.mor_status_string(99).decode()
+
+
+def test_argument_validation_without_a_gpu(B):
+    """Argument errors are reported before anything is launched, so they can be checked on the host: fake but
+    well-aligned device addresses are enough (they are never dereferenced)."""
+    lib = B.load()
+    base = 0x7F0000000000
+
+    def call(params, x=base, **over):
+        o = B.MorOutputs(fp8=base + (1 << 30), ld_fp8=params.cols, bf16=base + (2 << 30), ld_bf16=params.cols,
+                         scale=base + (3 << 30), amax=base + (3 << 30) + 4096, err_sum=base + (3 << 30) + 8192,
+                         nnz=base + (3 << 30) + 12288, mask=base + (3 << 30) + 16384, err5_sum=None,
+                         scale_e8m0=None, group_mantissa=None, amin=None)
+        for k, v in over.items():
+            setattr(o, k, v)
+        return lib.mor_analyze_quantize(C.byref(params), C.c_void_p(x), C.byref(o), None, 0, None)
+
+    assert call(B.make_params(128, 200, "sub1x128")) == 2                     # cols not a whole number of blocks
+    assert call(B.make_params(128, 200, "sub1x128", ragged=True), fp8=base + 4) == 3   # misaligned payload
+    assert call(B.make_params(100, 256, "block64")) == 2
+    assert call(B.make_params(128, 256, "channel_row", ld=128)) == 2          # ld < cols
+    assert call(B.make_params(128, 256, "sub128x1", ld=260)) == 3             # ld % 8
+    assert call(B.make_params(128, 256, 7)) == 4
+    assert call(B.make_params(128, 256, "sub1x128", formats=B.MOR_FMT_E4M3 | B.MOR_FMT_E5M2)) == 4
+    assert call(B.make_params(128, 256, "tensor", crit="e4m3_vs_e5m2", formats="e4m3|e5m2|bf16"), err5_sum=base + (4 << 30)) == 4
+    assert call(B.make_params(128, 256, "channel_col", crit="e4m3_vs_e5m2", formats="e4m3|e5m2|bf16"), err5_sum=base + (4 << 30)) == 4
+    assert call(B.make_params(128, 256, "sub1x128", scope="tensor", crit="e4m3_vs_e5m2", formats="e4m3|e5m2|bf16"),
+                err5_sum=base + (4 << 30)) == 4
+    assert call(B.make_params(128, 256, "sub1x128", scaling=3)) == 4
+    assert call(B.make_params(128, 256, "sub1x128", crit=5)) == 4
+    assert call(B.make_params(128, 256, "sub1x128"), x=base + 2) == 3
+    assert call(B.make_params(128, 256, "sub1x128"), mask=None) == 1
+    assert call(B.make_params(128, 256, "sub1x128", crit="e4m3_vs_e5m2")) == 1            # err5_sum missing
+    assert call(B.make_params(128, 256, "tensor")) == 5                                   # workspace missing
+    assert call(B.make_params(128, 256, "channel_col")) == 5
+    assert call(B.make_params(128, 256, "block128", scope="tensor")) == 5
+    p = B.make_params(128, 256, "sub1x128"); p.flags = 8
+    assert call(p) == 4
+    p = B.make_params(128, 256, "sub1x128"); p.reserved = 1
+    assert call(p) == 4
+    # fake quantization: y must not alias x, needs 16-byte alignment and ld_y >= cols
+    pr = B.make_params(128, 256, "block128")
+    o = B.MorOutputs(scale=base, amax=base + 4096, err_sum=base + 8192, nnz=base + 12288, mask=base + 16384)
+    fq = lambda x, y, ld: lib.mor_fake_quantize(C.byref(pr), C.c_void_p(x), C.c_void_p(y), ld, C.byref(o), None, 0, None)
+    assert fq(base + (1 << 30), base + (1 << 30), 256) == 4
+    assert fq(base + (1 << 30), base + (2 << 30) + 8, 256) == 3
+    assert fq(base + (1 << 30), base + (2 << 30), 128) == 2
+    assert fq(base + (1 << 30), None, 256) == 1
+    # histogram: argument checks only
+    assert lib.mor_histogram_update(None, C.c_void_p(base), 0, 6000, None) == 1
+    assert lib.mor_histogram_update(C.c_void_p(base), C.c_void_p(base + 1024), -1, 6000, None) == 2
+    assert lib.mor_histogram_update(C.c_void_p(base + 2), C.c_void_p(base + 1024), 0, 6000, None) == 3
