@@ -170,7 +170,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-operand", action="store_true", help="one analyze + one stats call per operand instead of one batch call")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run three plain 256 MiB device-to-device copies (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+                    help="kept for the profiling commands: the three plain 256 MiB device-to-device copies (reference for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE) are always run")
     ap.add_argument("--no-variants", action="store_true", help="skip the timing of the further rows (GAM, three-way, partitions, fake quantization)")
     ap.add_argument("--cpu-passes", type=int, default=0, help="oracle passes over the sample (0: repeat until 10 s of oracle time)")
     ap.add_argument("--cpu-sample-div", type=int, default=1, help="oracle is timed on the first rows/N rows of every operand")
@@ -231,13 +232,30 @@ def main() -> int:
     value = 2.0 * n_total / (elapsed / args.steps) / 1e9
     log(f"[bench] {args.steps} steps, {ms_per_step:.3f} ms/step, {value:.1f} GB/s of BF16 input")
 
-    if args.calibrate_copy:
-        src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+    # the same steps once more, each bracketed by its own pair of events: median and minimum step time
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for a, b in evs:
+        a.record(); step(); b.record()
+    torch.cuda.synchronize()
+    per_step = sorted(a.elapsed_time(b) for a, b in evs)
+    ms_median, ms_min = per_step[len(per_step) // 2], per_step[0]
+    log(f"[bench] per-step GPU time: median {ms_median:.3f} ms, min {ms_min:.3f} ms")
+
+    # plain device-to-device copy of 256 MiB in the same run: the practical ceiling of a streaming kernel on this machine
+    # (with --calibrate-copy these copies also calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters)
+    src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    c0 = torch.cuda.Event(enable_timing=True); c1 = torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(3):
+        dst.copy_(src)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2.0 * 3 * (256 << 20) / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    log(f"[bench] plain 256 MiB device copy: {copy_gbs:.1f} GB/s (read + write)")
+    del src, dst
 
     # selection result (after the timed region).  The batch call also reports, per operand, whether the quantize pass
     # wrote the fallback itself; in --per-operand mode one untimed batch call supplies that flag.
@@ -337,12 +355,22 @@ def main() -> int:
         cpu_baseline = {"value": round(2.0 * n_cpu / t_cpu / 1e9, 4), "unit": "GB/s", "cores": O.threads(), "kind": "oracle",
                         "sample": f"{passes} passes over the first 1/{div} of the rows of each of the 12 operands "
                                   f"({n_cpu} elements in all, {t_cpu:.1f} s of oracle time)"}
+        # one thread, on the activation operand alone (the first operand of the sweep), for scale
+        O.set_threads(1)
+        xs = np.ascontiguousarray(ops[0]["host"][:max(128, ops[0]["host"].shape[0] // 4)])
+        tt = time.perf_counter()
+        O.analyze_quantize(xs, ops[0]["gran"], "partition", "mean_rel_err", THRESHOLD)
+        t1 = time.perf_counter() - tt
+        O.set_threads(cpu_baseline["cores"])
+        cpu_baseline["single_thread_value"] = round(2.0 * xs.size / t1 / 1e9, 4)
+        cpu_baseline["single_thread_sample"] = f"first {xs.shape[0]} rows of X ({xs.size} elements, {t1:.1f} s)"
         log(f"[bench] cpu oracle: {cpu_baseline}")
 
     result = {
         "metric": "GB/s of BF16 input analysed+quantized (fraction of HBM peak); FP8-selected %",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(ms_per_step, 4), "ms_per_step_median": round(ms_median, 4), "ms_per_step_min": round(ms_min, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "cfg5: operand sweep of one Llama-style 8B layer (X 8192x4096 1x128; W_qkv 6144x4096, W_o 4096x4096, "
                                "W_gate/W_up 14336x4096, W_down 4096x14336 128x128; six same-shape gradients per-tensor); "
@@ -350,6 +378,7 @@ def main() -> int:
                                                  "one analyze_quantize_batch call incl. statistics") + ", one stream",
                    "elements_per_step": n_total, "row_div": args.row_div, "criterion": "mean_rel_err", "threshold": THRESHOLD},
         "hbm_algorithmic_gbs": round(step_gbs, 1), "hbm_frac_of_peak": round(step_gbs / HBM_PEAK_GBS, 4),
+        "plain_copy_gbs": round(copy_gbs, 1),
         "fp8_selected_pct": {"by_elements": round(100.0 * fp8_elems / n_total, 3), "by_blocks": round(100.0 * fp8_parts / tot_parts, 3),
                              "by_tensors": round(100.0 * fp8_tensors / len(ops), 3), "near_threshold_blocks": near},
         "roofline": roofline,

@@ -622,6 +622,16 @@ void mor_oracle_histogram_update(uint32_t *hist12, float tensor_metric, int64_t 
     hist12[bin]++;
 }
 
+/* Number of OpenMP threads the oracle may use from now on (benchmark's single-thread baseline). */
+void mor_oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int mor_oracle_threads(void)
 {
 #ifdef _OPENMP

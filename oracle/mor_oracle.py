@@ -101,6 +101,8 @@ def lib():
                                               C.c_int, C.c_float, C.c_float, C.POINTER(_Stats)]
         L.mor_oracle_select_stats.restype = C.c_int
         L.mor_oracle_threads.restype = C.c_int
+        L.mor_oracle_set_threads.argtypes = [C.c_int]
+        L.mor_oracle_set_threads.restype = None
         _lib = L
     return _lib
 
@@ -163,6 +165,10 @@ def num_partitions(gran: str, rows: int, cols: int, ragged: bool = False) -> int
 
 def threads() -> int:
     return int(lib().mor_oracle_threads())
+
+
+def set_threads(n: int) -> None:
+    lib().mor_oracle_set_threads(int(n))
 
 
 @dataclass

@@ -990,20 +990,30 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
                 if (c < n_chunks) store16(bf16 + c * 8, raw[u]);
             }
         }
-        if (fast) {
+        if (fast && FAKE && proven) {
+            // fake quantization of an operand already proven to stay in BF16: the output is the input (stored above);
+            // only the error sums are still needed
+#pragma unroll
+            for (int u = 0; u < kTensorChunksPerThread; ++u) {
+                (void)quant8_fast<false>(raw[u], s, acc.e0, acc.e1);
+                if constexpr (CRIT == kCritEq3) (void)quant8_fast<true>(raw[u], s5, acc.f0, acc.f1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else if (fast) {
 #pragma unroll
             for (int u = 0; u < kTensorChunksPerThread; ++u) {
                 const int64_t c = c0 + u * 256;
                 u32x4 deq;
                 const u32x2 codes = quant8_fast_deq<false, FAKE>(raw[u], s, s_inv, acc.e0, acc.e1, deq);
                 if (c < n_chunks) {
-                    if constexpr (FAKE) { if (!proven) store16(fakep + c * 8, deq); }
+                    if constexpr (FAKE) store16(fakep + c * 8, deq);
                     else store8(fp8 + c * 8, codes);
                 }
                 if constexpr (CRIT == kCritEq3) (void)quant8_fast<true>(raw[u], s5, acc.f0, acc.f1);
 #if MOR_TQ_SB
                 __builtin_amdgcn_sched_barrier(0);
 #endif
+                if constexpr (FAKE) __builtin_amdgcn_sched_barrier(0);
             }
         } else {
 #pragma clang loop unroll(disable)
