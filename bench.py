@@ -164,8 +164,8 @@ KERNEL_GRAN = {"sub1x128": "sub1x128", "team_block": "block128", "tensor_amax": 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--row-div", type=int, default=1, help="divide every operand's rows (debug only; 1 = full workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-operand", action="store_true", help="one analyze + one stats call per operand instead of one batch call")

@@ -796,7 +796,8 @@ __global__ void k_histogram_update(uint32_t* __restrict__ hist, const StatsDev* 
 // per-launch overhead is paid once per group instead of once per operand.  The descriptor tables
 // travel in the kernel-argument segment: no staging copy, nothing allocated.
 // ======================================================================================
-constexpr int kMaxGroup = 12;          // per-tensor operands / GAM pre-pass per launch
+constexpr int kMaxGroup = 8;           // per-tensor operands / GAM pre-pass per launch (their table shares the 4 KB
+                                       // kernel-argument segment with the statistics riders)
 constexpr int kMaxGroupSub = 16;       // 1x128 and 128x128 operands per launch
 #ifndef MOR_SUB_DOUBLE
 #define MOR_SUB_DOUBLE 0
@@ -862,6 +863,74 @@ __global__ __launch_bounds__(256) void k_sub1x128_group(GroupSub g) {
 #endif
 }
 
+// Statistics of sub-tensor operands of a group: pass 1 writes one partial record per workgroup into
+// the workspace, pass 2 (one workgroup per operand) combines them in a fixed order.
+struct StatsRec {      // 128 bytes
+    double e;
+    unsigned long long n, eb, e5;
+    uint32_t cnt[kStatCnt];
+    uint32_t pad[9];
+};
+struct StatsOp {
+    const float* err_sum; const uint32_t* nnz; const uint8_t* mask;
+    int64_t n_part;
+    StatsGeom geom;
+    float th;
+    StatsRec* rec;          // [n_wg]
+    StatsDev* out;
+};
+constexpr int kMaxGroupStats = 12;
+struct GroupStats {
+    int n;
+    int32_t wg_end[kMaxGroupStats];
+    float near_tol;
+    StatsOp op[kMaxGroupStats];
+};
+__device__ __forceinline__ void stats_partial_body(const GroupStats& g, int block) {
+    __shared__ StatsShared sh;
+    const int op = group_find32(g.wg_end, g.n, block);
+    const StatsOp& t = g.op[op];
+    const int b = block - (op ? g.wg_end[op - 1] : 0);
+    const int nb = g.wg_end[op] - (op ? g.wg_end[op - 1] : 0);
+    StatsAcc a;
+    stats_acc_clear(a);
+    for (int64_t p = (int64_t)b * 256 + threadIdx.x; p < t.n_part; p += (int64_t)nb * 256)
+        stats_accumulate(p, t.err_sum, t.nnz, t.mask, t.th, g.near_tol, t.geom, a);
+    stats_block_reduce(a, sh);
+    if (nb == 1) {      // the whole operand in one workgroup: write the result, no second pass needed
+        if (threadIdx.x < 12) t.out->hist[threadIdx.x] = sh.cnt[0][threadIdx.x];
+        if (threadIdx.x == 0)
+            stats_finish(t.out, t.n_part, (unsigned long long)(t.geom.rows * t.geom.cols), a.e, a.n, sh.cnt[0][12], sh.cnt[0][13],
+                         sh.cnt[0][14], a.eb, a.e5, 0u);
+        return;
+    }
+    StatsRec* r = t.rec + b;
+    if (threadIdx.x < kStatCnt) r->cnt[threadIdx.x] = sh.cnt[0][threadIdx.x];
+    if (threadIdx.x == 0) { r->e = a.e; r->n = a.n; r->eb = a.eb; r->e5 = a.e5; }
+}
+__device__ __forceinline__ void stats_final_body(const GroupStats& g, int op) {
+    __shared__ StatsShared sh;
+    const StatsOp& t = g.op[op];
+    const int nb = g.wg_end[op] - (op ? g.wg_end[op - 1] : 0);       // <= 256: one record per thread
+    if (nb == 1) return;                                             // already final
+    StatsAcc a;
+    stats_acc_clear(a);
+    if ((int)threadIdx.x < nb) {
+        const StatsRec& r = t.rec[threadIdx.x];
+        a.e = r.e; a.n = r.n; a.eb = r.eb; a.e5 = r.e5;
+#pragma unroll
+        for (int k = 0; k < kStatCnt; ++k) a.cnt[k] = r.cnt[k];      // per-workgroup counts fit 32 bits
+    }
+    stats_block_reduce(a, sh);
+    if (threadIdx.x < 12) t.out->hist[threadIdx.x] = sh.cnt[0][threadIdx.x];
+    if (threadIdx.x == 0)
+        stats_finish(t.out, t.n_part, (unsigned long long)(t.geom.rows * t.geom.cols), a.e, a.n, sh.cnt[0][12], sh.cnt[0][13],
+                     sh.cnt[0][14], a.eb, a.e5, 0u);
+}
+
+__global__ __launch_bounds__(256) void k_stats_group_partial(GroupStats g) { stats_partial_body(g, blockIdx.x); }
+__global__ __launch_bounds__(256) void k_stats_group_final(GroupStats g) { stats_final_body(g, blockIdx.x); }
+
 // Per-tensor operands of a group share three launches (amax, quantize, finish + fallback copy).
 struct TensorOp {
     const uint16_t* x;
@@ -891,7 +960,10 @@ struct GroupTensor {
 // place of the final one the test only becomes stricter, so the count is a lower bound.  When the
 // bound reaches flush_need, pass B writes the BF16 fallback in the same sweep and the separate copy
 // pass (2 more bytes read per element) is skipped.  The outputs are the same either way.
-__global__ __launch_bounds__(256) void k_tensor_amax_group(GroupTensor g) {
+// Workgroups from `stats_first` on do not belong to pass A: they compute the partial statistics records of the batch's
+// sub-tensor operands (whose kernels have already run), in the shadow of this bandwidth-bound pass.
+__global__ __launch_bounds__(256) void k_tensor_amax_group(GroupTensor g, GroupStats riders, int stats_first) {
+    if ((int)blockIdx.x >= stats_first) { stats_partial_body(riders, (int)blockIdx.x - stats_first); return; }
     __shared__ uint32_t sh4[4];
     const int op = group_find32(g.amax_end, g.n, blockIdx.x);
     const TensorOp& t = g.op[op];
@@ -1049,8 +1121,10 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
     TensorPartials tp{t.err, t.err5, t.zero, t.abits};
     tensor_publish<CRIT>(acc, tp, b);
 }
+// Workgroups from `stats_first` on combine the riders' partial statistics records (one workgroup per operand).
 template <int CRIT>
-__global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g) {
+__global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g, GroupStats riders, int stats_first) {
+    if ((int)blockIdx.x >= stats_first) { stats_final_body(riders, (int)blockIdx.x - stats_first); return; }
     __shared__ double shd[4];
     __shared__ unsigned long long shl[4];
     const int op = group_find32(g.copy_end, g.n, blockIdx.x);
@@ -1145,72 +1219,6 @@ __global__ __launch_bounds__(256) void k_gam_prepare(GroupGam g) {
         t.gam[1] = mg5;
         if (t.gmant) { t.gmant[0] = mg; t.gmant[1] = mg5; }
     }
-}
-
-// Statistics of sub-tensor operands of a group: pass 1 writes one partial record per workgroup into
-// the workspace, pass 2 (one workgroup per operand) combines them in a fixed order.
-struct StatsRec {      // 128 bytes
-    double e;
-    unsigned long long n, eb, e5;
-    uint32_t cnt[kStatCnt];
-    uint32_t pad[9];
-};
-struct StatsOp {
-    const float* err_sum; const uint32_t* nnz; const uint8_t* mask;
-    int64_t n_part;
-    StatsGeom geom;
-    float th;
-    StatsRec* rec;          // [n_wg]
-    StatsDev* out;
-};
-constexpr int kMaxGroupStats = 12;
-struct GroupStats {
-    int n;
-    int32_t wg_end[kMaxGroupStats];
-    float near_tol;
-    StatsOp op[kMaxGroupStats];
-};
-__global__ __launch_bounds__(256) void k_stats_group_partial(GroupStats g) {
-    __shared__ StatsShared sh;
-    const int op = group_find32(g.wg_end, g.n, blockIdx.x);
-    const StatsOp& t = g.op[op];
-    const int b = blockIdx.x - (op ? g.wg_end[op - 1] : 0);
-    const int nb = g.wg_end[op] - (op ? g.wg_end[op - 1] : 0);
-    StatsAcc a;
-    stats_acc_clear(a);
-    for (int64_t p = (int64_t)b * 256 + threadIdx.x; p < t.n_part; p += (int64_t)nb * 256)
-        stats_accumulate(p, t.err_sum, t.nnz, t.mask, t.th, g.near_tol, t.geom, a);
-    stats_block_reduce(a, sh);
-    if (nb == 1) {      // the whole operand in one workgroup: write the result, no second pass needed
-        if (threadIdx.x < 12) t.out->hist[threadIdx.x] = sh.cnt[0][threadIdx.x];
-        if (threadIdx.x == 0)
-            stats_finish(t.out, t.n_part, (unsigned long long)(t.geom.rows * t.geom.cols), a.e, a.n, sh.cnt[0][12], sh.cnt[0][13],
-                         sh.cnt[0][14], a.eb, a.e5, 0u);
-        return;
-    }
-    StatsRec* r = t.rec + b;
-    if (threadIdx.x < kStatCnt) r->cnt[threadIdx.x] = sh.cnt[0][threadIdx.x];
-    if (threadIdx.x == 0) { r->e = a.e; r->n = a.n; r->eb = a.eb; r->e5 = a.e5; }
-}
-__global__ __launch_bounds__(256) void k_stats_group_final(GroupStats g) {
-    __shared__ StatsShared sh;
-    const int op = blockIdx.x;
-    const StatsOp& t = g.op[op];
-    const int nb = g.wg_end[op] - (op ? g.wg_end[op - 1] : 0);       // <= 256: one record per thread
-    if (nb == 1) return;                                             // already final
-    StatsAcc a;
-    stats_acc_clear(a);
-    if ((int)threadIdx.x < nb) {
-        const StatsRec& r = t.rec[threadIdx.x];
-        a.e = r.e; a.n = r.n; a.eb = r.eb; a.e5 = r.e5;
-#pragma unroll
-        for (int k = 0; k < kStatCnt; ++k) a.cnt[k] = r.cnt[k];      // per-workgroup counts fit 32 bits
-    }
-    stats_block_reduce(a, sh);
-    if (threadIdx.x < 12) t.out->hist[threadIdx.x] = sh.cnt[0][threadIdx.x];
-    if (threadIdx.x == 0)
-        stats_finish(t.out, t.n_part, (unsigned long long)(t.geom.rows * t.geom.cols), a.e, a.n, sh.cnt[0][12], sh.cnt[0][13],
-                     sh.cnt[0][14], a.eb, a.e5, 0u);
 }
 
 // ======================================================================================
@@ -1365,7 +1373,7 @@ int share(int64_t mine, int64_t total, int budget, int64_t cap) {
     if (v > budget) v = budget;
     return (int)(v < 1 ? 1 : v);
 }
-constexpr int kMaxGroupTensor = 12;
+constexpr int kMaxGroupTensor = 8;
 }  // namespace
 
 size_t batch_workspace_bytes(const BatchItem* items, int n) {
@@ -1375,7 +1383,7 @@ size_t batch_workspace_bytes(const BatchItem* items, int n) {
 }
 
 hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws, size_t ws_bytes, hipStream_t st, KProf* prof) {
-    static_assert(sizeof(GroupSub) <= 3800 && sizeof(GroupTensor) <= 3800 && sizeof(GroupStats) <= 3800 &&
+    static_assert(sizeof(GroupSub) <= 3800 && sizeof(GroupTensor) + sizeof(GroupStats) <= 3800 &&
                   sizeof(GroupGam) <= 3800 && sizeof(GroupScope) <= 3800, "kernel-argument segment is 4 KB");
     static_assert(sizeof(StatsRec) == 128, "StatsRec layout");
     char* wsp = static_cast<char*>(ws);
@@ -1434,7 +1442,11 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
             }
             for (int k = 0; k < m; ++k)
                 if (slot_of[k] >= 0) gg.op[k].n_amax = ga.op[slot_of[k]].n_amax;
-            if (ga.n) { ProfScope ps(prof, kKernGroupAmax, st); k_tensor_amax_group<<<dim3(a_end), dim3(256), 0, st>>>(ga); }
+            if (ga.n) {
+                GroupStats none; none.n = 0; none.near_tol = near_tol;
+                ProfScope ps(prof, kKernGroupAmax, st);
+                k_tensor_amax_group<<<dim3(a_end), dim3(256), 0, st>>>(ga, none, a_end);
+            }
             { ProfScope ps(prof, kKernGroupMantissa, st); k_gam_prepare<<<dim3(m), dim3(256), 0, st>>>(gg); }
         }
     }
@@ -1511,6 +1523,68 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 }
             if (cnt) err = launch_channel_col_items(items, idx, cnt, crit, gam_of, ws_of, st, prof);
         }
+    }
+    // ---- tensor-level decision (Section 3.1) over the per-block sums the block kernels left behind
+    {
+        GroupScope g; g.n = 0;
+        int red = 0, copy = 0;
+        auto flush = [&]() {
+            if (g.n == 0) return;
+            { ProfScope ps(prof, kKernScopeReduce, st); k_scope_reduce_group<<<dim3(red), dim3(256), 0, st>>>(g); }
+            { ProfScope ps(prof, kKernScopeDecide, st); k_scope_decide_group<<<dim3(red), dim3(256), 0, st>>>(g); }
+            { ProfScope ps(prof, kKernFallbackCopy, st); k_scope_copy_group<<<dim3(copy), dim3(256), 0, st>>>(g); }
+            g.n = 0; red = 0; copy = 0;
+        };
+        int64_t total_elems = 0;
+        for (int i = 0; i < n; ++i)
+            if (items[i].gran != kGranTensor && items[i].scope == 1) total_elems += items[i].sh.rows * items[i].sh.cols;
+        for (int i = 0; i < n; ++i) {
+            const BatchItem& it = items[i];
+            if (it.gran == kGranTensor || it.scope != 1) continue;
+            ScopeOp& t = g.op[g.n];
+            char* w = carve(scope_workspace_bytes(0));
+            t.err_sum = it.o.err_sum; t.err5_sum = it.o.err5_sum; t.nnz = it.o.nnz; t.mask = it.o.mask;
+            t.n_part = item_parts(it);
+            t.part_err = reinterpret_cast<double*>(w); t.part_err5 = t.part_err + kScopeBlocks;
+            t.part_nnz = reinterpret_cast<unsigned long long*>(w) + 2 * kScopeBlocks;
+            t.decision = reinterpret_cast<uint32_t*>(w + 3 * sizeof(double) * kScopeBlocks);
+            t.th = it.th; t.crit = it.crit;
+            int64_t want = (t.n_part + 1023) / 1024;
+            t.n_red = (int)(want < 1 ? 1 : (want > kScopeBlocks ? kScopeBlocks : want));
+            t.x = it.x; t.bf16 = it.o.bf16;
+            t.rows = it.sh.rows; t.cols = it.sh.cols; t.ld = it.sh.ld; t.ld_bf16 = it.o.ld_bf16;
+            red += t.n_red;
+            copy += it.o.bf16 ? share(it.sh.rows * it.sh.cols, total_elems, 4096, 4096) : 1;
+            g.red_end[g.n] = red; g.copy_end[g.n] = copy;
+            if (++g.n == kMaxGroupScope) flush();
+        }
+        flush();
+    }
+    // ---- statistics of the operands with sub-tensor blocks: their kernels (and tensor-level decisions) are done, so the
+    //      first group can ride on the first per-tensor launches: partial records in the shadow of pass A, the combine
+    //      step next to the finish pass.  Groups that find no such launch run on their own at the end.
+    constexpr int kMaxStatsGroups = (kBatchMax + kMaxGroupStats - 1) / kMaxGroupStats;
+    GroupStats stats_groups[kMaxStatsGroups];
+    int n_stats_groups = 0;
+    bool riders_used = false;
+    {
+        GroupStats* g = nullptr;
+        for (int i = 0; i < n; ++i) {
+            const BatchItem& it = items[i];
+            if (!it.stats || it.gran == kGranTensor) continue;
+            if (!g || g->n == kMaxGroupStats) { g = &stats_groups[n_stats_groups++]; g->n = 0; g->near_tol = near_tol; }
+            StatsOp& t = g->op[g->n];
+            t.err_sum = it.o.err_sum; t.nnz = it.o.nnz; t.mask = it.o.mask;
+            t.geom = make_geom(it.gran, it.sh.rows, it.sh.cols);
+            t.n_part = geom_parts(t.geom);
+            t.th = it.th;
+            t.rec = reinterpret_cast<StatsRec*>(carve(sizeof(StatsRec) * kStatsMaxWg));
+            t.out = static_cast<StatsDev*>(it.stats);
+            g->wg_end[g->n] = (g->n ? g->wg_end[g->n - 1] : 0) + stats_wgs(t.n_part);
+            ++g->n;
+        }
+    }
+    for (int crit = 0; crit < 2 && err == hipSuccess; ++crit) {
         // ---- per-tensor operands: amax pass, quantize pass, finish (+ fallback copy) pass; FP8 payload and fake
         //      quantization are different kernels
         for (int fake = 0; fake < 2 && err == hipSuccess; ++fake) {
@@ -1550,7 +1624,15 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                     c_end += it.o.bf16 ? share(t.n_tiles, total_tiles, 2048, 2048) : 1;
                     g.amax_end[k] = a_end; g.slot_end[k] = s_end; g.copy_end[k] = c_end;
                 }
-                { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_group<<<dim3(a_end), dim3(256), 0, st>>>(g); }
+                GroupStats riders; riders.n = 0; riders.near_tol = near_tol;
+                int ride_partial = 0, ride_final = 0;
+                if (!riders_used && n_stats_groups > 0) {
+                    riders = stats_groups[0];
+                    ride_partial = riders.wg_end[riders.n - 1];
+                    ride_final = ride_partial > riders.n ? riders.n : 0;      // single-workgroup operands are final already
+                    riders_used = true;
+                }
+                { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_group<<<dim3(a_end + ride_partial), dim3(256), 0, st>>>(g, riders, a_end); }
                 {
                     ProfScope ps(prof, kKernTensorQuant, st);
                     if (fake) {
@@ -1563,8 +1645,8 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 }
                 {
                     ProfScope ps(prof, kKernFallbackCopy, st);
-                    if (crit == kCritEq3) k_tensor_finish_group<kCritEq3><<<dim3(c_end), dim3(256), 0, st>>>(g);
-                    else k_tensor_finish_group<kCritEq2><<<dim3(c_end), dim3(256), 0, st>>>(g);
+                    if (crit == kCritEq3) k_tensor_finish_group<kCritEq3><<<dim3(c_end + ride_final), dim3(256), 0, st>>>(g, riders, c_end);
+                    else k_tensor_finish_group<kCritEq2><<<dim3(c_end + ride_final), dim3(256), 0, st>>>(g, riders, c_end);
                 }
                 cnt = 0;
             };
@@ -1587,67 +1669,12 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 err = launch_select_stats(make_geom(it.gran, it.sh.rows, it.sh.cols), it.o.err_sum, it.o.nnz, it.o.mask, it.th, near_tol, it.stats, st);
         }
     }
-    // ---- tensor-level decision (Section 3.1) over the per-block sums the block kernels left behind
-    {
-        GroupScope g; g.n = 0;
-        int red = 0, copy = 0;
-        auto flush = [&]() {
-            if (g.n == 0) return;
-            { ProfScope ps(prof, kKernScopeReduce, st); k_scope_reduce_group<<<dim3(red), dim3(256), 0, st>>>(g); }
-            { ProfScope ps(prof, kKernScopeDecide, st); k_scope_decide_group<<<dim3(red), dim3(256), 0, st>>>(g); }
-            { ProfScope ps(prof, kKernFallbackCopy, st); k_scope_copy_group<<<dim3(copy), dim3(256), 0, st>>>(g); }
-            g.n = 0; red = 0; copy = 0;
-        };
-        int64_t total_elems = 0;
-        for (int i = 0; i < n; ++i)
-            if (items[i].gran != kGranTensor && items[i].scope == 1) total_elems += items[i].sh.rows * items[i].sh.cols;
-        for (int i = 0; i < n; ++i) {
-            const BatchItem& it = items[i];
-            if (it.gran == kGranTensor || it.scope != 1) continue;
-            ScopeOp& t = g.op[g.n];
-            char* w = carve(scope_workspace_bytes(0));
-            t.err_sum = it.o.err_sum; t.err5_sum = it.o.err5_sum; t.nnz = it.o.nnz; t.mask = it.o.mask;
-            t.n_part = item_parts(it);
-            t.part_err = reinterpret_cast<double*>(w); t.part_err5 = t.part_err + kScopeBlocks;
-            t.part_nnz = reinterpret_cast<unsigned long long*>(w) + 2 * kScopeBlocks;
-            t.decision = reinterpret_cast<uint32_t*>(w + 3 * sizeof(double) * kScopeBlocks);
-            t.th = it.th; t.crit = it.crit;
-            int64_t want = (t.n_part + 1023) / 1024;
-            t.n_red = (int)(want < 1 ? 1 : (want > kScopeBlocks ? kScopeBlocks : want));
-            t.x = it.x; t.bf16 = it.o.bf16;
-            t.rows = it.sh.rows; t.cols = it.sh.cols; t.ld = it.sh.ld; t.ld_bf16 = it.o.ld_bf16;
-            red += t.n_red;
-            copy += it.o.bf16 ? share(it.sh.rows * it.sh.cols, total_elems, 4096, 4096) : 1;
-            g.red_end[g.n] = red; g.copy_end[g.n] = copy;
-            if (++g.n == kMaxGroupScope) flush();
-        }
-        flush();
-    }
-    // ---- statistics of the operands with sub-tensor blocks
-    {
-        GroupStats g; g.n = 0; g.near_tol = near_tol;
-        int wg_total = 0;
-        auto flush = [&]() {
-            if (g.n == 0) return;
-            { ProfScope ps(prof, kKernStatsPartial, st); k_stats_group_partial<<<dim3(wg_total), dim3(256), 0, st>>>(g); }
-            if (wg_total > g.n) { ProfScope ps(prof, kKernStatsFinal, st); k_stats_group_final<<<dim3(g.n), dim3(256), 0, st>>>(g); }
-            g.n = 0; wg_total = 0;
-        };
-        for (int i = 0; i < n; ++i) {
-            const BatchItem& it = items[i];
-            if (!it.stats || it.gran == kGranTensor) continue;
-            StatsOp& t = g.op[g.n];
-            t.err_sum = it.o.err_sum; t.nnz = it.o.nnz; t.mask = it.o.mask;
-            t.geom = make_geom(it.gran, it.sh.rows, it.sh.cols);
-            t.n_part = geom_parts(t.geom);
-            t.th = it.th;
-            t.rec = reinterpret_cast<StatsRec*>(carve(sizeof(StatsRec) * kStatsMaxWg));
-            t.out = static_cast<StatsDev*>(it.stats);
-            wg_total += stats_wgs(t.n_part);
-            g.wg_end[g.n] = wg_total;
-            if (++g.n == kMaxGroupStats) flush();
-        }
-        flush();
+    // ---- statistics of the operands with sub-tensor blocks that found no per-tensor launch to ride on
+    for (int k = riders_used ? 1 : 0; k < n_stats_groups && err == hipSuccess; ++k) {
+        const GroupStats& g = stats_groups[k];
+        const int wg_total = g.wg_end[g.n - 1];
+        { ProfScope ps(prof, kKernStatsPartial, st); k_stats_group_partial<<<dim3(wg_total), dim3(256), 0, st>>>(g); }
+        if (wg_total > g.n) { ProfScope ps(prof, kKernStatsFinal, st); k_stats_group_final<<<dim3(g.n), dim3(256), 0, st>>>(g); }
     }
     if (err != hipSuccess) return err;
     return hipGetLastError();
