@@ -265,7 +265,7 @@ struct ColOp {
     int64_t tiles_x;            // 128-column strips
     int32_t tiles_per_strip;    // 128-row tiles a workgroup sweeps (1 for kColLocal)
     float th;
-    uint8_t defer, mode, pad0, pad1;
+    uint8_t defer, mode, three, pad1;
     const uint32_t* gam;
     // per-channel columns: workspace, [n_strips x cols_padded] each, cols_padded = tiles_x * 128
     uint16_t* part_amax;
@@ -285,6 +285,7 @@ struct ColShared {
     float scale[128], scale5[128];
     float err[4][128], err5[4][128];
     uint32_t zero[4][16][4];     // packed per-column zero counts
+    uint32_t amin[4][16][4];     // packed per-column (smallest non-zero pattern - 1), three-way recipe
     uint16_t abits[128];         // column amax patterns of the tile
     uint8_t mask[128];
 };
@@ -294,6 +295,10 @@ struct ColShared {
 __device__ __forceinline__ uint32_t colgroup_max2(uint32_t v) {
     v = pk_max_u16(v, (uint32_t)__shfl_xor((int)v, 16, 64));
     return pk_max_u16(v, (uint32_t)__shfl_xor((int)v, 32, 64));
+}
+__device__ __forceinline__ uint32_t colgroup_min2(uint32_t v) {
+    v = pk_min_u16(v, (uint32_t)__shfl_xor((int)v, 16, 64));
+    return pk_min_u16(v, (uint32_t)__shfl_xor((int)v, 32, 64));
 }
 __device__ __forceinline__ uint32_t colgroup_add2(uint32_t v) {
     v = pk_add_u16(v, (uint32_t)__shfl_xor((int)v, 16, 64));
@@ -360,7 +365,14 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
                 for (int j = 0; j < 4; ++j) amax2[j] = pk_max_u16(amax2[j], raw[i][j] & 0x7FFF7FFFu);
         }
         if constexpr (MODE == kColAmax) continue;
+        uint32_t mn2[4] = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
         if constexpr (MODE == kColLocal) {
+            if (t.three) {                                             // smallest non-zero magnitude per column (Eq. 4)
+#pragma unroll
+                for (int i = 0; i < kChunks; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) mn2[j] = pk_min_u16(mn2[j], pk_sub_u16(raw[i][j] & 0x7FFF7FFFu, 0x00010001u));
+            }
             // column amax of the tile: row groups of the wave, then the four waves through LDS
 #pragma unroll
             for (int j = 0; j < 4; ++j) amax2[j] = colgroup_max2(amax2[j]);
@@ -451,11 +463,15 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) zero2[j] = colgroup_add2(zero2[j]);
+            if (t.three) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) mn2[j] = colgroup_min2(mn2[j]);
+            }
             if (lane < 16) {
 #pragma unroll
                 for (int k = 0; k < 8; ++k) { sh.err[w][cg * 8 + k] = err[k]; if constexpr (CRIT == kCritEq3) sh.err5[w][cg * 8 + k] = err5[k]; }
 #pragma unroll
-                for (int j = 0; j < 4; ++j) sh.zero[w][cg][j] = zero2[j];
+                for (int j = 0; j < 4; ++j) { sh.zero[w][cg][j] = zero2[j]; sh.amin[w][cg][j] = mn2[j]; }
             }
             __syncthreads();
             if (tid < 128) {
@@ -470,22 +486,67 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
                 const uint32_t nnz = 128u - z;
                 if (a >= kInfBits) { e = __builtin_inff(); e5 = e; }
                 const bool defer = t.defer != 0;
-                const uint32_t mk = defer ? 0u : ((CRIT == kCritEq3) ? decide_eq3(e, e5) : decide_eq2(e, nnz, t.th));
+                uint32_t mk = defer ? 0u : ((CRIT == kCritEq3) ? decide_eq3(e, e5) : decide_eq2(e, nnz, t.th));
+                // three-way recipe: a column that failed M_1 is kept in E5M2 if its dynamic range fits (Eq. 4)
+                uint32_t amin_bits = 0u;
+                float s_out = sh.scale[tid];
+                if (t.three && mk == 1u) {
+                    uint32_t mn = 0xFFFFu;
+#pragma unroll
+                    for (int ww = 0; ww < 4; ++ww) mn = min(mn, (sh.amin[ww][g16][k >> 1] >> ((k & 1) * 16)) & 0xFFFFu);
+                    amin_bits = nnz ? ((mn + 1u) & 0xFFFFu) : 0u;
+                    if (range_fits_e5m2(a, amin_bits, nnz)) { mk = 2u; s_out = sh.scale5[tid]; }
+                }
                 sh.mask[tid] = (uint8_t)mk;
                 if (c0 + tid < t.cols) {
                     const int64_t p = (r0 >> 7) * t.cols + c0 + tid;
-                    o.scale[p] = sh.scale[tid];
+                    o.scale[p] = s_out;
                     o.amax[p] = __uint_as_float(a << 16);
                     o.err_sum[p] = e;
                     o.nnz[p] = nnz;
                     if constexpr (CRIT == kCritEq3) o.err5_sum[p] = e5;
                     if (!defer) o.mask[p] = (uint8_t)mk;
-                    if (mode != kScaleFp32 && o.e8m0) o.e8m0[p] = (uint8_t)(__float_as_uint(sh.scale[tid]) >> 23);
+                    if (mode != kScaleFp32 && o.e8m0) o.e8m0[p] = (uint8_t)(__float_as_uint(s_out) >> 23);
+                    if (t.three && o.amin) o.amin[p] = __uint_as_float(amin_bits << 16);
                 }
             }
             __syncthreads();
-            if (o.bf16) {
+            if (t.three) {
                 const uint64_t mk8 = *reinterpret_cast<const uint64_t*>(&sh.mask[cg * 8]);
+                const uint64_t sel = (mk8 >> 1) & 0x0101010101010101ull;       // byte k = 1: column k is kept in E5M2
+                if (sel) {
+                    // the E5M2 payload replaces the E4M3 one in those columns (whole chunks are stored again)
+#pragma clang loop unroll(disable)
+                    for (int i = 0; i < kChunks; ++i) {
+                        if (!is_valid(i)) continue;
+                        const uint32_t* src32 = reinterpret_cast<const uint32_t*>(src + (int64_t)i * 16 * t.ld);
+                        uint32_t cw[2] = {0u, 0u};
+                        uint32_t dq[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const uint32_t wv = src32[j];
+                            const bool lo5 = (sel >> (16 * j)) & 1u, hi5 = (sel >> (16 * j + 8)) & 1u;
+                            float dummy = 0.0f;
+                            const uint32_t c_lo = lo5 ? quant1_careful<true>(wv & 0xFFFFu, s5[2 * j], dummy)
+                                                      : quant1_careful<false>(wv & 0xFFFFu, s[2 * j], dummy);
+                            const uint32_t c_hi = hi5 ? quant1_careful<true>(wv >> 16, s5[2 * j + 1], dummy)
+                                                      : quant1_careful<false>(wv >> 16, s[2 * j + 1], dummy);
+                            cw[j >> 1] |= (c_lo | (c_hi << 8)) << ((j & 1) * 16);
+                            if constexpr (FAKE) {
+                                const float q_lo = lo5 ? cvt_pk_f32<true>((int)c_lo, false).x : cvt_pk_f32<false>((int)c_lo, false).x;
+                                const float q_hi = hi5 ? cvt_pk_f32<true>((int)c_hi, false).x : cvt_pk_f32<false>((int)c_hi, false).x;
+                                const float i_lo = 1.0f / (lo5 ? s5[2 * j] : s[2 * j]), i_hi = 1.0f / (hi5 ? s5[2 * j + 1] : s[2 * j + 1]);
+                                dq[j] = f32_to_bf16_rne(q_lo * i_lo) | (f32_to_bf16_rne(q_hi * i_hi) << 16);
+                            }
+                        }
+                        if constexpr (FAKE) { u32x4 d; d.x = dq[0]; d.y = dq[1]; d.z = dq[2]; d.w = dq[3]; store16(dstf + (int64_t)i * 16 * o.ld_fake, d); }
+                        else { u32x2 c; c.x = cw[0]; c.y = cw[1]; store8(dst8 + (int64_t)i * 16 * o.ld_fp8, c); }
+                    }
+                }
+            }
+            if (o.bf16) {
+                uint64_t mk8 = *reinterpret_cast<const uint64_t*>(&sh.mask[cg * 8]);
+                mk8 &= 0x0101010101010101ull;                          // byte k = 1: column k stays in BF16 (2 = E5M2 does not)
                 uint16_t* __restrict__ dbf = o.bf16 + row * o.ld_bf16 + col;
                 if (mk8 == 0x0101010101010101ull) {                    // all eight columns of this lane stay in BF16
                     const BufRsrc rb = make_buf(o.bf16 + r0 * o.ld_bf16 + c0);
@@ -771,7 +832,7 @@ void fill_col_op(ColOp& t, const BatchItem& it, const uint32_t* gam) {
     t.x = it.x; t.o = it.o; t.ld = it.sh.ld; t.rows = it.sh.rows; t.cols = it.sh.cols;
     t.tiles_x = (it.sh.cols + 127) / 128;
     t.tiles_per_strip = 1;
-    t.th = it.th; t.defer = it.scope == 1; t.mode = (uint8_t)it.scaling;
+    t.th = it.th; t.defer = it.scope == 1; t.mode = (uint8_t)it.scaling; t.three = (uint8_t)it.three;
     t.gam = gam;
 }
 template <int MODE, bool FAKE, bool EDGE>

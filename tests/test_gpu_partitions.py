@@ -152,15 +152,17 @@ def test_ragged_needs_the_flag(P):
 
 # ------------------------------------------------------------------ three-way selection
 
-@pytest.mark.parametrize("gran", ["sub1x128", "block128", "block64", "channel_row"])
+@pytest.mark.parametrize("gran", ["sub1x128", "block128", "block64", "channel_row", "sub128x1"])
 @pytest.mark.parametrize("crit", ["e4m3_vs_e5m2", "mean_rel_err"])
 @pytest.mark.parametrize("scaling", ["fp32_amax", "gam", "e8m0"])
 def test_three_way(P, gran, crit, scaling):
     xb = wide_operand(21, 256, 512)
+    if gran == "sub128x1":
+        xb = np.ascontiguousarray(wide_operand(21, 512, 256).T)     # the three kinds of blocks along the columns
     xb[3, :128] = 0                                        # an empty block of 1 x 128
     xb[5, 7] = 0x7F80                                      # a non-finite value
     r = P.compare(xb, gran, crit=crit, threshold=TH, formats=THREE, scaling=scaling, label="three-way")
-    if gran == "sub1x128":
+    if gran in ("sub1x128", "sub128x1"):
         assert r["n_e5m2"] > 10 and r["n_bf16"] > 10
     # de-quantizing from what was emitted reproduces the oracle's de-quantization (E5M2 blocks decode as E5M2)
     from paper_2512_22804_amd import binding as B
@@ -200,9 +202,11 @@ def test_three_way_handworked(P):
 def test_three_way_all_patterns(P):
     x = np.random.default_rng(5).permutation(all_patterns())
     x = np.where((x & 0x7FFF) >= 0x7F80, x & 0x80FF, x)            # finite, full dynamic range
-    for gran in ("sub1x128", "block64"):
+    for gran in ("sub1x128", "block64", "sub128x1"):
         for crit in ("e4m3_vs_e5m2", "mean_rel_err"):
             P.compare(x.reshape(256, 256), gran, crit=crit, formats=THREE, label="three-patterns")
+    P.compare(np.ascontiguousarray(x.reshape(256, 256)[:200, :136]), "sub128x1", crit="e4m3_vs_e5m2", formats=THREE, ragged=True,
+              label="three-patterns-ragged")
     sorted_x = np.sort(all_patterns() & 0x7FFF).astype(np.uint16)  # narrow blocks, incl. Inf/NaN blocks at the end
     P.compare(sorted_x.reshape(512, 128), "sub1x128", crit="e4m3_vs_e5m2", formats=THREE, label="three-sorted")
 
@@ -210,7 +214,7 @@ def test_three_way_all_patterns(P):
 def test_three_way_unsupported_combinations(P):
     from paper_2512_22804_amd import binding as B
     xb = W.activation(128, 256, 1)
-    for gran, scope in (("tensor", "partition"), ("channel_col", "partition"), ("sub128x1", "partition"), ("sub1x128", "tensor")):
+    for gran, scope in (("tensor", "partition"), ("channel_col", "partition"), ("sub1x128", "tensor")):
         with pytest.raises(B.MorError) as e:
             P.run_gpu(xb, gran, scope=scope, crit="e4m3_vs_e5m2", formats=THREE)
         assert e.value.status == 4
@@ -228,10 +232,13 @@ def test_fake_quantize(P, gran, scope):
     P.compare_fake(wide_operand(4, 256, 512), gran, scope=scope, crit="e4m3_vs_e5m2", scaling="gam", label="fake-gam-eq3")
 
 
-@pytest.mark.parametrize("gran", ["sub1x128", "block128", "block64", "channel_row"])
+@pytest.mark.parametrize("gran", ["sub1x128", "block128", "block64", "channel_row", "sub128x1"])
 def test_fake_quantize_three_way(P, gran):
-    r = P.compare_fake(wide_operand(9, 256, 512), gran, crit="e4m3_vs_e5m2", formats=THREE, label="fake-three")
-    if gran == "sub1x128":
+    xb = wide_operand(9, 256, 512)
+    if gran == "sub128x1":
+        xb = np.ascontiguousarray(wide_operand(9, 512, 256).T)
+    r = P.compare_fake(xb, gran, crit="e4m3_vs_e5m2", formats=THREE, label="fake-three")
+    if gran in ("sub1x128", "sub128x1"):
         assert r["n_e5m2"] > 10
 
 
