@@ -349,53 +349,36 @@ __device__ __forceinline__ uint32_t decide_eq3(float err4, float err5) { return 
 // Bounds-checked streaming accesses through a buffer resource: a lane whose offset is kBufOutside loads
 // zeros and stores nothing, so ragged edges need no per-lane branches.  Offsets are bytes from `base`
 // (32 bits; callers keep them below 2^31).
-#ifndef MOR_BUF_AUX
-#define MOR_BUF_AUX 2
-#endif
+constexpr int kBufAux = 2;      // cache-policy field of the buffer instructions: non-temporal
 typedef __amdgpu_buffer_rsrc_t BufRsrc;
 constexpr uint32_t kBufOutside = 0x80000000u;
 __device__ __forceinline__ BufRsrc make_buf(const void* base) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7FFFFFFF, 0x00020000);
 }
 __device__ __forceinline__ u32x4 buf_load16(BufRsrc r, uint32_t voff, uint32_t soff) {
-    return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 2);          // aux 2: non-temporal
+    return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, kBufAux);
 }
 // 16-byte stores never take a register in the scalar-offset field: the compiler assumes that form needs no wait
 // states before the data registers are overwritten and reuses them in the very next instruction, but on gfx950 the
 // first data dword of some lanes was then stored with its NEW contents (seen as rare, timing-dependent corruption of
 // fake-quantized rows).  With a constant scalar offset the compiler inserts the wait states and the data is intact.
 __device__ __forceinline__ void buf_store16(BufRsrc r, uint32_t voff, const u32x4& v) {
-    __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, 0, MOR_BUF_AUX);
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, 0, kBufAux);
 }
 __device__ __forceinline__ void buf_store8(BufRsrc r, uint32_t voff, uint32_t soff, const u32x2& v) {
-    __builtin_amdgcn_raw_buffer_store_b64(v, r, voff, soff, MOR_BUF_AUX);
+    __builtin_amdgcn_raw_buffer_store_b64(v, r, voff, soff, kBufAux);
 }
 
 // Streaming accesses: every operand byte is touched once per pass, so loads and stores carry the
 // non-temporal hint (measured +5-8 % on a plain copy of the same size on MI355X).
-#ifndef MOR_NT
-#define MOR_NT 1
-#endif
 __device__ __forceinline__ u32x4 load16(const void* p) {
-#if MOR_NT
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-#else
-    return *reinterpret_cast<const u32x4*>(p);
-#endif
 }
 __device__ __forceinline__ void store16(void* p, const u32x4& v) {
-#if MOR_NT
     __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
-#else
-    *reinterpret_cast<u32x4*>(p) = v;
-#endif
 }
 __device__ __forceinline__ void store8(void* p, const u32x2& v) {
-#if MOR_NT
     __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(p));
-#else
-    *reinterpret_cast<u32x2*>(p) = v;
-#endif
 }
 
 }  // namespace mor

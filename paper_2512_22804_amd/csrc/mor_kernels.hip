@@ -141,13 +141,6 @@ __device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const ui
     const int64_t prow = unit * 32 + g * 8;
     const int64_t off = prow * 128 + l * 8;
     uint8_t* __restrict__ fl = o.fp8 + off;
-#ifdef MOR_DBG_NOCOMPUTE
-    {
-#pragma unroll
-        for (int k = 0; k < 8; ++k) { u32x2 c; c.x = raw[k].x ^ raw[k].z; c.y = raw[k].y ^ raw[k].w; store8(fl + k * 128, c); }
-        return;
-    }
-#endif
     // phase 1: per-block amax (to the owner lane) and zero counts (packed 4 blocks per dword)
     uint32_t ab[8];
     uint32_t zp0 = 0u, zp1 = 0u;
@@ -296,16 +289,7 @@ struct TensorPartials {   // one slot per pass-B workgroup (at most kMaxQuantBlo
     uint32_t* zero;        // zero elements seen by the workgroup (padding chunks count as zeros)
     uint32_t* abits;       // [0] = global amax bits, published by workgroup 0 of pass B
 };
-#ifndef MOR_TQ_SLOTS
-#define MOR_TQ_SLOTS 16384
-#endif
-#ifndef MOR_TQ_DOUBLE
-#define MOR_TQ_DOUBLE 0
-#endif
-#ifndef MOR_TQ_SB
-#define MOR_TQ_SB 0
-#endif
-constexpr int kMaxQuantBlocks = MOR_TQ_SLOTS;
+constexpr int kMaxQuantBlocks = 16384;
 
 template <typename T>
 __device__ __forceinline__ T block_sum_256(T v, T* sh) {
@@ -799,9 +783,6 @@ __global__ void k_histogram_update(uint32_t* __restrict__ hist, const StatsDev* 
 constexpr int kMaxGroup = 8;           // per-tensor operands / GAM pre-pass per launch (their table shares the 4 KB
                                        // kernel-argument segment with the statistics riders)
 constexpr int kMaxGroupSub = 16;       // 1x128 and 128x128 operands per launch
-#ifndef MOR_SUB_DOUBLE
-#define MOR_SUB_DOUBLE 0
-#endif
 
 struct GroupSub {
     int n;
@@ -821,9 +802,6 @@ __global__ __launch_bounds__(256) void k_sub1x128_group(GroupSub g) {
     if (u >= total) return;
     const int lane_off = (row * 8) * 128 + l * 8;
     u32x4 bufA[8];
-#if MOR_SUB_DOUBLE
-    u32x4 bufB[8];
-#endif
     auto load_unit = [&](u32x4 (&raw)[8], int64_t unit, int& op, int64_t& local) {
         op = group_find(g.unit_end, g.n, unit);
         local = unit - (op ? g.unit_end[op - 1] : 0);
@@ -840,27 +818,12 @@ __global__ __launch_bounds__(256) void k_sub1x128_group(GroupSub g) {
     int opA;
     int64_t locA;
     load_unit(bufA, u, opA, locA);
-#if !MOR_SUB_DOUBLE
     for (;;) {
         process(bufA, opA, locA);
         u += W;
         if (u >= total) break;
         load_unit(bufA, u, opA, locA);
     }
-#else
-    int opB;
-    int64_t locB;
-    for (;;) {
-        const int64_t ub = u + W;
-        if (ub < total) load_unit(bufB, ub, opB, locB);
-        process(bufA, opA, locA);
-        if (ub >= total) break;
-        u = ub + W;
-        if (u < total) load_unit(bufA, u, opA, locA);
-        process(bufB, opB, locB);
-        if (u >= total) break;
-    }
-#endif
 }
 
 // Statistics of sub-tensor operands of a group: pass 1 writes one partial record per workgroup into
@@ -1024,9 +987,6 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
     uint8_t* __restrict__ fp8 = t.o.fp8;
     const int64_t n_chunks = t.n_chunks, n_tiles = t.n_tiles, G = t.n_slots;
     u32x4 bufA[kTensorChunksPerThread];
-#if MOR_TQ_DOUBLE
-    u32x4 bufB[kTensorChunksPerThread];
-#endif
     auto load_tile = [&](u32x4* raw, int64_t tile) {
         const int64_t c0 = tile * kTensorChunksPerBlock + threadIdx.x;
 #pragma unroll
@@ -1082,9 +1042,6 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
                     else store8(fp8 + c * 8, codes);
                 }
                 if constexpr (CRIT == kCritEq3) (void)quant8_fast<true>(raw[u], s5, acc.f0, acc.f1);
-#if MOR_TQ_SB
-                __builtin_amdgcn_sched_barrier(0);
-#endif
                 if constexpr (FAKE) __builtin_amdgcn_sched_barrier(0);
             }
         } else {
@@ -1099,25 +1056,12 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
             }
         }
     };
-#if MOR_TQ_DOUBLE
-    for (;;) {
-        const int64_t tb = tl + G;
-        if (tb < n_tiles) load_tile(bufB, tb);
-        process(bufA, tl);
-        if (tb >= n_tiles) break;
-        tl = tb + G;
-        if (tl < n_tiles) load_tile(bufA, tl);
-        process(bufB, tb);
-        if (tl >= n_tiles) break;
-    }
-#else
     for (;;) {
         process(bufA, tl);
         tl += G;
         if (tl >= n_tiles) break;
         load_tile(bufA, tl);
     }
-#endif
     TensorPartials tp{t.err, t.err5, t.zero, t.abits};
     tensor_publish<CRIT>(acc, tp, b);
 }
@@ -1259,10 +1203,7 @@ size_t scope_workspace_bytes(int64_t) { return align16(3 * sizeof(double) * kSco
 static bool is_flat(const KShape& sh, const KOut& o) {
     return sh.ld == sh.cols && o.ld_fp8 == sh.cols && (o.bf16 == nullptr || o.ld_bf16 == sh.cols);
 }
-#ifndef MOR_SUB_BLOCKS
-#define MOR_SUB_BLOCKS 1024
-#endif
-constexpr int64_t kSubFlatMaxBlocks = MOR_SUB_BLOCKS;   // workgroups of 4 waves; each wave strides over 8 KB units
+constexpr int64_t kSubFlatMaxBlocks = 1024;   // workgroups of 4 waves; each wave strides over 8 KB units
 static int clamp_grid_y(int64_t v) { return (int)(v < 1 ? 1 : (v > 65535 ? 65535 : v)); }
 
 // The general 1 x 128 kernel: one operand per launch.
