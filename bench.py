@@ -143,11 +143,8 @@ def run_variants(ops, B, torch, dev, steps, log):
         f"({100 * rec['hbm_frac_of_peak']:.1f} %)")
     results.append(rec)
 
-    def dequant_all():
-        for o, y in zip(ops, ys):
-            r = o["out"]
-            B.mor_dequantize(o["params"], r.fp8, r.scale, r.mask, r.bf16, y)
-    ms = timed(dequant_all, steps)
+    deq_items = B.make_dequant_batch([(o["params"], o["out"], y) for o, y in zip(ops, ys)])
+    ms = timed(lambda: B.mor_dequantize_batch(deq_items), steps)
     nbytes = sum((3.0 + 1.0 * o["fallback_frac"]) * o["n"] for o in ops)      # FP8 blocks: 1 + 2; BF16 blocks: 2 + 2
     rec = {"name": "dequantize_cfg5", "ms": round(ms, 4), "input_gbs": round(2.0 * n_total / ms / 1e6, 1),
            "hbm_algorithmic_gbs": round(nbytes / ms / 1e6, 1), "hbm_frac_of_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}

@@ -282,6 +282,23 @@ mor_status mor_dequantize_e8m0(const mor_params* params, const uint8_t* fp8, int
                                uint16_t* y, int64_t ld_y, void* stream);
 
 /*
+ * Many operands in one call (e.g. every operand of a layer before a BF16 GEMM): the operands share kernel launches.
+ * Each item is de-quantized as by mor_dequantize (scale != NULL) or mor_dequantize_e8m0 (scale == NULL, scale_e8m0 and
+ * group_mantissa set).  n_items must be in [1, MOR_BATCH_MAX].
+ */
+typedef struct mor_dequant_item {
+    mor_params      params;          /* rows, cols, granularity, flags are used */
+    const uint8_t*  fp8;   int64_t ld_fp8;
+    const float*    scale;           /* [P], or NULL for the stored GAM / E8M0 form */
+    const uint8_t*  scale_e8m0;      /* [P] when scale == NULL */
+    const uint32_t* group_mantissa;  /* [2] when scale == NULL */
+    const uint8_t*  mask;            /* [P] */
+    const uint16_t* bf16;  int64_t ld_bf16;   /* fallback payload, may be NULL */
+    uint16_t*       y;     int64_t ld_y;
+} mor_dequant_item;
+mor_status mor_dequantize_batch(const mor_dequant_item* items, int32_t n_items, void* stream);
+
+/*
  * Fake quantization (Section 4, Figure 4), the form in which the paper's training runs applied MoR:
  * y = de-quantize(quantize(x)) in one call, BF16 in and BF16 out.  Blocks kept in E4M3 (or E5M2) carry
  * the information loss of that format, y = bf16_rne(fl32(value(code) * fl32(1 / scale[p]))); blocks kept

@@ -33,7 +33,7 @@ SCALING = {"fp32_amax": MOR_SCALE_FP32_AMAX, "gam": MOR_SCALE_GAM, "e8m0": MOR_S
 
 EXPORTS = ("mor_num_partitions", "mor_params_num_partitions", "mor_workspace_bytes", "mor_analyze_quantize",
            "mor_analyze_quantize_profiled", "mor_batch_workspace_bytes", "mor_analyze_quantize_batch", "mor_fake_quantize",
-           "mor_dequantize", "mor_dequantize_e8m0", "mor_select_stats", "mor_histogram_update", "mor_status_string")
+           "mor_dequantize", "mor_dequantize_e8m0", "mor_dequantize_batch", "mor_select_stats", "mor_histogram_update", "mor_status_string")
 MOR_BATCH_MAX = 64
 MOR_PROFILE_MAX = 16
 MOR_STATS_FLAG_FUSED_FALLBACK = 1
@@ -76,6 +76,12 @@ class MorProfile(C.Structure):
 class MorBatchItem(C.Structure):
     _fields_ = [("params", MorParams), ("x", C.c_void_p), ("out", MorOutputs), ("stats", C.c_void_p),
                 ("fake_y", C.c_void_p), ("ld_fake_y", C.c_int64)]
+
+
+class MorDequantItem(C.Structure):
+    _fields_ = [("params", MorParams), ("fp8", C.c_void_p), ("ld_fp8", C.c_int64), ("scale", C.c_void_p),
+                ("scale_e8m0", C.c_void_p), ("group_mantissa", C.c_void_p), ("mask", C.c_void_p), ("bf16", C.c_void_p),
+                ("ld_bf16", C.c_int64), ("y", C.c_void_p), ("ld_y", C.c_int64)]
 
 
 class MorError(RuntimeError):
@@ -123,6 +129,8 @@ def load():
         L.mor_dequantize_e8m0.argtypes = [C.POINTER(MorParams), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p]
         L.mor_dequantize_e8m0.restype = C.c_int
+        L.mor_dequantize_batch.argtypes = [C.POINTER(MorDequantItem), C.c_int32, C.c_void_p]
+        L.mor_dequantize_batch.restype = C.c_int
         L.mor_select_stats.argtypes = [C.POINTER(MorParams), C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p,
                                        C.c_void_p]
         L.mor_select_stats.restype = C.c_int
@@ -354,6 +362,31 @@ def mor_dequantize_e8m0(params: MorParams, fp8: torch.Tensor, scale_e8m0: torch.
                                     y.stride(0), _stream())
     if rc != 0:
         raise MorError(rc, "mor_dequantize_e8m0")
+
+
+def make_dequant_batch(entries) -> "C.Array":
+    """entries: sequence of (params, result: MorResult, y: torch.Tensor[, stored: bool]); ``stored`` selects the E8M0 byte +
+    group mantissa form of the scales.  Returns the host item array for :func:`mor_dequantize_batch`."""
+    arr = (MorDequantItem * len(entries))()
+    for i, entry in enumerate(entries):
+        params, r, y = entry[:3]
+        stored = entry[3] if len(entry) > 3 else False
+        arr[i].params = params
+        arr[i].fp8 = r.fp8.data_ptr(); arr[i].ld_fp8 = r.fp8.stride(0)
+        arr[i].scale = None if stored else r.scale.data_ptr()
+        arr[i].scale_e8m0 = r.scale_e8m0.data_ptr() if stored else None
+        arr[i].group_mantissa = r.group_mantissa.data_ptr() if stored else None
+        arr[i].mask = r.mask.data_ptr()
+        arr[i].bf16 = r.bf16.data_ptr() if r.bf16 is not None else None
+        arr[i].ld_bf16 = r.bf16.stride(0) if r.bf16 is not None else 0
+        arr[i].y = y.data_ptr(); arr[i].ld_y = y.stride(0)
+    return arr
+
+
+def mor_dequantize_batch(items) -> None:
+    rc = load().mor_dequantize_batch(items, len(items), _stream())
+    if rc != 0:
+        raise MorError(rc, "mor_dequantize_batch")
 
 
 def mor_select_stats(params: MorParams, err_sum: torch.Tensor, nnz: torch.Tensor, mask: torch.Tensor,

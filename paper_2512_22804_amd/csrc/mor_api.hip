@@ -172,9 +172,9 @@ mor_status mor_fake_quantize(const mor_params* p, const uint16_t* x, uint16_t* y
     return run_batch(&it, 1, 0.0f, workspace, workspace_bytes, stream, nullptr);
 }
 
-static mor_status dequantize_any(const mor_params* p, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
-                                 const uint8_t* e8m0, const uint32_t* gmant, const uint8_t* mask, const uint16_t* bf16,
-                                 int64_t ld_bf16, uint16_t* y, int64_t ld_y, void* stream) {
+static mor_status check_dequantize(const mor_params* p, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
+                                   const uint8_t* e8m0, const uint32_t* gmant, const uint8_t* mask, const uint16_t* bf16,
+                                   int64_t ld_bf16, uint16_t* y, int64_t ld_y) {
     if (!p || !fp8 || !mask || !y) return MOR_ERR_NULL;
     if (!scale && !(e8m0 && gmant)) return MOR_ERR_NULL;
     mor_status st = check_common(p);
@@ -183,8 +183,32 @@ static mor_status dequantize_any(const mor_params* p, const uint8_t* fp8, int64_
     if (ld_fp8 % 8 || ld_y % 8 || (bf16 && ld_bf16 % 8)) return MOR_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(fp8) & 7u) || !aligned16(y) || (bf16 && !aligned16(bf16))) return MOR_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(scale) | reinterpret_cast<uintptr_t>(gmant)) & 3u) return MOR_ERR_ALIGN;
+    return MOR_OK;
+}
+static mor_status dequantize_any(const mor_params* p, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
+                                 const uint8_t* e8m0, const uint32_t* gmant, const uint8_t* mask, const uint16_t* bf16,
+                                 int64_t ld_bf16, uint16_t* y, int64_t ld_y, void* stream) {
+    mor_status st = check_dequantize(p, fp8, ld_fp8, scale, e8m0, gmant, mask, bf16, ld_bf16, y, ld_y);
+    if (st != MOR_OK) return st;
     hipError_t e = mor::launch_dequantize(mor::make_geom(p->granularity, p->rows, p->cols), fp8, ld_fp8, scale, mask, bf16, ld_bf16,
                                           y, ld_y, e8m0, gmant, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MOR_OK : MOR_ERR_HIP;
+}
+
+mor_status mor_dequantize_batch(const mor_dequant_item* items, int32_t n_items, void* stream) {
+    if (!items) return MOR_ERR_NULL;
+    if (n_items <= 0 || n_items > MOR_BATCH_MAX) return MOR_ERR_SHAPE;
+    mor::DeqItem its[MOR_BATCH_MAX];
+    for (int32_t i = 0; i < n_items; ++i) {
+        const mor_dequant_item& d = items[i];
+        const bool stored = d.scale == nullptr;
+        mor_status st = check_dequantize(&d.params, d.fp8, d.ld_fp8, d.scale, d.scale_e8m0, d.group_mantissa, d.mask, d.bf16, d.ld_bf16,
+                                         d.y, d.ld_y);
+        if (st != MOR_OK) return st;
+        its[i] = mor::DeqItem{mor::make_geom(d.params.granularity, d.params.rows, d.params.cols), d.fp8, d.ld_fp8, d.scale, d.mask,
+                              d.bf16, d.ld_bf16, d.y, d.ld_y, stored ? d.scale_e8m0 : nullptr, stored ? d.group_mantissa : nullptr};
+    }
+    hipError_t e = mor::launch_dequantize_batch(its, n_items, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? MOR_OK : MOR_ERR_HIP;
 }
 

@@ -573,6 +573,58 @@ __global__ __launch_bounds__(256) void k_dequant(StatsGeom g, int pr_log2, int p
         store16(y + r * ld_y + c, mk == 2u ? dequant8<true>(q, s_inv) : dequant8<false>(q, s_inv));
     }
 }
+// Grouped form for many operands (blocks whose width is a multiple of 8): a workgroup takes 64 rows x 128 columns of
+// one operand, four 8-byte payload loads in flight per lane.
+constexpr int kMaxGroupDeq = 16;
+struct DeqOp {
+    StatsGeom g;
+    int32_t pr_log2, pc_log2;
+    int64_t strips_x;
+    const uint8_t* fp8; int64_t ld_fp8;
+    const float* scale; const uint8_t* mask;
+    const uint16_t* bf16; int64_t ld_bf16;
+    uint16_t* y; int64_t ld_y;
+    const uint8_t* e8m0; const uint32_t* gmant;
+};
+struct GroupDeq {
+    int n;
+    int64_t unit_end[kMaxGroupDeq];
+    DeqOp op[kMaxGroupDeq];
+};
+__global__ __launch_bounds__(256) void k_dequant_group(GroupDeq gd) {
+    const int op = group_find(gd.unit_end, gd.n, blockIdx.x);
+    const DeqOp& t = gd.op[op];
+    const int64_t unit = (int64_t)blockIdx.x - (op ? gd.unit_end[op - 1] : 0);
+    const int64_t rg = unit / t.strips_x, strip = unit - rg * t.strips_x;
+    const int64_t c = strip * 128 + (threadIdx.x & 15) * 8;
+    if (c >= t.g.cols) return;
+    const int64_t r0 = rg * 64 + (threadIdx.x >> 4);
+    u32x2 q[4];
+    uint32_t mk[4];
+    float s[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int64_t r = r0 + 16 * k;
+        mk[k] = 1u; s[k] = 1.0f; q[k].x = 0u; q[k].y = 0u;
+        if (r < t.g.rows) {
+            const int64_t p = (r >> t.pr_log2) * t.g.gc + (c >> t.pc_log2);
+            mk[k] = t.mask[p];
+            s[k] = dequant_scale(t.scale, t.e8m0, t.gmant, p, mk[k]);
+            if (mk[k] != 1u) q[k] = *reinterpret_cast<const u32x2*>(t.fp8 + r * t.ld_fp8 + c);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int64_t r = r0 + 16 * k;
+        if (r >= t.g.rows) continue;
+        if (mk[k] == 1u) {
+            if (t.bf16) store16(t.y + r * t.ld_y + c, load16(t.bf16 + r * t.ld_bf16 + c));
+            continue;
+        }
+        const float s_inv = 1.0f / s[k];                                   // correctly rounded IEEE division
+        store16(t.y + r * t.ld_y + c, mk[k] == 2u ? dequant8<true>(q[k], s_inv) : dequant8<false>(q[k], s_inv));
+    }
+}
 __global__ __launch_bounds__(256) void k_dequant_columns(StatsGeom g, int pr_log2, const uint8_t* __restrict__ fp8, int64_t ld_fp8,
                                                          const float* __restrict__ scale, const uint8_t* __restrict__ mask,
                                                          const uint16_t* __restrict__ bf16, int64_t ld_bf16, uint16_t* __restrict__ y,
@@ -1627,6 +1679,39 @@ static int log2_or_whole(int64_t block, int64_t dim) {
     while ((1ll << l) < block) ++l;
     return l;
 }
+hipError_t launch_dequantize_batch(const DeqItem* items, int n, hipStream_t st) {
+    static_assert(sizeof(GroupDeq) <= 3800, "kernel-argument segment is 4 KB");
+    GroupDeq g; g.n = 0;
+    int64_t total = 0;
+    auto flush = [&]() {
+        if (g.n == 0) return;
+        k_dequant_group<<<dim3((unsigned)total), dim3(256), 0, st>>>(g);
+        g.n = 0; total = 0;
+    };
+    for (int i = 0; i < n; ++i) {
+        const DeqItem& it = items[i];
+        if (it.geom.pc == 1 && it.geom.cols > 1) {       // one column per block: its own kernel
+            hipError_t e = launch_dequantize(it.geom, it.fp8, it.ld_fp8, it.scale, it.mask, it.bf16, it.ld_bf16, it.y, it.ld_y, it.e8m0,
+                                             it.gmant, st);
+            if (e != hipSuccess) return e;
+            continue;
+        }
+        const int64_t strips_x = (it.geom.cols + 127) / 128, units = strips_x * ((it.geom.rows + 63) / 64);
+        if (units > 0x7FFFFFFF) return hipErrorInvalidValue;
+        if (total + units > 0x7FFFFFFF) flush();
+        DeqOp& t = g.op[g.n];
+        t.g = it.geom; t.pr_log2 = log2_or_whole(it.geom.pr, it.geom.rows); t.pc_log2 = log2_or_whole(it.geom.pc, it.geom.cols);
+        t.strips_x = strips_x;
+        t.fp8 = it.fp8; t.ld_fp8 = it.ld_fp8; t.scale = it.scale; t.mask = it.mask; t.bf16 = it.bf16; t.ld_bf16 = it.ld_bf16;
+        t.y = it.y; t.ld_y = it.ld_y; t.e8m0 = it.e8m0; t.gmant = it.gmant;
+        total += units;
+        g.unit_end[g.n] = total;
+        if (++g.n == kMaxGroupDeq) flush();
+    }
+    flush();
+    return hipGetLastError();
+}
+
 hipError_t launch_dequantize(const StatsGeom& geom, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
                              const uint8_t* mask, const uint16_t* bf16, int64_t ld_bf16, uint16_t* y, int64_t ld_y,
                              const uint8_t* e8m0, const uint32_t* gmant, hipStream_t st) {

@@ -111,6 +111,16 @@ hipError_t launch_channel_col_items(const BatchItem* items, const int* idx, int 
 hipError_t launch_dequantize(const StatsGeom& geom, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
                              const uint8_t* mask, const uint16_t* bf16, int64_t ld_bf16, uint16_t* y, int64_t ld_y,
                              const uint8_t* e8m0, const uint32_t* gmant, hipStream_t st);
+// One operand of a de-quantize batch (validated by the caller).
+struct DeqItem {
+    StatsGeom geom;
+    const uint8_t* fp8; int64_t ld_fp8;
+    const float* scale; const uint8_t* mask;
+    const uint16_t* bf16; int64_t ld_bf16;
+    uint16_t* y; int64_t ld_y;
+    const uint8_t* e8m0; const uint32_t* gmant;
+};
+hipError_t launch_dequantize_batch(const DeqItem* items, int n, hipStream_t st);
 hipError_t launch_select_stats(const StatsGeom& geom, const float* err_sum, const uint32_t* nnz,
                                const uint8_t* mask, float th, float near_tol, void* out_dev, hipStream_t st);
 hipError_t launch_histogram_update(uint32_t* hist, const void* stats_dev, int clear, hipStream_t st);

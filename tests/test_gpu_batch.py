@@ -104,3 +104,40 @@ def test_batch_argument_errors():
         B.mor_analyze_quantize_batch(bad, 1e-5, None)
     assert e.value.status == 2
     torch.cuda.synchronize()
+
+
+def test_dequantize_batch_equals_single_calls(oracle):
+    """One mor_dequantize_batch call over operands of every partition (incl. ragged edges, three types, the stored
+    GAM form) gives bit for bit what the single-operand calls give, which in turn match the oracle."""
+    import parity
+    from paper_2512_22804_amd import binding as B
+    rng = np.random.default_rng(17)
+    cases = [("sub1x128", W.gradient(256, 512, 31, tiny_half=True), {}),
+             ("block128", W.gradient(256, 512, 32, tiny_half=True), {}),
+             ("block64", W.activation(130, 200, 33), {"ragged": True}),
+             ("channel_row", W.activation(77, 1032, 34), {}),
+             ("tensor", W.weight(128, 256, 35), {}),
+             ("sub128x1", W.gradient(256, 384, 36, tiny_half=True), {}),
+             ("channel_col", W.gradient(300, 264 - 8, 37), {}),
+             ("sub1x128", W.gradient(128, 512, 38, tiny_half=True), {"crit": "e4m3_vs_e5m2", "formats": "e4m3|e5m2|bf16"}),
+             ("block128", W.gradient(256, 256, 39, tiny_half=True), {"scaling": "gam", "stored": True})]
+    entries, singles = [], []
+    for gran, xb, kw in cases:
+        stored = kw.pop("stored", False)
+        params, g = parity.run_gpu(xb, gran, **kw)
+        a = oracle.analyze_quantize(xb, gran, bf16_fill=parity.FILL, **kw)
+        y_b = torch.full(xb.shape, 0x2222, dtype=torch.int16, device="cuda")
+        y_s = torch.full(xb.shape, 0x2222, dtype=torch.int16, device="cuda")
+        entries.append((params, g, y_b, stored))
+        if stored:
+            B.mor_dequantize_e8m0(params, g.fp8, g.scale_e8m0, g.group_mantissa, g.mask, g.bf16, y_s)
+        else:
+            B.mor_dequantize(params, g.fp8, g.scale, g.mask, g.bf16, y_s)
+        singles.append((gran, xb, kw, a, g, y_s))
+    B.mor_dequantize_batch(B.make_dequant_batch(entries))
+    torch.cuda.synchronize()
+    for (gran, xb, kw, a, g, y_s), (_, _, y_b, _) in zip(singles, entries):
+        assert torch.equal(y_b, y_s), gran
+        if np.array_equal(g.mask.cpu().numpy(), a.mask):
+            want = oracle.dequantize(a.fp8, a.scale, a.mask, a.bf16, gran, ragged=kw.get("ragged", False))
+            assert np.array_equal(parity.u16(y_b), want), gran
