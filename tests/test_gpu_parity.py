@@ -306,6 +306,14 @@ def test_full_cfg4(P):
     assert 0 < r["n_bf16"] < r["P"]
 
 
+def test_full_configurations_with_eq3(P):
+    """Every benchmark configuration once more with the E4M3-versus-E5M2 criterion (two-way recipe)."""
+    cases = list(W.cfg1()) + list(W.cfg2()) + list(W.cfg3()) + list(W.cfg4())
+    for name, xb, gran in cases:
+        r = P.compare(xb, gran, crit="e4m3_vs_e5m2", label=f"{name}-eq3")
+        print(name, gran, {k: v for k, v in r.items() if k not in ("gpu", "oracle", "params")})
+
+
 @pytest.mark.parametrize("frac", [0.0, 0.02, 0.03, 0.042, 0.0455, 0.047, 0.06, 0.2, 1.0])
 def test_per_tensor_fallback_with_and_without_proof(P, frac):
     """Per-tensor operands whose flushed fraction sweeps across the threshold: below it the error of the
