@@ -70,8 +70,8 @@ typedef enum {
  * MOR_FMT_E4M3 | MOR_FMT_BF16 (two types) or MOR_FMT_E4M3 | MOR_FMT_E5M2 | MOR_FMT_BF16 (the three-way
  * recipe of Section 3.2: a block that fails M_1 is kept in E5M2 when its dynamic range fits E5M2's
  * normal range, Eq. (4): max|b| / min|b| < 57344 / 2^-14, the minimum taken over the non-zero elements,
- * a block without non-zero elements passing; otherwise BF16).  Three types need MOR_SCOPE_PARTITION and a
- * granularity other than MOR_GRAN_TENSOR and MOR_GRAN_CHANNEL_COL. */
+ * a block without non-zero elements passing; otherwise BF16).  Three types need MOR_SCOPE_PARTITION (the
+ * recipe decides block by block); every granularity supports them. */
 enum { MOR_FMT_E4M3 = 1, MOR_FMT_E5M2 = 2, MOR_FMT_BF16 = 4 };
 
 /* mor_params.flags */

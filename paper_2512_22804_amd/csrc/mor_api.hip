@@ -48,8 +48,7 @@ static mor_status make_item(const mor_params* p, const uint16_t* x, const mor_ou
     if (p->scaling < MOR_SCALE_FP32_AMAX || p->scaling > MOR_SCALE_E8M0) return MOR_ERR_UNSUPPORTED;
     const bool three = p->formats == (MOR_FMT_E4M3 | MOR_FMT_E5M2 | MOR_FMT_BF16);
     if (!three && p->formats != (MOR_FMT_E4M3 | MOR_FMT_BF16)) return MOR_ERR_UNSUPPORTED;
-    if (three && (p->scope != MOR_SCOPE_PARTITION || p->granularity == MOR_GRAN_TENSOR || p->granularity == MOR_GRAN_CHANNEL_COL))
-        return MOR_ERR_UNSUPPORTED;
+    if (three && p->scope != MOR_SCOPE_PARTITION) return MOR_ERR_UNSUPPORTED;
     if ((!fake_y && !out->fp8) || !out->scale || !out->amax || !out->err_sum || !out->nnz || !out->mask) return MOR_ERR_NULL;
     if (p->criterion == MOR_CRIT_E4M3_VS_E5M2 && !out->err5_sum) return MOR_ERR_NULL;
     if (p->ld < p->cols) return MOR_ERR_SHAPE;

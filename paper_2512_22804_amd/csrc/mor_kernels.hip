@@ -266,21 +266,51 @@ __device__ __forceinline__ uint32_t amax2_of(const u32x4& v, uint32_t a2) {
 }
 
 // Pass A, strided: one workgroup strides over rows; lanes stride over the row's chunks.
+// A partial word of pass A: low half = amax pattern; high half = (smallest non-zero pattern - 1) when the three-way
+// recipe needs it for Eq. (4) (0xFFFF: no non-zero element seen), else 0.
+__device__ __forceinline__ uint32_t block_allmin_u16(uint32_t v, uint32_t* sh4) { return 0xFFFFu - block_allmax_u32(0xFFFFu - v, sh4); }
 __global__ __launch_bounds__(256) void k_tensor_amax_strided(const uint16_t* __restrict__ x, KShape sh,
-                                                             uint32_t* __restrict__ part) {
+                                                             uint32_t* __restrict__ part, uint32_t three) {
     __shared__ uint32_t sh4[4];
-    uint32_t a2 = 0u;
+    uint32_t a2 = 0u, mn2 = 0xFFFFFFFFu;
     const int64_t cpr = sh.cols / 8;
     for (int64_t r = blockIdx.x; r < sh.rows; r += gridDim.x)
-        for (int64_t c = threadIdx.x; c < cpr; c += 256) a2 = amax2_of(load16(x + r * sh.ld + c * 8), a2);
+        for (int64_t c = threadIdx.x; c < cpr; c += 256) {
+            const u32x4 v = load16(x + r * sh.ld + c * 8);
+            a2 = amax2_of(v, a2);
+            if (three) mn2 = min_nonzero_m1(v, mn2);
+        }
     const uint32_t a = block_allmax_u32(fold_max16(a2), sh4);
-    if (threadIdx.x == 0) part[blockIdx.x] = a;
+    uint32_t mn = 0u;
+    if (three) mn = block_allmin_u16(fold_min16(mn2), sh4);
+    if (threadIdx.x == 0) part[blockIdx.x] = a | (mn << 16);
 }
 
 __device__ __forceinline__ uint32_t global_amax_bits(const uint32_t* __restrict__ part, int n_part_amax, uint32_t* sh4) {
     uint32_t a = 0u;
-    for (int i = threadIdx.x; i < n_part_amax; i += 256) a = max(a, part[i]);
+    for (int i = threadIdx.x; i < n_part_amax; i += 256) a = max(a, part[i] & 0xFFFFu);
     return block_allmax_u32(a, sh4);
+}
+// Smallest non-zero magnitude pattern of the operand from the partial words (0 when it has no non-zero element).
+__device__ __forceinline__ uint32_t global_amin_bits(const uint32_t* __restrict__ part, int n_part_amax, uint32_t* sh4) {
+    uint32_t m = 0xFFFFu;
+    for (int i = threadIdx.x; i < n_part_amax; i += 256) m = min(m, part[i] >> 16);
+    m = block_allmin_u16(m, sh4);
+    return m == 0xFFFFu ? 0u : m + 1u;
+}
+// The E5M2 payload of a whole operand (three-way recipe, per-tensor granularity): one more sweep that overwrites the
+// E4M3 codes (or the fake-quantized values) of pass B.  One 8-element chunk:
+__device__ __forceinline__ void requant_chunk_e5m2(const uint16_t* __restrict__ src, uint8_t* __restrict__ d8, uint16_t* __restrict__ df,
+                                                   float s5, float s_inv, bool fast) {
+    if (fast) {
+        const u32x4 raw = load16(src);
+        float e0 = 0.0f, e1 = 0.0f;
+        u32x4 deq;
+        if (df) { (void)quant8_fast_deq<true, true>(raw, s5, s_inv, e0, e1, deq); store16(df, deq); }
+        else store8(d8, quant8_fast_deq<true, false>(raw, s5, s_inv, e0, e1, deq));
+    } else {
+        (void)quant8_careful_mem<true>(src, s5, df ? nullptr : d8, df, s_inv);
+    }
 }
 
 struct TensorPartials {   // one slot per pass-B workgroup (at most kMaxQuantBlocks)
@@ -386,9 +416,11 @@ __global__ __launch_bounds__(256) void k_tensor_quant_strided(const uint16_t* __
 // (P = 1), and if the decision is BF16 the grid copies the operand into the fallback buffer.
 template <int CRIT>
 __global__ __launch_bounds__(256) void k_tensor_finish(TensorPartials tp, int n_slots, unsigned long long n_padded, KOut o, float th,
-                                                       const uint16_t* __restrict__ x, KShape sh, int flat, uint32_t mode) {
+                                                       const uint16_t* __restrict__ x, KShape sh, int flat, uint32_t mode,
+                                                       uint32_t three, const uint32_t* __restrict__ amax_part, int n_amax_part) {
     __shared__ double shd[4];
     __shared__ unsigned long long shl[4];
+    __shared__ uint32_t sh4[4];
     double se = 0.0, se5 = 0.0;
     unsigned long long sz = 0;
     for (int i = threadIdx.x; i < n_slots; i += 256) {
@@ -405,9 +437,16 @@ __global__ __launch_bounds__(256) void k_tensor_finish(TensorPartials tp, int n_
     uint32_t mask;
     if constexpr (CRIT == kCritEq3) mask = (se < se5) ? 0u : 1u;
     else mask = ((n ? se / (double)n : 0.0) < (double)th) ? 0u : 1u;
+    const float s5 = block_scale(abits, kE5M2Max, mode, group_mantissa_bits(abits, kE5M2Max, mode));
+    uint32_t amin_bits = 0u;
+    if (three && mask == 1u) {             // Eq. (4): the operand is kept in E5M2 if its dynamic range fits
+        amin_bits = global_amin_bits(amax_part, n_amax_part, sh4);
+        if (range_fits_e5m2(abits, amin_bits, n ? 1u : 0u)) mask = 2u;
+    }
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         const uint32_t mg = group_mantissa_bits(abits, kE4M3Max, mode);
-        const float s = block_scale(abits, kE4M3Max, mode, mg);
+        const float s = mask == 2u ? s5 : block_scale(abits, kE4M3Max, mode, mg);
+        if (three && o.amin) o.amin[0] = __uint_as_float(amin_bits << 16);
         o.scale[0] = s;
         if (mode != kScaleFp32 && o.e8m0) o.e8m0[0] = (uint8_t)(__float_as_uint(s) >> 23);
         if (mode != kScaleFp32 && o.gmant) { o.gmant[0] = mg; o.gmant[1] = group_mantissa_bits(abits, kE5M2Max, mode); }
@@ -416,6 +455,16 @@ __global__ __launch_bounds__(256) void k_tensor_finish(TensorPartials tp, int n_
         o.nnz[0] = n > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)n;
         if constexpr (CRIT == kCritEq3) o.err5_sum[0] = (float)se5;
         o.mask[0] = (uint8_t)mask;
+    }
+    if (mask == 2u) {
+        const bool fast = abits < fast_amax_limit(mode);
+        const float s_inv = o.fake ? 1.0f / s5 : 0.0f;
+        const int64_t cpr = sh.cols / 8;
+        for (int64_t r = blockIdx.x; r < sh.rows; r += gridDim.x)
+            for (int64_t c = threadIdx.x; c < cpr; c += 256)
+                requant_chunk_e5m2(x + r * sh.ld + c * 8, o.fake ? nullptr : o.fp8 + r * o.ld_fp8 + c * 8,
+                                   o.fake ? o.fake + r * o.ld_fake + c * 8 : nullptr, s5, s_inv, fast);
+        return;
     }
     if (mask == 0u || o.bf16 == nullptr) return;
     if (flat) {
@@ -953,6 +1002,7 @@ struct TensorOp {
     KOut o;
     float th;
     uint32_t mode;                       // scaling algorithm
+    uint32_t three;                      // type list [E4M3, E5M2, BF16]
     int n_amax, n_slots;                 // workgroups this operand gets in pass A / pass B
     uint32_t* amax_part;                 // [n_amax]
     float* err; float* err5; uint32_t* zero;   // [n_slots] each
@@ -984,7 +1034,9 @@ __global__ __launch_bounds__(256) void k_tensor_amax_group(GroupTensor g, GroupS
     const TensorOp& t = g.op[op];
     const int b = blockIdx.x - (op ? g.amax_end[op - 1] : 0);
     const bool prove = t.flush_need != 0ull;
+    const bool three = t.three != 0u;
     uint32_t a2 = 0u, keep2 = 0u, seen = 0u;      // keep2: per half-word count of elements NOT certain to flush
+    uint32_t mn2 = 0xFFFFFFFFu;                   // three-way recipe: smallest non-zero pattern, minus one, per half-word
     for (int64_t tile = b; tile < t.n_tiles; tile += t.n_amax) {
         const int64_t c0 = tile * kTensorChunksPerBlock + threadIdx.x;
         if (c0 + 7 * 256 < t.n_chunks) {
@@ -993,6 +1045,10 @@ __global__ __launch_bounds__(256) void k_tensor_amax_group(GroupTensor g, GroupS
             for (int u = 0; u < 8; ++u) v[u] = load16(t.x + (c0 + u * 256) * 8);
 #pragma unroll
             for (int u = 0; u < 8; ++u) a2 = amax2_of(v[u], a2);
+            if (three) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) mn2 = min_nonzero_m1(v[u], mn2);
+            }
             if (prove) {
                 // t = running amax with 20 taken off the exponent (0 if that underflows); 1 <= m < t  <=>  m-1 < t-1
                 const uint32_t t2 = pk_sub_sat_u16(a2, 0x0A000A00u);
@@ -1008,11 +1064,17 @@ __global__ __launch_bounds__(256) void k_tensor_amax_group(GroupTensor g, GroupS
             }
         } else {
             for (int u = 0; u < 8; ++u)
-                if (c0 + u * 256 < t.n_chunks) a2 = amax2_of(load16(t.x + (c0 + u * 256) * 8), a2);
+                if (c0 + u * 256 < t.n_chunks) {
+                    const u32x4 v = load16(t.x + (c0 + u * 256) * 8);
+                    a2 = amax2_of(v, a2);
+                    if (three) mn2 = min_nonzero_m1(v, mn2);
+                }
         }
     }
     const uint32_t a = block_allmax_u32(fold_max16(a2), sh4);
-    if (threadIdx.x == 0) t.amax_part[b] = a;
+    uint32_t mn = 0u;
+    if (three) mn = block_allmin_u16(fold_min16(mn2), sh4);
+    if (threadIdx.x == 0) t.amax_part[b] = a | (mn << 16);
     if (prove) {
         const uint32_t wf = wave_allsum_u32(seen - fold_add16(keep2));
         __syncthreads();
@@ -1146,12 +1208,20 @@ __global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g, Grou
     uint32_t mask;
     if constexpr (CRIT == kCritEq3) mask = (se < se5) ? 0u : 1u;
     else mask = ((n ? se / (double)n : 0.0) < (double)t.th) ? 0u : 1u;
+    const float s5 = block_scale(abits, kE5M2Max, t.mode, group_mantissa_bits(abits, kE5M2Max, t.mode));
+    uint32_t amin_bits = 0u;
+    if (t.three && mask == 1u) {           // Eq. (4): the operand is kept in E5M2 if its dynamic range fits
+        __shared__ uint32_t sh4[4];
+        amin_bits = global_amin_bits(t.amax_part, t.n_amax, sh4);
+        if (range_fits_e5m2(abits, amin_bits, n ? 1u : 0u)) mask = 2u;
+    }
     if (b == 0 && threadIdx.x == 0) {
         const KOut& o = t.o;
         const float err_f = (float)se;
         const uint32_t nnz32 = n > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)n;
         const uint32_t mg = group_mantissa_bits(abits, kE4M3Max, t.mode);
-        const float s = block_scale(abits, kE4M3Max, t.mode, mg);
+        const float s = mask == 2u ? s5 : block_scale(abits, kE4M3Max, t.mode, mg);
+        if (t.three && o.amin) o.amin[0] = __uint_as_float(amin_bits << 16);
         o.scale[0] = s;
         if (t.mode != kScaleFp32 && o.e8m0) o.e8m0[0] = (uint8_t)(__float_as_uint(s) >> 23);
         if (t.mode != kScaleFp32 && o.gmant) { o.gmant[0] = mg; o.gmant[1] = group_mantissa_bits(abits, kE5M2Max, t.mode); }
@@ -1168,8 +1238,17 @@ __global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g, Grou
             st->hist[stats_bin(metric)] = 1u;
             const bool near = fabs((double)metric - (double)t.th) <= (double)g.near_tol * (double)t.th;
             const unsigned long long total = (unsigned long long)t.n_chunks * 8ull;
-            stats_finish(st, 1, total, (double)err_f, nnz32, mask, near ? 1ull : 0ull, 0ull, mask ? total : 0ull, 0ull, proven ? 1u : 0u);
+            stats_finish(st, 1, total, (double)err_f, nnz32, mask == 1u ? 1ull : 0ull, near ? 1ull : 0ull, mask == 2u ? 1ull : 0ull,
+                         mask == 1u ? total : 0ull, mask == 2u ? total : 0ull, proven ? 1u : 0u);
         }
+    }
+    if (mask == 2u) {
+        const bool fast = abits < fast_amax_limit(t.mode);
+        uint16_t* __restrict__ fakep = t.o.fake;
+        const float s_inv = fakep ? 1.0f / s5 : 0.0f;
+        for (int64_t c = (int64_t)b * 256 + threadIdx.x; c < t.n_chunks; c += (int64_t)nb * 256)
+            requant_chunk_e5m2(t.x + c * 8, fakep ? nullptr : t.o.fp8 + c * 8, fakep ? fakep + c * 8 : nullptr, s5, s_inv, fast);
+        return;
     }
     if (proven || mask == 0u || t.o.bf16 == nullptr) return;
     // copy in tiles of 1024 consecutive chunks (16 KB): four 16-byte loads in flight per lane
@@ -1280,15 +1359,15 @@ static hipError_t launch_sub1x128(const uint16_t* x, const KShape& sh, const KOu
     return hipGetLastError();
 }
 
-static hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int crit, float th, uint32_t mode, void* ws,
-                                hipStream_t st, KProf* prof) {
+static hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut& o, int crit, float th, uint32_t mode, uint32_t three,
+                                void* ws, hipStream_t st, KProf* prof) {
     const TensorPlan pl = plan_tensor(sh.rows, sh.cols);
     char* w = static_cast<char*>(ws);
     uint32_t* amax_part = reinterpret_cast<uint32_t*>(w + pl.off_amax_part);
     TensorPartials tp{reinterpret_cast<float*>(w + pl.off_err_part), reinterpret_cast<float*>(w + pl.off_err5_part),
                       reinterpret_cast<uint32_t*>(w + pl.off_nnz_part), reinterpret_cast<uint32_t*>(w + pl.off_decision)};
     const int n_amax = (int)(sh.rows < kMaxAmaxBlocks ? sh.rows : kMaxAmaxBlocks);
-    { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_strided<<<dim3(n_amax), dim3(256), 0, st>>>(x, sh, amax_part); }
+    { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_strided<<<dim3(n_amax), dim3(256), 0, st>>>(x, sh, amax_part, three); }
     const int64_t gx = (sh.cols + 127) / 128, gy = (sh.rows + 15) / 16;
     if (gx * gy > 0x7FFFFFFF) return hipErrorInvalidValue;
     // 16-bit zero counters per lane: at most 8 zeros per tile and lane, so 4096 tiles per workgroup are safe
@@ -1309,10 +1388,10 @@ static hipError_t launch_tensor(const uint16_t* x, const KShape& sh, const KOut&
     }
     {
         ProfScope ps(prof, kKernFallbackCopy, st);
-        const int grid = o.bf16 ? 2048 : 1;
+        const int grid = (o.bf16 || three) ? 2048 : 1;
         const int flat = (sh.ld == sh.cols && o.ld_bf16 == sh.cols) ? 1 : 0;
-        if (crit == kCritEq3) k_tensor_finish<kCritEq3><<<dim3(grid), dim3(256), 0, st>>>(tp, n_slots, n_padded, o, th, x, sh, flat, mode);
-        else k_tensor_finish<kCritEq2><<<dim3(grid), dim3(256), 0, st>>>(tp, n_slots, n_padded, o, th, x, sh, flat, mode);
+        if (crit == kCritEq3) k_tensor_finish<kCritEq3><<<dim3(grid), dim3(256), 0, st>>>(tp, n_slots, n_padded, o, th, x, sh, flat, mode, three, amax_part, n_amax);
+        else k_tensor_finish<kCritEq2><<<dim3(grid), dim3(256), 0, st>>>(tp, n_slots, n_padded, o, th, x, sh, flat, mode, three, amax_part, n_amax);
     }
     return hipGetLastError();
 }
@@ -1423,7 +1502,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 } else {
                     q.n_amax = (int)(it.sh.rows < kMaxAmaxBlocks ? it.sh.rows : kMaxAmaxBlocks);
                     ProfScope ps(prof, kKernGroupAmax, st);
-                    k_tensor_amax_strided<<<dim3(q.n_amax), dim3(256), 0, st>>>(it.x, it.sh, part);
+                    k_tensor_amax_strided<<<dim3(q.n_amax), dim3(256), 0, st>>>(it.x, it.sh, part, 0u);
                 }
             }
             int a_end = 0;
@@ -1596,7 +1675,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 for (int k = 0; k < cnt; ++k) {
                     const BatchItem& it = items[idx[k]];
                     TensorOp& t = g.op[k];
-                    t.x = it.x; t.o = it.o; t.th = it.th; t.mode = (uint32_t)it.scaling;
+                    t.x = it.x; t.o = it.o; t.th = it.th; t.mode = (uint32_t)it.scaling; t.three = it.three ? 1u : 0u;
                     t.n_chunks = it.sh.rows * it.sh.cols / 8;
                     t.n_tiles = (t.n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
                     t.n_amax = share(t.n_tiles, total_tiles, kMaxAmaxBlocks, t.n_tiles);
@@ -1610,11 +1689,11 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                     t.abits = reinterpret_cast<uint32_t*>(w + pl.off_decision);
                     t.flush_part = reinterpret_cast<uint32_t*>(w + pl.off_flush_part);
                     t.flush_need = 0ull;
-                    if (crit == kCritEq2 && it.o.bf16 && it.th > 0.0f && it.th < 0.9f)      // 1 % margin over th * N covers the
+                    if (crit == kCritEq2 && it.o.bf16 && !it.three && it.th > 0.0f && it.th < 0.9f)      // 1 % margin over th * N covers the
                         t.flush_need = (unsigned long long)(1.01 * (double)it.th * (double)(it.sh.rows * it.sh.cols)) + 1ull;   // binary32 sums
                     t.stats = static_cast<StatsDev*>(it.stats);
                     a_end += t.n_amax; s_end += t.n_slots;
-                    c_end += it.o.bf16 ? share(t.n_tiles, total_tiles, 2048, 2048) : 1;
+                    c_end += (it.o.bf16 || it.three) ? share(t.n_tiles, total_tiles, 2048, 2048) : 1;
                     g.amax_end[k] = a_end; g.slot_end[k] = s_end; g.copy_end[k] = c_end;
                 }
                 GroupStats riders; riders.n = 0; riders.near_tol = near_tol;
@@ -1657,7 +1736,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
         for (int i = 0; i < n && err == hipSuccess; ++i) {
             const BatchItem& it = items[i];
             if (route[i] != kRouteTensorStrided || it.crit != crit) continue;
-            err = launch_tensor(it.x, it.sh, it.o, it.crit, it.th, (uint32_t)it.scaling, carve(plan_tensor(it.sh.rows, it.sh.cols).bytes), st, prof);
+            err = launch_tensor(it.x, it.sh, it.o, it.crit, it.th, (uint32_t)it.scaling, it.three ? 1u : 0u, carve(plan_tensor(it.sh.rows, it.sh.cols).bytes), st, prof);
             if (err == hipSuccess && it.stats)
                 err = launch_select_stats(make_geom(it.gran, it.sh.rows, it.sh.cols), it.o.err_sum, it.o.nnz, it.o.mask, it.th, near_tol, it.stats, st);
         }

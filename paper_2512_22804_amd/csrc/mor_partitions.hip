@@ -271,6 +271,8 @@ struct ColOp {
     uint16_t* part_amax;
     float* part_err; float* part_err5; uint16_t* part_zero;
     float* col_scale; float* col_scale5;                 // [cols_padded]
+    uint16_t* col_amin;                                  // [cols_padded] (smallest non-zero pattern - 1), three-way recipe; its
+                                                         // per-strip partials use part_zero, which is free until the quantize pass
     int32_t n_strips;
 };
 struct GroupCol {
@@ -327,6 +329,7 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
     for (int k = 0; k < 8; ++k) { err[k] = 0.0f; err5[k] = 0.0f; }
     float s[8], s5[8], s_inv[8];
     bool strip_fast = true;
+    uint32_t mn_strip[4] = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};      // kColAmax with three types
     if constexpr (MODE == kColExternal) {
         bool f = true;
 #pragma unroll
@@ -364,7 +367,15 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
 #pragma unroll
                 for (int j = 0; j < 4; ++j) amax2[j] = pk_max_u16(amax2[j], raw[i][j] & 0x7FFF7FFFu);
         }
-        if constexpr (MODE == kColAmax) continue;
+        if constexpr (MODE == kColAmax) {
+            if (t.three) {
+#pragma unroll
+                for (int i = 0; i < kChunks; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) mn_strip[j] = pk_min_u16(mn_strip[j], pk_sub_u16(raw[i][j] & 0x7FFF7FFFu, 0x00010001u));
+            }
+            continue;
+        }
         uint32_t mn2[4] = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
         if constexpr (MODE == kColLocal) {
             if (t.three) {                                             // smallest non-zero magnitude per column (Eq. 4)
@@ -579,17 +590,25 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
     if constexpr (MODE == kColAmax) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) amax2[j] = colgroup_max2(amax2[j]);
+        if (t.three) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) mn_strip[j] = colgroup_min2(mn_strip[j]);
+        }
         if (lane < 16) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) sh.amax[w][cg][j] = amax2[j];
+            for (int j = 0; j < 4; ++j) { sh.amax[w][cg][j] = amax2[j]; sh.amin[w][cg][j] = mn_strip[j]; }
         }
         __syncthreads();
         if (tid < 128) {
             const int g16 = tid >> 3, k = tid & 7;
-            uint32_t a = 0u;
+            uint32_t a = 0u, mn = 0xFFFFu;
 #pragma unroll
-            for (int ww = 0; ww < 4; ++ww) a = max(a, (sh.amax[ww][g16][k >> 1] >> ((k & 1) * 16)) & 0xFFFFu);
+            for (int ww = 0; ww < 4; ++ww) {
+                a = max(a, (sh.amax[ww][g16][k >> 1] >> ((k & 1) * 16)) & 0xFFFFu);
+                mn = min(mn, (sh.amin[ww][g16][k >> 1] >> ((k & 1) * 16)) & 0xFFFFu);
+            }
             t.part_amax[strip * cols_padded + c0 + tid] = (uint16_t)a;
+            if (t.three) t.part_zero[strip * cols_padded + c0 + tid] = (uint16_t)mn;
         }
     }
     if constexpr (MODE == kColExternal) {
@@ -640,6 +659,12 @@ __global__ __launch_bounds__(256) void k_col_scales(GroupCol g) {
     uint32_t a = 0u;
 #pragma unroll 8
     for (int sidx = 0; sidx < t.n_strips; ++sidx) a = max(a, (uint32_t)t.part_amax[sidx * cols_padded + c]);
+    if (t.three) {
+        uint32_t mn = 0xFFFFu;
+#pragma unroll 8
+        for (int sidx = 0; sidx < t.n_strips; ++sidx) mn = min(mn, (uint32_t)t.part_zero[sidx * cols_padded + c]);
+        t.col_amin[c] = (uint16_t)mn;
+    }
     uint32_t mg = 0u, mg5 = 0u;
     if (t.mode) { mg = t.gam[0]; mg5 = t.gam[1]; }
     const float s = block_scale(a, kE4M3Max, t.mode, mg);
@@ -679,31 +704,62 @@ __global__ __launch_bounds__(256) void k_col_finish(GroupCol g) {
         uint32_t mk;
         if constexpr (CRIT == kCritEq3) mk = (e < e5) ? 0u : 1u;
         else mk = ((n ? e / (double)n : 0.0) < (double)t.th) ? 0u : 1u;
+        if (t.three) {                     // a column that failed M_1 is kept in E5M2 if its dynamic range fits (Eq. 4)
+            uint32_t amin_bits = 0u;
+            if (mk == 1u) {
+                amin_bits = n ? (((uint32_t)t.col_amin[c] + 1u) & 0xFFFFu) : 0u;
+                if (range_fits_e5m2(abits, amin_bits, n ? 1u : 0u)) {
+                    mk = 2u;
+                    const float s5 = t.col_scale5[c];
+                    t.o.scale[c] = s5;
+                    if (t.mode != kScaleFp32 && t.o.e8m0) t.o.e8m0[c] = (uint8_t)(__float_as_uint(s5) >> 23);
+                }
+            }
+            if (t.o.amin) t.o.amin[c] = __uint_as_float(amin_bits << 16);
+        }
         t.o.mask[c] = (uint8_t)mk;
     }
 }
 // Columns kept in BF16 are copied: 16 bytes at a time where all eight columns of a chunk are kept, else by element.
+// Columns kept in E5M2 (three-way recipe) get their payload here, element by element, over the E4M3 one.
 // A workgroup takes one 128-column strip and strides over the rows with the other workgroups of that strip.
 constexpr int kColCopyRowGroups = 32;
 __global__ __launch_bounds__(256) void k_col_fallback(GroupCol g) {
     const int op = group_find32(g.copy_end, g.n, blockIdx.x);
     const ColOp& t = g.op[op];
-    if (t.defer || t.o.bf16 == nullptr) return;
+    if (t.defer || (t.o.bf16 == nullptr && !t.three)) return;
     const int b = blockIdx.x - (op ? g.copy_end[op - 1] : 0);
     const int64_t strip = b / kColCopyRowGroups, rg = b - strip * kColCopyRowGroups;
     const int64_t c = strip * 128 + (threadIdx.x & 15) * 8;
     if (c >= t.cols) return;
-    uint32_t keep = 0u;
+    uint32_t keep = 0u, five = 0u;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) keep |= (t.o.mask[c + k] == 1u ? 1u : 0u) << k;
-    if (!keep) return;
+    for (int k = 0; k < 8; ++k) {
+        const uint32_t mk = t.o.mask[c + k];
+        keep |= (mk == 1u ? 1u : 0u) << k;
+        five |= (mk == 2u ? 1u : 0u) << k;
+    }
+    if (t.o.bf16 == nullptr) keep = 0u;
+    if (!keep && !five) return;
+    uint16_t* __restrict__ fakep = t.o.fake;
     for (int64_t r = rg * 16 + (threadIdx.x >> 4); r < t.rows; r += kColCopyRowGroups * 16) {
         const uint16_t* sp = t.x + r * t.ld + c;
-        uint16_t* dp = t.o.bf16 + r * t.o.ld_bf16 + c;
-        if (keep == 0xFFu) store16(dp, load16(sp));
-        else
+        if (keep == 0xFFu) store16(t.o.bf16 + r * t.o.ld_bf16 + c, load16(sp));
+        else if (keep) {
+            uint16_t* dp = t.o.bf16 + r * t.o.ld_bf16 + c;
             for (int k = 0; k < 8; ++k)
                 if ((keep >> k) & 1u) dp[k] = sp[k];
+        }
+        if (five) {
+            for (int k = 0; k < 8; ++k) {
+                if (!((five >> k) & 1u)) continue;
+                const float s5 = t.col_scale5[c + k];
+                float dummy = 0.0f;
+                const uint32_t code = quant1_careful<true>((uint32_t)sp[k], s5, dummy);
+                if (fakep) fakep[r * t.o.ld_fake + c + k] = (uint16_t)f32_to_bf16_rne(cvt_pk_f32<true>((int)code, false).x * (1.0f / s5));
+                else t.o.fp8[r * t.o.ld_fp8 + c + k] = (uint8_t)code;
+            }
+        }
     }
 }
 
@@ -805,7 +861,7 @@ struct ColPlan {
     int32_t tiles_per_strip;
     int n_strips;
     int64_t cols_padded;
-    size_t off_amax, off_err, off_err5, off_zero, off_scale, off_scale5, bytes;
+    size_t off_amax, off_err, off_err5, off_zero, off_scale, off_scale5, off_amin, bytes;
 };
 ColPlan plan_columns(int64_t rows, int64_t cols) {
     ColPlan pl;
@@ -824,6 +880,7 @@ ColPlan plan_columns(int64_t rows, int64_t cols) {
     pl.off_zero = off; off = align16p(off + 2 * n);
     pl.off_scale = off; off = align16p(off + 4 * (size_t)pl.cols_padded);
     pl.off_scale5 = off; off = align16p(off + 4 * (size_t)pl.cols_padded);
+    pl.off_amin = off; off = align16p(off + 2 * (size_t)pl.cols_padded);
     pl.bytes = off;
     return pl;
 }
@@ -921,6 +978,7 @@ hipError_t launch_channel_col_items(const BatchItem* items, const int* idx, int 
             t.part_zero = reinterpret_cast<uint16_t*>(w + pl.off_zero);
             t.col_scale = reinterpret_cast<float*>(w + pl.off_scale);
             t.col_scale5 = reinterpret_cast<float*>(w + pl.off_scale5);
+            t.col_amin = reinterpret_cast<uint16_t*>(w + pl.off_amin);
             total += units;
             comb += (int)((pl.cols_padded + 255) / 256);
             copy += (int)(tiles_x * kColCopyRowGroups);

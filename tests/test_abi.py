@@ -104,8 +104,10 @@ def test_argument_validation_without_a_gpu(B):
     assert call(B.make_params(128, 256, "sub128x1", ld=260)) == 3             # ld % 8
     assert call(B.make_params(128, 256, 7)) == 4
     assert call(B.make_params(128, 256, "sub1x128", formats=B.MOR_FMT_E4M3 | B.MOR_FMT_E5M2)) == 4
-    assert call(B.make_params(128, 256, "tensor", crit="e4m3_vs_e5m2", formats="e4m3|e5m2|bf16"), err5_sum=base + (4 << 30)) == 4
-    assert call(B.make_params(128, 256, "channel_col", crit="e4m3_vs_e5m2", formats="e4m3|e5m2|bf16"), err5_sum=base + (4 << 30)) == 4
+    assert call(B.make_params(128, 256, "tensor", scope="tensor", crit="e4m3_vs_e5m2", formats="e4m3|e5m2|bf16"),
+                err5_sum=base + (4 << 30)) == 4
+    assert call(B.make_params(128, 256, "channel_col", scope="tensor", crit="e4m3_vs_e5m2", formats="e4m3|e5m2|bf16"),
+                err5_sum=base + (4 << 30)) == 4
     assert call(B.make_params(128, 256, "sub1x128", scope="tensor", crit="e4m3_vs_e5m2", formats="e4m3|e5m2|bf16"),
                 err5_sum=base + (4 << 30)) == 4
     assert call(B.make_params(128, 256, "sub1x128", scaling=3)) == 4

@@ -152,17 +152,19 @@ def test_ragged_needs_the_flag(P):
 
 # ------------------------------------------------------------------ three-way selection
 
-@pytest.mark.parametrize("gran", ["sub1x128", "block128", "block64", "channel_row", "sub128x1"])
+@pytest.mark.parametrize("gran", ["sub1x128", "block128", "block64", "channel_row", "sub128x1", "channel_col"])
 @pytest.mark.parametrize("crit", ["e4m3_vs_e5m2", "mean_rel_err"])
 @pytest.mark.parametrize("scaling", ["fp32_amax", "gam", "e8m0"])
 def test_three_way(P, gran, crit, scaling):
     xb = wide_operand(21, 256, 512)
+    if gran == "channel_col":
+        xb = np.ascontiguousarray(wide_operand(21, 512, 128).T)     # 128 x 512: every column is one block of a kind
     if gran == "sub128x1":
         xb = np.ascontiguousarray(wide_operand(21, 512, 256).T)     # the three kinds of blocks along the columns
     xb[3, :128] = 0                                        # an empty block of 1 x 128
     xb[5, 7] = 0x7F80                                      # a non-finite value
     r = P.compare(xb, gran, crit=crit, threshold=TH, formats=THREE, scaling=scaling, label="three-way")
-    if gran in ("sub1x128", "sub128x1"):
+    if gran in ("sub1x128", "sub128x1", "channel_col"):
         assert r["n_e5m2"] > 10 and r["n_bf16"] > 10
     # de-quantizing from what was emitted reproduces the oracle's de-quantization (E5M2 blocks decode as E5M2)
     from paper_2512_22804_amd import binding as B
@@ -202,19 +204,66 @@ def test_three_way_handworked(P):
 def test_three_way_all_patterns(P):
     x = np.random.default_rng(5).permutation(all_patterns())
     x = np.where((x & 0x7FFF) >= 0x7F80, x & 0x80FF, x)            # finite, full dynamic range
-    for gran in ("sub1x128", "block64", "sub128x1"):
+    for gran in ("sub1x128", "block64", "sub128x1", "channel_col", "tensor"):
         for crit in ("e4m3_vs_e5m2", "mean_rel_err"):
             P.compare(x.reshape(256, 256), gran, crit=crit, formats=THREE, label="three-patterns")
+    P.compare(np.ascontiguousarray(np.sort(all_patterns() & 0x7FFF).astype(np.uint16).reshape(512, 128).T), "channel_col", crit="e4m3_vs_e5m2",
+              formats=THREE, label="three-sorted-columns")
     P.compare(np.ascontiguousarray(x.reshape(256, 256)[:200, :136]), "sub128x1", crit="e4m3_vs_e5m2", formats=THREE, ragged=True,
               label="three-patterns-ragged")
     sorted_x = np.sort(all_patterns() & 0x7FFF).astype(np.uint16)  # narrow blocks, incl. Inf/NaN blocks at the end
     P.compare(sorted_x.reshape(512, 128), "sub1x128", crit="e4m3_vs_e5m2", formats=THREE, label="three-sorted")
 
 
+def narrow_tensor(seed, rows, cols, lo_exp):
+    """One block whose magnitudes span 2^lo_exp .. 1: E4M3 flushes its small half for lo_exp < -17."""
+    rng = np.random.default_rng(seed)
+    x = np.exp2(rng.uniform(lo_exp, 0.0, size=(rows, cols))).astype(np.float32) * rng.choice([-1.0, 1.0], size=(rows, cols)).astype(np.float32)
+    x[rng.random((rows, cols)) < 0.03] = 0.0
+    return W.f32_to_bf16_bits(x)
+
+
+@pytest.mark.parametrize("crit", ["e4m3_vs_e5m2", "mean_rel_err"])
+@pytest.mark.parametrize("scaling", ["fp32_amax", "gam", "e8m0"])
+def test_three_way_per_tensor(P, crit, scaling):
+    """The whole operand as one block: E4M3 / E5M2 payload / BF16, dense and with a padded leading dimension."""
+    want = {}
+    for name, xb in (("fits-e4m3", W.activation(200, 1024, 3)), ("needs-e5m2", narrow_tensor(1, 264, 2056, -26.0)),
+                     ("too-wide", narrow_tensor(2, 264, 2056, -34.0)), ("empty", np.zeros((16, 128), dtype=np.uint16)),
+                     ("one-tile", narrow_tensor(3, 8, 64, -24.0))):
+        r = P.compare(xb, "tensor", crit=crit, threshold=TH, formats=THREE, scaling=scaling, label="three-tensor-" + name)
+        want[name] = int(r["gpu"].mask[0].item())
+        rs = P.compare(np.ascontiguousarray(np.pad(xb, ((0, 0), (0, 64)))), "tensor", crit=crit, threshold=TH, formats=THREE, scaling=scaling,
+                       cols=xb.shape[1], label="three-tensor-strided-" + name)
+        assert torch.equal(rs["gpu"].fp8, r["gpu"].fp8) and torch.equal(rs["gpu"].mask, r["gpu"].mask)
+        P.compare_fake(xb, "tensor", crit=crit, threshold=TH, formats=THREE, scaling=scaling, label="three-tensor-fake-" + name)
+    assert want["needs-e5m2"] == 2 and want["too-wide"] == 1 and want["one-tile"] == 2
+    assert want["fits-e4m3"] == (0 if crit == "mean_rel_err" else want["fits-e4m3"])
+    nonfinite = narrow_tensor(4, 64, 512, -26.0)
+    nonfinite[5, 7] = 0x7F80
+    r = P.compare(nonfinite, "tensor", crit=crit, formats=THREE, scaling=scaling, label="three-tensor-inf")
+    assert int(r["gpu"].mask[0].item()) == 1
+    big = narrow_tensor(5, 64, 512, -26.0)
+    big[0, 0] = 0x7F00                                             # amax 2^127: the careful element path
+    P.compare(big, "tensor", crit=crit, formats=THREE, scaling=scaling, label="three-tensor-big")
+    P.compare_fake(big, "tensor", crit=crit, formats=THREE, scaling=scaling, label="three-tensor-big-fake")
+
+
+def test_three_way_per_tensor_full_size(P):
+    rows, cols = 8192, 14336
+    rng = np.random.default_rng(17)
+    xb = np.empty((rows, cols), dtype=np.uint16)
+    for r0 in range(0, rows, 1024):
+        xb[r0:r0 + 1024] = narrow_tensor(100 + r0, 1024, cols, -26.0)
+    r = P.compare(xb, "tensor", crit="e4m3_vs_e5m2", formats=THREE, label="three-tensor-full")
+    assert int(r["gpu"].mask[0].item()) == 2
+    P.compare_fake(xb, "tensor", threshold=TH, formats=THREE, label="three-tensor-full-fake")
+
+
 def test_three_way_unsupported_combinations(P):
     from paper_2512_22804_amd import binding as B
     xb = W.activation(128, 256, 1)
-    for gran, scope in (("tensor", "partition"), ("channel_col", "partition"), ("sub1x128", "tensor")):
+    for gran, scope in (("channel_col", "tensor"), ("sub1x128", "tensor"), ("tensor", "tensor")):
         with pytest.raises(B.MorError) as e:
             P.run_gpu(xb, gran, scope=scope, crit="e4m3_vs_e5m2", formats=THREE)
         assert e.value.status == 4
@@ -232,14 +281,38 @@ def test_fake_quantize(P, gran, scope):
     P.compare_fake(wide_operand(4, 256, 512), gran, scope=scope, crit="e4m3_vs_e5m2", scaling="gam", label="fake-gam-eq3")
 
 
-@pytest.mark.parametrize("gran", ["sub1x128", "block128", "block64", "channel_row", "sub128x1"])
+@pytest.mark.parametrize("gran", ["sub1x128", "block128", "block64", "channel_row", "sub128x1", "channel_col"])
 def test_fake_quantize_three_way(P, gran):
     xb = wide_operand(9, 256, 512)
+    if gran == "channel_col":
+        xb = np.ascontiguousarray(wide_operand(9, 512, 128).T)
     if gran == "sub128x1":
         xb = np.ascontiguousarray(wide_operand(9, 512, 256).T)
     r = P.compare_fake(xb, gran, crit="e4m3_vs_e5m2", formats=THREE, label="fake-three")
-    if gran in ("sub1x128", "sub128x1"):
+    if gran in ("sub1x128", "sub128x1", "channel_col"):
         assert r["n_e5m2"] > 10
+
+
+def test_three_way_channel_col_many_strips_ragged(P):
+    """Columns of three kinds over several strips of tiles, ragged in both directions, with a padded leading dimension."""
+    rows, cols = 8192 + 40, 1000
+    rng = np.random.default_rng(8)
+    x = (np.exp2(rng.uniform(-3.0, 0.0, size=(rows, cols))) * rng.choice([-1.0, 1.0], size=(rows, cols))).astype(np.float32)
+    kind = rng.integers(0, 3, size=cols)
+    small = rng.random((rows, cols)) < 0.3
+    x[small & (kind == 1)[None, :]] *= np.float32(2.0 ** -20)
+    x[small & (kind == 2)[None, :]] *= np.float32(2.0 ** -36)
+    x[rng.random((rows, cols)) < 0.02] = 0.0
+    x[:, 5] = 0.0                                                  # a column without non-zero elements
+    xb = W.f32_to_bf16_bits(x)
+    xb[4000, 9] = 0x7F80                                           # a non-finite column
+    for crit in ("e4m3_vs_e5m2", "mean_rel_err"):
+        r = P.compare(xb, "channel_col", crit=crit, threshold=TH, formats=THREE, ragged=True, label="three-col-strips")
+        # (under Eq. 3 the very wide columns flush the same elements in both formats, so E4M3 wins on the rest)
+        assert r["n_e5m2"] > 200 and r["n_bf16"] > (200 if crit == "mean_rel_err" else 0)
+    P.compare(np.ascontiguousarray(np.pad(xb, ((0, 0), (0, 24)))), "channel_col", crit="e4m3_vs_e5m2", formats=THREE, ragged=True, cols=cols,
+              label="three-col-strided")
+    P.compare_fake(xb, "channel_col", crit="e4m3_vs_e5m2", formats=THREE, ragged=True, label="three-col-fake")
 
 
 @pytest.mark.parametrize("gran", ALL_GRANS)
