@@ -167,6 +167,39 @@ __device__ __forceinline__ u32x2 quant8_fast_deq(const u32x4& raw, float s, floa
     u32x2 r; r.x = (uint32_t)w0; r.y = (uint32_t)w1;
     return r;
 }
+// Eq. (3) needs the error sums of both formats.  When the E5M2 scale is exactly 128 times the E4M3 scale (57344 = 128 * 448:
+// always so for binary32 amax scales unless one of them was clamped, and for GAM / E8M0 scales whose exponents differ
+// by 7), y5 = 128 * y exactly, so the E5M2 term |y5 - q5| / |y5| equals |y - q5 / 128| / |y|: one reciprocal serves both
+// terms, and gfx950's scaled conversions (v_cvt_scalef32_pk_bf8_f32 encodes src / 2^e, v_cvt_scalef32_pk_f32_bf8
+// decodes to code * 2^e, e taken from the scale operand 2^-7) deliver q5 / 128 without forming y5.  Adds the E4M3 terms
+// to e0 / e1 and the E5M2 terms to f0 / f1; returns the E4M3 codes.
+typedef short i16x2 __attribute__((ext_vector_type(2)));
+template <bool FAKE>
+__device__ __forceinline__ u32x2 quant8_dual(const u32x4& raw, float s, float s_inv, float& e0, float& e1, float& f0, float& f1, u32x4& deq) {
+    int w0 = 0, w1 = 0;
+    constexpr float kInv128 = 0.0078125f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float y0 = __uint_as_float(raw[j] << 16) * s;
+        const float y1 = __uint_as_float(raw[j] & 0xFFFF0000u) * s;
+        f32x2 q;
+        if (j == 0) { w0 = cvt_pk8<false>(y0, y1, w0, false); q = cvt_pk_f32<false>(w0, false); }
+        if (j == 1) { w0 = cvt_pk8<false>(y0, y1, w0, true);  q = cvt_pk_f32<false>(w0, true); }
+        if (j == 2) { w1 = cvt_pk8<false>(y0, y1, w1, false); q = cvt_pk_f32<false>(w1, false); }
+        if (j == 3) { w1 = cvt_pk8<false>(y0, y1, w1, true);  q = cvt_pk_f32<false>(w1, true); }
+        const float r0 = __builtin_amdgcn_rcpf(__builtin_fabsf(y0)), r1 = __builtin_amdgcn_rcpf(__builtin_fabsf(y1));
+        e0 += __builtin_amdgcn_fmed3f(__builtin_fabsf(y0 - q.x) * r0, 0.0f, 1.0f);
+        e1 += __builtin_amdgcn_fmed3f(__builtin_fabsf(y1 - q.y) * r1, 0.0f, 1.0f);
+        const i16x2 none = {0, 0};
+        const i16x2 c5 = __builtin_amdgcn_cvt_scalef32_pk_bf8_f32(none, y0, y1, kInv128, false);
+        const f32x2 q5 = __builtin_amdgcn_cvt_scalef32_pk_f32_bf8((uint32_t)(uint16_t)c5.x, kInv128, false);
+        f0 += __builtin_amdgcn_fmed3f(__builtin_fabsf(y0 - q5.x) * r0, 0.0f, 1.0f);
+        f1 += __builtin_amdgcn_fmed3f(__builtin_fabsf(y1 - q5.y) * r1, 0.0f, 1.0f);
+        if constexpr (FAKE) deq[j] = f32_to_bf16_rne_finite(q.x * s_inv) | (f32_to_bf16_rne_finite(q.y * s_inv) << 16);
+    }
+    u32x2 r; r.x = (uint32_t)w0; r.y = (uint32_t)w1;
+    return r;
+}
 // Eight values of eight different blocks (one column each): scales s[k], error terms added to err[k].
 template <bool E5M2, bool FAKE>
 __device__ __forceinline__ u32x2 quant8_cols(const u32x4& raw, const float (&s)[8], const float (&s_inv)[8], float (&err)[8], u32x4& deq) {

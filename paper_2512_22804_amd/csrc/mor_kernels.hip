@@ -171,16 +171,25 @@ __device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const ui
         sub_unit_careful<CRIT>(x + off, fl, lane, my_s, my_s5, my_err, my_err5);
     } else {
         float e[8], e5[8];
+        // Eq. 3: when every E5M2 scale of the wave is 128 times the E4M3 one, both formats share a reciprocal (quant8_dual)
+        const bool dual = CRIT == kCritEq3 && __all(my_s5 == 128.0f * my_s);
 #define MOR_SUB_ONE(K)                                                                     \
         {                                                                                  \
             float e0 = 0.0f, e1 = 0.0f;                                                    \
-            store8(fl + K * 128, quant8_fast<false>(raw[K], row_bcast_f32<K>(my_s), e0, e1)); \
-            e[K] = e0 + e1;                                                                \
-            if constexpr (CRIT == kCritEq3) {                                              \
+            if (CRIT == kCritEq3 && dual) {                                                \
                 float f0 = 0.0f, f1 = 0.0f;                                                \
-                (void)quant8_fast<true>(raw[K], row_bcast_f32<K>(my_s5), f0, f1);          \
+                u32x4 deq;                                                                 \
+                store8(fl + K * 128, quant8_dual<false>(raw[K], row_bcast_f32<K>(my_s), 0.0f, e0, e1, f0, f1, deq)); \
                 e5[K] = f0 + f1;                                                           \
+            } else {                                                                       \
+                store8(fl + K * 128, quant8_fast<false>(raw[K], row_bcast_f32<K>(my_s), e0, e1)); \
+                if constexpr (CRIT == kCritEq3) {                                          \
+                    float f0 = 0.0f, f1 = 0.0f;                                            \
+                    (void)quant8_fast<true>(raw[K], row_bcast_f32<K>(my_s5), f0, f1);      \
+                    e5[K] = f0 + f1;                                                       \
+                }                                                                          \
             }                                                                              \
+            e[K] = e0 + e1;                                                                \
             __builtin_amdgcn_sched_barrier(0);                                             \
         }
         MOR_SUB_ONE(0) MOR_SUB_ONE(1) MOR_SUB_ONE(2) MOR_SUB_ONE(3) MOR_SUB_ONE(4) MOR_SUB_ONE(5) MOR_SUB_ONE(6) MOR_SUB_ONE(7)
@@ -1122,6 +1131,7 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
     const float s = block_scale(abits, kE4M3Max, mode, group_mantissa_bits(abits, kE4M3Max, mode));
     const float s5 = (CRIT == kCritEq3) ? block_scale(abits, kE5M2Max, mode, group_mantissa_bits(abits, kE5M2Max, mode)) : 0.0f;
     const bool fast = abits < fast_amax_limit(mode);
+    const bool dual = CRIT == kCritEq3 && s5 == 128.0f * s;
     const float s_inv = FAKE ? 1.0f / s : 0.0f;
     uint16_t* __restrict__ fakep = t.o.fake;     // fake quantization: == bf16, so a proven fallback is already in place
     TensorAcc acc{0.0f, 0.0f, 0.0f, 0.0f, 0u};
@@ -1144,6 +1154,19 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
                 (void)quant8_fast<false>(raw[u], s, acc.e0, acc.e1);
                 if constexpr (CRIT == kCritEq3) (void)quant8_fast<true>(raw[u], s5, acc.f0, acc.f1);
                 __builtin_amdgcn_sched_barrier(0);
+            }
+        } else if (CRIT == kCritEq3 && fast && dual) {
+            // both formats in one sweep with one reciprocal per element (see quant8_dual)
+#pragma unroll
+            for (int u = 0; u < kTensorChunksPerThread; ++u) {
+                const int64_t c = c0 + u * 256;
+                u32x4 deq;
+                const u32x2 codes = quant8_dual<FAKE>(raw[u], s, s_inv, acc.e0, acc.e1, acc.f0, acc.f1, deq);
+                if (c < n_chunks) {
+                    if constexpr (FAKE) store16(fakep + c * 8, deq);
+                    else store8(fp8 + c * 8, codes);
+                }
+                if constexpr (FAKE) __builtin_amdgcn_sched_barrier(0);
             }
         } else if (fast) {
 #pragma unroll

@@ -190,9 +190,30 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
         }
         return e0 + e1;
     };
-    float err = quantize(std::false_type{}, s, true);
-    float err5 = 0.0f;
-    if constexpr (CRIT == kCritEq3) err5 = quantize(std::true_type{}, s5, false);
+    float err, err5 = 0.0f;
+    if (CRIT == kCritEq3 && fast && s5 == 128.0f * s) {
+        // both formats in one sweep, one reciprocal per element (see quant8_dual)
+        const float s_inv = FAKE ? 1.0f / s : 0.0f;
+        float e0 = 0.0f, e1 = 0.0f, f0 = 0.0f, f1 = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kChunks; ++i) {
+            u32x4 deq;
+            const u32x2 codes = quant8_dual<FAKE>(raw[i], s, s_inv, e0, e1, f0, f1, deq);
+            if constexpr (BUF) {
+                if constexpr (FAKE) buf_store16(rf, is_valid(i) ? offf + i * stepf : kBufOutside, deq);
+                else buf_store8(r8, is_valid(i) ? off8 : kBufOutside, i * step8, codes);
+            } else {
+                if constexpr (FAKE) store16(dstf + i * dstf_step, deq);
+                else store8(dst8 + i * dst8_step, codes);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        err = e0 + e1;
+        err5 = f0 + f1;
+    } else {
+        err = quantize(std::false_type{}, s, true);
+        if constexpr (CRIT == kCritEq3) err5 = quantize(std::true_type{}, s5, false);
+    }
     uint32_t zeros = fold_add16(sc.zero2);
     team_allsum3<TEAM>(err, err5, zeros, sh);
     constexpr uint32_t kTeamElems = (team_is_wg<TEAM>() ? (uint32_t)team_threads<TEAM>() : 64u) * kChunks * 8u;
