@@ -71,11 +71,12 @@ def run_variants(ops, B, torch, dev, steps, log):
         torch.cuda.synchronize()
         return t0.elapsed_time(t1) / iters
 
-    def analyze_variant(name, gran_of, scope="partition", crit="mean_rel_err", scaling="fp32_amax", formats="e4m3|bf16"):
+    def analyze_variant(name, gran_of, scope="partition", crit="mean_rel_err", scaling="fp32_amax", formats="e4m3|bf16", lean=False):
         entries, outs = [], []
         for o in ops:
             gran = gran_of(o)
-            params = B.make_params(o["params"].rows, o["params"].cols, gran, scope, crit, THRESHOLD, scaling=scaling, formats=formats)
+            params = B.make_params(o["params"].rows, o["params"].cols, gran, scope, crit, THRESHOLD, scaling=scaling, formats=formats,
+                                   lean_fp8=lean)
             out = B.alloc_outputs(params, dev, want_bf16=True)
             out.workspace = None
             entries.append((params, o["x"], out, None))
@@ -93,6 +94,8 @@ def run_variants(ops, B, torch, dev, steps, log):
             n = o["n"]
             if gran == "tensor":
                 b = 5.0 * n + 2.0 * n * f                       # amax pass + quantize pass (+ fallback written once)
+                if lean:
+                    b -= 1.0 * n * f                            # no FP8 payload for an operand known to stay in BF16
             else:
                 b = 3.0 * n + META_BYTES * P
                 if scope == "tensor":
@@ -115,6 +118,7 @@ def run_variants(ops, B, torch, dev, steps, log):
 
     own = lambda o: o["gran"]
     const = lambda g: (lambda o: g)
+    analyze_variant("hot_path_lean_fp8", own, lean=True)
     analyze_variant("gam_tensor_level_block128", const("block128"), scope="tensor", scaling="gam")
     analyze_variant("gam_tensor_level_channel_row", const("channel_row"), scope="tensor", scaling="gam")
     analyze_variant("gam_tensor_level_per_tensor", const("tensor"), scaling="gam")

@@ -76,8 +76,14 @@ enum { MOR_FMT_E4M3 = 1, MOR_FMT_E5M2 = 2, MOR_FMT_BF16 = 4 };
 
 /* mor_params.flags */
 enum {
-    MOR_FLAG_RAGGED = 1         /* rows / cols need not be multiples of the block shape (the paper is silent on
+    MOR_FLAG_RAGGED = 1,        /* rows / cols need not be multiples of the block shape (the paper is silent on
                                    edges): the grid is ceil(rows/pr) x ceil(cols/pc) and edge blocks are smaller */
+    MOR_FLAG_LEAN_FP8 = 2       /* Algorithm 2 keeps one representation per block: with this flag the FP8 payload of a
+                                   block whose BF16 decision is already known when its codes would be stored is not
+                                   written (those bytes of out->fp8 keep their previous content; mask[p] == 1 says so).
+                                   Today that is a per-tensor operand whose decision the amax pass has proven (see
+                                   MOR_STATS_FLAG_FUSED_FALLBACK): the quantize pass then moves 4 instead of 5 bytes
+                                   per element.  All other outputs are unchanged.  Ignored by mor_fake_quantize. */
 };
 
 /* Acceptance metric M_1 for E4M3. */

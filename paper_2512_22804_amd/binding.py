@@ -19,6 +19,7 @@ MOR_GRAN_TENSOR, MOR_GRAN_SUB_1x128, MOR_GRAN_BLOCK_128x128 = 0, 1, 2
 MOR_GRAN_CHANNEL_ROW, MOR_GRAN_CHANNEL_COL, MOR_GRAN_SUB_128x1, MOR_GRAN_BLOCK_64x64 = 3, 4, 5, 6
 MOR_FMT_E4M3, MOR_FMT_E5M2, MOR_FMT_BF16 = 1, 2, 4
 MOR_FLAG_RAGGED = 1
+MOR_FLAG_LEAN_FP8 = 2
 MOR_CRIT_MEAN_REL_ERR, MOR_CRIT_E4M3_VS_E5M2 = 0, 1
 MOR_SCOPE_PARTITION, MOR_SCOPE_TENSOR = 0, 1
 MOR_SCALE_FP32_AMAX, MOR_SCALE_GAM, MOR_SCALE_E8M0 = 0, 1, 2
@@ -142,13 +143,14 @@ def load():
 
 def make_params(rows: int, cols: int, gran: str | int, scope: str | int = "partition", crit: str | int = "mean_rel_err",
                 threshold: float = 0.045, ld: int | None = None, formats: int | str = MOR_FMT_E4M3 | MOR_FMT_BF16,
-                scaling: str | int = MOR_SCALE_FP32_AMAX, ragged: bool = False) -> MorParams:
+                scaling: str | int = MOR_SCALE_FP32_AMAX, ragged: bool = False, lean_fp8: bool = False) -> MorParams:
     g = GRAN[gran] if isinstance(gran, str) else gran
     s = SCOPE[scope] if isinstance(scope, str) else scope
     c = CRIT[crit] if isinstance(crit, str) else crit
     sc = SCALING[scaling] if isinstance(scaling, str) else scaling
     f = FORMATS[formats] if isinstance(formats, str) else formats
-    return MorParams(rows, cols, cols if ld is None else ld, g, s, c, sc, f, threshold, MOR_FLAG_RAGGED if ragged else 0, 0)
+    return MorParams(rows, cols, cols if ld is None else ld, g, s, c, sc, f, threshold,
+                     (MOR_FLAG_RAGGED if ragged else 0) | (MOR_FLAG_LEAN_FP8 if lean_fp8 else 0), 0)
 
 
 def mor_num_partitions(gran: str | int, rows: int, cols: int) -> int:

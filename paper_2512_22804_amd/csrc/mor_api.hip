@@ -19,7 +19,7 @@ mor_status check_shape(int32_t gran, int64_t rows, int64_t cols, bool ragged) {
 }
 mor_status check_common(const mor_params* p) {
     if (!p) return MOR_ERR_NULL;
-    if ((p->flags & ~(uint32_t)MOR_FLAG_RAGGED) || p->reserved) return MOR_ERR_UNSUPPORTED;
+    if ((p->flags & ~(uint32_t)(MOR_FLAG_RAGGED | MOR_FLAG_LEAN_FP8)) || p->reserved) return MOR_ERR_UNSUPPORTED;
     return check_shape(p->granularity, p->rows, p->cols, (p->flags & MOR_FLAG_RAGGED) != 0);
 }
 
@@ -88,6 +88,7 @@ static mor_status make_item(const mor_params* p, const uint16_t* x, const mor_ou
     item->scope = p->granularity == MOR_GRAN_TENSOR ? MOR_SCOPE_PARTITION : p->scope;
     item->three = three ? 1 : 0;
     item->ragged = (p->flags & MOR_FLAG_RAGGED) ? 1 : 0;
+    item->lean = ((p->flags & MOR_FLAG_LEAN_FP8) && !fake_y) ? 1 : 0;
     item->th = p->threshold;
     item->stats = stats;
     return MOR_OK;

@@ -1012,6 +1012,7 @@ struct TensorOp {
     float th;
     uint32_t mode;                       // scaling algorithm
     uint32_t three;                      // type list [E4M3, E5M2, BF16]
+    uint32_t lean;                       // a proven BF16 operand gets no FP8 payload
     int n_amax, n_slots;                 // workgroups this operand gets in pass A / pass B
     uint32_t* amax_part;                 // [n_amax]
     float* err; float* err5; uint32_t* zero;   // [n_slots] each
@@ -1132,6 +1133,7 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
     const float s5 = (CRIT == kCritEq3) ? block_scale(abits, kE5M2Max, mode, group_mantissa_bits(abits, kE5M2Max, mode)) : 0.0f;
     const bool fast = abits < fast_amax_limit(mode);
     const bool dual = CRIT == kCritEq3 && s5 == 128.0f * s;
+    const bool emit = !(proven && t.lean != 0u);             // lean payload: the codes of a proven BF16 operand are not stored
     const float s_inv = FAKE ? 1.0f / s : 0.0f;
     uint16_t* __restrict__ fakep = t.o.fake;     // fake quantization: == bf16, so a proven fallback is already in place
     TensorAcc acc{0.0f, 0.0f, 0.0f, 0.0f, 0u};
@@ -1176,7 +1178,7 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
                 const u32x2 codes = quant8_fast_deq<false, FAKE>(raw[u], s, s_inv, acc.e0, acc.e1, deq);
                 if (c < n_chunks) {
                     if constexpr (FAKE) store16(fakep + c * 8, deq);
-                    else store8(fp8 + c * 8, codes);
+                    else if (emit) store8(fp8 + c * 8, codes);
                 }
                 if constexpr (CRIT == kCritEq3) (void)quant8_fast<true>(raw[u], s5, acc.f0, acc.f1);
                 if constexpr (FAKE) __builtin_amdgcn_sched_barrier(0);
@@ -1186,7 +1188,7 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
             for (int u = 0; u < kTensorChunksPerThread; ++u) {
                 const int64_t c = c0 + u * 256;
                 if (c < n_chunks) {
-                    acc.e0 += quant8_careful_mem<false>(x + c * 8, s, FAKE ? nullptr : fp8 + c * 8,
+                    acc.e0 += quant8_careful_mem<false>(x + c * 8, s, (FAKE || !emit) ? nullptr : fp8 + c * 8,
                                                         (FAKE && !proven) ? fakep + c * 8 : nullptr, s_inv);
                     if constexpr (CRIT == kCritEq3) acc.f0 += quant8_careful_mem<true>(x + c * 8, s5, nullptr);
                 }
@@ -1698,7 +1700,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 for (int k = 0; k < cnt; ++k) {
                     const BatchItem& it = items[idx[k]];
                     TensorOp& t = g.op[k];
-                    t.x = it.x; t.o = it.o; t.th = it.th; t.mode = (uint32_t)it.scaling; t.three = it.three ? 1u : 0u;
+                    t.x = it.x; t.o = it.o; t.th = it.th; t.mode = (uint32_t)it.scaling; t.three = it.three ? 1u : 0u; t.lean = it.lean ? 1u : 0u;
                     t.n_chunks = it.sh.rows * it.sh.cols / 8;
                     t.n_tiles = (t.n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
                     t.n_amax = share(t.n_tiles, total_tiles, kMaxAmaxBlocks, t.n_tiles);

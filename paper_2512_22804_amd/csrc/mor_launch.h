@@ -92,6 +92,7 @@ struct BatchItem {
     int scaling;            // 0 FP32 amax, 1 GAM, 2 E8M0 only
     int three;              // 1: type list [E4M3, E5M2, BF16]
     int ragged;             // 1: edge blocks may be smaller
+    int lean;               // 1: the FP8 payload of blocks already known to stay in BF16 need not be written
     float th;
     void* stats;            // device mor_stats* or nullptr
 };

@@ -212,7 +212,7 @@ def test_argument_errors(P):
     assert status(B.make_params(128, 256, 7)) == 4
     assert status(B.make_params(128, 256, "sub1x128", formats=B.MOR_FMT_E4M3 | B.MOR_FMT_E5M2)) == 4     # no BF16 at the end
     assert status(B.make_params(128, 256, "sub1x128", formats=B.MOR_FMT_E4M3)) == 4
-    bad_flags = B.make_params(128, 256, "sub1x128"); bad_flags.flags = 2
+    bad_flags = B.make_params(128, 256, "sub1x128"); bad_flags.flags = 4
     assert status(bad_flags) == 4
     assert status(B.make_params(128, 260, "sub1x128", ld=264, ragged=True)) == 2                       # cols % 8
     assert status(B.make_params(128, 256, "sub1x128", scaling=3)) == 4
@@ -333,3 +333,42 @@ def test_per_tensor_fallback_with_and_without_proof(P, frac):
         assert r["n_bf16"] == 1
     P.compare(xb, "tensor", crit="e4m3_vs_e5m2", label=f"flush-{frac}-eq3")
     P.compare(xb, "tensor", threshold=0.5, label=f"flush-{frac}-th0.5")
+
+
+@pytest.mark.parametrize("frac", [0.0, 0.04, 0.2])
+def test_lean_fp8_payload(P, frac):
+    """MOR_FLAG_LEAN_FP8: every output equals the oracle's; the FP8 payload of a per-tensor operand whose BF16
+    decision the amax pass proves is left untouched, any other operand's payload is written as usual."""
+    from paper_2512_22804_amd import binding as B
+    from oracle import mor_oracle as O
+    rng = np.random.default_rng(int(frac * 1e4) + 7)
+    rows, cols = 520, 1024
+    x = np.exp2(rng.uniform(-3.0, 3.0, size=(rows, cols))).astype(np.float32) * (rng.integers(0, 2, size=(rows, cols)) * 2 - 1)
+    tiny = rng.random((rows, cols)) < frac
+    x[tiny] = np.float32(2.0 ** -40)
+    xb = W.f32_to_bf16_bits(x)
+    for gran in ("tensor", "block128"):
+        if gran == "block128":
+            xb = np.ascontiguousarray(xb[:512])
+        params = B.make_params(xb.shape[0], cols, gran, threshold=TH, lean_fp8=True)
+        xd = P.to_dev(xb)
+        out = B.alloc_outputs(params, xd.device, want_bf16=True, bf16_fill=P.FILL)
+        out.fp8.fill_(0xAA)
+        st = torch.zeros(B.STATS_BYTES, dtype=torch.uint8, device=xd.device)
+        items = B.make_batch([(params, xd, out, st)])
+        ws = torch.empty(max(16, B.mor_batch_workspace_bytes(items)), dtype=torch.uint8, device=xd.device)
+        B.mor_analyze_quantize_batch(items, 1e-5, ws)
+        torch.cuda.synchronize()
+        stats = B.read_stats(st)
+        a = O.analyze_quantize(xb, gran, "partition", "mean_rel_err", TH, bf16_fill=P.FILL)
+        assert np.array_equal(out.mask.cpu().numpy(), a.mask) and np.array_equal(out.scale.cpu().numpy(), a.scale)
+        assert np.array_equal(out.nnz.cpu().numpy().view(np.uint32), a.nnz)
+        assert np.allclose(out.err_sum.cpu().numpy().astype(np.float64), a.err_sum, rtol=1e-5, atol=0)
+        assert np.array_equal(P.u16(out.bf16), a.bf16)
+        proven = bool(stats["flags"] & B.MOR_STATS_FLAG_FUSED_FALLBACK)
+        fp8 = out.fp8.cpu().numpy()
+        if gran == "tensor" and frac >= 0.2:
+            assert proven and a.mask[0] == 1 and np.all(fp8 == 0xAA)
+        else:
+            assert not proven and np.array_equal(fp8, a.fp8)
+            assert gran != "tensor" or a.mask[0] == (1 if frac > 0 else 0)      # 4 % flushed: BF16, but not proven beforehand
