@@ -388,6 +388,11 @@ constexpr uint32_t kBufOutside = 0x80000000u;
 __device__ __forceinline__ BufRsrc make_buf(const void* base) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7FFFFFFF, 0x00020000);
 }
+// A window of `bytes` bytes from `base`: accesses beyond it load zeros / store nothing (bytes = 0: a null window,
+// `base` is then never dereferenced).
+__device__ __forceinline__ BufRsrc make_buf_window(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
 __device__ __forceinline__ u32x4 buf_load16(BufRsrc r, uint32_t voff, uint32_t soff) {
     return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, kBufAux);
 }

@@ -1137,17 +1137,24 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
     const float s_inv = FAKE ? 1.0f / s : 0.0f;
     uint16_t* __restrict__ fakep = t.o.fake;     // fake quantization: == bf16, so a proven fallback is already in place
     TensorAcc acc{0.0f, 0.0f, 0.0f, 0.0f, 0u};
+    // Stores go through bounds-checked buffer windows over the tile (a tail tile's window is shorter; a payload that
+    // is not wanted gets a null window), so the quantization sweep has no branches and stays one basic block: with
+    // per-lane or per-operand branches around the stores the compiler defers the error terms of all eight chunks
+    // and keeps their scaled values in registers.
     auto process = [&](const u32x4* raw, int64_t tile) {
-        const int64_t c0 = tile * kTensorChunksPerBlock + threadIdx.x;
+        const int64_t c_first = tile * kTensorChunksPerBlock;
+        const int64_t c0 = c_first + threadIdx.x;
+        const int64_t left = n_chunks - c_first;
+        const uint32_t valid = (uint32_t)(left < kTensorChunksPerBlock ? left : kTensorChunksPerBlock);      // chunks of this tile
+        const BufRsrc r8 = make_buf_window(fp8 + c_first * 8, (FAKE || !emit) ? 0u : valid * 8u);
+        const BufRsrc rb = make_buf_window(bf16 + c_first * 8, proven ? valid * 16u : 0u);
+        const BufRsrc rf = make_buf_window(fakep + c_first * 8, (FAKE && !proven) ? valid * 16u : 0u);
+        const uint32_t off8 = threadIdx.x * 8u, off16 = threadIdx.x * 16u;
 #pragma unroll
         for (int u = 0; u < kTensorChunksPerThread; ++u) acc.zero2 = zero2_of(raw[u], acc.zero2);
-        if (proven) {
+        asm volatile("" : "+v"(acc.zero2));      // counted here, not sunk below the sweep (which would keep the masked words alive)
 #pragma unroll
-            for (int u = 0; u < kTensorChunksPerThread; ++u) {
-                const int64_t c = c0 + u * 256;
-                if (c < n_chunks) store16(bf16 + c * 8, raw[u]);
-            }
-        }
+        for (int u = 0; u < kTensorChunksPerThread; ++u) buf_store16(rb, off16 + u * 4096u, raw[u]);       // proven fallback
         if (fast && FAKE && proven) {
             // fake quantization of an operand already proven to stay in BF16: the output is the input (stored above);
             // only the error sums are still needed
@@ -1161,27 +1168,21 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
             // both formats in one sweep with one reciprocal per element (see quant8_dual)
 #pragma unroll
             for (int u = 0; u < kTensorChunksPerThread; ++u) {
-                const int64_t c = c0 + u * 256;
                 u32x4 deq;
                 const u32x2 codes = quant8_dual<FAKE>(raw[u], s, s_inv, acc.e0, acc.e1, acc.f0, acc.f1, deq);
-                if (c < n_chunks) {
-                    if constexpr (FAKE) store16(fakep + c * 8, deq);
-                    else store8(fp8 + c * 8, codes);
-                }
-                if constexpr (FAKE) __builtin_amdgcn_sched_barrier(0);
+                if constexpr (FAKE) buf_store16(rf, off16 + u * 4096u, deq);
+                else buf_store8(r8, off8 + u * 2048u, 0u, codes);
+                __builtin_amdgcn_sched_barrier(0);
             }
         } else if (fast) {
 #pragma unroll
             for (int u = 0; u < kTensorChunksPerThread; ++u) {
-                const int64_t c = c0 + u * 256;
                 u32x4 deq;
                 const u32x2 codes = quant8_fast_deq<false, FAKE>(raw[u], s, s_inv, acc.e0, acc.e1, deq);
-                if (c < n_chunks) {
-                    if constexpr (FAKE) store16(fakep + c * 8, deq);
-                    else if (emit) store8(fp8 + c * 8, codes);
-                }
+                if constexpr (FAKE) buf_store16(rf, off16 + u * 4096u, deq);
+                else buf_store8(r8, off8 + u * 2048u, 0u, codes);
                 if constexpr (CRIT == kCritEq3) (void)quant8_fast<true>(raw[u], s5, acc.f0, acc.f1);
-                if constexpr (FAKE) __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_sched_barrier(0);
             }
         } else {
 #pragma clang loop unroll(disable)
@@ -1542,7 +1543,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
             if (ga.n) {
                 GroupStats none; none.n = 0; none.near_tol = near_tol;
                 ProfScope ps(prof, kKernGroupAmax, st);
-                k_tensor_amax_group<<<dim3(a_end), dim3(256), 0, st>>>(ga, none, a_end);
+                k_tensor_amax_group<<<dim3(a_end), dim3(256), kResidency3, st>>>(ga, none, a_end);
             }
             { ProfScope ps(prof, kKernGroupMantissa, st); k_gam_prepare<<<dim3(m), dim3(256), 0, st>>>(gg); }
         }
@@ -1729,15 +1730,15 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                     ride_final = ride_partial > riders.n ? riders.n : 0;      // single-workgroup operands are final already
                     riders_used = true;
                 }
-                { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_group<<<dim3(a_end + ride_partial), dim3(256), 0, st>>>(g, riders, a_end); }
+                { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_group<<<dim3(a_end + ride_partial), dim3(256), kResidency3, st>>>(g, riders, a_end); }
                 {
                     ProfScope ps(prof, kKernTensorQuant, st);
                     if (fake) {
-                        if (crit == kCritEq3) k_tensor_quant_group<kCritEq3, true><<<dim3(s_end), dim3(256), 0, st>>>(g);
-                        else k_tensor_quant_group<kCritEq2, true><<<dim3(s_end), dim3(256), 0, st>>>(g);
+                        if (crit == kCritEq3) k_tensor_quant_group<kCritEq3, true><<<dim3(s_end), dim3(256), kResidency3, st>>>(g);
+                        else k_tensor_quant_group<kCritEq2, true><<<dim3(s_end), dim3(256), kResidency3, st>>>(g);
                     } else {
-                        if (crit == kCritEq3) k_tensor_quant_group<kCritEq3, false><<<dim3(s_end), dim3(256), 0, st>>>(g);
-                        else k_tensor_quant_group<kCritEq2, false><<<dim3(s_end), dim3(256), 0, st>>>(g);
+                        if (crit == kCritEq3) k_tensor_quant_group<kCritEq3, false><<<dim3(s_end), dim3(256), kResidency3, st>>>(g);
+                        else k_tensor_quant_group<kCritEq2, false><<<dim3(s_end), dim3(256), kResidency3, st>>>(g);
                     }
                 }
                 {

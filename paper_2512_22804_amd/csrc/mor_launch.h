@@ -81,6 +81,17 @@ enum KernelId {
     kKernTeamBlock = 14, kKernColumnTile = 15, kKernColumnCombine = 16
 };
 
+// Residency caps: bytes of dynamic LDS a launch reserves (and never touches) so that only 3 or 5 workgroups of 256
+// lanes fit the 160 KB of a compute unit.  The streaming passes run faster with FEWER workgroups in flight than
+// their register use would allow (measured on MI355X: pass B of the per-tensor path 214 us at 3 per unit, 226 us at 4,
+// 237 us at 6, 223 us at 2; pass A 79 us at 3 against 81 us uncapped; the 128x128 team kernel 114 us at 4 or 5 against
+// 116 us at 7; the 64x64 wave teams 0.405 ms per twelve-operand pass at 3 or 4 against 0.425 ms uncapped): fewer
+// concurrent streams keep the accesses of each HBM channel closer together.  Kernels that need many waves to hide
+// latency (de-quantization, 128x1 sub-columns) lose with a cap and have none.
+constexpr int kResidency3 = 52000;
+constexpr int kResidency4 = 39000;
+constexpr int kResidency5 = 31000;
+
 constexpr int kBatchMax = 64;     // operands per batch call
 
 // One operand of a batch (validated by the caller).

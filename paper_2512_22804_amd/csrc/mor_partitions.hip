@@ -145,6 +145,9 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
     Scan8 sc{0u, 0u};
 #pragma unroll
     for (int i = 0; i < kChunks; ++i) scan8(raw[i], sc);
+    // pin both results here: otherwise the compiler sinks the zero count below the quantization sweep and keeps the
+    // 32 masked words of the block alive across it
+    asm volatile("" : "+v"(sc.amax2), "+v"(sc.zero2));
     const uint32_t abits = team_allmax<TEAM>(fold_max16(sc.amax2), sh);
     const uint32_t mode = t.mode;
     uint32_t mg = 0u, mg5 = 0u;
@@ -226,7 +229,11 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
     if (t.three && mask == 1u) {                           // uniform over the team
         uint32_t mn2 = 0xFFFFFFFFu;
 #pragma unroll
-        for (int i = 0; i < kChunks; ++i) mn2 = min_nonzero_m1(raw[i], mn2);
+        for (int i = 0; i < kChunks; ++i) {
+            u32x4 w = raw[i];
+            asm volatile("" : "+v"(w.x), "+v"(w.y), "+v"(w.z), "+v"(w.w));      // no reuse of the masked words of the amax sweep
+            mn2 = min_nonzero_m1(w, mn2);
+        }
         const uint32_t mn = ~team_allmax<TEAM>(~fold_min16(mn2), sh) & 0xFFFFu;
         amin_bits = nnz ? mn + 1u : 0u;
         if (range_fits_e5m2(abits, amin_bits, nnz)) {
@@ -382,29 +389,42 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
             if constexpr (EDGE) raw[i] = buf_load16(rx, is_valid(i) ? xoff : kBufOutside, i * xstep);
             else raw[i] = load16(src + (int64_t)i * 16 * t.ld);
         }
-        if constexpr (MODE != kColExternal) {
+        // one sweep over the chunks for everything that reads the magnitudes (column amax, zero counts, smallest
+        // non-zero magnitude), so that no masked copy of the tile stays in registers
+        uint32_t mn2[4] = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
+        const bool want_min = MODE != kColExternal && t.three;
 #pragma unroll
-            for (int i = 0; i < kChunks; ++i)
+        for (int i = 0; i < kChunks; ++i) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) amax2[j] = pk_max_u16(amax2[j], raw[i][j] & 0x7FFF7FFFu);
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t m = raw[i][j] & 0x7FFF7FFFu;
+                if constexpr (MODE != kColExternal) amax2[j] = pk_max_u16(amax2[j], m);
+                if constexpr (MODE != kColAmax) zero2[j] = pk_add_u16(zero2[j], pk_is_zero_u16(m));
+                if constexpr (MODE != kColExternal) {
+                    if (want_min) mn2[j] = pk_min_u16(mn2[j], pk_sub_u16(m, 0x00010001u));
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // pin the results here: otherwise the compiler sinks these sweeps below the quantization loop and keeps the 32
+        // masked words alive across it
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if constexpr (MODE != kColAmax) asm volatile("" : "+v"(zero2[j]));
+            if constexpr (MODE != kColExternal) asm volatile("" : "+v"(amax2[j]));
+        }
+        if (want_min) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(mn2[j]));
         }
         if constexpr (MODE == kColAmax) {
             if (t.three) {
 #pragma unroll
-                for (int i = 0; i < kChunks; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) mn_strip[j] = pk_min_u16(mn_strip[j], pk_sub_u16(raw[i][j] & 0x7FFF7FFFu, 0x00010001u));
+                for (int j = 0; j < 4; ++j) mn_strip[j] = pk_min_u16(mn_strip[j], mn2[j]);
             }
             continue;
         }
-        uint32_t mn2[4] = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
         if constexpr (MODE == kColLocal) {
-            if (t.three) {                                             // smallest non-zero magnitude per column (Eq. 4)
-#pragma unroll
-                for (int i = 0; i < kChunks; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) mn2[j] = pk_min_u16(mn2[j], pk_sub_u16(raw[i][j] & 0x7FFF7FFFu, 0x00010001u));
-            }
             // column amax of the tile: row groups of the wave, then the four waves through LDS
 #pragma unroll
             for (int j = 0; j < 4; ++j) amax2[j] = colgroup_max2(amax2[j]);
@@ -427,7 +447,7 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 s[k] = sh.scale[cg * 8 + k];
-                s5[k] = sh.scale5[cg * 8 + k];
+                s5[k] = CRIT == kCritEq3 ? sh.scale5[cg * 8 + k] : 0.0f;     // Eq. 2: read again by the three-way path only
                 s_inv[k] = FAKE ? 1.0f / s[k] : 0.0f;
                 f = f && (uint32_t)sh.abits[cg * 8 + k] < fast_amax_limit(mode);
             }
@@ -440,10 +460,6 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
         const uint32_t off8 = (uint32_t)((tid >> 4) * o.ld_fp8 + cg * 8), step8 = (uint32_t)(16 * o.ld_fp8);
         const BufRsrc rf = make_buf(FAKE ? o.fake + r0 * o.ld_fake + c0 : nullptr);
         const uint32_t offf = (uint32_t)(((tid >> 4) * o.ld_fake + cg * 8) * 2), stepf = (uint32_t)(16 * o.ld_fake * 2);
-#pragma unroll
-        for (int i = 0; i < kChunks; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) zero2[j] = pk_add_u16(zero2[j], pk_is_zero_u16(raw[i][j] & 0x7FFF7FFFu));
         if (strip_fast) {
 #pragma unroll
             for (int i = 0; i < kChunks; ++i) {
@@ -548,6 +564,10 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
                 const uint64_t sel = (mk8 >> 1) & 0x0101010101010101ull;       // byte k = 1: column k is kept in E5M2
                 if (sel) {
                     // the E5M2 payload replaces the E4M3 one in those columns (whole chunks are stored again)
+                    if constexpr (CRIT != kCritEq3) {
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) s5[k] = sh.scale5[cg * 8 + k];
+                    }
 #pragma clang loop unroll(disable)
                     for (int i = 0; i < kChunks; ++i) {
                         if (!is_valid(i)) continue;
@@ -804,8 +824,9 @@ size_t align16p(size_t v) { return (v + 15) & ~(size_t)15; }
 template <int TEAM, bool FAKE, bool EDGE>
 void launch_team_crit(const GroupTeam& g, int64_t total, int crit, hipStream_t st) {
     const dim3 grid((unsigned)total), block(TEAM == kTeamBigRow ? 1024 : 256);
-    if (crit == kCritEq3) k_team_group<TEAM, kCritEq3, FAKE, EDGE><<<grid, block, 0, st>>>(g);
-    else k_team_group<TEAM, kCritEq2, FAKE, EDGE><<<grid, block, 0, st>>>(g);
+    const int lds = TEAM == kTeamWg128 ? kResidency5 : (TEAM == kTeamWave64 ? kResidency4 : 0);
+    if (crit == kCritEq3) k_team_group<TEAM, kCritEq3, FAKE, EDGE><<<grid, block, lds, st>>>(g);
+    else k_team_group<TEAM, kCritEq2, FAKE, EDGE><<<grid, block, lds, st>>>(g);
 }
 template <int TEAM>
 void launch_team_kind(const GroupTeam& g, int64_t total, int crit, bool fake, bool edge, hipStream_t st) {
