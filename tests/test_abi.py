@@ -120,6 +120,7 @@ def test_argument_validation_without_a_gpu(B):
     assert call(B.make_params(128, 256, "block128", scope="tensor")) == 5
     p = B.make_params(128, 256, "sub1x128"); p.flags = 8
     assert call(p) == 4
+    assert call(B.make_params(128, 256, "tensor", lean_fp8=True, ragged=True)) == 5       # both flags pass validation
     p = B.make_params(128, 256, "sub1x128"); p.reserved = 1
     assert call(p) == 4
     # fake quantization: y must not alias x, needs 16-byte alignment and ld_y >= cols
