@@ -53,12 +53,17 @@ def run_gpu(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "me
 
 def compare(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "mean_rel_err", threshold: float = 0.045,
             cols: int | None = None, label: str = "", scaling: str = "fp32_amax", formats: str = "e4m3|bf16",
-            ragged: bool = False) -> dict:
+            ragged: bool = False, gpu=None) -> dict:
+    """``gpu``: (params, outputs) of a call already made (e.g. one operand of a batch call; its fallback buffer pre-filled
+    with FILL); by default the operand is run through mor_analyze_quantize here."""
     rows, ld = xb.shape
     cols = ld if cols is None else cols
     print(f"[parity] {label} shape={rows}x{cols} ld={ld} gran={gran} scope={scope} crit={crit} th={threshold} "
           f"scaling={scaling} formats={formats} ragged={ragged}", flush=True)
-    params, g = run_gpu(xb, gran, scope, crit, threshold, cols, scaling=scaling, formats=formats, ragged=ragged)
+    if gpu is None:
+        params, g = run_gpu(xb, gran, scope, crit, threshold, cols, scaling=scaling, formats=formats, ragged=ragged)
+    else:
+        params, g = gpu
     a = O.analyze_quantize(xb, gran, scope, crit, threshold, bf16_fill=FILL, ld=ld, cols=cols, scaling=scaling,
                            formats=formats, ragged=ragged)
     P = a.mask.size

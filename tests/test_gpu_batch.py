@@ -141,3 +141,35 @@ def test_dequantize_batch_equals_single_calls(oracle):
         if np.array_equal(g.mask.cpu().numpy(), a.mask):
             want = oracle.dequantize(a.fp8, a.scale, a.mask, a.bf16, gran, ragged=kw.get("ragged", False))
             assert np.array_equal(parity.u16(y_b), want), gran
+
+
+def test_cfg5_full_size_batch_matches_oracle(oracle):
+    """The benchmark's own launch configuration: the twelve full-size operands of the layer sweep in one
+    mor_analyze_quantize_batch call with statistics, every output of every operand against the oracle."""
+    import parity
+    from paper_2512_22804_amd import binding as B
+    from paper_2512_22804_amd import workloads as W
+    dev = torch.device("cuda:0")
+    sweep = W.cfg5()
+    entries = []
+    for name, xb, gran in sweep:
+        params = B.make_params(xb.shape[0], xb.shape[1], gran, "partition", "mean_rel_err", TH)
+        out = B.alloc_outputs(params, dev, bf16_fill=parity.FILL)
+        st = torch.zeros(B.STATS_BYTES, dtype=torch.uint8, device=dev)
+        entries.append((params, parity.to_dev(xb), out, st))
+    items = B.make_batch(entries)
+    ws = torch.empty(max(16, B.mor_batch_workspace_bytes(items)), dtype=torch.uint8, device=dev)
+    for _ in range(2):                       # the second call reuses the workspace as the benchmark's loop does
+        B.mor_analyze_quantize_batch(items, 1e-5, ws)
+    torch.cuda.synchronize()
+    n_fp8 = n_all = 0
+    for (name, xb, gran), (params, _, out, st) in zip(sweep, entries):
+        r = parity.compare(xb, gran, threshold=TH, label="cfg5-batch-" + name, gpu=(params, out))
+        got = B.read_stats(st)
+        a = r["oracle"]
+        ref = oracle.select_stats(out.err_sum.cpu().numpy(), a.nnz, a.mask, xb.shape[0], xb.shape[1], gran, TH, 1e-5)
+        for k in ("n_part", "n_fp8_part", "n_bf16_part", "n_elem_fp8", "n_elem_bf16", "nnz_total", "hist"):
+            assert got[k] == ref[k], (name, k, got[k], ref[k])
+        n_fp8 += got["n_elem_fp8"]; n_all += xb.size
+        del r
+    assert n_all == 503316480 and abs(n_fp8 / n_all - 0.5) < 0.01      # forward operands FP8, gradients BF16
