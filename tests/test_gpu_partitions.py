@@ -238,6 +238,24 @@ def test_three_way_per_tensor(P, crit, scaling):
         assert torch.equal(rs["gpu"].fp8, r["gpu"].fp8) and torch.equal(rs["gpu"].mask, r["gpu"].mask)
         P.compare_fake(xb, "tensor", crit=crit, threshold=TH, formats=THREE, scaling=scaling, label="three-tensor-fake-" + name)
     assert want["needs-e5m2"] == 2 and want["too-wide"] == 1 and want["one-tile"] == 2
+    # the statistics record that the batch call's finish pass writes itself counts the E5M2 operand as such
+    from paper_2512_22804_amd import binding as B
+    xb = narrow_tensor(1, 264, 2056, -26.0)
+    params = B.make_params(xb.shape[0], xb.shape[1], "tensor", crit=crit, threshold=TH, formats=THREE, scaling=scaling)
+    xd = P.to_dev(xb)
+    out = B.alloc_outputs(params, xd.device)
+    st = torch.zeros(B.STATS_BYTES, dtype=torch.uint8, device=xd.device)
+    st2 = torch.zeros(B.STATS_BYTES, dtype=torch.uint8, device=xd.device)
+    items = B.make_batch([(params, xd, out, st)])
+    ws = torch.empty(max(16, B.mor_batch_workspace_bytes(items)), dtype=torch.uint8, device=xd.device)
+    B.mor_analyze_quantize_batch(items, 1e-5, ws)
+    B.mor_select_stats(params, out.err_sum, out.nnz, out.mask, 1e-5, st2)
+    torch.cuda.synchronize()
+    got, ref = B.read_stats(st), B.read_stats(st2)
+    assert got["n_e5m2_part"] == 1 and got["n_elem_e5m2"] == xb.size and got["n_fp8_part"] == 0 and got["n_bf16_part"] == 0
+    for k in ref:
+        if k not in ("flags", "err_sum_total", "mean_err"):
+            assert got[k] == ref[k], (k, got[k], ref[k])
     assert want["fits-e4m3"] == (0 if crit == "mean_rel_err" else want["fits-e4m3"])
     nonfinite = narrow_tensor(4, 64, 512, -26.0)
     nonfinite[5, 7] = 0x7F80
