@@ -173,3 +173,45 @@ def test_cfg5_full_size_batch_matches_oracle(oracle):
         n_fp8 += got["n_elem_fp8"]; n_all += xb.size
         del r
     assert n_all == 503316480 and abs(n_fp8 / n_all - 0.5) < 0.01      # forward operands FP8, gradients BF16
+
+
+def test_batch_call_can_be_captured_in_a_graph():
+    """The library only launches kernels (no allocation, memset or synchronization), so a batch call can be captured
+    in a HIP graph; every replay, with eager work and synchronizations in between, gives the eager call's outputs."""
+    import parity
+    from paper_2512_22804_amd import binding as B
+    dev = torch.device("cuda:0")
+    entries = []
+    for name, xb, gran, scope, crit, cols in build_cases():
+        rows, ld = xb.shape
+        params = B.make_params(rows, ld if cols is None else cols, gran, scope, crit, TH, ld=ld)
+        out = B.alloc_outputs(params, dev, bf16_fill=parity.FILL)
+        st = torch.zeros(B.STATS_BYTES, dtype=torch.uint8, device=dev)
+        entries.append((params, parity.to_dev(xb), out, st))
+    items = B.make_batch(entries)
+    ws = torch.empty(max(16, B.mor_batch_workspace_bytes(items)), dtype=torch.uint8, device=dev)
+    fields = ("fp8", "bf16", "scale", "amax", "nnz", "mask", "err_sum", "err5_sum")
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [[getattr(o, f).clone() for f in fields if getattr(o, f) is not None] + [st.clone()] for _, _, o, st in entries]
+
+    def scrub():
+        for _, _, o, st in entries:
+            o.fp8.zero_(); o.mask.fill_(9); o.err_sum.fill_(-1.0); st.zero_()
+            o.bf16.fill_(parity.FILL if parity.FILL < 0x8000 else parity.FILL - 0x10000)
+
+    B.mor_analyze_quantize_batch(items, 1e-2, ws)
+    want = snapshot()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.mor_analyze_quantize_batch(items, 1e-2, ws)
+    for _ in range(3):
+        scrub()
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(want, got):
+            for ta, tb in zip(a, b):
+                assert torch.equal(ta.view(torch.uint8), tb.view(torch.uint8))
+        B.mor_analyze_quantize_batch(items, 1e-2, ws)       # eager work between the replays
+        torch.cuda.synchronize()
