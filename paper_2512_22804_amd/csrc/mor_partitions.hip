@@ -65,21 +65,23 @@ __device__ __forceinline__ uint32_t team_allmax(uint32_t v, TeamShared& sh) {
     }
     return v;
 }
-template <int TEAM>
+// `b` (the E5M2 error sum) is only reduced when WITH_B; otherwise it stays as it is (zero under Eq. 2).
+template <int TEAM, bool WITH_B>
 __device__ __forceinline__ void team_allsum3(float& a, float& b, uint32_t& z, TeamShared& sh) {
     a = wave_allsum_f32(a);
-    b = wave_allsum_f32(b);
+    if constexpr (WITH_B) b = wave_allsum_f32(b);
     z = wave_allsum_u32(z);
     if constexpr (team_is_wg<TEAM>()) {
         constexpr int NW = team_waves<TEAM>();
         const int w = threadIdx.x >> 6;
-        if ((threadIdx.x & 63) == 0) { sh.f[w] = a; sh.f[NW + w] = b; sh.u[w] = z; }
+        if ((threadIdx.x & 63) == 0) { sh.f[w] = a; if constexpr (WITH_B) sh.f[NW + w] = b; sh.u[w] = z; }
         __syncthreads();
-        a = 0.0f; b = 0.0f; z = 0u;
+        a = 0.0f; z = 0u;
+        if constexpr (WITH_B) b = 0.0f;
 #pragma unroll
         for (int k = 0; k < NW; k += 4) {       // fixed order: deterministic
             a += (sh.f[k] + sh.f[k + 1]) + (sh.f[k + 2] + sh.f[k + 3]);
-            b += (sh.f[NW + k] + sh.f[NW + k + 1]) + (sh.f[NW + k + 2] + sh.f[NW + k + 3]);
+            if constexpr (WITH_B) b += (sh.f[NW + k] + sh.f[NW + k + 1]) + (sh.f[NW + k + 2] + sh.f[NW + k + 3]);
             z += (sh.u[k] + sh.u[k + 1]) + (sh.u[k + 2] + sh.u[k + 3]);
         }
         __syncthreads();
@@ -153,7 +155,8 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
     uint32_t mg = 0u, mg5 = 0u;
     if (mode) { mg = t.gam[0]; mg5 = t.gam[1]; }
     float s = block_scale(abits, kE4M3Max, mode, mg);
-    const float s5 = block_scale(abits, kE5M2Max, mode, mg5);
+    float s5 = 0.0f;                                       // only Eq. 3 and the three-way recipe look at E5M2
+    if (CRIT == kCritEq3 || t.three) s5 = block_scale(abits, kE5M2Max, mode, mg5);
     // ---- destinations
     uint8_t* __restrict__ dst8 = FAKE ? nullptr : o.fp8 + (r0 + trow) * o.ld_fp8 + c0 + tcol;
     const int64_t dst8_step = (int64_t)rstep * o.ld_fp8 + cstep;
@@ -218,7 +221,7 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
         if constexpr (CRIT == kCritEq3) err5 = quantize(std::true_type{}, s5, false);
     }
     uint32_t zeros = fold_add16(sc.zero2);
-    team_allsum3<TEAM>(err, err5, zeros, sh);
+    team_allsum3<TEAM, CRIT == kCritEq3>(err, err5, zeros, sh);
     constexpr uint32_t kTeamElems = (team_is_wg<TEAM>() ? (uint32_t)team_threads<TEAM>() : 64u) * kChunks * 8u;
     const uint32_t nnz = kTeamElems - zeros;
     if (abits >= kInfBits) { err = __builtin_inff(); err5 = __builtin_inff(); }
