@@ -287,6 +287,12 @@ __global__ __launch_bounds__(TEAM == kTeamBigRow ? 1024 : 256) void k_team_group
 //   kColExternal  quantize with those scales, strip error sums -> workspace partials
 //   (combine)     column error sums, decision, fallback columns
 // 128 x 1 sub-columns are complete inside a tile (kColLocal): one pass.
+// Proven columns (Eq. 2, two types, fallback buffer present): the amax pass also counts, per column, elements that are
+// certain to flush -- non-zero and below 2^-20 of a LOWER bound of the column amax (the column's amax inside the
+// strip's first tile), hence below 2^-20 of the final amax: they scale to less than half the smallest E4M3
+// subnormal and contribute exactly 1 each.  A count above 1.01 * th * rows + 1 fixes the BF16 decision whatever the
+// other terms are; the quantize pass then writes those columns' BF16 payload from its registers and the fallback
+// pass skips them.  The decision itself is still taken from the full error sums.
 // ======================================================================================
 enum { kColLocal = 0, kColAmax = 1, kColExternal = 2 };
 struct ColOp {
@@ -296,7 +302,7 @@ struct ColOp {
     int64_t tiles_x;            // 128-column strips
     int32_t tiles_per_strip;    // 128-row tiles a workgroup sweeps (1 for kColLocal)
     float th;
-    uint8_t defer, mode, three, pad1;
+    uint8_t defer, mode, three, prove;   // prove: count certain flushes in the amax pass (see below)
     const uint32_t* gam;
     // per-channel columns: workspace, [n_strips x cols_padded] each, cols_padded = tiles_x * 128
     uint16_t* part_amax;
@@ -304,7 +310,11 @@ struct ColOp {
     float* col_scale; float* col_scale5;                 // [cols_padded]
     uint16_t* col_amin;                                  // [cols_padded] (smallest non-zero pattern - 1), three-way recipe; its
                                                          // per-strip partials use part_zero, which is free until the quantize pass
+    uint8_t* col_proven;                                 // [cols_padded] 1: the column's BF16 decision is proven before the quantize
+                                                         // pass; the per-strip flush counts (16 bits) use part_err until then
+    uint32_t flush_need;                                 // that many certain flushes in a column prove its BF16 decision
     int32_t n_strips;
+    int32_t copy_groups;                                 // workgroups per 128-column strip in the fallback-column pass
 };
 struct GroupCol {
     int n;
@@ -361,6 +371,11 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
     float s[8], s5[8], s_inv[8];
     bool strip_fast = true;
     uint32_t mn_strip[4] = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};      // kColAmax with three types
+    uint32_t bound2[4] = {0u, 0u, 0u, 0u}, flush2[4] = {0u, 0u, 0u, 0u};              // kColAmax with the flush-count proof
+    uint64_t pv8 = 0ull;                                                                // kColExternal: proven flags of my 8 columns
+    if constexpr (MODE == kColExternal) {
+        if (t.prove) pv8 = *reinterpret_cast<const uint64_t*>(t.col_proven + c0 + cg * 8);
+    }
     if constexpr (MODE == kColExternal) {
         bool f = true;
 #pragma unroll
@@ -425,7 +440,57 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
 #pragma unroll
                 for (int j = 0; j < 4; ++j) mn_strip[j] = pk_min_u16(mn_strip[j], mn2[j]);
             }
+            if (t.prove) {                                             // uniform over the workgroup
+                if (tt == 0) {
+                    // lower bound of the column amax: this tile's column amax over the whole workgroup, taken down by
+                    // 20 binades (0 if that underflows), minus one for the comparison below
+                    uint32_t a[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) a[j] = colgroup_max2(amax2[j]);
+                    if (lane < 16) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) sh.amax[w][cg][j] = a[j];
+                    }
+                    __syncthreads();
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        a[j] = pk_max_u16(pk_max_u16(sh.amax[0][cg][j], sh.amax[1][cg][j]), pk_max_u16(sh.amax[2][cg][j], sh.amax[3][cg][j]));
+                        bound2[j] = pk_sub_sat_u16(pk_sub_sat_u16(a[j], 0x0A000A00u), 0x00010001u);
+                    }
+                    __syncthreads();                                   // sh.amax is written again when the strip is published
+                }
+                // certain flush: 1 <= m < t  <=>  m - 1 < t - 1 (m - 1 wraps to 0xFFFF for zeros, which never count)
+#pragma unroll
+                for (int i = 0; i < kChunks; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t mm1 = pk_sub_u16(raw[i][j] & 0x7FFF7FFFu, 0x00010001u);
+                        flush2[j] = pk_add_u16(flush2[j], pk_min_u16(pk_sub_sat_u16(bound2[j], mm1), 0x00010001u));
+                    }
+            }
             continue;
+        }
+        if constexpr (MODE == kColExternal) {
+            if (pv8) {                                                 // per lane: some of my columns are proven to stay in BF16
+                if (pv8 == 0x0101010101010101ull) {
+                    const BufRsrc rb = make_buf(o.bf16 + r0 * o.ld_bf16 + c0);
+                    const uint32_t offb = (uint32_t)(((tid >> 4) * o.ld_bf16 + cg * 8) * 2), stepb = (uint32_t)(16 * o.ld_bf16 * 2);
+#pragma unroll
+                    for (int i = 0; i < kChunks; ++i) {
+                        if constexpr (EDGE) buf_store16(rb, is_valid(i) ? offb + i * stepb : kBufOutside, raw[i]);
+                        else store16(o.bf16 + (row + (int64_t)i * 16) * o.ld_bf16 + col, raw[i]);
+                    }
+                } else {
+#pragma clang loop unroll(disable)
+                    for (int i = 0; i < kChunks; ++i) {
+                        if (!is_valid(i)) continue;
+                        const uint16_t* sp = src + (int64_t)i * 16 * t.ld;
+                        uint16_t* dp = o.bf16 + (row + (int64_t)i * 16) * o.ld_bf16 + col;
+                        for (int k = 0; k < 8; ++k)
+                            if ((pv8 >> (8 * k)) & 1ull) dp[k] = sp[k];
+                    }
+                }
+            }
         }
         if constexpr (MODE == kColLocal) {
             // column amax of the tile: row groups of the wave, then the four waves through LDS
@@ -638,21 +703,27 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
 #pragma unroll
             for (int j = 0; j < 4; ++j) mn_strip[j] = colgroup_min2(mn_strip[j]);
         }
+        if (t.prove) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) flush2[j] = colgroup_add2(flush2[j]);     // <= 4 x 8 x 16 per half-word
+        }
         if (lane < 16) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { sh.amax[w][cg][j] = amax2[j]; sh.amin[w][cg][j] = mn_strip[j]; }
+            for (int j = 0; j < 4; ++j) { sh.amax[w][cg][j] = amax2[j]; sh.amin[w][cg][j] = mn_strip[j]; sh.zero[w][cg][j] = flush2[j]; }
         }
         __syncthreads();
         if (tid < 128) {
             const int g16 = tid >> 3, k = tid & 7;
-            uint32_t a = 0u, mn = 0xFFFFu;
+            uint32_t a = 0u, mn = 0xFFFFu, fl = 0u;
 #pragma unroll
             for (int ww = 0; ww < 4; ++ww) {
                 a = max(a, (sh.amax[ww][g16][k >> 1] >> ((k & 1) * 16)) & 0xFFFFu);
                 mn = min(mn, (sh.amin[ww][g16][k >> 1] >> ((k & 1) * 16)) & 0xFFFFu);
+                fl += (sh.zero[ww][g16][k >> 1] >> ((k & 1) * 16)) & 0xFFFFu;
             }
             t.part_amax[strip * cols_padded + c0 + tid] = (uint16_t)a;
             if (t.three) t.part_zero[strip * cols_padded + c0 + tid] = (uint16_t)mn;
+            if (t.prove) reinterpret_cast<uint16_t*>(t.part_err)[strip * cols_padded + c0 + tid] = (uint16_t)fl;
         }
     }
     if constexpr (MODE == kColExternal) {
@@ -708,6 +779,13 @@ __global__ __launch_bounds__(256) void k_col_scales(GroupCol g) {
 #pragma unroll 8
         for (int sidx = 0; sidx < t.n_strips; ++sidx) mn = min(mn, (uint32_t)t.part_zero[sidx * cols_padded + c]);
         t.col_amin[c] = (uint16_t)mn;
+    }
+    if (t.prove) {
+        const uint16_t* __restrict__ part_flush = reinterpret_cast<const uint16_t*>(t.part_err);
+        uint32_t fl = 0u;
+#pragma unroll 8
+        for (int sidx = 0; sidx < t.n_strips; ++sidx) fl += part_flush[sidx * cols_padded + c];
+        t.col_proven[c] = (c < t.cols && fl >= t.flush_need) ? 1 : 0;
     }
     uint32_t mg = 0u, mg5 = 0u;
     if (t.mode) { mg = t.gam[0]; mg5 = t.gam[1]; }
@@ -767,26 +845,27 @@ __global__ __launch_bounds__(256) void k_col_finish(GroupCol g) {
 // Columns kept in BF16 are copied: 16 bytes at a time where all eight columns of a chunk are kept, else by element.
 // Columns kept in E5M2 (three-way recipe) get their payload here, element by element, over the E4M3 one.
 // A workgroup takes one 128-column strip and strides over the rows with the other workgroups of that strip.
-constexpr int kColCopyRowGroups = 32;
+constexpr int kColCopyRowGroups = 32;      // at most; about 1024 workgroups per operand are enough
 __global__ __launch_bounds__(256) void k_col_fallback(GroupCol g) {
     const int op = group_find32(g.copy_end, g.n, blockIdx.x);
     const ColOp& t = g.op[op];
     if (t.defer || (t.o.bf16 == nullptr && !t.three)) return;
     const int b = blockIdx.x - (op ? g.copy_end[op - 1] : 0);
-    const int64_t strip = b / kColCopyRowGroups, rg = b - strip * kColCopyRowGroups;
+    const int64_t strip = b / t.copy_groups, rg = b - strip * t.copy_groups;
     const int64_t c = strip * 128 + (threadIdx.x & 15) * 8;
     if (c >= t.cols) return;
     uint32_t keep = 0u, five = 0u;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
         const uint32_t mk = t.o.mask[c + k];
-        keep |= (mk == 1u ? 1u : 0u) << k;
+        const bool done = t.prove && t.col_proven[c + k] != 0;       // written by the quantize pass already
+        keep |= ((mk == 1u && !done) ? 1u : 0u) << k;
         five |= (mk == 2u ? 1u : 0u) << k;
     }
     if (t.o.bf16 == nullptr) keep = 0u;
     if (!keep && !five) return;
     uint16_t* __restrict__ fakep = t.o.fake;
-    for (int64_t r = rg * 16 + (threadIdx.x >> 4); r < t.rows; r += kColCopyRowGroups * 16) {
+    for (int64_t r = rg * 16 + (threadIdx.x >> 4); r < t.rows; r += (int64_t)t.copy_groups * 16) {
         const uint16_t* sp = t.x + r * t.ld + c;
         if (keep == 0xFFu) store16(t.o.bf16 + r * t.o.ld_bf16 + c, load16(sp));
         else if (keep) {
@@ -906,7 +985,7 @@ struct ColPlan {
     int32_t tiles_per_strip;
     int n_strips;
     int64_t cols_padded;
-    size_t off_amax, off_err, off_err5, off_zero, off_scale, off_scale5, off_amin, bytes;
+    size_t off_amax, off_err, off_err5, off_zero, off_scale, off_scale5, off_amin, off_proven, bytes;
 };
 ColPlan plan_columns(int64_t rows, int64_t cols) {
     ColPlan pl;
@@ -926,6 +1005,7 @@ ColPlan plan_columns(int64_t rows, int64_t cols) {
     pl.off_scale = off; off = align16p(off + 4 * (size_t)pl.cols_padded);
     pl.off_scale5 = off; off = align16p(off + 4 * (size_t)pl.cols_padded);
     pl.off_amin = off; off = align16p(off + 2 * (size_t)pl.cols_padded);
+    pl.off_proven = off; off = align16p(off + (size_t)pl.cols_padded);
     pl.bytes = off;
     return pl;
 }
@@ -940,8 +1020,9 @@ void fill_col_op(ColOp& t, const BatchItem& it, const uint32_t* gam) {
 template <int MODE, bool FAKE, bool EDGE>
 void launch_col_crit(const GroupCol& g, int64_t total, int crit, hipStream_t st) {
     const dim3 grid((unsigned)total), block(256);
-    if (crit == kCritEq3) k_col_group<kCritEq3, MODE, FAKE, EDGE><<<grid, block, 0, st>>>(g);
-    else k_col_group<kCritEq2, MODE, FAKE, EDGE><<<grid, block, 0, st>>>(g);
+    const int lds = MODE == kColExternal ? kResidency4 : 0;      // 0.609 ms per twelve-operand pass at 4 per unit, 0.620 uncapped
+    if (crit == kCritEq3) k_col_group<kCritEq3, MODE, FAKE, EDGE><<<grid, block, lds, st>>>(g);
+    else k_col_group<kCritEq2, MODE, FAKE, EDGE><<<grid, block, lds, st>>>(g);
 }
 template <int MODE>
 void launch_col_kind(const GroupCol& g, int64_t total, int crit, bool fake, bool edge, hipStream_t st) {
@@ -1024,9 +1105,16 @@ hipError_t launch_channel_col_items(const BatchItem* items, const int* idx, int 
             t.col_scale = reinterpret_cast<float*>(w + pl.off_scale);
             t.col_scale5 = reinterpret_cast<float*>(w + pl.off_scale5);
             t.col_amin = reinterpret_cast<uint16_t*>(w + pl.off_amin);
+            t.col_proven = reinterpret_cast<uint8_t*>(w + pl.off_proven);
+            t.prove = (crit == kCritEq2 && it.o.bf16 && !it.o.fake && !it.three && it.scope != 1 && it.th > 0.0f && it.th < 0.9f) ? 1 : 0;
+            t.flush_need = (uint32_t)(1.01 * (double)it.th * (double)it.sh.rows) + 1u;      // 1 % margin covers the binary32 sums
             total += units;
             comb += (int)((pl.cols_padded + 255) / 256);
-            copy += (int)(tiles_x * kColCopyRowGroups);
+            int64_t groups = (1024 + tiles_x - 1) / tiles_x;
+            if (groups < 2) groups = 2;
+            if (groups > kColCopyRowGroups) groups = kColCopyRowGroups;
+            t.copy_groups = (int32_t)groups;
+            copy += (int)(tiles_x * groups);
             g.unit_end[g.n] = total; g.comb_end[g.n] = comb; g.copy_end[g.n] = copy;
             if (++g.n == kMaxTeamGroup) flush();
         }
