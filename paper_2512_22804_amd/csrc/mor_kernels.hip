@@ -1360,7 +1360,7 @@ size_t scope_workspace_bytes(int64_t) { return align16(3 * sizeof(double) * kSco
 static bool is_flat(const KShape& sh, const KOut& o) {
     return sh.ld == sh.cols && o.ld_fp8 == sh.cols && (o.bf16 == nullptr || o.ld_bf16 == sh.cols);
 }
-constexpr int64_t kSubFlatMaxBlocks = 1024;   // workgroups of 4 waves; each wave strides over 8 KB units
+constexpr int64_t kSubFlatMaxBlocks = 4096;   // workgroups of 4 waves; each wave strides over 8 KB units (256 MiB operand: 77 us at 4096, 88 us at 1024)
 static int clamp_grid_y(int64_t v) { return (int)(v < 1 ? 1 : (v > 65535 ? 65535 : v)); }
 
 // The general 1 x 128 kernel: one operand per launch.
