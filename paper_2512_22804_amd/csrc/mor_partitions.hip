@@ -334,22 +334,32 @@ struct ColShared {
 };
 
 // Combines a lane's 8 per-column values with the lanes that hold the same columns in the other row groups
-// of the wave (lane ^ 16, lane ^ 32).
+// of the wave (lane ^ 16, lane ^ 32).  gfx950's v_permlane16_swap / v_permlane32_swap, given the same register
+// twice, return the values of the even and of the odd 16-lane row of each pair (of the lower and of the upper half
+// of the wave): one VALU instruction per step instead of an LDS permute, and every lane combines in the same order.
 __device__ __forceinline__ uint32_t colgroup_max2(uint32_t v) {
-    v = pk_max_u16(v, (uint32_t)__shfl_xor((int)v, 16, 64));
-    return pk_max_u16(v, (uint32_t)__shfl_xor((int)v, 32, 64));
+    const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    v = pk_max_u16(r[0], r[1]);
+    const auto q = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return pk_max_u16(q[0], q[1]);
 }
 __device__ __forceinline__ uint32_t colgroup_min2(uint32_t v) {
-    v = pk_min_u16(v, (uint32_t)__shfl_xor((int)v, 16, 64));
-    return pk_min_u16(v, (uint32_t)__shfl_xor((int)v, 32, 64));
+    const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    v = pk_min_u16(r[0], r[1]);
+    const auto q = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return pk_min_u16(q[0], q[1]);
 }
 __device__ __forceinline__ uint32_t colgroup_add2(uint32_t v) {
-    v = pk_add_u16(v, (uint32_t)__shfl_xor((int)v, 16, 64));
-    return pk_add_u16(v, (uint32_t)__shfl_xor((int)v, 32, 64));
+    const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    v = pk_add_u16(r[0], r[1]);
+    const auto q = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return pk_add_u16(q[0], q[1]);
 }
 __device__ __forceinline__ float colgroup_addf(float v) {
-    v += __shfl_xor(v, 16, 64);
-    return v + __shfl_xor(v, 32, 64);
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    const auto q = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(q[0]) + __uint_as_float(q[1]);
 }
 
 template <int CRIT, int MODE, bool FAKE, bool EDGE>
@@ -501,25 +511,24 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
                 for (int j = 0; j < 4; ++j) sh.amax[w][cg][j] = amax2[j];
             }
             __syncthreads();
+            bool slow = false;                                         // some column needs the careful element path
             if (tid < 128) {                                           // thread tid owns column tid of the tile
                 const int g16 = tid >> 3, k = tid & 7;
                 uint32_t a = 0u;
 #pragma unroll
                 for (int ww = 0; ww < 4; ++ww) a = max(a, (sh.amax[ww][g16][k >> 1] >> ((k & 1) * 16)) & 0xFFFFu);
                 sh.scale[tid] = block_scale(a, kE4M3Max, mode, mg);
-                sh.scale5[tid] = block_scale(a, kE5M2Max, mode, mg5);
+                if (CRIT == kCritEq3 || t.three) sh.scale5[tid] = block_scale(a, kE5M2Max, mode, mg5);
                 sh.abits[tid] = (uint16_t)a;
+                slow = a >= fast_amax_limit(mode);
             }
-            __syncthreads();
-            bool f = true;
+            strip_fast = __syncthreads_or(slow ? 1 : 0) == 0;         // also publishes the scales
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 s[k] = sh.scale[cg * 8 + k];
                 s5[k] = CRIT == kCritEq3 ? sh.scale5[cg * 8 + k] : 0.0f;     // Eq. 2: read again by the three-way path only
                 s_inv[k] = FAKE ? 1.0f / s[k] : 0.0f;
-                f = f && (uint32_t)sh.abits[cg * 8 + k] < fast_amax_limit(mode);
             }
-            strip_fast = __syncthreads_and(f ? 1 : 0) != 0;
         }
         // ---- quantize the tile with the per-column scales
         uint8_t* __restrict__ dst8 = FAKE ? nullptr : o.fp8 + row * o.ld_fp8 + col;
@@ -687,7 +696,7 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
                     }
                 }
             }
-            __syncthreads();
+            if (tt + 1 < t.tiles_per_strip) __syncthreads();           // the LDS arrays are written again by the next tile
             // reset the per-tile accumulators (a strip of kColLocal is a single tile anyway)
 #pragma unroll
             for (int k = 0; k < 8; ++k) { err[k] = 0.0f; err5[k] = 0.0f; }
