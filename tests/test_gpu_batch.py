@@ -244,3 +244,49 @@ def test_cfg5_full_size_batch_is_deterministic():
             for f, r in zip(fields, ref):
                 assert torch.equal(getattr(o, f), r), (run, f)
             assert torch.equal(st, ref[-1]), (run, "stats")
+
+
+def test_batch_with_more_operands_than_one_launch_group_holds():
+    """60 operands (20 per-tensor, 20 at 128 x 128, 20 at 1 x 128, two of each kind with statistics only on some):
+    more than any kernel's descriptor table holds, so every kind is split over several launches; results must equal
+    operand-by-operand calls."""
+    import parity
+    from paper_2512_22804_amd import binding as B
+    dev = torch.device("cuda:0")
+    entries, singles = [], []
+    for i in range(60):
+        gran = ("tensor", "block128", "sub1x128")[i % 3]
+        rows = 128 * (1 + i % 4)
+        cols = 128 * (2 + i % 5)
+        xb = W.gradient(rows, cols, 1000 + i, tiny_half=(i % 2 == 0)) if i % 7 else W.activation(rows, cols, 1000 + i)
+        crit = "e4m3_vs_e5m2" if i % 5 == 0 else "mean_rel_err"
+        params = B.make_params(rows, cols, gran, "partition", crit, TH)
+        x = parity.to_dev(xb)
+        want_stats = i % 4 != 1
+        ob, os_ = B.alloc_outputs(params, dev, bf16_fill=parity.FILL), B.alloc_outputs(params, dev, bf16_fill=parity.FILL)
+        sb = torch.full((B.STATS_BYTES,), 0xEE, dtype=torch.uint8, device=dev) if want_stats else None
+        ss = torch.full((B.STATS_BYTES,), 0xEE, dtype=torch.uint8, device=dev) if want_stats else None
+        entries.append((params, x, ob, sb))
+        singles.append((params, x, os_, ss))
+    items = B.make_batch(entries)
+    ws = torch.empty(max(16, B.mor_batch_workspace_bytes(items)), dtype=torch.uint8, device=dev)
+    B.mor_analyze_quantize_batch(items, 1e-2, ws)
+    for params, x, out, st in singles:
+        B.mor_analyze_quantize(params, x, out)
+        if st is not None:
+            B.mor_select_stats(params, out.err_sum, out.nnz, out.mask, 1e-2, st)
+    torch.cuda.synchronize()
+    for i, ((_, _, ob, sb), (_, _, os_, ss)) in enumerate(zip(entries, singles)):
+        for f in ("fp8", "bf16", "scale", "amax", "nnz", "mask", "err_sum", "err5_sum"):
+            a, b = getattr(ob, f), getattr(os_, f)
+            if a is not None:
+                assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), (i, f)
+        if sb is not None:
+            got, want = B.read_stats(sb), B.read_stats(ss)
+            for k in want:
+                if k == "flags":
+                    continue
+                if k in ("err_sum_total", "mean_err"):
+                    assert got[k] == pytest.approx(want[k], rel=1e-12) or (np.isinf(got[k]) and np.isinf(want[k])), (i, k)
+                else:
+                    assert got[k] == want[k], (i, k, got[k], want[k])
