@@ -1327,18 +1327,6 @@ __global__ __launch_bounds__(256) void k_gam_prepare(GroupGam g) {
 // ======================================================================================
 static inline size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
 
-// Records the caller's events around one kernel launch when profiling is requested.
-struct ProfScope {
-    KProf* prof; hipStream_t st; int slot;
-    ProfScope(KProf* p, int kernel_id, hipStream_t s) : prof(p), st(s), slot(-1) {
-        if (prof && prof->count < prof->capacity && prof->count < kProfMax) {
-            slot = prof->count++;
-            prof->kernel[slot] = kernel_id;
-            (void)hipEventRecord(prof->start[slot], st);
-        }
-    }
-    ~ProfScope() { if (slot >= 0) (void)hipEventRecord(prof->stop[slot], st); }
-};
 
 TensorPlan plan_tensor(int64_t, int64_t) {
     TensorPlan pl;

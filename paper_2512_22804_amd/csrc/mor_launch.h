@@ -81,6 +81,19 @@ enum KernelId {
     kKernTeamBlock = 14, kKernColumnTile = 15, kKernColumnCombine = 16
 };
 
+// Records the caller's events around one kernel launch when profiling is requested.
+struct ProfScope {
+    KProf* prof; hipStream_t st; int slot;
+    ProfScope(KProf* p, int kernel_id, hipStream_t s) : prof(p), st(s), slot(-1) {
+        if (prof && prof->count < prof->capacity && prof->count < kProfMax) {
+            slot = prof->count++;
+            prof->kernel[slot] = kernel_id;
+            (void)hipEventRecord(prof->start[slot], st);
+        }
+    }
+    ~ProfScope() { if (slot >= 0) (void)hipEventRecord(prof->stop[slot], st); }
+};
+
 // Residency caps: bytes of dynamic LDS a launch reserves (and never touches) so that only 3 or 5 workgroups of 256
 // lanes fit the 160 KB of a compute unit.  The streaming passes run faster with FEWER workgroups in flight than
 // their register use would allow (measured on MI355X: pass B of the per-tensor path 214 us at 3 per unit, 226 us at 4,

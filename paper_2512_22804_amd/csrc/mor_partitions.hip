@@ -899,17 +899,6 @@ __global__ __launch_bounds__(256) void k_col_fallback(GroupCol g) {
 // Launchers
 // ======================================================================================
 namespace {
-struct ProfScope2 {
-    KProf* prof; hipStream_t st; int slot;
-    ProfScope2(KProf* p, int kernel_id, hipStream_t s) : prof(p), st(s), slot(-1) {
-        if (prof && prof->count < prof->capacity && prof->count < kProfMax) {
-            slot = prof->count++;
-            prof->kernel[slot] = kernel_id;
-            (void)hipEventRecord(prof->start[slot], st);
-        }
-    }
-    ~ProfScope2() { if (slot >= 0) (void)hipEventRecord(prof->stop[slot], st); }
-};
 size_t align16p(size_t v) { return (v + 15) & ~(size_t)15; }
 
 template <int TEAM, bool FAKE, bool EDGE>
@@ -953,7 +942,7 @@ hipError_t launch_team_items(const BatchItem* items, const int* idx, int cnt, in
     int64_t total = 0;
     auto flush = [&]() {
         if (g.n == 0) return;
-        ProfScope2 ps(prof, kKernTeamBlock, st);
+        ProfScope ps(prof, kKernTeamBlock, st);
         switch (kind) {
         case kTeamWg128: launch_team_kind<kTeamWg128>(g, total, crit, fake, edge, st); break;
         case kTeamWave64: launch_team_kind<kTeamWave64>(g, total, crit, fake, edge, st); break;
@@ -1052,7 +1041,7 @@ hipError_t launch_subcol_items(const BatchItem* items, const int* idx, int cnt, 
     int64_t total = 0;
     auto flush = [&]() {
         if (g.n == 0) return;
-        ProfScope2 ps(prof, kKernColumnTile, st);
+        ProfScope ps(prof, kKernColumnTile, st);
         launch_col_kind<kColLocal>(g, total, crit, fake, edge, st);
         g.n = 0; total = 0;
     };
@@ -1083,15 +1072,15 @@ hipError_t launch_channel_col_items(const BatchItem* items, const int* idx, int 
         int comb = 0, copy = 0;
         auto flush = [&]() {
             if (g.n == 0) return;
-            { ProfScope2 ps(prof, kKernColumnTile, st); launch_col_kind<kColAmax>(g, total, kCritEq2, false, edge, st); }
-            { ProfScope2 ps(prof, kKernColumnCombine, st); k_col_scales<<<dim3((unsigned)comb), dim3(256), 0, st>>>(g); }
-            { ProfScope2 ps(prof, kKernColumnTile, st); launch_col_kind<kColExternal>(g, total, crit, fake, edge, st); }
+            { ProfScope ps(prof, kKernColumnTile, st); launch_col_kind<kColAmax>(g, total, kCritEq2, false, edge, st); }
+            { ProfScope ps(prof, kKernColumnCombine, st); k_col_scales<<<dim3((unsigned)comb), dim3(256), 0, st>>>(g); }
+            { ProfScope ps(prof, kKernColumnTile, st); launch_col_kind<kColExternal>(g, total, crit, fake, edge, st); }
             {
-                ProfScope2 ps(prof, kKernColumnCombine, st);
+                ProfScope ps(prof, kKernColumnCombine, st);
                 if (crit == kCritEq3) k_col_finish<kCritEq3><<<dim3((unsigned)comb), dim3(256), 0, st>>>(g);
                 else k_col_finish<kCritEq2><<<dim3((unsigned)comb), dim3(256), 0, st>>>(g);
             }
-            { ProfScope2 ps(prof, kKernFallbackCopy, st); k_col_fallback<<<dim3((unsigned)copy), dim3(256), 0, st>>>(g); }
+            { ProfScope ps(prof, kKernFallbackCopy, st); k_col_fallback<<<dim3((unsigned)copy), dim3(256), 0, st>>>(g); }
             g.n = 0; total = 0; comb = 0; copy = 0;
         };
         for (int k = 0; k < cnt; ++k) {
