@@ -387,3 +387,30 @@ def test_threshold_compare_is_strict(oracle):
     assert oracle.analyze_quantize(xb, "sub1x128", threshold=up).mask[0] == 0
     assert oracle.analyze_quantize(xb, "tensor", threshold=0.25).mask[0] == 1
     assert oracle.analyze_quantize(xb, "sub1x128", scope="tensor", threshold=up).mask[0] == 0
+
+
+@pytest.mark.parametrize("scaling", ["fp32_amax", "gam", "e8m0"])
+@pytest.mark.parametrize("gran", ["tensor", "sub1x128", "channel_col"])
+def test_values_below_two_to_minus_20_of_amax_flush_and_force_bf16(oracle, gran, scaling):
+    """The bound the kernels' early BF16 proof rests on: a non-zero element below 2^-20 of (any lower bound of) its
+    block's amax scales to less than half the smallest E4M3 subnormal under every scaling algorithm, so its code is
+    zero and it adds exactly 1 to Eq. 2's sum; more than th * N such elements therefore force BF16."""
+    rng = np.random.default_rng(11)
+    rows, cols = 128, 256
+    x = np.exp2(rng.uniform(-2.0, 2.0, size=(rows, cols))).astype(np.float32) * rng.choice([-1.0, 1.0], size=(rows, cols)).astype(np.float32)
+    xb = W.f32_to_bf16_bits(x)
+    tiny = rng.random((rows, cols)) < 0.06                         # 6 % > 1.01 * 4.5 %
+    mag = xb & 0x7FFF
+    # just below 2^-20 of the SMALLEST amax any block can have here (2^-2): every such element is below the bound of its block
+    below = ((mag.astype(np.int32) & 0x7F) | ((125 - 20 - 1) << 7)).astype(np.uint16)      # exponent 2^-23 .. < 2^-22
+    xb = np.where(tiny, (xb & 0x8000) | below, xb).astype(np.uint16)
+    a = oracle.analyze_quantize(xb, gran, "partition", "mean_rel_err", 0.045, scaling=scaling)
+    codes = a.fp8[tiny]
+    assert np.all((codes & 0x7F) == 0), "an element below 2^-20 of the amax did not flush"
+    # a block whose count of such elements exceeds th * (block size) is BF16 whatever its other elements are
+    counts, size = {"tensor": (np.array([tiny.sum()]), rows * cols),
+                    "sub1x128": (tiny.reshape(rows, cols // 128, 128).sum(-1).ravel(), 128),
+                    "channel_col": (tiny.sum(0), rows)}[gran]
+    assert a.err_sum.sum() >= int(tiny.sum())
+    forced = counts > 0.045 * size
+    assert forced.any() and np.all(a.mask[forced] == 1)
