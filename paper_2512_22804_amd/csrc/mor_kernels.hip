@@ -1582,7 +1582,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
             err = launch_sub1x128(it.x, it.sh, it.o, crit, it.scope == 1, it.th, (uint32_t)it.scaling, gam_of[i], (uint32_t)it.three, st, prof);
         }
         // ---- team kernels: 128x128 and 64x64 blocks, per-channel rows
-        for (int kind = 0; kind < 5 && err == hipSuccess; ++kind) {
+        for (int kind = 0; kind < kTeamKinds && err == hipSuccess; ++kind) {
             int idx[kBatchMax];
             int cnt = 0;
             for (int i = 0; i < n; ++i)

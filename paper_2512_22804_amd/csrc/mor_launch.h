@@ -98,9 +98,9 @@ struct ProfScope {
 // lanes fit the 160 KB of a compute unit.  The streaming passes run faster with FEWER workgroups in flight than
 // their register use would allow (measured on MI355X: pass B of the per-tensor path 214 us at 3 per unit, 226 us at 4,
 // 237 us at 6, 223 us at 2; pass A 79 us at 3 against 81 us uncapped; the 128x128 team kernel 114 us at 4 or 5 against
-// 116 us at 7; the 64x64 wave teams 0.405 ms per twelve-operand pass at 3 or 4 against 0.425 ms uncapped): fewer
-// concurrent streams keep the accesses of each HBM channel closer together.  Kernels that need many waves to hide
-// latency (de-quantization, 128x1 sub-columns) lose with a cap and have none.
+// 116 us at 7; the quantize pass of the per-channel columns 0.609 ms per twelve-operand pass at 4 against 0.620 ms
+// uncapped): fewer concurrent streams keep the accesses of each HBM channel closer together.  Kernels that need many
+// waves to hide latency (de-quantization, 128x1 sub-columns) lose with a cap and have none.
 constexpr int kResidency3 = 52000;
 constexpr int kResidency4 = 39000;
 constexpr int kResidency5 = 31000;
@@ -124,6 +124,7 @@ size_t batch_workspace_bytes(const BatchItem* items, int n);
 hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws, size_t ws_bytes, hipStream_t st, KProf* prof);
 
 // mor_partitions.hip: team kernels (64x64, per-channel rows, general 128x128) and column kernels
+constexpr int kTeamKinds = 5;      // team kinds are numbered 0 .. kTeamKinds - 1 (mor_partitions.hip)
 int team_kind_of(const BatchItem& it);
 hipError_t launch_team_items(const BatchItem* items, const int* idx, int cnt, int kind, int crit, const uint32_t* const* gam_of,
                              hipStream_t st, KProf* prof);

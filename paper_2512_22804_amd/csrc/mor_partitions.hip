@@ -21,11 +21,13 @@ constexpr int kChunks = 8;     // 16-byte chunks per lane
 // ======================================================================================
 enum {
     kTeamWg128 = 0,     // 128 x 128 block, one workgroup
-    kTeamWave64 = 1,    // 64 x 64 block, one wave; a workgroup takes the four blocks of a 128 x 128 tile
+    kTeamHalf64 = 1,    // 64 x 64 blocks, two side by side per wave (32 lanes each, 16 chunks per lane), so that a wave's loads
+                        // cover 256-byte row segments; a workgroup takes a tile of 128 rows x 256 columns (eight blocks)
     kTeamWaveRow = 2,   // one row of at most 4096 elements, one wave; four rows per workgroup
     kTeamWgRow = 3,     // one row of at most 16384 elements, one workgroup of 256
     kTeamBigRow = 4     // one row of at most 65536 elements, one workgroup of 1024
 };
+static_assert(kTeamBigRow + 1 == kTeamKinds, "the batch launcher walks over every team kind");
 constexpr int kMaxTeamGroup = 12;
 struct TeamOp {
     const uint16_t* x;
@@ -49,11 +51,43 @@ struct TeamShared {
 template <int TEAM> __device__ __forceinline__ constexpr bool team_is_wg() { return TEAM == kTeamWg128 || TEAM == kTeamWgRow || TEAM == kTeamBigRow; }
 template <int TEAM> __device__ __forceinline__ constexpr int team_threads() { return TEAM == kTeamBigRow ? 1024 : 256; }
 template <int TEAM> __device__ __forceinline__ constexpr int team_waves() { return team_threads<TEAM>() / 64; }
+template <int TEAM> __device__ __forceinline__ constexpr int team_chunks() { return TEAM == kTeamHalf64 ? 16 : kChunks; }
+
+// All-reduce over the 32 lanes of a half-wave team: lanes with the same bit 3 (8-lane groups of the four 16-lane rows).
+// The lanes of the other half never enter, so the two blocks of a wave may sit in different branches.
+__device__ __forceinline__ uint32_t half_allmax_u32(uint32_t v) {
+    v = max(v, dpp_u32<kDppXor1>(v));
+    v = max(v, dpp_u32<kDppXor2>(v));
+    v = max(v, dpp_u32<kDppHalfMirror>(v));
+    const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    v = max(r[0], r[1]);
+    const auto q = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return max(q[0], q[1]);
+}
+__device__ __forceinline__ uint32_t half_allsum_u32(uint32_t v) {
+    v += dpp_u32<kDppXor1>(v);
+    v += dpp_u32<kDppXor2>(v);
+    v += dpp_u32<kDppHalfMirror>(v);
+    const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    v = r[0] + r[1];
+    const auto q = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return q[0] + q[1];
+}
+__device__ __forceinline__ float half_allsum_f32(float v) {
+    v += dpp_f32<kDppXor1>(v);
+    v += dpp_f32<kDppXor2>(v);
+    v += dpp_f32<kDppHalfMirror>(v);
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    const auto q = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(q[0]) + __uint_as_float(q[1]);
+}
 
 // All-reduce over the team.  Workgroup teams combine the four wave results through LDS (every thread
 // of the workgroup must call); wave teams stay inside the wave.
 template <int TEAM>
 __device__ __forceinline__ uint32_t team_allmax(uint32_t v, TeamShared& sh) {
+    if constexpr (TEAM == kTeamHalf64) return half_allmax_u32(v);
     v = wave_allmax_u32(v);
     if constexpr (team_is_wg<TEAM>()) {
         if ((threadIdx.x & 63) == 0) sh.u[threadIdx.x >> 6] = v;
@@ -68,6 +102,12 @@ __device__ __forceinline__ uint32_t team_allmax(uint32_t v, TeamShared& sh) {
 // `b` (the E5M2 error sum) is only reduced when WITH_B; otherwise it stays as it is (zero under Eq. 2).
 template <int TEAM, bool WITH_B>
 __device__ __forceinline__ void team_allsum3(float& a, float& b, uint32_t& z, TeamShared& sh) {
+    if constexpr (TEAM == kTeamHalf64) {
+        a = half_allsum_f32(a);
+        if constexpr (WITH_B) b = half_allsum_f32(b);
+        z = half_allsum_u32(z);
+        return;
+    }
     a = wave_allsum_f32(a);
     if constexpr (WITH_B) b = wave_allsum_f32(b);
     z = wave_allsum_u32(z);
@@ -95,8 +135,10 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const KOut& o = t.o;
     // ---- geometry: block index p, origin (r0, c0), valid extent h x wd, this lane's chunk positions
+    constexpr int NCH = team_chunks<TEAM>();
     int64_t p, r0, c0;
     int h, wd, trow, tcol, rstep, cstep;
+    int bcol = 0;                                          // kTeamHalf64: this lane's column inside its block
     bool active = true, leader;
     if constexpr (TEAM == kTeamWg128) {
         const int64_t tr = unit / t.units_x, tc = unit - tr * t.units_x;
@@ -104,15 +146,21 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
         trow = tid >> 4; tcol = (tid & 15) * 8; rstep = 16; cstep = 0;
         h = (int)(t.rows - r0 < 128 ? t.rows - r0 : 128); wd = (int)(t.cols - c0 < 128 ? t.cols - c0 : 128);
         leader = tid == 0;
-    } else if constexpr (TEAM == kTeamWave64) {
+    } else if constexpr (TEAM == kTeamHalf64) {
+        // wave w: rows (w >> 1) * 64 .., columns (w & 1) * 128 .. of the workgroup's 128 x 256 tile; lanes with bit 3 set
+        // own the right one of the wave's two blocks
         const int64_t tr = unit / t.units_x, tc = unit - tr * t.units_x;
-        const int64_t gc = (t.cols + 63) / 64, gr = (t.rows + 63) / 64;
-        const int64_t br = 2 * tr + (w >> 1), bc = 2 * tc + (w & 1);
-        active = br < gr && bc < gc;
-        p = br * gc + bc; r0 = br * 64; c0 = bc * 64;
-        trow = lane >> 3; tcol = (lane & 7) * 8; rstep = 8; cstep = 0;
-        h = (int)(t.rows - r0 < 64 ? t.rows - r0 : 64); wd = (int)(t.cols - c0 < 64 ? t.cols - c0 : 64);
-        leader = lane == 0;
+        const int64_t gc = (t.cols + 63) / 64;
+        const int side = (lane >> 3) & 1;
+        r0 = tr * 128 + (w >> 1) * 64; c0 = tc * 256 + (w & 1) * 128;
+        if (r0 >= t.rows || c0 >= t.cols) return;          // the whole wave is outside: uniform, and no barrier follows
+        p = (r0 >> 6) * gc + (c0 >> 6) + side;
+        trow = lane >> 4; tcol = (lane & 15) * 8; rstep = 4; cstep = 0;
+        bcol = tcol & 63;
+        h = (int)(t.rows - r0 < 64 ? t.rows - r0 : 64);
+        const int64_t left = t.cols - (c0 + side * 64);
+        wd = (int)(left < 0 ? 0 : (left < 64 ? left : 64));   // 0: this lane's block lies outside the tensor
+        leader = (lane & 0x37) == 0 && wd > 0;
     } else if constexpr (TEAM == kTeamWaveRow) {
         p = unit * 4 + w; r0 = p; c0 = 0;
         active = p < t.rows;
@@ -131,22 +179,26 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
     // Whole-block operands of the block teams use plain pointers; everything else (ragged edges, rows) goes through
     // bounds-checked buffer accesses relative to the block origin, where a lane outside the block costs no branch.
     constexpr bool BUF = EDGE || TEAM == kTeamWaveRow || TEAM == kTeamWgRow || TEAM == kTeamBigRow;
+    auto in_block = [&](int i) -> bool {
+        if constexpr (TEAM == kTeamHalf64) return (trow + i * rstep < h) && (bcol < wd);
+        else return (trow + i * rstep < h) && (tcol + i * cstep < wd);
+    };
     auto is_valid = [&](int i) -> bool {
-        if constexpr (BUF) return (trow + i * rstep < h) && (tcol + i * cstep < wd);
+        if constexpr (BUF) return in_block(i);
         else return true;
     };
     const BufRsrc rx = make_buf(t.x + r0 * t.ld + c0);
     const uint32_t xoff = (uint32_t)((trow * t.ld + tcol) * 2), xstep = (uint32_t)(src_step * 2);
-    u32x4 raw[kChunks];
+    u32x4 raw[NCH];
 #pragma unroll
-    for (int i = 0; i < kChunks; ++i) {
+    for (int i = 0; i < NCH; ++i) {
         if constexpr (BUF) raw[i] = buf_load16(rx, is_valid(i) ? xoff : kBufOutside, i * xstep);
         else raw[i] = load16(src + i * src_step);
     }
     // ---- amax and zero count (chunks outside the tensor count as zeros and change nothing)
     Scan8 sc{0u, 0u};
 #pragma unroll
-    for (int i = 0; i < kChunks; ++i) scan8(raw[i], sc);
+    for (int i = 0; i < NCH; ++i) scan8(raw[i], sc);
     // pin both results here: otherwise the compiler sinks the zero count below the quantization sweep and keeps the
     // 32 masked words of the block alive across it
     asm volatile("" : "+v"(sc.amax2), "+v"(sc.zero2));
@@ -174,7 +226,7 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
         float e0 = 0.0f, e1 = 0.0f;
         if (fast) {
 #pragma unroll
-            for (int i = 0; i < kChunks; ++i) {
+            for (int i = 0; i < NCH; ++i) {
                 u32x4 deq;
                 const u32x2 codes = quant8_fast_deq<E5, FAKE>(raw[i], sc_, s_inv, e0, e1, deq);
                 if constexpr (BUF) {
@@ -189,8 +241,8 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
             }
         } else {
 #pragma clang loop unroll(disable)
-            for (int i = 0; i < kChunks; ++i)
-                if ((trow + i * rstep < h) && (tcol + i * cstep < wd))
+            for (int i = 0; i < NCH; ++i)
+                if (in_block(i))
                     e0 += quant8_careful_mem<E5>(src + i * src_step, sc_, emit && !FAKE ? dst8 + i * dst8_step : nullptr,
                                                  emit && FAKE ? dstf + i * dstf_step : nullptr, s_inv);
         }
@@ -202,7 +254,7 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
         const float s_inv = FAKE ? 1.0f / s : 0.0f;
         float e0 = 0.0f, e1 = 0.0f, f0 = 0.0f, f1 = 0.0f;
 #pragma unroll
-        for (int i = 0; i < kChunks; ++i) {
+        for (int i = 0; i < NCH; ++i) {
             u32x4 deq;
             const u32x2 codes = quant8_dual<FAKE>(raw[i], s, s_inv, e0, e1, f0, f1, deq);
             if constexpr (BUF) {
@@ -222,7 +274,7 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
     }
     uint32_t zeros = fold_add16(sc.zero2);
     team_allsum3<TEAM, CRIT == kCritEq3>(err, err5, zeros, sh);
-    constexpr uint32_t kTeamElems = (team_is_wg<TEAM>() ? (uint32_t)team_threads<TEAM>() : 64u) * kChunks * 8u;
+    constexpr uint32_t kTeamElems = (team_is_wg<TEAM>() ? (uint32_t)team_threads<TEAM>() : (TEAM == kTeamHalf64 ? 32u : 64u)) * NCH * 8u;
     const uint32_t nnz = kTeamElems - zeros;
     if (abits >= kInfBits) { err = __builtin_inff(); err5 = __builtin_inff(); }
     const bool defer = t.defer != 0;
@@ -232,7 +284,7 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
     if (t.three && mask == 1u) {                           // uniform over the team
         uint32_t mn2 = 0xFFFFFFFFu;
 #pragma unroll
-        for (int i = 0; i < kChunks; ++i) {
+        for (int i = 0; i < NCH; ++i) {
             u32x4 w = raw[i];
             asm volatile("" : "+v"(w.x), "+v"(w.y), "+v"(w.z), "+v"(w.w));      // no reuse of the masked words of the amax sweep
             mn2 = min_nonzero_m1(w, mn2);
@@ -261,7 +313,7 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
         const BufRsrc rb = make_buf(o.bf16 + r0 * o.ld_bf16 + c0);
         const uint32_t offb = (uint32_t)((trow * o.ld_bf16 + tcol) * 2), stepb = (uint32_t)(dbf_step * 2);
 #pragma unroll
-        for (int i = 0; i < kChunks; ++i) {
+        for (int i = 0; i < NCH; ++i) {
             if constexpr (BUF) buf_store16(rb, is_valid(i) ? offb + i * stepb : kBufOutside, raw[i]);
             else store16(dbf + i * dbf_step, raw[i]);
         }
@@ -904,7 +956,7 @@ size_t align16p(size_t v) { return (v + 15) & ~(size_t)15; }
 template <int TEAM, bool FAKE, bool EDGE>
 void launch_team_crit(const GroupTeam& g, int64_t total, int crit, hipStream_t st) {
     const dim3 grid((unsigned)total), block(TEAM == kTeamBigRow ? 1024 : 256);
-    const int lds = TEAM == kTeamWg128 ? kResidency5 : (TEAM == kTeamWave64 ? kResidency4 : 0);
+    const int lds = TEAM == kTeamWg128 ? kResidency5 : 0;      // the other kinds show no gain from a cap
     if (crit == kCritEq3) k_team_group<TEAM, kCritEq3, FAKE, EDGE><<<grid, block, lds, st>>>(g);
     else k_team_group<TEAM, kCritEq2, FAKE, EDGE><<<grid, block, lds, st>>>(g);
 }
@@ -917,7 +969,7 @@ void launch_team_kind(const GroupTeam& g, int64_t total, int crit, bool fake, bo
 bool team_needs_edge(const BatchItem& it, int kind) {
     switch (kind) {
     case kTeamWg128: return it.sh.rows % 128 != 0 || it.sh.cols % 128 != 0;
-    case kTeamWave64: return it.sh.rows % 64 != 0 || it.sh.cols % 64 != 0;
+    case kTeamHalf64: return it.sh.rows % 64 != 0 || it.sh.cols % 128 != 0;      // a wave spans 128 columns
     default: return false;      // row teams always use the bounds-checked accesses
     }
 }
@@ -926,7 +978,7 @@ bool team_needs_edge(const BatchItem& it, int kind) {
 int team_kind_of(const BatchItem& it) {
     switch (it.gran) {
     case kGranBlock: return kTeamWg128;
-    case kGranBlock64: return kTeamWave64;
+    case kGranBlock64: return kTeamHalf64;
     case kGranRow: return it.sh.cols <= 4096 ? kTeamWaveRow : (it.sh.cols <= 16384 ? kTeamWgRow : kTeamBigRow);
     default: return -1;
     }
@@ -945,7 +997,7 @@ hipError_t launch_team_items(const BatchItem* items, const int* idx, int cnt, in
         ProfScope ps(prof, kKernTeamBlock, st);
         switch (kind) {
         case kTeamWg128: launch_team_kind<kTeamWg128>(g, total, crit, fake, edge, st); break;
-        case kTeamWave64: launch_team_kind<kTeamWave64>(g, total, crit, fake, edge, st); break;
+        case kTeamHalf64: launch_team_kind<kTeamHalf64>(g, total, crit, fake, edge, st); break;
         case kTeamWaveRow: launch_team_kind<kTeamWaveRow>(g, total, crit, fake, edge, st); break;
         case kTeamWgRow: launch_team_kind<kTeamWgRow>(g, total, crit, fake, edge, st); break;
         default: launch_team_kind<kTeamBigRow>(g, total, crit, fake, edge, st); break;
@@ -957,15 +1009,15 @@ hipError_t launch_team_items(const BatchItem* items, const int* idx, int cnt, in
         if ((it.o.fake != nullptr) != fake || team_needs_edge(it, kind) != edge) continue;
         int64_t units;
         TeamOp& t = g.op[g.n];
-        t.units_x = (it.sh.cols + 127) / 128;
-        if (kind == kTeamWg128 || kind == kTeamWave64) units = ((it.sh.rows + 127) / 128) * t.units_x;
+        t.units_x = kind == kTeamHalf64 ? (it.sh.cols + 255) / 256 : (it.sh.cols + 127) / 128;
+        if (kind == kTeamWg128 || kind == kTeamHalf64) units = ((it.sh.rows + 127) / 128) * t.units_x;
         else if (kind == kTeamWaveRow) units = (it.sh.rows + 3) / 4;
         else units = it.sh.rows;
         if (units > 0x7FFFFFFF) return hipErrorInvalidValue;
         if (total + units > 0x7FFFFFFF) { flush(); }
         TeamOp& u = g.op[g.n];
         u.x = it.x; u.o = it.o; u.ld = it.sh.ld; u.rows = it.sh.rows; u.cols = it.sh.cols;
-        u.units_x = (it.sh.cols + 127) / 128;
+        u.units_x = kind == kTeamHalf64 ? (it.sh.cols + 255) / 256 : (it.sh.cols + 127) / 128;
         u.th = it.th; u.defer = it.scope == 1; u.mode = (uint8_t)it.scaling; u.three = (uint8_t)it.three; u.pad = 0;
         u.gam = gam_of[idx[k]];
         total += units;
