@@ -112,14 +112,14 @@ __device__ __forceinline__ void rows_allsum(float (&v)[N]) {
 // Rarely taken: some block of this unit has amax >= 2^25 or is non-finite.  Rolled loop, data re-read
 // from memory, every block of the unit goes through the careful element path (valid for any input).
 template <int CRIT>
-__device__ __forceinline__ void sub_unit_careful(const uint16_t* __restrict__ xl, uint8_t* __restrict__ fl, int lane, float my_s,
-                                                 float my_s5, float& my_err, float& my_err5) {
+__device__ __forceinline__ void sub_unit_careful(const uint16_t* __restrict__ xl, uint8_t* __restrict__ fl, uint16_t* __restrict__ ff,
+                                                 int lane, float my_s, float my_s5, float& my_err, float& my_err5) {
     const int l = lane & 15;
 #pragma clang loop unroll(disable)
     for (int k = 0; k < 8; ++k) {
         const int src_lane = (lane & 48) + k;
         const float s_k = __shfl(my_s, src_lane, 64);
-        float e = quant8_careful_mem<false>(xl + k * 128, s_k, fl + k * 128);
+        float e = quant8_careful_mem<false>(xl + k * 128, s_k, ff ? nullptr : fl + k * 128, ff ? ff + k * 128 : nullptr, 1.0f / s_k);
         e = row_allsum_f32(e);
         if ((l & 7) == k) my_err = e;
         if constexpr (CRIT == kCritEq3) {
@@ -134,13 +134,14 @@ __device__ __forceinline__ void sub_unit_careful(const uint16_t* __restrict__ xl
 // One unit = 32 consecutive blocks: DPP row g (16 lanes x 8 elements) owns blocks g*8 .. g*8+7 of the
 // unit, all eight already loaded into raw[].  Lane j (and its mirror j+8) of the row keeps the scalars of
 // block g*8+j, so the per-block work (division, decision, metadata) runs once per 8 blocks.
-template <int CRIT>
+template <int CRIT, bool FAKE>
 __device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const uint16_t* __restrict__ x, const KOut& o, int64_t unit,
                                                  int lane, float th, bool defer, uint32_t mode, uint32_t mg, uint32_t mg5) {
     const int g = lane >> 4, l = lane & 15, own = l & 7;
     const int64_t prow = unit * 32 + g * 8;
     const int64_t off = prow * 128 + l * 8;
-    uint8_t* __restrict__ fl = o.fp8 + off;
+    uint8_t* __restrict__ fl = FAKE ? nullptr : o.fp8 + off;
+    uint16_t* __restrict__ ff = FAKE ? o.fake + off : nullptr;       // fake quantization: the de-quantized values go here
     // phase 1: per-block amax (to the owner lane) and zero counts (packed 4 blocks per dword)
     uint32_t ab[8];
     uint32_t zp0 = 0u, zp1 = 0u;
@@ -168,27 +169,33 @@ __device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const ui
     // phase 2: quantize with the owner's scale, reduce the error terms to the owner
     float my_err = 0.0f, my_err5 = 0.0f;
     if (__any(amax_unit >= fast_amax_limit(mode))) {
-        sub_unit_careful<CRIT>(x + off, fl, lane, my_s, my_s5, my_err, my_err5);
+        sub_unit_careful<CRIT>(x + off, fl, ff, lane, my_s, my_s5, my_err, my_err5);
     } else {
         float e[8], e5[8];
         // Eq. 3: when every E5M2 scale of the wave is 128 times the E4M3 one, both formats share a reciprocal (quant8_dual)
         const bool dual = CRIT == kCritEq3 && __all(my_s5 == 128.0f * my_s);
+        const float my_sinv = FAKE ? 1.0f / my_s : 0.0f;
 #define MOR_SUB_ONE(K)                                                                     \
         {                                                                                  \
             float e0 = 0.0f, e1 = 0.0f;                                                    \
+            const float s_K = row_bcast_f32<K>(my_s);                                      \
+            const float sinv_K = FAKE ? row_bcast_f32<K>(my_sinv) : 0.0f;                  \
+            u32x4 deq;                                                                     \
+            u32x2 codes;                                                                   \
             if (CRIT == kCritEq3 && dual) {                                                \
                 float f0 = 0.0f, f1 = 0.0f;                                                \
-                u32x4 deq;                                                                 \
-                store8(fl + K * 128, quant8_dual<false>(raw[K], row_bcast_f32<K>(my_s), 0.0f, e0, e1, f0, f1, deq)); \
+                codes = quant8_dual<FAKE>(raw[K], s_K, sinv_K, e0, e1, f0, f1, deq);       \
                 e5[K] = f0 + f1;                                                           \
             } else {                                                                       \
-                store8(fl + K * 128, quant8_fast<false>(raw[K], row_bcast_f32<K>(my_s), e0, e1)); \
+                codes = quant8_fast_deq<false, FAKE>(raw[K], s_K, sinv_K, e0, e1, deq);    \
                 if constexpr (CRIT == kCritEq3) {                                          \
                     float f0 = 0.0f, f1 = 0.0f;                                            \
                     (void)quant8_fast<true>(raw[K], row_bcast_f32<K>(my_s5), f0, f1);      \
                     e5[K] = f0 + f1;                                                       \
                 }                                                                          \
             }                                                                              \
+            if constexpr (FAKE) store16(ff + K * 128, deq);                                \
+            else store8(fl + K * 128, codes);                                              \
             e[K] = e0 + e1;                                                                \
             __builtin_amdgcn_sched_barrier(0);                                             \
         }
@@ -904,7 +911,7 @@ struct GroupSub {
     uint8_t mode[kMaxGroupSub];           // scaling algorithm
     const uint32_t* gam[kMaxGroupSub];    // mode != 0: {mantissa for E4M3, mantissa for E5M2} of the operand's group
 };
-template <int CRIT>
+template <int CRIT, bool FAKE>
 __global__ __launch_bounds__(256) void k_sub1x128_group(GroupSub g) {
     const int lane = threadIdx.x & 63, row = lane >> 4, l = lane & 15;
     const int64_t W = (int64_t)gridDim.x * 4, total = g.unit_end[g.n - 1];
@@ -923,7 +930,7 @@ __global__ __launch_bounds__(256) void k_sub1x128_group(GroupSub g) {
         const uint32_t mode = g.mode[op];
         uint32_t mg = 0u, mg5 = 0u;
         if (mode) { mg = g.gam[op][0]; if constexpr (CRIT == kCritEq3) mg5 = g.gam[op][1]; }
-        sub_unit_process<CRIT>(raw, g.x[op], g.o[op], local, lane, g.th[op], g.defer[op] != 0, mode, mg, mg5);
+        sub_unit_process<CRIT, FAKE>(raw, g.x[op], g.o[op], local, lane, g.th[op], g.defer[op] != 0, mode, mg, mg5);
     };
     int opA;
     int64_t locA;
@@ -1346,7 +1353,8 @@ TensorPlan plan_tensor(int64_t, int64_t) {
 size_t scope_workspace_bytes(int64_t) { return align16(3 * sizeof(double) * kScopeBlocks + 16); }
 
 static bool is_flat(const KShape& sh, const KOut& o) {
-    return sh.ld == sh.cols && o.ld_fp8 == sh.cols && (o.bf16 == nullptr || o.ld_bf16 == sh.cols);
+    return sh.ld == sh.cols && o.ld_fp8 == sh.cols && (o.bf16 == nullptr || o.ld_bf16 == sh.cols) &&
+           (o.fake == nullptr || o.ld_fake == sh.cols);
 }
 constexpr int64_t kSubFlatMaxBlocks = 4096;   // workgroups of 4 waves; each wave strides over 8 KB units (256 MiB operand: 77 us at 4096, 88 us at 1024)
 static int clamp_grid_y(int64_t v) { return (int)(v < 1 ? 1 : (v > 65535 ? 65535 : v)); }
@@ -1426,7 +1434,7 @@ enum Route {
 };
 bool item_is_flat(const BatchItem& it) { return is_flat(it.sh, it.o); }
 Route route_of(const BatchItem& it) {
-    const bool plain = !it.three && it.o.fake == nullptr;
+    const bool plain = !it.three;
     switch (it.gran) {
     case kGranTensor: return item_is_flat(it) ? kRouteTensorGroup : kRouteTensorStrided;
     case kGranSub: return (plain && item_is_flat(it) && it.sh.cols % 128 == 0) ? kRouteSubFlat : kRouteSubGeneral;
@@ -1538,8 +1546,8 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
     }
 
     for (int crit = 0; crit < 2 && err == hipSuccess; ++crit) {
-        // ---- 1x128 sub-channel operands, persistent grouped kernel
-        {
+        // ---- 1x128 sub-channel operands, persistent grouped kernel (FP8 payload, then fake quantization)
+        for (int fake = 0; fake < 2 && err == hipSuccess; ++fake) {
             GroupSub g; g.n = 0;
             int64_t total = 0;
             auto flush = [&]() {
@@ -1547,13 +1555,18 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 int64_t blocks = (total + 3) / 4;
                 if (blocks > kSubFlatMaxBlocks) blocks = kSubFlatMaxBlocks;
                 ProfScope ps(prof, kKernSub1x128, st);
-                if (crit == kCritEq3) k_sub1x128_group<kCritEq3><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(g);
-                else k_sub1x128_group<kCritEq2><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(g);
+                if (fake) {
+                    if (crit == kCritEq3) k_sub1x128_group<kCritEq3, true><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(g);
+                    else k_sub1x128_group<kCritEq2, true><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(g);
+                } else {
+                    if (crit == kCritEq3) k_sub1x128_group<kCritEq3, false><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(g);
+                    else k_sub1x128_group<kCritEq2, false><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(g);
+                }
                 g.n = 0; total = 0;
             };
             for (int i = 0; i < n; ++i) {
                 const BatchItem& it = items[i];
-                if (route[i] != kRouteSubFlat || it.crit != crit) continue;
+                if (route[i] != kRouteSubFlat || it.crit != crit || (it.o.fake != nullptr) != (fake != 0)) continue;
                 const int64_t n_part = item_parts(it), n_units = n_part / 32, n_full = n_units * 32, n_tail = n_part - n_full;
                 if (n_units > 0) {
                     total += n_units;
@@ -1564,7 +1577,9 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 if (n_tail > 0) {     // fewer than 32 blocks left: the general kernel takes them
                     KShape ts{n_tail, 128, 128};
                     KOut to = it.o;
-                    to.fp8 += n_full * 128; to.ld_fp8 = 128;
+                    if (to.fp8) to.fp8 += n_full * 128;
+                    to.ld_fp8 = 128;
+                    if (to.fake) { to.fake += n_full * 128; to.ld_fake = 128; }
                     if (to.bf16) to.bf16 += n_full * 128;
                     to.ld_bf16 = 128;
                     to.scale += n_full; to.amax += n_full; to.err_sum += n_full; to.nnz += n_full; to.mask += n_full;
