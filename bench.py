@@ -283,6 +283,10 @@ def main() -> int:
         step(profiles)
         torch.cuda.synchronize()
         for o, pr in zip(ops, profiles):
+            # a small 1x128 operand rides in extra workgroups of the 128x128 team launch (no launch of its own): its bytes
+            # then belong to that launch
+            seen = {B.KERNEL_NAMES[pr.kernel[k]] for k in range(pr.count)}
+            sub_rides = not args.per_operand and "sub1x128" not in seen and "team_block" in seen
             for k in range(pr.count):
                 kname = B.KERNEL_NAMES[pr.kernel[k]]
                 ms = ev.elapsed_ms(pr.start[k], pr.stop[k])
@@ -295,7 +299,7 @@ def main() -> int:
                     for q in ops:
                         if kname.startswith("stats"):
                             rec["bytes"] += algorithmic_bytes(kname, q["n"], q["P"], 0.0) if q["gran"] != "tensor" else 0.0
-                        elif KERNEL_GRAN.get(kname) == q["gran"]:
+                        elif KERNEL_GRAN.get(kname) == q["gran"] or (sub_rides and kname == "team_block" and q["gran"] == "sub1x128"):
                             rec["bytes"] += algorithmic_bytes(kname, q["n"], q["P"], q["fallback_frac"], q["fused_fallback"])
             if not args.per_operand:
                 break

@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmor.so")
 SOURCES = ["mor_kernels.hip", "mor_partitions.hip", "mor_api.hip"]
-HEADERS = ["mor_device.h", "mor_launch.h", os.path.join("..", "..", "include", "mor.h")]
+HEADERS = ["mor_device.h", "mor_launch.h", "mor_sub1x128.h", os.path.join("..", "..", "include", "mor.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fno-fast-math",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
 

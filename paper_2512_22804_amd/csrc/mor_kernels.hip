@@ -9,10 +9,10 @@
 
 #include "mor_device.h"
 #include "mor_launch.h"
+#include "mor_sub1x128.h"
 
 namespace mor {
 
-enum { kCritEq2 = 0, kCritEq3 = 1 };
 
 // ======================================================================================
 // 1 x 128 sub-channel blocks (Section 3: sub-channel partition; DeepSeek-style activations)
@@ -80,160 +80,6 @@ __device__ __forceinline__ void sub_block_body(const u32x4& raw, const uint16_t*
     }
     if constexpr (!DEFER) {
         if (mask == 1u && dst_bf16 && valid) store16(dst_bf16, raw);
-    }
-}
-
-// Dense operands (every leading dimension == cols): blocks are consecutive 256-byte runs.
-// A wave owns 64 consecutive blocks.  DPP row g (16 lanes x 8 elements) works through blocks
-// g*16 .. g*16+15, eight at a time with all eight loads in flight; lane j of the row keeps the
-// scalars of block g*16+j, so the per-block work (division, decision, metadata) is done once per
-// 16 blocks by 64 lanes in parallel and the metadata stores are contiguous 256-byte runs.
-// Batched 16-lane butterflies over N independent values: the N chains interleave, which hides the
-// DPP read-after-write wait states.
-template <int CTRL, int N>
-__device__ __forceinline__ void rows_max_step(uint32_t (&v)[N]) {
-#pragma unroll
-    for (int i = 0; i < N; ++i) v[i] = max(v[i], dpp_u32<CTRL>(v[i]));
-}
-template <int CTRL, int N>
-__device__ __forceinline__ void rows_add_step(float (&v)[N]) {
-#pragma unroll
-    for (int i = 0; i < N; ++i) v[i] += dpp_f32<CTRL>(v[i]);
-}
-template <int N>
-__device__ __forceinline__ void rows_allmax(uint32_t (&v)[N]) {
-    rows_max_step<kDppXor1, N>(v); rows_max_step<kDppXor2, N>(v); rows_max_step<kDppHalfMirror, N>(v); rows_max_step<kDppMirror, N>(v);
-}
-template <int N>
-__device__ __forceinline__ void rows_allsum(float (&v)[N]) {
-    rows_add_step<kDppXor1, N>(v); rows_add_step<kDppXor2, N>(v); rows_add_step<kDppHalfMirror, N>(v); rows_add_step<kDppMirror, N>(v);
-}
-
-// Rarely taken: some block of this unit has amax >= 2^25 or is non-finite.  Rolled loop, data re-read
-// from memory, every block of the unit goes through the careful element path (valid for any input).
-template <int CRIT>
-__device__ __forceinline__ void sub_unit_careful(const uint16_t* __restrict__ xl, uint8_t* __restrict__ fl, uint16_t* __restrict__ ff,
-                                                 int lane, float my_s, float my_s5, float& my_err, float& my_err5) {
-    const int l = lane & 15;
-#pragma clang loop unroll(disable)
-    for (int k = 0; k < 8; ++k) {
-        const int src_lane = (lane & 48) + k;
-        const float s_k = __shfl(my_s, src_lane, 64);
-        float e = quant8_careful_mem<false>(xl + k * 128, s_k, ff ? nullptr : fl + k * 128, ff ? ff + k * 128 : nullptr, 1.0f / s_k);
-        e = row_allsum_f32(e);
-        if ((l & 7) == k) my_err = e;
-        if constexpr (CRIT == kCritEq3) {
-            const float s5_k = __shfl(my_s5, src_lane, 64);
-            float e5 = quant8_careful_mem<true>(xl + k * 128, s5_k, nullptr);
-            e5 = row_allsum_f32(e5);
-            if ((l & 7) == k) my_err5 = e5;
-        }
-    }
-}
-
-// One unit = 32 consecutive blocks: DPP row g (16 lanes x 8 elements) owns blocks g*8 .. g*8+7 of the
-// unit, all eight already loaded into raw[].  Lane j (and its mirror j+8) of the row keeps the scalars of
-// block g*8+j, so the per-block work (division, decision, metadata) runs once per 8 blocks.
-template <int CRIT, bool FAKE>
-__device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const uint16_t* __restrict__ x, const KOut& o, int64_t unit,
-                                                 int lane, float th, bool defer, uint32_t mode, uint32_t mg, uint32_t mg5) {
-    const int g = lane >> 4, l = lane & 15, own = l & 7;
-    const int64_t prow = unit * 32 + g * 8;
-    const int64_t off = prow * 128 + l * 8;
-    uint8_t* __restrict__ fl = FAKE ? nullptr : o.fp8 + off;
-    uint16_t* __restrict__ ff = FAKE ? o.fake + off : nullptr;       // fake quantization: the de-quantized values go here
-    // phase 1: per-block amax (to the owner lane) and zero counts (packed 4 blocks per dword)
-    uint32_t ab[8];
-    uint32_t zp0 = 0u, zp1 = 0u;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        Scan8 sc{0u, 0u};
-        scan8(raw[k], sc);
-        ab[k] = fold_max16(sc.amax2);
-        const uint32_t zc = __builtin_amdgcn_sad_u16(sc.zero2, 0u, 0u);       // low + high half-word counts (<= 8)
-        if (k < 4) zp0 |= zc << (8 * k); else zp1 |= zc << (8 * (k - 4));
-    }
-    rows_allmax<8>(ab);
-    uint32_t amax_unit = 0u, my_abits = 0u;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        amax_unit = max(amax_unit, ab[k]);
-        if (own == k) my_abits = ab[k];
-    }
-    zp0 = row_allsum_u32(zp0);        // byte sums <= 128: no carry between bytes
-    zp1 = row_allsum_u32(zp1);
-    const uint32_t my_zero = (((own & 4) ? zp1 : zp0) >> (8 * (own & 3))) & 0xFFu;
-    const float my_s = block_scale(my_abits, kE4M3Max, mode, mg);
-    float my_s5 = 0.0f;
-    if constexpr (CRIT == kCritEq3) my_s5 = block_scale(my_abits, kE5M2Max, mode, mg5);
-    // phase 2: quantize with the owner's scale, reduce the error terms to the owner
-    float my_err = 0.0f, my_err5 = 0.0f;
-    if (__any(amax_unit >= fast_amax_limit(mode))) {
-        sub_unit_careful<CRIT>(x + off, fl, ff, lane, my_s, my_s5, my_err, my_err5);
-    } else {
-        float e[8], e5[8];
-        // Eq. 3: when every E5M2 scale of the wave is 128 times the E4M3 one, both formats share a reciprocal (quant8_dual)
-        const bool dual = CRIT == kCritEq3 && __all(my_s5 == 128.0f * my_s);
-        const float my_sinv = FAKE ? 1.0f / my_s : 0.0f;
-#define MOR_SUB_ONE(K)                                                                     \
-        {                                                                                  \
-            float e0 = 0.0f, e1 = 0.0f;                                                    \
-            const float s_K = row_bcast_f32<K>(my_s);                                      \
-            const float sinv_K = FAKE ? row_bcast_f32<K>(my_sinv) : 0.0f;                  \
-            u32x4 deq;                                                                     \
-            u32x2 codes;                                                                   \
-            if (CRIT == kCritEq3 && dual) {                                                \
-                float f0 = 0.0f, f1 = 0.0f;                                                \
-                codes = quant8_dual<FAKE>(raw[K], s_K, sinv_K, e0, e1, f0, f1, deq);       \
-                e5[K] = f0 + f1;                                                           \
-            } else {                                                                       \
-                codes = quant8_fast_deq<false, FAKE>(raw[K], s_K, sinv_K, e0, e1, deq);    \
-                if constexpr (CRIT == kCritEq3) {                                          \
-                    float f0 = 0.0f, f1 = 0.0f;                                            \
-                    (void)quant8_fast<true>(raw[K], row_bcast_f32<K>(my_s5), f0, f1);      \
-                    e5[K] = f0 + f1;                                                       \
-                }                                                                          \
-            }                                                                              \
-            if constexpr (FAKE) store16(ff + K * 128, deq);                                \
-            else store8(fl + K * 128, codes);                                              \
-            e[K] = e0 + e1;                                                                \
-            __builtin_amdgcn_sched_barrier(0);                                             \
-        }
-        MOR_SUB_ONE(0) MOR_SUB_ONE(1) MOR_SUB_ONE(2) MOR_SUB_ONE(3) MOR_SUB_ONE(4) MOR_SUB_ONE(5) MOR_SUB_ONE(6) MOR_SUB_ONE(7)
-#undef MOR_SUB_ONE
-        rows_allsum<8>(e);
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-            if (own == k) my_err = e[k];
-        if constexpr (CRIT == kCritEq3) {
-            rows_allsum<8>(e5);
-#pragma unroll
-            for (int k = 0; k < 8; ++k)
-                if (own == k) my_err5 = e5[k];
-        }
-    }
-    if (my_abits >= kInfBits) { my_err = __builtin_inff(); my_err5 = my_err; }
-    uint32_t my_mask = 0u;
-    if (!defer) my_mask = (CRIT == kCritEq3) ? decide_eq3(my_err, my_err5) : decide_eq2(my_err, 128u - my_zero, th);
-    if (l < 8) {
-        const int64_t p = prow + l;
-        o.scale[p] = my_s;
-        o.amax[p] = __uint_as_float(my_abits << 16);
-        o.err_sum[p] = my_err;
-        o.nnz[p] = 128u - my_zero;
-        if constexpr (CRIT == kCritEq3) o.err5_sum[p] = my_err5;
-        if (!defer) o.mask[p] = (uint8_t)my_mask;
-        if (mode != kScaleFp32 && o.e8m0) o.e8m0[p] = (uint8_t)(__float_as_uint(my_s) >> 23);
-    }
-    if (!defer && o.bf16) {
-        const unsigned long long want = __ballot(l < 8 && my_mask != 0u);
-        if (want) {
-            const uint32_t bits = (uint32_t)(want >> (lane & 48)) & 0xFFu;   // my row's eight blocks
-            uint16_t* __restrict__ bl = o.bf16 + off;
-#pragma unroll
-            for (int k = 0; k < 8; ++k)
-                if ((bits >> k) & 1u) store16(bl + k * 128, raw[k]);
-        }
     }
 }
 
@@ -899,48 +745,10 @@ __global__ void k_histogram_update(uint32_t* __restrict__ hist, const StatsDev* 
 // ======================================================================================
 constexpr int kMaxGroup = 8;           // per-tensor operands / GAM pre-pass per launch (their table shares the 4 KB
                                        // kernel-argument segment with the statistics riders)
-constexpr int kMaxGroupSub = 16;       // 1x128 and 128x128 operands per launch
 
-struct GroupSub {
-    int n;
-    int64_t unit_end[kMaxGroupSub];       // running total of 32-block units
-    const uint16_t* x[kMaxGroupSub];
-    KOut o[kMaxGroupSub];
-    float th[kMaxGroupSub];
-    uint8_t defer[kMaxGroupSub];          // 1: tensor-level decision follows, write no mask / fallback here
-    uint8_t mode[kMaxGroupSub];           // scaling algorithm
-    const uint32_t* gam[kMaxGroupSub];    // mode != 0: {mantissa for E4M3, mantissa for E5M2} of the operand's group
-};
 template <int CRIT, bool FAKE>
 __global__ __launch_bounds__(256) void k_sub1x128_group(GroupSub g) {
-    const int lane = threadIdx.x & 63, row = lane >> 4, l = lane & 15;
-    const int64_t W = (int64_t)gridDim.x * 4, total = g.unit_end[g.n - 1];
-    int64_t u = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (u >= total) return;
-    const int lane_off = (row * 8) * 128 + l * 8;
-    u32x4 bufA[8];
-    auto load_unit = [&](u32x4 (&raw)[8], int64_t unit, int& op, int64_t& local) {
-        op = group_find(g.unit_end, g.n, unit);
-        local = unit - (op ? g.unit_end[op - 1] : 0);
-        const uint16_t* __restrict__ src = g.x[op] + local * (32 * 128) + lane_off;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) raw[k] = load16(src + k * 128);
-    };
-    auto process = [&](const u32x4 (&raw)[8], int op, int64_t local) {
-        const uint32_t mode = g.mode[op];
-        uint32_t mg = 0u, mg5 = 0u;
-        if (mode) { mg = g.gam[op][0]; if constexpr (CRIT == kCritEq3) mg5 = g.gam[op][1]; }
-        sub_unit_process<CRIT, FAKE>(raw, g.x[op], g.o[op], local, lane, g.th[op], g.defer[op] != 0, mode, mg, mg5);
-    };
-    int opA;
-    int64_t locA;
-    load_unit(bufA, u, opA, locA);
-    for (;;) {
-        process(bufA, opA, locA);
-        u += W;
-        if (u >= total) break;
-        load_unit(bufA, u, opA, locA);
-    }
+    sub_group_body<CRIT, FAKE>(g, (int64_t)blockIdx.x, (int64_t)gridDim.x);
 }
 
 // Statistics of sub-tensor operands of a group: pass 1 writes one partial record per workgroup into
@@ -1356,6 +1164,7 @@ static bool is_flat(const KShape& sh, const KOut& o) {
     return sh.ld == sh.cols && o.ld_fp8 == sh.cols && (o.bf16 == nullptr || o.ld_bf16 == sh.cols) &&
            (o.fake == nullptr || o.ld_fake == sh.cols);
 }
+constexpr int64_t kSubRiderMaxUnits = 16384;  // 1x128 operands of at most 128 MiB ride on a team launch; larger ones run faster uncapped
 constexpr int64_t kSubFlatMaxBlocks = 4096;   // workgroups of 4 waves; each wave strides over 8 KB units (256 MiB operand: 77 us at 4096, 88 us at 1024)
 static int clamp_grid_y(int64_t v) { return (int)(v < 1 ? 1 : (v > 65535 ? 65535 : v)); }
 
@@ -1546,6 +1355,14 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
     }
 
     for (int crit = 0; crit < 2 && err == hipSuccess; ++crit) {
+        // ---- small flat 1x128 operands ride on the first 128x128 team launch of the same criterion and output kind
+        // (extra workgroups of that launch) instead of paying the ramp and tail of a launch of their own
+        TeamRiders riders;
+        riders.table.n = 0; riders.blocks = 0; riders.fake = false; riders.used = false;
+        int64_t rider_units = 0;
+        bool team_has[2] = {false, false};
+        for (int i = 0; i < n; ++i)
+            if (route[i] == kRouteTeam && items[i].crit == crit && team_kind_of(items[i]) == 0) team_has[items[i].o.fake ? 1 : 0] = true;
         // ---- 1x128 sub-channel operands, persistent grouped kernel (FP8 payload, then fake quantization)
         for (int fake = 0; fake < 2 && err == hipSuccess; ++fake) {
             GroupSub g; g.n = 0;
@@ -1568,7 +1385,16 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 const BatchItem& it = items[i];
                 if (route[i] != kRouteSubFlat || it.crit != crit || (it.o.fake != nullptr) != (fake != 0)) continue;
                 const int64_t n_part = item_parts(it), n_units = n_part / 32, n_full = n_units * 32, n_tail = n_part - n_full;
-                if (n_units > 0) {
+                if (n_units > 0 && n_units <= kSubRiderMaxUnits && team_has[fake] && riders.table.n < kMaxSubRiders &&
+                    (riders.table.n == 0 || riders.fake == (fake != 0))) {
+                    SubRiders& r = riders.table;
+                    rider_units += n_units;
+                    r.unit_end[r.n] = rider_units; r.x[r.n] = it.x; r.o[r.n] = it.o; r.th[r.n] = it.th; r.defer[r.n] = it.scope == 1;
+                    r.mode[r.n] = (uint8_t)it.scaling; r.gam[r.n] = gam_of[i];
+                    ++r.n;
+                    riders.fake = fake != 0;
+                    riders.blocks = (rider_units + 3) / 4 < kSubFlatMaxBlocks ? (rider_units + 3) / 4 : kSubFlatMaxBlocks;
+                } else if (n_units > 0) {
                     total += n_units;
                     g.unit_end[g.n] = total; g.x[g.n] = it.x; g.o[g.n] = it.o; g.th[g.n] = it.th; g.defer[g.n] = it.scope == 1;
                     g.mode[g.n] = (uint8_t)it.scaling; g.gam[g.n] = gam_of[i];
@@ -1602,7 +1428,25 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
             int cnt = 0;
             for (int i = 0; i < n; ++i)
                 if (route[i] == kRouteTeam && items[i].crit == crit && team_kind_of(items[i]) == kind) idx[cnt++] = i;
-            if (cnt) err = launch_team_items(items, idx, cnt, kind, crit, gam_of, st, prof);
+            if (cnt) err = launch_team_items(items, idx, cnt, kind, crit, gam_of, &riders, st, prof);
+        }
+        if (err == hipSuccess && riders.table.n > 0 && !riders.used) {      // no team launch took them: a launch of their own
+            GroupSub g; g.n = riders.table.n;
+            for (int k = 0; k < g.n; ++k) {
+                const SubRiders& r = riders.table;
+                g.unit_end[k] = r.unit_end[k]; g.x[k] = r.x[k]; g.o[k] = r.o[k]; g.th[k] = r.th[k]; g.defer[k] = r.defer[k];
+                g.mode[k] = r.mode[k]; g.gam[k] = r.gam[k];
+            }
+            ProfScope ps(prof, kKernSub1x128, st);
+            const dim3 grid((unsigned)riders.blocks);
+            if (riders.fake) {
+                if (crit == kCritEq3) k_sub1x128_group<kCritEq3, true><<<grid, dim3(256), 0, st>>>(g);
+                else k_sub1x128_group<kCritEq2, true><<<grid, dim3(256), 0, st>>>(g);
+            } else {
+                if (crit == kCritEq3) k_sub1x128_group<kCritEq3, false><<<grid, dim3(256), 0, st>>>(g);
+                else k_sub1x128_group<kCritEq2, false><<<grid, dim3(256), 0, st>>>(g);
+            }
+            riders.used = true;
         }
         // ---- 128x1 sub-columns
         if (err == hipSuccess) {

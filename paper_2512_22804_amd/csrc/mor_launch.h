@@ -124,10 +124,13 @@ size_t batch_workspace_bytes(const BatchItem* items, int n);
 hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws, size_t ws_bytes, hipStream_t st, KProf* prof);
 
 // mor_partitions.hip: team kernels (64x64, per-channel rows, general 128x128) and column kernels
+enum { kCritEq2 = 0, kCritEq3 = 1 };
+
 constexpr int kTeamKinds = 5;      // team kinds are numbered 0 .. kTeamKinds - 1 (mor_partitions.hip)
 int team_kind_of(const BatchItem& it);
+struct TeamRiders;      // mor_sub1x128.h
 hipError_t launch_team_items(const BatchItem* items, const int* idx, int cnt, int kind, int crit, const uint32_t* const* gam_of,
-                             hipStream_t st, KProf* prof);
+                             TeamRiders* riders, hipStream_t st, KProf* prof);
 hipError_t launch_subcol_items(const BatchItem* items, const int* idx, int cnt, int crit, const uint32_t* const* gam_of,
                                hipStream_t st, KProf* prof);
 size_t column_workspace_bytes(int64_t rows, int64_t cols);

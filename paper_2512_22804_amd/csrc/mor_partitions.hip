@@ -10,10 +10,10 @@
 
 #include "mor_device.h"
 #include "mor_launch.h"
+#include "mor_sub1x128.h"
 
 namespace mor {
 
-enum { kCritEq2 = 0, kCritEq3 = 1 };
 constexpr int kChunks = 8;     // 16-byte chunks per lane
 
 // ======================================================================================
@@ -320,8 +320,16 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
     }
 }
 
+// Workgroups from `sub_first` on (block teams of 256 lanes only) run the flat 1 x 128 body over the riders: a small
+// 1 x 128 operand then shares this launch instead of paying the ramp and tail of a launch of its own.
 template <int TEAM, int CRIT, bool FAKE, bool EDGE>
-__global__ __launch_bounds__(TEAM == kTeamBigRow ? 1024 : 256) void k_team_group(GroupTeam g) {
+__global__ __launch_bounds__(TEAM == kTeamBigRow ? 1024 : 256) void k_team_group(GroupTeam g, SubRiders riders, int64_t sub_first) {
+    if constexpr (TEAM == kTeamWg128) {
+        if ((int64_t)blockIdx.x >= sub_first) {
+            sub_group_body<CRIT, FAKE>(riders, (int64_t)blockIdx.x - sub_first, (int64_t)gridDim.x - sub_first);
+            return;
+        }
+    }
     __shared__ TeamShared sh;
     const int op = group_find(g.unit_end, g.n, blockIdx.x);
     const TeamOp& t = g.op[op];
@@ -954,16 +962,22 @@ namespace {
 size_t align16p(size_t v) { return (v + 15) & ~(size_t)15; }
 
 template <int TEAM, bool FAKE, bool EDGE>
-void launch_team_crit(const GroupTeam& g, int64_t total, int crit, hipStream_t st) {
-    const dim3 grid((unsigned)total), block(TEAM == kTeamBigRow ? 1024 : 256);
+void launch_team_crit(const GroupTeam& g, int64_t total, int crit, const SubRiders& riders, int64_t rider_blocks, hipStream_t st) {
+    const dim3 grid((unsigned)(total + rider_blocks)), block(TEAM == kTeamBigRow ? 1024 : 256);
     const int lds = TEAM == kTeamWg128 ? kResidency5 : 0;      // the other kinds show no gain from a cap
-    if (crit == kCritEq3) k_team_group<TEAM, kCritEq3, FAKE, EDGE><<<grid, block, lds, st>>>(g);
-    else k_team_group<TEAM, kCritEq2, FAKE, EDGE><<<grid, block, lds, st>>>(g);
+    if (crit == kCritEq3) k_team_group<TEAM, kCritEq3, FAKE, EDGE><<<grid, block, lds, st>>>(g, riders, total);
+    else k_team_group<TEAM, kCritEq2, FAKE, EDGE><<<grid, block, lds, st>>>(g, riders, total);
 }
 template <int TEAM>
-void launch_team_kind(const GroupTeam& g, int64_t total, int crit, bool fake, bool edge, hipStream_t st) {
-    if (fake) { if (edge) launch_team_crit<TEAM, true, true>(g, total, crit, st); else launch_team_crit<TEAM, true, false>(g, total, crit, st); }
-    else      { if (edge) launch_team_crit<TEAM, false, true>(g, total, crit, st); else launch_team_crit<TEAM, false, false>(g, total, crit, st); }
+void launch_team_kind(const GroupTeam& g, int64_t total, int crit, bool fake, bool edge, const SubRiders& riders, int64_t rider_blocks,
+                      hipStream_t st) {
+    if (fake) {
+        if (edge) launch_team_crit<TEAM, true, true>(g, total, crit, riders, rider_blocks, st);
+        else launch_team_crit<TEAM, true, false>(g, total, crit, riders, rider_blocks, st);
+    } else {
+        if (edge) launch_team_crit<TEAM, false, true>(g, total, crit, riders, rider_blocks, st);
+        else launch_team_crit<TEAM, false, false>(g, total, crit, riders, rider_blocks, st);
+    }
 }
 // Does the operand need per-lane validity predicates in the team kernel of this kind?
 bool team_needs_edge(const BatchItem& it, int kind) {
@@ -984,10 +998,13 @@ int team_kind_of(const BatchItem& it) {
     }
 }
 
-// All operands of `items` (indices idx[0..cnt)) that share one team kind and criterion, in groups.
+// All operands of `items` (indices idx[0..cnt)) that share one team kind and criterion, in groups.  `riders`
+// (may be null): flat 1 x 128 operands of the same criterion that ride on the first 128 x 128 launch whose output
+// kind (FP8 payload or fake quantization) matches theirs; `riders->used` is set when they went along.
 hipError_t launch_team_items(const BatchItem* items, const int* idx, int cnt, int kind, int crit, const uint32_t* const* gam_of,
-                             hipStream_t st, KProf* prof) {
-    static_assert(sizeof(GroupTeam) <= 3800 && sizeof(GroupCol) <= 3800, "kernel-argument segment is 4 KB");
+                             TeamRiders* riders, hipStream_t st, KProf* prof) {
+    static_assert(sizeof(GroupTeam) + sizeof(SubRiders) <= 3800 && sizeof(GroupCol) <= 3800, "kernel-argument segment is 4 KB");
+    SubRiders none; none.n = 0;
     for (int variant = 0; variant < 4; ++variant) {
     const bool fake = (variant & 1) != 0, edge = (variant & 2) != 0;
     GroupTeam g; g.n = 0;
@@ -995,12 +1012,16 @@ hipError_t launch_team_items(const BatchItem* items, const int* idx, int cnt, in
     auto flush = [&]() {
         if (g.n == 0) return;
         ProfScope ps(prof, kKernTeamBlock, st);
+        const bool ride = kind == kTeamWg128 && riders && !riders->used && riders->table.n > 0 && riders->fake == fake;
+        const SubRiders& rt = ride ? riders->table : none;
+        const int64_t rb = ride ? riders->blocks : 0;
+        if (ride) riders->used = true;
         switch (kind) {
-        case kTeamWg128: launch_team_kind<kTeamWg128>(g, total, crit, fake, edge, st); break;
-        case kTeamHalf64: launch_team_kind<kTeamHalf64>(g, total, crit, fake, edge, st); break;
-        case kTeamWaveRow: launch_team_kind<kTeamWaveRow>(g, total, crit, fake, edge, st); break;
-        case kTeamWgRow: launch_team_kind<kTeamWgRow>(g, total, crit, fake, edge, st); break;
-        default: launch_team_kind<kTeamBigRow>(g, total, crit, fake, edge, st); break;
+        case kTeamWg128: launch_team_kind<kTeamWg128>(g, total, crit, fake, edge, rt, rb, st); break;
+        case kTeamHalf64: launch_team_kind<kTeamHalf64>(g, total, crit, fake, edge, rt, rb, st); break;
+        case kTeamWaveRow: launch_team_kind<kTeamWaveRow>(g, total, crit, fake, edge, rt, rb, st); break;
+        case kTeamWgRow: launch_team_kind<kTeamWgRow>(g, total, crit, fake, edge, rt, rb, st); break;
+        default: launch_team_kind<kTeamBigRow>(g, total, crit, fake, edge, rt, rb, st); break;
         }
         g.n = 0; total = 0;
     };
@@ -1014,7 +1035,7 @@ hipError_t launch_team_items(const BatchItem* items, const int* idx, int cnt, in
         else if (kind == kTeamWaveRow) units = (it.sh.rows + 3) / 4;
         else units = it.sh.rows;
         if (units > 0x7FFFFFFF) return hipErrorInvalidValue;
-        if (total + units > 0x7FFFFFFF) { flush(); }
+        if (total + units > 0x7FFF0000) { flush(); }       // leaves room for the riders' workgroups
         TeamOp& u = g.op[g.n];
         u.x = it.x; u.o = it.o; u.ld = it.sh.ld; u.rows = it.sh.rows; u.cols = it.sh.cols;
         u.units_x = kind == kTeamHalf64 ? (it.sh.cols + 255) / 256 : (it.sh.cols + 127) / 128;
