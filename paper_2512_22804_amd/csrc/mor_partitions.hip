@@ -934,7 +934,18 @@ __global__ __launch_bounds__(256) void k_col_fallback(GroupCol g) {
     if (t.o.bf16 == nullptr) keep = 0u;
     if (!keep && !five) return;
     uint16_t* __restrict__ fakep = t.o.fake;
-    for (int64_t r = rg * 16 + (threadIdx.x >> 4); r < t.rows; r += (int64_t)t.copy_groups * 16) {
+    const int64_t rstep = (int64_t)t.copy_groups * 16;
+    int64_t r = rg * 16 + (threadIdx.x >> 4);
+    if (keep == 0xFFu && !five) {          // whole chunks stay in BF16: four 16-byte loads in flight per lane
+        for (; r + 3 * rstep < t.rows; r += 4 * rstep) {
+            u32x4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = load16(t.x + (r + u * rstep) * t.ld + c);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) store16(t.o.bf16 + (r + u * rstep) * t.o.ld_bf16 + c, v[u]);
+        }
+    }
+    for (; r < t.rows; r += rstep) {
         const uint16_t* sp = t.x + r * t.ld + c;
         if (keep == 0xFFu) store16(t.o.bf16 + r * t.o.ld_bf16 + c, load16(sp));
         else if (keep) {
