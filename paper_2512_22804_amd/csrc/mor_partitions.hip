@@ -322,9 +322,10 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
 
 // Workgroups from `sub_first` on (block teams of 256 lanes only) run the flat 1 x 128 body over the riders: a small
 // 1 x 128 operand then shares this launch instead of paying the ramp and tail of a launch of its own.
-template <int TEAM, int CRIT, bool FAKE, bool EDGE>
+// RIDE is a template parameter so that launches without riders keep the team body's smaller register allocation.
+template <int TEAM, int CRIT, bool FAKE, bool EDGE, bool RIDE>
 __global__ __launch_bounds__(TEAM == kTeamBigRow ? 1024 : 256) void k_team_group(GroupTeam g, SubRiders riders, int64_t sub_first) {
-    if constexpr (TEAM == kTeamWg128) {
+    if constexpr (RIDE) {
         if ((int64_t)blockIdx.x >= sub_first) {
             sub_group_body<CRIT, FAKE>(riders, (int64_t)blockIdx.x - sub_first, (int64_t)gridDim.x - sub_first);
             return;
@@ -976,8 +977,15 @@ template <int TEAM, bool FAKE, bool EDGE>
 void launch_team_crit(const GroupTeam& g, int64_t total, int crit, const SubRiders& riders, int64_t rider_blocks, hipStream_t st) {
     const dim3 grid((unsigned)(total + rider_blocks)), block(TEAM == kTeamBigRow ? 1024 : 256);
     const int lds = TEAM == kTeamWg128 ? kResidency5 : 0;      // the other kinds show no gain from a cap
-    if (crit == kCritEq3) k_team_group<TEAM, kCritEq3, FAKE, EDGE><<<grid, block, lds, st>>>(g, riders, total);
-    else k_team_group<TEAM, kCritEq2, FAKE, EDGE><<<grid, block, lds, st>>>(g, riders, total);
+    if constexpr (TEAM == kTeamWg128) {
+        if (rider_blocks > 0) {
+            if (crit == kCritEq3) k_team_group<TEAM, kCritEq3, FAKE, EDGE, true><<<grid, block, lds, st>>>(g, riders, total);
+            else k_team_group<TEAM, kCritEq2, FAKE, EDGE, true><<<grid, block, lds, st>>>(g, riders, total);
+            return;
+        }
+    }
+    if (crit == kCritEq3) k_team_group<TEAM, kCritEq3, FAKE, EDGE, false><<<grid, block, lds, st>>>(g, riders, total);
+    else k_team_group<TEAM, kCritEq2, FAKE, EDGE, false><<<grid, block, lds, st>>>(g, riders, total);
 }
 template <int TEAM>
 void launch_team_kind(const GroupTeam& g, int64_t total, int crit, bool fake, bool edge, const SubRiders& riders, int64_t rider_blocks,
