@@ -98,7 +98,9 @@ def run_variants(ops, B, torch, dev, steps, log):
                     b -= 1.0 * n * f                            # no FP8 payload for an operand known to stay in BF16
             else:
                 b = 3.0 * n + META_BYTES * P
-                if scope == "tensor":
+                if scope == "tensor" and scaling == "gam" and gran in ("block128", "channel_row"):
+                    b += 2.0 * n * f                            # these inputs' BF16 decision is proven by the pre-pass: written by the block kernel
+                elif scope == "tensor":
                     b += 4.0 * n * f                            # separate copy pass after the tensor-wide decision
                 else:
                     b += 2.0 * n * f

@@ -362,6 +362,7 @@ struct ScopeOp {
     int64_t n_part;
     double* part_err; double* part_err5; unsigned long long* part_nnz;     // [kScopeBlocks] each
     uint32_t* decision;                                                    // [1]
+    const uint32_t* proven;                                                // non-null and [0] != 0: the block kernel wrote the fallback
     float th;
     int32_t crit;
     int32_t n_red;                                                         // workgroups of the reduce pass (<= kScopeBlocks)
@@ -418,7 +419,7 @@ __global__ __launch_bounds__(256) void k_scope_decide_group(GroupScope g) {
 __global__ __launch_bounds__(256) void k_scope_copy_group(GroupScope g) {
     const int op = group_find32(g.copy_end, g.n, blockIdx.x);
     const ScopeOp& t = g.op[op];
-    if (t.bf16 == nullptr || t.decision[0] == 0u) return;
+    if (t.bf16 == nullptr || t.decision[0] == 0u || (t.proven && t.proven[0] != 0u)) return;
     const int b = blockIdx.x - (op ? g.copy_end[op - 1] : 0);
     const int nb = g.copy_end[op] - (op ? g.copy_end[op - 1] : 0);
     if (t.ld == t.cols && t.ld_bf16 == t.cols) {
@@ -1117,8 +1118,11 @@ __global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g, Grou
 struct GamOp {
     const uint32_t* amax_part; int n_amax;
     uint32_t mode;
-    uint32_t* gam;         // [2] workspace words read by the block kernels
+    uint32_t* gam;         // [4] workspace words read by the block kernels: the two mantissas, then 1 if the pre-pass proved
+                           // the tensor-level BF16 decision
     uint32_t* gmant;       // caller's group-mantissa output, may be nullptr
+    const uint32_t* flush_part;          // [n_amax] certain flushes counted by the pre-pass, or nullptr
+    unsigned long long flush_need;       // that many prove the decision
 };
 struct GroupGam {
     int n;
@@ -1126,9 +1130,15 @@ struct GroupGam {
 };
 __global__ __launch_bounds__(256) void k_gam_prepare(GroupGam g) {
     __shared__ uint32_t sh4[4];
+    __shared__ unsigned long long shl[4];
     const GamOp& t = g.op[blockIdx.x];
     const uint32_t gbits = global_amax_bits(t.amax_part, t.n_amax, sh4);
+    unsigned long long fl = 0ull;
+    if (t.flush_part)
+        for (int i = threadIdx.x; i < t.n_amax; i += 256) fl += t.flush_part[i];
+    fl = block_sum_shfl<unsigned long long>(fl, shl);
     if (threadIdx.x == 0) {
+        t.gam[2] = (t.flush_part && fl >= t.flush_need) ? 1u : 0u;
         const uint32_t mg = group_mantissa_bits(gbits, kE4M3Max, t.mode);
         t.gam[0] = mg;
         const uint32_t mg5 = group_mantissa_bits(gbits, kE5M2Max, t.mode);
@@ -1266,7 +1276,7 @@ size_t item_workspace(const BatchItem& it) {
     if (it.stats && it.gran != kGranTensor) b += align16(sizeof(StatsRec) * kStatsMaxWg);
     if (it.gran != kGranTensor && it.scaling != kScaleFp32) {
         b += 16;                                                                   // group mantissa words
-        if (it.scaling == kScaleGam) b += align16(sizeof(uint32_t) * kMaxAmaxBlocks);   // amax partials of the pre-pass
+        if (it.scaling == kScaleGam) b += 2 * align16(sizeof(uint32_t) * kMaxAmaxBlocks);   // amax and flush partials of the pre-pass
     }
     return b;
 }
@@ -1305,6 +1315,41 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
         int cnt = 0;
         for (int i = 0; i < n; ++i)
             if (items[i].gran != kGranTensor && items[i].scaling != kScaleFp32) idx[cnt++] = i;
+        // operands whose tensor-level decision the pre-pass may prove: block-shaped pre-pass (group amax and, per block,
+        // the elements that are certain to flush), as many operands per launch as its argument table holds
+        uint32_t* pv_part[kBatchMax] = {};
+        uint32_t* pv_flush[kBatchMax] = {};
+        int pv_wg[kBatchMax] = {};
+        {
+            constexpr int kProveGroup = 12;
+            BlockProveItem pv[kProveGroup];
+            int pv_item[kProveGroup];
+            int n_pv = 0;
+            int64_t pv_units = 0;
+            auto flush = [&]() {
+                if (n_pv == 0) return;
+                for (int j = 0; j < n_pv; ++j) {
+                    const int64_t units = scope_proof_units(items[pv_item[j]]);
+                    pv[j].n_wg = share(units, pv_units, kMaxAmaxBlocks, units);     // 0.566 ms per twelve-operand pass at 2048, 0.581 ms at 1024
+                    pv_wg[pv_item[j]] = pv[j].n_wg;
+                }
+                ProfScope ps(prof, kKernGroupAmax, st);
+                err = launch_block_amax_prove(pv, n_pv, st);
+                n_pv = 0; pv_units = 0;
+            };
+            for (int k = 0; k < cnt && err == hipSuccess; ++k) {
+                const int i = idx[k];
+                const BatchItem& it = items[i];
+                if (!scope_proof_applies(it)) continue;
+                pv_part[i] = reinterpret_cast<uint32_t*>(carve(sizeof(uint32_t) * kMaxAmaxBlocks));
+                pv_flush[i] = reinterpret_cast<uint32_t*>(carve(sizeof(uint32_t) * kMaxAmaxBlocks));
+                pv[n_pv] = BlockProveItem{it.x, it.sh.rows, it.sh.cols, it.sh.ld, pv_part[i], pv_flush[i], 0, it.gran == kGranRow};
+                pv_units += scope_proof_units(it);
+                pv_item[n_pv] = i;
+                if (++n_pv == kProveGroup) flush();
+            }
+            flush();
+        }
         for (int base = 0; base < cnt; base += kMaxGroupTensor) {
             const int m = cnt - base < kMaxGroupTensor ? cnt - base : kMaxGroupTensor;
             GroupGam gg; gg.n = m;
@@ -1312,14 +1357,22 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
             int slot_of[kMaxGroupTensor];
             int64_t total_tiles = 0;
             for (int k = 0; k < m; ++k) {
-                const BatchItem& it = items[idx[base + k]];
+                const int i = idx[base + k];
+                const BatchItem& it = items[i];
                 uint32_t* gam = reinterpret_cast<uint32_t*>(carve(16));
-                gam_of[idx[base + k]] = gam;
+                gam_of[i] = gam;
                 GamOp& q = gg.op[k];
                 q.amax_part = nullptr; q.n_amax = 0; q.mode = (uint32_t)it.scaling; q.gam = gam; q.gmant = it.o.gmant;
+                q.flush_part = nullptr; q.flush_need = 0ull;
                 slot_of[k] = -1;
                 if (it.scaling != kScaleGam) continue;
-                uint32_t* part = reinterpret_cast<uint32_t*>(carve(sizeof(uint32_t) * kMaxAmaxBlocks));
+                if (pv_part[i]) {
+                    q.amax_part = pv_part[i]; q.n_amax = pv_wg[i];
+                    q.flush_part = pv_flush[i];
+                    q.flush_need = (unsigned long long)(1.01 * (double)it.th * (double)(it.sh.rows * it.sh.cols)) + 1ull;   // binary32 sums
+                    continue;
+                }
+                uint32_t* part = reinterpret_cast<uint32_t*>(carve(2 * sizeof(uint32_t) * kMaxAmaxBlocks));
                 q.amax_part = part;
                 if (it.sh.ld == it.sh.cols) {
                     TensorOp& t = ga.op[ga.n];
@@ -1494,6 +1547,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
             t.part_nnz = reinterpret_cast<unsigned long long*>(w) + 2 * kScopeBlocks;
             t.decision = reinterpret_cast<uint32_t*>(w + 3 * sizeof(double) * kScopeBlocks);
             t.th = it.th; t.crit = it.crit;
+            t.proven = scope_proof_applies(it) ? gam_of[i] + 2 : nullptr;
             int64_t want = (t.n_part + 1023) / 1024;
             t.n_red = (int)(want < 1 ? 1 : (want > kScopeBlocks ? kScopeBlocks : want));
             t.x = it.x; t.bf16 = it.o.bf16;

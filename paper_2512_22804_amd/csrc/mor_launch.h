@@ -126,6 +126,30 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
 // mor_partitions.hip: team kernels (64x64, per-channel rows, general 128x128) and column kernels
 enum { kCritEq2 = 0, kCritEq3 = 1 };
 
+// Tensor-level decision (Section 3.1) over GAM-scaled 128 x 128 blocks or per-channel rows: the amax pre-pass of
+// Algorithm 1 can prove the BF16 decision under Eq. 2 from elements that are certain to flush inside their block, so
+// the block kernel writes the BF16 payload from its registers and the operand is not read a third time.
+inline bool scope_proof_applies(const BatchItem& it) {
+    if (it.scaling != 1 || it.scope != 1 || it.crit != kCritEq2 || it.three || it.o.bf16 == nullptr || it.o.fake != nullptr) return false;
+    if (it.gran == kGranBlock) return it.sh.rows % 128 == 0 && it.sh.cols % 128 == 0;
+    return it.gran == kGranRow;
+}
+// Work units of the pre-pass (16384 elements each) and its per-operand arguments: per workgroup the largest amax and
+// the number of certain flushes it saw.
+inline int64_t scope_proof_units(const BatchItem& it) {
+    if (it.gran == kGranRow) return (it.sh.rows * ((it.sh.cols + 4095) / 4096) + 3) / 4;
+    return (it.sh.rows / 128) * (it.sh.cols / 128);
+}
+struct BlockProveItem {
+    const uint16_t* x;
+    int64_t rows, cols, ld;
+    uint32_t* amax_part;     // [n_wg]
+    uint32_t* flush_part;    // [n_wg]
+    int n_wg;
+    int by_rows;             // per-channel rows instead of 128 x 128 blocks
+};
+hipError_t launch_block_amax_prove(const BlockProveItem* ops, int n, hipStream_t st);
+
 constexpr int kTeamKinds = 5;      // team kinds are numbered 0 .. kTeamKinds - 1 (mor_partitions.hip)
 int team_kind_of(const BatchItem& it);
 struct TeamRiders;      // mor_sub1x128.h

@@ -35,7 +35,7 @@ struct TeamOp {
     int64_t ld, rows, cols;
     int64_t units_x;        // 128-column tiles per row of tiles (block kinds)
     float th;
-    uint8_t defer, mode, three, pad;
+    uint8_t defer, mode, three, prove;      // prove: gam[2] != 0 says the tensor-level BF16 decision is already proven
     const uint32_t* gam;
 };
 struct GroupTeam {
@@ -307,7 +307,9 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
         if (mode != kScaleFp32 && o.e8m0) o.e8m0[p] = (uint8_t)(__float_as_uint(s) >> 23);
         if (t.three && o.amin) o.amin[p] = __uint_as_float(amin_bits << 16);
     }
-    if (mask == 1u && o.bf16) {                            // BF16: the block stays as it is
+    bool keep = mask == 1u;
+    if (t.prove) keep = t.gam[2] != 0u;                    // deferred decision, proven by the pre-pass (uniform)
+    if (keep && o.bf16) {                                  // BF16: the block stays as it is
         uint16_t* __restrict__ dbf = o.bf16 + (r0 + trow) * o.ld_bf16 + c0 + tcol;
         const int64_t dbf_step = (int64_t)rstep * o.ld_bf16 + cstep;
         const BufRsrc rb = make_buf(o.bf16 + r0 * o.ld_bf16 + c0);
@@ -336,6 +338,99 @@ __global__ __launch_bounds__(TEAM == kTeamBigRow ? 1024 : 256) void k_team_group
     const TeamOp& t = g.op[op];
     const int64_t unit = (int64_t)blockIdx.x - (op ? g.unit_end[op - 1] : 0);
     team_block<TEAM, CRIT, FAKE, EDGE>(t, unit, sh);
+}
+
+// Pre-pass of Algorithm 1 (group amax) for operands with 128 x 128 blocks or per-channel rows whose decision is taken
+// per tensor under Eq. 2: a workgroup walks over tiles, keeps the running maximum and counts the elements that are
+// certain to flush -- non-zero and below 2^-20 of a LOWER bound of their own block's amax (the amax of the part of the
+// block that the lane's wave holds: 32 rows of a 128 x 128 block, up to 4096 consecutive elements of a row), so that
+// under any scale of Algorithm 1 (never above 448 / amax) they land below half the smallest E4M3 subnormal and contribute
+// exactly 1 to the error sum.  The waves of a workgroup never wait for each other inside the loop, and the next tile's
+// loads are in flight while the current one is counted.
+struct ProveOp {
+    const uint16_t* x;
+    int64_t ld, cols;
+    int64_t units_x;         // blocks: 128-column tiles per row of tiles; rows: pieces of 4096 elements per row
+    int64_t n_units;         // blocks: tiles; rows: pieces (one per wave)
+    uint32_t* amax_part;
+    uint32_t* flush_part;
+    int32_t by_rows;
+};
+struct GroupProve {
+    int n;
+    int32_t wg_end[kMaxTeamGroup];
+    ProveOp op[kMaxTeamGroup];
+};
+constexpr int kProvePiece = 64 * 8 * kChunks;      // elements of a row that one wave holds at a time
+static_assert(kProvePiece == 4096, "scope_proof_units() counts pieces of 4096 elements");
+template <bool BY_ROWS>
+__device__ __forceinline__ void prove_tiles(const ProveOp& t, int b, int nb, uint32_t& amax_run, uint32_t& flush_run) {
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    auto load_tile = [&](u32x4 (&raw)[kChunks], int64_t unit) {
+        if constexpr (BY_ROWS) {
+            // wave w of the workgroup's unit takes piece 4 * unit + w; chunks beyond the row (or beyond the operand) load zeros
+            const int64_t piece = unit * 4 + w, row = piece / t.units_x, c0 = (piece - row * t.units_x) * kProvePiece;
+            const BufRsrc rx = make_buf(t.x + row * t.ld + c0);
+            const bool inside = piece < t.n_units;
+#pragma unroll
+            for (int i = 0; i < kChunks; ++i)
+                raw[i] = buf_load16(rx, (inside && c0 + (i * 64 + lane) * 8 < t.cols) ? (uint32_t)(lane * 16) : kBufOutside, i * 1024);
+        } else {
+            const int64_t tr = unit / t.units_x, tc = unit - tr * t.units_x;
+            const uint16_t* __restrict__ src = t.x + (tr * 128 + (tid >> 4)) * t.ld + tc * 128 + (tid & 15) * 8;
+#pragma unroll
+            for (int i = 0; i < kChunks; ++i) raw[i] = load16(src + (int64_t)i * 16 * t.ld);
+        }
+    };
+    const int64_t n_wg_units = BY_ROWS ? (t.n_units + 3) / 4 : t.n_units;
+    u32x4 cur[kChunks], nxt[kChunks];
+    int64_t unit = b;
+    if (unit < n_wg_units) load_tile(cur, unit);
+    while (unit < n_wg_units) {
+        const int64_t next = unit + nb;
+        if (next < n_wg_units) load_tile(nxt, next);        // uniform over the workgroup
+        uint32_t a2 = 0u;
+#pragma unroll
+        for (int i = 0; i < kChunks; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a2 = pk_max_u16(a2, cur[i][j] & 0x7FFF7FFFu);
+        const uint32_t abits = wave_allmax_u32(fold_max16(a2));      // what this wave holds of the block
+        amax_run = max(amax_run, abits);
+        // certain flush: 1 <= m < t  <=>  m - 1 < t - 1, with t the amax pattern taken down by 20 binades (0 if that
+        // underflows); m - 1 wraps to 0xFFFF for zeros, which never count
+        const uint32_t t1 = abits > 0x0A00u ? abits - 0x0A01u : 0u;
+        const uint32_t bound2 = t1 | (t1 << 16);
+        uint32_t f2 = 0u;
+#pragma unroll
+        for (int i = 0; i < kChunks; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t mm1 = pk_sub_u16(cur[i][j] & 0x7FFF7FFFu, 0x00010001u);
+                f2 = pk_add_u16(f2, pk_min_u16(pk_sub_sat_u16(bound2, mm1), 0x00010001u));
+            }
+        flush_run += fold_add16(f2);                       // at most 64 per tile and lane
+#pragma unroll
+        for (int i = 0; i < kChunks; ++i) cur[i] = nxt[i];
+        unit = next;
+    }
+}
+__global__ __launch_bounds__(256) void k_block_amax_prove(GroupProve g) {
+    __shared__ uint32_t sh[8];
+    const int op = group_find32(g.wg_end, g.n, blockIdx.x);
+    const ProveOp& t = g.op[op];
+    const int first = op ? g.wg_end[op - 1] : 0;
+    const int b = blockIdx.x - first, nb = g.wg_end[op] - first;
+    const int tid = threadIdx.x;
+    uint32_t amax_run = 0u, flush_run = 0u;
+    if (t.by_rows) prove_tiles<true>(t, b, nb, amax_run, flush_run);
+    else prove_tiles<false>(t, b, nb, amax_run, flush_run);
+    flush_run = wave_allsum_u32(flush_run);                // amax_run is already uniform over the wave
+    if ((tid & 63) == 0) { sh[tid >> 6] = amax_run; sh[4 + (tid >> 6)] = flush_run; }
+    __syncthreads();
+    if (tid == 0) {
+        t.amax_part[b] = max(max(sh[0], sh[1]), max(sh[2], sh[3]));
+        t.flush_part[b] = (sh[4] + sh[5]) + (sh[6] + sh[7]);
+    }
 }
 
 // ======================================================================================
@@ -1058,13 +1153,33 @@ hipError_t launch_team_items(const BatchItem* items, const int* idx, int cnt, in
         TeamOp& u = g.op[g.n];
         u.x = it.x; u.o = it.o; u.ld = it.sh.ld; u.rows = it.sh.rows; u.cols = it.sh.cols;
         u.units_x = kind == kTeamHalf64 ? (it.sh.cols + 255) / 256 : (it.sh.cols + 127) / 128;
-        u.th = it.th; u.defer = it.scope == 1; u.mode = (uint8_t)it.scaling; u.three = (uint8_t)it.three; u.pad = 0;
+        u.th = it.th; u.defer = it.scope == 1; u.mode = (uint8_t)it.scaling; u.three = (uint8_t)it.three;
+        u.prove = scope_proof_applies(it);
         u.gam = gam_of[idx[k]];
         total += units;
         g.unit_end[g.n] = total;
         if (++g.n == kMaxTeamGroup) flush();
     }
     flush();
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_block_amax_prove(const BlockProveItem* ops, int n, hipStream_t st) {
+    static_assert(sizeof(GroupProve) <= 3800, "kernel-argument segment is 4 KB");
+    for (int base = 0; base < n; base += kMaxTeamGroup) {
+        GroupProve g; g.n = 0;
+        int end = 0;
+        for (int k = base; k < n && k < base + kMaxTeamGroup; ++k) {
+            ProveOp& t = g.op[g.n];
+            t.x = ops[k].x; t.ld = ops[k].ld; t.cols = ops[k].cols; t.by_rows = ops[k].by_rows;
+            if (t.by_rows) { t.units_x = (ops[k].cols + kProvePiece - 1) / kProvePiece; t.n_units = ops[k].rows * t.units_x; }
+            else { t.units_x = ops[k].cols / 128; t.n_units = (ops[k].rows / 128) * t.units_x; }
+            t.amax_part = ops[k].amax_part; t.flush_part = ops[k].flush_part;
+            end += ops[k].n_wg;
+            g.wg_end[g.n++] = end;
+        }
+        k_block_amax_prove<<<dim3((unsigned)end), dim3(256), 0, st>>>(g);
     }
     return hipGetLastError();
 }

@@ -121,3 +121,81 @@ def test_dequantize_from_stored_scale_form(oracle, scaling, gran):
     assert np.array_equal(parity.u16(y), want) and np.array_equal(parity.u16(y2), want)
     with pytest.raises(B.MorError):
         B.mor_dequantize_e8m0(params, g.fp8, None, g.group_mantissa, g.mask, g.bf16, y)
+
+
+def _with_tiny(rows, cols, frac, seed, tiny_exp=-40):
+    rng = np.random.default_rng(seed)
+    x = np.exp2(rng.uniform(-3.0, 3.0, size=(rows, cols))).astype(np.float32) * (rng.integers(0, 2, size=(rows, cols)) * 2 - 1)
+    x[rng.random((rows, cols)) < frac] = np.float32(2.0 ** tiny_exp)
+    return x
+
+
+@pytest.mark.parametrize("frac", [0.0, 0.04, 0.2])
+@pytest.mark.parametrize("pad", [0, 64])
+@pytest.mark.parametrize("gran,shape", [("block128", (640, 1152)), ("channel_row", (70, 1152)), ("channel_row", (9, 9000)),
+                                        ("channel_row", (5, 20000))])
+def test_gam_tensor_level_decision_proven_by_the_pre_pass(frac, pad, gran, shape):
+    """Tensor-level decision over GAM-scaled 128x128 blocks or per-channel rows (the recipe of Section 3.1): with enough
+    certain flushes the amax pre-pass proves the BF16 decision and the block kernel writes the fallback itself; with 4 %
+    flushed values the decision is BF16 without a proof (separate copy), with none it is E4M3.  Every output equals the
+    oracle's either way, and the fallback buffer is untouched when the decision is E4M3."""
+    rows, cols = shape
+    x = _with_tiny(rows, cols, frac, 11 + int(frac * 100))
+    xb = np.zeros((rows, cols + pad), np.uint16)
+    xb[:, :cols] = W.f32_to_bf16_bits(x)
+    r = parity.compare(xb, gran, "tensor", "mean_rel_err", 0.045, cols=cols, label=f"gam proof frac={frac}", scaling="gam")
+    assert r["n_bf16"] == (r["P"] if frac > 0 else 0)
+
+
+def test_gam_tensor_level_proof_uses_each_rows_own_amax():
+    """Per-channel rows: rows of small values only do not flush, whatever the other rows hold."""
+    x = _with_tiny(64, 4096, 0.0, 15)
+    x[1:, :] *= np.float32(2.0 ** -30)
+    x[0, np.random.default_rng(16).random(4096) < 0.5] = np.float32(2.0 ** -30)     # half of one row flushes
+    r = parity.compare(W.f32_to_bf16_bits(x), "channel_row", "tensor", "mean_rel_err", 0.045, label="gam proof per row", scaling="gam")
+    assert r["n_bf16"] == 0
+
+
+def test_gam_tensor_level_proof_uses_each_blocks_own_amax():
+    """Values that flush next to the large amax of one block do not flush in blocks that hold nothing larger: a bound taken
+    from the operand's amax would 'prove' a BF16 decision that the error sums do not support."""
+    rows, cols = 256, 256
+    x = _with_tiny(rows, cols, 0.0, 5)
+    x[128:, :] *= np.float32(2.0 ** -30)                  # two blocks of small values only
+    x[:128, 128:] *= np.float32(2.0 ** -30)               # and a third
+    top = np.random.default_rng(6).random((128, 128)) < 0.03
+    x[:128, :128][top] = np.float32(2.0 ** -30)            # 3 % of the remaining block flushes
+    xb = W.f32_to_bf16_bits(x)
+    r = parity.compare(xb, "block128", "tensor", "mean_rel_err", 0.045, label="gam proof per block", scaling="gam")
+    assert r["n_bf16"] == 0
+    # the same operand once its flushes are frequent enough in every block
+    x2 = _with_tiny(rows, cols, 0.3, 9, tiny_exp=-30)
+    x2[128:, :] *= np.float32(2.0 ** -20)
+    r = parity.compare(W.f32_to_bf16_bits(x2), "block128", "tensor", "mean_rel_err", 0.045, label="gam proof mixed", scaling="gam")
+    assert r["n_bf16"] == r["P"]
+
+
+def test_gam_tensor_level_proof_in_a_batch_with_statistics():
+    """Several provable and unprovable operands in one batch call (one pre-pass launch for all of them)."""
+    from oracle import mor_oracle as O
+    dev = torch.device("cuda")
+    specs = [(512, 1024, 0.2, "block128"), (256, 384, 0.0, "block128"), (384, 512, 0.04, "block128"), (128, 128, 0.5, "block128"),
+             (640, 256, 0.1, "block128"), (33, 4096, 0.2, "channel_row"), (7, 17000, 0.3, "channel_row"), (50, 512, 0.0, "channel_row")]
+    ops, keep = [], []
+    for k, (rows, cols, frac, gran) in enumerate(specs):
+        xb = W.f32_to_bf16_bits(_with_tiny(rows, cols, frac, 40 + k))
+        params = B.make_params(rows, cols, gran, "tensor", "mean_rel_err", 0.045, scaling="gam")
+        xd = parity.to_dev(xb)
+        out = B.alloc_outputs(params, dev, want_bf16=True, bf16_fill=parity.FILL)
+        st = torch.zeros(B.STATS_BYTES, dtype=torch.uint8, device=dev)
+        ops.append((params, xd, out, st)); keep.append(xb)
+    items = B.make_batch(ops)
+    ws = torch.empty(max(16, B.mor_batch_workspace_bytes(items)), dtype=torch.uint8, device=dev)
+    for _ in range(2):                                     # twice on the same workspace
+        B.mor_analyze_quantize_batch(items, 1e-5, ws)
+    torch.cuda.synchronize()
+    for (params, xd, out, st), xb, (rows, cols, frac, gran) in zip(ops, keep, specs):
+        r = parity.compare(xb, gran, "tensor", "mean_rel_err", 0.045, label="gam proof batch", scaling="gam", gpu=(params, out))
+        assert r["n_bf16"] == (r["P"] if frac > 0 else 0)
+        s = B.read_stats(st)
+        assert s["n_bf16_part"] == r["n_bf16"] and s["n_part"] == r["P"]
