@@ -567,6 +567,8 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
         // and stores nothing, without a branch)
         const BufRsrc rx = make_buf(t.x + r0 * t.ld + c0);
         const uint32_t xoff = (uint32_t)(((tid >> 4) * t.ld + cg * 8) * 2), xstep = (uint32_t)(16 * t.ld * 2);
+        // (the next tile's loads are not started early: with 32 more registers fewer workgroups fit, and the quantize pass
+        // of the per-channel columns took 407 us instead of 396 us)
         u32x4 raw[kChunks];
 #pragma unroll
         for (int i = 0; i < kChunks; ++i) {
@@ -1010,7 +1012,8 @@ __global__ __launch_bounds__(256) void k_col_finish(GroupCol g) {
 // Columns kept in BF16 are copied: 16 bytes at a time where all eight columns of a chunk are kept, else by element.
 // Columns kept in E5M2 (three-way recipe) get their payload here, element by element, over the E4M3 one.
 // A workgroup takes one 128-column strip and strides over the rows with the other workgroups of that strip.
-constexpr int kColCopyRowGroups = 32;      // at most; about 1024 workgroups per operand are enough
+constexpr int kColCopyRowGroups = 32;      // at most, per 128-column strip
+constexpr int kColCopyBudget = 4096;       // workgroups per launch, about
 __global__ __launch_bounds__(256) void k_col_fallback(GroupCol g) {
     const int op = group_find32(g.copy_end, g.n, blockIdx.x);
     const ColOp& t = g.op[op];
@@ -1279,6 +1282,18 @@ hipError_t launch_channel_col_items(const BatchItem* items, const int* idx, int 
         int comb = 0, copy = 0;
         auto flush = [&]() {
             if (g.n == 0) return;
+            // fallback-column pass: about kColCopyBudget workgroups over all operands of the launch (a workgroup that finds
+            // every kept column already written costs a few nanoseconds of dispatch, which adds up over 12 000 of them)
+            copy = 0;
+            for (int k = 0; k < g.n; ++k) {
+                ColOp& t = g.op[k];
+                int64_t groups = (kColCopyBudget / g.n + t.tiles_x - 1) / t.tiles_x;
+                if (groups < 2) groups = 2;
+                if (groups > kColCopyRowGroups) groups = kColCopyRowGroups;
+                t.copy_groups = (int32_t)groups;
+                copy += (int)(t.tiles_x * groups);
+                g.copy_end[k] = copy;
+            }
             { ProfScope ps(prof, kKernColumnTile, st); launch_col_kind<kColAmax>(g, total, kCritEq2, false, edge, st); }
             { ProfScope ps(prof, kKernColumnCombine, st); k_col_scales<<<dim3((unsigned)comb), dim3(256), 0, st>>>(g); }
             { ProfScope ps(prof, kKernColumnTile, st); launch_col_kind<kColExternal>(g, total, crit, fake, edge, st); }
@@ -1315,12 +1330,8 @@ hipError_t launch_channel_col_items(const BatchItem* items, const int* idx, int 
             t.flush_need = (uint32_t)(1.01 * (double)it.th * (double)it.sh.rows) + 1u;      // 1 % margin covers the binary32 sums
             total += units;
             comb += (int)((pl.cols_padded + 255) / 256);
-            int64_t groups = (1024 + tiles_x - 1) / tiles_x;
-            if (groups < 2) groups = 2;
-            if (groups > kColCopyRowGroups) groups = kColCopyRowGroups;
-            t.copy_groups = (int32_t)groups;
-            copy += (int)(tiles_x * groups);
-            g.unit_end[g.n] = total; g.comb_end[g.n] = comb; g.copy_end[g.n] = copy;
+            copy += (int)(tiles_x * kColCopyRowGroups);          // upper bound, for the overflow check above; set in flush()
+            g.unit_end[g.n] = total; g.comb_end[g.n] = comb;
             if (++g.n == kMaxTeamGroup) flush();
         }
         flush();
