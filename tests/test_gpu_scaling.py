@@ -199,3 +199,25 @@ def test_gam_tensor_level_proof_in_a_batch_with_statistics():
         assert r["n_bf16"] == (r["P"] if frac > 0 else 0)
         s = B.read_stats(st)
         assert s["n_bf16_part"] == r["n_bf16"] and s["n_part"] == r["P"]
+
+
+def test_gam_tensor_level_full_benchmark_sizes():
+    """The full-size weight (cfg3, stays E4M3) and gradient (cfg4, BF16 proven by the pre-pass) operands with a tensor-level
+    decision over GAM-scaled 128x128 blocks and per-channel rows, all in one batch call as the benchmark issues it."""
+    dev = torch.device("cuda")
+    (_, w, _), _ = W.cfg3()
+    (_, g, _), _ = W.cfg4()
+    ops, keep = [], []
+    for xb in (w, g):
+        xd = parity.to_dev(xb)
+        for gran in ("block128", "channel_row"):
+            params = B.make_params(xb.shape[0], xb.shape[1], gran, "tensor", "mean_rel_err", 0.045, scaling="gam")
+            out = B.alloc_outputs(params, dev, want_bf16=True, bf16_fill=parity.FILL)
+            ops.append((params, xd, out, None)); keep.append((xb, gran))
+    items = B.make_batch(ops)
+    ws = torch.empty(max(16, B.mor_batch_workspace_bytes(items)), dtype=torch.uint8, device=dev)
+    B.mor_analyze_quantize_batch(items, 1e-5, ws)
+    torch.cuda.synchronize()
+    for (params, xd, out, _), (xb, gran) in zip(ops, keep):
+        r = parity.compare(xb, gran, "tensor", "mean_rel_err", 0.045, label="gam tensor-level full size", scaling="gam", gpu=(params, out))
+        assert r["n_bf16"] == (r["P"] if xb is g else 0)
