@@ -112,6 +112,7 @@ __global__ __launch_bounds__(256) void k_sub1x128_strided(const uint16_t* __rest
 constexpr int kTensorChunksPerThread = 8;                       // 16-byte chunks per thread in pass B
 constexpr int kTensorChunksPerBlock = 256 * kTensorChunksPerThread;
 constexpr int kMaxAmaxBlocks = 2048;
+constexpr int kProveMaxWg = 8192;      // workgroups of one launch (and partial records per operand) of the block-shaped GAM pre-pass
 
 __device__ __forceinline__ uint32_t block_allmax_u32(uint32_t v, uint32_t* sh4) {
     const uint32_t wv = wave_allmax_u32(v);
@@ -1276,7 +1277,7 @@ size_t item_workspace(const BatchItem& it) {
     if (it.stats && it.gran != kGranTensor) b += align16(sizeof(StatsRec) * kStatsMaxWg);
     if (it.gran != kGranTensor && it.scaling != kScaleFp32) {
         b += 16;                                                                   // group mantissa words
-        if (it.scaling == kScaleGam) b += 2 * align16(sizeof(uint32_t) * kMaxAmaxBlocks);   // amax and flush partials of the pre-pass
+        if (it.scaling == kScaleGam) b += 2 * align16(sizeof(uint32_t) * kProveMaxWg);   // amax and flush partials of the pre-pass
     }
     return b;
 }
@@ -1330,7 +1331,8 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 if (n_pv == 0) return;
                 for (int j = 0; j < n_pv; ++j) {
                     const int64_t units = scope_proof_units(items[pv_item[j]]);
-                    pv[j].n_wg = share(units, pv_units, kMaxAmaxBlocks, units);     // 0.566 ms per twelve-operand pass at 2048, 0.581 ms at 1024
+                    // twelve operands, 128x128: 0.577 ms per pass at 2048 workgroups in all, 0.564 ms at 4096 and at 8192
+                    pv[j].n_wg = share(units, pv_units, kProveMaxWg, units);
                     pv_wg[pv_item[j]] = pv[j].n_wg;
                 }
                 ProfScope ps(prof, kKernGroupAmax, st);
@@ -1341,8 +1343,8 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                 const int i = idx[k];
                 const BatchItem& it = items[i];
                 if (!scope_proof_applies(it)) continue;
-                pv_part[i] = reinterpret_cast<uint32_t*>(carve(sizeof(uint32_t) * kMaxAmaxBlocks));
-                pv_flush[i] = reinterpret_cast<uint32_t*>(carve(sizeof(uint32_t) * kMaxAmaxBlocks));
+                pv_part[i] = reinterpret_cast<uint32_t*>(carve(sizeof(uint32_t) * kProveMaxWg));
+                pv_flush[i] = reinterpret_cast<uint32_t*>(carve(sizeof(uint32_t) * kProveMaxWg));
                 pv[n_pv] = BlockProveItem{it.x, it.sh.rows, it.sh.cols, it.sh.ld, pv_part[i], pv_flush[i], 0, it.gran == kGranRow};
                 pv_units += scope_proof_units(it);
                 pv_item[n_pv] = i;
@@ -1372,7 +1374,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
                     q.flush_need = (unsigned long long)(1.01 * (double)it.th * (double)(it.sh.rows * it.sh.cols)) + 1ull;   // binary32 sums
                     continue;
                 }
-                uint32_t* part = reinterpret_cast<uint32_t*>(carve(2 * sizeof(uint32_t) * kMaxAmaxBlocks));
+                uint32_t* part = reinterpret_cast<uint32_t*>(carve(2 * sizeof(uint32_t) * kProveMaxWg));
                 q.amax_part = part;
                 if (it.sh.ld == it.sh.cols) {
                     TensorOp& t = ga.op[ga.n];
