@@ -221,3 +221,13 @@ def test_gam_tensor_level_full_benchmark_sizes():
     for (params, xd, out, _), (xb, gran) in zip(ops, keep):
         r = parity.compare(xb, gran, "tensor", "mean_rel_err", 0.045, label="gam tensor-level full size", scaling="gam", gpu=(params, out))
         assert r["n_bf16"] == (r["P"] if xb is g else 0)
+
+
+@pytest.mark.parametrize("th", [0.0, 0.01, 0.3, 0.95, 1.5])
+@pytest.mark.parametrize("gran", ["block128", "channel_row"])
+def test_gam_tensor_level_thresholds_outside_the_usual_range(th, gran):
+    """20 % flushed values: BF16 for th <= 0.2 (proven or not), E4M3 above; thresholds for which no proof is attempted
+    (0, >= 0.9) take the separate copy and give the same outputs."""
+    xb = W.f32_to_bf16_bits(_with_tiny(256, 512, 0.2, 77))
+    r = parity.compare(xb, gran, "tensor", "mean_rel_err", th, label=f"gam th={th}", scaling="gam")
+    assert r["n_bf16"] == (r["P"] if th < 0.2 else 0)
