@@ -41,10 +41,13 @@
 extern "C" {
 #endif
 
+#define MOR_MAX_LD 4194304   /* elements (2^22) */
+
 typedef enum {
     MOR_OK = 0,
     MOR_ERR_NULL = 1,        /* a required pointer is NULL */
-    MOR_ERR_SHAPE = 2,       /* rows/cols <= 0, ld < cols, or not a multiple of the block shape */
+    MOR_ERR_SHAPE = 2,       /* rows/cols <= 0, ld < cols, not a multiple of the block shape, or a leading dimension
+                                above MOR_MAX_LD for a granularity whose blocks span several rows */
     MOR_ERR_ALIGN = 3,       /* a pointer is not 16-byte aligned or a leading dimension breaks 16-byte rows */
     MOR_ERR_UNSUPPORTED = 4, /* enum value or format set this build does not implement */
     MOR_ERR_WORKSPACE = 5,   /* workspace NULL or smaller than mor_workspace_bytes() */
@@ -119,7 +122,9 @@ typedef enum {
 
 typedef struct mor_params {
     int64_t  rows, cols;  /* operand shape, elements */
-    int64_t  ld;          /* leading dimension of x in elements, >= cols, multiple of 8 */
+    int64_t  ld;          /* leading dimension of x in elements, >= cols, multiple of 8; at most MOR_MAX_LD (as every
+                             other leading dimension of the call) when blocks span several rows (128x128, 64x64, 128x1,
+                             per-channel columns): their kernels address a tile of rows with 32-bit byte offsets */
     int32_t  granularity; /* mor_granularity */
     int32_t  scope;       /* mor_scope */
     int32_t  criterion;   /* mor_criterion */

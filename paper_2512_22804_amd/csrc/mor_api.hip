@@ -68,6 +68,12 @@ static mor_status make_item(const mor_params* p, const uint16_t* x, const mor_ou
         if ((reinterpret_cast<uintptr_t>(out->fp8) & 7u) || (want_bf16 && !aligned16(out->bf16))) return MOR_ERR_ALIGN;
     }
     if (p->granularity != MOR_GRAN_TENSOR && p->rows / 128 > 65535 && p->scope == MOR_SCOPE_TENSOR) return MOR_ERR_SHAPE;
+    // kernels whose blocks span several rows address a tile of up to 128 rows with 32-bit byte offsets
+    if (p->granularity == MOR_GRAN_BLOCK_128x128 || p->granularity == MOR_GRAN_BLOCK_64x64 || p->granularity == MOR_GRAN_SUB_128x1 ||
+        p->granularity == MOR_GRAN_CHANNEL_COL) {
+        if (p->ld > MOR_MAX_LD || (fake_y ? ld_fake > MOR_MAX_LD : (out->ld_fp8 > MOR_MAX_LD || (want_bf16 && out->ld_bf16 > MOR_MAX_LD))))
+            return MOR_ERR_SHAPE;
+    }
     if ((reinterpret_cast<uintptr_t>(out->scale) | reinterpret_cast<uintptr_t>(out->amax) |
          reinterpret_cast<uintptr_t>(out->err_sum) | reinterpret_cast<uintptr_t>(out->nnz) |
          reinterpret_cast<uintptr_t>(out->amin)) & 3u) return MOR_ERR_ALIGN;

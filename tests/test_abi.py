@@ -102,6 +102,11 @@ def test_argument_validation_without_a_gpu(B):
     assert call(B.make_params(100, 256, "block64")) == 2
     assert call(B.make_params(128, 256, "channel_row", ld=128)) == 2          # ld < cols
     assert call(B.make_params(128, 256, "sub128x1", ld=260)) == 3             # ld % 8
+    big = (1 << 22) + 8                                                       # above MOR_MAX_LD
+    assert call(B.make_params(128, 256, "block128", ld=big)) == 2
+    assert call(B.make_params(128, 256, "channel_col"), ld_fp8=big) == 2
+    assert call(B.make_params(128, 256, "block64"), ld_bf16=big) == 2
+    assert call(B.make_params(128, 256, "tensor", ld=big)) == 5              # no such limit where blocks do not span rows (passes validation)
     assert call(B.make_params(128, 256, 7)) == 4
     assert call(B.make_params(128, 256, "sub1x128", formats=B.MOR_FMT_E4M3 | B.MOR_FMT_E5M2)) == 4
     assert call(B.make_params(128, 256, "tensor", scope="tensor", crit="e4m3_vs_e5m2", formats="e4m3|e5m2|bf16"),
