@@ -372,3 +372,45 @@ def test_lean_fp8_payload(P, frac):
         else:
             assert not proven and np.array_equal(fp8, a.fp8)
             assert gran != "tensor" or a.mask[0] == (1 if frac > 0 else 0)      # 4 % flushed: BF16, but not proven beforehand
+
+
+def test_operand_beyond_2_to_32_bytes(P):
+    """Maximum sizes: one operand of 34 816 x 65 536 elements (2.28 G elements, 4.6 GB of BF16), so that element indices
+    pass 2^31 and byte offsets pass 2^32 in the input, the payload and the fallback buffer; per-tensor, 128 x 128, 1 x 128
+    and per-channel rows (of 65 536 elements), every output against the oracle.  The operand is 34 row bands of one random 1024-row band, each band in its own
+    binade, a fifth of the 128 x 128 blocks carrying values that flush."""
+    from paper_2512_22804_amd import binding as B
+    from oracle import mor_oracle as O
+    rows0, cols, bands = 1024, 65536, 34
+    rng = np.random.default_rng(2512)
+    base = rng.standard_normal((rows0, cols), dtype=np.float32)
+    blk = rng.random((rows0 // 128, cols // 128)) < 0.2
+    tiny = (rng.random((rows0, cols), dtype=np.float32) < 0.3) & np.repeat(np.repeat(blk, 128, 0), 128, 1)
+    base[tiny] *= np.float32(2.0 ** -24)
+    band = W.f32_to_bf16_bits(base)
+    del base, tiny
+    xb = np.empty((rows0 * bands, cols), np.uint16)
+    for k in range(bands):
+        # band k scaled by 2^(k - 17): the exponent field moves, zeros stay zeros (no value is near the ends of the range)
+        xb[k * rows0:(k + 1) * rows0] = np.where((band & 0x7FFF) != 0, (band.astype(np.int32) + ((k - 17) << 7)).astype(np.uint16), band)
+    assert xb.size > 2 ** 31
+    xd = P.to_dev(xb)
+    for gran in ("tensor", "block128", "sub1x128", "channel_row"):
+        print(f"[parity] large operand {xb.shape} gran={gran}", flush=True)
+        params = B.make_params(xb.shape[0], cols, gran, threshold=TH)
+        out = B.alloc_outputs(params, xd.device, want_bf16=True, bf16_fill=P.FILL)
+        B.mor_analyze_quantize(params, xd, out)
+        torch.cuda.synchronize()
+        a = O.analyze_quantize(xb, gran, "partition", "mean_rel_err", TH, bf16_fill=P.FILL)
+        assert np.array_equal(out.amax.cpu().numpy().view(np.uint32), a.amax.view(np.uint32))
+        assert np.array_equal(out.scale.cpu().numpy().view(np.uint32), a.scale.view(np.uint32))
+        assert np.array_equal(out.nnz.cpu().numpy().view(np.uint32), a.nnz)
+        assert np.array_equal(out.mask.cpu().numpy(), a.mask)             # no block is near the threshold (checked below)
+        metric = a.err_sum / np.maximum(a.nnz, 1)
+        assert np.all(np.abs(metric - TH) > 1e-3 * TH)
+        assert np.allclose(out.err_sum.cpu().numpy().astype(np.float64), a.err_sum, rtol=1e-5, atol=0)
+        assert np.array_equal(out.fp8.cpu().numpy(), a.fp8), "fp8 payload differs"
+        assert np.array_equal(P.u16(out.bf16), a.bf16), "BF16 fallback differs"
+        if gran in ("block128", "sub1x128"):
+            assert 0.1 < a.mask.mean() < 0.3                              # both kinds of block occur
+        del out, a
