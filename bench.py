@@ -139,6 +139,25 @@ def run_variants(ops, B, torch, dev, steps, log):
         metas.append(meta)
         ys.append(torch.empty_like(o["x"]))
 
+    # the configuration of the paper's own experiments: fake quantization, tensor-level decision, GAM scales, 128x128 blocks
+    for gran in ("block128", "channel_row"):
+        entries, nbytes = [], 0.0
+        for o, y in zip(ops, ys):
+            pr = B.make_params(o["params"].rows, o["params"].cols, gran, "tensor", "mean_rel_err", THRESHOLD, scaling="gam")
+            meta = B.alloc_outputs(pr, dev, want_bf16=False, want_fp8=False)
+            entries.append((pr, o["x"], meta, None, y))
+            # pre-pass 2, block pass 2 + 2 (these inputs' BF16 decisions are proven by the pre-pass, so nothing is copied afterwards)
+            nbytes += 6.0 * o["n"] + META_BYTES * meta.mask.numel()
+        items = B.make_batch(entries)
+        ws = torch.empty(max(16, B.mor_batch_workspace_bytes(items)), dtype=torch.uint8, device=dev)
+        ms = timed(lambda: B.mor_analyze_quantize_batch(items, 1e-5, ws), steps)
+        rec = {"name": f"fake_gam_tensor_level_{gran}", "ms": round(ms, 4), "input_gbs": round(2.0 * n_total / ms / 1e6, 1),
+               "hbm_algorithmic_gbs": round(nbytes / ms / 1e6, 1), "hbm_frac_of_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        log(f"[bench]   variant {rec['name']:34s} {ms:8.3f} ms  {rec['input_gbs']:8.1f} GB/s in  {rec['hbm_algorithmic_gbs']:8.1f} GB/s HBM "
+            f"({100 * rec['hbm_frac_of_peak']:.1f} %)")
+        results.append(rec)
+        del entries, items, ws
+
     fake_items = B.make_batch([(o["params"], o["x"], meta, None, y) for o, meta, y in zip(ops, metas, ys)])
     fake_ws = torch.empty(max(16, B.mor_batch_workspace_bytes(fake_items)), dtype=torch.uint8, device=dev)
     ms = timed(lambda: B.mor_analyze_quantize_batch(fake_items, 1e-5, fake_ws), steps)

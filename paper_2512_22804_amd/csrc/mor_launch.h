@@ -130,7 +130,8 @@ enum { kCritEq2 = 0, kCritEq3 = 1 };
 // Algorithm 1 can prove the BF16 decision under Eq. 2 from elements that are certain to flush inside their block, so
 // the block kernel writes the BF16 payload from its registers and the operand is not read a third time.
 inline bool scope_proof_applies(const BatchItem& it) {
-    if (it.scaling != 1 || it.scope != 1 || it.crit != kCritEq2 || it.three || it.o.bf16 == nullptr || it.o.fake != nullptr) return false;
+    // (fake quantization: o.bf16 == o.fake, and a proven operand's output is its input)
+    if (it.scaling != 1 || it.scope != 1 || it.crit != kCritEq2 || it.three || it.o.bf16 == nullptr) return false;
     if (!(it.th > 0.0f && it.th < 0.9f)) return false;      // the flush count is compared with 1.01 * th * N + 1
     if (it.gran == kGranBlock) return it.sh.rows % 128 == 0 && it.sh.cols % 128 == 0;
     return it.gran == kGranRow;

@@ -229,7 +229,9 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
             for (int i = 0; i < NCH; ++i) {
                 u32x4 deq;
                 const u32x2 codes = quant8_fast_deq<E5, FAKE>(raw[i], sc_, s_inv, e0, e1, deq);
-                if constexpr (BUF) {
+                // (fake quantization always stores through the buffer window: `emit` is a run-time value there, and a
+                // branch around the stores would split the sweep into basic blocks and cost > 100 registers)
+                if constexpr (BUF || FAKE) {
                     const bool put = emit && is_valid(i);
                     if constexpr (FAKE) buf_store16(rf, put ? offf + i * stepf : kBufOutside, deq);
                     else buf_store8(r8, put ? off8 : kBufOutside, i * step8, codes);
@@ -248,6 +250,10 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
         }
         return e0 + e1;
     };
+    // tensor-level decision already proven by the pre-pass (uniform): the BF16 payload is stored below; a fake-quantized
+    // output of such an operand is its input, so the de-quantized values are not stored at all
+    bool proven = false;
+    if (t.prove) proven = t.gam[2] != 0u;
     float err, err5 = 0.0f;
     if (CRIT == kCritEq3 && fast && s5 == 128.0f * s) {
         // both formats in one sweep, one reciprocal per element (see quant8_dual)
@@ -269,7 +275,7 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
         err = e0 + e1;
         err5 = f0 + f1;
     } else {
-        err = quantize(std::false_type{}, s, true);
+        err = quantize(std::false_type{}, s, !(FAKE && proven));
         if constexpr (CRIT == kCritEq3) err5 = quantize(std::true_type{}, s5, false);
     }
     uint32_t zeros = fold_add16(sc.zero2);
@@ -307,8 +313,7 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
         if (mode != kScaleFp32 && o.e8m0) o.e8m0[p] = (uint8_t)(__float_as_uint(s) >> 23);
         if (t.three && o.amin) o.amin[p] = __uint_as_float(amin_bits << 16);
     }
-    bool keep = mask == 1u;
-    if (t.prove) keep = t.gam[2] != 0u;                    // deferred decision, proven by the pre-pass (uniform)
+    const bool keep = mask == 1u || proven;                // (a deferred decision has mask 0 here)
     if (keep && o.bf16) {                                  // BF16: the block stays as it is
         uint16_t* __restrict__ dbf = o.bf16 + (r0 + trow) * o.ld_bf16 + c0 + tcol;
         const int64_t dbf_step = (int64_t)rstep * o.ld_bf16 + cstep;

@@ -145,6 +145,9 @@ def test_gam_tensor_level_decision_proven_by_the_pre_pass(frac, pad, gran, shape
     xb[:, :cols] = W.f32_to_bf16_bits(x)
     r = parity.compare(xb, gran, "tensor", "mean_rel_err", 0.045, cols=cols, label=f"gam proof frac={frac}", scaling="gam")
     assert r["n_bf16"] == (r["P"] if frac > 0 else 0)
+    # fake quantization of the same operand: a proven BF16 tensor passes through without its de-quantized values being stored
+    f = parity.compare_fake(xb, gran, "tensor", "mean_rel_err", 0.045, cols=cols, label=f"gam proof fake frac={frac}", scaling="gam")
+    assert f["n_bf16"] == r["n_bf16"] and f["n_mismatch"] == 0
 
 
 def test_gam_tensor_level_proof_uses_each_rows_own_amax():
@@ -168,6 +171,7 @@ def test_gam_tensor_level_proof_uses_each_blocks_own_amax():
     xb = W.f32_to_bf16_bits(x)
     r = parity.compare(xb, "block128", "tensor", "mean_rel_err", 0.045, label="gam proof per block", scaling="gam")
     assert r["n_bf16"] == 0
+    assert parity.compare_fake(xb, "block128", "tensor", "mean_rel_err", 0.045, label="gam proof per block, fake", scaling="gam")["n_bf16"] == 0
     # the same operand once its flushes are frequent enough in every block
     x2 = _with_tiny(rows, cols, 0.3, 9, tiny_exp=-30)
     x2[128:, :] *= np.float32(2.0 ** -20)
