@@ -235,3 +235,50 @@ def test_gam_tensor_level_thresholds_outside_the_usual_range(th, gran):
     xb = W.f32_to_bf16_bits(_with_tiny(256, 512, 0.2, 77))
     r = parity.compare(xb, gran, "tensor", "mean_rel_err", th, label=f"gam th={th}", scaling="gam")
     assert r["n_bf16"] == (r["P"] if th < 0.2 else 0)
+
+
+def test_gam_tensor_level_proof_with_a_dirty_workspace_and_in_a_graph():
+    """Nothing may depend on what the workspace held before (partials, the 'proven' word): the batch of provable and
+    unprovable operands is run on a workspace filled with 0xFF, then captured in a HIP graph and replayed three times with
+    the workspace and the outputs scrubbed in between; every run gives the outputs of the first, which equal the oracle's."""
+    dev = torch.device("cuda")
+    specs = [(512, 1024, 0.2, "block128"), (256, 384, 0.0, "block128"), (384, 512, 0.04, "block128"),
+             (33, 4096, 0.2, "channel_row"), (50, 512, 0.0, "channel_row")]
+    ops, keep = [], []
+    for k, (rows, cols, frac, gran) in enumerate(specs):
+        xb = W.f32_to_bf16_bits(_with_tiny(rows, cols, frac, 60 + k))
+        params = B.make_params(rows, cols, gran, "tensor", "mean_rel_err", 0.045, scaling="gam")
+        out = B.alloc_outputs(params, dev, want_bf16=True, bf16_fill=parity.FILL)
+        ops.append((params, parity.to_dev(xb), out, None)); keep.append(xb)
+    items = B.make_batch(ops)
+    ws = torch.empty(max(16, B.mor_batch_workspace_bytes(items)), dtype=torch.uint8, device=dev)
+    fields = ("fp8", "bf16", "scale", "amax", "nnz", "mask", "err_sum", "scale_e8m0", "group_mantissa")
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [[getattr(o, f).clone() for f in fields] for _, _, o, _ in ops]
+
+    def scrub():
+        ws.fill_(0xFF)
+        for _, _, o, _ in ops:
+            o.fp8.zero_(); o.mask.fill_(9); o.err_sum.fill_(-1.0)
+            o.bf16.fill_(parity.FILL if parity.FILL < 0x8000 else parity.FILL - 0x10000)
+
+    scrub()
+    B.mor_analyze_quantize_batch(items, 1e-5, ws)
+    want = snapshot()
+    for (params, xd, out, _), xb, (rows, cols, frac, gran) in zip(ops, keep, specs):
+        r = parity.compare(xb, gran, "tensor", "mean_rel_err", 0.045, label="gam proof dirty workspace", scaling="gam", gpu=(params, out))
+        assert r["n_bf16"] == (r["P"] if frac > 0 else 0)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.mor_analyze_quantize_batch(items, 1e-5, ws)
+    for _ in range(3):
+        scrub()
+        graph.replay()
+        for a, b in zip(want, snapshot()):
+            for ta, tb in zip(a, b):
+                assert torch.equal(ta.view(torch.uint8), tb.view(torch.uint8))
+        scrub()
+        B.mor_analyze_quantize_batch(items, 1e-5, ws)       # eager work between the replays
+        torch.cuda.synchronize()
