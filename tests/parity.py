@@ -46,6 +46,8 @@ def run_gpu(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "me
     params = B.make_params(rows, cols, gran, scope, crit, threshold, ld=ld, scaling=scaling, formats=formats, ragged=ragged)
     x = to_dev(xb)
     out = B.alloc_outputs(params, x.device, want_bf16=want_bf16, bf16_fill=FILL)
+    if out.workspace is not None:
+        out.workspace.fill_(0xFF)          # nothing may depend on what the workspace held before
     B.mor_analyze_quantize(params, x, out)
     torch.cuda.synchronize()
     return params, out
@@ -155,6 +157,8 @@ def compare_fake(xb: np.ndarray, gran: str, scope: str = "partition", crit: str 
     params = B.make_params(rows, cols, gran, scope, crit, threshold, ld=ld, scaling=scaling, formats=formats, ragged=ragged)
     x = to_dev(xb)
     meta = B.alloc_outputs(params, x.device, want_bf16=False, want_fp8=False)
+    if meta.workspace is not None:
+        meta.workspace.fill_(0xFF)
     y = torch.full((rows, cols), FILL if FILL < 0x8000 else FILL - 0x10000, dtype=torch.int16, device=x.device)
     B.mor_fake_quantize(params, x, y, meta)
     torch.cuda.synchronize()
