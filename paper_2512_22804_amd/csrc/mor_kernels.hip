@@ -1296,388 +1296,425 @@ size_t batch_workspace_bytes(const BatchItem* items, int n) {
     return b;
 }
 
-hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws, size_t ws_bytes, hipStream_t st, KProf* prof) {
-    static_assert(sizeof(GroupSub) <= 3800 && sizeof(GroupTensor) + sizeof(GroupStats) <= 3800 &&
-                  sizeof(GroupGam) <= 3800 && sizeof(GroupScope) <= 3800, "kernel-argument segment is 4 KB");
-    static_assert(sizeof(StatsRec) == 128, "StatsRec layout");
-    char* wsp = static_cast<char*>(ws);
+namespace {
+// One batch call: the launches of every phase, in stream order.  The phases share the workspace cursor, the routes, the
+// group-mantissa words of Algorithm 1 and the statistics groups, which is all this object holds.
+constexpr int kMaxStatsGroups = (kBatchMax + kMaxGroupStats - 1) / kMaxGroupStats;
+struct BatchRun {
+    const BatchItem* items;
+    int n;
+    float near_tol;
+    hipStream_t st;
+    KProf* prof;
+    char* wsp;
     size_t ws_off = 0;
-    auto carve = [&](size_t bytes) -> char* { char* p = wsp + ws_off; ws_off += align16(bytes); return p; };
-    (void)ws_bytes;
     hipError_t err = hipSuccess;
     Route route[kBatchMax];
-    for (int i = 0; i < n; ++i) route[i] = route_of(items[i]);
+    const uint32_t* gam_of[kBatchMax] = {};      // per operand: {mantissa for E4M3, for E5M2, "BF16 proven" flag}
+    GroupStats stats_groups[kMaxStatsGroups];
+    int n_stats_groups = 0;
+    bool riders_used = false;                    // the first statistics group went along with a per-tensor launch
 
-    // ---- Algorithm 1, group loop: operands with sub-tensor blocks and GAM / E8M0 scaling get their group
-    //      mantissas first (GAM: one more read of the operand for its amax)
-    const uint32_t* gam_of[kBatchMax] = {};
-    {
-        int idx[kBatchMax];
-        int cnt = 0;
-        for (int i = 0; i < n; ++i)
-            if (items[i].gran != kGranTensor && items[i].scaling != kScaleFp32) idx[cnt++] = i;
-        // operands whose tensor-level decision the pre-pass may prove: block-shaped pre-pass (group amax and, per block,
-        // the elements that are certain to flush), as many operands per launch as its argument table holds
-        uint32_t* pv_part[kBatchMax] = {};
-        uint32_t* pv_flush[kBatchMax] = {};
-        int pv_wg[kBatchMax] = {};
-        {
-            constexpr int kProveGroup = 12;
-            BlockProveItem pv[kProveGroup];
-            int pv_item[kProveGroup];
-            int n_pv = 0;
-            int64_t pv_units = 0;
-            auto flush = [&]() {
-                if (n_pv == 0) return;
-                for (int j = 0; j < n_pv; ++j) {
-                    const int64_t units = scope_proof_units(items[pv_item[j]]);
-                    // twelve operands, 128x128: 0.577 ms per pass at 2048 workgroups in all, 0.564 ms at 4096 and at 8192
-                    pv[j].n_wg = share(units, pv_units, kProveMaxWg, units);
-                    pv_wg[pv_item[j]] = pv[j].n_wg;
-                }
-                ProfScope ps(prof, kKernGroupAmax, st);
-                err = launch_block_amax_prove(pv, n_pv, st);
-                n_pv = 0; pv_units = 0;
-            };
-            for (int k = 0; k < cnt && err == hipSuccess; ++k) {
-                const int i = idx[k];
-                const BatchItem& it = items[i];
-                if (!scope_proof_applies(it)) continue;
-                pv_part[i] = reinterpret_cast<uint32_t*>(carve(sizeof(uint32_t) * kProveMaxWg));
-                pv_flush[i] = reinterpret_cast<uint32_t*>(carve(sizeof(uint32_t) * kProveMaxWg));
-                pv[n_pv] = BlockProveItem{it.x, it.sh.rows, it.sh.cols, it.sh.ld, pv_part[i], pv_flush[i], 0, it.gran == kGranRow};
-                pv_units += scope_proof_units(it);
-                pv_item[n_pv] = i;
-                if (++n_pv == kProveGroup) flush();
-            }
-            flush();
-        }
-        for (int base = 0; base < cnt; base += kMaxGroupTensor) {
-            const int m = cnt - base < kMaxGroupTensor ? cnt - base : kMaxGroupTensor;
-            GroupGam gg; gg.n = m;
-            GroupTensor ga; ga.n = 0; ga.near_tol = near_tol;
-            int slot_of[kMaxGroupTensor];
-            int64_t total_tiles = 0;
-            for (int k = 0; k < m; ++k) {
-                const int i = idx[base + k];
-                const BatchItem& it = items[i];
-                uint32_t* gam = reinterpret_cast<uint32_t*>(carve(16));
-                gam_of[i] = gam;
-                GamOp& q = gg.op[k];
-                q.amax_part = nullptr; q.n_amax = 0; q.mode = (uint32_t)it.scaling; q.gam = gam; q.gmant = it.o.gmant;
-                q.flush_part = nullptr; q.flush_need = 0ull;
-                slot_of[k] = -1;
-                if (it.scaling != kScaleGam) continue;
-                if (pv_part[i]) {
-                    q.amax_part = pv_part[i]; q.n_amax = pv_wg[i];
-                    q.flush_part = pv_flush[i];
-                    q.flush_need = (unsigned long long)(1.01 * (double)it.th * (double)(it.sh.rows * it.sh.cols)) + 1ull;   // binary32 sums
-                    continue;
-                }
-                uint32_t* part = reinterpret_cast<uint32_t*>(carve(2 * sizeof(uint32_t) * kProveMaxWg));
-                q.amax_part = part;
-                if (it.sh.ld == it.sh.cols) {
-                    TensorOp& t = ga.op[ga.n];
-                    t = TensorOp{};
-                    t.x = it.x;
-                    t.n_chunks = it.sh.rows * it.sh.cols / 8;
-                    t.n_tiles = (t.n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
-                    t.amax_part = part;
-                    total_tiles += t.n_tiles;
-                    slot_of[k] = ga.n++;
-                } else {
-                    q.n_amax = (int)(it.sh.rows < kMaxAmaxBlocks ? it.sh.rows : kMaxAmaxBlocks);
-                    ProfScope ps(prof, kKernGroupAmax, st);
-                    k_tensor_amax_strided<<<dim3(q.n_amax), dim3(256), 0, st>>>(it.x, it.sh, part, 0u);
-                }
-            }
-            int a_end = 0;
-            for (int j = 0; j < ga.n; ++j) {
-                TensorOp& t = ga.op[j];
-                t.n_amax = share(t.n_tiles, total_tiles, kMaxAmaxBlocks, t.n_tiles);
-                a_end += t.n_amax;
-                ga.amax_end[j] = a_end;
-            }
-            for (int k = 0; k < m; ++k)
-                if (slot_of[k] >= 0) gg.op[k].n_amax = ga.op[slot_of[k]].n_amax;
-            if (ga.n) {
-                GroupStats none; none.n = 0; none.near_tol = near_tol;
-                ProfScope ps(prof, kKernGroupAmax, st);
-                k_tensor_amax_group<<<dim3(a_end), dim3(256), kResidency3, st>>>(ga, none, a_end);
-            }
-            { ProfScope ps(prof, kKernGroupMantissa, st); k_gam_prepare<<<dim3(m), dim3(256), 0, st>>>(gg); }
-        }
-    }
+    char* carve(size_t bytes) { char* p = wsp + ws_off; ws_off += align16(bytes); return p; }
+    void group_mantissas();
+    void sub_tensor_operands(int crit);
+    void tensor_level_decisions();
+    void collect_statistics();
+    void per_tensor_operands(int crit);
+    void leftover_statistics();
+};
 
-    for (int crit = 0; crit < 2 && err == hipSuccess; ++crit) {
-        // ---- small flat 1x128 operands ride on the first 128x128 team launch of the same criterion and output kind
-        // (extra workgroups of that launch) instead of paying the ramp and tail of a launch of their own
-        TeamRiders riders;
-        riders.table.n = 0; riders.blocks = 0; riders.fake = false; riders.used = false;
-        int64_t rider_units = 0;
-        bool team_has[2] = {false, false};
-        for (int i = 0; i < n; ++i)
-            if (route[i] == kRouteTeam && items[i].crit == crit && team_kind_of(items[i]) == 0) team_has[items[i].o.fake ? 1 : 0] = true;
-        // ---- 1x128 sub-channel operands, persistent grouped kernel (FP8 payload, then fake quantization)
-        for (int fake = 0; fake < 2 && err == hipSuccess; ++fake) {
-            GroupSub g; g.n = 0;
-            int64_t total = 0;
-            auto flush = [&]() {
-                if (g.n == 0) return;
-                int64_t blocks = (total + 3) / 4;
-                if (blocks > kSubFlatMaxBlocks) blocks = kSubFlatMaxBlocks;
-                ProfScope ps(prof, kKernSub1x128, st);
-                if (fake) {
-                    if (crit == kCritEq3) k_sub1x128_group<kCritEq3, true><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(g);
-                    else k_sub1x128_group<kCritEq2, true><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(g);
-                } else {
-                    if (crit == kCritEq3) k_sub1x128_group<kCritEq3, false><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(g);
-                    else k_sub1x128_group<kCritEq2, false><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(g);
-                }
-                g.n = 0; total = 0;
-            };
-            for (int i = 0; i < n; ++i) {
-                const BatchItem& it = items[i];
-                if (route[i] != kRouteSubFlat || it.crit != crit || (it.o.fake != nullptr) != (fake != 0)) continue;
-                const int64_t n_part = item_parts(it), n_units = n_part / 32, n_full = n_units * 32, n_tail = n_part - n_full;
-                if (n_units > 0 && n_units <= kSubRiderMaxUnits && team_has[fake] && riders.table.n < kMaxSubRiders &&
-                    (riders.table.n == 0 || riders.fake == (fake != 0))) {
-                    SubRiders& r = riders.table;
-                    rider_units += n_units;
-                    r.unit_end[r.n] = rider_units; r.x[r.n] = it.x; r.o[r.n] = it.o; r.th[r.n] = it.th; r.defer[r.n] = it.scope == 1;
-                    r.mode[r.n] = (uint8_t)it.scaling; r.gam[r.n] = gam_of[i];
-                    ++r.n;
-                    riders.fake = fake != 0;
-                    riders.blocks = (rider_units + 3) / 4 < kSubFlatMaxBlocks ? (rider_units + 3) / 4 : kSubFlatMaxBlocks;
-                } else if (n_units > 0) {
-                    total += n_units;
-                    g.unit_end[g.n] = total; g.x[g.n] = it.x; g.o[g.n] = it.o; g.th[g.n] = it.th; g.defer[g.n] = it.scope == 1;
-                    g.mode[g.n] = (uint8_t)it.scaling; g.gam[g.n] = gam_of[i];
-                    if (++g.n == kMaxGroupSub) flush();
-                }
-                if (n_tail > 0) {     // fewer than 32 blocks left: the general kernel takes them
-                    KShape ts{n_tail, 128, 128};
-                    KOut to = it.o;
-                    if (to.fp8) to.fp8 += n_full * 128;
-                    to.ld_fp8 = 128;
-                    if (to.fake) { to.fake += n_full * 128; to.ld_fake = 128; }
-                    if (to.bf16) to.bf16 += n_full * 128;
-                    to.ld_bf16 = 128;
-                    to.scale += n_full; to.amax += n_full; to.err_sum += n_full; to.nnz += n_full; to.mask += n_full;
-                    if (to.err5_sum) to.err5_sum += n_full;
-                    if (to.e8m0) to.e8m0 += n_full;
-                    err = launch_sub1x128(it.x + n_full * 128, ts, to, crit, it.scope == 1, it.th, (uint32_t)it.scaling, gam_of[i], 0u, st, nullptr);
-                }
-            }
-            flush();
-        }
-        // ---- 1x128 sub-channel operands, general kernel
-        for (int i = 0; i < n && err == hipSuccess; ++i) {
-            const BatchItem& it = items[i];
-            if (route[i] != kRouteSubGeneral || it.crit != crit) continue;
-            err = launch_sub1x128(it.x, it.sh, it.o, crit, it.scope == 1, it.th, (uint32_t)it.scaling, gam_of[i], (uint32_t)it.three, st, prof);
-        }
-        // ---- team kernels: 128x128 and 64x64 blocks, per-channel rows
-        for (int kind = 0; kind < kTeamKinds && err == hipSuccess; ++kind) {
-            int idx[kBatchMax];
-            int cnt = 0;
-            for (int i = 0; i < n; ++i)
-                if (route[i] == kRouteTeam && items[i].crit == crit && team_kind_of(items[i]) == kind) idx[cnt++] = i;
-            if (cnt) err = launch_team_items(items, idx, cnt, kind, crit, gam_of, &riders, st, prof);
-        }
-        if (err == hipSuccess && riders.table.n > 0 && !riders.used) {      // no team launch took them: a launch of their own
-            GroupSub g; g.n = riders.table.n;
-            for (int k = 0; k < g.n; ++k) {
-                const SubRiders& r = riders.table;
-                g.unit_end[k] = r.unit_end[k]; g.x[k] = r.x[k]; g.o[k] = r.o[k]; g.th[k] = r.th[k]; g.defer[k] = r.defer[k];
-                g.mode[k] = r.mode[k]; g.gam[k] = r.gam[k];
-            }
-            ProfScope ps(prof, kKernSub1x128, st);
-            const dim3 grid((unsigned)riders.blocks);
-            if (riders.fake) {
-                if (crit == kCritEq3) k_sub1x128_group<kCritEq3, true><<<grid, dim3(256), 0, st>>>(g);
-                else k_sub1x128_group<kCritEq2, true><<<grid, dim3(256), 0, st>>>(g);
-            } else {
-                if (crit == kCritEq3) k_sub1x128_group<kCritEq3, false><<<grid, dim3(256), 0, st>>>(g);
-                else k_sub1x128_group<kCritEq2, false><<<grid, dim3(256), 0, st>>>(g);
-            }
-            riders.used = true;
-        }
-        // ---- 128x1 sub-columns
-        if (err == hipSuccess) {
-            int idx[kBatchMax];
-            int cnt = 0;
-            for (int i = 0; i < n; ++i)
-                if (route[i] == kRouteSubCol && items[i].crit == crit) idx[cnt++] = i;
-            if (cnt) err = launch_subcol_items(items, idx, cnt, crit, gam_of, st, prof);
-        }
-        // ---- per-channel columns
-        if (err == hipSuccess) {
-            int idx[kBatchMax];
-            char* ws_of[kBatchMax];
-            int cnt = 0;
-            for (int i = 0; i < n; ++i)
-                if (route[i] == kRouteChannelCol && items[i].crit == crit) {
-                    ws_of[cnt] = carve(column_workspace_bytes(items[i].sh.rows, items[i].sh.cols));
-                    idx[cnt++] = i;
-                }
-            if (cnt) err = launch_channel_col_items(items, idx, cnt, crit, gam_of, ws_of, st, prof);
-        }
-    }
-    // ---- tensor-level decision (Section 3.1) over the per-block sums the block kernels left behind
+// ---- Algorithm 1, group loop: operands with sub-tensor blocks and GAM / E8M0 scaling get their group
+//      mantissas first (GAM: one more read of the operand for its amax)
+void BatchRun::group_mantissas() {
+    int idx[kBatchMax];
+    int cnt = 0;
+    for (int i = 0; i < n; ++i)
+        if (items[i].gran != kGranTensor && items[i].scaling != kScaleFp32) idx[cnt++] = i;
+    // operands whose tensor-level decision the pre-pass may prove: block-shaped pre-pass (group amax and, per block,
+    // the elements that are certain to flush), as many operands per launch as its argument table holds
+    uint32_t* pv_part[kBatchMax] = {};
+    uint32_t* pv_flush[kBatchMax] = {};
+    int pv_wg[kBatchMax] = {};
     {
-        GroupScope g; g.n = 0;
-        int red = 0, copy = 0;
+        constexpr int kProveGroup = 12;
+        BlockProveItem pv[kProveGroup];
+        int pv_item[kProveGroup];
+        int n_pv = 0;
+        int64_t pv_units = 0;
         auto flush = [&]() {
-            if (g.n == 0) return;
-            { ProfScope ps(prof, kKernScopeReduce, st); k_scope_reduce_group<<<dim3(red), dim3(256), 0, st>>>(g); }
-            { ProfScope ps(prof, kKernScopeDecide, st); k_scope_decide_group<<<dim3(red), dim3(256), 0, st>>>(g); }
-            { ProfScope ps(prof, kKernFallbackCopy, st); k_scope_copy_group<<<dim3(copy), dim3(256), 0, st>>>(g); }
-            g.n = 0; red = 0; copy = 0;
+            if (n_pv == 0) return;
+            for (int j = 0; j < n_pv; ++j) {
+                const int64_t units = scope_proof_units(items[pv_item[j]]);
+                // twelve operands, 128x128: 0.577 ms per pass at 2048 workgroups in all, 0.564 ms at 4096 and at 8192
+                pv[j].n_wg = share(units, pv_units, kProveMaxWg, units);
+                pv_wg[pv_item[j]] = pv[j].n_wg;
+            }
+            ProfScope ps(prof, kKernGroupAmax, st);
+            err = launch_block_amax_prove(pv, n_pv, st);
+            n_pv = 0; pv_units = 0;
         };
-        int64_t total_elems = 0;
-        for (int i = 0; i < n; ++i)
-            if (items[i].gran != kGranTensor && items[i].scope == 1) total_elems += items[i].sh.rows * items[i].sh.cols;
-        for (int i = 0; i < n; ++i) {
+        for (int k = 0; k < cnt && err == hipSuccess; ++k) {
+            const int i = idx[k];
             const BatchItem& it = items[i];
-            if (it.gran == kGranTensor || it.scope != 1) continue;
-            ScopeOp& t = g.op[g.n];
-            char* w = carve(scope_workspace_bytes(0));
-            t.err_sum = it.o.err_sum; t.err5_sum = it.o.err5_sum; t.nnz = it.o.nnz; t.mask = it.o.mask;
-            t.n_part = item_parts(it);
-            t.part_err = reinterpret_cast<double*>(w); t.part_err5 = t.part_err + kScopeBlocks;
-            t.part_nnz = reinterpret_cast<unsigned long long*>(w) + 2 * kScopeBlocks;
-            t.decision = reinterpret_cast<uint32_t*>(w + 3 * sizeof(double) * kScopeBlocks);
-            t.th = it.th; t.crit = it.crit;
-            t.proven = scope_proof_applies(it) ? gam_of[i] + 2 : nullptr;
-            int64_t want = (t.n_part + 1023) / 1024;
-            t.n_red = (int)(want < 1 ? 1 : (want > kScopeBlocks ? kScopeBlocks : want));
-            t.x = it.x; t.bf16 = it.o.bf16;
-            t.rows = it.sh.rows; t.cols = it.sh.cols; t.ld = it.sh.ld; t.ld_bf16 = it.o.ld_bf16;
-            red += t.n_red;
-            copy += it.o.bf16 ? share(it.sh.rows * it.sh.cols, total_elems, 4096, 4096) : 1;
-            g.red_end[g.n] = red; g.copy_end[g.n] = copy;
-            if (++g.n == kMaxGroupScope) flush();
+            if (!scope_proof_applies(it)) continue;
+            pv_part[i] = reinterpret_cast<uint32_t*>(carve(sizeof(uint32_t) * kProveMaxWg));
+            pv_flush[i] = reinterpret_cast<uint32_t*>(carve(sizeof(uint32_t) * kProveMaxWg));
+            pv[n_pv] = BlockProveItem{it.x, it.sh.rows, it.sh.cols, it.sh.ld, pv_part[i], pv_flush[i], 0, it.gran == kGranRow};
+            pv_units += scope_proof_units(it);
+            pv_item[n_pv] = i;
+            if (++n_pv == kProveGroup) flush();
         }
         flush();
     }
-    // ---- statistics of the operands with sub-tensor blocks: their kernels (and tensor-level decisions) are done, so the
-    //      first group can ride on the first per-tensor launches: partial records in the shadow of pass A, the combine
-    //      step next to the finish pass.  Groups that find no such launch run on their own at the end.
-    constexpr int kMaxStatsGroups = (kBatchMax + kMaxGroupStats - 1) / kMaxGroupStats;
-    GroupStats stats_groups[kMaxStatsGroups];
-    int n_stats_groups = 0;
-    bool riders_used = false;
-    {
-        GroupStats* g = nullptr;
+    for (int base = 0; base < cnt; base += kMaxGroupTensor) {
+        const int m = cnt - base < kMaxGroupTensor ? cnt - base : kMaxGroupTensor;
+        GroupGam gg; gg.n = m;
+        GroupTensor ga; ga.n = 0; ga.near_tol = near_tol;
+        int slot_of[kMaxGroupTensor];
+        int64_t total_tiles = 0;
+        for (int k = 0; k < m; ++k) {
+            const int i = idx[base + k];
+            const BatchItem& it = items[i];
+            uint32_t* gam = reinterpret_cast<uint32_t*>(carve(16));
+            gam_of[i] = gam;
+            GamOp& q = gg.op[k];
+            q.amax_part = nullptr; q.n_amax = 0; q.mode = (uint32_t)it.scaling; q.gam = gam; q.gmant = it.o.gmant;
+            q.flush_part = nullptr; q.flush_need = 0ull;
+            slot_of[k] = -1;
+            if (it.scaling != kScaleGam) continue;
+            if (pv_part[i]) {
+                q.amax_part = pv_part[i]; q.n_amax = pv_wg[i];
+                q.flush_part = pv_flush[i];
+                q.flush_need = (unsigned long long)(1.01 * (double)it.th * (double)(it.sh.rows * it.sh.cols)) + 1ull;   // binary32 sums
+                continue;
+            }
+            uint32_t* part = reinterpret_cast<uint32_t*>(carve(2 * sizeof(uint32_t) * kProveMaxWg));
+            q.amax_part = part;
+            if (it.sh.ld == it.sh.cols) {
+                TensorOp& t = ga.op[ga.n];
+                t = TensorOp{};
+                t.x = it.x;
+                t.n_chunks = it.sh.rows * it.sh.cols / 8;
+                t.n_tiles = (t.n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
+                t.amax_part = part;
+                total_tiles += t.n_tiles;
+                slot_of[k] = ga.n++;
+            } else {
+                q.n_amax = (int)(it.sh.rows < kMaxAmaxBlocks ? it.sh.rows : kMaxAmaxBlocks);
+                ProfScope ps(prof, kKernGroupAmax, st);
+                k_tensor_amax_strided<<<dim3(q.n_amax), dim3(256), 0, st>>>(it.x, it.sh, part, 0u);
+            }
+        }
+        int a_end = 0;
+        for (int j = 0; j < ga.n; ++j) {
+            TensorOp& t = ga.op[j];
+            t.n_amax = share(t.n_tiles, total_tiles, kMaxAmaxBlocks, t.n_tiles);
+            a_end += t.n_amax;
+            ga.amax_end[j] = a_end;
+        }
+        for (int k = 0; k < m; ++k)
+            if (slot_of[k] >= 0) gg.op[k].n_amax = ga.op[slot_of[k]].n_amax;
+        if (ga.n) {
+            GroupStats none; none.n = 0; none.near_tol = near_tol;
+            ProfScope ps(prof, kKernGroupAmax, st);
+            k_tensor_amax_group<<<dim3(a_end), dim3(256), kResidency3, st>>>(ga, none, a_end);
+        }
+        { ProfScope ps(prof, kKernGroupMantissa, st); k_gam_prepare<<<dim3(m), dim3(256), 0, st>>>(gg); }
+    }
+}
+
+// ---- operands with sub-tensor blocks of one criterion
+void BatchRun::sub_tensor_operands(int crit) {
+    // ---- small flat 1x128 operands ride on the first 128x128 team launch of the same criterion and output kind
+    // (extra workgroups of that launch) instead of paying the ramp and tail of a launch of their own
+    TeamRiders riders;
+    riders.table.n = 0; riders.blocks = 0; riders.fake = false; riders.used = false;
+    int64_t rider_units = 0;
+    bool team_has[2] = {false, false};
+    for (int i = 0; i < n; ++i)
+        if (route[i] == kRouteTeam && items[i].crit == crit && team_kind_of(items[i]) == 0) team_has[items[i].o.fake ? 1 : 0] = true;
+    // ---- 1x128 sub-channel operands, persistent grouped kernel (FP8 payload, then fake quantization)
+    for (int fake = 0; fake < 2 && err == hipSuccess; ++fake) {
+        GroupSub g; g.n = 0;
+        int64_t total = 0;
+        auto flush = [&]() {
+            if (g.n == 0) return;
+            int64_t blocks = (total + 3) / 4;
+            if (blocks > kSubFlatMaxBlocks) blocks = kSubFlatMaxBlocks;
+            ProfScope ps(prof, kKernSub1x128, st);
+            if (fake) {
+                if (crit == kCritEq3) k_sub1x128_group<kCritEq3, true><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(g);
+                else k_sub1x128_group<kCritEq2, true><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(g);
+            } else {
+                if (crit == kCritEq3) k_sub1x128_group<kCritEq3, false><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(g);
+                else k_sub1x128_group<kCritEq2, false><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(g);
+            }
+            g.n = 0; total = 0;
+        };
         for (int i = 0; i < n; ++i) {
             const BatchItem& it = items[i];
-            if (!it.stats || it.gran == kGranTensor) continue;
-            if (!g || g->n == kMaxGroupStats) { g = &stats_groups[n_stats_groups++]; g->n = 0; g->near_tol = near_tol; }
-            StatsOp& t = g->op[g->n];
-            t.err_sum = it.o.err_sum; t.nnz = it.o.nnz; t.mask = it.o.mask;
-            t.geom = make_geom(it.gran, it.sh.rows, it.sh.cols);
-            t.n_part = geom_parts(t.geom);
-            t.th = it.th;
-            t.rec = reinterpret_cast<StatsRec*>(carve(sizeof(StatsRec) * kStatsMaxWg));
-            t.out = static_cast<StatsDev*>(it.stats);
-            g->wg_end[g->n] = (g->n ? g->wg_end[g->n - 1] : 0) + stats_wgs(t.n_part);
-            ++g->n;
-        }
-    }
-    for (int crit = 0; crit < 2 && err == hipSuccess; ++crit) {
-        // ---- per-tensor operands: amax pass, quantize pass, finish (+ fallback copy) pass; FP8 payload and fake
-        //      quantization are different kernels
-        for (int fake = 0; fake < 2 && err == hipSuccess; ++fake) {
-            int idx[kMaxGroupTensor];
-            int cnt = 0;
-            auto flush = [&]() {
-                if (cnt == 0) return;
-                GroupTensor g; g.n = cnt; g.near_tol = near_tol;
-                int64_t total_tiles = 0;
-                for (int k = 0; k < cnt; ++k) {
-                    const BatchItem& it = items[idx[k]];
-                    const int64_t n_chunks = it.sh.rows * it.sh.cols / 8;
-                    total_tiles += (n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
-                }
-                int a_end = 0, s_end = 0, c_end = 0;
-                for (int k = 0; k < cnt; ++k) {
-                    const BatchItem& it = items[idx[k]];
-                    TensorOp& t = g.op[k];
-                    t.x = it.x; t.o = it.o; t.th = it.th; t.mode = (uint32_t)it.scaling; t.three = it.three ? 1u : 0u; t.lean = it.lean ? 1u : 0u;
-                    t.n_chunks = it.sh.rows * it.sh.cols / 8;
-                    t.n_tiles = (t.n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
-                    t.n_amax = share(t.n_tiles, total_tiles, kMaxAmaxBlocks, t.n_tiles);
-                    t.n_slots = share(t.n_tiles, total_tiles, kMaxQuantBlocks, t.n_tiles);
-                    const TensorPlan pl = plan_tensor(it.sh.rows, it.sh.cols);
-                    char* w = carve(pl.bytes);
-                    t.amax_part = reinterpret_cast<uint32_t*>(w + pl.off_amax_part);
-                    t.err = reinterpret_cast<float*>(w + pl.off_err_part);
-                    t.err5 = reinterpret_cast<float*>(w + pl.off_err5_part);
-                    t.zero = reinterpret_cast<uint32_t*>(w + pl.off_nnz_part);
-                    t.abits = reinterpret_cast<uint32_t*>(w + pl.off_decision);
-                    t.flush_part = reinterpret_cast<uint32_t*>(w + pl.off_flush_part);
-                    t.flush_need = 0ull;
-                    if (crit == kCritEq2 && it.o.bf16 && !it.three && it.th > 0.0f && it.th < 0.9f)      // 1 % margin over th * N covers the
-                        t.flush_need = (unsigned long long)(1.01 * (double)it.th * (double)(it.sh.rows * it.sh.cols)) + 1ull;   // binary32 sums
-                    t.stats = static_cast<StatsDev*>(it.stats);
-                    a_end += t.n_amax; s_end += t.n_slots;
-                    c_end += (it.o.bf16 || it.three) ? share(t.n_tiles, total_tiles, 2048, 2048) : 1;
-                    g.amax_end[k] = a_end; g.slot_end[k] = s_end; g.copy_end[k] = c_end;
-                }
-                GroupStats riders; riders.n = 0; riders.near_tol = near_tol;
-                int ride_partial = 0, ride_final = 0;
-                if (!riders_used && n_stats_groups > 0) {
-                    riders = stats_groups[0];
-                    ride_partial = riders.wg_end[riders.n - 1];
-                    ride_final = ride_partial > riders.n ? riders.n : 0;      // single-workgroup operands are final already
-                    riders_used = true;
-                }
-                { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_group<<<dim3(a_end + ride_partial), dim3(256), kResidency3, st>>>(g, riders, a_end); }
-                {
-                    ProfScope ps(prof, kKernTensorQuant, st);
-                    if (fake) {
-                        if (crit == kCritEq3) k_tensor_quant_group<kCritEq3, true><<<dim3(s_end), dim3(256), kResidency3, st>>>(g);
-                        else k_tensor_quant_group<kCritEq2, true><<<dim3(s_end), dim3(256), kResidency3, st>>>(g);
-                    } else {
-                        if (crit == kCritEq3) k_tensor_quant_group<kCritEq3, false><<<dim3(s_end), dim3(256), kResidency3, st>>>(g);
-                        else k_tensor_quant_group<kCritEq2, false><<<dim3(s_end), dim3(256), kResidency3, st>>>(g);
-                    }
-                }
-                {
-                    ProfScope ps(prof, kKernFallbackCopy, st);
-                    if (crit == kCritEq3) k_tensor_finish_group<kCritEq3><<<dim3(c_end + ride_final), dim3(256), 0, st>>>(g, riders, c_end);
-                    else k_tensor_finish_group<kCritEq2><<<dim3(c_end + ride_final), dim3(256), 0, st>>>(g, riders, c_end);
-                }
-                cnt = 0;
-            };
-            for (int i = 0; i < n; ++i) {
-                const BatchItem& it = items[i];
-                if (route[i] != kRouteTensorGroup || it.crit != crit || (it.o.fake != nullptr) != (fake != 0)) continue;
-                const int64_t n_tiles = (it.sh.rows * it.sh.cols / 8 + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
-                if (n_tiles > 2000ll * kMaxQuantBlocks) return hipErrorInvalidValue;   // 16-bit per-lane zero counters
-                idx[cnt] = i;
-                if (++cnt == kMaxGroupTensor) flush();
+            if (route[i] != kRouteSubFlat || it.crit != crit || (it.o.fake != nullptr) != (fake != 0)) continue;
+            const int64_t n_part = item_parts(it), n_units = n_part / 32, n_full = n_units * 32, n_tail = n_part - n_full;
+            if (n_units > 0 && n_units <= kSubRiderMaxUnits && team_has[fake] && riders.table.n < kMaxSubRiders &&
+                (riders.table.n == 0 || riders.fake == (fake != 0))) {
+                SubRiders& r = riders.table;
+                rider_units += n_units;
+                r.unit_end[r.n] = rider_units; r.x[r.n] = it.x; r.o[r.n] = it.o; r.th[r.n] = it.th; r.defer[r.n] = it.scope == 1;
+                r.mode[r.n] = (uint8_t)it.scaling; r.gam[r.n] = gam_of[i];
+                ++r.n;
+                riders.fake = fake != 0;
+                riders.blocks = (rider_units + 3) / 4 < kSubFlatMaxBlocks ? (rider_units + 3) / 4 : kSubFlatMaxBlocks;
+            } else if (n_units > 0) {
+                total += n_units;
+                g.unit_end[g.n] = total; g.x[g.n] = it.x; g.o[g.n] = it.o; g.th[g.n] = it.th; g.defer[g.n] = it.scope == 1;
+                g.mode[g.n] = (uint8_t)it.scaling; g.gam[g.n] = gam_of[i];
+                if (++g.n == kMaxGroupSub) flush();
             }
-            flush();
+            if (n_tail > 0) {     // fewer than 32 blocks left: the general kernel takes them
+                KShape ts{n_tail, 128, 128};
+                KOut to = it.o;
+                if (to.fp8) to.fp8 += n_full * 128;
+                to.ld_fp8 = 128;
+                if (to.fake) { to.fake += n_full * 128; to.ld_fake = 128; }
+                if (to.bf16) to.bf16 += n_full * 128;
+                to.ld_bf16 = 128;
+                to.scale += n_full; to.amax += n_full; to.err_sum += n_full; to.nnz += n_full; to.mask += n_full;
+                if (to.err5_sum) to.err5_sum += n_full;
+                if (to.e8m0) to.e8m0 += n_full;
+                err = launch_sub1x128(it.x + n_full * 128, ts, to, crit, it.scope == 1, it.th, (uint32_t)it.scaling, gam_of[i], 0u, st, nullptr);
+            }
         }
-        // ---- per-tensor operands with padded leading dimensions, one at a time
-        for (int i = 0; i < n && err == hipSuccess; ++i) {
-            const BatchItem& it = items[i];
-            if (route[i] != kRouteTensorStrided || it.crit != crit) continue;
-            err = launch_tensor(it.x, it.sh, it.o, it.crit, it.th, (uint32_t)it.scaling, it.three ? 1u : 0u, carve(plan_tensor(it.sh.rows, it.sh.cols).bytes), st, prof);
-            if (err == hipSuccess && it.stats)
-                err = launch_select_stats(make_geom(it.gran, it.sh.rows, it.sh.cols), it.o.err_sum, it.o.nnz, it.o.mask, it.th, near_tol, it.stats, st);
-        }
+        flush();
     }
-    // ---- statistics of the operands with sub-tensor blocks that found no per-tensor launch to ride on
+    // ---- 1x128 sub-channel operands, general kernel
+    for (int i = 0; i < n && err == hipSuccess; ++i) {
+        const BatchItem& it = items[i];
+        if (route[i] != kRouteSubGeneral || it.crit != crit) continue;
+        err = launch_sub1x128(it.x, it.sh, it.o, crit, it.scope == 1, it.th, (uint32_t)it.scaling, gam_of[i], (uint32_t)it.three, st, prof);
+    }
+    // ---- team kernels: 128x128 and 64x64 blocks, per-channel rows
+    for (int kind = 0; kind < kTeamKinds && err == hipSuccess; ++kind) {
+        int idx[kBatchMax];
+        int cnt = 0;
+        for (int i = 0; i < n; ++i)
+            if (route[i] == kRouteTeam && items[i].crit == crit && team_kind_of(items[i]) == kind) idx[cnt++] = i;
+        if (cnt) err = launch_team_items(items, idx, cnt, kind, crit, gam_of, &riders, st, prof);
+    }
+    if (err == hipSuccess && riders.table.n > 0 && !riders.used) {      // no team launch took them: a launch of their own
+        GroupSub g; g.n = riders.table.n;
+        for (int k = 0; k < g.n; ++k) {
+            const SubRiders& r = riders.table;
+            g.unit_end[k] = r.unit_end[k]; g.x[k] = r.x[k]; g.o[k] = r.o[k]; g.th[k] = r.th[k]; g.defer[k] = r.defer[k];
+            g.mode[k] = r.mode[k]; g.gam[k] = r.gam[k];
+        }
+        ProfScope ps(prof, kKernSub1x128, st);
+        const dim3 grid((unsigned)riders.blocks);
+        if (riders.fake) {
+            if (crit == kCritEq3) k_sub1x128_group<kCritEq3, true><<<grid, dim3(256), 0, st>>>(g);
+            else k_sub1x128_group<kCritEq2, true><<<grid, dim3(256), 0, st>>>(g);
+        } else {
+            if (crit == kCritEq3) k_sub1x128_group<kCritEq3, false><<<grid, dim3(256), 0, st>>>(g);
+            else k_sub1x128_group<kCritEq2, false><<<grid, dim3(256), 0, st>>>(g);
+        }
+        riders.used = true;
+    }
+    // ---- 128x1 sub-columns
+    if (err == hipSuccess) {
+        int idx[kBatchMax];
+        int cnt = 0;
+        for (int i = 0; i < n; ++i)
+            if (route[i] == kRouteSubCol && items[i].crit == crit) idx[cnt++] = i;
+        if (cnt) err = launch_subcol_items(items, idx, cnt, crit, gam_of, st, prof);
+    }
+    // ---- per-channel columns
+    if (err == hipSuccess) {
+        int idx[kBatchMax];
+        char* ws_of[kBatchMax];
+        int cnt = 0;
+        for (int i = 0; i < n; ++i)
+            if (route[i] == kRouteChannelCol && items[i].crit == crit) {
+                ws_of[cnt] = carve(column_workspace_bytes(items[i].sh.rows, items[i].sh.cols));
+                idx[cnt++] = i;
+            }
+        if (cnt) err = launch_channel_col_items(items, idx, cnt, crit, gam_of, ws_of, st, prof);
+    }
+}
+
+// ---- tensor-level decision (Section 3.1) over the per-block sums the block kernels left behind
+void BatchRun::tensor_level_decisions() {
+    GroupScope g; g.n = 0;
+    int red = 0, copy = 0;
+    auto flush = [&]() {
+        if (g.n == 0) return;
+        { ProfScope ps(prof, kKernScopeReduce, st); k_scope_reduce_group<<<dim3(red), dim3(256), 0, st>>>(g); }
+        { ProfScope ps(prof, kKernScopeDecide, st); k_scope_decide_group<<<dim3(red), dim3(256), 0, st>>>(g); }
+        { ProfScope ps(prof, kKernFallbackCopy, st); k_scope_copy_group<<<dim3(copy), dim3(256), 0, st>>>(g); }
+        g.n = 0; red = 0; copy = 0;
+    };
+    int64_t total_elems = 0;
+    for (int i = 0; i < n; ++i)
+        if (items[i].gran != kGranTensor && items[i].scope == 1) total_elems += items[i].sh.rows * items[i].sh.cols;
+    for (int i = 0; i < n; ++i) {
+        const BatchItem& it = items[i];
+        if (it.gran == kGranTensor || it.scope != 1) continue;
+        ScopeOp& t = g.op[g.n];
+        char* w = carve(scope_workspace_bytes(0));
+        t.err_sum = it.o.err_sum; t.err5_sum = it.o.err5_sum; t.nnz = it.o.nnz; t.mask = it.o.mask;
+        t.n_part = item_parts(it);
+        t.part_err = reinterpret_cast<double*>(w); t.part_err5 = t.part_err + kScopeBlocks;
+        t.part_nnz = reinterpret_cast<unsigned long long*>(w) + 2 * kScopeBlocks;
+        t.decision = reinterpret_cast<uint32_t*>(w + 3 * sizeof(double) * kScopeBlocks);
+        t.th = it.th; t.crit = it.crit;
+        t.proven = scope_proof_applies(it) ? gam_of[i] + 2 : nullptr;
+        int64_t want = (t.n_part + 1023) / 1024;
+        t.n_red = (int)(want < 1 ? 1 : (want > kScopeBlocks ? kScopeBlocks : want));
+        t.x = it.x; t.bf16 = it.o.bf16;
+        t.rows = it.sh.rows; t.cols = it.sh.cols; t.ld = it.sh.ld; t.ld_bf16 = it.o.ld_bf16;
+        red += t.n_red;
+        copy += it.o.bf16 ? share(it.sh.rows * it.sh.cols, total_elems, 4096, 4096) : 1;
+        g.red_end[g.n] = red; g.copy_end[g.n] = copy;
+        if (++g.n == kMaxGroupScope) flush();
+    }
+    flush();
+}
+
+// ---- statistics of the operands with sub-tensor blocks: their kernels (and tensor-level decisions) are done, so the
+//      first group can ride on the first per-tensor launches: partial records in the shadow of pass A, the combine
+//      step next to the finish pass.  Groups that find no such launch run on their own at the end.
+void BatchRun::collect_statistics() {
+    GroupStats* g = nullptr;
+    for (int i = 0; i < n; ++i) {
+        const BatchItem& it = items[i];
+        if (!it.stats || it.gran == kGranTensor) continue;
+        if (!g || g->n == kMaxGroupStats) { g = &stats_groups[n_stats_groups++]; g->n = 0; g->near_tol = near_tol; }
+        StatsOp& t = g->op[g->n];
+        t.err_sum = it.o.err_sum; t.nnz = it.o.nnz; t.mask = it.o.mask;
+        t.geom = make_geom(it.gran, it.sh.rows, it.sh.cols);
+        t.n_part = geom_parts(t.geom);
+        t.th = it.th;
+        t.rec = reinterpret_cast<StatsRec*>(carve(sizeof(StatsRec) * kStatsMaxWg));
+        t.out = static_cast<StatsDev*>(it.stats);
+        g->wg_end[g->n] = (g->n ? g->wg_end[g->n - 1] : 0) + stats_wgs(t.n_part);
+        ++g->n;
+    }
+}
+
+void BatchRun::per_tensor_operands(int crit) {
+    // ---- per-tensor operands: amax pass, quantize pass, finish (+ fallback copy) pass; FP8 payload and fake
+    //      quantization are different kernels
+    for (int fake = 0; fake < 2 && err == hipSuccess; ++fake) {
+        int idx[kMaxGroupTensor];
+        int cnt = 0;
+        auto flush = [&]() {
+            if (cnt == 0) return;
+            GroupTensor g; g.n = cnt; g.near_tol = near_tol;
+            int64_t total_tiles = 0;
+            for (int k = 0; k < cnt; ++k) {
+                const BatchItem& it = items[idx[k]];
+                const int64_t n_chunks = it.sh.rows * it.sh.cols / 8;
+                total_tiles += (n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
+            }
+            int a_end = 0, s_end = 0, c_end = 0;
+            for (int k = 0; k < cnt; ++k) {
+                const BatchItem& it = items[idx[k]];
+                TensorOp& t = g.op[k];
+                t.x = it.x; t.o = it.o; t.th = it.th; t.mode = (uint32_t)it.scaling; t.three = it.three ? 1u : 0u; t.lean = it.lean ? 1u : 0u;
+                t.n_chunks = it.sh.rows * it.sh.cols / 8;
+                t.n_tiles = (t.n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
+                t.n_amax = share(t.n_tiles, total_tiles, kMaxAmaxBlocks, t.n_tiles);
+                t.n_slots = share(t.n_tiles, total_tiles, kMaxQuantBlocks, t.n_tiles);
+                const TensorPlan pl = plan_tensor(it.sh.rows, it.sh.cols);
+                char* w = carve(pl.bytes);
+                t.amax_part = reinterpret_cast<uint32_t*>(w + pl.off_amax_part);
+                t.err = reinterpret_cast<float*>(w + pl.off_err_part);
+                t.err5 = reinterpret_cast<float*>(w + pl.off_err5_part);
+                t.zero = reinterpret_cast<uint32_t*>(w + pl.off_nnz_part);
+                t.abits = reinterpret_cast<uint32_t*>(w + pl.off_decision);
+                t.flush_part = reinterpret_cast<uint32_t*>(w + pl.off_flush_part);
+                t.flush_need = 0ull;
+                if (crit == kCritEq2 && it.o.bf16 && !it.three && it.th > 0.0f && it.th < 0.9f)      // 1 % margin over th * N covers the
+                    t.flush_need = (unsigned long long)(1.01 * (double)it.th * (double)(it.sh.rows * it.sh.cols)) + 1ull;   // binary32 sums
+                t.stats = static_cast<StatsDev*>(it.stats);
+                a_end += t.n_amax; s_end += t.n_slots;
+                c_end += (it.o.bf16 || it.three) ? share(t.n_tiles, total_tiles, 2048, 2048) : 1;
+                g.amax_end[k] = a_end; g.slot_end[k] = s_end; g.copy_end[k] = c_end;
+            }
+            GroupStats riders; riders.n = 0; riders.near_tol = near_tol;
+            int ride_partial = 0, ride_final = 0;
+            if (!riders_used && n_stats_groups > 0) {
+                riders = stats_groups[0];
+                ride_partial = riders.wg_end[riders.n - 1];
+                ride_final = ride_partial > riders.n ? riders.n : 0;      // single-workgroup operands are final already
+                riders_used = true;
+            }
+            { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_group<<<dim3(a_end + ride_partial), dim3(256), kResidency3, st>>>(g, riders, a_end); }
+            {
+                ProfScope ps(prof, kKernTensorQuant, st);
+                if (fake) {
+                    if (crit == kCritEq3) k_tensor_quant_group<kCritEq3, true><<<dim3(s_end), dim3(256), kResidency3, st>>>(g);
+                    else k_tensor_quant_group<kCritEq2, true><<<dim3(s_end), dim3(256), kResidency3, st>>>(g);
+                } else {
+                    if (crit == kCritEq3) k_tensor_quant_group<kCritEq3, false><<<dim3(s_end), dim3(256), kResidency3, st>>>(g);
+                    else k_tensor_quant_group<kCritEq2, false><<<dim3(s_end), dim3(256), kResidency3, st>>>(g);
+                }
+            }
+            {
+                ProfScope ps(prof, kKernFallbackCopy, st);
+                if (crit == kCritEq3) k_tensor_finish_group<kCritEq3><<<dim3(c_end + ride_final), dim3(256), 0, st>>>(g, riders, c_end);
+                else k_tensor_finish_group<kCritEq2><<<dim3(c_end + ride_final), dim3(256), 0, st>>>(g, riders, c_end);
+            }
+            cnt = 0;
+        };
+        for (int i = 0; i < n; ++i) {
+            const BatchItem& it = items[i];
+            if (route[i] != kRouteTensorGroup || it.crit != crit || (it.o.fake != nullptr) != (fake != 0)) continue;
+            const int64_t n_tiles = (it.sh.rows * it.sh.cols / 8 + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
+            if (n_tiles > 2000ll * kMaxQuantBlocks) { err = hipErrorInvalidValue; return; }   // 16-bit per-lane zero counters
+            idx[cnt] = i;
+            if (++cnt == kMaxGroupTensor) flush();
+        }
+        flush();
+    }
+    // ---- per-tensor operands with padded leading dimensions, one at a time
+    for (int i = 0; i < n && err == hipSuccess; ++i) {
+        const BatchItem& it = items[i];
+        if (route[i] != kRouteTensorStrided || it.crit != crit) continue;
+        err = launch_tensor(it.x, it.sh, it.o, it.crit, it.th, (uint32_t)it.scaling, it.three ? 1u : 0u, carve(plan_tensor(it.sh.rows, it.sh.cols).bytes), st, prof);
+        if (err == hipSuccess && it.stats)
+            err = launch_select_stats(make_geom(it.gran, it.sh.rows, it.sh.cols), it.o.err_sum, it.o.nnz, it.o.mask, it.th, near_tol, it.stats, st);
+    }
+}
+
+// ---- statistics of the operands with sub-tensor blocks that found no per-tensor launch to ride on
+void BatchRun::leftover_statistics() {
     for (int k = riders_used ? 1 : 0; k < n_stats_groups && err == hipSuccess; ++k) {
         const GroupStats& g = stats_groups[k];
         const int wg_total = g.wg_end[g.n - 1];
         { ProfScope ps(prof, kKernStatsPartial, st); k_stats_group_partial<<<dim3(wg_total), dim3(256), 0, st>>>(g); }
         if (wg_total > g.n) { ProfScope ps(prof, kKernStatsFinal, st); k_stats_group_final<<<dim3(g.n), dim3(256), 0, st>>>(g); }
     }
-    if (err != hipSuccess) return err;
+}
+
+}  // namespace
+
+hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws, size_t ws_bytes, hipStream_t st, KProf* prof) {
+    static_assert(sizeof(GroupSub) <= 3800 && sizeof(GroupTensor) + sizeof(GroupStats) <= 3800 &&
+                  sizeof(GroupGam) <= 3800 && sizeof(GroupScope) <= 3800, "kernel-argument segment is 4 KB");
+    static_assert(sizeof(StatsRec) == 128, "StatsRec layout");
+    (void)ws_bytes;                              // checked by the caller against batch_workspace_bytes()
+    BatchRun run;
+    run.items = items; run.n = n; run.near_tol = near_tol; run.st = st; run.prof = prof;
+    run.wsp = static_cast<char*>(ws);
+    for (int i = 0; i < n; ++i) run.route[i] = route_of(items[i]);
+    run.group_mantissas();
+    for (int crit = 0; crit < 2 && run.err == hipSuccess; ++crit) run.sub_tensor_operands(crit);
+    run.tensor_level_decisions();
+    // the statistics of the sub-tensor operands are collected after their kernels (and tensor-level decisions)
+    run.collect_statistics();
+    for (int crit = 0; crit < 2 && run.err == hipSuccess; ++crit) run.per_tensor_operands(crit);
+    run.leftover_statistics();
+    if (run.err != hipSuccess) return run.err;
     return hipGetLastError();
 }
 
