@@ -98,7 +98,7 @@ def run_variants(ops, B, torch, dev, steps, log):
                     b -= 1.0 * n * f                            # no FP8 payload for an operand known to stay in BF16
             else:
                 b = 3.0 * n + META_BYTES * P
-                if scope == "tensor" and scaling == "gam" and gran in ("block128", "channel_row"):
+                if scope == "tensor" and scaling == "gam" and gran in ("block128", "block64", "channel_row"):
                     b += 2.0 * n * f                            # these inputs' BF16 decision is proven by the pre-pass: written by the block kernel
                 elif scope == "tensor":
                     b += 4.0 * n * f                            # separate copy pass after the tensor-wide decision
@@ -122,6 +122,7 @@ def run_variants(ops, B, torch, dev, steps, log):
     const = lambda g: (lambda o: g)
     analyze_variant("hot_path_lean_fp8", own, lean=True)
     analyze_variant("gam_tensor_level_block128", const("block128"), scope="tensor", scaling="gam")
+    analyze_variant("gam_tensor_level_block64", const("block64"), scope="tensor", scaling="gam")
     analyze_variant("gam_tensor_level_channel_row", const("channel_row"), scope="tensor", scaling="gam")
     analyze_variant("gam_tensor_level_per_tensor", const("tensor"), scaling="gam")
     analyze_variant("e8m0_block128", const("block128"), scaling="e8m0")

@@ -1360,7 +1360,7 @@ void BatchRun::group_mantissas() {
             if (!scope_proof_applies(it)) continue;
             pv_part[i] = reinterpret_cast<uint32_t*>(carve(sizeof(uint32_t) * kProveMaxWg));
             pv_flush[i] = reinterpret_cast<uint32_t*>(carve(sizeof(uint32_t) * kProveMaxWg));
-            pv[n_pv] = BlockProveItem{it.x, it.sh.rows, it.sh.cols, it.sh.ld, pv_part[i], pv_flush[i], 0, it.gran == kGranRow};
+            pv[n_pv] = BlockProveItem{it.x, it.sh.rows, it.sh.cols, it.sh.ld, pv_part[i], pv_flush[i], 0, it.gran == kGranRow ? 1 : (it.gran == kGranBlock64 ? 2 : 0)};
             pv_units += scope_proof_units(it);
             pv_item[n_pv] = i;
             if (++n_pv == kProveGroup) flush();

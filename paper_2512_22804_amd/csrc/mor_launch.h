@@ -126,14 +126,14 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
 // mor_partitions.hip: team kernels (64x64, per-channel rows, general 128x128) and column kernels
 enum { kCritEq2 = 0, kCritEq3 = 1 };
 
-// Tensor-level decision (Section 3.1) over GAM-scaled 128 x 128 blocks or per-channel rows: the amax pre-pass of
+// Tensor-level decision (Section 3.1) over GAM-scaled 128 x 128 / 64 x 64 blocks or per-channel rows: the amax pre-pass of
 // Algorithm 1 can prove the BF16 decision under Eq. 2 from elements that are certain to flush inside their block, so
 // the block kernel writes the BF16 payload from its registers and the operand is not read a third time.
 inline bool scope_proof_applies(const BatchItem& it) {
     // (fake quantization: o.bf16 == o.fake, and a proven operand's output is its input)
     if (it.scaling != 1 || it.scope != 1 || it.crit != kCritEq2 || it.three || it.o.bf16 == nullptr) return false;
     if (!(it.th > 0.0f && it.th < 0.9f)) return false;      // the flush count is compared with 1.01 * th * N + 1
-    if (it.gran == kGranBlock) return it.sh.rows % 128 == 0 && it.sh.cols % 128 == 0;
+    if (it.gran == kGranBlock || it.gran == kGranBlock64) return it.sh.rows % 128 == 0 && it.sh.cols % 128 == 0;   // whole 128 x 128 tiles
     return it.gran == kGranRow;
 }
 // Work units of the pre-pass (16384 elements each) and its per-operand arguments: per workgroup the largest amax and
@@ -148,7 +148,7 @@ struct BlockProveItem {
     uint32_t* amax_part;     // [n_wg]
     uint32_t* flush_part;    // [n_wg]
     int n_wg;
-    int by_rows;             // per-channel rows instead of 128 x 128 blocks
+    int kind;                // 0: 128 x 128 blocks, 1: per-channel rows, 2: 64 x 64 blocks
 };
 hipError_t launch_block_amax_prove(const BlockProveItem* ops, int n, hipStream_t st);
 

@@ -345,10 +345,10 @@ __global__ __launch_bounds__(TEAM == kTeamBigRow ? 1024 : 256) void k_team_group
     team_block<TEAM, CRIT, FAKE, EDGE>(t, unit, sh);
 }
 
-// Pre-pass of Algorithm 1 (group amax) for operands with 128 x 128 blocks or per-channel rows whose decision is taken
+// Pre-pass of Algorithm 1 (group amax) for operands with 128 x 128 / 64 x 64 blocks or per-channel rows whose decision is taken
 // per tensor under Eq. 2: a workgroup walks over tiles, keeps the running maximum and counts the elements that are
 // certain to flush -- non-zero and below 2^-20 of a LOWER bound of their own block's amax (the amax of the part of the
-// block that the lane's wave holds: 32 rows of a 128 x 128 block, up to 4096 consecutive elements of a row), so that
+// block that the lane's wave holds: 32 rows of a 128 x 128 block, 16 rows of a 64 x 64 block, up to 4096 consecutive elements of a row), so that
 // under any scale of Algorithm 1 (never above 448 / amax) they land below half the smallest E4M3 subnormal and contribute
 // exactly 1 to the error sum.  The waves of a workgroup never wait for each other inside the loop, and the next tile's
 // loads are in flight while the current one is counted.
@@ -359,8 +359,9 @@ struct ProveOp {
     int64_t n_units;         // blocks: tiles; rows: pieces (one per wave)
     uint32_t* amax_part;
     uint32_t* flush_part;
-    int32_t by_rows;
+    int32_t kind;            // kProveBlock128, kProveRows, kProveBlock64
 };
+enum { kProveBlock128 = 0, kProveRows = 1, kProveBlock64 = 2 };
 struct GroupProve {
     int n;
     int32_t wg_end[kMaxTeamGroup];
@@ -368,11 +369,13 @@ struct GroupProve {
 };
 constexpr int kProvePiece = 64 * 8 * kChunks;      // elements of a row that one wave holds at a time
 static_assert(kProvePiece == 4096, "scope_proof_units() counts pieces of 4096 elements");
-template <bool BY_ROWS>
+// KIND kProveBlock64: the same 128 x 128 tiles as for kProveBlock128, four blocks each; a lane's first four chunks lie
+// in an upper block, the others in a lower one, lanes with bit 3 set in a right-hand one.
+template <int KIND>
 __device__ __forceinline__ void prove_tiles(const ProveOp& t, int b, int nb, uint32_t& amax_run, uint32_t& flush_run) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     auto load_tile = [&](u32x4 (&raw)[kChunks], int64_t unit) {
-        if constexpr (BY_ROWS) {
+        if constexpr (KIND == kProveRows) {
             // wave w of the workgroup's unit takes piece 4 * unit + w; chunks beyond the row (or beyond the operand) load zeros
             const int64_t piece = unit * 4 + w, row = piece / t.units_x, c0 = (piece - row * t.units_x) * kProvePiece;
             const BufRsrc rx = make_buf(t.x + row * t.ld + c0);
@@ -387,31 +390,45 @@ __device__ __forceinline__ void prove_tiles(const ProveOp& t, int b, int nb, uin
             for (int i = 0; i < kChunks; ++i) raw[i] = load16(src + (int64_t)i * 16 * t.ld);
         }
     };
-    const int64_t n_wg_units = BY_ROWS ? (t.n_units + 3) / 4 : t.n_units;
+    const int64_t n_wg_units = KIND == kProveRows ? (t.n_units + 3) / 4 : t.n_units;
     u32x4 cur[kChunks], nxt[kChunks];
     int64_t unit = b;
     if (unit < n_wg_units) load_tile(cur, unit);
     while (unit < n_wg_units) {
         const int64_t next = unit + nb;
         if (next < n_wg_units) load_tile(nxt, next);        // uniform over the workgroup
-        uint32_t a2 = 0u;
+        // amax of what this wave holds of the lane's block(s): one value, or one for each half of the chunks
+        uint32_t a2[2] = {0u, 0u};
 #pragma unroll
         for (int i = 0; i < kChunks; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) a2 = pk_max_u16(a2, cur[i][j] & 0x7FFF7FFFu);
-        const uint32_t abits = wave_allmax_u32(fold_max16(a2));      // what this wave holds of the block
-        amax_run = max(amax_run, abits);
+            for (int j = 0; j < 4; ++j) {
+                const int h = KIND == kProveBlock64 ? i / (kChunks / 2) : 0;
+                a2[h] = pk_max_u16(a2[h], cur[i][j] & 0x7FFF7FFFu);
+            }
+        uint32_t abits[2];
+        if constexpr (KIND == kProveBlock64) {
+            abits[0] = half_allmax_u32(fold_max16(a2[0]));
+            abits[1] = half_allmax_u32(fold_max16(a2[1]));
+        } else {
+            abits[0] = abits[1] = wave_allmax_u32(fold_max16(a2[0]));
+        }
+        amax_run = max(amax_run, max(abits[0], abits[1]));
         // certain flush: 1 <= m < t  <=>  m - 1 < t - 1, with t the amax pattern taken down by 20 binades (0 if that
         // underflows); m - 1 wraps to 0xFFFF for zeros, which never count
-        const uint32_t t1 = abits > 0x0A00u ? abits - 0x0A01u : 0u;
-        const uint32_t bound2 = t1 | (t1 << 16);
+        uint32_t bound2[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t t1 = abits[h] > 0x0A00u ? abits[h] - 0x0A01u : 0u;
+            bound2[h] = t1 | (t1 << 16);
+        }
         uint32_t f2 = 0u;
 #pragma unroll
         for (int i = 0; i < kChunks; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const uint32_t mm1 = pk_sub_u16(cur[i][j] & 0x7FFF7FFFu, 0x00010001u);
-                f2 = pk_add_u16(f2, pk_min_u16(pk_sub_sat_u16(bound2, mm1), 0x00010001u));
+                f2 = pk_add_u16(f2, pk_min_u16(pk_sub_sat_u16(bound2[i / (kChunks / 2)], mm1), 0x00010001u));
             }
         flush_run += fold_add16(f2);                       // at most 64 per tile and lane
 #pragma unroll
@@ -427,9 +444,11 @@ __global__ __launch_bounds__(256) void k_block_amax_prove(GroupProve g) {
     const int b = blockIdx.x - first, nb = g.wg_end[op] - first;
     const int tid = threadIdx.x;
     uint32_t amax_run = 0u, flush_run = 0u;
-    if (t.by_rows) prove_tiles<true>(t, b, nb, amax_run, flush_run);
-    else prove_tiles<false>(t, b, nb, amax_run, flush_run);
-    flush_run = wave_allsum_u32(flush_run);                // amax_run is already uniform over the wave
+    if (t.kind == kProveRows) prove_tiles<kProveRows>(t, b, nb, amax_run, flush_run);
+    else if (t.kind == kProveBlock64) prove_tiles<kProveBlock64>(t, b, nb, amax_run, flush_run);
+    else prove_tiles<kProveBlock128>(t, b, nb, amax_run, flush_run);
+    amax_run = wave_allmax_u32(amax_run);
+    flush_run = wave_allsum_u32(flush_run);
     if ((tid & 63) == 0) { sh[tid >> 6] = amax_run; sh[4 + (tid >> 6)] = flush_run; }
     __syncthreads();
     if (tid == 0) {
@@ -1180,8 +1199,8 @@ hipError_t launch_block_amax_prove(const BlockProveItem* ops, int n, hipStream_t
         int end = 0;
         for (int k = base; k < n && k < base + kMaxTeamGroup; ++k) {
             ProveOp& t = g.op[g.n];
-            t.x = ops[k].x; t.ld = ops[k].ld; t.cols = ops[k].cols; t.by_rows = ops[k].by_rows;
-            if (t.by_rows) { t.units_x = (ops[k].cols + kProvePiece - 1) / kProvePiece; t.n_units = ops[k].rows * t.units_x; }
+            t.x = ops[k].x; t.ld = ops[k].ld; t.cols = ops[k].cols; t.kind = ops[k].kind;
+            if (t.kind == kProveRows) { t.units_x = (ops[k].cols + kProvePiece - 1) / kProvePiece; t.n_units = ops[k].rows * t.units_x; }
             else { t.units_x = ops[k].cols / 128; t.n_units = (ops[k].rows / 128) * t.units_x; }
             t.amax_part = ops[k].amax_part; t.flush_part = ops[k].flush_part;
             end += ops[k].n_wg;

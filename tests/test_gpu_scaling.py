@@ -132,8 +132,8 @@ def _with_tiny(rows, cols, frac, seed, tiny_exp=-40):
 
 @pytest.mark.parametrize("frac", [0.0, 0.04, 0.2])
 @pytest.mark.parametrize("pad", [0, 64])
-@pytest.mark.parametrize("gran,shape", [("block128", (640, 1152)), ("channel_row", (70, 1152)), ("channel_row", (9, 9000)),
-                                        ("channel_row", (5, 20000))])
+@pytest.mark.parametrize("gran,shape", [("block128", (640, 1152)), ("block64", (640, 1152)), ("block64", (192, 320)),
+                                        ("channel_row", (70, 1152)), ("channel_row", (9, 9000)), ("channel_row", (5, 20000))])
 def test_gam_tensor_level_decision_proven_by_the_pre_pass(frac, pad, gran, shape):
     """Tensor-level decision over GAM-scaled 128x128 blocks or per-channel rows (the recipe of Section 3.1): with enough
     certain flushes the amax pre-pass proves the BF16 decision and the block kernel writes the fallback itself; with 4 %
@@ -172,6 +172,13 @@ def test_gam_tensor_level_proof_uses_each_blocks_own_amax():
     r = parity.compare(xb, "block128", "tensor", "mean_rel_err", 0.045, label="gam proof per block", scaling="gam")
     assert r["n_bf16"] == 0
     assert parity.compare_fake(xb, "block128", "tensor", "mean_rel_err", 0.045, label="gam proof per block, fake", scaling="gam")["n_bf16"] == 0
+    # 64 x 64 blocks: the same picture one size down (the block at the origin holds the large values and its 3 % of flushes)
+    x = _with_tiny(128, 256, 0.0, 25)
+    x[64:, :] *= np.float32(2.0 ** -30)
+    x[:64, 64:] *= np.float32(2.0 ** -30)
+    x[:64, :64][np.random.default_rng(26).random((64, 64)) < 0.03] = np.float32(2.0 ** -30)
+    r = parity.compare(W.f32_to_bf16_bits(x), "block64", "tensor", "mean_rel_err", 0.045, label="gam proof per 64x64 block", scaling="gam")
+    assert r["n_bf16"] == 0
     # the same operand once its flushes are frequent enough in every block
     x2 = _with_tiny(rows, cols, 0.3, 9, tiny_exp=-30)
     x2[128:, :] *= np.float32(2.0 ** -20)
@@ -184,7 +191,7 @@ def test_gam_tensor_level_proof_in_a_batch_with_statistics():
     from oracle import mor_oracle as O
     dev = torch.device("cuda")
     specs = [(512, 1024, 0.2, "block128"), (256, 384, 0.0, "block128"), (384, 512, 0.04, "block128"), (128, 128, 0.5, "block128"),
-             (640, 256, 0.1, "block128"), (33, 4096, 0.2, "channel_row"), (7, 17000, 0.3, "channel_row"), (50, 512, 0.0, "channel_row")]
+             (640, 256, 0.1, "block128"), (256, 640, 0.2, "block64"), (128, 128, 0.0, "block64"), (33, 4096, 0.2, "channel_row"), (7, 17000, 0.3, "channel_row"), (50, 512, 0.0, "channel_row")]
     ops, keep = [], []
     for k, (rows, cols, frac, gran) in enumerate(specs):
         xb = W.f32_to_bf16_bits(_with_tiny(rows, cols, frac, 40 + k))
@@ -214,7 +221,7 @@ def test_gam_tensor_level_full_benchmark_sizes():
     ops, keep = [], []
     for xb in (w, g):
         xd = parity.to_dev(xb)
-        for gran in ("block128", "channel_row"):
+        for gran in ("block128", "block64", "channel_row"):
             params = B.make_params(xb.shape[0], xb.shape[1], gran, "tensor", "mean_rel_err", 0.045, scaling="gam")
             out = B.alloc_outputs(params, dev, want_bf16=True, bf16_fill=parity.FILL)
             ops.append((params, xd, out, None)); keep.append((xb, gran))
@@ -228,7 +235,7 @@ def test_gam_tensor_level_full_benchmark_sizes():
 
 
 @pytest.mark.parametrize("th", [0.0, 0.01, 0.3, 0.95, 1.5])
-@pytest.mark.parametrize("gran", ["block128", "channel_row"])
+@pytest.mark.parametrize("gran", ["block128", "block64", "channel_row"])
 def test_gam_tensor_level_thresholds_outside_the_usual_range(th, gran):
     """20 % flushed values: BF16 for th <= 0.2 (proven or not), E4M3 above; thresholds for which no proof is attempted
     (0, >= 0.9) take the separate copy and give the same outputs."""
