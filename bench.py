@@ -125,6 +125,9 @@ def run_variants(ops, B, torch, dev, steps, log):
     analyze_variant("gam_tensor_level_block64", const("block64"), scope="tensor", scaling="gam")
     analyze_variant("gam_tensor_level_channel_row", const("channel_row"), scope="tensor", scaling="gam")
     analyze_variant("gam_tensor_level_per_tensor", const("tensor"), scaling="gam")
+    # the scaling ablation of Section 4.1.2 keeps the tensor-level decision and swaps the scaling algorithm
+    analyze_variant("e8m0_tensor_level_block128", const("block128"), scope="tensor", scaling="e8m0")
+    analyze_variant("fp32_amax_tensor_level_block128", const("block128"), scope="tensor")
     analyze_variant("e8m0_block128", const("block128"), scaling="e8m0")
     analyze_variant("two_way_eq3_block128", const("block128"), crit="e4m3_vs_e5m2")
     analyze_variant("three_way_eq3_block128", const("block128"), crit="e4m3_vs_e5m2", formats="e4m3|e5m2|bf16")
