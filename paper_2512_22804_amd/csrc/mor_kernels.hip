@@ -1124,6 +1124,7 @@ struct GamOp {
     uint32_t* gmant;       // caller's group-mantissa output, may be nullptr
     const uint32_t* flush_part;          // [n_amax] certain flushes counted by the pre-pass, or nullptr
     unsigned long long flush_need;       // that many prove the decision
+    uint32_t skip;                       // per-channel columns under GAM: their own combine kernel derives the mantissas
 };
 struct GroupGam {
     int n;
@@ -1133,6 +1134,7 @@ __global__ __launch_bounds__(256) void k_gam_prepare(GroupGam g) {
     __shared__ uint32_t sh4[4];
     __shared__ unsigned long long shl[4];
     const GamOp& t = g.op[blockIdx.x];
+    if (t.skip) return;                  // uniform over the workgroup
     const uint32_t gbits = global_amax_bits(t.amax_part, t.n_amax, sh4);
     unsigned long long fl = 0ull;
     if (t.flush_part)
@@ -1311,6 +1313,7 @@ struct BatchRun {
     hipError_t err = hipSuccess;
     Route route[kBatchMax];
     const uint32_t* gam_of[kBatchMax] = {};      // per operand: {mantissa for E4M3, for E5M2, "BF16 proven" flag}
+    char* col_ws[kBatchMax] = {};                // per operand with per-channel columns: its column workspace
     GroupStats stats_groups[kMaxStatsGroups];
     int n_stats_groups = 0;
     bool riders_used = false;                    // the first statistics group went along with a per-tensor launch
@@ -1380,9 +1383,10 @@ void BatchRun::group_mantissas() {
             gam_of[i] = gam;
             GamOp& q = gg.op[k];
             q.amax_part = nullptr; q.n_amax = 0; q.mode = (uint32_t)it.scaling; q.gam = gam; q.gmant = it.o.gmant;
-            q.flush_part = nullptr; q.flush_need = 0ull;
+            q.flush_part = nullptr; q.flush_need = 0ull; q.skip = 0u;
             slot_of[k] = -1;
             if (it.scaling != kScaleGam) continue;
+            if (it.gran == kGranCol) { q.skip = 1u; continue; }      // the group amax comes out of the column-amax pass
             if (pv_part[i]) {
                 q.amax_part = pv_part[i]; q.n_amax = pv_wg[i];
                 q.flush_part = pv_flush[i];
@@ -1535,6 +1539,7 @@ void BatchRun::sub_tensor_operands(int crit) {
         for (int i = 0; i < n; ++i)
             if (route[i] == kRouteChannelCol && items[i].crit == crit) {
                 ws_of[cnt] = carve(column_workspace_bytes(items[i].sh.rows, items[i].sh.cols));
+                col_ws[i] = ws_of[cnt];
                 idx[cnt++] = i;
             }
         if (cnt) err = launch_channel_col_items(items, idx, cnt, crit, gam_of, ws_of, st, prof);
@@ -1567,6 +1572,7 @@ void BatchRun::tensor_level_decisions() {
         t.decision = reinterpret_cast<uint32_t*>(w + 3 * sizeof(double) * kScopeBlocks);
         t.th = it.th; t.crit = it.crit;
         t.proven = scope_proof_applies(it) ? gam_of[i] + 2 : nullptr;
+        if (column_tensor_proof_applies(it)) t.proven = column_tensor_proven_word(col_ws[i], it.sh.rows, it.sh.cols);
         int64_t want = (t.n_part + 1023) / 1024;
         t.n_red = (int)(want < 1 ? 1 : (want > kScopeBlocks ? kScopeBlocks : want));
         t.x = it.x; t.bf16 = it.o.bf16;

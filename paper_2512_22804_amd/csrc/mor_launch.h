@@ -160,6 +160,13 @@ hipError_t launch_team_items(const BatchItem* items, const int* idx, int cnt, in
 hipError_t launch_subcol_items(const BatchItem* items, const int* idx, int cnt, int crit, const uint32_t* const* gam_of,
                                hipStream_t st, KProf* prof);
 size_t column_workspace_bytes(int64_t rows, int64_t cols);
+// Per-channel columns with a tensor-level decision: the column-amax pass counts certain flushes per column anyway, and their
+// total may prove the operand's BF16 decision (Eq. 2); the quantize pass then writes the fallback and the word below says so.
+inline bool column_tensor_proof_applies(const BatchItem& it) {
+    return it.gran == kGranCol && it.scope == 1 && it.crit == kCritEq2 && !it.three && it.o.bf16 != nullptr && it.o.fake == nullptr &&
+           it.th > 0.0f && it.th < 0.9f;
+}
+uint32_t* column_tensor_proven_word(char* column_workspace, int64_t rows, int64_t cols);
 hipError_t launch_channel_col_items(const BatchItem* items, const int* idx, int cnt, int crit, const uint32_t* const* gam_of,
                                     char* const* ws_of, hipStream_t st, KProf* prof);
 

@@ -483,6 +483,7 @@ struct ColOp {
     int32_t tiles_per_strip;    // 128-row tiles a workgroup sweeps (1 for kColLocal)
     float th;
     uint8_t defer, mode, three, prove;   // prove: count certain flushes in the amax pass (see below)
+    uint8_t derive_gam;
     const uint32_t* gam;
     // per-channel columns: workspace, [n_strips x cols_padded] each, cols_padded = tiles_x * 128
     uint16_t* part_amax;
@@ -495,6 +496,15 @@ struct ColOp {
     uint32_t flush_need;                                 // that many certain flushes in a column prove its BF16 decision
     int32_t n_strips;
     int32_t copy_groups;                                 // workgroups per 128-column strip in the fallback-column pass
+    // tensor-level decision (Section 3.1) over per-channel columns: the certain flushes of ALL columns together may prove the
+    // BF16 decision of the operand; every column then counts as proven and the quantize pass writes the whole fallback
+    uint32_t* wg;                                        // [2 + 2 x n_strips x tiles_x]: word 0 = "BF16 proven for the whole operand" (read by the
+                                                         // tensor-level copy pass), then per workgroup of the amax pass its largest column
+                                                         // amax and its flush total
+    unsigned long long tensor_need;                      // 0: columns are proven one by one (decisions per column)
+    // GAM scaling (derive_gam): the group amax is the largest column amax, so the first combine derives the group mantissas
+    // itself (no pre-pass over the operand) and leaves them in `gam` and in the caller's output
+    uint32_t* gmant;                                     // caller's [2] or nullptr
 };
 struct GroupCol {
     int n;
@@ -511,6 +521,7 @@ struct ColShared {
     uint32_t amin[4][16][4];     // packed per-column (smallest non-zero pattern - 1), three-way recipe
     uint16_t abits[128];         // column amax patterns of the tile
     uint8_t mask[128];
+    uint32_t wg[8];              // per-wave amax / flush totals of a strip (column-amax pass)
 };
 
 // Combines a lane's 8 per-column values with the lanes that hold the same columns in the other row groups
@@ -903,9 +914,10 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
             for (int j = 0; j < 4; ++j) { sh.amax[w][cg][j] = amax2[j]; sh.amin[w][cg][j] = mn_strip[j]; sh.zero[w][cg][j] = flush2[j]; }
         }
         __syncthreads();
+        uint32_t a = 0u, fl = 0u;
         if (tid < 128) {
             const int g16 = tid >> 3, k = tid & 7;
-            uint32_t a = 0u, mn = 0xFFFFu, fl = 0u;
+            uint32_t mn = 0xFFFFu;
 #pragma unroll
             for (int ww = 0; ww < 4; ++ww) {
                 a = max(a, (sh.amax[ww][g16][k >> 1] >> ((k & 1) * 16)) & 0xFFFFu);
@@ -915,6 +927,16 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
             t.part_amax[strip * cols_padded + c0 + tid] = (uint16_t)a;
             if (t.three) t.part_zero[strip * cols_padded + c0 + tid] = (uint16_t)mn;
             if (t.prove) reinterpret_cast<uint16_t*>(t.part_err)[strip * cols_padded + c0 + tid] = (uint16_t)fl;
+        }
+        // the strip's largest column amax and its flush total, for the combine kernel's whole-operand figures
+        // (group amax of Algorithm 1, tensor-level proof)
+        a = wave_allmax_u32(a);
+        fl = wave_allsum_u32(t.prove ? fl : 0u);
+        if (lane == 0) { sh.wg[w] = a; sh.wg[4 + w] = fl; }
+        __syncthreads();
+        if (tid == 0) {
+            t.wg[2 + 2 * unit] = max(max(sh.wg[0], sh.wg[1]), max(sh.wg[2], sh.wg[3]));
+            t.wg[3 + 2 * unit] = (sh.wg[4] + sh.wg[5]) + (sh.wg[6] + sh.wg[7]);
         }
     }
     if constexpr (MODE == kColExternal) {
@@ -956,11 +978,48 @@ __global__ __launch_bounds__(256) void k_col_group(GroupCol g) {
 }
 
 // Per-channel columns, first combine: column amax over the strips -> amax, scale (Algorithm 1), E8M0 byte.
+// Under GAM every workgroup first takes the largest column amax of the operand (the group amax of Algorithm 1), and for a tensor-level decision the sum of all columns' certain flushes: the same values in every
+// workgroup, from the per-workgroup figures of the amax pass (a handful of loads per thread).
 __global__ __launch_bounds__(256) void k_col_scales(GroupCol g) {
+    __shared__ uint32_t sh4[4];
+    __shared__ unsigned long long shl[4];
     const int op = group_find32(g.comb_end, g.n, blockIdx.x);
     const ColOp& t = g.op[op];
-    const int64_t c = (int64_t)(blockIdx.x - (op ? g.comb_end[op - 1] : 0)) * 256 + threadIdx.x;
+    const int b = blockIdx.x - (op ? g.comb_end[op - 1] : 0);
+    const int tid = threadIdx.x;
+    const int64_t c = (int64_t)b * 256 + tid;
     const int64_t cols_padded = t.tiles_x * 128;
+    const int64_t n_wg = (int64_t)t.n_strips * t.tiles_x;  // workgroups of the amax pass
+    uint32_t mg = 0u, mg5 = 0u;
+    if (t.derive_gam) {                                    // GAM (uniform over the workgroup)
+        uint32_t ga = 0u;
+        for (int64_t i = tid; i < n_wg; i += 256) ga = max(ga, t.wg[2 + 2 * i]);
+        ga = wave_allmax_u32(ga);
+        if ((tid & 63) == 0) sh4[tid >> 6] = ga;
+        __syncthreads();
+        ga = max(max(sh4[0], sh4[1]), max(sh4[2], sh4[3]));
+        mg = group_mantissa_bits(ga, kE4M3Max, t.mode);
+        mg5 = group_mantissa_bits(ga, kE5M2Max, t.mode);
+        if (b == 0 && tid == 0) {
+            uint32_t* gam_out = const_cast<uint32_t*>(t.gam);
+            gam_out[0] = mg; gam_out[1] = mg5;
+            if (t.gmant) { t.gmant[0] = mg; t.gmant[1] = mg5; }
+        }
+    } else if (t.mode) {
+        mg = t.gam[0]; mg5 = t.gam[1];
+    }
+    bool all_proven = false;
+    if (t.prove && t.tensor_need) {                        // uniform over the workgroup
+        unsigned long long f = 0ull;
+        for (int64_t i = tid; i < n_wg; i += 256) f += t.wg[3 + 2 * i];
+#pragma unroll
+        for (int m = 32; m > 0; m >>= 1) f += __shfl_xor(f, m, 64);
+        if ((tid & 63) == 0) shl[tid >> 6] = f;
+        __syncthreads();
+        f = (shl[0] + shl[1]) + (shl[2] + shl[3]);
+        all_proven = f >= t.tensor_need;
+        if (b == 0 && tid == 0) t.wg[0] = all_proven ? 1u : 0u;
+    }
     if (c >= cols_padded) return;
     uint32_t a = 0u;
 #pragma unroll 8
@@ -972,14 +1031,16 @@ __global__ __launch_bounds__(256) void k_col_scales(GroupCol g) {
         t.col_amin[c] = (uint16_t)mn;
     }
     if (t.prove) {
-        const uint16_t* __restrict__ part_flush = reinterpret_cast<const uint16_t*>(t.part_err);
-        uint32_t fl = 0u;
+        if (t.tensor_need) {
+            t.col_proven[c] = (c < t.cols && all_proven) ? 1 : 0;
+        } else {
+            const uint16_t* __restrict__ part_flush = reinterpret_cast<const uint16_t*>(t.part_err);
+            uint32_t fl = 0u;
 #pragma unroll 8
-        for (int sidx = 0; sidx < t.n_strips; ++sidx) fl += part_flush[sidx * cols_padded + c];
-        t.col_proven[c] = (c < t.cols && fl >= t.flush_need) ? 1 : 0;
+            for (int sidx = 0; sidx < t.n_strips; ++sidx) fl += part_flush[sidx * cols_padded + c];
+            t.col_proven[c] = (c < t.cols && fl >= t.flush_need) ? 1 : 0;
+        }
     }
-    uint32_t mg = 0u, mg5 = 0u;
-    if (t.mode) { mg = t.gam[0]; mg5 = t.gam[1]; }
     const float s = block_scale(a, kE4M3Max, t.mode, mg);
     t.col_scale[c] = s;
     t.col_scale5[c] = block_scale(a, kE5M2Max, t.mode, mg5);
@@ -1217,7 +1278,7 @@ struct ColPlan {
     int32_t tiles_per_strip;
     int n_strips;
     int64_t cols_padded;
-    size_t off_amax, off_err, off_err5, off_zero, off_scale, off_scale5, off_amin, off_proven, bytes;
+    size_t off_amax, off_err, off_err5, off_zero, off_scale, off_scale5, off_amin, off_proven, off_wg, bytes;
 };
 ColPlan plan_columns(int64_t rows, int64_t cols) {
     ColPlan pl;
@@ -1238,6 +1299,7 @@ ColPlan plan_columns(int64_t rows, int64_t cols) {
     pl.off_scale5 = off; off = align16p(off + 4 * (size_t)pl.cols_padded);
     pl.off_amin = off; off = align16p(off + 2 * (size_t)pl.cols_padded);
     pl.off_proven = off; off = align16p(off + (size_t)pl.cols_padded);
+    pl.off_wg = off; off = align16p(off + 4 * (2 + 2 * (size_t)pl.n_strips * (size_t)tiles_x));
     pl.bytes = off;
     return pl;
 }
@@ -1264,6 +1326,9 @@ void launch_col_kind(const GroupCol& g, int64_t total, int crit, bool fake, bool
 bool col_needs_edge(const BatchItem& it) { return it.sh.rows % 128 != 0 || it.sh.cols % 128 != 0; }
 }  // namespace
 
+uint32_t* column_tensor_proven_word(char* ws, int64_t rows, int64_t cols) {
+    return reinterpret_cast<uint32_t*>(ws + plan_columns(rows, cols).off_wg);
+}
 size_t column_workspace_bytes(int64_t rows, int64_t cols) { return plan_columns(rows, cols).bytes; }
 
 // 128 x 1 sub-columns: grouped, one pass.
@@ -1350,8 +1415,12 @@ hipError_t launch_channel_col_items(const BatchItem* items, const int* idx, int 
             t.col_scale5 = reinterpret_cast<float*>(w + pl.off_scale5);
             t.col_amin = reinterpret_cast<uint16_t*>(w + pl.off_amin);
             t.col_proven = reinterpret_cast<uint8_t*>(w + pl.off_proven);
-            t.prove = (crit == kCritEq2 && it.o.bf16 && !it.o.fake && !it.three && it.scope != 1 && it.th > 0.0f && it.th < 0.9f) ? 1 : 0;
+            t.prove = (crit == kCritEq2 && it.o.bf16 && !it.o.fake && !it.three && it.th > 0.0f && it.th < 0.9f) ? 1 : 0;
             t.flush_need = (uint32_t)(1.01 * (double)it.th * (double)it.sh.rows) + 1u;      // 1 % margin covers the binary32 sums
+            t.tensor_need = it.scope == 1 ? (unsigned long long)(1.01 * (double)it.th * (double)(it.sh.rows * it.sh.cols)) + 1ull : 0ull;
+            t.wg = reinterpret_cast<uint32_t*>(w + pl.off_wg);
+            t.derive_gam = it.scaling == kScaleGam ? 1 : 0;
+            t.gmant = it.o.gmant;
             total += units;
             comb += (int)((pl.cols_padded + 255) / 256);
             copy += (int)(tiles_x * kColCopyRowGroups);          // upper bound, for the overflow check above; set in flush()

@@ -289,3 +289,32 @@ def test_gam_tensor_level_proof_with_a_dirty_workspace_and_in_a_graph():
         scrub()
         B.mor_analyze_quantize_batch(items, 1e-5, ws)       # eager work between the replays
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("scaling", ["fp32_amax", "gam", "e8m0"])
+@pytest.mark.parametrize("frac", [0.0, 0.04, 0.2])
+@pytest.mark.parametrize("shape,pad,ragged", [((1280, 384), 0, False), ((700, 264), 8, True), ((2304, 128), 0, False)])
+def test_per_channel_columns_tensor_level_decision(scaling, frac, shape, pad, ragged):
+    """Per-channel columns with a tensor-level decision (the second GEMM operand of the per-channel strategy, Section
+    4.1.1): under GAM the group mantissa comes out of the column-amax pass (no pre-pass), and with enough certain
+    flushes over all columns the quantize pass writes the BF16 fallback itself.  Every output equals the oracle's."""
+    rows, cols = shape
+    x = _with_tiny(rows, cols, frac, 90 + int(frac * 100))
+    xb = np.zeros((rows, cols + pad), np.uint16)
+    xb[:, :cols] = W.f32_to_bf16_bits(x)
+    r = parity.compare(xb, "channel_col", "tensor", "mean_rel_err", 0.045, cols=cols, label=f"columns tensor-level frac={frac}",
+                       scaling=scaling, ragged=ragged)
+    assert r["n_bf16"] == (r["P"] if frac > 0 else 0)
+    f = parity.compare_fake(xb, "channel_col", "tensor", "mean_rel_err", 0.045, cols=cols, label="columns tensor-level fake",
+                            scaling=scaling, ragged=ragged)
+    assert f["n_bf16"] == r["n_bf16"] and f["n_mismatch"] == 0
+
+
+def test_per_channel_columns_tensor_level_proof_uses_each_columns_own_amax():
+    """Columns of small values only do not flush; a bound taken from the operand's amax would prove a BF16 decision that
+    the error sums do not support."""
+    x = _with_tiny(512, 256, 0.0, 35)
+    x[:, 1:] *= np.float32(2.0 ** -30)
+    x[np.random.default_rng(36).random(512) < 0.5, 0] = np.float32(2.0 ** -30)      # half of one column flushes
+    r = parity.compare(W.f32_to_bf16_bits(x), "channel_col", "tensor", "mean_rel_err", 0.045, label="columns own amax", scaling="gam")
+    assert r["n_bf16"] == 0
