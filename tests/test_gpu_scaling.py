@@ -107,7 +107,7 @@ def test_scaling_batch_mixes_modes():
 
 
 @pytest.mark.parametrize("scaling", SCALINGS)
-@pytest.mark.parametrize("gran", ["sub1x128", "block128", "tensor"])
+@pytest.mark.parametrize("gran", ["sub1x128", "block128", "tensor", "channel_row", "channel_col", "sub128x1", "block64"])
 def test_dequantize_from_stored_scale_form(oracle, scaling, gran):
     xb = spread(W.gradient(256, 512, 61, tiny_half=True), 4)
     params, g = parity.run_gpu(xb, gran, scaling=scaling)
