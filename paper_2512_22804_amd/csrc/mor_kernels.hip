@@ -349,6 +349,25 @@ __global__ __launch_bounds__(256) void k_tensor_finish(TensorPartials tp, int n_
     }
 }
 
+// Copies `n_chunks` 16-byte chunks from x to dst with workgroup `b` of `nb`: tiles of 1024 consecutive chunks (16 KB),
+// four 16-byte loads in flight per lane.
+__device__ __forceinline__ void copy_chunk_tiles(const uint16_t* __restrict__ x, uint16_t* __restrict__ dst, int64_t n_chunks, int b, int nb) {
+    const int64_t n_tiles = (n_chunks + 1023) / 1024;
+    for (int64_t ct = b; ct < n_tiles; ct += nb) {
+        const int64_t c0 = ct * 1024 + threadIdx.x;
+        if (c0 + 3 * 256 < n_chunks) {
+            u32x4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = load16(x + (c0 + u * 256) * 8);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) store16(dst + (c0 + u * 256) * 8, v[u]);
+        } else {
+            for (int u = 0; u < 4; ++u)
+                if (c0 + u * 256 < n_chunks) store16(dst + (c0 + u * 256) * 8, load16(x + (c0 + u * 256) * 8));
+        }
+    }
+}
+
 // ======================================================================================
 // Tensor-level decision over sub-tensor scaling (Section 3.1): the deferred block kernels wrote
 // err_sum / nnz per block; aggregate sum(err_sum) / sum(nnz), decide once, broadcast the mask.
@@ -424,21 +443,7 @@ __global__ __launch_bounds__(256) void k_scope_copy_group(GroupScope g) {
     const int b = blockIdx.x - (op ? g.copy_end[op - 1] : 0);
     const int nb = g.copy_end[op] - (op ? g.copy_end[op - 1] : 0);
     if (t.ld == t.cols && t.ld_bf16 == t.cols) {
-        // tiles of 1024 consecutive chunks (16 KB): four 16-byte loads in flight per lane
-        const int64_t n_chunks = t.rows * t.cols / 8, n_tiles = (n_chunks + 1023) / 1024;
-        for (int64_t ct = b; ct < n_tiles; ct += nb) {
-            const int64_t c0 = ct * 1024 + threadIdx.x;
-            if (c0 + 3 * 256 < n_chunks) {
-                u32x4 v[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) v[u] = load16(t.x + (c0 + u * 256) * 8);
-#pragma unroll
-                for (int u = 0; u < 4; ++u) store16(t.bf16 + (c0 + u * 256) * 8, v[u]);
-            } else {
-                for (int u = 0; u < 4; ++u)
-                    if (c0 + u * 256 < n_chunks) store16(t.bf16 + (c0 + u * 256) * 8, load16(t.x + (c0 + u * 256) * 8));
-            }
-        }
+        copy_chunk_tiles(t.x, t.bf16, t.rows * t.cols / 8, b, nb);
     } else {
         const int64_t cpr = t.cols / 8;
         for (int64_t r = b; r < t.rows; r += nb)
@@ -1094,23 +1099,7 @@ __global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g, Grou
         return;
     }
     if (proven || mask == 0u || t.o.bf16 == nullptr) return;
-    // copy in tiles of 1024 consecutive chunks (16 KB): four 16-byte loads in flight per lane
-    const uint16_t* __restrict__ x = t.x;
-    uint16_t* __restrict__ dst = t.o.bf16;
-    const int64_t n_ctiles = (t.n_chunks + 1023) / 1024;
-    for (int64_t ct = b; ct < n_ctiles; ct += nb) {
-        const int64_t c0 = ct * 1024 + threadIdx.x;
-        if (c0 + 3 * 256 < t.n_chunks) {
-            u32x4 v[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) v[u] = load16(x + (c0 + u * 256) * 8);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) store16(dst + (c0 + u * 256) * 8, v[u]);
-        } else {
-            for (int u = 0; u < 4; ++u)
-                if (c0 + u * 256 < t.n_chunks) store16(dst + (c0 + u * 256) * 8, load16(x + (c0 + u * 256) * 8));
-        }
-    }
+    copy_chunk_tiles(t.x, t.o.bf16, t.n_chunks, b, nb);
 }
 
 // Group loop of Algorithm 1 for sub-tensor operands: the operand's amax (partials of pass A) gives the
