@@ -80,6 +80,13 @@ __device__ __forceinline__ uint32_t pk_sub_u16(uint32_t a, uint32_t b) {
 __device__ __forceinline__ uint32_t pk_add_u16(uint32_t a, uint32_t b) {
     return __builtin_bit_cast(uint32_t, (u16x2)(__builtin_bit_cast(u16x2, a) + __builtin_bit_cast(u16x2, b)));
 }
+// Certain flushes among the two BF16 values of `word`, given the packed bound t - 1 where t is a lower bound of the block's
+// amax pattern taken down by 20 binades (0 if that underflows): 1 <= m < t  <=>  m - 1 < t - 1, and m - 1 wraps to 0xFFFF
+// for zeros, which never count.  Returns 0 or 1 in each half-word.
+__device__ __forceinline__ uint32_t pk_certain_flush(uint32_t word, uint32_t bound_m1_2) {
+    const uint32_t mm1 = pk_sub_u16(word & 0x7FFF7FFFu, 0x00010001u);
+    return pk_min_u16(pk_sub_sat_u16(bound_m1_2, mm1), 0x00010001u);
+}
 __device__ __forceinline__ void scan8(const u32x4& raw, Scan8& sc) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {

@@ -414,8 +414,7 @@ __device__ __forceinline__ void prove_tiles(const ProveOp& t, int b, int nb, uin
             abits[0] = abits[1] = wave_allmax_u32(fold_max16(a2[0]));
         }
         amax_run = max(amax_run, max(abits[0], abits[1]));
-        // certain flush: 1 <= m < t  <=>  m - 1 < t - 1, with t the amax pattern taken down by 20 binades (0 if that
-        // underflows); m - 1 wraps to 0xFFFF for zeros, which never count
+        // t - 1, with t the amax pattern taken down by 20 binades (0 if that underflows)
         uint32_t bound2[2];
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -426,10 +425,7 @@ __device__ __forceinline__ void prove_tiles(const ProveOp& t, int b, int nb, uin
 #pragma unroll
         for (int i = 0; i < kChunks; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t mm1 = pk_sub_u16(cur[i][j] & 0x7FFF7FFFu, 0x00010001u);
-                f2 = pk_add_u16(f2, pk_min_u16(pk_sub_sat_u16(bound2[i / (kChunks / 2)], mm1), 0x00010001u));
-            }
+            for (int j = 0; j < 4; ++j) f2 = pk_add_u16(f2, pk_certain_flush(cur[i][j], bound2[i / (kChunks / 2)]));
         flush_run += fold_add16(f2);                       // at most 64 per tile and lane
 #pragma unroll
         for (int i = 0; i < kChunks; ++i) cur[i] = nxt[i];
@@ -662,14 +658,10 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
                     }
                     __syncthreads();                                   // sh.amax is written again when the strip is published
                 }
-                // certain flush: 1 <= m < t  <=>  m - 1 < t - 1 (m - 1 wraps to 0xFFFF for zeros, which never count)
 #pragma unroll
                 for (int i = 0; i < kChunks; ++i)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const uint32_t mm1 = pk_sub_u16(raw[i][j] & 0x7FFF7FFFu, 0x00010001u);
-                        flush2[j] = pk_add_u16(flush2[j], pk_min_u16(pk_sub_sat_u16(bound2[j], mm1), 0x00010001u));
-                    }
+                    for (int j = 0; j < 4; ++j) flush2[j] = pk_add_u16(flush2[j], pk_certain_flush(raw[i][j], bound2[j]));
             }
             continue;
         }
