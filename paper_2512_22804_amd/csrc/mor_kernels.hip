@@ -1379,7 +1379,7 @@ void BatchRun::group_mantissas() {
             if (pv_part[i]) {
                 q.amax_part = pv_part[i]; q.n_amax = pv_wg[i];
                 q.flush_part = pv_flush[i];
-                q.flush_need = (unsigned long long)(1.01 * (double)it.th * (double)(it.sh.rows * it.sh.cols)) + 1ull;   // binary32 sums
+                q.flush_need = flush_need_of(it.th, it.sh.rows * it.sh.cols);
                 continue;
             }
             uint32_t* part = reinterpret_cast<uint32_t*>(carve(2 * sizeof(uint32_t) * kProveMaxWg));
@@ -1628,8 +1628,8 @@ void BatchRun::per_tensor_operands(int crit) {
                 t.abits = reinterpret_cast<uint32_t*>(w + pl.off_decision);
                 t.flush_part = reinterpret_cast<uint32_t*>(w + pl.off_flush_part);
                 t.flush_need = 0ull;
-                if (crit == kCritEq2 && it.o.bf16 && !it.three && it.th > 0.0f && it.th < 0.9f)      // 1 % margin over th * N covers the
-                    t.flush_need = (unsigned long long)(1.01 * (double)it.th * (double)(it.sh.rows * it.sh.cols)) + 1ull;   // binary32 sums
+                if (crit == kCritEq2 && it.o.bf16 && !it.three && it.th > 0.0f && it.th < 0.9f)
+                    t.flush_need = flush_need_of(it.th, it.sh.rows * it.sh.cols);
                 t.stats = static_cast<StatsDev*>(it.stats);
                 a_end += t.n_amax; s_end += t.n_slots;
                 c_end += (it.o.bf16 || it.three) ? share(t.n_tiles, total_tiles, 2048, 2048) : 1;

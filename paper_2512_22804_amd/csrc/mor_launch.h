@@ -126,6 +126,11 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
 // mor_partitions.hip: team kernels (64x64, per-channel rows, general 128x128) and column kernels
 enum { kCritEq2 = 0, kCritEq3 = 1 };
 
+// That many elements certain to flush (each contributes exactly 1 to the error sum of Eq. 2) prove "mean relative error
+// >= th" for a block of `n` elements, whatever the other terms are: the 1 % margin over th * n covers the rounding of the
+// binary32 error sums that the decision itself is taken from.  Only used for 0 < th < 0.9.
+inline unsigned long long flush_need_of(float th, int64_t n) { return (unsigned long long)(1.01 * (double)th * (double)n) + 1ull; }
+
 // Tensor-level decision (Section 3.1) over GAM-scaled 128 x 128 / 64 x 64 blocks or per-channel rows: the amax pre-pass of
 // Algorithm 1 can prove the BF16 decision under Eq. 2 from elements that are certain to flush inside their block, so
 // the block kernel writes the BF16 payload from its registers and the operand is not read a third time.

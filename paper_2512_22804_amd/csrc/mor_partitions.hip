@@ -1408,8 +1408,8 @@ hipError_t launch_channel_col_items(const BatchItem* items, const int* idx, int 
             t.col_amin = reinterpret_cast<uint16_t*>(w + pl.off_amin);
             t.col_proven = reinterpret_cast<uint8_t*>(w + pl.off_proven);
             t.prove = (crit == kCritEq2 && it.o.bf16 && !it.o.fake && !it.three && it.th > 0.0f && it.th < 0.9f) ? 1 : 0;
-            t.flush_need = (uint32_t)(1.01 * (double)it.th * (double)it.sh.rows) + 1u;      // 1 % margin covers the binary32 sums
-            t.tensor_need = it.scope == 1 ? (unsigned long long)(1.01 * (double)it.th * (double)(it.sh.rows * it.sh.cols)) + 1ull : 0ull;
+            t.flush_need = (uint32_t)flush_need_of(it.th, it.sh.rows);
+            t.tensor_need = it.scope == 1 ? flush_need_of(it.th, it.sh.rows * it.sh.cols) : 0ull;
             t.wg = reinterpret_cast<uint32_t*>(w + pl.off_wg);
             t.derive_gam = it.scaling == kScaleGam ? 1 : 0;
             t.gmant = it.o.gmant;
