@@ -201,8 +201,9 @@ size_t mor_workspace_bytes(const mor_params* params);
  *   out        host struct of device pointers, see mor_outputs
  *   workspace  device scratch of at least mor_workspace_bytes(params) bytes, 16-byte aligned;
  *              may be NULL when that size is 0
- * One fused pass for sub-tensor granularities; per-tensor granularity needs the global amax
- * first and therefore reads x twice.  Concurrent calls must not share a workspace.
+ * One fused pass for the granularities whose blocks fit a workgroup; per-tensor granularity and
+ * per-channel columns need an amax that spans the operand first and therefore read x twice, and so do
+ * sub-tensor blocks under GAM scaling (group amax of Algorithm 1).  Concurrent calls must not share a workspace.
  */
 mor_status mor_analyze_quantize(const mor_params* params, const uint16_t* x, const mor_outputs* out,
                                 void* workspace, size_t workspace_bytes, void* stream);
