@@ -372,9 +372,9 @@ __device__ __forceinline__ void copy_chunk_tiles(const uint16_t* __restrict__ x,
 // Tensor-level decision over sub-tensor scaling (Section 3.1): the deferred block kernels wrote
 // err_sum / nnz per block; aggregate sum(err_sum) / sum(nnz), decide once, broadcast the mask.
 // ======================================================================================
-// Grouped: every operand with a tensor-level decision shares three launches -- partial sums per workgroup, decision
+// Grouped: every operand with a tensor-level decision shares two launches -- partial sums per workgroup, then the decision
 // (re-derived by every workgroup of the operand from the partials in a fixed order, so all agree) with the mask
-// broadcast, and the conditional copy of the BF16 fallback.
+// broadcast and the conditional copy of the BF16 fallback.
 constexpr int kScopeBlocks = 256;       // partial records per operand
 constexpr int kMaxGroupScope = 16;
 struct ScopeOp {
@@ -425,23 +425,19 @@ __device__ __forceinline__ uint32_t scope_decision(const ScopeOp& t, double* shd
     if (t.crit == kCritEq3) return (e < e5) ? 0u : 1u;
     return ((n ? e / (double)n : 0.0) < (double)t.th) ? 0u : 1u;
 }
-__global__ __launch_bounds__(256) void k_scope_decide_group(GroupScope g) {
+// Decision (every workgroup re-derives it from the partial records: the same value everywhere), mask broadcast over the
+// operand's workgroups, then the copy of a BF16 tensor that no earlier pass has proven and written.
+__global__ __launch_bounds__(256) void k_scope_copy_group(GroupScope g) {
     __shared__ double shd[4];
     __shared__ unsigned long long shl[4];
-    const int op = group_find32(g.red_end, g.n, blockIdx.x);
-    const ScopeOp& t = g.op[op];
-    const int b = blockIdx.x - (op ? g.red_end[op - 1] : 0);
-    const uint32_t m = scope_decision(t, shd, shl);
-    if (b == 0 && threadIdx.x == 0) t.decision[0] = m;
-    const int64_t stride = (int64_t)t.n_red * 256;
-    for (int64_t p = (int64_t)b * 256 + threadIdx.x; p < t.n_part; p += stride) t.mask[p] = (uint8_t)m;
-}
-__global__ __launch_bounds__(256) void k_scope_copy_group(GroupScope g) {
     const int op = group_find32(g.copy_end, g.n, blockIdx.x);
     const ScopeOp& t = g.op[op];
-    if (t.bf16 == nullptr || t.decision[0] == 0u || (t.proven && t.proven[0] != 0u)) return;
     const int b = blockIdx.x - (op ? g.copy_end[op - 1] : 0);
     const int nb = g.copy_end[op] - (op ? g.copy_end[op - 1] : 0);
+    const uint32_t m = scope_decision(t, shd, shl);
+    if (b == 0 && threadIdx.x == 0) t.decision[0] = m;
+    for (int64_t p = (int64_t)b * 256 + threadIdx.x; p < t.n_part; p += (int64_t)nb * 256) t.mask[p] = (uint8_t)m;
+    if (t.bf16 == nullptr || m == 0u || (t.proven && t.proven[0] != 0u)) return;
     if (t.ld == t.cols && t.ld_bf16 == t.cols) {
         copy_chunk_tiles(t.x, t.bf16, t.rows * t.cols / 8, b, nb);
     } else {
@@ -1542,7 +1538,6 @@ void BatchRun::tensor_level_decisions() {
     auto flush = [&]() {
         if (g.n == 0) return;
         { ProfScope ps(prof, kKernScopeReduce, st); k_scope_reduce_group<<<dim3(red), dim3(256), 0, st>>>(g); }
-        { ProfScope ps(prof, kKernScopeDecide, st); k_scope_decide_group<<<dim3(red), dim3(256), 0, st>>>(g); }
         { ProfScope ps(prof, kKernFallbackCopy, st); k_scope_copy_group<<<dim3(copy), dim3(256), 0, st>>>(g); }
         g.n = 0; red = 0; copy = 0;
     };
@@ -1567,7 +1562,10 @@ void BatchRun::tensor_level_decisions() {
         t.x = it.x; t.bf16 = it.o.bf16;
         t.rows = it.sh.rows; t.cols = it.sh.cols; t.ld = it.sh.ld; t.ld_bf16 = it.o.ld_bf16;
         red += t.n_red;
-        copy += it.o.bf16 ? share(it.sh.rows * it.sh.cols, total_elems, 4096, 4096) : 1;
+        {   // workgroups of the decision / mask / copy launch: enough for the copy, and never fewer than the reduce pass had
+            const int c = it.o.bf16 ? share(it.sh.rows * it.sh.cols, total_elems, 4096, 4096) : 1;
+            copy += c > t.n_red ? c : t.n_red;
+        }
         g.red_end[g.n] = red; g.copy_end[g.n] = copy;
         if (++g.n == kMaxGroupScope) flush();
     }
