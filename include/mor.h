@@ -106,9 +106,9 @@ typedef enum {
 
 /* How the per-block scale is formed. */
 typedef enum {
-    MOR_SCALE_FP32_AMAX = 0,    /* s = fl32(448 / amax), "standard per-block FP32 amax scaling"
-                                   (Section 4.1.2).  amax == 0 -> s = 1; an overflowing quotient
-                                   -> s = FLT_MAX; non-finite amax -> s = 1. */
+    MOR_SCALE_FP32_AMAX = 0,    /* s = fl32(448 / amax): one binary32 scale per block straight from its amax
+                                   (first scaling variant of the ablation in Section 4.1.2).  amax == 0 -> s = 1;
+                                   an overflowing quotient -> s = FLT_MAX; non-finite amax -> s = 1. */
     MOR_SCALE_GAM = 1,          /* Group Amax Mantissa scaling (Algorithm 1) with one group = the whole
                                    operand: s_g = fl32(448 / amax of the operand), m_g = its mantissa;
                                    per block s_b as above, e = exponent(s_b), lowered by one when

@@ -13,8 +13,8 @@
  *     Section 3, first paragraph;
  *   - amax = max(abs(b)) and scale = q_amax / amax: Algorithm 1, the two
  *     assignments at the top of the group loop and of the block loop, used
- *     here in their plain FP32 form (the "standard per-block FP32 amax
- *     scaling" of the ablation in Section 4.1.2);
+ *     here in their plain form, one binary32 scale per block straight from
+ *     its amax (the first scaling variant of the ablation in Section 4.1.2);
  *   - E4M3 / E5M2 value sets, saturation and underflow: Section 1 (format
  *     widths) and Section 2, first paragraph (ranges 2^-9..448, 2^-16..57344,
  *     clipping large values, flushing small ones to zero);
@@ -53,7 +53,13 @@
  *   R8  Eq. (3) is strict: a tie selects BF16.
  *   R9  a block holding Inf or NaN: amax = that pattern, s = 1, codes by R3,
  *       error sums = +inf, selection = BF16.
- *   R10 de-scaling multiplies by s_inv = fl32(1 / s), then rounds to BF16 RNE.
+ *   R10 de-scaling multiplies by s_inv = fl32(1 / s), then rounds to BF16 RNE
+ *       (the paper only says the values are de-scaled to their original range;
+ *       a division by s would round differently on some elements).
+ *   R4b the tensor-wide decision under Eq. (3) compares the two totals,
+ *       sum of block err_sum < sum of block err5_sum.  This is an extension:
+ *       the paper states Eq. (3) per block (Section 3.2) and the aggregation
+ *       of local errors for Eq. (2) only (Section 3.1).
  *   R16 GAM (Algorithm 1) is run with one group = the whole tensor, the
  *       configuration of the paper's experiments (Section 2, the paragraph
  *       after the algorithm's description).  mantissa(s) and exponent(s) are
@@ -83,10 +89,12 @@
  *   R21 fake quantization (Section 4, Figure 4) is de-quantize(quantize(x)):
  *       BF16 in, BF16 out; blocks kept in BF16 pass through unchanged.
  *
- * parity unpinned: R8 (tie handling), R9 (non-finite policy), R17 (which
- * power of two the E8M0 ablation uses), R19 (zeros in the minimum of Eq. (4))
- * and R20 (ragged edges) are fixed by these readings only; nothing in the paper
- * pins them.
+ * parity unpinned: R8 (tie handling), R9 (non-finite policy), R10 (product with
+ * the rounded reciprocal rather than a quotient), R4b (Eq. (3) over a whole
+ * tensor), R17 (which power of two the E8M0 ablation uses), R19 (zeros in the
+ * minimum of Eq. (4)) and R20 (ragged edges) are fixed by these readings only;
+ * nothing in the paper pins the CHOICE.  The arithmetic of each reading is
+ * pinned by the CPU tests (exact-rational model, hand-worked blocks).
  */
 #include <float.h>
 #include <math.h>

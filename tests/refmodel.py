@@ -2,7 +2,8 @@
 arithmetic (``fractions``), for tiny inputs.  Independent of both the C oracle and the HIP path:
 it is written directly from the format definitions (Section 1-2 of the paper) and Eq. (1)-(3).
 Only the two binary32 roundings the method fixes (scale = fl32(q_amax/amax), y = fl32(x*s)) use
-numpy float32 as a library primitive."""
+numpy float32 as a library primitive; the de-quantize / de-scale half (Section 4, Figure 4) does every
+rounding (binary32 and BF16) in exact rationals."""
 from fractions import Fraction
 import bisect
 import math
@@ -154,4 +155,66 @@ def analyze_block(bits, crit="mean_rel_err", threshold=0.045, scaling="fp32_amax
         if fits:
             s5, codes5, _ = run(57344.0, 5, 2)
             out.update(choice="e5m2", scale=s5, codes=codes5)
+    return out
+
+
+# ---------------------------------------------------------------- de-quantize / de-scale (Section 4, Figure 4)
+
+def round_to_binary(v, sig_bits, emin, emax):
+    """Exact round-to-nearest-even of the rational ``v`` to a binary floating-point grid with ``sig_bits``
+    significant bits, smallest normal exponent ``emin`` (values below 2^emin sit on the subnormal grid
+    2^(emin - sig_bits + 1)) and largest exponent ``emax`` (beyond it: infinity).  Returns a Fraction, or
+    +-math.inf.  Written from the IEEE-754 definition; no floating-point arithmetic is used."""
+    v = Fraction(v)
+    if v == 0:
+        return Fraction(0)
+    sign = -1 if v < 0 else 1
+    a = abs(v)
+    _, e = _mant_exp(a)
+    e = max(e, emin)
+    ulp = Fraction(2) ** (e - (sig_bits - 1))
+    n = a / ulp                                     # position on the grid of this binade
+    lo = n.numerator // n.denominator
+    rem = n - lo
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and lo % 2 == 1):
+        lo += 1
+    r = lo * ulp
+    if r >= Fraction(2) ** (emax + 1):
+        return sign * math.inf
+    return sign * r
+
+
+def fl32(v):
+    """binary32 rounding of a rational."""
+    return round_to_binary(v, 24, -126, 127)
+
+
+def bf16_rne_bits(v):
+    """BF16 bit pattern (8 significant bits, binary32's exponent range) of the rational ``v``, round to nearest even.
+    ``negative_zero`` cannot be expressed by a Fraction: callers pass the sign separately when v == 0."""
+    r = round_to_binary(v, 8, -126, 127)
+    if r in (math.inf, -math.inf):
+        return 0x7F80 | (0x8000 if r < 0 else 0)
+    f = np.float32(float(r))                         # exact: r is on the BF16 grid
+    assert Fraction(float(f)) == r
+    bits = int(np.array([f], np.float32).view(np.uint32)[0])
+    assert bits & 0xFFFF == 0
+    return bits >> 16
+
+
+def dequantize_block(codes, scale, ebits=4, mbits=3):
+    """De-quantize and de-scale the FP8 codes of one block: value(code) times fl32(1 / scale), rounded to binary32,
+    then to BF16 round-to-nearest-even -- every rounding done in exact rationals.  Returns BF16 bit patterns.
+    The sign of a zero result is the sign of the code (a product of a signed zero and a positive number)."""
+    s = Fraction(float(np.float32(scale)))
+    assert s > 0
+    s_inv = fl32(1 / s)
+    out = []
+    for c in codes:
+        q = fp8_decode(int(c), ebits, mbits)
+        v = fl32(q * s_inv)
+        bits = bf16_rne_bits(v)
+        if v == 0 and (int(c) & 0x80):
+            bits |= 0x8000
+        out.append(bits)
     return out
