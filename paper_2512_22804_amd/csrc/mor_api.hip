@@ -125,6 +125,7 @@ static mor_status run_batch(const mor::BatchItem* items, int n, float near_tol, 
     }
     hipError_t e = mor::launch_batch(items, n, near_tol, workspace, workspace_bytes, static_cast<hipStream_t>(stream),
                                      reinterpret_cast<mor::KProf*>(profile));
+    if (e == hipErrorOutOfMemory) return MOR_ERR_WORKSPACE;      // the launcher's own bound check on the workspace
     return e == hipSuccess ? MOR_OK : MOR_ERR_HIP;
 }
 

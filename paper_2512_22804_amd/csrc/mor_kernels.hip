@@ -1303,7 +1303,17 @@ struct BatchRun {
     int n_stats_groups = 0;
     bool riders_used = false;                    // the first statistics group went along with a per-tensor launch
 
-    char* carve(size_t bytes) { char* p = wsp + ws_off; ws_off += align16(bytes); return p; }
+    size_t ws_bytes = 0;
+    // Next `bytes` of the caller's workspace.  The phases below carve exactly what item_workspace() adds up; should the
+    // two ever drift apart, the call fails (hipErrorOutOfMemory) instead of writing beyond the workspace: once `err`
+    // is set no further kernel is launched, so the pointer returned here is never dereferenced.
+    char* carve(size_t bytes) {
+        const size_t need = align16(bytes);
+        if (err != hipSuccess || need > ws_bytes - ws_off) { if (err == hipSuccess) err = hipErrorOutOfMemory; return wsp; }
+        char* p = wsp + ws_off;
+        ws_off += need;
+        return p;
+    }
     void group_mantissas();
     void sub_tensor_operands(int crit);
     void tensor_level_decisions();
@@ -1331,7 +1341,7 @@ void BatchRun::group_mantissas() {
         int n_pv = 0;
         int64_t pv_units = 0;
         auto flush = [&]() {
-            if (n_pv == 0) return;
+            if (n_pv == 0 || err != hipSuccess) { n_pv = 0; pv_units = 0; return; }
             for (int j = 0; j < n_pv; ++j) {
                 const int64_t units = scope_proof_units(items[pv_item[j]]);
                 // twelve operands, 128x128: 0.577 ms per pass at 2048 workgroups in all, 0.564 ms at 4096 and at 8192
@@ -1355,7 +1365,7 @@ void BatchRun::group_mantissas() {
         }
         flush();
     }
-    for (int base = 0; base < cnt; base += kMaxGroupTensor) {
+    for (int base = 0; base < cnt && err == hipSuccess; base += kMaxGroupTensor) {
         const int m = cnt - base < kMaxGroupTensor ? cnt - base : kMaxGroupTensor;
         GroupGam gg; gg.n = m;
         GroupTensor ga; ga.n = 0; ga.near_tol = near_tol;
@@ -1389,7 +1399,7 @@ void BatchRun::group_mantissas() {
                 t.amax_part = part;
                 total_tiles += t.n_tiles;
                 slot_of[k] = ga.n++;
-            } else {
+            } else if (err == hipSuccess) {
                 q.n_amax = (int)(it.sh.rows < kMaxAmaxBlocks ? it.sh.rows : kMaxAmaxBlocks);
                 ProfScope ps(prof, kKernGroupAmax, st);
                 k_tensor_amax_strided<<<dim3(q.n_amax), dim3(256), 0, st>>>(it.x, it.sh, part, 0u);
@@ -1404,6 +1414,7 @@ void BatchRun::group_mantissas() {
         }
         for (int k = 0; k < m; ++k)
             if (slot_of[k] >= 0) gg.op[k].n_amax = ga.op[slot_of[k]].n_amax;
+        if (err != hipSuccess) return;
         if (ga.n) {
             GroupStats none; none.n = 0; none.near_tol = near_tol;
             ProfScope ps(prof, kKernGroupAmax, st);
@@ -1428,7 +1439,7 @@ void BatchRun::sub_tensor_operands(int crit) {
         GroupSub g; g.n = 0;
         int64_t total = 0;
         auto flush = [&]() {
-            if (g.n == 0) return;
+            if (g.n == 0 || err != hipSuccess) { g.n = 0; total = 0; return; }
             int64_t blocks = (total + 3) / 4;
             if (blocks > kSubFlatMaxBlocks) blocks = kSubFlatMaxBlocks;
             ProfScope ps(prof, kKernSub1x128, st);
@@ -1471,7 +1482,7 @@ void BatchRun::sub_tensor_operands(int crit) {
                 to.scale += n_full; to.amax += n_full; to.err_sum += n_full; to.nnz += n_full; to.mask += n_full;
                 if (to.err5_sum) to.err5_sum += n_full;
                 if (to.e8m0) to.e8m0 += n_full;
-                err = launch_sub1x128(it.x + n_full * 128, ts, to, crit, it.scope == 1, it.th, (uint32_t)it.scaling, gam_of[i], 0u, st, nullptr);
+                if (err == hipSuccess) err = launch_sub1x128(it.x + n_full * 128, ts, to, crit, it.scope == 1, it.th, (uint32_t)it.scaling, gam_of[i], 0u, st, nullptr);
             }
         }
         flush();
@@ -1527,7 +1538,7 @@ void BatchRun::sub_tensor_operands(int crit) {
                 col_ws[i] = ws_of[cnt];
                 idx[cnt++] = i;
             }
-        if (cnt) err = launch_channel_col_items(items, idx, cnt, crit, gam_of, ws_of, st, prof);
+        if (cnt && err == hipSuccess) err = launch_channel_col_items(items, idx, cnt, crit, gam_of, ws_of, st, prof);
     }
 }
 
@@ -1536,7 +1547,7 @@ void BatchRun::tensor_level_decisions() {
     GroupScope g; g.n = 0;
     int red = 0, copy = 0;
     auto flush = [&]() {
-        if (g.n == 0) return;
+        if (g.n == 0 || err != hipSuccess) { g.n = 0; red = 0; copy = 0; return; }
         { ProfScope ps(prof, kKernScopeReduce, st); k_scope_reduce_group<<<dim3(red), dim3(256), 0, st>>>(g); }
         { ProfScope ps(prof, kKernFallbackCopy, st); k_scope_copy_group<<<dim3(copy), dim3(256), 0, st>>>(g); }
         g.n = 0; red = 0; copy = 0;
@@ -1600,7 +1611,7 @@ void BatchRun::per_tensor_operands(int crit) {
         int idx[kMaxGroupTensor];
         int cnt = 0;
         auto flush = [&]() {
-            if (cnt == 0) return;
+            if (cnt == 0 || err != hipSuccess) { cnt = 0; return; }
             GroupTensor g; g.n = cnt; g.near_tol = near_tol;
             int64_t total_tiles = 0;
             for (int k = 0; k < cnt; ++k) {
@@ -1633,6 +1644,7 @@ void BatchRun::per_tensor_operands(int crit) {
                 c_end += (it.o.bf16 || it.three) ? share(t.n_tiles, total_tiles, 2048, 2048) : 1;
                 g.amax_end[k] = a_end; g.slot_end[k] = s_end; g.copy_end[k] = c_end;
             }
+            if (err != hipSuccess) { cnt = 0; return; }      // the workspace ran out while carving
             GroupStats riders; riders.n = 0; riders.near_tol = near_tol;
             int ride_partial = 0, ride_final = 0;
             if (!riders_used && n_stats_groups > 0) {
@@ -1673,7 +1685,9 @@ void BatchRun::per_tensor_operands(int crit) {
     for (int i = 0; i < n && err == hipSuccess; ++i) {
         const BatchItem& it = items[i];
         if (route[i] != kRouteTensorStrided || it.crit != crit) continue;
-        err = launch_tensor(it.x, it.sh, it.o, it.crit, it.th, (uint32_t)it.scaling, it.three ? 1u : 0u, carve(plan_tensor(it.sh.rows, it.sh.cols).bytes), st, prof);
+        char* w = carve(plan_tensor(it.sh.rows, it.sh.cols).bytes);
+        if (err != hipSuccess) return;
+        err = launch_tensor(it.x, it.sh, it.o, it.crit, it.th, (uint32_t)it.scaling, it.three ? 1u : 0u, w, st, prof);
         if (err == hipSuccess && it.stats)
             err = launch_select_stats(make_geom(it.gran, it.sh.rows, it.sh.cols), it.o.err_sum, it.o.nnz, it.o.mask, it.th, near_tol, it.stats, st);
     }
@@ -1695,16 +1709,16 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
     static_assert(sizeof(GroupSub) <= 3800 && sizeof(GroupTensor) + sizeof(GroupStats) <= 3800 &&
                   sizeof(GroupGam) <= 3800 && sizeof(GroupScope) <= 3800, "kernel-argument segment is 4 KB");
     static_assert(sizeof(StatsRec) == 128, "StatsRec layout");
-    (void)ws_bytes;                              // checked by the caller against batch_workspace_bytes()
     BatchRun run;
     run.items = items; run.n = n; run.near_tol = near_tol; run.st = st; run.prof = prof;
     run.wsp = static_cast<char*>(ws);
+    run.ws_bytes = ws_bytes;
     for (int i = 0; i < n; ++i) run.route[i] = route_of(items[i]);
     run.group_mantissas();
     for (int crit = 0; crit < 2 && run.err == hipSuccess; ++crit) run.sub_tensor_operands(crit);
-    run.tensor_level_decisions();
+    if (run.err == hipSuccess) run.tensor_level_decisions();
     // the statistics of the sub-tensor operands are collected after their kernels (and tensor-level decisions)
-    run.collect_statistics();
+    if (run.err == hipSuccess) run.collect_statistics();
     for (int crit = 0; crit < 2 && run.err == hipSuccess; ++crit) run.per_tensor_operands(crit);
     run.leftover_statistics();
     if (run.err != hipSuccess) return run.err;
