@@ -209,6 +209,21 @@ mor_status mor_analyze_quantize(const mor_params* params, const uint16_t* x, con
                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same call for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The scratch is a fixed array of
+ * MOR_STATIC_SCRATCH_BYTES inside the library's device image (one copy per GPU, held until the process ends);
+ * the call allocates and frees nothing.  Parameters whose mor_workspace_bytes() exceeds MOR_STATIC_SCRATCH_BYTES
+ * are refused with MOR_ERR_WORKSPACE and nothing is launched (per-tensor operands and tensor-level decisions of
+ * any size fit; per-channel columns up to about 2048 x 4096 elements).  Outputs are identical to
+ * mor_analyze_quantize.  Every call on one GPU shares that GPU's array: calls whose work overlaps in time on
+ * one GPU (different streams, or threads) race; calls on one stream are ordered and safe.  The first call on a
+ * device looks the array's address up (hipGetSymbolAddress, no allocation); make that call outside any capture.
+ */
+#define MOR_STATIC_SCRATCH_BYTES 1048576   /* 1 MiB */
+mor_status mor_analyze_quantize_static(const mor_params* params, const uint16_t* x, const mor_outputs* out,
+                                       void* stream);
+
+/*
  * Measurement aid: the same call, with the caller's HIP events recorded on `stream` right before
  * and after each kernel it launches, so a benchmark can time individual kernels inside its own
  * timed loop.  `profile` is a HOST struct: the caller fills `capacity` (<= MOR_PROFILE_MAX) and that many

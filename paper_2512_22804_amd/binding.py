@@ -33,6 +33,7 @@ SCOPE = {"partition": MOR_SCOPE_PARTITION, "tensor": MOR_SCOPE_TENSOR}
 SCALING = {"fp32_amax": MOR_SCALE_FP32_AMAX, "gam": MOR_SCALE_GAM, "e8m0": MOR_SCALE_E8M0}
 
 EXPORTS = ("mor_num_partitions", "mor_params_num_partitions", "mor_workspace_bytes", "mor_analyze_quantize",
+           "mor_analyze_quantize_static",
            "mor_analyze_quantize_profiled", "mor_batch_workspace_bytes", "mor_analyze_quantize_batch", "mor_fake_quantize",
            "mor_dequantize", "mor_dequantize_e8m0", "mor_dequantize_batch", "mor_select_stats", "mor_histogram_update", "mor_status_string")
 MOR_BATCH_MAX = 64
@@ -116,6 +117,8 @@ def load():
         L.mor_analyze_quantize.argtypes = [C.POINTER(MorParams), C.c_void_p, C.POINTER(MorOutputs), C.c_void_p,
                                            C.c_size_t, C.c_void_p]
         L.mor_analyze_quantize.restype = C.c_int
+        L.mor_analyze_quantize_static.argtypes = [C.POINTER(MorParams), C.c_void_p, C.POINTER(MorOutputs), C.c_void_p]
+        L.mor_analyze_quantize_static.restype = C.c_int
         L.mor_analyze_quantize_profiled.argtypes = [C.POINTER(MorParams), C.c_void_p, C.POINTER(MorOutputs), C.c_void_p,
                                                     C.c_size_t, C.c_void_p, C.POINTER(MorProfile)]
         L.mor_analyze_quantize_profiled.restype = C.c_int
@@ -235,6 +238,19 @@ def mor_analyze_quantize(params: MorParams, x: torch.Tensor, out: MorResult) -> 
                                      _stream())
     if rc != 0:
         raise MorError(rc, "mor_analyze_quantize")
+
+
+MOR_STATIC_SCRATCH_BYTES = 1 << 20
+
+
+def mor_analyze_quantize_static(params: MorParams, x: torch.Tensor, out: MorResult) -> None:
+    """The same call on the library's built-in scratch (``out.workspace`` is not used; nothing is allocated)."""
+    if not x.is_cuda:
+        raise ValueError("x must live in device memory")
+    o = _outputs_struct(out)
+    rc = load().mor_analyze_quantize_static(C.byref(params), _ptr(x), C.byref(o), _stream())
+    if rc != 0:
+        raise MorError(rc, "mor_analyze_quantize_static")
 
 
 def mor_analyze_quantize_profiled(params: MorParams, x: torch.Tensor, out: MorResult, profile: MorProfile) -> None:

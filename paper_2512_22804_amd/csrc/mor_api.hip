@@ -1,9 +1,34 @@
 // C ABI of the MoR analyse-select-quantize library: argument validation and dispatch only.
 // Every step of the path runs in the kernels of mor_kernels.hip.
+#include <mutex>
+
 #include "../../include/mor.h"
 #include "mor_launch.h"
 
+// Built-in scratch of mor_analyze_quantize_static.  Every GPU the library runs on holds its own copy of this array at
+// its own address until the process ends.  In host code the NAME of the array is only a handle for
+// hipGetSymbolAddress: it is never passed to a kernel, a copy or a fill (static_scratch() below returns the device
+// address that is).
+static __device__ __align__(256) unsigned char scratch[MOR_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+mor_status static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOR_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return MOR_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return MOR_OK;
+}
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -135,6 +160,18 @@ mor_status mor_analyze_quantize(const mor_params* p, const uint16_t* x, const mo
     mor_status st = make_item(p, x, out, nullptr, nullptr, 0, &it);
     if (st != MOR_OK) return st;
     return run_batch(&it, 1, 0.0f, workspace, workspace_bytes, stream, nullptr);
+}
+
+mor_status mor_analyze_quantize_static(const mor_params* p, const uint16_t* x, const mor_outputs* out, void* stream) {
+    mor::BatchItem it{};
+    mor_status st = make_item(p, x, out, nullptr, nullptr, 0, &it);
+    if (st != MOR_OK) return st;
+    if (mor::batch_workspace_bytes(&it, 1) > (size_t)MOR_STATIC_SCRATCH_BYTES) return MOR_ERR_WORKSPACE;
+    void* ws = nullptr;
+    st = static_scratch(&ws);
+    if (st != MOR_OK) return st;
+    // the kernels write every scratch word before they read it, so nothing of the previous call's content has to be cleared
+    return run_batch(&it, 1, 0.0f, ws, MOR_STATIC_SCRATCH_BYTES, stream, nullptr);
 }
 
 mor_status mor_analyze_quantize_profiled(const mor_params* p, const uint16_t* x, const mor_outputs* out, void* workspace,
