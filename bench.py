@@ -7,9 +7,17 @@ per-tensor; Eq. 2, th = 4.5 %) go through ONE ``mor_analyze_quantize_batch`` cal
 each operand's selection statistics, on one stream, inputs already resident in HBM.  With
 ``--per-operand`` the same work is issued as 12 ``mor_analyze_quantize`` + 12 ``mor_select_stats`` calls.
 
+Before the ``--warmup`` steps the step is run for ``--prewarm-ms`` of wall time and the JSON line says so
+(``prewarm``): after an idle period (here: the seconds of host-side data generation) the GPU's power management
+takes some tens of steps to settle -- the first handful run at full speed, the next twenty or so 5-10 % slower,
+then the time per step becomes steady -- and a short warm-up would put the timed steps exactly into that window.
+
 Prints ONE JSON line on stdout: whole-job throughput in GB/s of BF16 input, the roofline record
 of the dominant kernel (timed live with HIP events recorded by the library around each kernel),
-and the CPU oracle timed on a bounded sample of the same workload.  Everything else goes to stderr.
+one measured row per configuration of the workload list (``configs``: the single operands at full size, each
+rotated over enough buffer sets that the working set exceeds twice the 256 MB Infinity Cache), the further rows
+of the method on the sweep's operands, and the CPU oracle timed on a bounded sample of the same workload.
+Everything else goes to stderr.
 """
 from __future__ import annotations
 
@@ -32,6 +40,18 @@ THRESHOLD = 0.045
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def csrc_sha256() -> str:
+    """Hash of the kernel sources and the public header of this tree (what a rocprofv3 traffic measurement is tied to)."""
+    import hashlib
+    h = hashlib.sha256()
+    base = os.path.join(ROOT, "paper_2512_22804_amd", "csrc")
+    for f in sorted(os.listdir(base)) + [os.path.join("..", "..", "include", "mor.h")]:
+        path = os.path.join(base, f)
+        if os.path.isfile(path) and not f.endswith((".o", ".so")):
+            h.update(os.path.basename(f).encode() + b"\0" + open(path, "rb").read())
+    return h.hexdigest()[:16]
 
 
 def algorithmic_bytes(kernel: str, n_elem: int, n_part: int, fallback_frac: float, fused: bool = False) -> float:
@@ -184,6 +204,135 @@ def run_variants(ops, B, torch, dev, steps, log):
     return results
 
 
+INFINITY_CACHE_BYTES = 256 << 20
+
+
+def run_configs(B, W, torch, dev, log, target_ms=40.0):
+    """One measured row per single-operand configuration of the workload list, each at full size: cfg1 (1024x1024, per
+    tensor and 128x128: launch-latency-bound, flagged), cfg2 (activation, 1x128), cfg3 (weight, 128x128 and per tensor),
+    cfg4 (gradient, 1x128 and 128x128) and cfg4b (the gradient whose chosen sub-channels are shrunk by half: a mixed
+    mask with about 10 % fallback at 1x128).  A call = mor_analyze_quantize_batch with one item including its
+    selection statistics.  Calls rotate over `buffer_sets` distinct sets of input / output buffers so that the bytes
+    touched between two uses of a set exceed twice the Infinity Cache.  One rotation is captured in a HIP graph and
+    replayed (calls of 10-80 us with two or three launches each are otherwise bound by the host's launch calls, which is
+    reported beside it as `ms_eager_calls`); the GPU time of all replays is taken with one pair of events."""
+    cases = []
+    t0 = time.time()
+    for name, xb, gran in W.cfg1():
+        cases.append(("cfg1", xb, gran))
+    for name, xb, gran in W.cfg2():
+        cases.append(("cfg2", xb, gran))
+    for name, xb, gran in W.cfg3():
+        cases.append(("cfg3", xb, gran))
+    for name, xb, gran in W.cfg4():
+        cases.append(("cfg4", xb, gran))
+    cases.append(("cfg4b", W.cfg4(tiny_half=True)[0][1], "sub1x128"))
+    log(f"[bench] generated the single-operand configurations in {time.time() - t0:.1f}s")
+    ev = B.HipEvents()
+    rows_out = []
+    dev_cache = {}
+    for cfg, xb, gran in cases:
+        rows, cols = xb.shape
+        n = rows * cols
+        params = B.make_params(rows, cols, gran, "partition", "mean_rel_err", THRESHOLD)
+        P = B.mor_num_partitions(gran, rows, cols)
+        set_bytes = 5 * n + META_BYTES * P                       # input, FP8 payload, BF16 fallback buffer, block outputs
+        n_sets = max(2, 2 * INFINITY_CACHE_BYTES // set_bytes + 1)
+        key = id(xb)
+        if key not in dev_cache:                                 # the same host tensor serves both granularities of a config
+            dev_cache.clear()
+            x0 = torch.from_numpy(xb.view(np.int16)).to(dev)
+            dev_cache[key] = [x0] + [x0.clone() for _ in range(n_sets - 1)]
+        xs = dev_cache[key]
+        while len(xs) < n_sets:
+            xs.append(xs[0].clone())
+        sets = []
+        for k in range(n_sets):
+            out = B.alloc_outputs(params, dev, want_bf16=True)
+            out.workspace = None
+            st = torch.zeros(B.STATS_BYTES, dtype=torch.uint8, device=dev)
+            sets.append((B.make_batch([(params, xs[k], out, st)]), out, st, B.make_batch([(params, xs[k], out, None)])))
+        ws = torch.empty(max(16, B.mor_batch_workspace_bytes(sets[0][0])), dtype=torch.uint8, device=dev)
+        for entry in sets:                                        # warm-up: one rotation
+            B.mor_analyze_quantize_batch(entry[0], 1e-5, ws)
+        torch.cuda.synchronize()
+
+        def rotation(reps, which=0):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                for entry in sets:
+                    B.mor_analyze_quantize_batch(entry[which], 1e-5, ws)
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / (reps * n_sets)
+
+        def graph_rotation(reps, which=0):
+            """The same rotation captured once in a HIP graph and replayed: the launches are then issued by the GPU's command
+            processor back to back, as a training loop that captures its step would issue them.  (The library only launches
+            kernels: nothing else is recorded into the graph.)"""
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for entry in sets:
+                    B.mor_analyze_quantize_batch(entry[which], 1e-5, ws)
+            graph.replay()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                graph.replay()
+            b.record()
+            torch.cuda.synchronize()
+            t = a.elapsed_time(b) / (reps * n_sets)
+            del graph
+            return t
+
+        first = rotation(1)
+        reps = max(2, min(2000, int(target_ms / max(first * n_sets, 1e-3))))
+        ms_eager = rotation(reps)
+        ms = graph_rotation(reps)
+        ms_analyze = graph_rotation(reps, 3)                      # the same call without the selection statistics
+        # the kernels of one call, bracketed by the library's own events
+        prof = ev.new_profile(8)
+        kern = {}
+        for entry in sets[:4]:
+            B.mor_analyze_quantize_batch(entry[0], 1e-5, ws, prof)
+            torch.cuda.synchronize()
+            for k in range(prof.count):
+                kn = B.KERNEL_NAMES[prof.kernel[k]]
+                kern.setdefault(kn, []).append(ev.elapsed_ms(prof.start[k], prof.stop[k]) * 1e3)
+        kern = {k: round(sum(v) / len(v), 2) for k, v in kern.items()}
+        s = B.read_stats(sets[0][2])
+        f = s["n_elem_bf16"] / float(n)
+        fused = bool(s["flags"] & B.MOR_STATS_FLAG_FUSED_FALLBACK)
+        if gran == "tensor":
+            nbytes = sum(algorithmic_bytes(k, n, 1, f, fused) for k in ("tensor_amax", "tensor_quant", "fallback_copy"))
+        else:
+            nbytes = algorithmic_bytes("team_block", n, P, f)
+        gbs = nbytes / ms / 1e6
+        rec = {"config": cfg, "shape": [rows, cols], "granularity": gran, "elements": n, "buffer_sets": n_sets,
+               "working_set_mb": round(n_sets * set_bytes / 1e6, 1), "calls_timed": reps * n_sets, "ms": round(ms, 5),
+               "input_gbs": round(2.0 * n / ms / 1e6, 1), "algorithmic_bytes": int(nbytes),
+               "hbm_algorithmic_gbs": round(gbs, 1), "hbm_frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
+               "timing": "GPU time per call of a rotation over the buffer sets, captured in a HIP graph and replayed",
+               "ms_eager_calls": round(ms_eager, 5),       # the same rotation issued call by call from Python: host-bound when above ms
+               "ms_without_statistics": round(ms_analyze, 5),
+               "hbm_frac_of_peak_without_statistics": round(nbytes / ms_analyze / 1e6 / HBM_PEAK_GBS, 4),
+               "fp8_pct_by_elements": round(100.0 * s["n_elem_fp8"] / n, 3),
+               "fp8_pct_by_blocks": round(100.0 * s["n_fp8_part"] / s["n_part"], 3),
+               "near_threshold_blocks": s["n_near_threshold"], "mean_err": round(s["mean_err"], 6),
+               "latency_bound": bool(nbytes / (HBM_PEAK_GBS * 1e9) < 5e-6),     # under 5 us of traffic at peak: launch latency dominates
+               "kernels_us": kern}
+        log(f"[bench]   config {cfg:6s} {rows}x{cols} {gran:9s} sets={n_sets:3d} {ms * 1e3:9.1f} us/call  {rec['input_gbs']:8.1f} GB/s in  "
+            f"{gbs:8.1f} GB/s HBM ({100 * rec['hbm_frac_of_peak']:.1f} %; eager calls {ms_eager * 1e3:.1f} us; without statistics {ms_analyze * 1e3:.1f} us, "
+            f"{100 * rec['hbm_frac_of_peak_without_statistics']:.1f} %)  FP8 {rec['fp8_pct_by_elements']:.2f} % of elements  kernels {kern}")
+        rows_out.append(rec)
+        del sets, ws
+        torch.cuda.empty_cache()
+    ev.destroy()
+    return rows_out
+
+
 KERNEL_GRAN = {"sub1x128": "sub1x128", "team_block": "block128", "tensor_amax": "tensor", "tensor_quant": "tensor",
                "fallback_copy": "tensor"}
 
@@ -199,6 +348,9 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="kept for the profiling commands: the three plain 256 MiB device-to-device copies (reference for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE) are always run")
+    ap.add_argument("--prewarm-ms", type=float, default=300.0,
+                    help="run the step for this much wall time before the warm-up steps (reported as `prewarm`; 0: none)")
+    ap.add_argument("--no-configs", action="store_true", help="skip the single-operand rows (cfg1-cfg4, cfg4b)")
     ap.add_argument("--no-variants", action="store_true", help="skip the timing of the further rows (GAM, three-way, partitions, fake quantization)")
     ap.add_argument("--cpu-passes", type=int, default=0, help="oracle passes over the sample (0: repeat until 10 s of oracle time)")
     ap.add_argument("--cpu-sample-div", type=int, default=1, help="oracle is timed on the first rows/N rows of every operand")
@@ -247,6 +399,15 @@ def main() -> int:
                 B.mor_analyze_quantize_profiled(o["params"], o["x"], o["out"], profiles[i])
             B.mor_select_stats(o["params"], o["out"].err_sum, o["out"].nnz, o["out"].mask, 1e-5, o["stats"])
 
+    # reported pre-warm: bring the GPU's clocks / power state to steady state after the idle seconds of data generation
+    prewarm_steps = 0
+    t_pre = time.perf_counter()
+    while args.prewarm_ms > 0 and (time.perf_counter() - t_pre) * 1e3 < args.prewarm_ms:
+        for _ in range(10):
+            step()
+        torch.cuda.synchronize()
+        prewarm_steps += 10
+    prewarm_ms = (time.perf_counter() - t_pre) * 1e3
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -257,16 +418,21 @@ def main() -> int:
     elapsed = time.perf_counter() - t_start
     ms_per_step = elapsed / args.steps * 1e3
     value = 2.0 * n_total / (elapsed / args.steps) / 1e9
-    log(f"[bench] {args.steps} steps, {ms_per_step:.3f} ms/step, {value:.1f} GB/s of BF16 input")
+    log(f"[bench] pre-warm {prewarm_steps} steps ({prewarm_ms:.0f} ms), warm-up {args.warmup} steps; "
+        f"{args.steps} timed steps, {ms_per_step:.4f} ms/step (wall clock, mean), {value:.1f} GB/s of BF16 input")
 
-    # the same steps once more, each bracketed by its own pair of events: median and minimum step time
+    # the same steps once more, each bracketed by its own pair of events: per-step GPU times in issue order, median, minimum
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     for a, b in evs:
         a.record(); step(); b.record()
     torch.cuda.synchronize()
-    per_step = sorted(a.elapsed_time(b) for a, b in evs)
+    in_order = [a.elapsed_time(b) for a, b in evs]
+    per_step = sorted(in_order)
     ms_median, ms_min = per_step[len(per_step) // 2], per_step[0]
-    log(f"[bench] per-step GPU time: median {ms_median:.3f} ms, min {ms_min:.3f} ms")
+    ms_event_mean = sum(in_order) / len(in_order)
+    log("[bench] per-step GPU time in issue order (ms): " + " ".join(f"{t:.4f}" for t in in_order[:64]) +
+        (" ..." if len(in_order) > 64 else ""))
+    log(f"[bench] per-step GPU time: mean {ms_event_mean:.4f} ms, median {ms_median:.4f} ms, min {ms_min:.4f} ms")
 
     # plain device-to-device copy of 256 MiB in the same run: the practical ceiling of a streaming kernel on this machine
     # (with --calibrate-copy these copies also calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters)
@@ -337,14 +503,24 @@ def main() -> int:
     dom_name, dom = max(per_kernel.items(), key=lambda kv: kv[1]["ms"])
     achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
     traffic = None
+    traffic_commit = traffic_sha = None
+    tree_sha = csrc_sha256()
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath) and args.row_div == 1:
         try:
-            traffic = json.load(open(tpath)).get(dom_name, {}).get("bytes_per_launch")
+            tj = json.load(open(tpath))
+            traffic = tj.get(dom_name, {}).get("bytes_per_launch")
+            traffic_commit = tj.get("_measured_on", {}).get("commit")
+            traffic_sha = tj.get("_measured_on", {}).get("csrc_sha256")
         except Exception:
             traffic = None
+    if traffic is not None and traffic_sha != tree_sha:
+        log(f"[bench] WARNING: profiles/hbm_traffic.json was measured on kernel sources {traffic_sha} (commit {traffic_commit}), "
+            f"this tree's are {tree_sha}: roofline.traffic may be stale")
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "traffic_commit": traffic_commit, "traffic_csrc_sha256": traffic_sha, "tree_csrc_sha256": tree_sha,
+                "traffic_matches_tree": bool(traffic is not None and traffic_sha == tree_sha),
                 "avg_launch_us": round(dom["ms"] / dom["launches"] * 1e3, 2),
                 "algorithmic_bytes_per_launch": round(dom["bytes"] / dom["launches"], 1),
                 "per_kernel": {k: {"avg_us": round(r["ms"] / r["launches"] * 1e3, 2),
@@ -361,6 +537,10 @@ def main() -> int:
         else:
             step_bytes += algorithmic_bytes("team_block" if o["gran"] == "block128" else o["gran"], o["n"], o["P"], o["fallback_frac"])
     step_gbs = step_bytes / (elapsed / args.steps) / 1e9
+
+    configs = None
+    if not args.no_configs and not args.per_operand and args.row_div == 1:
+        configs = run_configs(B, W, torch, dev, log)
 
     variants = None
     if not args.no_variants and not args.per_operand:
@@ -401,6 +581,10 @@ def main() -> int:
         "metric": "GB/s of BF16 input analysed+quantized (fraction of HBM peak); FP8-selected %",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "ms_per_step_median": round(ms_median, 4), "ms_per_step_min": round(ms_min, 4),
+        "ms_per_step_event_mean": round(ms_event_mean, 4),
+        "prewarm": {"steps": prewarm_steps, "ms": round(prewarm_ms, 1),
+                    "why": "steady clocks: after the idle seconds of data generation the first ~5 steps run fast, the next ~20 "
+                           "5-10 % slower, then the step time settles; the warm-up and timed steps follow this pre-warm unchanged"},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "cfg5: operand sweep of one Llama-style 8B layer (X 8192x4096 1x128; W_qkv 6144x4096, W_o 4096x4096, "
@@ -414,6 +598,7 @@ def main() -> int:
                              "by_tensors": round(100.0 * fp8_tensors / len(ops), 3), "near_threshold_blocks": near},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
+        "configs": configs,
         "further_rows": variants,
     }
     print(json.dumps(result), flush=True)

@@ -183,6 +183,7 @@ struct TensorPartials {   // one slot per pass-B workgroup (at most kMaxQuantBlo
     uint32_t* abits;       // [0] = global amax bits, published by workgroup 0 of pass B
 };
 constexpr int kMaxQuantBlocks = 16384;
+constexpr int kSoloAmaxBlocks = 768, kSoloQuantBlocks = 1536;     // launch shape of a per-tensor operand that is alone in its launches
 
 template <typename T>
 __device__ __forceinline__ T block_sum_256(T v, T* sh) {
@@ -819,8 +820,157 @@ __device__ __forceinline__ void stats_final_body(const GroupStats& g, int op) {
                      sh.cnt[0][14], a.eb, a.e5, 0u);
 }
 
-__global__ __launch_bounds__(256) void k_stats_group_partial(GroupStats g) { stats_partial_body(g, blockIdx.x); }
-__global__ __launch_bounds__(256) void k_stats_group_final(GroupStats g) { stats_final_body(g, blockIdx.x); }
+// ---- statistics launches of their own (operands that found no per-tensor launch to ride on, e.g. a single sub-tensor
+//      operand): here the statistics are on the critical path of the call, so the kernels are built for latency --
+//      workgroups of 1024 lanes, every lane's loads in flight together, the fifteen small counters packed two per
+//      dword, wave sums through DPP, one barrier.  An operand of up to kStatsDirectParts blocks is finished by one
+//      workgroup in one launch; larger ones leave one record per workgroup for the combine launch.
+constexpr int kStatsFastThreads = 1024;
+constexpr int kStatsFastPerLane = 4;                   // blocks per lane of a partial workgroup
+constexpr int64_t kStatsDirectParts = 16384;           // one workgroup, 16 blocks per lane at most: packed 16-bit counters cannot overflow
+template <int CTRL>
+__device__ __forceinline__ unsigned long long dpp_u64(unsigned long long v) {
+    return ((unsigned long long)dpp_u32<CTRL>((uint32_t)(v >> 32)) << 32) | dpp_u32<CTRL>((uint32_t)v);
+}
+__device__ __forceinline__ unsigned long long readlane_u64(unsigned long long v, int lane) {
+    return ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(v >> 32), lane) << 32) | (uint32_t)__builtin_amdgcn_readlane((int)v, lane);
+}
+__device__ __forceinline__ unsigned long long wave_allsum_u64(unsigned long long v) {
+    v += dpp_u64<kDppXor1>(v); v += dpp_u64<kDppXor2>(v); v += dpp_u64<kDppHalfMirror>(v); v += dpp_u64<kDppMirror>(v);
+    return (readlane_u64(v, 0) + readlane_u64(v, 16)) + (readlane_u64(v, 32) + readlane_u64(v, 48));
+}
+__device__ __forceinline__ double wave_allsum_f64(double v) {      // fixed order: deterministic
+    auto sh = [](double x, auto ctrl) { return __longlong_as_double((long long)dpp_u64<decltype(ctrl)::value>((unsigned long long)__double_as_longlong(x))); };
+    v += sh(v, std::integral_constant<int, kDppXor1>{}); v += sh(v, std::integral_constant<int, kDppXor2>{});
+    v += sh(v, std::integral_constant<int, kDppHalfMirror>{}); v += sh(v, std::integral_constant<int, kDppMirror>{});
+    auto rl = [&](int lane) { return __longlong_as_double((long long)readlane_u64((unsigned long long)__double_as_longlong(v), lane)); };
+    return (rl(0) + rl(16)) + (rl(32) + rl(48));
+}
+struct StatsPacked {
+    double e;
+    unsigned long long n, eb, e5;
+    uint32_t pk[8];        // counter k of StatsAcc::cnt in half (k & 1) of pk[k >> 1]
+};
+// Totals of one workgroup: the packed per-lane counters (at most 65535 blocks per lane) are widened before they are summed.
+struct StatsTotals {
+    double e;
+    unsigned long long n, eb, e5;
+    uint32_t c[kStatCnt];
+};
+template <int WAVES>
+struct StatsFastShared {
+    double e[WAVES];
+    unsigned long long n[WAVES], eb[WAVES], e5[WAVES];
+    uint32_t c[WAVES][kStatCnt];
+};
+__device__ __forceinline__ void stats_accumulate_packed(float es, uint32_t nz, uint32_t mk, unsigned long long ne, float th, float near_tol,
+                                                        StatsPacked& a) {
+    const float metric = nz ? es / (float)nz : 0.0f;           // binary32, IEEE division
+    const int bin = stats_bin(metric);
+    const uint32_t inc = 1u << ((bin & 1) * 16);
+#pragma unroll
+    for (int k = 0; k < 6; ++k) a.pk[k] += ((bin >> 1) == k) ? inc : 0u;
+    a.e += (double)es;
+    a.n += nz;
+    a.pk[6] += (mk == 1u ? 1u : 0u) + ((fabs((double)metric - (double)th) <= (double)near_tol * (double)th) ? 0x10000u : 0u);
+    a.pk[7] += mk == 2u ? 1u : 0u;
+    if (mk == 1u) a.eb += ne;
+    if (mk == 2u) a.e5 += ne;
+}
+__device__ __forceinline__ void stats_wave_sums(StatsTotals& t) {
+    t.e = wave_allsum_f64(t.e); t.n = wave_allsum_u64(t.n); t.eb = wave_allsum_u64(t.eb); t.e5 = wave_allsum_u64(t.e5);
+#pragma unroll
+    for (int k = 0; k < kStatCnt; ++k) t.c[k] = wave_allsum_u32(t.c[k]);
+}
+// Sums over the workgroup (WAVES <= 64 waves), fixed order; the totals arrive in every lane of wave 0 (the other waves
+// return with meaningless values).
+template <int WAVES>
+__device__ __forceinline__ void stats_fast_reduce(StatsTotals& t, StatsFastShared<WAVES>& sh) {
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    stats_wave_sums(t);
+    if (lane == 0) {
+        sh.e[w] = t.e; sh.n[w] = t.n; sh.eb[w] = t.eb; sh.e5[w] = t.e5;
+#pragma unroll
+        for (int k = 0; k < kStatCnt; ++k) sh.c[w][k] = t.c[k];
+    }
+    __syncthreads();
+    if (w != 0) return;
+    const bool live = lane < WAVES;
+    const int src = live ? lane : 0;
+    t.e = live ? sh.e[src] : 0.0; t.n = live ? sh.n[src] : 0ull; t.eb = live ? sh.eb[src] : 0ull; t.e5 = live ? sh.e5[src] : 0ull;
+#pragma unroll
+    for (int k = 0; k < kStatCnt; ++k) t.c[k] = live ? sh.c[src][k] : 0u;
+    stats_wave_sums(t);
+}
+// Value k (per lane, 0 .. kStatCnt - 1) of the totals, without indexing registers dynamically.
+__device__ __forceinline__ uint32_t stats_pick(const StatsTotals& t, int k) {
+    uint32_t v = 0u;
+#pragma unroll
+    for (int j = 0; j < kStatCnt; ++j) v = k == j ? t.c[j] : v;
+    return v;
+}
+// Wave 0 writes either the operand's final statistics (`final_out`) or this workgroup's record.
+__device__ __forceinline__ void stats_emit(const StatsTotals& t, const StatsOp& op, StatsRec* rec) {
+    if (threadIdx.x >= 64) return;
+    const uint32_t mine = stats_pick(t, (int)threadIdx.x < kStatCnt ? (int)threadIdx.x : 0);
+    if (rec == nullptr) {
+        if (threadIdx.x < 12) op.out->hist[threadIdx.x] = mine;
+        if (threadIdx.x == 0)
+            stats_finish(op.out, op.n_part, (unsigned long long)(op.geom.rows * op.geom.cols), t.e, t.n, t.c[12], t.c[13], t.c[14], t.eb, t.e5, 0u);
+        return;
+    }
+    if (threadIdx.x < kStatCnt) rec->cnt[threadIdx.x] = mine;
+    if (threadIdx.x == 0) { rec->e = t.e; rec->n = t.n; rec->eb = t.eb; rec->e5 = t.e5; }
+}
+__global__ __launch_bounds__(kStatsFastThreads) void k_stats_group_partial(GroupStats g) {
+    __shared__ StatsFastShared<kStatsFastThreads / 64> sh;
+    const int op = group_find32(g.wg_end, g.n, blockIdx.x);
+    const StatsOp& t = g.op[op];
+    const int b = blockIdx.x - (op ? g.wg_end[op - 1] : 0);
+    const int nb = g.wg_end[op] - (op ? g.wg_end[op - 1] : 0);
+    StatsPacked a;
+    a.e = 0.0; a.n = 0ull; a.eb = 0ull; a.e5 = 0ull;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) a.pk[k] = 0u;
+    const int64_t stride = (int64_t)nb * kStatsFastThreads;
+    for (int64_t p0 = (int64_t)b * kStatsFastThreads + threadIdx.x; p0 < t.n_part; p0 += 4 * stride) {
+        float es[4]; uint32_t nz[4], mk[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {                          // four blocks' loads in flight per lane
+            const int64_t p = p0 + u * stride;
+            const bool ok = p < t.n_part;
+            es[u] = ok ? t.err_sum[p] : 0.0f; nz[u] = ok ? t.nnz[p] : 0u; mk[u] = ok ? (uint32_t)t.mask[p] : 3u;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (mk[u] != 3u) stats_accumulate_packed(es[u], nz[u], mk[u], mk[u] ? block_elems(t.geom, p0 + u * stride) : 0ull, t.th, g.near_tol, a);
+    }
+    StatsTotals tot;
+    tot.e = a.e; tot.n = a.n; tot.eb = a.eb; tot.e5 = a.e5;
+#pragma unroll
+    for (int k = 0; k < kStatCnt; ++k) tot.c[k] = (k & 1) ? a.pk[k >> 1] >> 16 : a.pk[k >> 1] & 0xFFFFu;
+    stats_fast_reduce(tot, sh);
+    stats_emit(tot, t, nb == 1 ? nullptr : t.rec + b);
+}
+// Combine launch: one workgroup of 256 lanes per operand, one record per lane.
+__global__ __launch_bounds__(256) void k_stats_group_final(GroupStats g) {
+    __shared__ StatsFastShared<4> sh;
+    const StatsOp& t = g.op[blockIdx.x];
+    const int nb = g.wg_end[blockIdx.x] - (blockIdx.x ? g.wg_end[blockIdx.x - 1] : 0);       // <= kStatsMaxWg = 256
+    if (nb == 1) return;                                                                       // already final
+    StatsTotals tot;
+    tot.e = 0.0; tot.n = 0ull; tot.eb = 0ull; tot.e5 = 0ull;
+#pragma unroll
+    for (int k = 0; k < kStatCnt; ++k) tot.c[k] = 0u;
+    if ((int)threadIdx.x < nb) {
+        const StatsRec& r = t.rec[threadIdx.x];
+        tot.e = r.e; tot.n = r.n; tot.eb = r.eb; tot.e5 = r.e5;
+#pragma unroll
+        for (int k = 0; k < kStatCnt; ++k) tot.c[k] = r.cnt[k];
+    }
+    stats_fast_reduce(tot, sh);
+    stats_emit(tot, t, nullptr);
+}
 
 // Per-tensor operands of a group share three launches (amax, quantize, finish + fallback copy).
 struct TensorOp {
@@ -834,7 +984,7 @@ struct TensorOp {
     int n_amax, n_slots;                 // workgroups this operand gets in pass A / pass B
     uint32_t* amax_part;                 // [n_amax]
     float* err; float* err5; uint32_t* zero;   // [n_slots] each
-    uint32_t* abits;                     // [1]
+    uint32_t* abits;                     // [2]: global amax bits; 1 if pass B wrote the fallback
     uint32_t* flush_part;                // [n_amax] lower bounds on the number of elements certain to flush to zero
     unsigned long long flush_need;       // that many certain flushes prove the BF16 decision (0 = proof not attempted)
     StatsDev* stats;                     // optional
@@ -1027,14 +1177,14 @@ __global__ __launch_bounds__(256) void k_tensor_quant_group(GroupTensor g) {
 template <int CRIT>
 __global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g, GroupStats riders, int stats_first) {
     if ((int)blockIdx.x >= stats_first) { stats_final_body(riders, (int)blockIdx.x - stats_first); return; }
-    __shared__ double shd[4];
-    __shared__ unsigned long long shl[4];
     const int op = group_find32(g.copy_end, g.n, blockIdx.x);
     const TensorOp& t = g.op[op];
     const int b = blockIdx.x - (op ? g.copy_end[op - 1] : 0);
     const int nb = g.copy_end[op] - (op ? g.copy_end[op - 1] : 0);
     const bool proven = t.abits[1] != 0u;                     // pass B already wrote the fallback
     if (proven && b != 0) return;                             // only the operand's first workgroup has work left
+    __shared__ double shd[4];
+    __shared__ unsigned long long shl[4];
     double se = 0.0, se5 = 0.0;
     unsigned long long sz = 0;
     for (int i = threadIdx.x; i < t.n_slots; i += 256) {
@@ -1163,7 +1313,10 @@ static bool is_flat(const KShape& sh, const KOut& o) {
            (o.fake == nullptr || o.ld_fake == sh.cols);
 }
 constexpr int64_t kSubRiderMaxUnits = 16384;  // 1x128 operands of at most 128 MiB ride on a team launch; larger ones run faster uncapped
-constexpr int64_t kSubFlatMaxBlocks = 4096;   // workgroups of 4 waves; each wave strides over 8 KB units (256 MiB operand: 77 us at 4096, 88 us at 1024)
+constexpr int64_t kSubFlatMaxBlocks = 1536;   // workgroups of 4 waves, each wave strides over 8 KB units: 6 per compute unit is what the kernel's
+                                              // registers let be resident, so no workgroup waits for another to end (one 64 MiB operand, cold
+                                              // caches: 21.0 us at 1536 against 23.2 us at 2048 (one unit per wave); 112 MiB: 32.1 against 34.5 us;
+                                              // 224 MiB: 65 us either way)
 static int clamp_grid_y(int64_t v) { return (int)(v < 1 ? 1 : (v > 65535 ? 65535 : v)); }
 
 // The general 1 x 128 kernel: one operand per launch.
@@ -1251,9 +1404,14 @@ Route route_of(const BatchItem& it) {
     }
 }
 int64_t item_parts(const BatchItem& it) { return geom_parts(make_geom(it.gran, it.sh.rows, it.sh.cols)); }
-int stats_wgs(int64_t n_part) {
+int stats_wgs(int64_t n_part) {                        // riding in a launch of 256-lane workgroups
     if (n_part <= 4096) return 1;                       // one workgroup writes the result directly
     int64_t w = (n_part + 1023) / 1024;
+    return (int)(w > kStatsMaxWg ? kStatsMaxWg : w);
+}
+int stats_wgs_fast(int64_t n_part) {                   // launch of its own: workgroups of kStatsFastThreads lanes
+    if (n_part <= kStatsDirectParts) return 1;
+    int64_t w = (n_part + kStatsFastThreads * kStatsFastPerLane - 1) / (kStatsFastThreads * kStatsFastPerLane);
     return (int)(w > kStatsMaxWg ? kStatsMaxWg : w);
 }
 size_t item_workspace(const BatchItem& it) {
@@ -1588,6 +1746,8 @@ void BatchRun::tensor_level_decisions() {
 //      step next to the finish pass.  Groups that find no such launch run on their own at the end.
 void BatchRun::collect_statistics() {
     GroupStats* g = nullptr;
+    bool will_ride = false;
+    for (int i = 0; i < n; ++i) will_ride |= route[i] == kRouteTensorGroup;
     for (int i = 0; i < n; ++i) {
         const BatchItem& it = items[i];
         if (!it.stats || it.gran == kGranTensor) continue;
@@ -1599,7 +1759,9 @@ void BatchRun::collect_statistics() {
         t.th = it.th;
         t.rec = reinterpret_cast<StatsRec*>(carve(sizeof(StatsRec) * kStatsMaxWg));
         t.out = static_cast<StatsDev*>(it.stats);
-        g->wg_end[g->n] = (g->n ? g->wg_end[g->n - 1] : 0) + stats_wgs(t.n_part);
+        // the first group rides on the first grouped per-tensor launches if the batch has any, the others are launched on their own
+        const bool rides = n_stats_groups == 1 && will_ride;
+        g->wg_end[g->n] = (g->n ? g->wg_end[g->n - 1] : 0) + (rides ? stats_wgs(t.n_part) : stats_wgs_fast(t.n_part));
         ++g->n;
     }
 }
@@ -1620,14 +1782,22 @@ void BatchRun::per_tensor_operands(int crit) {
                 total_tiles += (n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
             }
             int a_end = 0, s_end = 0, c_end = 0;
+            // Launch shape.  Several operands in the launch: one 32 KB tile per workgroup of pass B (up to 16384), at most three
+            // workgroups resident per compute unit.  One operand alone does better with persistent workgroups that are all
+            // resident from the start (measured with cold caches: 112 MiB, E4M3 kept: 57 us against 77 us per call; 336 MiB:
+            // 148 against 195 us; 224 MiB falling back: 146 against 157 us), whereas the six gradients of the layer sweep
+            // lose with that shape (333 against 294 us for the three launches).
+            const bool solo = cnt == 1 && total_tiles <= 2000ll * kSoloQuantBlocks;
+            const int amax_cap = solo ? kSoloAmaxBlocks : kMaxAmaxBlocks, quant_cap = solo ? kSoloQuantBlocks : kMaxQuantBlocks;
+            const int pass_lds = solo ? 0 : kResidency3;
             for (int k = 0; k < cnt; ++k) {
                 const BatchItem& it = items[idx[k]];
                 TensorOp& t = g.op[k];
                 t.x = it.x; t.o = it.o; t.th = it.th; t.mode = (uint32_t)it.scaling; t.three = it.three ? 1u : 0u; t.lean = it.lean ? 1u : 0u;
                 t.n_chunks = it.sh.rows * it.sh.cols / 8;
                 t.n_tiles = (t.n_chunks + kTensorChunksPerBlock - 1) / kTensorChunksPerBlock;
-                t.n_amax = share(t.n_tiles, total_tiles, kMaxAmaxBlocks, t.n_tiles);
-                t.n_slots = share(t.n_tiles, total_tiles, kMaxQuantBlocks, t.n_tiles);
+                t.n_amax = share(t.n_tiles, total_tiles, amax_cap, t.n_tiles);
+                t.n_slots = share(t.n_tiles, total_tiles, quant_cap, t.n_tiles);
                 const TensorPlan pl = plan_tensor(it.sh.rows, it.sh.cols);
                 char* w = carve(pl.bytes);
                 t.amax_part = reinterpret_cast<uint32_t*>(w + pl.off_amax_part);
@@ -1653,15 +1823,15 @@ void BatchRun::per_tensor_operands(int crit) {
                 ride_final = ride_partial > riders.n ? riders.n : 0;      // single-workgroup operands are final already
                 riders_used = true;
             }
-            { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_group<<<dim3(a_end + ride_partial), dim3(256), kResidency3, st>>>(g, riders, a_end); }
+            { ProfScope ps(prof, kKernTensorAmax, st); k_tensor_amax_group<<<dim3(a_end + ride_partial), dim3(256), pass_lds, st>>>(g, riders, a_end); }
             {
                 ProfScope ps(prof, kKernTensorQuant, st);
                 if (fake) {
-                    if (crit == kCritEq3) k_tensor_quant_group<kCritEq3, true><<<dim3(s_end), dim3(256), kResidency3, st>>>(g);
-                    else k_tensor_quant_group<kCritEq2, true><<<dim3(s_end), dim3(256), kResidency3, st>>>(g);
+                    if (crit == kCritEq3) k_tensor_quant_group<kCritEq3, true><<<dim3(s_end), dim3(256), pass_lds, st>>>(g);
+                    else k_tensor_quant_group<kCritEq2, true><<<dim3(s_end), dim3(256), pass_lds, st>>>(g);
                 } else {
-                    if (crit == kCritEq3) k_tensor_quant_group<kCritEq3, false><<<dim3(s_end), dim3(256), kResidency3, st>>>(g);
-                    else k_tensor_quant_group<kCritEq2, false><<<dim3(s_end), dim3(256), kResidency3, st>>>(g);
+                    if (crit == kCritEq3) k_tensor_quant_group<kCritEq3, false><<<dim3(s_end), dim3(256), pass_lds, st>>>(g);
+                    else k_tensor_quant_group<kCritEq2, false><<<dim3(s_end), dim3(256), pass_lds, st>>>(g);
                 }
             }
             {
@@ -1698,7 +1868,7 @@ void BatchRun::leftover_statistics() {
     for (int k = riders_used ? 1 : 0; k < n_stats_groups && err == hipSuccess; ++k) {
         const GroupStats& g = stats_groups[k];
         const int wg_total = g.wg_end[g.n - 1];
-        { ProfScope ps(prof, kKernStatsPartial, st); k_stats_group_partial<<<dim3(wg_total), dim3(256), 0, st>>>(g); }
+        { ProfScope ps(prof, kKernStatsPartial, st); k_stats_group_partial<<<dim3(wg_total), dim3(kStatsFastThreads), 0, st>>>(g); }
         if (wg_total > g.n) { ProfScope ps(prof, kKernStatsFinal, st); k_stats_group_final<<<dim3(g.n), dim3(256), 0, st>>>(g); }
     }
 }
