@@ -24,11 +24,21 @@ SCOPE = {"partition": 0, "tensor": 1}
 SCALING = {"fp32_amax": 0, "gam": 1, "e8m0": 2}
 
 
+_SANITIZE = os.environ.get("MOR_ORACLE_SANITIZE", "") not in ("", "0")
+if _SANITIZE:
+    # host-only checking build (AddressSanitizer + UndefinedBehaviorSanitizer, any finding aborts): run the CPU tests as
+    #   MOR_ORACLE_SANITIZE=1 LD_PRELOAD=$(gcc -print-file-name=libasan.so) ASAN_OPTIONS=detect_leaks=0 \
+    #       python -m pytest tests -m "not gpu" -q
+    _LIB = os.path.join(_HERE, "libmor_oracle_san.so")
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (strict IEEE: no contraction, no fast-math)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-std=c11", "-O2", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
                "-Wall", "-Wextra", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+        if _SANITIZE:
+            cmd[2:3] = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"]
         subprocess.run(cmd, check=True)
     return _LIB
 

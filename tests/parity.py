@@ -19,6 +19,55 @@ from paper_2512_22804_amd import binding as B
 
 REL_TOL = 1e-5
 FILL = 0x5A5A        # pattern pre-filled into the BF16 fallback buffer to detect stray writes
+GUARD = 512          # bytes of canary on either side of every output buffer and of the workspace
+CANARY = 0xC3
+
+
+class Guards:
+    """Output buffers carved out of larger canary-filled allocations: `check()` fails if a kernel wrote outside one."""
+
+    def __init__(self, device):
+        self.device = device
+        self.bufs = []
+
+    def carve(self, name, shape, dtype, fill=None):
+        n = int(np.prod(shape)) * torch.empty((), dtype=dtype).element_size()
+        body = (n + 255) // 256 * 256                  # keeps the view 256-byte aligned and the tail guard whole
+        raw = torch.full((GUARD + body + GUARD,), CANARY, dtype=torch.uint8, device=self.device)
+        view = raw[GUARD:GUARD + n].view(dtype).reshape(shape)
+        if fill is not None:
+            view.fill_(fill)
+        self.bufs.append((name, raw, n))
+        return view
+
+    def check(self):
+        for name, raw, n in self.bufs:
+            assert bool((raw[:GUARD] == CANARY).all()), f"write BEFORE the start of {name}"
+            assert bool((raw[GUARD + n:] == CANARY).all()), f"write BEYOND the end of {name}"
+
+
+def guarded_outputs(params, device, want_bf16=True, bf16_fill=None, want_fp8=True):
+    """The buffers of binding.alloc_outputs (dense leading dimensions), each between two guard bands."""
+    g = Guards(device)
+    rows, cols = params.rows, params.cols
+    P = B.mor_params_num_partitions(params)
+    fp8 = g.carve("fp8", (rows, cols), torch.uint8) if want_fp8 else None
+    bf16 = None
+    if want_bf16:
+        bf16 = g.carve("bf16", (rows, cols), torch.int16,
+                       None if bf16_fill is None else (bf16_fill if bf16_fill < 0x8000 else bf16_fill - 0x10000))
+    err5 = g.carve("err5_sum", (P,), torch.float32) if params.criterion == B.MOR_CRIT_E4M3_VS_E5M2 else None
+    nbytes = B.mor_workspace_bytes(params)
+    ws = g.carve("workspace", (nbytes,), torch.uint8, 0xFF) if nbytes else None     # nothing may depend on what the workspace held before
+    e8m0 = gmant = None
+    if params.scaling != B.MOR_SCALE_FP32_AMAX:
+        e8m0 = g.carve("scale_e8m0", (P,), torch.uint8, 0xEE)
+        gmant = g.carve("group_mantissa", (2,), torch.int32, -1)
+    amin = g.carve("amin", (P,), torch.float32, -1.0) if params.formats & B.MOR_FMT_E5M2 else None
+    out = B.MorResult(fp8, bf16, g.carve("scale", (P,), torch.float32), g.carve("amax", (P,), torch.float32),
+                      g.carve("err_sum", (P,), torch.float32), g.carve("nnz", (P,), torch.int32), g.carve("mask", (P,), torch.uint8),
+                      err5, ws, params, e8m0, gmant, amin)
+    return out, g
 
 
 def to_dev(xb: np.ndarray) -> torch.Tensor:
@@ -45,11 +94,10 @@ def run_gpu(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "me
     cols = ld if cols is None else cols
     params = B.make_params(rows, cols, gran, scope, crit, threshold, ld=ld, scaling=scaling, formats=formats, ragged=ragged)
     x = to_dev(xb)
-    out = B.alloc_outputs(params, x.device, want_bf16=want_bf16, bf16_fill=FILL)
-    if out.workspace is not None:
-        out.workspace.fill_(0xFF)          # nothing may depend on what the workspace held before
+    out, guards = guarded_outputs(params, x.device, want_bf16=want_bf16, bf16_fill=FILL)
     B.mor_analyze_quantize(params, x, out)
     torch.cuda.synchronize()
+    guards.check()
     return params, out
 
 
@@ -156,12 +204,11 @@ def compare_fake(xb: np.ndarray, gran: str, scope: str = "partition", crit: str 
           f"scaling={scaling} formats={formats} ragged={ragged}", flush=True)
     params = B.make_params(rows, cols, gran, scope, crit, threshold, ld=ld, scaling=scaling, formats=formats, ragged=ragged)
     x = to_dev(xb)
-    meta = B.alloc_outputs(params, x.device, want_bf16=False, want_fp8=False)
-    if meta.workspace is not None:
-        meta.workspace.fill_(0xFF)
-    y = torch.full((rows, cols), FILL if FILL < 0x8000 else FILL - 0x10000, dtype=torch.int16, device=x.device)
+    meta, guards = guarded_outputs(params, x.device, want_bf16=False, want_fp8=False)
+    y = guards.carve("fake_y", (rows, cols), torch.int16, FILL if FILL < 0x8000 else FILL - 0x10000)
     B.mor_fake_quantize(params, x, y, meta)
     torch.cuda.synchronize()
+    guards.check()
     a = O.analyze_quantize(xb, gran, scope, crit, threshold, ld=ld, cols=cols, scaling=scaling, formats=formats,
                            ragged=ragged, want_fake=True)
     g_mask = meta.mask.cpu().numpy()
