@@ -41,13 +41,15 @@
 extern "C" {
 #endif
 
-#define MOR_MAX_LD 4194304   /* elements (2^22) */
+#define MOR_MAX_LD 4194304   /* elements (2^22): largest leading dimension of a call whose blocks span several rows */
+#define MOR_MAX_ROWS_TENSOR_SCOPE 8388607   /* MOR_SCOPE_TENSOR over a sub-tensor granularity: rows / 128 <= 65535 */
 
 typedef enum {
     MOR_OK = 0,
     MOR_ERR_NULL = 1,        /* a required pointer is NULL */
-    MOR_ERR_SHAPE = 2,       /* rows/cols <= 0, ld < cols, not a multiple of the block shape, or a leading dimension
-                                above MOR_MAX_LD for a granularity whose blocks span several rows */
+    MOR_ERR_SHAPE = 2,       /* rows/cols <= 0, ld < cols, not a multiple of the block shape, a leading dimension
+                                above MOR_MAX_LD for a granularity whose blocks span several rows, or more than
+                                MOR_MAX_ROWS_TENSOR_SCOPE rows for a tensor-level decision over sub-tensor blocks */
     MOR_ERR_ALIGN = 3,       /* a pointer is not 16-byte aligned or a leading dimension breaks 16-byte rows */
     MOR_ERR_UNSUPPORTED = 4, /* enum value or format set this build does not implement */
     MOR_ERR_WORKSPACE = 5,   /* workspace NULL or smaller than mor_workspace_bytes() */
@@ -101,7 +103,8 @@ typedef enum {
     MOR_SCOPE_PARTITION = 0,    /* sub-tensor MoR (Section 3.2): one decision per block */
     MOR_SCOPE_TENSOR = 1        /* tensor-level MoR (Section 3.1): block error sums are aggregated,
                                    sum(err_sum)/sum(nnz) (or the two Eq. 3 totals) decides once and
-                                   every mask[p] receives that decision */
+                                   every mask[p] receives that decision.  With a sub-tensor granularity the
+                                   operand may have at most MOR_MAX_ROWS_TENSOR_SCOPE rows (MOR_ERR_SHAPE) */
 } mor_scope;
 
 /* How the per-block scale is formed. */

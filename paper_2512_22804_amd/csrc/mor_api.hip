@@ -92,7 +92,8 @@ static mor_status make_item(const mor_params* p, const uint16_t* x, const mor_ou
         if (out->ld_fp8 % 8 || (want_bf16 && out->ld_bf16 % 8)) return MOR_ERR_ALIGN;
         if ((reinterpret_cast<uintptr_t>(out->fp8) & 7u) || (want_bf16 && !aligned16(out->bf16))) return MOR_ERR_ALIGN;
     }
-    if (p->granularity != MOR_GRAN_TENSOR && p->rows / 128 > 65535 && p->scope == MOR_SCOPE_TENSOR) return MOR_ERR_SHAPE;
+    static_assert(MOR_MAX_ROWS_TENSOR_SCOPE == 65535 * 128 + 127, "documented row limit");
+    if (p->granularity != MOR_GRAN_TENSOR && p->rows > MOR_MAX_ROWS_TENSOR_SCOPE && p->scope == MOR_SCOPE_TENSOR) return MOR_ERR_SHAPE;
     // kernels whose blocks span several rows address a tile of up to 128 rows with 32-bit byte offsets
     if (p->granularity == MOR_GRAN_BLOCK_128x128 || p->granularity == MOR_GRAN_BLOCK_64x64 || p->granularity == MOR_GRAN_SUB_128x1 ||
         p->granularity == MOR_GRAN_CHANNEL_COL) {

@@ -410,6 +410,9 @@ __device__ __forceinline__ u32x4 buf_load16(BufRsrc r, uint32_t voff, uint32_t s
 __device__ __forceinline__ void buf_store16(BufRsrc r, uint32_t voff, const u32x4& v) {
     __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, 0, kBufAux);
 }
+// No other code may issue a 16-byte buffer store (a register scalar offset would bring the hazard back): any later use
+// of the builtin's name is a compile error.
+#pragma GCC poison __builtin_amdgcn_raw_buffer_store_b128
 __device__ __forceinline__ void buf_store8(BufRsrc r, uint32_t voff, uint32_t soff, const u32x2& v) {
     __builtin_amdgcn_raw_buffer_store_b64(v, r, voff, soff, kBufAux);
 }
