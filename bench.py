@@ -118,7 +118,7 @@ def run_variants(ops, B, torch, dev, steps, log):
                     b -= 1.0 * n * f                            # no FP8 payload for an operand known to stay in BF16
             else:
                 b = 3.0 * n + META_BYTES * P
-                if scope == "tensor" and ((scaling == "gam" and gran in ("block128", "block64", "channel_row")) or gran == "channel_col"):
+                if scope == "tensor" and ((scaling == "gam" and gran in ("block128", "block64", "channel_row", "sub1x128", "sub128x1")) or gran == "channel_col"):
                     b += 2.0 * n * f                            # these inputs' BF16 decision is proven by the pre-pass: written by the block kernel
                 elif scope == "tensor":
                     b += 4.0 * n * f                            # separate copy pass after the tensor-wide decision
@@ -145,6 +145,8 @@ def run_variants(ops, B, torch, dev, steps, log):
     analyze_variant("gam_tensor_level_block64", const("block64"), scope="tensor", scaling="gam")
     analyze_variant("gam_tensor_level_channel_row", const("channel_row"), scope="tensor", scaling="gam")
     analyze_variant("gam_tensor_level_channel_col", const("channel_col"), scope="tensor", scaling="gam")
+    analyze_variant("gam_tensor_level_sub1x128", const("sub1x128"), scope="tensor", scaling="gam")
+    analyze_variant("gam_tensor_level_sub128x1", const("sub128x1"), scope="tensor", scaling="gam")
     analyze_variant("gam_tensor_level_per_tensor", const("tensor"), scaling="gam")
     # the scaling ablation of Section 4.1.2 keeps the tensor-level decision and swaps the scaling algorithm
     analyze_variant("e8m0_tensor_level_block128", const("block128"), scope="tensor", scaling="e8m0")

@@ -1516,7 +1516,7 @@ void BatchRun::group_mantissas() {
             if (!scope_proof_applies(it)) continue;
             pv_part[i] = reinterpret_cast<uint32_t*>(carve(sizeof(uint32_t) * kProveMaxWg));
             pv_flush[i] = reinterpret_cast<uint32_t*>(carve(sizeof(uint32_t) * kProveMaxWg));
-            pv[n_pv] = BlockProveItem{it.x, it.sh.rows, it.sh.cols, it.sh.ld, pv_part[i], pv_flush[i], 0, it.gran == kGranRow ? 1 : (it.gran == kGranBlock64 ? 2 : 0)};
+            pv[n_pv] = BlockProveItem{it.x, it.sh.rows, it.sh.cols, it.sh.ld, pv_part[i], pv_flush[i], 0, scope_proof_kind(it)};
             pv_units += scope_proof_units(it);
             pv_item[n_pv] = i;
             if (++n_pv == kProveGroup) flush();
@@ -1619,14 +1619,14 @@ void BatchRun::sub_tensor_operands(int crit) {
                 SubRiders& r = riders.table;
                 rider_units += n_units;
                 r.unit_end[r.n] = rider_units; r.x[r.n] = it.x; r.o[r.n] = it.o; r.th[r.n] = it.th; r.defer[r.n] = it.scope == 1;
-                r.mode[r.n] = (uint8_t)it.scaling; r.gam[r.n] = gam_of[i];
+                r.mode[r.n] = (uint8_t)it.scaling; r.gam[r.n] = gam_of[i]; r.prove[r.n] = scope_proof_applies(it) ? 1 : 0;
                 ++r.n;
                 riders.fake = fake != 0;
                 riders.blocks = (rider_units + 3) / 4 < kSubFlatMaxBlocks ? (rider_units + 3) / 4 : kSubFlatMaxBlocks;
             } else if (n_units > 0) {
                 total += n_units;
                 g.unit_end[g.n] = total; g.x[g.n] = it.x; g.o[g.n] = it.o; g.th[g.n] = it.th; g.defer[g.n] = it.scope == 1;
-                g.mode[g.n] = (uint8_t)it.scaling; g.gam[g.n] = gam_of[i];
+                g.mode[g.n] = (uint8_t)it.scaling; g.gam[g.n] = gam_of[i]; g.prove[g.n] = scope_proof_applies(it) ? 1 : 0;
                 if (++g.n == kMaxGroupSub) flush();
             }
             if (n_tail > 0) {     // fewer than 32 blocks left: the general kernel takes them
@@ -1664,7 +1664,7 @@ void BatchRun::sub_tensor_operands(int crit) {
         for (int k = 0; k < g.n; ++k) {
             const SubRiders& r = riders.table;
             g.unit_end[k] = r.unit_end[k]; g.x[k] = r.x[k]; g.o[k] = r.o[k]; g.th[k] = r.th[k]; g.defer[k] = r.defer[k];
-            g.mode[k] = r.mode[k]; g.gam[k] = r.gam[k];
+            g.mode[k] = r.mode[k]; g.gam[k] = r.gam[k]; g.prove[k] = r.prove[k];
         }
         ProfScope ps(prof, kKernSub1x128, st);
         const dim3 grid((unsigned)riders.blocks);

@@ -131,14 +131,17 @@ enum { kCritEq2 = 0, kCritEq3 = 1 };
 // binary32 error sums that the decision itself is taken from.  Only used for 0 < th < 0.9.
 inline unsigned long long flush_need_of(float th, int64_t n) { return (unsigned long long)(1.01 * (double)th * (double)n) + 1ull; }
 
-// Tensor-level decision (Section 3.1) over GAM-scaled 128 x 128 / 64 x 64 blocks or per-channel rows: the amax pre-pass of
-// Algorithm 1 can prove the BF16 decision under Eq. 2 from elements that are certain to flush inside their block, so
-// the block kernel writes the BF16 payload from its registers and the operand is not read a third time.
+// Tensor-level decision (Section 3.1) over GAM-scaled sub-tensor blocks (128 x 128, 64 x 64, per-channel rows, 1 x 128 sub-rows,
+// 128 x 1 sub-columns): the amax pre-pass of Algorithm 1 can prove the BF16 decision under Eq. 2 from elements that are certain to
+// flush inside their block, so the block kernel writes the BF16 payload from its registers and the operand is not read a third time.
 inline bool scope_proof_applies(const BatchItem& it) {
     // (fake quantization: o.bf16 == o.fake, and a proven operand's output is its input)
     if (it.scaling != 1 || it.scope != 1 || it.crit != kCritEq2 || it.three || it.o.bf16 == nullptr) return false;
     if (!(it.th > 0.0f && it.th < 0.9f)) return false;      // the flush count is compared with 1.01 * th * N + 1
-    if (it.gran == kGranBlock || it.gran == kGranBlock64) return it.sh.rows % 128 == 0 && it.sh.cols % 128 == 0;   // whole 128 x 128 tiles
+    const bool whole_tiles = it.sh.rows % 128 == 0 && it.sh.cols % 128 == 0;
+    if (it.gran == kGranBlock || it.gran == kGranBlock64 || it.gran == kGranSubCol) return whole_tiles;
+    if (it.gran == kGranSub)      // the flat 1 x 128 kernel only (dense operand)
+        return whole_tiles && it.sh.ld == it.sh.cols && it.o.ld_bf16 == it.sh.cols && (it.o.fake != nullptr ? it.o.ld_fake == it.sh.cols : it.o.ld_fp8 == it.sh.cols);
     return it.gran == kGranRow;
 }
 // Work units of the pre-pass (16384 elements each) and its per-operand arguments: per workgroup the largest amax and
@@ -147,13 +150,23 @@ inline int64_t scope_proof_units(const BatchItem& it) {
     if (it.gran == kGranRow) return (it.sh.rows * ((it.sh.cols + 4095) / 4096) + 3) / 4;
     return (it.sh.rows / 128) * (it.sh.cols / 128);
 }
+enum { kProveKindBlock128 = 0, kProveKindRows = 1, kProveKindBlock64 = 2, kProveKindSubRow = 3, kProveKindSubCol = 4 };
+inline int scope_proof_kind(const BatchItem& it) {
+    switch (it.gran) {
+    case kGranRow: return kProveKindRows;
+    case kGranBlock64: return kProveKindBlock64;
+    case kGranSub: return kProveKindSubRow;
+    case kGranSubCol: return kProveKindSubCol;
+    default: return kProveKindBlock128;
+    }
+}
 struct BlockProveItem {
     const uint16_t* x;
     int64_t rows, cols, ld;
     uint32_t* amax_part;     // [n_wg]
     uint32_t* flush_part;    // [n_wg]
     int n_wg;
-    int kind;                // 0: 128 x 128 blocks, 1: per-channel rows, 2: 64 x 64 blocks
+    int kind;                // kProveKind*
 };
 hipError_t launch_block_amax_prove(const BlockProveItem* ops, int n, hipStream_t st);
 

@@ -361,7 +361,10 @@ struct ProveOp {
     uint32_t* flush_part;
     int32_t kind;            // kProveBlock128, kProveRows, kProveBlock64
 };
-enum { kProveBlock128 = 0, kProveRows = 1, kProveBlock64 = 2 };
+enum { kProveBlock128 = kProveKindBlock128, kProveRows = kProveKindRows, kProveBlock64 = kProveKindBlock64,
+       kProveSubRow = kProveKindSubRow,       // 1 x 128 sub-rows: the 16 lanes of a DPP row hold one whole block per chunk
+       kProveSubCol = kProveKindSubCol };     // 128 x 1 sub-columns: a lane holds 8 rows of 8 column blocks, its wave 32 rows of each
+__device__ __forceinline__ uint32_t colgroup_max2(uint32_t v);
 struct GroupProve {
     int n;
     int32_t wg_end[kMaxTeamGroup];
@@ -397,6 +400,55 @@ __device__ __forceinline__ void prove_tiles(const ProveOp& t, int b, int nb, uin
     while (unit < n_wg_units) {
         const int64_t next = unit + nb;
         if (next < n_wg_units) load_tile(nxt, next);        // uniform over the workgroup
+        if constexpr (KIND == kProveSubRow) {
+            // every chunk of a DPP row is one block: its exact amax, and the flushes relative to it
+            uint32_t ab[kChunks];
+#pragma unroll
+            for (int i = 0; i < kChunks; ++i) {
+                uint32_t a2 = 0u;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) a2 = pk_max_u16(a2, cur[i][j] & 0x7FFF7FFFu);
+                ab[i] = fold_max16(a2);
+            }
+            rows_allmax<kChunks>(ab);
+            uint32_t f2 = 0u;
+#pragma unroll
+            for (int i = 0; i < kChunks; ++i) {
+                amax_run = max(amax_run, ab[i]);
+                const uint32_t t1 = ab[i] > 0x0A00u ? ab[i] - 0x0A01u : 0u;
+                const uint32_t bound2 = t1 | (t1 << 16);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) f2 = pk_add_u16(f2, pk_certain_flush(cur[i][j], bound2));
+            }
+            flush_run += fold_add16(f2);
+#pragma unroll
+            for (int i = 0; i < kChunks; ++i) cur[i] = nxt[i];
+            unit = next;
+            continue;
+        }
+        if constexpr (KIND == kProveSubCol) {
+            // word j of every chunk holds two of the lane's eight columns: column maxima over the lane's 8 rows and the wave's
+            // four row groups (32 of the block's 128 rows: a lower bound of the block's amax), flushes relative to them
+            uint32_t c2[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int i = 0; i < kChunks; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) c2[j] = pk_max_u16(c2[j], cur[i][j] & 0x7FFF7FFFu);
+            uint32_t f2 = 0u;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                c2[j] = colgroup_max2(c2[j]);
+                amax_run = max(amax_run, fold_max16(c2[j]));
+                const uint32_t bound2 = pk_sub_sat_u16(pk_sub_sat_u16(c2[j], 0x0A000A00u), 0x00010001u);
+#pragma unroll
+                for (int i = 0; i < kChunks; ++i) f2 = pk_add_u16(f2, pk_certain_flush(cur[i][j], bound2));
+            }
+            flush_run += fold_add16(f2);
+#pragma unroll
+            for (int i = 0; i < kChunks; ++i) cur[i] = nxt[i];
+            unit = next;
+            continue;
+        }
         // amax of what this wave holds of the lane's block(s): one value, or one for each half of the chunks
         uint32_t a2[2] = {0u, 0u};
 #pragma unroll
@@ -442,6 +494,8 @@ __global__ __launch_bounds__(256) void k_block_amax_prove(GroupProve g) {
     uint32_t amax_run = 0u, flush_run = 0u;
     if (t.kind == kProveRows) prove_tiles<kProveRows>(t, b, nb, amax_run, flush_run);
     else if (t.kind == kProveBlock64) prove_tiles<kProveBlock64>(t, b, nb, amax_run, flush_run);
+    else if (t.kind == kProveSubRow) prove_tiles<kProveSubRow>(t, b, nb, amax_run, flush_run);
+    else if (t.kind == kProveSubCol) prove_tiles<kProveSubCol>(t, b, nb, amax_run, flush_run);
     else prove_tiles<kProveBlock128>(t, b, nb, amax_run, flush_run);
     amax_run = wave_allmax_u32(amax_run);
     flush_run = wave_allsum_u32(flush_run);
@@ -807,7 +861,8 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
                     amin_bits = nnz ? ((mn + 1u) & 0xFFFFu) : 0u;
                     if (range_fits_e5m2(a, amin_bits, nnz)) { mk = 2u; s_out = sh.scale5[tid]; }
                 }
-                sh.mask[tid] = (uint8_t)mk;
+                // (128 x 1 blocks whose tensor-level BF16 decision the pre-pass has proven: every column's payload is stored below)
+                sh.mask[tid] = (uint8_t)((defer && t.prove && t.gam[2] != 0u) ? 1u : mk);
                 if (c0 + tid < t.cols) {
                     const int64_t p = (r0 >> 7) * t.cols + c0 + tid;
                     o.scale[p] = s_out;
@@ -1302,6 +1357,7 @@ void fill_col_op(ColOp& t, const BatchItem& it, const uint32_t* gam) {
     t.tiles_per_strip = 1;
     t.th = it.th; t.defer = it.scope == 1; t.mode = (uint8_t)it.scaling; t.three = (uint8_t)it.three;
     t.gam = gam;
+    t.prove = (it.gran == kGranSubCol && scope_proof_applies(it)) ? 1 : 0;     // (per-channel columns set their own meaning afterwards)
 }
 template <int MODE, bool FAKE, bool EDGE>
 void launch_col_crit(const GroupCol& g, int64_t total, int crit, hipStream_t st) {

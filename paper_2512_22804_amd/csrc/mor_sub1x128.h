@@ -60,7 +60,7 @@ __device__ __forceinline__ void sub_unit_careful(const uint16_t* __restrict__ xl
 // block g*8+j, so the per-block work (division, decision, metadata) runs once per 8 blocks.
 template <int CRIT, bool FAKE>
 __device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const uint16_t* __restrict__ x, const KOut& o, int64_t unit,
-                                                 int lane, float th, bool defer, uint32_t mode, uint32_t mg, uint32_t mg5) {
+                                                 int lane, float th, bool defer, uint32_t mode, uint32_t mg, uint32_t mg5, bool proven) {
     const int g = lane >> 4, l = lane & 15, own = l & 7;
     const int64_t prow = unit * 32 + g * 8;
     const int64_t off = prow * 128 + l * 8;
@@ -149,6 +149,13 @@ __device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const ui
         if (!defer) o.mask[p] = (uint8_t)my_mask;
         if (mode != kScaleFp32 && o.e8m0) o.e8m0[p] = (uint8_t)(__float_as_uint(my_s) >> 23);
     }
+    if (defer && proven) {
+        // tensor-level decision already proven to be BF16 by the pre-pass (uniform over the launch's operand): the fallback
+        // payload of every block is stored from the registers (for fake quantization this overwrites the de-quantized values)
+        uint16_t* __restrict__ bl = o.bf16 + off;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) store16(bl + k * 128, raw[k]);
+    }
     if (!defer && o.bf16) {
         const unsigned long long want = __ballot(l < 8 && my_mask != 0u);
         if (want) {
@@ -172,7 +179,8 @@ struct GroupSubT {
     float th[N];
     uint8_t defer[N];          // 1: tensor-level decision follows, write no mask / fallback here
     uint8_t mode[N];           // scaling algorithm
-    const uint32_t* gam[N];    // mode != 0: {mantissa for E4M3, mantissa for E5M2} of the operand's group
+    uint8_t prove[N];          // 1: gam[2] != 0 says that the tensor-level BF16 decision is already proven (fallback stored here)
+    const uint32_t* gam[N];    // mode != 0: {mantissa for E4M3, mantissa for E5M2, proven flag} of the operand's group
 };
 constexpr int kMaxGroupSub = 16;       // operands per launch of the kernel of its own
 constexpr int kMaxSubRiders = 2;       // operands that can ride on a block-team launch
@@ -205,7 +213,8 @@ __device__ __forceinline__ void sub_group_body(const G& g, int64_t block, int64_
         const uint32_t mode = g.mode[op];
         uint32_t mg = 0u, mg5 = 0u;
         if (mode) { mg = g.gam[op][0]; if constexpr (CRIT == kCritEq3) mg5 = g.gam[op][1]; }
-        sub_unit_process<CRIT, FAKE>(raw, g.x[op], g.o[op], local, lane, g.th[op], g.defer[op] != 0, mode, mg, mg5);
+        const bool proven = g.prove[op] != 0 && g.gam[op][2] != 0u;
+        sub_unit_process<CRIT, FAKE>(raw, g.x[op], g.o[op], local, lane, g.th[op], g.defer[op] != 0, mode, mg, mg5, proven);
     };
     int opA;
     int64_t locA;

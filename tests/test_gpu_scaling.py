@@ -133,7 +133,9 @@ def _with_tiny(rows, cols, frac, seed, tiny_exp=-40):
 @pytest.mark.parametrize("frac", [0.0, 0.04, 0.2])
 @pytest.mark.parametrize("pad", [0, 64])
 @pytest.mark.parametrize("gran,shape", [("block128", (640, 1152)), ("block64", (640, 1152)), ("block64", (192, 320)),
-                                        ("channel_row", (70, 1152)), ("channel_row", (9, 9000)), ("channel_row", (5, 20000))])
+                                        ("channel_row", (70, 1152)), ("channel_row", (9, 9000)), ("channel_row", (5, 20000)),
+                                        ("sub1x128", (640, 1152)), ("sub1x128", (128, 128)), ("sub1x128", (200, 384)),
+                                        ("sub128x1", (640, 1152)), ("sub128x1", (256, 384))])
 def test_gam_tensor_level_decision_proven_by_the_pre_pass(frac, pad, gran, shape):
     """Tensor-level decision over GAM-scaled 128x128 blocks or per-channel rows (the recipe of Section 3.1): with enough
     certain flushes the amax pre-pass proves the BF16 decision and the block kernel writes the fallback itself; with 4 %
@@ -157,6 +159,30 @@ def test_gam_tensor_level_proof_uses_each_rows_own_amax():
     x[0, np.random.default_rng(16).random(4096) < 0.5] = np.float32(2.0 ** -30)     # half of one row flushes
     r = parity.compare(W.f32_to_bf16_bits(x), "channel_row", "tensor", "mean_rel_err", 0.045, label="gam proof per row", scaling="gam")
     assert r["n_bf16"] == 0
+
+
+@pytest.mark.parametrize("gran", ["sub1x128", "sub128x1"])
+def test_gam_tensor_level_proof_uses_each_sub_channels_own_amax(gran):
+    """Sub-channels of small values only do not flush; the few sub-channels with large values hold 3 % of flushes: no proof,
+    and the decision (E4M3) comes from the error sums.  With 30 % of certain flushes in every sub-channel the pre-pass
+    proves BF16."""
+    rows, cols = 256, 384
+    x = _with_tiny(rows, cols, 0.0, 45)
+    big = np.zeros((rows, cols), bool)
+    if gran == "sub1x128":
+        big[::8, :128] = True                              # one sub-row in eight of the first column strip keeps its large values
+    else:
+        big[:128, ::8] = True                              # one sub-column in eight of the first row strip
+    x[~big] *= np.float32(2.0 ** -30)
+    x[big & (np.random.default_rng(46).random((rows, cols)) < 0.03)] = np.float32(2.0 ** -30)
+    xb = W.f32_to_bf16_bits(x)
+    r = parity.compare(xb, gran, "tensor", "mean_rel_err", 0.045, label="gam proof per sub-channel", scaling="gam")
+    assert r["n_bf16"] == 0
+    assert parity.compare_fake(xb, gran, "tensor", "mean_rel_err", 0.045, label="gam proof per sub-channel, fake", scaling="gam")["n_bf16"] == 0
+    x2 = _with_tiny(rows, cols, 0.3, 47, tiny_exp=-30)
+    x2[128:, :] *= np.float32(2.0 ** -20)                  # flushes relative to their own sub-channel's amax all the same
+    r = parity.compare(W.f32_to_bf16_bits(x2), gran, "tensor", "mean_rel_err", 0.045, label="gam proof per sub-channel, mixed", scaling="gam")
+    assert r["n_bf16"] == r["P"]
 
 
 def test_gam_tensor_level_proof_uses_each_blocks_own_amax():
@@ -191,7 +217,8 @@ def test_gam_tensor_level_proof_in_a_batch_with_statistics():
     from oracle import mor_oracle as O
     dev = torch.device("cuda")
     specs = [(512, 1024, 0.2, "block128"), (256, 384, 0.0, "block128"), (384, 512, 0.04, "block128"), (128, 128, 0.5, "block128"),
-             (640, 256, 0.1, "block128"), (256, 640, 0.2, "block64"), (128, 128, 0.0, "block64"), (33, 4096, 0.2, "channel_row"), (7, 17000, 0.3, "channel_row"), (50, 512, 0.0, "channel_row")]
+             (640, 256, 0.1, "block128"), (256, 640, 0.2, "block64"), (128, 128, 0.0, "block64"), (33, 4096, 0.2, "channel_row"), (7, 17000, 0.3, "channel_row"), (50, 512, 0.0, "channel_row"),
+             (384, 512, 0.2, "sub1x128"), (128, 256, 0.0, "sub1x128"), (256, 256, 0.04, "sub1x128"), (384, 256, 0.2, "sub128x1"), (128, 384, 0.0, "sub128x1")]
     ops, keep = [], []
     for k, (rows, cols, frac, gran) in enumerate(specs):
         xb = W.f32_to_bf16_bits(_with_tiny(rows, cols, frac, 40 + k))
@@ -221,7 +248,7 @@ def test_gam_tensor_level_full_benchmark_sizes():
     ops, keep = [], []
     for xb in (w, g):
         xd = parity.to_dev(xb)
-        for gran in ("block128", "block64", "channel_row"):
+        for gran in ("block128", "block64", "channel_row", "sub1x128", "sub128x1"):
             params = B.make_params(xb.shape[0], xb.shape[1], gran, "tensor", "mean_rel_err", 0.045, scaling="gam")
             out = B.alloc_outputs(params, dev, want_bf16=True, bf16_fill=parity.FILL)
             ops.append((params, xd, out, None)); keep.append((xb, gran))
@@ -231,11 +258,14 @@ def test_gam_tensor_level_full_benchmark_sizes():
     torch.cuda.synchronize()
     for (params, xd, out, _), (xb, gran) in zip(ops, keep):
         r = parity.compare(xb, gran, "tensor", "mean_rel_err", 0.045, label="gam tensor-level full size", scaling="gam", gpu=(params, out))
-        assert r["n_bf16"] == (r["P"] if xb is g else 0)
+        if gran == "sub1x128":      # a uniformly shrunk sub-channel does not flush under its own scale: the gradient stays E4M3 too
+            assert r["n_bf16"] == 0
+        else:
+            assert r["n_bf16"] == (r["P"] if xb is g else 0)
 
 
 @pytest.mark.parametrize("th", [0.0, 0.01, 0.3, 0.95, 1.5])
-@pytest.mark.parametrize("gran", ["block128", "block64", "channel_row"])
+@pytest.mark.parametrize("gran", ["block128", "block64", "channel_row", "sub1x128", "sub128x1"])
 def test_gam_tensor_level_thresholds_outside_the_usual_range(th, gran):
     """20 % flushed values: BF16 for th <= 0.2 (proven or not), E4M3 above; thresholds for which no proof is attempted
     (0, >= 0.9) take the separate copy and give the same outputs."""
@@ -250,7 +280,7 @@ def test_gam_tensor_level_proof_with_a_dirty_workspace_and_in_a_graph():
     the workspace and the outputs scrubbed in between; every run gives the outputs of the first, which equal the oracle's."""
     dev = torch.device("cuda")
     specs = [(512, 1024, 0.2, "block128"), (256, 384, 0.0, "block128"), (384, 512, 0.04, "block128"),
-             (33, 4096, 0.2, "channel_row"), (50, 512, 0.0, "channel_row")]
+             (33, 4096, 0.2, "channel_row"), (50, 512, 0.0, "channel_row"), (256, 512, 0.2, "sub1x128"), (256, 384, 0.2, "sub128x1")]
     ops, keep = [], []
     for k, (rows, cols, frac, gran) in enumerate(specs):
         xb = W.f32_to_bf16_bits(_with_tiny(rows, cols, frac, 60 + k))
