@@ -62,7 +62,9 @@
  *       of local errors for Eq. (2) only (Section 3.1).
  *   R16 GAM (Algorithm 1) is run with one group = the whole tensor, the
  *       configuration of the paper's experiments (Section 2, the paragraph
- *       after the algorithm's description).  mantissa(s) and exponent(s) are
+ *       after the algorithm's description), or, on request, with the groups
+ *       of G taken as bands of `group_rows` consecutive rows (whole blocks
+ *       each; the last band may be shorter): Algorithm 1 leaves G open.  mantissa(s) and exponent(s) are
  *       those of the binary32 number s = m * 2^e, 1 <= m < 2.  The scale that
  *       is applied is m_g * 2^e, exact in binary32.  The stored E8M0 code is
  *       e + 127, the stored group mantissa the 23 fraction bits of m_g.
@@ -369,6 +371,7 @@ typedef struct {
     uint32_t formats;       /* FMT_E4M3 | FMT_BF16, or FMT_E4M3 | FMT_E5M2 | FMT_BF16 (three-way) */
     int32_t  ragged;        /* 1: edge blocks may be smaller than the nominal block (R20) */
     float    threshold;
+    int32_t  group_rows;    /* GAM: 0 = one group (the whole tensor); else the groups of Algorithm 1 are bands of this many rows */
 } oracle_params;
 
 typedef struct {
@@ -382,7 +385,7 @@ typedef struct {
     double   *err5_sum;     /* [P] or NULL */
     double   *err_sum_unscaled; /* [P] or NULL */
     uint8_t  *e8m0;         /* [P] or NULL (GAM / E8M0 scaling) */
-    uint32_t *group_mantissa;   /* [2] or NULL: fraction bits of m_g for E4M3 and for E5M2 */
+    uint32_t *group_mantissa;   /* [n_groups][2] or NULL: fraction bits of m_g for E4M3 and for E5M2, group by group */
     float    *amin;         /* [P] or NULL: smallest non-zero magnitude (0 when there is none) */
     uint16_t *fake;         /* [rows x cols] or NULL: fake-quantized tensor (R21) */
 } oracle_out;
@@ -397,10 +400,16 @@ int mor_oracle_run(const oracle_params *pp, const uint16_t *x, const oracle_out 
     const int three = pp->formats == (FMT_E4M3 | FMT_E5M2 | FMT_BF16);
     const int want5 = pp->crit == CRIT_E4M3_VS_E5M2;
     int64_t pr, pc, gr, gc, P;
-    double m_g = 1.0, m_g5 = 1.0;
+    int64_t band, n_groups;
+    double *m_g, *m_g5;
     float *scale5;
     uint8_t *e8m0_5;
     if (rows <= 0 || cols <= 0 || ld < cols || part_shape_ex(pp->gran, rows, cols, pp->ragged, &pr, &pc)) return -1;
+    /* groups of Algorithm 1: bands of whole blocks (a block never straddles two groups) */
+    if (pp->group_rows < 0) return -1;
+    band = pp->group_rows > 0 && pp->scaling == SCALING_GAM ? pp->group_rows : rows;
+    if (band % pr) return -1;
+    n_groups = (rows + band - 1) / band;
     if (pp->scaling < SCALING_FP32_AMAX || pp->scaling > SCALING_E8M0) return -1;
     if (!three && pp->formats != (FMT_E4M3 | FMT_BF16)) return -1;
     if (three && pp->scope != SCOPE_PARTITION) return -1;     /* the paper's three-way recipe is per block */
@@ -408,23 +417,29 @@ int mor_oracle_run(const oracle_params *pp, const uint16_t *x, const oracle_out 
     gr = (rows + pr - 1) / pr; gc = (cols + pc - 1) / pc; P = gr * gc;
     scale5 = (float *)malloc(sizeof(float) * (size_t)P);
     e8m0_5 = (uint8_t *)malloc((size_t)P);
-    if (!scale5 || !e8m0_5) { free(scale5); free(e8m0_5); return -1; }
+    m_g = (double *)malloc(sizeof(double) * (size_t)n_groups);
+    m_g5 = (double *)malloc(sizeof(double) * (size_t)n_groups);
+    if (!scale5 || !e8m0_5 || !m_g || !m_g5) { free(scale5); free(e8m0_5); free(m_g); free(m_g5); return -1; }
 
-    if (pp->scaling == SCALING_GAM) {          /* the group loop of Algorithm 1, one group */
-        uint16_t g = 0;
-        float g_amax;
-        for (int64_t r = 0; r < rows; ++r)
-            for (int64_t c = 0; c < cols; ++c) {
-                uint16_t m = (uint16_t)(x[r * ld + c] & 0x7FFFu);
-                if (m > g) g = m;
-            }
-        g_amax = bf16_to_f32(g);
-        m_g = mor_oracle_group_mantissa(g_amax, 448.0f, pp->scaling);
-        m_g5 = mor_oracle_group_mantissa(g_amax, 57344.0f, pp->scaling);
-    }
-    if (o->group_mantissa) {
-        o->group_mantissa[0] = (uint32_t)ldexp(m_g - 1.0, 23);
-        o->group_mantissa[1] = (uint32_t)ldexp(m_g5 - 1.0, 23);
+    for (int64_t gi = 0; gi < n_groups; ++gi) {           /* the group loop of Algorithm 1 */
+        m_g[gi] = 1.0; m_g5[gi] = 1.0;
+        if (pp->scaling == SCALING_GAM) {
+            uint16_t g = 0;
+            float g_amax;
+            int64_t r_end = (gi + 1) * band < rows ? (gi + 1) * band : rows;
+            for (int64_t r = gi * band; r < r_end; ++r)
+                for (int64_t c = 0; c < cols; ++c) {
+                    uint16_t m = (uint16_t)(x[r * ld + c] & 0x7FFFu);
+                    if (m > g) g = m;
+                }
+            g_amax = bf16_to_f32(g);
+            m_g[gi] = mor_oracle_group_mantissa(g_amax, 448.0f, pp->scaling);
+            m_g5[gi] = mor_oracle_group_mantissa(g_amax, 57344.0f, pp->scaling);
+        }
+        if (o->group_mantissa) {
+            o->group_mantissa[2 * gi] = (uint32_t)ldexp(m_g[gi] - 1.0, 23);
+            o->group_mantissa[2 * gi + 1] = (uint32_t)ldexp(m_g5[gi] - 1.0, 23);
+        }
     }
 
 #pragma omp parallel for schedule(dynamic, 16) if (P > 1)
@@ -433,7 +448,7 @@ int mor_oracle_run(const oracle_params *pp, const uint16_t *x, const oracle_out 
         int64_t r0 = br * pr, c0 = bc * pc;
         int64_t h = rows - r0 < pr ? rows - r0 : pr, w = cols - c0 < pc ? cols - c0 : pc;
         block_result res;
-        analyze_block(x + r0 * ld + c0, ld, h, w, want5, pp->scaling, m_g, m_g5,
+        analyze_block(x + r0 * ld + c0, ld, h, w, want5, pp->scaling, m_g[r0 / band], m_g5[r0 / band],
                       o->fp8 + r0 * cols + c0, cols, &res);
         if (o->e8m0) o->e8m0[p] = (uint8_t)res.e8m0;
         e8m0_5[p] = (uint8_t)res.e8m0_5; scale5[p] = res.scale5;
@@ -487,7 +502,7 @@ int mor_oracle_run(const oracle_params *pp, const uint16_t *x, const oracle_out 
                 }
         }
     }
-    free(scale5); free(e8m0_5);
+    free(scale5); free(e8m0_5); free(m_g); free(m_g5);
     return 0;
 }
 
@@ -500,7 +515,7 @@ int mor_oracle_analyze_quantize_ex(const uint16_t *x, int64_t rows, int64_t cols
                                    uint8_t *mask, double *err5_sum, double *err_sum_unscaled,
                                    uint8_t *e8m0, uint32_t *group_mantissa)
 {
-    oracle_params pp = { rows, cols, ld, gran, scope, crit, scaling, FMT_E4M3 | FMT_BF16, 0, threshold };
+    oracle_params pp = { rows, cols, ld, gran, scope, crit, scaling, FMT_E4M3 | FMT_BF16, 0, threshold, 0 };
     uint32_t gm[2] = { 0u, 0u };
     oracle_out o = { fp8, bf16, scale, amax, err_sum, nnz, mask, err5_sum, err_sum_unscaled, e8m0, gm, NULL, NULL };
     int rc = mor_oracle_run(&pp, x, &o);

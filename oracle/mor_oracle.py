@@ -55,7 +55,7 @@ class _Stats(C.Structure):
 class _Params(C.Structure):
     _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64),
                 ("gran", C.c_int32), ("scope", C.c_int32), ("crit", C.c_int32), ("scaling", C.c_int32),
-                ("formats", C.c_uint32), ("ragged", C.c_int32), ("threshold", C.c_float)]
+                ("formats", C.c_uint32), ("ragged", C.c_int32), ("threshold", C.c_float), ("group_rows", C.c_int32)]
 
 
 class _Out(C.Structure):
@@ -193,10 +193,11 @@ class Analysis:
     err5_sum: np.ndarray       # (P,) float64 (zeros unless criterion is e4m3_vs_e5m2)
     err_sum_unscaled: np.ndarray  # (P,) float64, Eq. (2) evaluated in the unscaled domain
     e8m0: np.ndarray | None = None          # (P,) uint8 block exponents + 127 (GAM / E8M0 scaling)
-    group_mantissa: int | None = None       # 23 fraction bits of m_g (GAM / E8M0 scaling)
+    group_mantissa: int | None = None       # 23 fraction bits of m_g (GAM / E8M0 scaling) of the first (or only) group
     group_mantissa5: int | None = None      # the same for the E5M2 scales
     amin: np.ndarray | None = None          # (P,) float32 smallest non-zero magnitude (0 if none)
     fake: np.ndarray | None = None          # (rows, cols) uint16 fake-quantized tensor, on request
+    group_mantissas: np.ndarray | None = None   # (n_groups, 2) uint32: fraction bits of m_g for E4M3 / E5M2, for every group of Algorithm 1
 
     def metric(self) -> np.ndarray:
         n = self.nnz.astype(np.float64)
@@ -207,7 +208,7 @@ class Analysis:
 def analyze_quantize(x: np.ndarray, gran: str, scope: str = "partition", crit: str = "mean_rel_err",
                      threshold: float = 0.045, bf16_fill: int = 0, ld: int | None = None,
                      cols: int | None = None, scaling: str = "fp32_amax", formats: str = "e4m3|bf16",
-                     ragged: bool = False, want_fake: bool = False) -> Analysis:
+                     ragged: bool = False, want_fake: bool = False, gam_group_rows: int = 0) -> Analysis:
     """Run the oracle on BF16 bit patterns ``x`` (2-D uint16).  ``ld``/``cols`` allow a padded
     leading dimension: ``x`` is then (rows, ld) and only the first ``cols`` columns are used."""
     x = np.ascontiguousarray(x, dtype=np.uint16)
@@ -223,17 +224,18 @@ def analyze_quantize(x: np.ndarray, gran: str, scope: str = "partition", crit: s
     es = np.zeros(P, np.float64); e5 = np.zeros(P, np.float64); eu = np.zeros(P, np.float64)
     nz = np.zeros(P, np.uint32); mk = np.zeros(P, np.uint8)
     ex = np.zeros(P, np.uint8)
-    gm = np.zeros(2, np.uint32)
+    n_groups = -(-rows // gam_group_rows) if (gam_group_rows and scaling == "gam") else 1
+    gm = np.zeros(2 * n_groups, np.uint32)
     fake = np.zeros((rows, cols), np.uint16) if want_fake else None
     pp = _Params(rows, cols, ld, GRAN[gran], SCOPE[scope], CRIT[crit], SCALING[scaling], FORMATS[formats],
-                 1 if ragged else 0, float(np.float32(threshold)))
+                 1 if ragged else 0, float(np.float32(threshold)), int(gam_group_rows))
     oo = _Out(*[None if a is None else a.ctypes.data for a in (fp8, bf16, sc, am, es, nz, mk, e5, eu, ex, gm, mn, fake)])
     rc = lib().mor_oracle_run(C.byref(pp), _p(x), C.byref(oo))
     if rc != 0:
         raise ValueError("mor_oracle_run rejected the arguments")
     if scaling == "fp32_amax":
         return Analysis(fp8, bf16, sc, am, es, nz, mk, e5, eu, amin=mn, fake=fake)
-    return Analysis(fp8, bf16, sc, am, es, nz, mk, e5, eu, ex, int(gm[0]), int(gm[1]), mn, fake)
+    return Analysis(fp8, bf16, sc, am, es, nz, mk, e5, eu, ex, int(gm[0]), int(gm[1]), mn, fake, gm.reshape(n_groups, 2))
 
 
 def dequantize(fp8: np.ndarray, scale_: np.ndarray, mask: np.ndarray, bf16: np.ndarray | None,

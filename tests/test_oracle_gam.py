@@ -197,3 +197,91 @@ def test_gam_never_loses_more_than_one_binade_of_range(oracle):
     half = np.abs(xs * (f.scale[:, None] / 2)) <= 2.0 ** -10          # at or below half the smallest subnormal: flushed at s/2
     bound = (half & nz.reshape(-1, 128)).sum(-1)
     assert np.all(flushed_g <= np.maximum(bound, flushed_f))
+
+
+# ---- several groups per tensor (the partition G of Algorithm 1 taken as bands of rows) ----------------------------
+def test_gam_row_band_groups_hand_worked(oracle):
+    """Four 1x128 blocks, groups of two rows.  Band 0 holds amax 3 and 1: m_g = mantissa(448/3) = 1.1666.., the block of
+    amax 1 (s_b = 448 = 1.75 * 2^8, m_b >= m_g) gets 1.1666.. * 2^8.  Band 1 holds amax 5 and 7: s_g = 64, m_g = 1; the
+    block of amax 5 (s_b = 89.6 = 1.4 * 2^6) gets 2^6.  As ONE group (amax 7, m_g = 1) the first two blocks would get 2^7 and
+    2^8: the bands keep more of their blocks' range."""
+    x = block_tensor([3.0, 1.0, 5.0, 7.0])
+    a = oracle.analyze_quantize(x, "sub1x128", scaling="gam", gam_group_rows=2)
+    assert list(a.scale) == [F32(S3), F32(2 * S3), F32(64.0), F32(64.0)]
+    assert list(a.e8m0) == [127 + 7, 127 + 8, 127 + 6, 127 + 6]
+    frac3 = int(np.array([S3], np.float32).view(np.uint32)[0]) & 0x7FFFFF
+    assert a.group_mantissas.tolist() == [[frac3, frac3], [0, 0]]          # 57344 / amax has the mantissa of 448 / amax
+    one = oracle.analyze_quantize(x, "sub1x128", scaling="gam")
+    assert list(one.scale) == [F32(128.0), F32(256.0), F32(64.0), F32(64.0)]
+    assert one.group_mantissas.tolist() == [[0, 0]]
+    # a band that covers the tensor is the single group; E8M0-only scaling has no groups to speak of
+    whole = oracle.analyze_quantize(x, "sub1x128", scaling="gam", gam_group_rows=4)
+    assert np.array_equal(whole.scale, one.scale) and np.array_equal(whole.fp8, one.fp8)
+    e8 = oracle.analyze_quantize(x, "sub1x128", scaling="e8m0", gam_group_rows=2)
+    assert np.array_equal(e8.scale, oracle.analyze_quantize(x, "sub1x128", scaling="e8m0").scale)
+
+
+@pytest.mark.parametrize("gran,shape,band,crit", [("sub1x128", (10, 256), 4, "mean_rel_err"), ("sub1x128", (6, 128), 2, "e4m3_vs_e5m2"),
+                                                  ("channel_row", (9, 384), 2, "mean_rel_err"), ("block128", (384, 256), 128, "mean_rel_err"),
+                                                  ("block64", (192, 128), 128, "e4m3_vs_e5m2"), ("sub128x1", (256, 8), 128, "mean_rel_err")])
+def test_gam_row_band_groups_match_rational_model(oracle, gran, shape, band, crit):
+    """Every block against the exact-rational Algorithm 1 with the amax of ITS band as group amax (the last band may be
+    shorter), and the stored form (band mantissa + E8M0 byte) rebuilds the applied scale."""
+    rows, cols = shape
+    rng = np.random.default_rng(rows * 7 + cols)
+    x = (np.exp2(rng.uniform(-6.0, 6.0, size=(rows, cols))) * rng.choice([-1.0, 1.0], size=(rows, cols))).astype(np.float32)
+    x *= np.exp2(rng.integers(-8, 8, size=(rows, 1))).astype(np.float32)            # row magnitudes differ: the bands' amaxes too
+    xb = W.f32_to_bf16_bits(x)
+    a = oracle.analyze_quantize(xb, gran, "partition", crit, 0.045, scaling="gam", gam_group_rows=band)
+    pr, pc = {"sub1x128": (1, 128), "channel_row": (1, cols), "block128": (128, 128), "block64": (64, 64), "sub128x1": (128, 1)}[gran]
+    gc = cols // pc
+    n_groups = -(-rows // band)
+    assert a.group_mantissas.shape == (n_groups, 2)
+    mags = xb & 0x7FFF
+    for p in range(a.mask.size):
+        r0, c0 = (p // gc) * pr, (p % gc) * pc
+        g = r0 // band
+        g_amax = float(R.bf16_to_f32(int(mags[g * band:(g + 1) * band].max())))
+        blk = xb[r0:r0 + pr, c0:c0 + pc].reshape(-1)
+        if blk.size > 2048 and (p > 0 or blk.size > 8192):
+            # large blocks: only the scale of Algorithm 1 (what the grouping changes); everything after the scale is pinned elsewhere
+            b_amax = float(R.bf16_to_f32(int((blk & 0x7FFF).max())))
+            assert Fraction(float(a.scale[p])) == R.gam_scale(b_amax, g_amax, 448.0)[0], (p, g)
+        else:
+            r = R.analyze_block(blk, crit, 0.045, scaling="gam", g_amax=g_amax)
+            assert a.scale[p] == F32(r["scale"]), (p, g)
+            assert list(a.fp8[r0:r0 + pr, c0:c0 + pc].reshape(-1)) == r["codes"]
+            assert a.err_sum[p] == pytest.approx(float(r["err_sum"]), rel=1e-12, abs=1e-300)
+            assert a.mask[p] == (0 if r["fp8"] else 1)
+        rebuilt = np.ldexp(F32(1.0) + F32(int(a.group_mantissas[g, 0])) / F32(2 ** 23), int(a.e8m0[p]) - 127)
+        assert F32(rebuilt) == a.scale[p]
+
+
+def test_gam_row_band_groups_guarantees(oracle):
+    """Per band: no saturation, at most one binade lost against the block's own FP32 scale, and the block that holds the
+    band's amax is scaled by s_g itself (the band's amax is kept at full precision)."""
+    rng = np.random.default_rng(3)
+    rows, cols, band = 64, 128, 8
+    x = (rng.standard_normal((rows, cols)) * np.exp2(rng.integers(-20, 20, size=(rows, 1)))).astype(np.float32)
+    xb = W.f32_to_bf16_bits(x)
+    a = oracle.analyze_quantize(xb, "sub1x128", scaling="gam", gam_group_rows=band)
+    own = oracle.analyze_quantize(xb, "sub1x128", scaling="fp32_amax")
+    assert np.all(a.scale <= own.scale) and np.all(a.scale > own.scale / 2)
+    y = W.bf16_bits_to_f32(xb) * a.scale[:, None]
+    assert np.all(np.abs(y) <= 448.0 * (1 + 2.0 ** -22))
+    for g in range(rows // band):
+        top = g * band + int(np.argmax(a.amax[g * band:(g + 1) * band]))
+        assert a.scale[top] == own.scale[top]
+    # more groups never scale a block down further than one group does
+    one = oracle.analyze_quantize(xb, "sub1x128", scaling="gam")
+    assert np.all(a.scale >= one.scale / 2) and (a.scale != one.scale).any()
+
+
+def test_gam_row_band_groups_must_hold_whole_blocks(oracle):
+    xb = W.activation(256, 256, 9)
+    with pytest.raises(ValueError):
+        oracle.analyze_quantize(xb, "block128", scaling="gam", gam_group_rows=64)
+    with pytest.raises(ValueError):
+        oracle.analyze_quantize(xb, "channel_col", scaling="gam", gam_group_rows=128)      # a column block spans every band
+    with pytest.raises(ValueError):
+        oracle.analyze_quantize(xb, "tensor", scaling="gam", gam_group_rows=128)
