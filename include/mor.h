@@ -112,8 +112,8 @@ typedef enum {
     MOR_SCALE_FP32_AMAX = 0,    /* s = fl32(448 / amax): one binary32 scale per block straight from its amax
                                    (first scaling variant of the ablation in Section 4.1.2).  amax == 0 -> s = 1;
                                    an overflowing quotient -> s = FLT_MAX; non-finite amax -> s = 1. */
-    MOR_SCALE_GAM = 1,          /* Group Amax Mantissa scaling (Algorithm 1) with one group = the whole
-                                   operand: s_g = fl32(448 / amax of the operand), m_g = its mantissa;
+    MOR_SCALE_GAM = 1,          /* Group Amax Mantissa scaling (Algorithm 1).  One group = the whole operand unless
+                                   mor_params.gam_group_rows says otherwise: s_g = fl32(448 / amax of the group), m_g = its mantissa;
                                    per block s_b as above, e = exponent(s_b), lowered by one when
                                    m_g > mantissa(s_b); applied scale s = m_g * 2^e (s_b/2 < s <= s_b).
                                    Stored form: one 23-bit mantissa + one E8M0 byte per block.  The
@@ -135,7 +135,11 @@ typedef struct mor_params {
     uint32_t formats;     /* MOR_FMT_E4M3 | MOR_FMT_BF16, or MOR_FMT_E4M3 | MOR_FMT_E5M2 | MOR_FMT_BF16 */
     float    threshold;   /* th_E4M3 of Eq. (2), e.g. 0.045f (Section 4.1.1); ignored for Eq. (3) */
     uint32_t flags;       /* MOR_FLAG_* bits */
-    uint32_t reserved;    /* must be 0 */
+    uint32_t gam_group_rows; /* MOR_SCALE_GAM only (ignored otherwise): 0 = one group, the whole operand (the configuration of the
+                                paper's experiments); else the groups of Algorithm 1 are bands of this many consecutive rows,
+                                each with its own mantissa m_g.  A band must hold whole blocks (a multiple of the block
+                                height: 128, 64 or 1), so per-tensor granularity and per-channel columns take 0 only
+                                (MOR_ERR_UNSUPPORTED); a value >= rows means one group.  n_groups = ceil(rows / gam_group_rows) */
 } mor_params;
 
 typedef struct mor_outputs {
@@ -157,9 +161,10 @@ typedef struct mor_outputs {
                            for MOR_CRIT_E4M3_VS_E5M2, otherwise ignored and may be NULL */
     uint8_t*  scale_e8m0;     /* [P] MOR_SCALE_GAM / MOR_SCALE_E8M0: biased exponent (bias 127) of scale[p];
                                  optional (NULL = not written); untouched for MOR_SCALE_FP32_AMAX */
-    uint32_t* group_mantissa; /* [2] MOR_SCALE_GAM / MOR_SCALE_E8M0: [0] the 23 fraction bits of m_g (0 for
-                                 E8M0-only), so that scale[p] == bits((scale_e8m0[p] << 23) | group_mantissa[0]);
-                                 [1] the same for the E5M2 scales (used by blocks with mask == 2);
+    uint32_t* group_mantissa; /* [2 * n_groups] MOR_SCALE_GAM / MOR_SCALE_E8M0 (n_groups = 1 unless gam_group_rows is set):
+                                 [2g] the 23 fraction bits of group g's m_g (0 for E8M0-only), so that for a block p of
+                                 group g scale[p] == bits((scale_e8m0[p] << 23) | group_mantissa[2g]);
+                                 [2g + 1] the same for the E5M2 scales (used by blocks with mask == 2);
                                  optional; untouched for MOR_SCALE_FP32_AMAX */
     float*    amin;     /* [P] three-way recipe: smallest non-zero |x| of blocks that failed M_1 (0 when the block
                            has no non-zero element, and for blocks kept in E4M3); optional */
@@ -302,9 +307,9 @@ mor_status mor_dequantize(const mor_params* params, const uint8_t* fp8, int64_t 
 /*
  * The same from the stored form of GAM / E8M0 scaling (Algorithm 1 and the paragraph before it: the
  * per-block scale is rebuilt on the fly from the shared 23-bit group mantissa and the block's 8-bit
- * exponent): scale[p] = bits((scale_e8m0[p] << 23) | group_mantissa[0]), with group_mantissa[1] in
- * blocks with mask 2.  scale_e8m0 [P] and group_mantissa [2] are device arrays as written by
- * mor_analyze_quantize.
+ * exponent): scale[p] = bits((scale_e8m0[p] << 23) | group_mantissa[2g]) for a block of group g, with
+ * group_mantissa[2g + 1] in blocks with mask 2.  scale_e8m0 [P] and group_mantissa [2 * n_groups] are device
+ * arrays as written by mor_analyze_quantize with the same params (gam_group_rows included).
  */
 mor_status mor_dequantize_e8m0(const mor_params* params, const uint8_t* fp8, int64_t ld_fp8,
                                const uint8_t* scale_e8m0, const uint32_t* group_mantissa, const uint8_t* mask,
@@ -321,7 +326,7 @@ typedef struct mor_dequant_item {
     const uint8_t*  fp8;   int64_t ld_fp8;
     const float*    scale;           /* [P], or NULL for the stored GAM / E8M0 form */
     const uint8_t*  scale_e8m0;      /* [P] when scale == NULL */
-    const uint32_t* group_mantissa;  /* [2] when scale == NULL */
+    const uint32_t* group_mantissa;  /* [2 * n_groups] when scale == NULL */
     const uint8_t*  mask;            /* [P] */
     const uint16_t* bf16;  int64_t ld_bf16;   /* fallback payload, may be NULL */
     uint16_t*       y;     int64_t ld_y;

@@ -408,7 +408,8 @@ int mor_oracle_run(const oracle_params *pp, const uint16_t *x, const oracle_out 
     /* groups of Algorithm 1: bands of whole blocks (a block never straddles two groups) */
     if (pp->group_rows < 0) return -1;
     band = pp->group_rows > 0 && pp->scaling == SCALING_GAM ? pp->group_rows : rows;
-    if (band % pr) return -1;
+    if (band >= rows) band = rows;                           /* one group */
+    else if (band % pr) return -1;
     n_groups = (rows + band - 1) / band;
     if (pp->scaling < SCALING_FP32_AMAX || pp->scaling > SCALING_E8M0) return -1;
     if (!three && pp->formats != (FMT_E4M3 | FMT_BF16)) return -1;

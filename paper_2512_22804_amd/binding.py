@@ -49,7 +49,7 @@ KERNEL_NAMES = {1: "sub1x128", 2: "block128", 3: "tensor_amax", 4: "tensor_quant
 class MorParams(C.Structure):
     _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64),
                 ("granularity", C.c_int32), ("scope", C.c_int32), ("criterion", C.c_int32), ("scaling", C.c_int32),
-                ("formats", C.c_uint32), ("threshold", C.c_float), ("flags", C.c_uint32), ("reserved", C.c_uint32)]
+                ("formats", C.c_uint32), ("threshold", C.c_float), ("flags", C.c_uint32), ("gam_group_rows", C.c_uint32)]
 
 
 class MorOutputs(C.Structure):
@@ -146,14 +146,15 @@ def load():
 
 def make_params(rows: int, cols: int, gran: str | int, scope: str | int = "partition", crit: str | int = "mean_rel_err",
                 threshold: float = 0.045, ld: int | None = None, formats: int | str = MOR_FMT_E4M3 | MOR_FMT_BF16,
-                scaling: str | int = MOR_SCALE_FP32_AMAX, ragged: bool = False, lean_fp8: bool = False) -> MorParams:
+                scaling: str | int = MOR_SCALE_FP32_AMAX, ragged: bool = False, lean_fp8: bool = False,
+                gam_group_rows: int = 0) -> MorParams:
     g = GRAN[gran] if isinstance(gran, str) else gran
     s = SCOPE[scope] if isinstance(scope, str) else scope
     c = CRIT[crit] if isinstance(crit, str) else crit
     sc = SCALING[scaling] if isinstance(scaling, str) else scaling
     f = FORMATS[formats] if isinstance(formats, str) else formats
     return MorParams(rows, cols, cols if ld is None else ld, g, s, c, sc, f, threshold,
-                     (MOR_FLAG_RAGGED if ragged else 0) | (MOR_FLAG_LEAN_FP8 if lean_fp8 else 0), 0)
+                     (MOR_FLAG_RAGGED if ragged else 0) | (MOR_FLAG_LEAN_FP8 if lean_fp8 else 0), int(gam_group_rows))
 
 
 def mor_num_partitions(gran: str | int, rows: int, cols: int) -> int:
@@ -191,8 +192,15 @@ class MorResult:
     workspace: torch.Tensor | None
     params: MorParams
     scale_e8m0: torch.Tensor | None = None      # (P,) uint8, GAM / E8M0 scaling only
-    group_mantissa: torch.Tensor | None = None  # (2,) int32, GAM / E8M0 scaling only: E4M3's, E5M2's
+    group_mantissa: torch.Tensor | None = None  # (2 * n_groups,) int32, GAM / E8M0 scaling only: per group E4M3's, E5M2's
     amin: torch.Tensor | None = None            # (P,) float32, three-way recipe only
+
+
+def gam_groups(params: MorParams) -> int:
+    """Number of groups of Algorithm 1 for these parameters (1 unless GAM scaling with bands of rows as groups)."""
+    if params.scaling != MOR_SCALE_GAM or params.gam_group_rows == 0 or params.gam_group_rows >= params.rows:
+        return 1
+    return -(-params.rows // params.gam_group_rows)
 
 
 def alloc_outputs(params: MorParams, device, want_bf16: bool = True, bf16_fill: int | None = None,
@@ -214,7 +222,7 @@ def alloc_outputs(params: MorParams, device, want_bf16: bool = True, bf16_fill: 
     e8m0 = gmant = None
     if params.scaling != MOR_SCALE_FP32_AMAX:
         e8m0 = torch.full((P,), 0xEE, dtype=torch.uint8, device=device)
-        gmant = torch.full((2,), -1, dtype=torch.int32, device=device)
+        gmant = torch.full((2 * gam_groups(params),), -1, dtype=torch.int32, device=device)
     amin = torch.full((P,), -1.0, dtype=torch.float32, device=device) if params.formats & MOR_FMT_E5M2 else None
     return MorResult(fp8, bf16, f32(), f32(), f32(), torch.empty(P, dtype=torch.int32, device=device),
                      torch.empty(P, dtype=torch.uint8, device=device), err5, ws, params, e8m0, gmant, amin)

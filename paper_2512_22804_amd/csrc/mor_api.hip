@@ -44,8 +44,17 @@ mor_status check_shape(int32_t gran, int64_t rows, int64_t cols, bool ragged) {
 }
 mor_status check_common(const mor_params* p) {
     if (!p) return MOR_ERR_NULL;
-    if ((p->flags & ~(uint32_t)(MOR_FLAG_RAGGED | MOR_FLAG_LEAN_FP8)) || p->reserved) return MOR_ERR_UNSUPPORTED;
+    if (p->flags & ~(uint32_t)(MOR_FLAG_RAGGED | MOR_FLAG_LEAN_FP8)) return MOR_ERR_UNSUPPORTED;
     return check_shape(p->granularity, p->rows, p->cols, (p->flags & MOR_FLAG_RAGGED) != 0);
+}
+// Rows per group of Algorithm 1 as the kernels see it: 0 = one group.  `*st` receives the argument error, if any.
+int64_t group_rows_of(const mor_params* p, mor_status* st) {
+    *st = MOR_OK;
+    if (p->scaling != MOR_SCALE_GAM || p->gam_group_rows == 0 || (int64_t)p->gam_group_rows >= p->rows) return 0;
+    if (p->granularity == MOR_GRAN_TENSOR || p->granularity == MOR_GRAN_CHANNEL_COL) { *st = MOR_ERR_UNSUPPORTED; return 0; }
+    const mor::StatsGeom g = mor::make_geom(p->granularity, p->rows, p->cols);
+    if (p->gam_group_rows % g.pr) { *st = MOR_ERR_SHAPE; return 0; }      // a band holds whole blocks
+    return (int64_t)p->gam_group_rows;
 }
 
 }  // namespace
@@ -105,6 +114,8 @@ static mor_status make_item(const mor_params* p, const uint16_t* x, const mor_ou
          reinterpret_cast<uintptr_t>(out->amin)) & 3u) return MOR_ERR_ALIGN;
     if (stats && (reinterpret_cast<uintptr_t>(stats) & 7u)) return MOR_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(out->group_mantissa) & 3u) return MOR_ERR_ALIGN;
+    item->group_rows = group_rows_of(p, &st);
+    if (st != MOR_OK) return st;
     item->sh = mor::KShape{p->rows, p->cols, p->ld};
     if (fake_y)
         item->o = mor::KOut{nullptr, p->cols, fake_y, ld_fake, out->scale, out->amax, out->err_sum, out->nnz, out->mask,
@@ -135,6 +146,9 @@ size_t mor_workspace_bytes(const mor_params* p) {
     it.o.ld_fp8 = p->cols;
     it.scaling = p->scaling;
     it.ragged = (p->flags & MOR_FLAG_RAGGED) ? 1 : 0;
+    mor_status st;
+    it.group_rows = group_rows_of(p, &st);
+    if (st != MOR_OK) return 0;
     return mor::batch_workspace_bytes(&it, 1);
 }
 
@@ -235,8 +249,11 @@ static mor_status dequantize_any(const mor_params* p, const uint8_t* fp8, int64_
                                  int64_t ld_bf16, uint16_t* y, int64_t ld_y, void* stream) {
     mor_status st = check_dequantize(p, fp8, ld_fp8, scale, e8m0, gmant, mask, bf16, ld_bf16, y, ld_y);
     if (st != MOR_OK) return st;
+    mor_status gs;
+    const int64_t group_rows = group_rows_of(p, &gs);
+    if (e8m0 && gs != MOR_OK) return gs;
     hipError_t e = mor::launch_dequantize(mor::make_geom(p->granularity, p->rows, p->cols), fp8, ld_fp8, scale, mask, bf16, ld_bf16,
-                                          y, ld_y, e8m0, gmant, static_cast<hipStream_t>(stream));
+                                          y, ld_y, e8m0, gmant, e8m0 ? group_rows : 0, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? MOR_OK : MOR_ERR_HIP;
 }
 
@@ -250,8 +267,12 @@ mor_status mor_dequantize_batch(const mor_dequant_item* items, int32_t n_items, 
         mor_status st = check_dequantize(&d.params, d.fp8, d.ld_fp8, d.scale, d.scale_e8m0, d.group_mantissa, d.mask, d.bf16, d.ld_bf16,
                                          d.y, d.ld_y);
         if (st != MOR_OK) return st;
+        mor_status gs;
+        const int64_t group_rows = group_rows_of(&d.params, &gs);
+        if (stored && gs != MOR_OK) return gs;
         its[i] = mor::DeqItem{mor::make_geom(d.params.granularity, d.params.rows, d.params.cols), d.fp8, d.ld_fp8, d.scale, d.mask,
-                              d.bf16, d.ld_bf16, d.y, d.ld_y, stored ? d.scale_e8m0 : nullptr, stored ? d.group_mantissa : nullptr};
+                              d.bf16, d.ld_bf16, d.y, d.ld_y, stored ? d.scale_e8m0 : nullptr, stored ? d.group_mantissa : nullptr,
+                              stored ? group_rows : 0};
     }
     hipError_t e = mor::launch_dequantize_batch(its, n_items, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? MOR_OK : MOR_ERR_HIP;

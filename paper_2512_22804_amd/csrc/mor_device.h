@@ -58,6 +58,13 @@ __device__ __forceinline__ float block_scale(uint32_t abits, float q_amax, uint3
     const uint32_t e = (b >> 23) - ((mg > (b & 0x7FFFFFu)) ? 1u : 0u);
     return __uint_as_float((e << 23) | mg);
 }
+// Words that the group loop of Algorithm 1 leaves for the block kernels of one operand: {mantissa for E4M3, for E5M2, "BF16
+// proven" flag, unused} when the operand is one group; with bands of `group_rows` rows as groups, a table of {E4M3, E5M2}
+// mantissas per band follows those four words.  Returns the two words of the block whose first row is r0.
+constexpr int kGamHeaderWords = 4;
+__device__ __forceinline__ const uint32_t* gam_words(const uint32_t* gam, uint32_t group_rows, int64_t r0) {
+    return group_rows ? gam + kGamHeaderWords + 2 * (r0 / group_rows) : gam;
+}
 // With a scale of up to one binade below s_b, the smallest BF16 subnormal times the scale can round to a
 // binary32 zero one binade of amax earlier, so the branch-free path ends at 2^24 instead of 2^25.
 __device__ __forceinline__ uint32_t fast_amax_limit(uint32_t mode) { return mode == kScaleFp32 ? kFastAmaxBits : kFastAmaxBits - 0x80u; }

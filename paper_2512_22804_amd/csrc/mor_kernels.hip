@@ -87,9 +87,8 @@ __device__ __forceinline__ void sub_block_body(const u32x4& raw, const uint16_t*
 // quantization): grid.x = 128-column block, grid.y strides over groups of 16 rows.
 template <int CRIT, bool DEFER, bool FAKE>
 __global__ __launch_bounds__(256) void k_sub1x128_strided(const uint16_t* __restrict__ x, KShape sh, KOut o, float th,
-                                                          uint32_t mode, const uint32_t* __restrict__ gam, uint32_t three) {
+                                                          uint32_t mode, const uint32_t* __restrict__ gam, uint32_t three, uint32_t group_rows) {
     const int lane = threadIdx.x & 63, g = lane >> 4, l = lane & 15;
-    const uint32_t mg = mode ? gam[0] : 0u, mg5 = mode ? gam[1] : 0u;
     const int64_t cb = blockIdx.x, cpr = (sh.cols + 127) / 128;
     const int64_t c = cb * 128 + l * 8;
     const bool valid = c < sh.cols;
@@ -97,6 +96,8 @@ __global__ __launch_bounds__(256) void k_sub1x128_strided(const uint16_t* __rest
         const uint16_t* src = x + r * sh.ld + c;
         u32x4 raw; raw.x = 0u; raw.y = 0u; raw.z = 0u; raw.w = 0u;
         if (valid) raw = load16(src);
+        uint32_t mg = 0u, mg5 = 0u;
+        if (mode) { const uint32_t* gw = gam_words(gam, group_rows, r); mg = gw[0]; mg5 = gw[1]; }
         sub_block_body<CRIT, DEFER, FAKE>(raw, src, valid, l, r * cpr + cb, o, FAKE ? nullptr : o.fp8 + r * o.ld_fp8 + c,
                                           o.bf16 ? o.bf16 + r * o.ld_bf16 + c : nullptr, FAKE ? o.fake + r * o.ld_fake + c : nullptr,
                                           th, mode, mg, mg5, three != 0u);
@@ -455,9 +456,9 @@ __global__ __launch_bounds__(256) void k_scope_copy_group(GroupScope g) {
 // column scales are inverted once per tile.
 // ======================================================================================
 __device__ __forceinline__ float dequant_scale(const float* __restrict__ scale, const uint8_t* __restrict__ e8m0,
-                                               const uint32_t* __restrict__ gmant, int64_t p, uint32_t mk) {
-    // stored GAM form (Algorithm 1): the scale is rebuilt from the shared mantissa and the block's E8M0 byte
-    return e8m0 ? __uint_as_float(((uint32_t)e8m0[p] << 23) | gmant[mk == 2u ? 1 : 0]) : scale[p];
+                                               const uint32_t* __restrict__ gmant, int64_t p, uint32_t mk, int64_t band) {
+    // stored GAM form (Algorithm 1): the scale is rebuilt from the group's shared mantissa and the block's E8M0 byte
+    return e8m0 ? __uint_as_float(((uint32_t)e8m0[p] << 23) | gmant[2 * band + (mk == 2u ? 1 : 0)]) : scale[p];
 }
 template <bool E5M2>
 __device__ __forceinline__ u32x4 dequant8(const u32x2& q, float s_inv) {
@@ -473,7 +474,8 @@ __device__ __forceinline__ u32x4 dequant8(const u32x2& q, float s_inv) {
 __global__ __launch_bounds__(256) void k_dequant(StatsGeom g, int pr_log2, int pc_log2, const uint8_t* __restrict__ fp8, int64_t ld_fp8,
                                                  const float* __restrict__ scale, const uint8_t* __restrict__ mask,
                                                  const uint16_t* __restrict__ bf16, int64_t ld_bf16, uint16_t* __restrict__ y,
-                                                 int64_t ld_y, const uint8_t* __restrict__ e8m0, const uint32_t* __restrict__ gmant) {
+                                                 int64_t ld_y, const uint8_t* __restrict__ e8m0, const uint32_t* __restrict__ gmant,
+                                                 int64_t group_rows) {
     const int64_t c = (int64_t)blockIdx.x * 128 + (threadIdx.x & 15) * 8;
     if (c >= g.cols) return;
     for (int64_t r = (int64_t)blockIdx.y * 16 + (threadIdx.x >> 4); r < g.rows; r += (int64_t)gridDim.y * 16) {
@@ -483,7 +485,7 @@ __global__ __launch_bounds__(256) void k_dequant(StatsGeom g, int pr_log2, int p
             if (bf16) store16(y + r * ld_y + c, load16(bf16 + r * ld_bf16 + c));
             continue;
         }
-        const float s_inv = 1.0f / dequant_scale(scale, e8m0, gmant, p, mk);     // correctly rounded IEEE division
+        const float s_inv = 1.0f / dequant_scale(scale, e8m0, gmant, p, mk, group_rows ? r / group_rows : 0);     // correctly rounded IEEE division
         const u32x2 q = *reinterpret_cast<const u32x2*>(fp8 + r * ld_fp8 + c);
         store16(y + r * ld_y + c, mk == 2u ? dequant8<true>(q, s_inv) : dequant8<false>(q, s_inv));
     }
@@ -500,6 +502,7 @@ struct DeqOp {
     const uint16_t* bf16; int64_t ld_bf16;
     uint16_t* y; int64_t ld_y;
     const uint8_t* e8m0; const uint32_t* gmant;
+    int64_t group_rows;
 };
 struct GroupDeq {
     int n;
@@ -524,7 +527,7 @@ __global__ __launch_bounds__(256) void k_dequant_group(GroupDeq gd) {
         if (r < t.g.rows) {
             const int64_t p = (r >> t.pr_log2) * t.g.gc + (c >> t.pc_log2);
             mk[k] = t.mask[p];
-            s[k] = dequant_scale(t.scale, t.e8m0, t.gmant, p, mk[k]);
+            s[k] = dequant_scale(t.scale, t.e8m0, t.gmant, p, mk[k], t.group_rows ? r / t.group_rows : 0);
             if (mk[k] != 1u) q[k] = *reinterpret_cast<const u32x2*>(t.fp8 + r * t.ld_fp8 + c);
         }
     }
@@ -543,10 +546,12 @@ __global__ __launch_bounds__(256) void k_dequant_group(GroupDeq gd) {
 __global__ __launch_bounds__(256) void k_dequant_columns(StatsGeom g, int pr_log2, const uint8_t* __restrict__ fp8, int64_t ld_fp8,
                                                          const float* __restrict__ scale, const uint8_t* __restrict__ mask,
                                                          const uint16_t* __restrict__ bf16, int64_t ld_bf16, uint16_t* __restrict__ y,
-                                                         int64_t ld_y, const uint8_t* __restrict__ e8m0, const uint32_t* __restrict__ gmant) {
+                                                         int64_t ld_y, const uint8_t* __restrict__ e8m0, const uint32_t* __restrict__ gmant,
+                                                         int64_t group_rows) {
     const int64_t c = (int64_t)blockIdx.x * 128 + (threadIdx.x & 15) * 8;
     if (c >= g.cols) return;
     for (int64_t tr = blockIdx.y; tr * 128 < g.rows; tr += gridDim.y) {
+        const int64_t band = group_rows ? tr * 128 / group_rows : 0;        // (a band holds whole 128 x 1 blocks)
         const int64_t p0 = ((tr * 128) >> pr_log2) * g.gc + c;
         float s_inv[8];
         uint32_t mk[8];
@@ -555,7 +560,7 @@ __global__ __launch_bounds__(256) void k_dequant_columns(StatsGeom g, int pr_log
         for (int j = 0; j < 8; ++j) {
             mk[j] = mask[p0 + j];
             any_bf16 |= mk[j] == 1u;
-            s_inv[j] = 1.0f / dequant_scale(scale, e8m0, gmant, p0 + j, mk[j]);
+            s_inv[j] = 1.0f / dequant_scale(scale, e8m0, gmant, p0 + j, mk[j], band);
         }
 #pragma unroll 1
         for (int i = 0; i < 8; ++i) {
@@ -1285,10 +1290,47 @@ __global__ __launch_bounds__(256) void k_gam_prepare(GroupGam g) {
     }
 }
 
+// Group loop of Algorithm 1 with bands of rows as groups: workgroup (band, w) scans its share of the band's 16-byte chunks,
+// then one lane per band turns the band's amax into its two mantissas (table behind the four header words of `gam`).
+__global__ __launch_bounds__(256) void k_band_amax(const uint16_t* __restrict__ x, KShape sh, int64_t group_rows, int wpb,
+                                                   uint32_t* __restrict__ part) {
+    __shared__ uint32_t sh4[4];
+    const int64_t band = blockIdx.x / wpb;
+    const int w = blockIdx.x - (int)band * wpb;
+    const int64_t r_first = band * group_rows;
+    const int64_t n_rows = sh.rows - r_first < group_rows ? sh.rows - r_first : group_rows;
+    const int64_t cpr = sh.cols / 8, n_chunks = n_rows * cpr;
+    uint32_t a2 = 0u;
+    for (int64_t c = (int64_t)w * 256 + threadIdx.x; c < n_chunks; c += (int64_t)wpb * 256) {
+        const int64_t r = c / cpr, cc = c - r * cpr;
+        a2 = amax2_of(load16(x + (r_first + r) * sh.ld + cc * 8), a2);
+    }
+    const uint32_t a = block_allmax_u32(fold_max16(a2), sh4);
+    if (threadIdx.x == 0) part[blockIdx.x] = a;
+}
+__global__ __launch_bounds__(256) void k_gam_prepare_bands(const uint32_t* __restrict__ part, int wpb, int64_t n_groups,
+                                                           uint32_t* __restrict__ gam, uint32_t* __restrict__ gmant) {
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (blockIdx.x == 0 && threadIdx.x < kGamHeaderWords) gam[threadIdx.x] = 0u;     // no single mantissa, nothing proven
+    if (g >= n_groups) return;
+    uint32_t a = 0u;
+    for (int k = 0; k < wpb; ++k) a = max(a, part[g * wpb + k]);
+    const uint32_t mg = group_mantissa_bits(a, kE4M3Max, kScaleGam), mg5 = group_mantissa_bits(a, kE5M2Max, kScaleGam);
+    gam[kGamHeaderWords + 2 * g] = mg; gam[kGamHeaderWords + 2 * g + 1] = mg5;
+    if (gmant) { gmant[2 * g] = mg; gmant[2 * g + 1] = mg5; }
+}
+
 // ======================================================================================
 // Launchers
 // ======================================================================================
 static inline size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
+// Workgroups per band of the band-amax pass: about 2048 in all, at most one per 8 KB of the band.
+static int band_wgs(const BatchItem& it) {
+    const int64_t n_groups = (it.sh.rows + it.group_rows - 1) / it.group_rows;
+    int64_t per = 2048 / n_groups, cap = (it.group_rows * it.sh.cols + 4095) / 4096;
+    if (per > cap) per = cap;
+    return (int)(per < 1 ? 1 : per);
+}
 
 
 TensorPlan plan_tensor(int64_t, int64_t) {
@@ -1322,22 +1364,22 @@ static int clamp_grid_y(int64_t v) { return (int)(v < 1 ? 1 : (v > 65535 ? 65535
 // The general 1 x 128 kernel: one operand per launch.
 template <int CRIT>
 static void launch_sub1x128_crit(const dim3& grid, const uint16_t* x, const KShape& sh, const KOut& o, bool defer, float th,
-                                 uint32_t mode, const uint32_t* gam, uint32_t three, hipStream_t st) {
+                                 uint32_t mode, const uint32_t* gam, uint32_t three, uint32_t group_rows, hipStream_t st) {
     const bool fake = o.fake != nullptr;
     if (defer) {
-        if (fake) k_sub1x128_strided<CRIT, true, true><<<grid, dim3(256), 0, st>>>(x, sh, o, th, mode, gam, three);
-        else k_sub1x128_strided<CRIT, true, false><<<grid, dim3(256), 0, st>>>(x, sh, o, th, mode, gam, three);
+        if (fake) k_sub1x128_strided<CRIT, true, true><<<grid, dim3(256), 0, st>>>(x, sh, o, th, mode, gam, three, group_rows);
+        else k_sub1x128_strided<CRIT, true, false><<<grid, dim3(256), 0, st>>>(x, sh, o, th, mode, gam, three, group_rows);
     } else {
-        if (fake) k_sub1x128_strided<CRIT, false, true><<<grid, dim3(256), 0, st>>>(x, sh, o, th, mode, gam, three);
-        else k_sub1x128_strided<CRIT, false, false><<<grid, dim3(256), 0, st>>>(x, sh, o, th, mode, gam, three);
+        if (fake) k_sub1x128_strided<CRIT, false, true><<<grid, dim3(256), 0, st>>>(x, sh, o, th, mode, gam, three, group_rows);
+        else k_sub1x128_strided<CRIT, false, false><<<grid, dim3(256), 0, st>>>(x, sh, o, th, mode, gam, three, group_rows);
     }
 }
 static hipError_t launch_sub1x128(const uint16_t* x, const KShape& sh, const KOut& o, int crit, bool defer, float th, uint32_t mode,
-                                  const uint32_t* gam, uint32_t three, hipStream_t st, KProf* prof) {
+                                  const uint32_t* gam, uint32_t three, uint32_t group_rows, hipStream_t st, KProf* prof) {
     ProfScope ps(prof, kKernSub1x128, st);
     const dim3 grid((unsigned)((sh.cols + 127) / 128), (unsigned)clamp_grid_y((sh.rows + 15) / 16));
-    if (crit == kCritEq3) launch_sub1x128_crit<kCritEq3>(grid, x, sh, o, defer, th, mode, gam, three, st);
-    else launch_sub1x128_crit<kCritEq2>(grid, x, sh, o, defer, th, mode, gam, three, st);
+    if (crit == kCritEq3) launch_sub1x128_crit<kCritEq3>(grid, x, sh, o, defer, th, mode, gam, three, group_rows, st);
+    else launch_sub1x128_crit<kCritEq2>(grid, x, sh, o, defer, th, mode, gam, three, group_rows, st);
     return hipGetLastError();
 }
 
@@ -1397,7 +1439,9 @@ Route route_of(const BatchItem& it) {
     const bool plain = !it.three;
     switch (it.gran) {
     case kGranTensor: return item_is_flat(it) ? kRouteTensorGroup : kRouteTensorStrided;
-    case kGranSub: return (plain && item_is_flat(it) && it.sh.cols % 128 == 0) ? kRouteSubFlat : kRouteSubGeneral;
+    case kGranSub:      // (with bands of rows as GAM groups the flat kernel takes whole 32-block units only: no renumbered tail)
+        return (plain && item_is_flat(it) && it.sh.cols % 128 == 0 && (it.group_rows == 0 || (it.sh.rows * (it.sh.cols / 128)) % 32 == 0))
+                   ? kRouteSubFlat : kRouteSubGeneral;
     case kGranBlock: case kGranBlock64: case kGranRow: return kRouteTeam;
     case kGranSubCol: return kRouteSubCol;
     default: return kRouteChannelCol;
@@ -1422,7 +1466,11 @@ size_t item_workspace(const BatchItem& it) {
     if (it.stats && it.gran != kGranTensor) b += align16(sizeof(StatsRec) * kStatsMaxWg);
     if (it.gran != kGranTensor && it.scaling != kScaleFp32) {
         b += 16;                                                                   // group mantissa words
-        if (it.scaling == kScaleGam) b += 2 * align16(sizeof(uint32_t) * kProveMaxWg);   // amax and flush partials of the pre-pass
+        if (it.scaling == kScaleGam && it.group_rows == 0) b += 2 * align16(sizeof(uint32_t) * kProveMaxWg);   // amax and flush partials of the pre-pass
+        if (it.scaling == kScaleGam && it.group_rows != 0) {                       // bands of rows as groups: mantissa table, amax partials
+            const size_t n_groups = (size_t)((it.sh.rows + it.group_rows - 1) / it.group_rows);
+            b += align16(8 * n_groups) + align16(sizeof(uint32_t) * n_groups * (size_t)band_wgs(it));
+        }
     }
     return b;
 }
@@ -1486,7 +1534,21 @@ void BatchRun::group_mantissas() {
     int idx[kBatchMax];
     int cnt = 0;
     for (int i = 0; i < n; ++i)
-        if (items[i].gran != kGranTensor && items[i].scaling != kScaleFp32) idx[cnt++] = i;
+        if (items[i].gran != kGranTensor && items[i].scaling != kScaleFp32 && items[i].group_rows == 0) idx[cnt++] = i;
+    // operands whose groups are bands of rows: one mantissa pair per band, in a table behind the four header words
+    for (int i = 0; i < n && err == hipSuccess; ++i) {
+        const BatchItem& it = items[i];
+        if (it.group_rows == 0) continue;
+        const int64_t n_groups = (it.sh.rows + it.group_rows - 1) / it.group_rows;
+        const int wpb = band_wgs(it);
+        if (n_groups * wpb > 0x7FFFFFFF) { err = hipErrorInvalidValue; return; }
+        uint32_t* gam = reinterpret_cast<uint32_t*>(carve(16 + align16(8 * (size_t)n_groups)));
+        uint32_t* part = reinterpret_cast<uint32_t*>(carve(sizeof(uint32_t) * (size_t)n_groups * (size_t)wpb));
+        if (err != hipSuccess) return;
+        gam_of[i] = gam;
+        { ProfScope ps(prof, kKernGroupAmax, st); k_band_amax<<<dim3((unsigned)(n_groups * wpb)), dim3(256), 0, st>>>(it.x, it.sh, it.group_rows, wpb, part); }
+        { ProfScope ps(prof, kKernGroupMantissa, st); k_gam_prepare_bands<<<dim3((unsigned)((n_groups + 255) / 256)), dim3(256), 0, st>>>(part, wpb, n_groups, gam, it.o.gmant); }
+    }
     // operands whose tensor-level decision the pre-pass may prove: block-shaped pre-pass (group amax and, per block,
     // the elements that are certain to flush), as many operands per launch as its argument table holds
     uint32_t* pv_part[kBatchMax] = {};
@@ -1620,6 +1682,7 @@ void BatchRun::sub_tensor_operands(int crit) {
                 rider_units += n_units;
                 r.unit_end[r.n] = rider_units; r.x[r.n] = it.x; r.o[r.n] = it.o; r.th[r.n] = it.th; r.defer[r.n] = it.scope == 1;
                 r.mode[r.n] = (uint8_t)it.scaling; r.gam[r.n] = gam_of[i]; r.prove[r.n] = scope_proof_applies(it) ? 1 : 0;
+                r.group_rows[r.n] = (uint32_t)it.group_rows; r.bpr[r.n] = (uint32_t)(it.sh.cols / 128);
                 ++r.n;
                 riders.fake = fake != 0;
                 riders.blocks = (rider_units + 3) / 4 < kSubFlatMaxBlocks ? (rider_units + 3) / 4 : kSubFlatMaxBlocks;
@@ -1627,6 +1690,7 @@ void BatchRun::sub_tensor_operands(int crit) {
                 total += n_units;
                 g.unit_end[g.n] = total; g.x[g.n] = it.x; g.o[g.n] = it.o; g.th[g.n] = it.th; g.defer[g.n] = it.scope == 1;
                 g.mode[g.n] = (uint8_t)it.scaling; g.gam[g.n] = gam_of[i]; g.prove[g.n] = scope_proof_applies(it) ? 1 : 0;
+                g.group_rows[g.n] = (uint32_t)it.group_rows; g.bpr[g.n] = (uint32_t)(it.sh.cols / 128);
                 if (++g.n == kMaxGroupSub) flush();
             }
             if (n_tail > 0) {     // fewer than 32 blocks left: the general kernel takes them
@@ -1640,7 +1704,8 @@ void BatchRun::sub_tensor_operands(int crit) {
                 to.scale += n_full; to.amax += n_full; to.err_sum += n_full; to.nnz += n_full; to.mask += n_full;
                 if (to.err5_sum) to.err5_sum += n_full;
                 if (to.e8m0) to.e8m0 += n_full;
-                if (err == hipSuccess) err = launch_sub1x128(it.x + n_full * 128, ts, to, crit, it.scope == 1, it.th, (uint32_t)it.scaling, gam_of[i], 0u, st, nullptr);
+                // (the tail's rows are renumbered from 0; an operand with bands of rows as GAM groups has no tail, see route_of)
+                if (err == hipSuccess) err = launch_sub1x128(it.x + n_full * 128, ts, to, crit, it.scope == 1, it.th, (uint32_t)it.scaling, gam_of[i], 0u, 0u, st, nullptr);
             }
         }
         flush();
@@ -1649,7 +1714,8 @@ void BatchRun::sub_tensor_operands(int crit) {
     for (int i = 0; i < n && err == hipSuccess; ++i) {
         const BatchItem& it = items[i];
         if (route[i] != kRouteSubGeneral || it.crit != crit) continue;
-        err = launch_sub1x128(it.x, it.sh, it.o, crit, it.scope == 1, it.th, (uint32_t)it.scaling, gam_of[i], (uint32_t)it.three, st, prof);
+        err = launch_sub1x128(it.x, it.sh, it.o, crit, it.scope == 1, it.th, (uint32_t)it.scaling, gam_of[i], (uint32_t)it.three,
+                              (uint32_t)it.group_rows, st, prof);
     }
     // ---- team kernels: 128x128 and 64x64 blocks, per-channel rows
     for (int kind = 0; kind < kTeamKinds && err == hipSuccess; ++kind) {
@@ -1664,7 +1730,7 @@ void BatchRun::sub_tensor_operands(int crit) {
         for (int k = 0; k < g.n; ++k) {
             const SubRiders& r = riders.table;
             g.unit_end[k] = r.unit_end[k]; g.x[k] = r.x[k]; g.o[k] = r.o[k]; g.th[k] = r.th[k]; g.defer[k] = r.defer[k];
-            g.mode[k] = r.mode[k]; g.gam[k] = r.gam[k]; g.prove[k] = r.prove[k];
+            g.mode[k] = r.mode[k]; g.gam[k] = r.gam[k]; g.prove[k] = r.prove[k]; g.group_rows[k] = r.group_rows[k]; g.bpr[k] = r.bpr[k];
         }
         ProfScope ps(prof, kKernSub1x128, st);
         const dim3 grid((unsigned)riders.blocks);
@@ -1914,7 +1980,7 @@ hipError_t launch_dequantize_batch(const DeqItem* items, int n, hipStream_t st) 
         const DeqItem& it = items[i];
         if (it.geom.pc == 1 && it.geom.cols > 1) {       // one column per block: its own kernel
             hipError_t e = launch_dequantize(it.geom, it.fp8, it.ld_fp8, it.scale, it.mask, it.bf16, it.ld_bf16, it.y, it.ld_y, it.e8m0,
-                                             it.gmant, st);
+                                             it.gmant, it.group_rows, st);
             if (e != hipSuccess) return e;
             continue;
         }
@@ -1925,7 +1991,7 @@ hipError_t launch_dequantize_batch(const DeqItem* items, int n, hipStream_t st) 
         t.g = it.geom; t.pr_log2 = log2_or_whole(it.geom.pr, it.geom.rows); t.pc_log2 = log2_or_whole(it.geom.pc, it.geom.cols);
         t.strips_x = strips_x;
         t.fp8 = it.fp8; t.ld_fp8 = it.ld_fp8; t.scale = it.scale; t.mask = it.mask; t.bf16 = it.bf16; t.ld_bf16 = it.ld_bf16;
-        t.y = it.y; t.ld_y = it.ld_y; t.e8m0 = it.e8m0; t.gmant = it.gmant;
+        t.y = it.y; t.ld_y = it.ld_y; t.e8m0 = it.e8m0; t.gmant = it.gmant; t.group_rows = it.group_rows;
         total += units;
         g.unit_end[g.n] = total;
         if (++g.n == kMaxGroupDeq) flush();
@@ -1936,14 +2002,14 @@ hipError_t launch_dequantize_batch(const DeqItem* items, int n, hipStream_t st) 
 
 hipError_t launch_dequantize(const StatsGeom& geom, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
                              const uint8_t* mask, const uint16_t* bf16, int64_t ld_bf16, uint16_t* y, int64_t ld_y,
-                             const uint8_t* e8m0, const uint32_t* gmant, hipStream_t st) {
+                             const uint8_t* e8m0, const uint32_t* gmant, int64_t group_rows, hipStream_t st) {
     const int prl = log2_or_whole(geom.pr, geom.rows), pcl = log2_or_whole(geom.pc, geom.cols);
     if (geom.pc == 1 && geom.cols > 1) {
         const dim3 grid((unsigned)((geom.cols + 127) / 128), (unsigned)clamp_grid_y((geom.rows + 127) / 128));
-        k_dequant_columns<<<grid, dim3(256), 0, st>>>(geom, prl, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y, e8m0, gmant);
+        k_dequant_columns<<<grid, dim3(256), 0, st>>>(geom, prl, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y, e8m0, gmant, group_rows);
     } else {
         const dim3 grid((unsigned)((geom.cols + 127) / 128), (unsigned)clamp_grid_y((geom.rows + 15) / 16));
-        k_dequant<<<grid, dim3(256), 0, st>>>(geom, prl, pcl, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y, e8m0, gmant);
+        k_dequant<<<grid, dim3(256), 0, st>>>(geom, prl, pcl, fp8, ld_fp8, scale, mask, bf16, ld_bf16, y, ld_y, e8m0, gmant, group_rows);
     }
     return hipGetLastError();
 }

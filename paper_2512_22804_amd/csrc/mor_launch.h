@@ -119,6 +119,7 @@ struct BatchItem {
     int lean;               // 1: the FP8 payload of blocks already known to stay in BF16 need not be written
     float th;
     void* stats;            // device mor_stats* or nullptr
+    int64_t group_rows;     // GAM: 0 = one group (the whole operand); else the groups of Algorithm 1 are bands of this many rows
 };
 size_t batch_workspace_bytes(const BatchItem* items, int n);
 hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws, size_t ws_bytes, hipStream_t st, KProf* prof);
@@ -136,7 +137,7 @@ inline unsigned long long flush_need_of(float th, int64_t n) { return (unsigned 
 // flush inside their block, so the block kernel writes the BF16 payload from its registers and the operand is not read a third time.
 inline bool scope_proof_applies(const BatchItem& it) {
     // (fake quantization: o.bf16 == o.fake, and a proven operand's output is its input)
-    if (it.scaling != 1 || it.scope != 1 || it.crit != kCritEq2 || it.three || it.o.bf16 == nullptr) return false;
+    if (it.scaling != 1 || it.scope != 1 || it.crit != kCritEq2 || it.three || it.o.bf16 == nullptr || it.group_rows != 0) return false;
     if (!(it.th > 0.0f && it.th < 0.9f)) return false;      // the flush count is compared with 1.01 * th * N + 1
     const bool whole_tiles = it.sh.rows % 128 == 0 && it.sh.cols % 128 == 0;
     if (it.gran == kGranBlock || it.gran == kGranBlock64 || it.gran == kGranSubCol) return whole_tiles;
@@ -190,7 +191,7 @@ hipError_t launch_channel_col_items(const BatchItem* items, const int* idx, int 
 
 hipError_t launch_dequantize(const StatsGeom& geom, const uint8_t* fp8, int64_t ld_fp8, const float* scale,
                              const uint8_t* mask, const uint16_t* bf16, int64_t ld_bf16, uint16_t* y, int64_t ld_y,
-                             const uint8_t* e8m0, const uint32_t* gmant, hipStream_t st);
+                             const uint8_t* e8m0, const uint32_t* gmant, int64_t group_rows, hipStream_t st);
 // One operand of a de-quantize batch (validated by the caller).
 struct DeqItem {
     StatsGeom geom;
@@ -199,6 +200,7 @@ struct DeqItem {
     const uint16_t* bf16; int64_t ld_bf16;
     uint16_t* y; int64_t ld_y;
     const uint8_t* e8m0; const uint32_t* gmant;
+    int64_t group_rows;      // stored GAM form: rows per group (0 = one group)
 };
 hipError_t launch_dequantize_batch(const DeqItem* items, int n, hipStream_t st);
 hipError_t launch_select_stats(const StatsGeom& geom, const float* err_sum, const uint32_t* nnz,

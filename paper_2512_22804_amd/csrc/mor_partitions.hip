@@ -36,6 +36,7 @@ struct TeamOp {
     int64_t units_x;        // 128-column tiles per row of tiles (block kinds)
     float th;
     uint8_t defer, mode, three, prove;      // prove: gam[2] != 0 says the tensor-level BF16 decision is already proven
+    uint32_t group_rows;                    // GAM with bands of rows as groups (0: one group)
     const uint32_t* gam;
 };
 struct GroupTeam {
@@ -205,7 +206,7 @@ __device__ __forceinline__ void team_block(const TeamOp& t, int64_t unit, TeamSh
     const uint32_t abits = team_allmax<TEAM>(fold_max16(sc.amax2), sh);
     const uint32_t mode = t.mode;
     uint32_t mg = 0u, mg5 = 0u;
-    if (mode) { mg = t.gam[0]; mg5 = t.gam[1]; }
+    if (mode) { const uint32_t* gw = gam_words(t.gam, t.group_rows, r0); mg = gw[0]; mg5 = gw[1]; }
     float s = block_scale(abits, kE4M3Max, mode, mg);
     float s5 = 0.0f;                                       // only Eq. 3 and the three-way recipe look at E5M2
     if (CRIT == kCritEq3 || t.three) s5 = block_scale(abits, kE5M2Max, mode, mg5);
@@ -532,6 +533,7 @@ struct ColOp {
     int64_t tiles_x;            // 128-column strips
     int32_t tiles_per_strip;    // 128-row tiles a workgroup sweeps (1 for kColLocal)
     float th;
+    uint32_t group_rows;        // 128 x 1 blocks under GAM with bands of rows as groups (0: one group)
     uint8_t defer, mode, three, prove;   // prove: count certain flushes in the amax pass (see below)
     uint8_t derive_gam;
     const uint32_t* gam;
@@ -613,7 +615,10 @@ __device__ __forceinline__ void col_strip(const ColOp& t, int64_t unit, ColShare
     const int64_t cols_padded = t.tiles_x * 128;
     const uint32_t mode = t.mode;
     uint32_t mg = 0u, mg5 = 0u;
-    if (mode) { mg = t.gam[0]; mg5 = t.gam[1]; }
+    if (mode) {      // (bands of rows as groups only occur with 128 x 1 blocks, where a strip is one tile)
+        const uint32_t* gw = gam_words(t.gam, MODE == kColLocal ? t.group_rows : 0u, strip * t.tiles_per_strip * 128);
+        mg = gw[0]; mg5 = gw[1];
+    }
     // strip-level accumulators (per-channel columns); for kColLocal a strip is one tile
     uint32_t amax2[4] = {0u, 0u, 0u, 0u}, zero2[4] = {0u, 0u, 0u, 0u};
     float err[8], err5[8];
@@ -1291,6 +1296,7 @@ hipError_t launch_team_items(const BatchItem* items, const int* idx, int cnt, in
         u.th = it.th; u.defer = it.scope == 1; u.mode = (uint8_t)it.scaling; u.three = (uint8_t)it.three;
         u.prove = scope_proof_applies(it);
         u.gam = gam_of[idx[k]];
+        u.group_rows = (uint32_t)it.group_rows;
         total += units;
         g.unit_end[g.n] = total;
         if (++g.n == kMaxTeamGroup) flush();
@@ -1357,6 +1363,7 @@ void fill_col_op(ColOp& t, const BatchItem& it, const uint32_t* gam) {
     t.tiles_per_strip = 1;
     t.th = it.th; t.defer = it.scope == 1; t.mode = (uint8_t)it.scaling; t.three = (uint8_t)it.three;
     t.gam = gam;
+    t.group_rows = it.gran == kGranSubCol ? (uint32_t)it.group_rows : 0u;
     t.prove = (it.gran == kGranSubCol && scope_proof_applies(it)) ? 1 : 0;     // (per-channel columns set their own meaning afterwards)
 }
 template <int MODE, bool FAKE, bool EDGE>

@@ -60,9 +60,15 @@ __device__ __forceinline__ void sub_unit_careful(const uint16_t* __restrict__ xl
 // block g*8+j, so the per-block work (division, decision, metadata) runs once per 8 blocks.
 template <int CRIT, bool FAKE>
 __device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const uint16_t* __restrict__ x, const KOut& o, int64_t unit,
-                                                 int lane, float th, bool defer, uint32_t mode, uint32_t mg, uint32_t mg5, bool proven) {
+                                                 int lane, float th, bool defer, uint32_t mode, uint32_t mg, uint32_t mg5, bool proven,
+                                                 const uint32_t* __restrict__ gam, uint32_t group_rows, uint32_t bpr) {
     const int g = lane >> 4, l = lane & 15, own = l & 7;
     const int64_t prow = unit * 32 + g * 8;
+    if (group_rows) {                                      // the owner lane's block may lie in another band than its neighbours'
+        const uint32_t* gw = gam_words(gam, group_rows, (prow + own) / bpr);
+        mg = gw[0];
+        if constexpr (CRIT == kCritEq3) mg5 = gw[1];
+    }
     const int64_t off = prow * 128 + l * 8;
     uint8_t* __restrict__ fl = FAKE ? nullptr : o.fp8 + off;
     uint16_t* __restrict__ ff = FAKE ? o.fake + off : nullptr;       // fake quantization: the de-quantized values go here
@@ -181,6 +187,8 @@ struct GroupSubT {
     uint8_t mode[N];           // scaling algorithm
     uint8_t prove[N];          // 1: gam[2] != 0 says that the tensor-level BF16 decision is already proven (fallback stored here)
     const uint32_t* gam[N];    // mode != 0: {mantissa for E4M3, mantissa for E5M2, proven flag} of the operand's group
+    uint32_t group_rows[N];    // GAM with bands of rows as groups (0: one group): the band's mantissas come from the table behind gam
+    uint32_t bpr[N];           // blocks per row (cols / 128), to find a block's row
 };
 constexpr int kMaxGroupSub = 16;       // operands per launch of the kernel of its own
 constexpr int kMaxSubRiders = 2;       // operands that can ride on a block-team launch
@@ -214,7 +222,8 @@ __device__ __forceinline__ void sub_group_body(const G& g, int64_t block, int64_
         uint32_t mg = 0u, mg5 = 0u;
         if (mode) { mg = g.gam[op][0]; if constexpr (CRIT == kCritEq3) mg5 = g.gam[op][1]; }
         const bool proven = g.prove[op] != 0 && g.gam[op][2] != 0u;
-        sub_unit_process<CRIT, FAKE>(raw, g.x[op], g.o[op], local, lane, g.th[op], g.defer[op] != 0, mode, mg, mg5, proven);
+        sub_unit_process<CRIT, FAKE>(raw, g.x[op], g.o[op], local, lane, g.th[op], g.defer[op] != 0, mode, mg, mg5, proven,
+                                     g.gam[op], mode == kScaleGam ? g.group_rows[op] : 0u, g.bpr[op]);
     };
     int opA;
     int64_t locA;

@@ -62,7 +62,7 @@ def guarded_outputs(params, device, want_bf16=True, bf16_fill=None, want_fp8=Tru
     e8m0 = gmant = None
     if params.scaling != B.MOR_SCALE_FP32_AMAX:
         e8m0 = g.carve("scale_e8m0", (P,), torch.uint8, 0xEE)
-        gmant = g.carve("group_mantissa", (2,), torch.int32, -1)
+        gmant = g.carve("group_mantissa", (2 * B.gam_groups(params),), torch.int32, -1)
     amin = g.carve("amin", (P,), torch.float32, -1.0) if params.formats & B.MOR_FMT_E5M2 else None
     out = B.MorResult(fp8, bf16, g.carve("scale", (P,), torch.float32), g.carve("amax", (P,), torch.float32),
                       g.carve("err_sum", (P,), torch.float32), g.carve("nnz", (P,), torch.int32), g.carve("mask", (P,), torch.uint8),
@@ -88,11 +88,12 @@ def block_map(gran: str, rows: int, cols: int) -> np.ndarray:
 
 def run_gpu(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "mean_rel_err", threshold: float = 0.045,
             cols: int | None = None, want_bf16: bool = True, scaling: str = "fp32_amax", formats: str = "e4m3|bf16",
-            ragged: bool = False):
+            ragged: bool = False, gam_group_rows: int = 0):
     """xb: (rows, ld) uint16.  Returns (params, MorResult) with outputs still on the device."""
     rows, ld = xb.shape
     cols = ld if cols is None else cols
-    params = B.make_params(rows, cols, gran, scope, crit, threshold, ld=ld, scaling=scaling, formats=formats, ragged=ragged)
+    params = B.make_params(rows, cols, gran, scope, crit, threshold, ld=ld, scaling=scaling, formats=formats, ragged=ragged,
+                           gam_group_rows=gam_group_rows)
     x = to_dev(xb)
     out, guards = guarded_outputs(params, x.device, want_bf16=want_bf16, bf16_fill=FILL)
     B.mor_analyze_quantize(params, x, out)
@@ -103,19 +104,20 @@ def run_gpu(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "me
 
 def compare(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "mean_rel_err", threshold: float = 0.045,
             cols: int | None = None, label: str = "", scaling: str = "fp32_amax", formats: str = "e4m3|bf16",
-            ragged: bool = False, gpu=None) -> dict:
+            ragged: bool = False, gpu=None, gam_group_rows: int = 0) -> dict:
     """``gpu``: (params, outputs) of a call already made (e.g. one operand of a batch call; its fallback buffer pre-filled
     with FILL); by default the operand is run through mor_analyze_quantize here."""
     rows, ld = xb.shape
     cols = ld if cols is None else cols
     print(f"[parity] {label} shape={rows}x{cols} ld={ld} gran={gran} scope={scope} crit={crit} th={threshold} "
-          f"scaling={scaling} formats={formats} ragged={ragged}", flush=True)
+          f"scaling={scaling} formats={formats} ragged={ragged} gam_group_rows={gam_group_rows}", flush=True)
     if gpu is None:
-        params, g = run_gpu(xb, gran, scope, crit, threshold, cols, scaling=scaling, formats=formats, ragged=ragged)
+        params, g = run_gpu(xb, gran, scope, crit, threshold, cols, scaling=scaling, formats=formats, ragged=ragged,
+                            gam_group_rows=gam_group_rows)
     else:
         params, g = gpu
     a = O.analyze_quantize(xb, gran, scope, crit, threshold, bf16_fill=FILL, ld=ld, cols=cols, scaling=scaling,
-                           formats=formats, ragged=ragged)
+                           formats=formats, ragged=ragged, gam_group_rows=gam_group_rows)
     P = a.mask.size
     three = formats != "e4m3|bf16"
     bmap = block_map(gran, rows, cols)
@@ -127,7 +129,7 @@ def compare(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "me
     if scaling != "fp32_amax":      # stored form of the scales: one E8M0 byte per block, shared 23-bit mantissas
         assert np.array_equal(g.scale_e8m0.cpu().numpy()[agree], a.e8m0[agree]), "E8M0 exponents differ"
         gm = g.group_mantissa.cpu().numpy().view(np.uint32)
-        assert int(gm[0]) == a.group_mantissa and int(gm[1]) == a.group_mantissa5, "group mantissa differs"
+        assert np.array_equal(gm.reshape(-1, 2), a.group_mantissas), "group mantissas differ"
     g_fp8 = g.fp8.cpu().numpy()
     same = agree[bmap]
     if not np.array_equal(g_fp8[same], a.fp8[same]):
@@ -195,14 +197,15 @@ def compare(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "me
 
 def compare_fake(xb: np.ndarray, gran: str, scope: str = "partition", crit: str = "mean_rel_err", threshold: float = 0.045,
                  cols: int | None = None, label: str = "", scaling: str = "fp32_amax", formats: str = "e4m3|bf16",
-                 ragged: bool = False) -> dict:
+                 ragged: bool = False, gam_group_rows: int = 0) -> dict:
     """mor_fake_quantize against the oracle's fake-quantized tensor, and against the library's own
     analyze + de-quantize pair (which must give the same bits)."""
     rows, ld = xb.shape
     cols = ld if cols is None else cols
     print(f"[parity-fake] {label} shape={rows}x{cols} ld={ld} gran={gran} scope={scope} crit={crit} th={threshold} "
           f"scaling={scaling} formats={formats} ragged={ragged}", flush=True)
-    params = B.make_params(rows, cols, gran, scope, crit, threshold, ld=ld, scaling=scaling, formats=formats, ragged=ragged)
+    params = B.make_params(rows, cols, gran, scope, crit, threshold, ld=ld, scaling=scaling, formats=formats, ragged=ragged,
+                           gam_group_rows=gam_group_rows)
     x = to_dev(xb)
     meta, guards = guarded_outputs(params, x.device, want_bf16=False, want_fp8=False)
     y = guards.carve("fake_y", (rows, cols), torch.int16, FILL if FILL < 0x8000 else FILL - 0x10000)
@@ -210,7 +213,7 @@ def compare_fake(xb: np.ndarray, gran: str, scope: str = "partition", crit: str 
     torch.cuda.synchronize()
     guards.check()
     a = O.analyze_quantize(xb, gran, scope, crit, threshold, ld=ld, cols=cols, scaling=scaling, formats=formats,
-                           ragged=ragged, want_fake=True)
+                           ragged=ragged, want_fake=True, gam_group_rows=gam_group_rows)
     g_mask = meta.mask.cpu().numpy()
     assert np.array_equal(meta.amax.cpu().numpy().view(np.uint32), a.amax.view(np.uint32)), "amax differs"
     assert np.array_equal(meta.nnz.cpu().numpy().view(np.uint32), a.nnz), "nnz differs"
@@ -223,7 +226,7 @@ def compare_fake(xb: np.ndarray, gran: str, scope: str = "partition", crit: str 
         raise AssertionError(f"fake-quantized tensor differs at {len(bad)} elements, first ({r},{c}): gpu {gy[r, c]:#06x} "
                              f"oracle {a.fake[r, c]:#06x} x={xb[r, c]:#06x}")
     # the analyse + de-quantize pair of the library gives the same tensor
-    _, g = run_gpu(xb, gran, scope, crit, threshold, cols, scaling=scaling, formats=formats, ragged=ragged)
+    _, g = run_gpu(xb, gran, scope, crit, threshold, cols, scaling=scaling, formats=formats, ragged=ragged, gam_group_rows=gam_group_rows)
     y2 = torch.full_like(y, 0x1111)
     B.mor_dequantize(params, g.fp8, g.scale, g.mask, g.bf16, y2)
     torch.cuda.synchronize()

@@ -126,8 +126,11 @@ def test_argument_validation_without_a_gpu(B):
     p = B.make_params(128, 256, "sub1x128"); p.flags = 8
     assert call(p) == 4
     assert call(B.make_params(128, 256, "tensor", lean_fp8=True, ragged=True)) == 5       # both flags pass validation
-    p = B.make_params(128, 256, "sub1x128"); p.reserved = 1
-    assert call(p) == 4
+    # GAM groups as bands of rows: whole blocks only, and not for partitions whose blocks span every band
+    assert call(B.make_params(256, 256, "block128", scaling="gam", gam_group_rows=64)) == 2
+    assert call(B.make_params(256, 256, "tensor", scaling="gam", gam_group_rows=128)) == 4
+    assert call(B.make_params(256, 256, "channel_col", scaling="gam", gam_group_rows=128)) == 4
+    assert call(B.make_params(256, 256, "block128", scaling="gam", gam_group_rows=128)) == 5     # valid: workspace missing
     # fake quantization: y must not alias x, needs 16-byte alignment and ld_y >= cols
     pr = B.make_params(128, 256, "block128")
     o = B.MorOutputs(scale=base, amax=base + 4096, err_sum=base + 8192, nnz=base + 12288, mask=base + 16384)

@@ -348,3 +348,77 @@ def test_per_channel_columns_tensor_level_proof_uses_each_columns_own_amax():
     x[np.random.default_rng(36).random(512) < 0.5, 0] = np.float32(2.0 ** -30)      # half of one column flushes
     r = parity.compare(W.f32_to_bf16_bits(x), "channel_col", "tensor", "mean_rel_err", 0.045, label="columns own amax", scaling="gam")
     assert r["n_bf16"] == 0
+
+
+# ---- GAM with several groups per tensor: the groups of Algorithm 1 as bands of rows ---------------------------------
+def _banded(rows, cols, seed, tiny_frac=0.0):
+    """Rows of very different magnitude, so that the bands' amaxes (and mantissas) differ."""
+    rng = np.random.default_rng(seed)
+    x = (np.exp2(rng.uniform(-4.0, 4.0, size=(rows, cols))) * rng.choice([-1.0, 1.0], size=(rows, cols))).astype(np.float32)
+    x *= np.exp2(rng.integers(-12, 12, size=(rows, 1))).astype(np.float32)
+    if tiny_frac:
+        x[rng.random((rows, cols)) < tiny_frac] = np.float32(2.0 ** -60)
+    return W.f32_to_bf16_bits(x)
+
+
+@pytest.mark.parametrize("gran,shape,band", [("sub1x128", (64, 512), 8), ("sub1x128", (10, 256), 4), ("sub1x128", (96, 4096), 1),
+                                             ("channel_row", (37, 640), 5), ("channel_row", (8, 9000), 2), ("block128", (640, 384), 128),
+                                             ("block128", (512, 256), 384), ("block64", (320, 256), 64), ("block64", (256, 128), 128),
+                                             ("sub128x1", (384, 256), 128), ("sub128x1", (512, 136), 256)])
+@pytest.mark.parametrize("crit", ["mean_rel_err", "e4m3_vs_e5m2"])
+def test_gam_row_band_groups(gran, shape, band, crit):
+    """Every output equals the oracle's: one mantissa pair per band in group_mantissa, per-block E8M0 exponents, scales,
+    codes, error sums, decisions (per block and per tensor), fake quantization, and de-quantization from the stored form."""
+    rows, cols = shape
+    xb = _banded(rows, cols, rows + cols + band, tiny_frac=0.02)
+    r = parity.compare(xb, gran, "partition", crit, 0.045, label="gam bands", scaling="gam", gam_group_rows=band)
+    assert r["gpu"].group_mantissa.numel() == 2 * -(-rows // band)
+    g, params = r["gpu"], r["params"]
+    # stored form -> scale, band by band
+    y = torch.full((rows, cols), 0x1111, dtype=torch.int16, device="cuda")
+    y2 = torch.full_like(y, 0x2222)
+    B.mor_dequantize_e8m0(params, g.fp8, g.scale_e8m0, g.group_mantissa, g.mask, g.bf16, y)
+    B.mor_dequantize(params, g.fp8, g.scale, g.mask, g.bf16, y2)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
+    from oracle import mor_oracle as O
+    want = O.dequantize(g.fp8.cpu().numpy(), g.scale.cpu().numpy(), g.mask.cpu().numpy(), parity.u16(g.bf16), gran)
+    assert np.array_equal(parity.u16(y), want)
+    if crit == "mean_rel_err":
+        parity.compare(xb, gran, "tensor", crit, 0.045, label="gam bands, tensor-level", scaling="gam", gam_group_rows=band)
+        f = parity.compare_fake(xb, gran, "partition", crit, 0.045, label="gam bands, fake", scaling="gam", gam_group_rows=band)
+        assert f["n_mismatch"] == 0
+
+
+def test_gam_row_band_groups_in_a_batch_and_degenerate_bands():
+    """Operands with and without bands in one batch call (de-quantized in one batch call from the stored form); a band of
+    at least `rows` rows is one group; the parameter is ignored without GAM scaling."""
+    dev = torch.device("cuda")
+    specs = [("sub1x128", (64, 512), 8), ("block128", (384, 256), 128), ("block128", (256, 256), 0), ("channel_row", (20, 1024), 4),
+             ("sub128x1", (256, 128), 128), ("block64", (128, 192), 64)]
+    ops, keep = [], []
+    for k, (gran, (rows, cols), band) in enumerate(specs):
+        xb = _banded(rows, cols, 300 + k)
+        params = B.make_params(rows, cols, gran, scaling="gam", gam_group_rows=band)
+        out = B.alloc_outputs(params, dev, want_bf16=True, bf16_fill=parity.FILL)
+        out.workspace = None
+        ops.append((params, parity.to_dev(xb), out, None)); keep.append((xb, gran, band))
+    items = B.make_batch(ops)
+    ws = torch.empty(max(16, B.mor_batch_workspace_bytes(items)), dtype=torch.uint8, device=dev)
+    ws.fill_(0xFF)
+    B.mor_analyze_quantize_batch(items, 1e-5, ws)
+    torch.cuda.synchronize()
+    ys = [torch.full_like(o.bf16, 0x1111) for _, _, o, _ in ops]
+    B.mor_dequantize_batch(B.make_dequant_batch([(p, o, y, True) for (p, _, o, _), y in zip(ops, ys)]))
+    torch.cuda.synchronize()
+    from oracle import mor_oracle as O
+    for (params, xd, out, _), (xb, gran, band), y in zip(ops, keep, ys):
+        parity.compare(xb, gran, label="gam bands in a batch", scaling="gam", gam_group_rows=band, gpu=(params, out))
+        want = O.dequantize(out.fp8.cpu().numpy(), out.scale.cpu().numpy(), out.mask.cpu().numpy(), parity.u16(out.bf16), gran)
+        assert np.array_equal(parity.u16(y), want)
+    xb = _banded(256, 256, 400)
+    one = parity.compare(xb, "block128", label="one group", scaling="gam")
+    whole = parity.compare(xb, "block128", label="band >= rows", scaling="gam", gam_group_rows=256)
+    assert torch.equal(one["gpu"].scale, whole["gpu"].scale) and whole["gpu"].group_mantissa.numel() == 2
+    parity.compare(xb, "block128", label="ignored for E8M0", scaling="e8m0", gam_group_rows=128)
+    parity.compare(xb, "block128", label="ignored for FP32 amax", scaling="fp32_amax", gam_group_rows=128)
