@@ -91,12 +91,13 @@ def run_variants(ops, B, torch, dev, steps, log):
         torch.cuda.synchronize()
         return t0.elapsed_time(t1) / iters
 
-    def analyze_variant(name, gran_of, scope="partition", crit="mean_rel_err", scaling="fp32_amax", formats="e4m3|bf16", lean=False):
+    def analyze_variant(name, gran_of, scope="partition", crit="mean_rel_err", scaling="fp32_amax", formats="e4m3|bf16", lean=False,
+                        gam_group_rows=0):
         entries, outs = [], []
         for o in ops:
             gran = gran_of(o)
             params = B.make_params(o["params"].rows, o["params"].cols, gran, scope, crit, THRESHOLD, scaling=scaling, formats=formats,
-                                   lean_fp8=lean)
+                                   lean_fp8=lean, gam_group_rows=gam_group_rows)
             out = B.alloc_outputs(params, dev, want_bf16=True)
             out.workspace = None
             entries.append((params, o["x"], out, None))
@@ -118,7 +119,8 @@ def run_variants(ops, B, torch, dev, steps, log):
                     b -= 1.0 * n * f                            # no FP8 payload for an operand known to stay in BF16
             else:
                 b = 3.0 * n + META_BYTES * P
-                if scope == "tensor" and ((scaling == "gam" and gran in ("block128", "block64", "channel_row", "sub1x128", "sub128x1")) or gran == "channel_col"):
+                if scope == "tensor" and ((scaling == "gam" and not gam_group_rows and gran in ("block128", "block64", "channel_row", "sub1x128", "sub128x1"))
+                                          or gran == "channel_col"):
                     b += 2.0 * n * f                            # these inputs' BF16 decision is proven by the pre-pass: written by the block kernel
                 elif scope == "tensor":
                     b += 4.0 * n * f                            # separate copy pass after the tensor-wide decision
@@ -148,6 +150,8 @@ def run_variants(ops, B, torch, dev, steps, log):
     analyze_variant("gam_tensor_level_sub1x128", const("sub1x128"), scope="tensor", scaling="gam")
     analyze_variant("gam_tensor_level_sub128x1", const("sub128x1"), scope="tensor", scaling="gam")
     analyze_variant("gam_tensor_level_per_tensor", const("tensor"), scaling="gam")
+    # Algorithm 1 with several groups per tensor: one mantissa per band of 128 rows, block decisions
+    analyze_variant("gam_bands_of_128_rows_block128", const("block128"), scaling="gam", gam_group_rows=128)
     # the scaling ablation of Section 4.1.2 keeps the tensor-level decision and swaps the scaling algorithm
     analyze_variant("e8m0_tensor_level_block128", const("block128"), scope="tensor", scaling="e8m0")
     analyze_variant("fp32_amax_tensor_level_block128", const("block128"), scope="tensor")

@@ -1,5 +1,5 @@
 """Seeded random sweep over the whole parameter space of the analyse-select-quantize entry points (granularity,
-scope, criterion, scaling, type list, ragged shapes, padded leading dimensions, fake quantization): every case is
+scope, criterion, scaling, GAM groups, type list, ragged shapes, padded leading dimensions, fake quantization): every case is
 compared with the CPU oracle to the usual bar.  Small shapes, many combinations."""
 import numpy as np
 import pytest
@@ -66,6 +66,11 @@ def test_random_case(P, seed):
     xb = operand(rng, rows, ld)
     kw = dict(scope=scope, crit=crit, threshold=th, scaling=scaling, formats="e4m3|e5m2|bf16" if three else "e4m3|bf16",
               ragged=ragged, cols=cols, label=f"sweep-{seed}")
+    # GAM: half of the cases take bands of rows as the groups of Algorithm 1 (drawn from a generator of its own, so that the
+    # operands of the cases above stay what they were)
+    rng_band = np.random.default_rng(77000 + seed)
+    if scaling == "gam" and gran in ("sub1x128", "block128", "channel_row", "sub128x1", "block64") and rng_band.integers(0, 2):
+        kw["gam_group_rows"] = pr * int(rng_band.integers(1, max(2, rows // pr + 1)))
     if fake:
         P.compare_fake(xb, gran, **kw)
     else:
