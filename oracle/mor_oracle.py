@@ -32,8 +32,15 @@ if _SANITIZE:
     _LIB = os.path.join(_HERE, "libmor_oracle_san.so")
 
 
+_PREBUILT = os.environ.get("MOR_ORACLE_LIB")      # a library built elsewhere from (a variant of) mor_oracle.c: mutation runs of the pins
+if _PREBUILT:
+    _LIB = _PREBUILT
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (strict IEEE: no contraction, no fast-math)."""
+    if _PREBUILT:
+        return _LIB
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-std=c11", "-O2", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
                "-Wall", "-Wextra", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
