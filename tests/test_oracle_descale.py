@@ -140,6 +140,21 @@ def test_descale_handworked_elements(oracle):
     assert np.array_equal(back, a.fake)
 
 
+def test_dequantize_without_fallback_payload_leaves_bf16_blocks_untouched(oracle):
+    """Interface rule (Section 4, Figure 4: the fallback operand is used as it is): with no BF16 payload passed,
+    a block whose mask says BF16 is not written at all -- the caller's y may already hold it -- while E4M3 blocks are
+    de-quantized as usual."""
+    keep = one_block([3.0, 1.0, -1.0])
+    fall = one_block([448.0] + [2.0 ** -12] * 100)                     # 100 of 101 non-zeros flush: BF16
+    a = oracle.analyze_quantize(np.vstack([keep, fall]), "sub1x128", threshold=0.045)
+    assert list(a.mask) == [0, 1]
+    back = oracle.dequantize(a.fp8, a.scale, a.mask, None, "sub1x128", fill=0xABCD)
+    assert list(back[0][:4]) == [0x4040, 0x3F77, 0xBF77, 0x0000]
+    assert (back[1] == 0xABCD).all()
+    with_payload = oracle.dequantize(a.fp8, a.scale, a.mask, a.bf16, "sub1x128", fill=0xABCD)
+    assert np.array_equal(with_payload[1], fall[0]) and np.array_equal(with_payload[0], back[0])
+
+
 # ---------------------------------------------------------------- tensor-wide decision under Eq. (3)
 
 def _eq3_pair(n_flushed):
