@@ -387,6 +387,16 @@ __device__ __forceinline__ int group_find32(const int32_t* end, int n, int v) {
 // ---- Algorithm 2 with [E4M3, BF16]: 0 = keep E4M3, 1 = keep BF16 ------------------------------
 // Eq. (2): err_sum / nnz < th, evaluated division-free as err_sum < th * nnz (the metric of a
 // block without non-zero elements is 0).  False for NaN / inf sums.
+// Bin of the error histogram (Section 4.1.3) a mean relative error falls into: twelve bins of width 0.005, the last one open.
+__device__ __forceinline__ int stats_bin(float metric) {
+    if (!(metric < __builtin_inff())) return 11;
+    int bin = 0;
+#pragma unroll
+    for (int k = 1; k <= 11; ++k)
+        if (metric >= (float)(0.005 * k)) bin = k;
+    return bin;
+}
+constexpr int kStatCnt = 15;     // 12 histogram bins, BF16 blocks, near-threshold blocks, E5M2 blocks
 __device__ __forceinline__ uint32_t decide_eq2(float err_sum, uint32_t nnz, float th) {
     const bool accept = nnz ? (err_sum < th * (float)nnz) : (0.0f < th);
     return accept ? 0u : 1u;

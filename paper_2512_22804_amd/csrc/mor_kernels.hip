@@ -595,14 +595,6 @@ struct StatsDev {   // must match mor_stats in include/mor.h
     uint32_t reserved2;
     unsigned long long n_e5m2_part, n_elem_e5m2;
 };
-__device__ __forceinline__ int stats_bin(float metric) {
-    if (!(metric < __builtin_inff())) return 11;
-    int bin = 0;
-#pragma unroll
-    for (int k = 1; k <= 11; ++k)
-        if (metric >= (float)(0.005 * k)) bin = k;
-    return bin;
-}
 // Number of elements of block p: blocks at the right / bottom edge of a ragged tensor are smaller.
 __device__ __forceinline__ unsigned long long block_elems(const StatsGeom& g, int64_t p) {
     if (g.uniform) return (unsigned long long)(g.pr * g.pc);
@@ -611,7 +603,6 @@ __device__ __forceinline__ unsigned long long block_elems(const StatsGeom& g, in
     const int64_t w = g.cols - bc * g.pc < g.pc ? g.cols - bc * g.pc : g.pc;
     return (unsigned long long)(h * w);
 }
-constexpr int kStatCnt = 15;     // 12 histogram bins, BF16 blocks, near-threshold blocks, E5M2 blocks
 struct StatsAcc {
     double e;
     unsigned long long n, eb, e5;        // non-zeros; elements in BF16 blocks; elements in E5M2 blocks
@@ -915,13 +906,13 @@ __device__ __forceinline__ uint32_t stats_pick(const StatsTotals& t, int k) {
     return v;
 }
 // Wave 0 writes either the operand's final statistics (`final_out`) or this workgroup's record.
-__device__ __forceinline__ void stats_emit(const StatsTotals& t, const StatsOp& op, StatsRec* rec) {
+__device__ __forceinline__ void stats_emit(const StatsTotals& t, StatsDev* out, int64_t n_part, unsigned long long total_elems, StatsRec* rec) {
     if (threadIdx.x >= 64) return;
     const uint32_t mine = stats_pick(t, (int)threadIdx.x < kStatCnt ? (int)threadIdx.x : 0);
     if (rec == nullptr) {
-        if (threadIdx.x < 12) op.out->hist[threadIdx.x] = mine;
+        if (threadIdx.x < 12) out->hist[threadIdx.x] = mine;
         if (threadIdx.x == 0)
-            stats_finish(op.out, op.n_part, (unsigned long long)(op.geom.rows * op.geom.cols), t.e, t.n, t.c[12], t.c[13], t.c[14], t.eb, t.e5, 0u);
+            stats_finish(out, n_part, total_elems, t.e, t.n, t.c[12], t.c[13], t.c[14], t.eb, t.e5, 0u);
         return;
     }
     if (threadIdx.x < kStatCnt) rec->cnt[threadIdx.x] = mine;
@@ -955,7 +946,7 @@ __global__ __launch_bounds__(kStatsFastThreads) void k_stats_group_partial(Group
 #pragma unroll
     for (int k = 0; k < kStatCnt; ++k) tot.c[k] = (k & 1) ? a.pk[k >> 1] >> 16 : a.pk[k >> 1] & 0xFFFFu;
     stats_fast_reduce(tot, sh);
-    stats_emit(tot, t, nb == 1 ? nullptr : t.rec + b);
+    stats_emit(tot, t.out, t.n_part, (unsigned long long)(t.geom.rows * t.geom.cols), nb == 1 ? nullptr : t.rec + b);
 }
 // Combine launch: one workgroup of 256 lanes per operand, one record per lane.
 __global__ __launch_bounds__(256) void k_stats_group_final(GroupStats g) {
@@ -974,7 +965,70 @@ __global__ __launch_bounds__(256) void k_stats_group_final(GroupStats g) {
         for (int k = 0; k < kStatCnt; ++k) tot.c[k] = r.cnt[k];
     }
     stats_fast_reduce(tot, sh);
-    stats_emit(tot, t, nullptr);
+    stats_emit(tot, t.out, t.n_part, (unsigned long long)(t.geom.rows * t.geom.cols), nullptr);
+}
+
+// ---- a lone dense 1 x 128 operand: the block kernel gathers the statistics of its workgroups itself (one record per
+//      workgroup), so that the call needs one small combine launch afterwards instead of two statistics launches that
+//      read the per-block outputs again.  (Combining the records inside the block kernel as well -- the workgroup that
+//      draws the last of a set of ticket counters reads all records -- was built and measured: device-wide atomics on one
+//      address complete about 15 ns apart, a device-wide release fence per workgroup writes back what its XCD still
+//      holds of the payload (80 us per call), and with write-through record stores and two levels of counters the chain
+//      of dependent device-scope round trips at the end of the kernel took as long as the launch it was to save.)
+constexpr int kSoloRecWords = 20;          // dwords of a workgroup's record in use: 15 counters, pad, the sum (2), non-zeros, pad
+struct SoloStats {
+    StatsRec* rec;         // [gridDim.x]: 128 bytes apart, the first kSoloRecWords dwords used
+    StatsDev* out;
+    int64_t n_part;
+    float near_tol;
+    int n_rec;
+};
+// (Six workgroups per compute unit as for the kernel without statistics: the second launch bound makes the compiler fit
+// Eq. 2's variants into 80 registers, which it does without spilling; Eq. 3's variants need more either way.)
+template <int CRIT, bool FAKE>
+__global__ __launch_bounds__(256, CRIT == kCritEq3 ? 4 : 6) void k_sub1x128_solo_stats(SubRiders g, SoloStats s) {
+    __shared__ SubStatsShared ssh;
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (threadIdx.x < 17) reinterpret_cast<uint32_t*>(&ssh)[threadIdx.x] = 0u;      // c[16], n
+    ssh.e_lane[threadIdx.x] = 0.0;
+    ssh.n_lane[threadIdx.x] = 0u;
+    __syncthreads();
+    sub_group_body<CRIT, FAKE, true>(g, (int64_t)blockIdx.x, (int64_t)gridDim.x, &ssh, s.near_tol);
+    const double e_w = wave_allsum_f64(ssh.e_lane[threadIdx.x]);
+    const uint32_t n_w = wave_allsum_u32(ssh.n_lane[threadIdx.x]);
+    if (lane == 0) { ssh.e[w] = e_w; atomicAdd(&ssh.n, n_w); }
+    __syncthreads();
+    if (w != 0) return;
+    uint32_t word = 0u;                                   // one dword of the record per lane
+    if (lane < kStatCnt) word = ssh.c[lane];
+    const double e_wg = (ssh.e[0] + ssh.e[1]) + (ssh.e[2] + ssh.e[3]);
+    const unsigned long long e_bits = (unsigned long long)__double_as_longlong(e_wg);
+    if (lane == 16) word = (uint32_t)e_bits;
+    if (lane == 17) word = (uint32_t)(e_bits >> 32);
+    if (lane == 18) word = ssh.n;
+    if (lane < kSoloRecWords) reinterpret_cast<uint32_t*>(s.rec + blockIdx.x)[lane] = word;
+}
+// Combine launch of the above: one workgroup, the records in a fixed order.
+constexpr int kSoloFinalThreads = 1024;
+__global__ __launch_bounds__(kSoloFinalThreads) void k_solo_stats_final(SoloStats s) {
+    __shared__ StatsFastShared<kSoloFinalThreads / 64> fin;
+    StatsTotals tot;
+    tot.e = 0.0; tot.n = 0ull; tot.eb = 0ull; tot.e5 = 0ull;
+#pragma unroll
+    for (int k = 0; k < kStatCnt; ++k) tot.c[k] = 0u;
+    for (int i = threadIdx.x; i < s.n_rec; i += kSoloFinalThreads) {
+        const unsigned long long* r = reinterpret_cast<const unsigned long long*>(s.rec + i);
+        unsigned long long q[kSoloRecWords / 2];
+#pragma unroll
+        for (int k = 0; k < kSoloRecWords / 2; ++k) q[k] = r[k];
+#pragma unroll
+        for (int k = 0; k < kStatCnt; ++k) tot.c[k] += (uint32_t)(q[k >> 1] >> (32 * (k & 1)));
+        tot.e += __longlong_as_double((long long)q[8]);
+        tot.n += (uint32_t)q[9];
+    }
+    tot.eb = 128ull * tot.c[12];          // (per lane; the sums below add the lanes' products)
+    stats_fast_reduce(tot, fin);
+    stats_emit(tot, s.out, s.n_part, (unsigned long long)s.n_part * 128ull, nullptr);
 }
 
 // Per-tensor operands of a group share three launches (amax, quantize, finish + fallback copy).
@@ -1448,6 +1502,11 @@ Route route_of(const BatchItem& it) {
     }
 }
 int64_t item_parts(const BatchItem& it) { return geom_parts(make_geom(it.gran, it.sh.rows, it.sh.cols)); }
+// A dense 1 x 128 operand of whole 32-block units whose blocks are decided one by one can gather its statistics in its own
+// kernel (k_sub1x128_solo_stats) when it is alone in its launch and the batch has no per-tensor launch they could ride on.
+bool solo_stats_candidate(const BatchItem& it) {
+    return it.stats && it.scope == 0 && route_of(it) == kRouteSubFlat && item_parts(it) % 32 == 0;
+}
 int stats_wgs(int64_t n_part) {                        // riding in a launch of 256-lane workgroups
     if (n_part <= 4096) return 1;                       // one workgroup writes the result directly
     int64_t w = (n_part + 1023) / 1024;
@@ -1463,7 +1522,7 @@ size_t item_workspace(const BatchItem& it) {
     if (it.gran == kGranTensor) b += plan_tensor(it.sh.rows, it.sh.cols).bytes;
     else if (it.scope == 1) b += scope_workspace_bytes(item_parts(it));
     if (it.gran == kGranCol) b += column_workspace_bytes(it.sh.rows, it.sh.cols);
-    if (it.stats && it.gran != kGranTensor) b += align16(sizeof(StatsRec) * kStatsMaxWg);
+    if (it.stats && it.gran != kGranTensor) b += align16(sizeof(StatsRec) * (solo_stats_candidate(it) ? kSubFlatMaxBlocks : kStatsMaxWg));
     if (it.gran != kGranTensor && it.scaling != kScaleFp32) {
         b += 16;                                                                   // group mantissa words
         if (it.scaling == kScaleGam && it.group_rows == 0) b += 2 * align16(sizeof(uint32_t) * kProveMaxWg);   // amax and flush partials of the pre-pass
@@ -1507,7 +1566,9 @@ struct BatchRun {
     char* col_ws[kBatchMax] = {};                // per operand with per-channel columns: its column workspace
     GroupStats stats_groups[kMaxStatsGroups];
     int n_stats_groups = 0;
+    bool will_ride = false;                      // the batch has grouped per-tensor launches for statistics to ride on
     bool riders_used = false;                    // the first statistics group went along with a per-tensor launch
+    bool stats_done[kBatchMax] = {};             // the operand's block kernel has written its statistics already
 
     size_t ws_bytes = 0;
     // Next `bytes` of the caller's workspace.  The phases below carve exactly what item_workspace() adds up; should the
@@ -1658,10 +1719,39 @@ void BatchRun::sub_tensor_operands(int crit) {
     for (int fake = 0; fake < 2 && err == hipSuccess; ++fake) {
         GroupSub g; g.n = 0;
         int64_t total = 0;
+        int newest = -1;                                  // the item added to the table last
         auto flush = [&]() {
             if (g.n == 0 || err != hipSuccess) { g.n = 0; total = 0; return; }
             int64_t blocks = (total + 3) / 4;
             if (blocks > kSubFlatMaxBlocks) blocks = kSubFlatMaxBlocks;
+            if (g.n == 1 && !will_ride && solo_stats_candidate(items[newest])) {
+                // a lone operand: its kernel gathers the statistics as well
+                SoloStats ss;
+                ss.rec = reinterpret_cast<StatsRec*>(carve(sizeof(StatsRec) * (size_t)blocks));
+                ss.out = static_cast<StatsDev*>(items[newest].stats);
+                ss.n_part = item_parts(items[newest]);
+                ss.near_tol = near_tol;
+                ss.n_rec = (int)blocks;
+                if (err != hipSuccess) { g.n = 0; total = 0; return; }
+                SubRiders one; one.n = 1;
+                one.unit_end[0] = g.unit_end[0]; one.x[0] = g.x[0]; one.o[0] = g.o[0]; one.th[0] = g.th[0]; one.defer[0] = g.defer[0];
+                one.mode[0] = g.mode[0]; one.prove[0] = g.prove[0]; one.gam[0] = g.gam[0]; one.group_rows[0] = g.group_rows[0]; one.bpr[0] = g.bpr[0];
+                {
+                    ProfScope ps(prof, kKernSub1x128, st);
+                    const dim3 grid((unsigned)blocks);
+                    if (fake) {
+                        if (crit == kCritEq3) k_sub1x128_solo_stats<kCritEq3, true><<<grid, dim3(256), 0, st>>>(one, ss);
+                        else k_sub1x128_solo_stats<kCritEq2, true><<<grid, dim3(256), 0, st>>>(one, ss);
+                    } else {
+                        if (crit == kCritEq3) k_sub1x128_solo_stats<kCritEq3, false><<<grid, dim3(256), 0, st>>>(one, ss);
+                        else k_sub1x128_solo_stats<kCritEq2, false><<<grid, dim3(256), 0, st>>>(one, ss);
+                    }
+                }
+                { ProfScope ps2(prof, kKernStatsFinal, st); k_solo_stats_final<<<dim3(1), dim3(kSoloFinalThreads), 0, st>>>(ss); }
+                stats_done[newest] = true;
+                g.n = 0; total = 0;
+                return;
+            }
             ProfScope ps(prof, kKernSub1x128, st);
             if (fake) {
                 if (crit == kCritEq3) k_sub1x128_group<kCritEq3, true><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(g);
@@ -1691,6 +1781,7 @@ void BatchRun::sub_tensor_operands(int crit) {
                 g.unit_end[g.n] = total; g.x[g.n] = it.x; g.o[g.n] = it.o; g.th[g.n] = it.th; g.defer[g.n] = it.scope == 1;
                 g.mode[g.n] = (uint8_t)it.scaling; g.gam[g.n] = gam_of[i]; g.prove[g.n] = scope_proof_applies(it) ? 1 : 0;
                 g.group_rows[g.n] = (uint32_t)it.group_rows; g.bpr[g.n] = (uint32_t)(it.sh.cols / 128);
+                newest = i;
                 if (++g.n == kMaxGroupSub) flush();
             }
             if (n_tail > 0) {     // fewer than 32 blocks left: the general kernel takes them
@@ -1812,11 +1903,9 @@ void BatchRun::tensor_level_decisions() {
 //      step next to the finish pass.  Groups that find no such launch run on their own at the end.
 void BatchRun::collect_statistics() {
     GroupStats* g = nullptr;
-    bool will_ride = false;
-    for (int i = 0; i < n; ++i) will_ride |= route[i] == kRouteTensorGroup;
     for (int i = 0; i < n; ++i) {
         const BatchItem& it = items[i];
-        if (!it.stats || it.gran == kGranTensor) continue;
+        if (!it.stats || it.gran == kGranTensor || stats_done[i]) continue;
         if (!g || g->n == kMaxGroupStats) { g = &stats_groups[n_stats_groups++]; g->n = 0; g->near_tol = near_tol; }
         StatsOp& t = g->op[g->n];
         t.err_sum = it.o.err_sum; t.nnz = it.o.nnz; t.mask = it.o.mask;
@@ -1950,6 +2039,7 @@ hipError_t launch_batch(const BatchItem* items, int n, float near_tol, void* ws,
     run.wsp = static_cast<char*>(ws);
     run.ws_bytes = ws_bytes;
     for (int i = 0; i < n; ++i) run.route[i] = route_of(items[i]);
+    for (int i = 0; i < n; ++i) run.will_ride |= run.route[i] == kRouteTensorGroup;
     run.group_mantissas();
     for (int crit = 0; crit < 2 && run.err == hipSuccess; ++crit) run.sub_tensor_operands(crit);
     if (run.err == hipSuccess) run.tensor_level_decisions();

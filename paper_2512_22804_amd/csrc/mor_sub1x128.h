@@ -55,13 +55,26 @@ __device__ __forceinline__ void sub_unit_careful(const uint16_t* __restrict__ xl
     }
 }
 
+// Statistics gathered by the block kernel itself (a lone operand has no later launch to give them to): the small counters
+// of a workgroup live in shared memory and take one atomic add per block from the lane that owns the block; the two sums
+// stay with the owner lanes until the workgroup's last unit is done.
+struct SubStatsShared {
+    uint32_t c[16];        // kStatCnt counters of the workgroup (12 histogram bins, BF16 blocks, near-threshold blocks, unused)
+    uint32_t n;            // non-zero elements
+    uint32_t pad;
+    double e[4];           // per wave: sum of the blocks' error sums
+    double e_lane[256];    // per lane: running sum of its blocks' error sums (kept here to spare registers)
+    uint32_t n_lane[256];  // per lane: non-zero elements of its blocks
+};
+
 // One unit = 32 consecutive blocks: DPP row g (16 lanes x 8 elements) owns blocks g*8 .. g*8+7 of the
 // unit, all eight already loaded into raw[].  Lane j (and its mirror j+8) of the row keeps the scalars of
 // block g*8+j, so the per-block work (division, decision, metadata) runs once per 8 blocks.
-template <int CRIT, bool FAKE>
+template <int CRIT, bool FAKE, bool STATS = false>
 __device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const uint16_t* __restrict__ x, const KOut& o, int64_t unit,
                                                  int lane, float th, bool defer, uint32_t mode, uint32_t mg, uint32_t mg5, bool proven,
-                                                 const uint32_t* __restrict__ gam, uint32_t group_rows, uint32_t bpr) {
+                                                 const uint32_t* __restrict__ gam, uint32_t group_rows, uint32_t bpr,
+                                                 SubStatsShared* ssh = nullptr, float near_tol = 0.0f) {
     const int g = lane >> 4, l = lane & 15, own = l & 7;
     const int64_t prow = unit * 32 + g * 8;
     if (group_rows) {                                      // the owner lane's block may lie in another band than its neighbours'
@@ -172,6 +185,17 @@ __device__ __forceinline__ void sub_unit_process(const u32x4 (&raw)[8], const ui
                 if ((bits >> k) & 1u) store16(bl + k * 128, raw[k]);
         }
     }
+    if constexpr (STATS) {          // the same arithmetic as the statistics kernels apply to the stored per-block values
+        if (l < 8) {
+            const uint32_t nz = 128u - my_zero;
+            const float metric = nz ? my_err / (float)nz : 0.0f;
+            atomicAdd(&ssh->c[stats_bin(metric)], 1u);
+            ssh->e_lane[threadIdx.x] += (double)my_err;
+            ssh->n_lane[threadIdx.x] += nz;
+            if (my_mask == 1u) atomicAdd(&ssh->c[12], 1u);
+            if (fabs((double)metric - (double)th) <= (double)near_tol * (double)th) atomicAdd(&ssh->c[13], 1u);
+        }
+    }
 }
 
 
@@ -202,8 +226,9 @@ struct TeamRiders {
 };
 
 // Workgroup `block` of `n_blocks` (4 waves each): a wave strides over the 8 KB units of all operands of the table.
-template <int CRIT, bool FAKE, class G>
-__device__ __forceinline__ void sub_group_body(const G& g, int64_t block, int64_t n_blocks) {
+template <int CRIT, bool FAKE, bool STATS = false, class G>
+__device__ __forceinline__ void sub_group_body(const G& g, int64_t block, int64_t n_blocks, SubStatsShared* ssh = nullptr,
+                                               float near_tol = 0.0f) {
     const int lane = threadIdx.x & 63, row = lane >> 4, l = lane & 15;
     const int64_t W = n_blocks * 4, total = g.unit_end[g.n - 1];
     int64_t u = block * 4 + (threadIdx.x >> 6);
@@ -222,8 +247,8 @@ __device__ __forceinline__ void sub_group_body(const G& g, int64_t block, int64_
         uint32_t mg = 0u, mg5 = 0u;
         if (mode) { mg = g.gam[op][0]; if constexpr (CRIT == kCritEq3) mg5 = g.gam[op][1]; }
         const bool proven = g.prove[op] != 0 && g.gam[op][2] != 0u;
-        sub_unit_process<CRIT, FAKE>(raw, g.x[op], g.o[op], local, lane, g.th[op], g.defer[op] != 0, mode, mg, mg5, proven,
-                                     g.gam[op], mode == kScaleGam ? g.group_rows[op] : 0u, g.bpr[op]);
+        sub_unit_process<CRIT, FAKE, STATS>(raw, g.x[op], g.o[op], local, lane, g.th[op], g.defer[op] != 0, mode, mg, mg5, proven,
+                                            g.gam[op], mode == kScaleGam ? g.group_rows[op] : 0u, g.bpr[op], ssh, near_tol);
     };
     int opA;
     int64_t locA;
