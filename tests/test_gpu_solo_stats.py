@@ -150,3 +150,43 @@ def test_not_alone_or_not_eligible_still_right(oracle):
                     assert got[k] == ref[k], k
     _check(oracle, _mixed(5, 640, 60))       # 25 blocks: no whole unit
     _check(oracle, _mixed(9, 640, 61))       # 45 blocks: one unit and a tail
+
+
+def test_lone_operand_in_a_graph_and_deterministic():
+    """The lone-operand call only launches kernels: captured in a HIP graph, every replay into scrubbed buffers (with
+    eager work in between, and with the workspace overwritten) gives the eager call's outputs and statistics bit for bit."""
+    import parity
+    from paper_2512_22804_amd import binding as B
+    dev = torch.device("cuda:0")
+    xb = _mixed(2048, 4096, 99)
+    params = B.make_params(2048, 4096, "sub1x128", "partition", "mean_rel_err", 0.045)
+    out = B.alloc_outputs(params, dev, bf16_fill=parity.FILL)
+    st = torch.zeros(B.STATS_BYTES, dtype=torch.uint8, device=dev)
+    x = parity.to_dev(xb)                     # (kept alive: the item array only holds its address)
+    items = B.make_batch([(params, x, out, st)])
+    ws = torch.empty(B.mor_batch_workspace_bytes(items), dtype=torch.uint8, device=dev)
+    fields = ("fp8", "bf16", "scale", "amax", "nnz", "mask", "err_sum")
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [getattr(out, f).clone() for f in fields] + [st.clone()]
+
+    def scrub(fill):
+        out.fp8.zero_(); out.mask.fill_(9); out.err_sum.fill_(-1.0); st.fill_(fill); ws.fill_(fill)
+        out.bf16.fill_(parity.FILL if parity.FILL < 0x8000 else parity.FILL - 0x10000)
+
+    scrub(0x11)
+    B.mor_analyze_quantize_batch(items, NEAR, ws)
+    want = snapshot()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.mor_analyze_quantize_batch(items, NEAR, ws)
+    for rep in range(3):
+        scrub(0x22 + rep)
+        graph.replay()
+        for a, b in zip(want, snapshot()):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+        scrub(0x55)
+        B.mor_analyze_quantize_batch(items, NEAR, ws)       # eager work between the replays
+        for a, b in zip(want, snapshot()):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
