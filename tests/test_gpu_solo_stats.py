@@ -84,6 +84,13 @@ def test_lone_activation_full_size(oracle):
     assert got["n_part"] == 262144
 
 
+def test_lone_gradient_full_size_mixed_mask(oracle):
+    """The benchmark's cfg4b call: 8192 x 14336, about 10 % of the 1x128 blocks fall back."""
+    xb = W.cfg4(tiny_half=True)[0][1]
+    got = _check(oracle, xb, calls=1)
+    assert got["n_part"] == 917504 and 0.05 < got["n_bf16_part"] / got["n_part"] < 0.15
+
+
 @pytest.mark.parametrize("crit", ["mean_rel_err", "e4m3_vs_e5m2"])
 @pytest.mark.parametrize("fake", [False, True])
 def test_lone_operand_criteria_and_fake_quantization(oracle, crit, fake):
