@@ -197,3 +197,16 @@ def test_lone_operand_in_a_graph_and_deterministic():
         B.mor_analyze_quantize_batch(items, NEAR, ws)       # eager work between the replays
         for a, b in zip(want, snapshot()):
             assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_lone_operands(oracle, seed):
+    """Random shapes (whole units, units and a tail, no whole unit), criteria, scalings, thresholds and output kinds."""
+    rng = np.random.default_rng(31000 + seed)
+    cols = 128 * int(rng.integers(1, 41))
+    rows = int(rng.integers(1, 400))
+    xb = W.gradient(rows, cols, 4000 + seed, tiny_frac=float(rng.choice([0.0, 0.1, 0.5])), tiny_half=bool(rng.integers(0, 2)))
+    crit = ["mean_rel_err", "e4m3_vs_e5m2"][int(rng.integers(0, 2))]
+    scaling = ["fp32_amax", "gam", "e8m0"][int(rng.integers(0, 3))]
+    th = float(rng.choice([0.045, 0.02, 0.1, 0.5]))
+    _check(oracle, xb, crit=crit, th=th, scaling=scaling, fake=bool(rng.integers(0, 2)), calls=1)
