@@ -50,10 +50,25 @@ def _check(oracle, xb, crit="mean_rel_err", th=0.045, scaling="fp32_amax", fake=
         else:
             assert got[k] == want[k], (k, got[k], want[k])
     # (2) the oracle, on its own analysis of the same input
-    a = oracle.analyze_quantize(xb, "sub1x128", "partition", crit, th, scaling=scaling, gam_group_rows=gam_group_rows)
+    a = oracle.analyze_quantize(xb, "sub1x128", "partition", crit, th, scaling=scaling, gam_group_rows=gam_group_rows,
+                                want_fake=fake)
     mask = out.mask.cpu().numpy()
     err = out.err_sum.cpu().numpy()
     assert np.array_equal(out.nnz.cpu().numpy(), a.nnz)
+    # the per-block outputs and the payloads of this kernel variant, bit for bit
+    assert np.array_equal(out.scale.cpu().numpy().view(np.uint32), a.scale.view(np.uint32))
+    assert np.array_equal(out.amax.cpu().numpy().view(np.uint32), a.amax.view(np.uint32))
+    finite = np.isfinite(a.err_sum)
+    assert np.allclose(err[finite], a.err_sum[finite], rtol=1e-5, atol=128 * 2.0 ** -23)
+    if np.array_equal(mask, a.mask):
+        if fake:
+            assert np.array_equal(parity.u16(fake_y), a.fake)
+        else:
+            assert np.array_equal(out.fp8.cpu().numpy(), a.fp8)
+            rows_bf16 = np.repeat(a.mask.reshape(rows, cols // 128) == 1, 128, axis=1)
+            got_bf16 = parity.u16(out.bf16)
+            assert np.array_equal(got_bf16[rows_bf16], xb[rows_bf16])
+            assert (got_bf16[~rows_bf16] == parity.FILL).all()
     if np.array_equal(mask, a.mask):
         ref = oracle.select_stats(err, a.nnz, a.mask, rows, cols, "sub1x128", th, NEAR)
         for k in INT_KEYS:
