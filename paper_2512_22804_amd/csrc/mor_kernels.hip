@@ -279,6 +279,36 @@ __global__ __launch_bounds__(256) void k_tensor_quant_strided(const uint16_t* __
 // Pass C: every workgroup re-derives the tensor's decision from the per-workgroup partials
 // (binary64 sums in a fixed order, so all workgroups agree), workgroup 0 writes the block outputs
 // (P = 1), and if the decision is BF16 the grid copies the operand into the fallback buffer.
+// A thread's share of the per-workgroup partial sums of pass B (slots threadIdx.x, threadIdx.x + 256, ... in that order).
+// Eight slots' loads are in flight together: the workgroup that does this is on the critical path of the call (one
+// dependent load per slot took 11 round trips for the 2731 slots of an operand of the layer sweep).  A slot beyond the
+// end adds +0, which leaves the (non-negative) sums as they are, so the result is that of the plain loop bit for bit.
+template <int CRIT>
+__device__ __forceinline__ void tensor_partial_sums(const float* __restrict__ err, const float* __restrict__ err5,
+                                                    const uint32_t* __restrict__ zero, int n_slots, double& se, double& se5,
+                                                    unsigned long long& sz) {
+    for (int i0 = threadIdx.x; i0 < n_slots; i0 += 8 * 256) {
+        float e[8], e5[8];
+        uint32_t z[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u * 256;
+            const bool ok = i < n_slots;
+            const int ic = ok ? i : n_slots - 1;           // always a valid slot: the loads need no branch
+            const float ev = err[ic];
+            const uint32_t zv = zero[ic];
+            e[u] = ok ? ev : 0.0f;
+            z[u] = ok ? zv : 0u;
+            if constexpr (CRIT == kCritEq3) { const float e5v = err5[ic]; e5[u] = ok ? e5v : 0.0f; } else e5[u] = 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            se += (double)e[u];
+            sz += z[u];
+            if constexpr (CRIT == kCritEq3) se5 += (double)e5[u];
+        }
+    }
+}
 template <int CRIT>
 __global__ __launch_bounds__(256) void k_tensor_finish(TensorPartials tp, int n_slots, unsigned long long n_padded, KOut o, float th,
                                                        const uint16_t* __restrict__ x, KShape sh, int flat, uint32_t mode,
@@ -288,11 +318,7 @@ __global__ __launch_bounds__(256) void k_tensor_finish(TensorPartials tp, int n_
     __shared__ uint32_t sh4[4];
     double se = 0.0, se5 = 0.0;
     unsigned long long sz = 0;
-    for (int i = threadIdx.x; i < n_slots; i += 256) {
-        se += (double)tp.err[i];
-        sz += tp.zero[i];
-        if constexpr (CRIT == kCritEq3) se5 += (double)tp.err5[i];
-    }
+    tensor_partial_sums<CRIT>(tp.err, tp.err5, tp.zero, n_slots, se, se5, sz);
     se = block_sum_shfl<double>(se, shd);
     sz = block_sum_shfl<unsigned long long>(sz, shl);
     if constexpr (CRIT == kCritEq3) se5 = block_sum_shfl<double>(se5, shd);
@@ -1016,15 +1042,22 @@ __global__ __launch_bounds__(kSoloFinalThreads) void k_solo_stats_final(SoloStat
     tot.e = 0.0; tot.n = 0ull; tot.eb = 0ull; tot.e5 = 0ull;
 #pragma unroll
     for (int k = 0; k < kStatCnt; ++k) tot.c[k] = 0u;
-    for (int i = threadIdx.x; i < s.n_rec; i += kSoloFinalThreads) {
-        const unsigned long long* r = reinterpret_cast<const unsigned long long*>(s.rec + i);
-        unsigned long long q[kSoloRecWords / 2];
+    // a lane's records (lane, lane + 1024; there are at most 2048) are loaded together: one round trip instead of two
+    unsigned long long q[2][kSoloRecWords / 2];
 #pragma unroll
-        for (int k = 0; k < kSoloRecWords / 2; ++k) q[k] = r[k];
+    for (int j = 0; j < 2; ++j) {
+        const int i = (int)threadIdx.x + j * kSoloFinalThreads;
+        const unsigned long long* r = reinterpret_cast<const unsigned long long*>(s.rec + (i < s.n_rec ? i : s.n_rec - 1));
 #pragma unroll
-        for (int k = 0; k < kStatCnt; ++k) tot.c[k] += (uint32_t)(q[k >> 1] >> (32 * (k & 1)));
-        tot.e += __longlong_as_double((long long)q[8]);
-        tot.n += (uint32_t)q[9];
+        for (int k = 0; k < kSoloRecWords / 2; ++k) q[j][k] = r[k];
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        if ((int)threadIdx.x + j * kSoloFinalThreads >= s.n_rec) continue;
+#pragma unroll
+        for (int k = 0; k < kStatCnt; ++k) tot.c[k] += (uint32_t)(q[j][k >> 1] >> (32 * (k & 1)));
+        tot.e += __longlong_as_double((long long)q[j][8]);
+        tot.n += (uint32_t)q[j][9];
     }
     tot.eb = 128ull * tot.c[12];          // (per lane; the sums below add the lanes' products)
     stats_fast_reduce(tot, fin);
@@ -1246,11 +1279,7 @@ __global__ __launch_bounds__(256) void k_tensor_finish_group(GroupTensor g, Grou
     __shared__ unsigned long long shl[4];
     double se = 0.0, se5 = 0.0;
     unsigned long long sz = 0;
-    for (int i = threadIdx.x; i < t.n_slots; i += 256) {
-        se += (double)t.err[i];
-        sz += t.zero[i];
-        if constexpr (CRIT == kCritEq3) se5 += (double)t.err5[i];
-    }
+    tensor_partial_sums<CRIT>(t.err, t.err5, t.zero, t.n_slots, se, se5, sz);
     se = block_sum_shfl<double>(se, shd);
     sz = block_sum_shfl<unsigned long long>(sz, shl);
     if constexpr (CRIT == kCritEq3) se5 = block_sum_shfl<double>(se5, shd);
@@ -1413,6 +1442,7 @@ constexpr int64_t kSubFlatMaxBlocks = 1536;   // workgroups of 4 waves, each wav
                                               // registers let be resident, so no workgroup waits for another to end (one 64 MiB operand, cold
                                               // caches: 21.0 us at 1536 against 23.2 us at 2048 (one unit per wave); 112 MiB: 32.1 against 34.5 us;
                                               // 224 MiB: 65 us either way)
+static_assert(kSubFlatMaxBlocks <= 2 * kSoloFinalThreads, "k_solo_stats_final takes two records per lane");
 static int clamp_grid_y(int64_t v) { return (int)(v < 1 ? 1 : (v > 65535 ? 65535 : v)); }
 
 // The general 1 x 128 kernel: one operand per launch.
