@@ -301,13 +301,14 @@ def run_configs(B, W, torch, dev, log, target_ms=40.0):
         # the kernels of one call, bracketed by the library's own events
         prof = ev.new_profile(8)
         kern = {}
-        for entry in sets[:4]:
-            B.mor_analyze_quantize_batch(entry[0], 1e-5, ws, prof)
+        for i in range(9):                                        # the first call after the idle gap is dropped; medians of the rest
+            B.mor_analyze_quantize_batch(sets[i % n_sets][0], 1e-5, ws, prof)
             torch.cuda.synchronize()
             for k in range(prof.count):
                 kn = B.KERNEL_NAMES[prof.kernel[k]]
-                kern.setdefault(kn, []).append(ev.elapsed_ms(prof.start[k], prof.stop[k]) * 1e3)
-        kern = {k: round(sum(v) / len(v), 2) for k, v in kern.items()}
+                if i > 0:
+                    kern.setdefault(kn, []).append(ev.elapsed_ms(prof.start[k], prof.stop[k]) * 1e3)
+        kern = {k: round(float(np.median(v)), 2) for k, v in kern.items()}
         s = B.read_stats(sets[0][2])
         f = s["n_elem_bf16"] / float(n)
         fused = bool(s["flags"] & B.MOR_STATS_FLAG_FUSED_FALLBACK)
