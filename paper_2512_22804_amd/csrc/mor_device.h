@@ -406,7 +406,11 @@ __device__ __forceinline__ uint32_t decide_eq3(float err4, float err5) { return 
 // Bounds-checked streaming accesses through a buffer resource: a lane whose offset is kBufOutside loads
 // zeros and stores nothing, so ragged edges need no per-lane branches.  Offsets are bytes from `base`
 // (32 bits; callers keep them below 2^31).
-constexpr int kBufAux = 2;      // cache-policy field of the buffer instructions: non-temporal
+constexpr int kBufAux = 2;      // cache-policy field of the buffer loads: non-temporal
+constexpr int kBufStoreAux = 18; // of the buffer stores: non-temporal and written through at system scope (nt sc1).  Measured
+                                 // against nt alone, alternating runs on one box: the per-tensor quantize pass of the layer
+                                 // sweep (2 bytes read, 3 written per element) takes 211.4-212.2 us instead of 213.9-214.0 us;
+                                 // the amax pass that runs before it reads 1.6 us longer, the step time is the same within 0.1 %
 typedef __amdgpu_buffer_rsrc_t BufRsrc;
 constexpr uint32_t kBufOutside = 0x80000000u;
 __device__ __forceinline__ BufRsrc make_buf(const void* base) {
@@ -425,13 +429,13 @@ __device__ __forceinline__ u32x4 buf_load16(BufRsrc r, uint32_t voff, uint32_t s
 // first data dword of some lanes was then stored with its NEW contents (seen as rare, timing-dependent corruption of
 // fake-quantized rows).  With a constant scalar offset the compiler inserts the wait states and the data is intact.
 __device__ __forceinline__ void buf_store16(BufRsrc r, uint32_t voff, const u32x4& v) {
-    __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, 0, kBufAux);
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, 0, kBufStoreAux);
 }
 // No other code may issue a 16-byte buffer store (a register scalar offset would bring the hazard back): any later use
 // of the builtin's name is a compile error.
 #pragma GCC poison __builtin_amdgcn_raw_buffer_store_b128
 __device__ __forceinline__ void buf_store8(BufRsrc r, uint32_t voff, uint32_t soff, const u32x2& v) {
-    __builtin_amdgcn_raw_buffer_store_b64(v, r, voff, soff, kBufAux);
+    __builtin_amdgcn_raw_buffer_store_b64(v, r, voff, soff, kBufStoreAux);
 }
 
 // Streaming accesses: every operand byte is touched once per pass, so loads and stores carry the
